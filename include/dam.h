@@ -1,0 +1,231 @@
+/*
+ * dam.h -- C ABI of the DAM (Dynamic Attention Mask) hot path for AMD MI355X (gfx950).
+ *
+ * Three operations, all enqueued on a caller-supplied HIP stream:
+ *
+ *   dam_mask_build            attention statistics captured at length L  ->  per-head sparse mask
+ *                             (paper Sec. 4.2.2 - 4.2.4 and Sec. 4.3), emitted as an element bitmask
+ *                             pooled by tile plus a compressed block index, and optionally as
+ *                             per-row kept-key lists and a dense bitmask.
+ *   dam_sparse_attn_prefill   masked causal self-attention over the kept (query, key) entries only
+ *                             (paper Sec. 3 and the last two equations of Sec. 4.3).
+ *   dam_sparse_attn_decode    the same formula for one new query row per (sequence, head), reading
+ *                             only the kept K/V rows.
+ *
+ * Conventions shared by every entry point
+ *   - Plain C. "device" pointers are HIP device addresses, "host" pointers are ordinary host memory.
+ *     Parameter structs are host memory and are read before the call returns.
+ *   - Ownership: every buffer (inputs, outputs, workspace) is allocated and freed by the caller.
+ *     The library keeps no state between calls and allocates nothing.
+ *   - Asynchrony: all device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream). No entry point synchronises the host. Device scalars written by a call
+ *     (bmin, blk_total, kept_total) are valid once the caller has synchronised the stream.
+ *   - Errors: the return value only (a dam_status). Argument errors are detected on the host
+ *     before anything is launched; in that case no output is touched.
+ *   - All indices are 0-based. Causality (key j <= query i) is part of every mask.
+ *   - Masks belong to a (layer, head) pair, not to an input, so one mask serves every batch entry.
+ */
+#ifndef DAM_H
+#define DAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DAM_OK = 0,
+  DAM_ERR_INVALID_ARG = -1, /* null required pointer, non-positive size, hq % hkv != 0, bad ranges */
+  DAM_ERR_UNSUPPORTED = -2, /* a head_dim / dtype / tile / lambda outside the built set          */
+  DAM_ERR_WORKSPACE = -3,   /* ws_bytes smaller than the matching *_workspace() query             */
+  DAM_ERR_CAPACITY = -4,    /* reserved: capacity overflow is reported through blk_total/kept_total */
+  DAM_ERR_DEVICE = -5       /* a kernel launch failed                                              */
+} dam_status;
+
+typedef enum { DAM_F32 = 0, DAM_BF16 = 1 } dam_dtype;
+
+typedef enum {
+  DAM_FROM_ATTN_MAP = 0, /* derive the true mask and the matched patterns from A (and C)          */
+  DAM_FROM_PATTERNS = 1  /* matched patterns (and optionally a true mask) are supplied            */
+} dam_mask_mode;
+
+/* ------------------------------------------------------------------------------------------------
+ * dam_mask_build
+ *
+ * Sec. 4.2.2:  Abar = A / (C + eps);  X = max(Abar, eps);  B = (X^lambda - 1) / lambda;
+ *              Bstar = B - min over every map and entry of the call (or bmin_override).
+ * Sec. 4.2.3:  true mask  m[i][j] = (Bstar[i][j] >= tau)  and  j <= i,   an L x L matrix per map.
+ * Sec. 4.2.4:  match score of the diagonal pattern r (entries j = i - r) and of the vertical pattern c
+ *              (entries j = c, i >= c):  gamma = (kept entries on the pattern) / (entries of the
+ *              pattern);  a pattern is matched when gamma >= mu.
+ * Sec. 4.3:    mask of an S x S problem.  S <= L: the top-left S x S crop of m.   S > L: m inside the
+ *              top-left L x L block; elsewhere entry (i, j), j <= i, is kept iff (i - j) is a matched
+ *              diagonal or j is a matched column.
+ *
+ * The arithmetic of the first three steps is a fixed fp32 sequence, each operation rounded to
+ * nearest-even and never contracted: abar = a / (c + eps); x = max(abar, eps);
+ * lambda = 0.5: b = (sqrt(x) - 1) / 0.5;  lambda = 1: b = x - 1;  keep = (b - bmin) >= tau;
+ * gamma = (float)count / (float)length; matched = gamma >= mu.  Other lambda: DAM_ERR_UNSUPPORTED.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t mode;      /* dam_mask_mode                                                              */
+  int32_t n_maps;    /* H: number of (layer, head) maps handled by this call                        */
+  int32_t pcl;       /* L: pattern capture length. FROM_PATTERNS: side of the supplied true mask, or
+                        0 when there is none (then the pattern rule applies everywhere)             */
+  int32_t seq;       /* S: length of the problem the mask is built for                              */
+  int32_t tile_m;    /* block-index tile, query rows;  multiple of 64, at most 256                  */
+  int32_t tile_n;    /* block-index tile, key columns; multiple of 64, at most 256                  */
+  int32_t row_begin; /* kept lists are emitted for rows [row_begin, row_end) of the S x S mask      */
+  int32_t row_end;   /*   (0 <= row_begin <= row_end <= S); ignored when kept_ptr is NULL           */
+  float lambda;      /* Box-Cox exponent: 0.5 (the paper's) or 1                                    */
+  float eps;         /* epsilon of the mean and of the clamp, > 0 (paper: 1e-8)                     */
+  float tau;         /* true-mask threshold (paper: 0.3)                                            */
+  float mu;          /* pattern-match threshold (paper: 0.8)                                        */
+  float bmin_override; /* NaN: use the minimum over this call's maps; otherwise this value is bmin  */
+} dam_mask_params;
+
+/* Outputs of dam_mask_build. Every pointer is a device pointer owned by the caller; any of them may
+ * be NULL when that output is not wanted (exceptions are stated).
+ *
+ *   true_bits  [H][L][ceil(L/64)] u64   bit (j % 64) of word j / 64 of row i is m[i][j]. Written in
+ *                                       FROM_ATTN_MAP mode (required there when S > 0 outputs that
+ *                                       depend on it are requested: it is then also read back);
+ *                                       read in FROM_PATTERNS mode when pcl > 0.
+ *   diag_cnt, vert_cnt [H][L] i32       kept entries on each diagonal / column of the true mask.
+ *   diag_flag, vert_flag [H][P] u8      1 = matched.  P = L in FROM_ATTN_MAP mode (written; required
+ *                                       when any S-sized output is requested), P = S in
+ *                                       FROM_PATTERNS mode, where they are not written: the inputs
+ *                                       diag_in / vert_in are used instead.
+ *   bmin       [1] f32                  the minimum used by the threshold.
+ *   blk_row_ptr [H][nQt + 1] i32        CSR offsets into blk_col; offsets are global over all maps
+ *                                       (blk_row_ptr[h][0] == blk_row_ptr[h-1][nQt]),
+ *                                       nQt = ceil(S / tile_m). Required for any block output.
+ *   blk_col    [blk_capacity] i32       key-tile index of each listed tile, ascending per query tile.
+ *                                       A tile is listed iff it holds at least one kept entry.
+ *   blk_kind   [blk_capacity] u8        1 = every entry of the tile is kept and the tile lies
+ *                                       strictly below the diagonal and inside S; else 0.
+ *   tile_bits  [blk_capacity][tile_m][tile_n / 64] u64   element bits of listed tile t at index t
+ *                                       (also for kind 1 tiles: all ones); bits beyond S are 0.
+ *   blk_total  [1] i64                  number of listed tiles, valid even when it exceeds
+ *                                       blk_capacity (nothing is written past the capacity). Call
+ *                                       with blk_col == NULL to size the buffers.
+ *   dense_bits [H][S][ceil(S/64)] u64   the whole mask; only sensible for small S.
+ *   kept_ptr   [H * (row_end - row_begin) + 1] i32   CSR offsets into kept_idx, map-major.
+ *   kept_idx   [kept_capacity] i32      kept keys of each emitted row, ascending, no duplicates.
+ *   kept_total [1] i64                  number of kept keys over the emitted rows (as blk_total).
+ */
+typedef struct {
+  uint64_t *true_bits;
+  int32_t *diag_cnt, *vert_cnt;
+  uint8_t *diag_flag, *vert_flag;
+  float *bmin;
+  int32_t *blk_row_ptr, *blk_col;
+  uint8_t *blk_kind;
+  uint64_t *tile_bits;
+  int64_t blk_capacity;
+  int64_t *blk_total;
+  uint64_t *dense_bits;
+  int32_t *kept_ptr, *kept_idx;
+  int64_t kept_capacity;
+  int64_t *kept_total;
+} dam_mask_out;
+
+/* Bytes of device workspace dam_mask_build needs for these parameters (0 on invalid parameters). */
+size_t dam_mask_build_workspace(const dam_mask_params *params);
+
+/* params     host.
+ * attn_sum   device, f32 [H][L][L] row-major: A, attention summed over the captured batches.
+ *            FROM_ATTN_MAP only (else NULL).
+ * attn_cnt   device, f32 [H][L][L]: C, how often each pair was computed; or NULL, meaning one
+ *            causal capture: C = 1 for j <= i and, for j > i, C = 0 and A is taken as 0 without
+ *            being read.
+ * diag_in, vert_in   device, u8 [H][S]: matched diagonal offsets / columns. FROM_PATTERNS only.
+ * out        host struct of device pointers, see above.
+ * ws         device workspace of at least dam_mask_build_workspace(params) bytes, 256-byte aligned.
+ * Returns DAM_OK or a negative dam_status; on DAM_ERR_INVALID_ARG / UNSUPPORTED / WORKSPACE nothing
+ * was launched. */
+int dam_mask_build(const dam_mask_params *params, const float *attn_sum, const float *attn_cnt,
+                   const uint8_t *diag_in, const uint8_t *vert_in, const dam_mask_out *out,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * dam_sparse_attn_prefill
+ *
+ * Sec. 3 / Sec. 4.3: for every batch entry b, query head h and row i,
+ *     O[i] = sum_{j in K_i} softmax_j(q_i . k_j * scale) v_j,   K_i = kept keys of row i of head h's
+ * mask (masked entries are -inf before the softmax). A row without kept keys gives O[i] = 0 and
+ * lse[i] = -inf. Query head h reads KV head h / (hq / hkv).
+ * dtype DAM_BF16: bf16 in, fp32 accumulation on the matrix cores, bf16 out (round to nearest even);
+ *                 head_dim 128, tiles 128 x 128.
+ * dtype DAM_F32:  fp32 throughout; head_dim 64 or 128, tiles of 64 or 128 in either direction.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t batch, hq, hkv, seq, head_dim;
+  int32_t dtype;        /* dam_dtype of q, k, v and out                                           */
+  float scale;          /* logit scale; 0 means 1 / sqrt(head_dim)                                */
+  int64_t q_stride[3];  /* element strides of the batch, head and sequence index; head_dim is     */
+  int64_t k_stride[3];  /*   contiguous (stride 1). Rows must be 16-byte aligned.                 */
+  int64_t v_stride[3];
+  int64_t o_stride[3];
+  int32_t tile_m, tile_n; /* the tile the block index was built with                              */
+} dam_attn_params;
+
+/* The block-index outputs of dam_mask_build for the hq query heads (device pointers). */
+typedef struct {
+  const int32_t *blk_row_ptr; /* [hq][nQt + 1]                                                     */
+  const int32_t *blk_col;
+  const uint8_t *blk_kind;
+  const uint64_t *tile_bits;
+} dam_mask_view;
+
+size_t dam_sparse_attn_prefill_workspace(const dam_attn_params *params);
+
+/* q, k, v, out  device, laid out by the strides above ([batch][heads][seq][head_dim] when dense).
+ * lse           device f32 [batch][hq][seq] (natural-log sum-exp of the kept logits) or NULL.
+ * ws            device workspace (may be NULL when the query returns 0). */
+int dam_sparse_attn_prefill(const dam_attn_params *params, const void *q, const void *k,
+                            const void *v, const dam_mask_view *mask, void *out, float *lse, void *ws,
+                            size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * dam_sparse_attn_decode
+ *
+ * The formula above for one query row per (sequence b, query head h): the row attends the keys
+ * listed in kept_idx[kept_ptr[b*hq+h] .. kept_ptr[b*hq+h+1]), positions in that sequence's cache,
+ * ascending and without duplicates (row p of the head's mask, Sec. 4.3). An empty list gives
+ * O = 0, lse = -inf. bf16 (fp32 accumulation) or fp32; head_dim 64 or 128.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t batch, hq, hkv;
+  int32_t kv_capacity;   /* rows allocated per (sequence, KV head) in the caches                   */
+  int32_t head_dim;
+  int32_t dtype;
+  float scale;           /* 0 means 1 / sqrt(head_dim)                                            */
+  int64_t q_stride[2];   /* element strides of batch and head; head_dim contiguous                */
+  int64_t kv_stride[3];  /* element strides of batch, KV head and position, for both caches       */
+  int64_t o_stride[2];
+} dam_decode_params;
+
+/* max_kept: upper bound of the kept keys of one (sequence, head) list. */
+size_t dam_sparse_attn_decode_workspace(const dam_decode_params *params, int64_t max_kept);
+
+/* q, out      device [batch][hq][head_dim] by the strides above.
+ * kcache, vcache  device [batch][hkv][kv_capacity][head_dim] by kv_stride.
+ * kept_ptr    device i32 [batch*hq + 1]; kept_idx device i32.
+ * max_kept    the bound given to the workspace query (the library does not read kept_ptr on the
+ *             host); every list must be no longer than it and every index < kv_capacity.
+ * lse         device f32 [batch][hq] or NULL. */
+int dam_sparse_attn_decode(const dam_decode_params *params, const void *q, const void *kcache,
+                           const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
+                           int64_t max_kept, void *out, float *lse, void *ws, size_t ws_bytes,
+                           void *stream);
+
+/* Library version, for the loader's sanity check. */
+int dam_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAM_H */

@@ -1,0 +1,276 @@
+"""CPU oracle of the DAM hot path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper over ``dam_oracle.c`` (plain C, fp32 mask rule, fp64 attention). Only tests,
+``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this package; the
+GPU library and its Python binding never do, and this package imports nothing of theirs.
+
+Paper: arXiv 2506.11104 (Dynamic Attention Mask). Section numbers in the docstrings refer to it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def _ptr(a: Optional[np.ndarray], ctype):
+    if a is None:
+        return ctypes.cast(None, ctypes.POINTER(ctype))
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def lib() -> ctypes.CDLL:
+    global _LIB
+    if _LIB is None:
+        path = _build.build(force=False)
+        _LIB = ctypes.CDLL(path)
+        _LIB.dam_oracle_boxcox.restype = ctypes.c_float
+        _LIB.dam_oracle_boxcox.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
+                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
+                                           ctypes.POINTER(ctypes.c_float)]
+        _LIB.dam_oracle_true_mask.restype = None
+        _LIB.dam_oracle_true_mask.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int32, ctypes.c_int32,
+                                              ctypes.c_float, ctypes.c_float, ctypes.POINTER(ctypes.c_uint8)]
+        _LIB.dam_oracle_match.restype = None
+        _LIB.dam_oracle_match.argtypes = [ctypes.POINTER(ctypes.c_uint8), ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_float, ctypes.POINTER(ctypes.c_int32),
+                                          ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint8),
+                                          ctypes.POINTER(ctypes.c_uint8)]
+        head = [ctypes.POINTER(ctypes.c_uint8), ctypes.c_int32, ctypes.POINTER(ctypes.c_uint8),
+                ctypes.POINTER(ctypes.c_uint8), ctypes.c_int32]
+        _LIB.dam_oracle_kept.restype = ctypes.c_int
+        _LIB.dam_oracle_kept.argtypes = head + [ctypes.c_int64, ctypes.c_int64]
+        _LIB.dam_oracle_rows.restype = None
+        _LIB.dam_oracle_rows.argtypes = head + [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                                ctypes.POINTER(ctypes.c_uint8)]
+        _LIB.dam_oracle_kept_list.restype = ctypes.c_int64
+        _LIB.dam_oracle_kept_list.argtypes = head + [ctypes.c_int64, ctypes.POINTER(ctypes.c_int32),
+                                                     ctypes.c_int64]
+        _LIB.dam_oracle_block_index.restype = ctypes.c_int64
+        _LIB.dam_oracle_block_index.argtypes = head + [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                       ctypes.c_int64, ctypes.c_int64,
+                                                       ctypes.POINTER(ctypes.c_int32),
+                                                       ctypes.POINTER(ctypes.c_int32),
+                                                       ctypes.POINTER(ctypes.c_uint8),
+                                                       ctypes.POINTER(ctypes.c_uint64), ctypes.c_int64]
+        _LIB.dam_oracle_attend_lists.restype = None
+        _LIB.dam_oracle_attend_lists.argtypes = [ctypes.POINTER(ctypes.c_float)] * 3 + [
+            ctypes.POINTER(ctypes.c_int32), ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64),
+            ctypes.POINTER(ctypes.c_int32), ctypes.c_int64, ctypes.c_double, ctypes.POINTER(ctypes.c_double),
+            ctypes.POINTER(ctypes.c_double)]
+        _LIB.dam_oracle_attend_rows.restype = None
+        _LIB.dam_oracle_attend_rows.argtypes = [ctypes.POINTER(ctypes.c_float)] * 3 + [
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_uint8),
+            ctypes.c_int32, ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(ctypes.c_uint8), ctypes.c_int32,
+            ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64), ctypes.c_int64, ctypes.c_double,
+            ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        _LIB.dam_oracle_threads.restype = ctypes.c_int
+        _LIB.dam_oracle_threads.argtypes = []
+    return _LIB
+
+
+def threads() -> int:
+    """Threads the oracle's parallel loops use."""
+    return int(lib().dam_oracle_threads())
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _u8(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.uint8)
+
+
+@dataclass
+class MaskArtefact:
+    """What is stored per (layer, head) after stage one (Sec. 4.3, "stored matched positions"):
+    the L x L true mask and the matched diagonal offsets / columns as flags over 0..P-1."""
+    L: int
+    P: int
+    true_mask: Optional[np.ndarray]   # [H][L][L] u8, None when L == 0
+    diag_flag: np.ndarray             # [H][P] u8
+    vert_flag: np.ndarray             # [H][P] u8
+    diag_cnt: Optional[np.ndarray] = None  # [H][L] i32
+    vert_cnt: Optional[np.ndarray] = None
+    bmin: Optional[float] = None
+
+    @property
+    def H(self) -> int:
+        return int(self.diag_flag.shape[0])
+
+    def head_args(self, h: int):
+        tm = self.true_mask[h] if self.true_mask is not None else None
+        return (_ptr(tm, ctypes.c_uint8), ctypes.c_int32(self.L), _ptr(self.diag_flag[h], ctypes.c_uint8),
+                _ptr(self.vert_flag[h], ctypes.c_uint8), ctypes.c_int32(self.P))
+
+
+def boxcox(attn_sum: np.ndarray, attn_cnt: Optional[np.ndarray], lam: float, eps: float):
+    """Sec. 4.2.2: returns (B [H][L][L] f32, bmin). B* = B - bmin is the normalised map."""
+    A = _f32(attn_sum)
+    H, L, _ = A.shape
+    C = _f32(attn_cnt) if attn_cnt is not None else None
+    B = np.empty_like(A)
+    bmin = lib().dam_oracle_boxcox(_ptr(A, ctypes.c_float), _ptr(C, ctypes.c_float), H, L,
+                                   ctypes.c_float(lam), ctypes.c_float(eps), _ptr(B, ctypes.c_float))
+    return B, np.float32(bmin)
+
+
+def true_mask(B: np.ndarray, bmin, tau: float) -> np.ndarray:
+    """Sec. 4.2.3: m = (B - bmin >= tau) and causal, [H][L][L] u8."""
+    B = _f32(B)
+    H, L, _ = B.shape
+    m = np.empty((H, L, L), dtype=np.uint8)
+    lib().dam_oracle_true_mask(_ptr(B, ctypes.c_float), H, L, ctypes.c_float(bmin), ctypes.c_float(tau),
+                               _ptr(m, ctypes.c_uint8))
+    return m
+
+
+def match(m: np.ndarray, mu: float):
+    """Sec. 4.2.4: (diag_cnt, vert_cnt, diag_flag, vert_flag), each [H][L]."""
+    m = _u8(m)
+    H, L, _ = m.shape
+    dc = np.empty((H, L), np.int32)
+    vc = np.empty((H, L), np.int32)
+    df = np.empty((H, L), np.uint8)
+    vf = np.empty((H, L), np.uint8)
+    lib().dam_oracle_match(_ptr(m, ctypes.c_uint8), H, L, ctypes.c_float(mu), _ptr(dc, ctypes.c_int32),
+                           _ptr(vc, ctypes.c_int32), _ptr(df, ctypes.c_uint8), _ptr(vf, ctypes.c_uint8))
+    return dc, vc, df, vf
+
+
+def derive(attn_sum, attn_cnt, lam: float, eps: float, tau: float, mu: float,
+           bmin_override: Optional[float] = None) -> MaskArtefact:
+    """Stage one end to end (Sec. 4.2.2 - 4.2.4): statistics at length L -> stored artefact."""
+    B, bmin = boxcox(attn_sum, attn_cnt, lam, eps)
+    if bmin_override is not None:
+        bmin = np.float32(bmin_override)
+    m = true_mask(B, bmin, tau)
+    dc, vc, df, vf = match(m, mu)
+    L = m.shape[1]
+    return MaskArtefact(L=L, P=L, true_mask=m, diag_flag=df, vert_flag=vf, diag_cnt=dc, vert_cnt=vc,
+                        bmin=float(bmin))
+
+
+def from_patterns(diag_flag, vert_flag, true_mask_: Optional[np.ndarray] = None) -> MaskArtefact:
+    """Artefact from given matched sets (flags over 0..P-1) and an optional true mask."""
+    df, vf = _u8(diag_flag), _u8(vert_flag)
+    tm = _u8(true_mask_) if true_mask_ is not None else None
+    return MaskArtefact(L=0 if tm is None else tm.shape[1], P=df.shape[1], true_mask=tm, diag_flag=df,
+                        vert_flag=vf)
+
+
+def kept(art: MaskArtefact, h: int, i: int, j: int) -> int:
+    """Sec. 4.3: entry (i, j) of head h's mask."""
+    return int(lib().dam_oracle_kept(*art.head_args(h), i, j))
+
+
+def rows(art: MaskArtefact, h: int, S: int, i0: int, i1: int) -> np.ndarray:
+    """Rows [i0, i1) of head h's S x S mask, [i1-i0][S] u8."""
+    out = np.empty((i1 - i0, S), np.uint8)
+    lib().dam_oracle_rows(*art.head_args(h), S, i0, i1, _ptr(out, ctypes.c_uint8))
+    return out
+
+
+def kept_list(art: MaskArtefact, h: int, i: int) -> np.ndarray:
+    """Kept keys of row i of head h, ascending (i32)."""
+    idx = np.empty(i + 1, np.int32)
+    n = lib().dam_oracle_kept_list(*art.head_args(h), i, _ptr(idx, ctypes.c_int32), i + 1)
+    return idx[:n].copy()
+
+
+def block_index(art: MaskArtefact, S: int, tile_m: int, tile_n: int, heads: Optional[Sequence[int]] = None,
+                want_bits: bool = True, workers: int = 8):
+    """Block index of the given heads (default all): returns
+    (row_ptr [n_heads][nQt+1] i64 with offsets global over the given heads in order,
+     col i32 [n_tiles], kind u8 [n_tiles], tile_bits u64 [n_tiles][tile_m][tile_n//64] or None)."""
+    heads = list(range(art.H)) if heads is None else list(heads)
+    nQt = (S + tile_m - 1) // tile_m
+    wpr = tile_n // 64
+    chunk = max(1, nQt // 16)
+    jobs = [(h, q0, min(nQt, q0 + chunk)) for h in heads for q0 in range(0, nQt, chunk)]
+
+    def run(job):
+        h, q0, q1 = job
+        cnt = np.zeros(q1 - q0, np.int32)
+        args = art.head_args(h)
+        n = lib().dam_oracle_block_index(*args, S, tile_m, tile_n, q0, q1, _ptr(cnt, ctypes.c_int32),
+                                         _ptr(None, ctypes.c_int32), _ptr(None, ctypes.c_uint8),
+                                         _ptr(None, ctypes.c_uint64), 0)
+        col = np.empty(n, np.int32)
+        kind = np.empty(n, np.uint8)
+        bits = np.empty((n, tile_m, wpr), np.uint64) if want_bits else None
+        lib().dam_oracle_block_index(*args, S, tile_m, tile_n, q0, q1, _ptr(cnt, ctypes.c_int32),
+                                     _ptr(col, ctypes.c_int32), _ptr(kind, ctypes.c_uint8),
+                                     _ptr(bits, ctypes.c_uint64), n)
+        return cnt, col, kind, bits
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        res = list(ex.map(run, jobs))
+    cnts = np.concatenate([r[0] for r in res]).reshape(len(heads), nQt)
+    row_ptr = np.zeros((len(heads), nQt + 1), np.int64)
+    flat = np.concatenate([[0], np.cumsum(cnts.reshape(-1), dtype=np.int64)])
+    for a in range(len(heads)):
+        row_ptr[a] = flat[a * nQt:(a + 1) * nQt + 1]
+    col = np.concatenate([r[1] for r in res]) if res else np.empty(0, np.int32)
+    kind = np.concatenate([r[2] for r in res]) if res else np.empty(0, np.uint8)
+    bits = np.concatenate([r[3] for r in res]) if want_bits else None
+    return row_ptr, col, kind, bits
+
+
+def attend_rows(q_rows, K, V, art: MaskArtefact, Hq: int, heads, rows_, scale: Optional[float] = None):
+    """Sec. 3 / 4.3: masked attention of rows (heads[a], rows_[a]). q_rows [n][d] f32 (the query
+    vectors of those rows), K, V [Hkv][S][d] f32. Returns (O [n][d] f64, lse [n] f64)."""
+    q_rows, K, V = _f32(q_rows), _f32(K), _f32(V)
+    Hkv, S, d = K.shape
+    n = q_rows.shape[0]
+    heads = np.ascontiguousarray(heads, np.int32)
+    rows_ = np.ascontiguousarray(rows_, np.int64)
+    assert art.H == Hq and heads.shape[0] == n and rows_.shape[0] == n
+    sc = float(scale) if scale else 1.0 / float(np.sqrt(np.float64(d)))
+    out = np.empty((n, d), np.float64)
+    lse = np.empty(n, np.float64)
+    tm = art.true_mask if art.true_mask is not None else None
+    lib().dam_oracle_attend_rows(_ptr(q_rows, ctypes.c_float), _ptr(K, ctypes.c_float), _ptr(V, ctypes.c_float),
+                                 Hq, Hkv, S, d, _ptr(tm, ctypes.c_uint8), art.L,
+                                 _ptr(art.diag_flag, ctypes.c_uint8), _ptr(art.vert_flag, ctypes.c_uint8), art.P,
+                                 _ptr(heads, ctypes.c_int32), _ptr(rows_, ctypes.c_int64), n,
+                                 ctypes.c_double(sc), _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    return out, lse
+
+
+def attend_prefill(Q, K, V, art: MaskArtefact, scale: Optional[float] = None):
+    """All rows of one batch entry: Q [Hq][S][d], K, V [Hkv][S][d] -> (O [Hq][S][d] f64, lse [Hq][S])."""
+    Q = _f32(Q)
+    Hq, S, d = Q.shape
+    heads = np.repeat(np.arange(Hq, dtype=np.int32), S)
+    rws = np.tile(np.arange(S, dtype=np.int64), Hq)
+    out, lse = attend_rows(Q.reshape(Hq * S, d), K, V, art, Hq, heads, rws, scale)
+    return out.reshape(Hq, S, d), lse.reshape(Hq, S)
+
+
+def attend_lists(q, kcache, vcache, kv_of, kept_ptr, kept_idx, scale: Optional[float] = None):
+    """Decode form: q [n][d] f32; caches [n_blocks][T][d] f32; kv_of [n] i32 (cache block per item);
+    CSR lists. Returns (O [n][d] f64, lse [n] f64)."""
+    q, kcache, vcache = _f32(q), _f32(kcache), _f32(vcache)
+    n, d = q.shape
+    T = kcache.shape[1]
+    kv_of = np.ascontiguousarray(kv_of, np.int32)
+    kept_ptr = np.ascontiguousarray(kept_ptr, np.int64)
+    kept_idx = np.ascontiguousarray(kept_idx, np.int32)
+    sc = float(scale) if scale else 1.0 / float(np.sqrt(np.float64(d)))
+    out = np.empty((n, d), np.float64)
+    lse = np.empty(n, np.float64)
+    lib().dam_oracle_attend_lists(_ptr(q, ctypes.c_float), _ptr(kcache, ctypes.c_float), _ptr(vcache, ctypes.c_float),
+                                  _ptr(kv_of, ctypes.c_int32), T, d, _ptr(kept_ptr, ctypes.c_int64),
+                                  _ptr(kept_idx, ctypes.c_int32), n, ctypes.c_double(sc),
+                                  _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double))
+    return out, lse

@@ -1,0 +1,157 @@
+"""Pins of the oracle's masked attention (Sec. 3 and the end of Sec. 4.3) against library dense
+causal attention, a brute-force dense softmax, and identities any correct implementation obeys."""
+import numpy as np
+import torch
+
+import oracle
+
+
+def rand_qkv(rng, Hq, Hkv, S, d, scale=1.0):
+    Q = (rng.standard_normal((Hq, S, d)) * scale).astype(np.float32)
+    K = (rng.standard_normal((Hkv, S, d)) * scale).astype(np.float32)
+    V = rng.standard_normal((Hkv, S, d)).astype(np.float32)
+    return Q, K, V
+
+
+def random_art(rng, H, S, L=0, p_diag=0.15, p_vert=0.1):
+    d = (rng.random((H, S)) < p_diag).astype(np.uint8)
+    v = (rng.random((H, S)) < p_vert).astype(np.uint8)
+    tm = None
+    if L:
+        tm = (rng.random((H, L, L)) < 0.4).astype(np.uint8) * np.tril(np.ones((L, L), np.uint8))
+    return oracle.from_patterns(d, v, tm)
+
+
+def brute(Q, K, V, art, scale=None):
+    """Dense logits, -inf fill from the dense mask, softmax, matmul; fp64 numpy."""
+    Hq, S, d = Q.shape
+    G = Hq // K.shape[0]
+    sc = scale if scale else 1.0 / np.sqrt(d)
+    O = np.zeros((Hq, S, d))
+    lse = np.full((Hq, S), -np.inf)
+    for h in range(Hq):
+        M = oracle.rows(art, h, S, 0, S).astype(bool)
+        s = (Q[h].astype(np.float64) @ K[h // G].astype(np.float64).T) * sc
+        s = np.where(M, s, -np.inf)
+        for i in range(S):
+            if not M[i].any():
+                continue
+            mx = s[i].max()
+            e = np.exp(s[i] - mx)
+            O[h, i] = (e / e.sum()) @ V[h // G].astype(np.float64)
+            lse[h, i] = mx + np.log(e.sum())
+    return O, lse
+
+
+def test_all_ones_mask_is_dense_causal_attention():
+    rng = np.random.default_rng(10)
+    Hq, Hkv, S, d = 4, 2, 65, 16
+    Q, K, V = rand_qkv(rng, Hq, Hkv, S, d)
+    art = oracle.from_patterns(np.ones((Hq, S), np.uint8), np.zeros((Hq, S), np.uint8))
+    O, lse = oracle.attend_prefill(Q, K, V, art)
+    tq = torch.from_numpy(Q).double()[None]
+    tk = torch.from_numpy(K).double().repeat_interleave(Hq // Hkv, 0)[None]
+    tv = torch.from_numpy(V).double().repeat_interleave(Hq // Hkv, 0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].numpy()
+    np.testing.assert_allclose(O, ref, atol=1e-12)
+    s = torch.einsum("hid,hjd->hij", tq[0], tk[0]) / np.sqrt(d)
+    s = s.masked_fill(~torch.tril(torch.ones(S, S, dtype=torch.bool)), float("-inf"))
+    np.testing.assert_allclose(lse, torch.logsumexp(s, -1).numpy(), atol=1e-12)
+
+
+def test_brute_force_random_masks_gqa_and_scale():
+    rng = np.random.default_rng(11)
+    Hq, Hkv, S, d = 6, 2, 50, 8
+    Q, K, V = rand_qkv(rng, Hq, Hkv, S, d, scale=2.0)
+    art = random_art(rng, Hq, S, L=12)
+    for scale in (None, 0.37):
+        O, lse = oracle.attend_prefill(Q, K, V, art, scale)
+        Ob, lb = brute(Q, K, V, art, scale)
+        np.testing.assert_allclose(O, Ob, atol=1e-12)
+        np.testing.assert_allclose(lse, lb, atol=1e-12)
+    # GQA equals multi-head attention with the K/V heads repeated
+    O2, _ = oracle.attend_prefill(Q, np.repeat(K, 3, 0), np.repeat(V, 3, 0), art)
+    O1, _ = oracle.attend_prefill(Q, K, V, art)
+    assert np.array_equal(O1, O2)
+    # ... and the grouping is contiguous: head h reads KV head h // G (a transposed grouping fails)
+    Kp = K.copy()
+    Kp[1] += 1.0
+    O3, _ = oracle.attend_prefill(Q, Kp, V, art)
+    assert np.array_equal(O3[:3], O1[:3]) and not np.allclose(O3[3:], O1[3:])
+
+
+def test_empty_rows_single_key_and_convexity():
+    rng = np.random.default_rng(12)
+    Hq, S, d = 2, 40, 8
+    Q, K, V = rand_qkv(rng, Hq, Hq, S, d, scale=3.0)
+    # head 0: only the diagonal r = 3  -> rows 0..2 empty, rows >= 3 keep exactly key i-3
+    # head 1: random
+    dg = np.zeros((Hq, S), np.uint8)
+    vt = np.zeros((Hq, S), np.uint8)
+    dg[0, 3] = 1
+    dg[1] = rng.random(S) < 0.3
+    art = oracle.from_patterns(dg, vt)
+    O, lse = oracle.attend_prefill(Q, K, V, art)
+    assert np.all(O[0, :3] == 0) and np.all(np.isneginf(lse[0, :3])) and not np.isnan(O).any()
+    assert np.array_equal(O[0, 3:], V[0, :S - 3].astype(np.float64))      # that V row exactly
+    np.testing.assert_allclose(lse[0, 3:], np.einsum("id,id->i", Q[0, 3:].astype(np.float64),
+                                                     K[0, :S - 3].astype(np.float64)) / np.sqrt(d), atol=1e-12)
+    for i in range(S):
+        kept = oracle.kept_list(art, 1, i)
+        if len(kept) == 0:
+            assert np.all(O[1, i] == 0)
+            continue
+        lo, hi = V[1, kept].min(0), V[1, kept].max(0)
+        assert np.all(O[1, i] >= lo - 1e-12) and np.all(O[1, i] <= hi + 1e-12)
+
+
+def test_list_form_identities():
+    rng = np.random.default_rng(13)
+    d, T = 16, 300
+    q = rng.standard_normal((1, d)).astype(np.float32) * 2
+    Kc = rng.standard_normal((1, T, d)).astype(np.float32)
+    Vc = rng.standard_normal((1, T, d)).astype(np.float32)
+    idx = np.sort(rng.choice(T, 70, replace=False)).astype(np.int32)
+    O, lse = oracle.attend_lists(q, Kc, Vc, [0], [0, 70], idx)
+    # permuting the kept keys changes nothing but rounding
+    perm = rng.permutation(70)
+    Op, lp = oracle.attend_lists(q, Kc, Vc, [0], [0, 70], idx[perm])
+    np.testing.assert_allclose(Op, O, atol=1e-13)
+    # adding a constant to every logit (append a constant feature) changes nothing but lse
+    q2 = np.concatenate([q, np.full((1, 1), 4.0, np.float32)], 1)
+    K2 = np.concatenate([Kc, np.full((1, T, 1), 0.5, np.float32)], 2)
+    V2 = np.concatenate([Vc, np.zeros((1, T, 1), np.float32)], 2)
+    sc = 1.0 / np.sqrt(d)
+    O2, l2 = oracle.attend_lists(q2, K2, V2, [0], [0, 70], idx, scale=sc)
+    np.testing.assert_allclose(O2[:, :d], O, atol=1e-12)
+    np.testing.assert_allclose(l2 - lse, 2.0 * sc, atol=1e-12)
+    # split the list in two and merge by log-sum-exp
+    Oa, la = oracle.attend_lists(q, Kc, Vc, [0], [0, 30], idx[:30])
+    Ob, lb = oracle.attend_lists(q, Kc, Vc, [0], [0, 40], idx[30:])
+    m = np.maximum(la, lb)
+    wa, wb = np.exp(la - m), np.exp(lb - m)
+    np.testing.assert_allclose((wa * Oa + wb * Ob) / (wa + wb), O, atol=1e-12)
+    np.testing.assert_allclose(m + np.log(wa + wb), lse, atol=1e-12)
+    # several items, different cache blocks, one empty list
+    q3 = rng.standard_normal((3, d)).astype(np.float32)
+    K3 = rng.standard_normal((2, T, d)).astype(np.float32)
+    V3 = rng.standard_normal((2, T, d)).astype(np.float32)
+    O3, l3 = oracle.attend_lists(q3, K3, V3, [1, 0, 1], [0, 5, 5, 9], np.array([1, 2, 3, 4, 5, 7, 8, 9, 10], np.int32))
+    assert np.all(O3[1] == 0) and np.isneginf(l3[1])
+    s = (K3[1, [1, 2, 3, 4, 5]].astype(np.float64) @ q3[0].astype(np.float64)) / np.sqrt(d)
+    w = np.exp(s - s.max())
+    np.testing.assert_allclose(O3[0], (w / w.sum()) @ V3[1, [1, 2, 3, 4, 5]].astype(np.float64), atol=1e-12)
+
+
+def test_decode_row_equals_prefill_row():
+    rng = np.random.default_rng(14)
+    Hq, Hkv, S, d = 4, 2, 90, 8
+    Q, K, V = rand_qkv(rng, Hq, Hkv, S, d)
+    art = random_art(rng, Hq, S, L=20)
+    O, lse = oracle.attend_prefill(Q, K, V, art)
+    p = S - 1
+    lists = [oracle.kept_list(art, h, p) for h in range(Hq)]
+    ptr = np.concatenate([[0], np.cumsum([len(x) for x in lists])])
+    Od, ld = oracle.attend_lists(Q[:, p], K, V, [h // 2 for h in range(Hq)], ptr, np.concatenate(lists))
+    np.testing.assert_allclose(Od, O[:, p], atol=1e-13)
+    np.testing.assert_allclose(ld, lse[:, p], atol=1e-13)
