@@ -1,0 +1,297 @@
+"""ctypes binding of libdam.so (the C ABI declared in include/dam.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP stream, every step of
+the path runs in the library's kernels. There is no CPU fallback: if the library has not been
+built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdam.so")
+
+DAM_OK, DAM_ERR_INVALID_ARG, DAM_ERR_UNSUPPORTED, DAM_ERR_WORKSPACE, DAM_ERR_CAPACITY, DAM_ERR_DEVICE = 0, -1, -2, -3, -4, -5
+DAM_F32, DAM_BF16 = 0, 1
+DAM_FROM_ATTN_MAP, DAM_FROM_PATTERNS = 0, 1
+
+_STATUS = {0: "DAM_OK", -1: "DAM_ERR_INVALID_ARG", -2: "DAM_ERR_UNSUPPORTED", -3: "DAM_ERR_WORKSPACE",
+           -4: "DAM_ERR_CAPACITY", -5: "DAM_ERR_DEVICE"}
+
+
+class DamError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        super().__init__(f"{fn} returned {_STATUS.get(status, status)}")
+        self.status = status
+
+
+class MaskParams(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("n_maps", ctypes.c_int32), ("pcl", ctypes.c_int32),
+                ("seq", ctypes.c_int32), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
+                ("row_begin", ctypes.c_int32), ("row_end", ctypes.c_int32), ("lam", ctypes.c_float),
+                ("eps", ctypes.c_float), ("tau", ctypes.c_float), ("mu", ctypes.c_float),
+                ("bmin_override", ctypes.c_float)]
+
+
+class MaskOut(ctypes.Structure):
+    _fields_ = [("true_bits", ctypes.c_void_p), ("diag_cnt", ctypes.c_void_p), ("vert_cnt", ctypes.c_void_p),
+                ("diag_flag", ctypes.c_void_p), ("vert_flag", ctypes.c_void_p), ("bmin", ctypes.c_void_p),
+                ("blk_row_ptr", ctypes.c_void_p), ("blk_col", ctypes.c_void_p), ("blk_kind", ctypes.c_void_p),
+                ("tile_bits", ctypes.c_void_p), ("blk_capacity", ctypes.c_int64), ("blk_total", ctypes.c_void_p),
+                ("dense_bits", ctypes.c_void_p), ("kept_ptr", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
+                ("kept_capacity", ctypes.c_int64), ("kept_total", ctypes.c_void_p)]
+
+
+class AttnParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32), ("seq", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
+                ("o_stride", ctypes.c_int64 * 3), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32)]
+
+
+class MaskView(ctypes.Structure):
+    _fields_ = [("blk_row_ptr", ctypes.c_void_p), ("blk_col", ctypes.c_void_p), ("blk_kind", ctypes.c_void_p),
+                ("tile_bits", ctypes.c_void_p)]
+
+
+class DecodeParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32),
+                ("kv_capacity", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("scale", ctypes.c_float), ("q_stride", ctypes.c_int64 * 2), ("kv_stride", ctypes.c_int64 * 3),
+                ("o_stride", ctypes.c_int64 * 2)]
+
+
+EXPORTS = ["dam_mask_build_workspace", "dam_mask_build", "dam_sparse_attn_prefill_workspace",
+           "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode", "dam_version"]
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libdam.so; raises if it has not been built (python -m paper_2506_11104_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python paper_2506_11104_amd/build.py` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64
+        L.dam_mask_build_workspace.restype = sz
+        L.dam_mask_build_workspace.argtypes = [ctypes.POINTER(MaskParams)]
+        L.dam_mask_build.restype = ctypes.c_int
+        L.dam_mask_build.argtypes = [ctypes.POINTER(MaskParams), vp, vp, vp, vp, ctypes.POINTER(MaskOut), vp, sz, vp]
+        L.dam_sparse_attn_prefill_workspace.restype = sz
+        L.dam_sparse_attn_prefill_workspace.argtypes = [ctypes.POINTER(AttnParams)]
+        L.dam_sparse_attn_prefill.restype = ctypes.c_int
+        L.dam_sparse_attn_prefill.argtypes = [ctypes.POINTER(AttnParams), vp, vp, vp, ctypes.POINTER(MaskView), vp, vp,
+                                              vp, sz, vp]
+        L.dam_sparse_attn_decode_workspace.restype = sz
+        L.dam_sparse_attn_decode_workspace.argtypes = [ctypes.POINTER(DecodeParams), i64]
+        L.dam_sparse_attn_decode.restype = ctypes.c_int
+        L.dam_sparse_attn_decode.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dam_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _p(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(fn: str, st: int):
+    if st != DAM_OK:
+        raise DamError(fn, st)
+
+
+# ---------------------------------------------------------------------------------------------
+@dataclass
+class Mask:
+    """Device buffers written by dam_mask_build for H heads at problem length S."""
+    H: int
+    L: int
+    S: int
+    tile_m: int
+    tile_n: int
+    true_bits: Optional[torch.Tensor] = None   # [H][L][ceil(L/64)] i64 (bit patterns of u64)
+    diag_cnt: Optional[torch.Tensor] = None
+    vert_cnt: Optional[torch.Tensor] = None
+    diag_flag: Optional[torch.Tensor] = None
+    vert_flag: Optional[torch.Tensor] = None
+    bmin: Optional[torch.Tensor] = None
+    blk_row_ptr: Optional[torch.Tensor] = None  # [H][nQt+1] i32
+    blk_col: Optional[torch.Tensor] = None
+    blk_kind: Optional[torch.Tensor] = None
+    tile_bits: Optional[torch.Tensor] = None    # [n_tiles][tile_m][tile_n/64] i64
+    n_tiles: int = 0
+    dense_bits: Optional[torch.Tensor] = None
+    kept_ptr: Optional[torch.Tensor] = None
+    kept_idx: Optional[torch.Tensor] = None
+    n_kept: int = 0
+
+    def view(self) -> MaskView:
+        return MaskView(_p(self.blk_row_ptr), _p(self.blk_col), _p(self.blk_kind), _p(self.tile_bits))
+
+
+def mask_workspace(params: MaskParams, device) -> torch.Tensor:
+    n = lib().dam_mask_build_workspace(ctypes.byref(params))
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def dam_mask_build(params: MaskParams, attn_sum, attn_cnt, diag_in, vert_in, out: MaskOut, ws: torch.Tensor) -> None:
+    """Raw call: enqueues on torch's current stream; raises DamError on a non-zero status."""
+    st = lib().dam_mask_build(ctypes.byref(params), _p(attn_sum), _p(attn_cnt), _p(diag_in), _p(vert_in),
+                              ctypes.byref(out), _p(ws), ws.numel(), _stream())
+    _check("dam_mask_build", st)
+
+
+def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: int = 128, lam: float = 0.5,
+               eps: float = 1e-8, tau: float = 0.3, mu: float = 0.8, bmin_override: float = float("nan"),
+               attn_sum: Optional[torch.Tensor] = None, attn_cnt: Optional[torch.Tensor] = None,
+               diag_in: Optional[torch.Tensor] = None, vert_in: Optional[torch.Tensor] = None,
+               true_bits: Optional[torch.Tensor] = None, blocks: bool = True, tile_bits: bool = True,
+               dense: bool = False, rows: Optional[Tuple[int, int]] = None, device="cuda") -> Mask:
+    """Convenience wrapper: allocates the outputs, sizes the tile pool / kept lists with a first
+    call (blk_col == NULL), then fills them with a second. Only allocation and marshalling."""
+    dev = torch.device(device)
+    p = MaskParams(mode, H, L, S, tile_m, tile_n, rows[0] if rows else 0, rows[1] if rows else 0, lam, eps, tau, mu,
+                   bmin_override)
+    ws = mask_workspace(p, dev)
+    m = Mask(H=H, L=L, S=S, tile_m=tile_m, tile_n=tile_n)
+    nQt = (S + tile_m - 1) // tile_m
+    if mode == DAM_FROM_ATTN_MAP:
+        m.true_bits = torch.empty((H, L, (L + 63) // 64), dtype=torch.int64, device=dev)
+        m.diag_cnt = torch.empty((H, L), dtype=torch.int32, device=dev)
+        m.vert_cnt = torch.empty((H, L), dtype=torch.int32, device=dev)
+        m.diag_flag = torch.empty((H, L), dtype=torch.uint8, device=dev)
+        m.vert_flag = torch.empty((H, L), dtype=torch.uint8, device=dev)
+        m.bmin = torch.empty(1, dtype=torch.float32, device=dev)
+    else:
+        m.true_bits = true_bits
+        m.diag_flag, m.vert_flag = diag_in, vert_in
+    totals = torch.zeros(2, dtype=torch.int64, device=dev)
+    o = MaskOut()
+    o.true_bits = _p(m.true_bits)
+    if mode == DAM_FROM_ATTN_MAP:
+        o.diag_cnt, o.vert_cnt, o.diag_flag, o.vert_flag, o.bmin = (_p(m.diag_cnt), _p(m.vert_cnt), _p(m.diag_flag),
+                                                                    _p(m.vert_flag), _p(m.bmin))
+    if blocks:
+        m.blk_row_ptr = torch.empty((H, nQt + 1), dtype=torch.int32, device=dev)
+        o.blk_row_ptr, o.blk_total = _p(m.blk_row_ptr), totals[0:1].data_ptr()
+    if rows:
+        m.kept_ptr = torch.empty(H * (rows[1] - rows[0]) + 1, dtype=torch.int32, device=dev)
+        o.kept_ptr, o.kept_total = _p(m.kept_ptr), totals[1:2].data_ptr()
+    if dense:
+        m.dense_bits = torch.empty((H, S, (S + 63) // 64), dtype=torch.int64, device=dev)
+        o.dense_bits = _p(m.dense_bits)
+    dam_mask_build(p, attn_sum, attn_cnt, diag_in, vert_in, o, ws)
+    if blocks or rows:
+        n_tiles, n_kept = (int(x) for x in totals.cpu())
+        again = False
+        if blocks and n_tiles > 0:
+            m.n_tiles = n_tiles
+            m.blk_col = torch.empty(n_tiles, dtype=torch.int32, device=dev)
+            m.blk_kind = torch.empty(n_tiles, dtype=torch.uint8, device=dev)
+            o.blk_col, o.blk_kind, o.blk_capacity = _p(m.blk_col), _p(m.blk_kind), n_tiles
+            if tile_bits:
+                m.tile_bits = torch.empty((n_tiles, tile_m, tile_n // 64), dtype=torch.int64, device=dev)
+                o.tile_bits = _p(m.tile_bits)
+            again = True
+        elif blocks:
+            m.blk_col = torch.empty(1, dtype=torch.int32, device=dev)
+            m.blk_kind = torch.empty(1, dtype=torch.uint8, device=dev)
+            m.tile_bits = torch.empty((1, tile_m, tile_n // 64), dtype=torch.int64, device=dev)
+        if rows and n_kept > 0:
+            m.n_kept = n_kept
+            m.kept_idx = torch.empty(n_kept, dtype=torch.int32, device=dev)
+            o.kept_idx, o.kept_capacity = _p(m.kept_idx), n_kept
+            again = True
+        if again:
+            o.dense_bits = None
+            dam_mask_build(p, attn_sum, attn_cnt, diag_in, vert_in, o, ws)
+    return m
+
+
+# ---------------------------------------------------------------------------------------------
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DAM_F32
+    if t.dtype == torch.bfloat16:
+        return DAM_BF16
+    raise DamError("dtype", DAM_ERR_UNSUPPORTED)
+
+
+def attn_params(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor, tile_m: int, tile_n: int,
+                scale: float = 0.0) -> AttnParams:
+    B, Hq, S, d = q.shape
+    p = AttnParams()
+    p.batch, p.hq, p.hkv, p.seq, p.head_dim = B, Hq, k.shape[1], S, d
+    p.dtype, p.scale, p.tile_m, p.tile_n = _dtype_code(q), scale, tile_m, tile_n
+    for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o)):
+        assert t.stride(3) == 1
+        setattr(p, name, (ctypes.c_int64 * 3)(*t.stride()[:3]))
+    return p
+
+
+def prefill_workspace(p: AttnParams, device) -> torch.Tensor:
+    n = lib().dam_sparse_attn_prefill_workspace(ctypes.byref(p))
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def dam_sparse_attn_prefill(q, k, v, mask: Mask, out=None, lse=None, scale: float = 0.0, ws=None,
+                            want_lse: bool = False):
+    """q [B][Hq][S][d], k, v [B][Hkv][S][d] (d contiguous) -> out like q (and lse [B][Hq][S] f32)."""
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    p = attn_params(q, k, v, out, mask.tile_m, mask.tile_n, scale)
+    if ws is None:
+        ws = prefill_workspace(p, q.device)
+    mv = mask.view()
+    st = lib().dam_sparse_attn_prefill(ctypes.byref(p), _p(q), _p(k), _p(v), ctypes.byref(mv), _p(out), _p(lse),
+                                       _p(ws), ws.numel(), _stream())
+    _check("dam_sparse_attn_prefill", st)
+    return (out, lse) if (want_lse or lse is not None) else out
+
+
+def decode_params(q: torch.Tensor, kc: torch.Tensor, out: torch.Tensor, scale: float = 0.0) -> DecodeParams:
+    B, Hq, d = q.shape
+    p = DecodeParams()
+    p.batch, p.hq, p.hkv, p.kv_capacity, p.head_dim = B, Hq, kc.shape[1], kc.shape[2], d
+    p.dtype, p.scale = _dtype_code(q), scale
+    p.q_stride = (ctypes.c_int64 * 2)(*q.stride()[:2])
+    p.kv_stride = (ctypes.c_int64 * 3)(*kc.stride()[:3])
+    p.o_stride = (ctypes.c_int64 * 2)(*out.stride()[:2])
+    return p
+
+
+def decode_workspace(p: DecodeParams, max_kept: int, device) -> torch.Tensor:
+    n = lib().dam_sparse_attn_decode_workspace(ctypes.byref(p), max_kept)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def dam_sparse_attn_decode(q, kcache, vcache, kept_ptr, kept_idx, max_kept: int, out=None, lse=None,
+                           scale: float = 0.0, ws=None, want_lse: bool = False):
+    """q [B][Hq][d]; caches [B][Hkv][cap][d] with identical strides; CSR kept lists per (b, hq)."""
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    assert kcache.stride() == vcache.stride()
+    p = decode_params(q, kcache, out, scale)
+    if ws is None:
+        ws = decode_workspace(p, max_kept, q.device)
+    st = lib().dam_sparse_attn_decode(ctypes.byref(p), _p(q), _p(kcache), _p(vcache), _p(kept_ptr), _p(kept_idx),
+                                      max_kept, _p(out), _p(lse), _p(ws), ws.numel(), _stream())
+    _check("dam_sparse_attn_decode", st)
+    return (out, lse) if (want_lse or lse is not None) else out

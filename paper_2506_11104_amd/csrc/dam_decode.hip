@@ -1,0 +1,265 @@
+// dam_sparse_attn_decode: one query row per (sequence, query head) over an explicit kept-key list.
+//
+// Paper (arXiv 2506.11104): Sec. 3 (scaled dot-product attention) with the mask of Sec. 4.3 applied
+// as -inf before the softmax; the kept list is row p of the head's mask.
+//
+// HBM-bound gather of 2 * head_dim * sizeof(T) bytes per kept key. A K or V row is read by LPR
+// adjacent lanes with one 16-byte load each (a whole row per load instruction group, fully
+// coalesced); every lane keeps 4 keys in flight. The kept list is split over several workgroups
+// per head so that all 256 CUs stream; partial (max, sum, O) triples are merged by log-sum-exp.
+// Workgroups are numbered so that all query heads sharing a KV head run on the same XCD and hit
+// the same L2 for the rows their lists have in common.
+#include <hip/hip_bf16.h>
+#include <math.h>
+
+#include <algorithm>
+
+#include "dam_internal.h"
+
+namespace {
+using namespace dam;
+
+constexpr int kXcd = 8;
+constexpr int kUnroll = 4;
+
+struct DecodeArgs {
+  int B, Hq, Hkv, cap, splits;
+  float scale;
+  int64_t q_sb, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_sh;
+};
+
+template <typename T>
+struct Frag;  // 16 bytes of a row as floats
+
+template <>
+struct Frag<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float *p, float (&f)[4]) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
+};
+
+template <>
+struct Frag<__hip_bfloat16> {
+  static constexpr int N = 8;
+  __device__ static void load(const __hip_bfloat16 *p, float (&f)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    const unsigned u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f[2 * k] = __uint_as_float(u[k] << 16);
+      f[2 * k + 1] = __uint_as_float(u[k] & 0xFFFF0000u);
+    }
+  }
+};
+
+__device__ __forceinline__ void store_out(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_out(__hip_bfloat16 *p, float v) { *p = __float2bfloat16(v); }
+
+// Partial result of one split: running max m, sum l (relative to m) and un-normalised O.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *__restrict__ q,
+                                                        const T *__restrict__ kc,
+                                                        const T *__restrict__ vc,
+                                                        const int *__restrict__ kept_ptr,
+                                                        const int *__restrict__ kept_idx,
+                                                        float *__restrict__ part_o,
+                                                        float *__restrict__ part_ml) {
+  constexpr int N = Frag<T>::N;        // elements per lane
+  constexpr int LPR = D / N;           // lanes per row
+  constexpr int GROUPS = 256 / LPR;    // rows in flight per pass of the block
+  __shared__ float s_o[GROUPS][D];
+  __shared__ float s_m[GROUPS], s_l[GROUPS];
+
+  // XCD-aware numbering: block n runs on XCD n % 8; all splits and query heads of one
+  // (sequence, KV head) pair are given ids with the same n % 8.
+  const int G = a.Hq / a.Hkv;
+  const int per_pair = G * a.splits;
+  const int n_pairs = a.B * a.Hkv;
+  const int n = blockIdx.x;
+  const int xcd = n % kXcd, slot = n / kXcd;
+  const int pair = (slot / per_pair) * kXcd + xcd;
+  if (pair >= n_pairs) return;
+  const int within = slot % per_pair;
+  const int hq_in = within / a.splits, split = within % a.splits;
+  const int b = pair / a.Hkv, hkv = pair % a.Hkv;
+  const int hq = hkv * G + hq_in;
+  const int item = b * a.Hq + hq;
+
+  const int group = threadIdx.x / LPR, sub = threadIdx.x % LPR;
+  const int64_t lo = kept_ptr[item], hi = kept_ptr[item + 1];
+  const int64_t len = hi - lo;
+  const int64_t chunk = (len + a.splits - 1) / a.splits;
+  const int64_t beg = lo + (int64_t)split * chunk;
+  const int64_t end = std::min<int64_t>(hi, beg + chunk);
+
+  float qf[N];
+  Frag<T>::load(q + b * a.q_sb + hq * a.q_sh + sub * N, qf);
+  const T *kb = kc + b * a.kv_sb + hkv * a.kv_sh + sub * N;
+  const T *vb = vc + b * a.kv_sb + hkv * a.kv_sh + sub * N;
+  const float sl2 = a.scale * 1.4426950408889634f;  // logits in log2 units
+
+  float m = -INFINITY, l = 0.0f, o[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) o[e] = 0.0f;
+
+  for (int64_t p0 = beg + group * kUnroll; p0 < end; p0 += GROUPS * kUnroll) {
+    float kf[kUnroll][N], vf[kUnroll][N], s[kUnroll];
+    bool live[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      live[u] = p0 + u < end;
+      const int64_t row = live[u] ? kept_idx[p0 + u] : kept_idx[p0];
+      Frag<T>::load(kb + row * a.kv_ss, kf[u]);
+      Frag<T>::load(vb + row * a.kv_ss, vf[u]);
+    }
+    float mx = m;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      float d = 0.0f;
+#pragma unroll
+      for (int e = 0; e < N; ++e) d = fmaf(qf[e], kf[u][e], d);
+#pragma unroll
+      for (int off = LPR / 2; off; off >>= 1) d += __shfl_xor(d, off);
+      s[u] = live[u] ? d * sl2 : -INFINITY;
+      mx = fmaxf(mx, s[u]);
+    }
+    const float corr = exp2f(m - mx);  // m = -inf, mx finite -> 0; p0 < end guarantees mx finite
+    l *= corr;
+#pragma unroll
+    for (int e = 0; e < N; ++e) o[e] *= corr;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const float w = exp2f(s[u] - mx);
+      l += w;
+#pragma unroll
+      for (int e = 0; e < N; ++e) o[e] = fmaf(w, vf[u][e], o[e]);
+    }
+    m = mx;
+  }
+
+  // merge the groups of this block
+  if (sub == 0) {
+    s_m[group] = m;
+    s_l[group] = l;
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) s_o[group][sub * N + e] = o[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float M = -INFINITY;
+    for (int g = 0; g < GROUPS; ++g) M = fmaxf(M, s_m[g]);
+    float Lsum = 0.0f, acc = 0.0f;
+    if (M > -INFINITY)
+      for (int g = 0; g < GROUPS; ++g) {
+        const float w = exp2f(s_m[g] - M);
+        Lsum += w * s_l[g];
+        acc += w * s_o[g][threadIdx.x];
+      }
+    const int64_t slot_out = (int64_t)item * a.splits + split;
+    part_o[slot_out * D + threadIdx.x] = acc;
+    if (threadIdx.x == 0) {
+      part_ml[slot_out * 2] = M;
+      part_ml[slot_out * 2 + 1] = Lsum;
+    }
+  }
+}
+
+template <typename T, int D>
+__global__ void k_decode_merge(DecodeArgs a, const float *__restrict__ part_o,
+                               const float *__restrict__ part_ml, T *__restrict__ out,
+                               float *__restrict__ lse) {
+  const int item = blockIdx.x;
+  const int b = item / a.Hq, hq = item % a.Hq;
+  const int t = threadIdx.x;
+  float M = -INFINITY;
+  for (int s = 0; s < a.splits; ++s) M = fmaxf(M, part_ml[((int64_t)item * a.splits + s) * 2]);
+  float L = 0.0f, acc = 0.0f;
+  if (M > -INFINITY)
+    for (int s = 0; s < a.splits; ++s) {
+      const int64_t at = (int64_t)item * a.splits + s;
+      const float w = exp2f(part_ml[at * 2] - M);
+      L += w * part_ml[at * 2 + 1];
+      acc += w * part_o[at * D + t];
+    }
+  const float res = L > 0.0f ? acc / L : 0.0f;
+  store_out(out + b * a.o_sb + hq * a.o_sh + t, res);
+  if (lse && t == 0)
+    lse[item] = L > 0.0f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+}
+
+int pick_splits(const dam_decode_params *p, int64_t max_kept) {
+  const int64_t items = (int64_t)p->batch * p->hq;
+  int64_t s = (max_kept + 511) / 512;                       // about 512 keys per workgroup
+  s = std::max<int64_t>(s, (1024 + items - 1) / items);     // at least ~4 workgroups per CU
+  s = std::min<int64_t>(s, std::max<int64_t>(1, max_kept / 64));
+  return (int)std::min<int64_t>(std::max<int64_t>(s, 1), 64);
+}
+
+int validate(const dam_decode_params *p, const void *q, const void *kc, const void *vc,
+             const int32_t *kept_ptr, const int32_t *kept_idx, int64_t max_kept, const void *out) {
+  if (!p || !q || !kc || !vc || !kept_ptr || !out) return DAM_ERR_INVALID_ARG;
+  if (p->batch < 1 || p->hq < 1 || p->hkv < 1 || p->hq % p->hkv || p->kv_capacity < 1) return DAM_ERR_INVALID_ARG;
+  if (max_kept < 0 || (max_kept > 0 && !kept_idx)) return DAM_ERR_INVALID_ARG;
+  if (p->dtype != DAM_F32 && p->dtype != DAM_BF16) return DAM_ERR_UNSUPPORTED;
+  if (p->head_dim != 64 && p->head_dim != 128) return DAM_ERR_UNSUPPORTED;
+  const int align = p->dtype == DAM_BF16 ? 8 : 4;  // elements per 16 bytes
+  const int64_t strides[] = {p->q_stride[0], p->q_stride[1], p->kv_stride[0], p->kv_stride[1], p->kv_stride[2]};
+  for (int64_t s : strides)
+    if (s < 0 || s % align) return DAM_ERR_INVALID_ARG;
+  if (p->o_stride[0] < 0 || p->o_stride[1] < 0) return DAM_ERR_INVALID_ARG;
+  if (!(p->scale >= 0.0f)) return DAM_ERR_INVALID_ARG;
+  return DAM_OK;
+}
+
+template <typename T, int D>
+void launch(const DecodeArgs &a, const void *q, const void *kc, const void *vc, const int32_t *kept_ptr,
+            const int32_t *kept_idx, void *out, float *lse, float *part_o, float *part_ml, hipStream_t st) {
+  const int G = a.Hq / a.Hkv;
+  const int n_pairs = a.B * a.Hkv;
+  const int rounds = (n_pairs + kXcd - 1) / kXcd;
+  const int blocks = rounds * kXcd * G * a.splits;
+  k_decode_partial<T, D><<<blocks, 256, 0, st>>>(a, static_cast<const T *>(q), static_cast<const T *>(kc),
+                                                static_cast<const T *>(vc), kept_ptr, kept_idx, part_o, part_ml);
+  k_decode_merge<T, D><<<a.B * a.Hq, D, 0, st>>>(a, part_o, part_ml, static_cast<T *>(out), lse);
+}
+
+}  // namespace
+
+extern "C" size_t dam_sparse_attn_decode_workspace(const dam_decode_params *p, int64_t max_kept) {
+  if (!p || p->batch < 1 || p->hq < 1 || p->head_dim < 1 || max_kept < 0) return 0;
+  const int splits = pick_splits(p, max_kept);
+  Carver c(nullptr);
+  c.take<float>((size_t)p->batch * p->hq * splits * p->head_dim);
+  c.take<float>((size_t)p->batch * p->hq * splits * 2);
+  return c.off;
+}
+
+extern "C" int dam_sparse_attn_decode(const dam_decode_params *p, const void *q, const void *kcache,
+                                      const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
+                                      int64_t max_kept, void *out, float *lse, void *ws, size_t ws_bytes,
+                                      void *stream_v) {
+  const int bad = validate(p, q, kcache, vcache, kept_ptr, kept_idx, max_kept, out);
+  if (bad != DAM_OK) return bad;
+  if (!ws || ws_bytes < dam_sparse_attn_decode_workspace(p, max_kept)) return DAM_ERR_WORKSPACE;
+  DecodeArgs a;
+  a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity;
+  a.splits = pick_splits(p, max_kept);
+  a.scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf((float)p->head_dim);
+  a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1];
+  a.kv_sb = p->kv_stride[0]; a.kv_sh = p->kv_stride[1]; a.kv_ss = p->kv_stride[2];
+  a.o_sb = p->o_stride[0]; a.o_sh = p->o_stride[1];
+  Carver c(ws);
+  float *part_o = c.take<float>((size_t)a.B * a.Hq * a.splits * p->head_dim);
+  float *part_ml = c.take<float>((size_t)a.B * a.Hq * a.splits * 2);
+  hipStream_t st = static_cast<hipStream_t>(stream_v);
+  if (p->dtype == DAM_BF16) {
+    if (p->head_dim == 128) launch<__hip_bfloat16, 128>(a, q, kcache, vcache, kept_ptr, kept_idx, out, lse, part_o, part_ml, st);
+    else launch<__hip_bfloat16, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, out, lse, part_o, part_ml, st);
+  } else {
+    if (p->head_dim == 128) launch<float, 128>(a, q, kcache, vcache, kept_ptr, kept_idx, out, lse, part_o, part_ml, st);
+    else launch<float, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, out, lse, part_o, part_ml, st);
+  }
+  return launch_status();
+}

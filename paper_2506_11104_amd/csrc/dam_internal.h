@@ -1,0 +1,31 @@
+// Internal helpers shared by the HIP translation units of libdam.so (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dam.h"
+
+namespace dam {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Converts the status of the launches enqueued so far into a dam_status.
+inline int launch_status() { return hipGetLastError() == hipSuccess ? DAM_OK : DAM_ERR_DEVICE; }
+
+// Carves consecutive 256-byte aligned regions out of one workspace allocation.
+struct Carver {
+  char *base;
+  size_t off = 0;
+  explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+  template <typename T>
+  T *take(size_t n) {
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off = align_up(off + n * sizeof(T), 256);
+    return p;
+  }
+};
+
+}  // namespace dam

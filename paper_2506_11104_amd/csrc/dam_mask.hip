@@ -1,0 +1,598 @@
+// dam_mask_build: attention statistics at the pattern capture length -> per-head sparse mask.
+//
+// Paper (arXiv 2506.11104): Sec. 4.2.2 (mean, clamp, Box-Cox, global-min shift), Sec. 4.2.3 (true
+// mask by threshold tau), Sec. 4.2.4 (diagonal / vertical pattern pool, match score gamma against
+// mu), Sec. 4.3 (mask of a length-S problem: true mask inside the L x L block, matched patterns
+// continued elsewhere). The tile pooling, block index and kept lists are this library's own data
+// structures for the sparse attention kernels.
+//
+// Everything here is streaming bit work bounded by HBM bandwidth: A is read once (lower triangle
+// only for a single causal capture), one wave turns 64 keys into one mask word with a ballot, and
+// the S x S mask is never materialised: any 64-key word of any row is recomputed on the fly from
+// the true bits, the column bitset and a bit-reversed diagonal bitset (one funnel shift).
+#include <math.h>
+
+#include <algorithm>
+
+#include "dam_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+using namespace dam;
+
+struct Geom {
+  int H, L, S, P;            // P: length of the pattern flag arrays (L from a map, S when given)
+  int tile_m, tile_n, nQt, nKt, wpr;
+  int tbw;                   // words per true_bits row, ceil(L / 64)
+  int pw;                    // words per pattern bitset, ceil(P / 64)
+  int occw;                  // occupancy words per query tile, ceil(nKt / 64)
+};
+
+// ------------------------------------------------------------------------------------------------
+// Sec. 4.2.2 in the fixed fp32 sequence (each op rounded to nearest, nothing contracted).
+__device__ __forceinline__ float clamp_mean(float a, float c, float eps) {
+  const float denom = __fadd_rn(c, eps);
+  const float abar = __fdiv_rn(a, denom);
+  return fmaxf(abar, eps);
+}
+
+template <int LAMBDA2>  // 2 * lambda: 1 -> lambda 0.5, 2 -> lambda 1
+__device__ __forceinline__ float box_cox(float x) {
+  if (LAMBDA2 == 1) {
+    const float root = __fsqrt_rn(x);
+    const float num = __fsub_rn(root, 1.0f);
+    return __fdiv_rn(num, 0.5f);
+  }
+  return __fsub_rn(x, 1.0f);
+}
+
+// Single causal capture with L >= 2: some pair was never computed, its X is the clamp eps, and no
+// X is smaller; Box-Cox is non-decreasing, so the global minimum is the Box-Cox of eps.
+template <int LAMBDA2>
+__global__ void k_bmin_closed(float eps, float *bmin) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *bmin = box_cox<LAMBDA2>(clamp_mean(0.0f, 0.0f, eps));
+}
+
+__global__ void k_set_f32(float *p, float v) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
+}
+
+__global__ void k_copy_f32(float *dst, const float *src) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
+}
+
+// General case: min over every stored entry. min B = B(min X) because every step after X is
+// non-decreasing; X > 0, so its bit pattern orders like an unsigned integer.
+__global__ void k_min_x(const float *__restrict__ A, const float *__restrict__ C, int64_t n, int L,
+                        float eps, unsigned *xmin_bits) {
+  float m = INFINITY;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    float a, c;
+    if (C) {
+      a = A[e];
+      c = C[e];
+    } else {  // only reached for L == 1 (a single valid pair per map)
+      a = A[e];
+      c = 1.0f;
+    }
+    m = fminf(m, clamp_mean(a, c, eps));
+  }
+  for (int off = 32; off; off >>= 1) m = fminf(m, __shfl_xor(m, off));
+  if ((threadIdx.x & 63) == 0) atomicMin(xmin_bits, __float_as_uint(m));
+}
+
+template <int LAMBDA2>
+__global__ void k_bmin_from_x(const unsigned *xmin_bits, float *bmin) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *bmin = box_cox<LAMBDA2>(__uint_as_float(*xmin_bits));
+}
+
+__global__ void k_fill_u32(unsigned *p, int64_t n, unsigned v) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+       e += (int64_t)gridDim.x * blockDim.x)
+    p[e] = v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Sec. 4.2.3: m[i][j] = (B - bmin >= tau) and j <= i. One wave = 4 rows x 4 words (256 keys); each
+// lane owns one key per word so every load is a fully coalesced 256-byte row segment, and the
+// 16 loads of a lane are independent. Entries above the diagonal are never kept, so never read.
+constexpr int kTmRows = 16;  // rows per block (4 per wave)
+
+template <int LAMBDA2>
+__global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A,
+                                                   const float *__restrict__ C, int L, int tbw,
+                                                   float eps, float tau,
+                                                   const float *__restrict__ bmin_p,
+                                                   uint64_t *__restrict__ true_bits) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.z;
+  const int w0 = blockIdx.x * 4;
+  const int r0 = blockIdx.y * kTmRows + wave * 4;
+  const float bmin = *bmin_p;
+  const float *Ah = A + (int64_t)h * L * L;
+  const float *Ch = C ? C + (int64_t)h * L * L : nullptr;
+  float a[4][4], c[4][4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = r0 + r, j = (w0 + k) * 64 + lane;
+      const bool live = i < L && j <= i;
+      a[r][k] = live ? Ah[(int64_t)i * L + j] : 0.0f;
+      c[r][k] = live ? (Ch ? Ch[(int64_t)i * L + j] : 1.0f) : 0.0f;
+    }
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = r0 + r, j = (w0 + k) * 64 + lane;
+      const bool live = i < L && j <= i;
+      const float b = box_cox<LAMBDA2>(clamp_mean(a[r][k], c[r][k], eps));
+      const float bstar = __fsub_rn(b, bmin);
+      const uint64_t word = __ballot(live && bstar >= tau);
+      if (lane == 0 && i < L && w0 + k < tbw) true_bits[((int64_t)h * L + i) * tbw + w0 + k] = word;
+    }
+}
+
+// Sec. 4.2.4 numerators: kept entries per column and per diagonal of the true mask. Each wave
+// walks 64 rows; lane = column (vertical) or offset (diagonal). Integer atomics: order-free.
+__global__ __launch_bounds__(256) void k_pattern_counts(const uint64_t *__restrict__ true_bits, int L,
+                                                        int tbw, int *__restrict__ vert_cnt,
+                                                        int *__restrict__ diag_cnt) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.z;
+  const int p = blockIdx.x * 64 + lane;  // column c, and also offset r
+  const int i0 = blockIdx.y * 256 + wave * 64;
+  const uint64_t *tb = true_bits + (int64_t)h * L * tbw;
+  int nv = 0, nd = 0;
+  const int i1 = min(L, i0 + 64);
+  for (int i = i0; i < i1; ++i) {
+    const uint64_t wv = tb[(int64_t)i * tbw + blockIdx.x];
+    nv += (int)((wv >> lane) & 1);
+    const int j = i - p;
+    if (j >= 0) nd += (int)((tb[(int64_t)i * tbw + (j >> 6)] >> (j & 63)) & 1);
+  }
+  if (p < L) {
+    if (nv) atomicAdd(&vert_cnt[(int64_t)h * L + p], nv);
+    if (nd) atomicAdd(&diag_cnt[(int64_t)h * L + p], nd);
+  }
+}
+
+// gamma = kept / size, matched iff gamma >= mu; pattern p has L - p entries.
+__global__ void k_pattern_flags(const int *__restrict__ diag_cnt, const int *__restrict__ vert_cnt,
+                                int H, int L, float mu, uint8_t *__restrict__ diag_flag,
+                                uint8_t *__restrict__ vert_flag) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= (int64_t)H * L) return;
+  const int p = (int)(e % L);
+  const float size = (float)(L - p);
+  diag_flag[e] = (uint8_t)(__fdiv_rn((float)diag_cnt[e], size) >= mu);
+  vert_flag[e] = (uint8_t)(__fdiv_rn((float)vert_cnt[e], size) >= mu);
+}
+
+// Flags -> bitsets. cbits bit c = column c matched. rrev bit q = diagonal (pw*64 - 1 - q) matched,
+// i.e. the diagonal set reversed, so that the 64 offsets i-j, i-j-1, ... of one mask word are 64
+// consecutive ascending bits.
+__global__ void k_pattern_bitsets(const uint8_t *__restrict__ diag_flag,
+                                  const uint8_t *__restrict__ vert_flag, int P, int pw,
+                                  uint64_t *__restrict__ cbits, uint64_t *__restrict__ rrev) {
+  const int lane = threadIdx.x & 63;
+  const int w = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int h = blockIdx.y;
+  if (w >= pw) return;
+  const int q = w * 64 + lane;
+  const int r = pw * 64 - 1 - q;
+  const uint64_t cw = __ballot(q < P && vert_flag[(int64_t)h * P + q] != 0);
+  const uint64_t rw = __ballot(r < P && diag_flag[(int64_t)h * P + r] != 0);
+  if (lane == 0) {
+    cbits[(int64_t)h * pw + w] = cw;
+    rrev[(int64_t)h * pw + w] = rw;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Sec. 4.3: the 64 mask bits of row i, keys [64 wj, 64 wj + 64) of one head.
+__device__ __forceinline__ uint64_t diag_window(const uint64_t *__restrict__ rrev, int pw, int64_t u) {
+  // bit t <- diagonal offset u - t; in the reversed set that is position s0 + t.
+  const int64_t Q = (int64_t)pw * 64 - 1;
+  const int64_t s0 = Q - u;
+  if (s0 > Q || s0 + 63 < 0) return 0;
+  const int64_t w0 = s0 >> 6;
+  const int sh = (int)(s0 & 63);
+  const uint64_t lo = (w0 >= 0 && w0 < pw) ? rrev[w0] : 0;
+  if (sh == 0) return lo;
+  const uint64_t hi = (w0 + 1 >= 0 && w0 + 1 < pw) ? rrev[w0 + 1] : 0;
+  return (lo >> sh) | (hi << (64 - sh));
+}
+
+__device__ __forceinline__ uint64_t mask_word(const Geom &g, const uint64_t *__restrict__ tb_h,
+                                              const uint64_t *__restrict__ cb_h,
+                                              const uint64_t *__restrict__ rr_h, int i, int wj) {
+  if (i >= g.S) return 0;
+  const int64_t u = (int64_t)i - (int64_t)wj * 64;
+  if (u < 0) return 0;
+  const uint64_t causal = u >= 63 ? ~0ull : ((2ull << u) - 1);
+  if (i < g.L) {  // top-left block (and the whole mask when S <= L): the true mask
+    const int64_t left = (int64_t)g.L - (int64_t)wj * 64;  // > 0 because j <= i < L
+    const uint64_t inside = left >= 64 ? ~0ull : ((1ull << left) - 1);
+    return tb_h[(int64_t)i * g.tbw + wj] & causal & inside;
+  }
+  uint64_t pat = wj < g.pw ? cb_h[wj] : 0;
+  pat |= diag_window(rr_h, g.pw, u);
+  return pat & causal;
+}
+
+// Pass 1 of the block index: which key tiles of query tile (h, qt) hold a kept entry / are full.
+// One wave evaluates one tile (lanes cover its tile_m x wpr words).
+__global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__restrict__ true_bits,
+                                                   const uint64_t *__restrict__ cbits,
+                                                   const uint64_t *__restrict__ rrev,
+                                                   uint64_t *__restrict__ occ,
+                                                   uint64_t *__restrict__ full, int *__restrict__ cnt) {
+  extern __shared__ uint8_t flags[];  // [nKt] bit0 occupied, bit1 full
+  __shared__ int total;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qt = blockIdx.x, h = blockIdx.y;
+  const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
+  const uint64_t *cb = cbits + (int64_t)h * g.pw;
+  const uint64_t *rr = rrev + (int64_t)h * g.pw;
+  const int i_last = min(g.S - 1, qt * g.tile_m + g.tile_m - 1);
+  const int kmax = i_last / g.tile_n;
+  if (threadIdx.x == 0) total = 0;
+  for (int kt = threadIdx.x; kt < g.nKt; kt += blockDim.x) flags[kt] = 0;
+  __syncthreads();
+  const int words = g.tile_m * g.wpr;
+  for (int kt = wave; kt <= kmax; kt += 4) {
+    bool any = false, all = true;
+    for (int w = lane; w < words; w += 64) {
+      const uint64_t m = mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + w % g.wpr);
+      any |= m != 0;
+      all &= m == ~0ull;
+    }
+    const bool t_any = __ballot(any) != 0;
+    const bool t_all = __ballot(!all) == 0;
+    if (lane == 0) flags[kt] = (uint8_t)((t_any ? 1 : 0) | (t_all ? 2 : 0));
+  }
+  __syncthreads();
+  int mine = 0;
+  for (int w = wave; w < g.occw; w += 4) {
+    const int kt = w * 64 + lane;
+    const uint8_t f = kt < g.nKt ? flags[kt] : 0;
+    const uint64_t ow = __ballot(f & 1), fw = __ballot(f & 2);
+    if (lane == 0) {
+      occ[((int64_t)h * g.nQt + qt) * g.occw + w] = ow;
+      full[((int64_t)h * g.nQt + qt) * g.occw + w] = fw;
+      mine += __popcll(ow);
+    }
+  }
+  if (lane == 0 && mine) atomicAdd(&total, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) cnt[(int64_t)h * g.nQt + qt] = total;
+}
+
+// Exclusive scan of n counts by one block. group > 0: the result is laid out as [n / group]
+// rows of group + 1 offsets (row r ends where row r + 1 begins); group == 0: plain [n + 1].
+__global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__ cnt, int64_t n,
+                                                         int group, int *__restrict__ ptr,
+                                                         int64_t *__restrict__ total) {
+  __shared__ int64_t wave_sum[16];
+  __shared__ int64_t carry;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < n; base += 1024) {
+    const int64_t e = base + threadIdx.x;
+    const int64_t v = e < n ? cnt[e] : 0;
+    int64_t incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+      const int64_t up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int64_t before = carry;
+    for (int w = 0; w < wave; ++w) before += wave_sum[w];
+    const int64_t excl = before + incl - v;
+    if (e < n) {
+      if (group > 0) {
+        const int64_t r = e / group, q = e % group;
+        ptr[r * (group + 1) + q] = (int)excl;
+        if (q == 0 && r > 0) ptr[(r - 1) * (group + 1) + group] = (int)excl;
+      } else {
+        ptr[e] = (int)excl;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 1023) carry = excl + v;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    if (group > 0)
+      ptr[(n / group - 1) * (group + 1) + group] = (int)carry;
+    else
+      ptr[n] = (int)carry;
+    if (total) *total = carry;
+  }
+}
+
+// Pass 2: write column, kind and the tile's element bits for every listed tile (below capacity).
+__global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__restrict__ true_bits,
+                                                   const uint64_t *__restrict__ cbits,
+                                                   const uint64_t *__restrict__ rrev,
+                                                   const uint64_t *__restrict__ occ,
+                                                   const uint64_t *__restrict__ full,
+                                                   const int *__restrict__ row_ptr,
+                                                   int *__restrict__ blk_col,
+                                                   uint8_t *__restrict__ blk_kind,
+                                                   uint64_t *__restrict__ tile_bits, int64_t capacity) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qt = blockIdx.x, h = blockIdx.y;
+  const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
+  const uint64_t *cb = cbits + (int64_t)h * g.pw;
+  const uint64_t *rr = rrev + (int64_t)h * g.pw;
+  const uint64_t *oc = occ + ((int64_t)h * g.nQt + qt) * g.occw;
+  const uint64_t *fl = full + ((int64_t)h * g.nQt + qt) * g.occw;
+  const int64_t first = row_ptr[(int64_t)h * (g.nQt + 1) + qt];
+  const int i_last = min(g.S - 1, qt * g.tile_m + g.tile_m - 1);
+  const int kmax = i_last / g.tile_n;
+  const int words = g.tile_m * g.wpr;
+  for (int kt = wave; kt <= kmax; kt += 4) {
+    const uint64_t ow = oc[kt >> 6];
+    if (!((ow >> (kt & 63)) & 1)) continue;
+    int rank = __popcll(ow & (((uint64_t)1 << (kt & 63)) - 1));
+    for (int w = 0; w < (kt >> 6); ++w) rank += __popcll(oc[w]);
+    const int64_t t = first + rank;
+    if (t >= capacity) continue;
+    if (lane == 0) {
+      if (blk_col) blk_col[t] = kt;
+      if (blk_kind) blk_kind[t] = (uint8_t)((fl[kt >> 6] >> (kt & 63)) & 1);
+    }
+    if (tile_bits)
+      for (int w = lane; w < words; w += 64)
+        tile_bits[t * words + w] =
+            mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + w % g.wpr);
+  }
+}
+
+__global__ void k_dense_bits(Geom g, const uint64_t *__restrict__ true_bits,
+                             const uint64_t *__restrict__ cbits, const uint64_t *__restrict__ rrev,
+                             int sw, uint64_t *__restrict__ dense) {
+  const int h = blockIdx.z, i = blockIdx.y;
+  const int w = blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= sw) return;
+  const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
+  dense[((int64_t)h * g.S + i) * sw + w] =
+      mask_word(g, tb, cbits + (int64_t)h * g.pw, rrev + (int64_t)h * g.pw, i, w);
+}
+
+// Kept-key lists of rows [row_begin, row_end): count, scan, fill (ascending).
+__global__ __launch_bounds__(256) void k_row_count(Geom g, const uint64_t *__restrict__ true_bits,
+                                                   const uint64_t *__restrict__ cbits,
+                                                   const uint64_t *__restrict__ rrev, int row_begin,
+                                                   int nrows, int *__restrict__ cnt) {
+  __shared__ int total;
+  const int h = blockIdx.y, i = row_begin + blockIdx.x;
+  const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
+  if (threadIdx.x == 0) total = 0;
+  __syncthreads();
+  int mine = 0;
+  for (int w = threadIdx.x; w <= (i >> 6); w += blockDim.x)
+    mine += __popcll(mask_word(g, tb, cbits + (int64_t)h * g.pw, rrev + (int64_t)h * g.pw, i, w));
+  for (int off = 32; off; off >>= 1) mine += __shfl_xor(mine, off);
+  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&total, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) cnt[(int64_t)h * nrows + blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void k_row_fill(Geom g, const uint64_t *__restrict__ true_bits,
+                                                  const uint64_t *__restrict__ cbits,
+                                                  const uint64_t *__restrict__ rrev, int row_begin,
+                                                  int nrows, const int *__restrict__ kept_ptr,
+                                                  int *__restrict__ kept_idx, int64_t capacity) {
+  __shared__ int wave_sum[4];
+  __shared__ int carry;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.y, i = row_begin + blockIdx.x;
+  const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
+  const int64_t first = kept_ptr[(int64_t)h * nrows + blockIdx.x];
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  const int nw = (i >> 6) + 1;
+  for (int base = 0; base < nw; base += 256) {
+    const int w = base + threadIdx.x;
+    uint64_t m = w < nw ? mask_word(g, tb, cbits + (int64_t)h * g.pw, rrev + (int64_t)h * g.pw, i, w) : 0;
+    const int v = __popcll(m);
+    int incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int before = carry;
+    for (int x = 0; x < wave; ++x) before += wave_sum[x];
+    int64_t at = first + before + incl - v;
+    while (m) {
+      const int b = __ffsll((unsigned long long)m) - 1;
+      if (at < capacity) kept_idx[at] = w * 64 + b;
+      ++at;
+      m &= m - 1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 255) carry = before + incl;
+    __syncthreads();
+  }
+}
+
+int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *diag_in,
+             const uint8_t *vert_in, const dam_mask_out *o) {
+  if (!p || !o) return DAM_ERR_INVALID_ARG;
+  if (p->mode != DAM_FROM_ATTN_MAP && p->mode != DAM_FROM_PATTERNS) return DAM_ERR_INVALID_ARG;
+  if (p->n_maps < 1 || p->seq < 1) return DAM_ERR_INVALID_ARG;
+  if (p->tile_m < 64 || p->tile_n < 64 || p->tile_m % 64 || p->tile_n % 64) return DAM_ERR_INVALID_ARG;
+  if (p->tile_m > 256 || p->tile_n > 256) return DAM_ERR_UNSUPPORTED;
+  if ((int64_t)(p->seq + p->tile_n - 1) / p->tile_n > 32768) return DAM_ERR_UNSUPPORTED;
+  if (p->mode == DAM_FROM_ATTN_MAP) {
+    if (p->pcl < 1 || !attn_sum || !o->true_bits) return DAM_ERR_INVALID_ARG;
+    if (!(p->eps > 0.0f)) return DAM_ERR_INVALID_ARG;
+    if (p->lambda != 0.5f && p->lambda != 1.0f) return DAM_ERR_UNSUPPORTED;
+    if (isnan(p->tau) || isnan(p->mu)) return DAM_ERR_INVALID_ARG;
+  } else {
+    if (p->pcl < 0 || !diag_in || !vert_in) return DAM_ERR_INVALID_ARG;
+    if (p->pcl > 0 && !o->true_bits) return DAM_ERR_INVALID_ARG;
+  }
+  const bool blocks = o->blk_col || o->blk_kind || o->tile_bits || o->blk_total || o->blk_row_ptr;
+  if (blocks && (!o->blk_row_ptr || !o->blk_total || o->blk_capacity < 0)) return DAM_ERR_INVALID_ARG;
+  if ((o->blk_col || o->blk_kind || o->tile_bits) && o->blk_capacity < 1) return DAM_ERR_INVALID_ARG;
+  if (o->dense_bits && p->seq > 65535) return DAM_ERR_UNSUPPORTED;
+  if (o->kept_ptr || o->kept_idx || o->kept_total) {
+    if (!o->kept_ptr || !o->kept_total || o->kept_capacity < 0) return DAM_ERR_INVALID_ARG;
+    if (p->row_begin < 0 || p->row_begin > p->row_end || p->row_end > p->seq) return DAM_ERR_INVALID_ARG;
+    if ((int64_t)p->n_maps * (p->row_end - p->row_begin) > (int64_t)1 << 30) return DAM_ERR_UNSUPPORTED;
+  }
+  return DAM_OK;
+}
+
+struct Workspace {
+  float *bmin;
+  unsigned *xmin_bits;
+  int *diag_cnt, *vert_cnt;
+  uint8_t *diag_flag, *vert_flag;
+  uint64_t *cbits, *rrev, *occ, *full;
+  int *tile_cnt, *row_cnt;
+  size_t bytes;
+};
+
+Geom geometry(const dam_mask_params *p) {
+  Geom g;
+  g.H = p->n_maps;
+  g.L = p->pcl;
+  g.S = p->seq;
+  g.P = p->mode == DAM_FROM_ATTN_MAP ? p->pcl : p->seq;
+  g.tile_m = p->tile_m;
+  g.tile_n = p->tile_n;
+  g.nQt = (g.S + g.tile_m - 1) / g.tile_m;
+  g.nKt = (g.S + g.tile_n - 1) / g.tile_n;
+  g.wpr = g.tile_n / 64;
+  g.tbw = (g.L + 63) / 64;
+  g.pw = (g.P + 63) / 64;
+  g.occw = (g.nKt + 63) / 64;
+  return g;
+}
+
+Workspace carve(const dam_mask_params *p, void *ws) {
+  const Geom g = geometry(p);
+  Carver c(ws);
+  Workspace w;
+  const size_t HL = (size_t)g.H * (size_t)(g.L > 0 ? g.L : 1);
+  w.bmin = c.take<float>(1);
+  w.xmin_bits = c.take<unsigned>(1);
+  w.diag_cnt = c.take<int>(HL);
+  w.vert_cnt = c.take<int>(HL);
+  w.diag_flag = c.take<uint8_t>(HL);
+  w.vert_flag = c.take<uint8_t>(HL);
+  w.cbits = c.take<uint64_t>((size_t)g.H * g.pw);
+  w.rrev = c.take<uint64_t>((size_t)g.H * g.pw);
+  w.occ = c.take<uint64_t>((size_t)g.H * g.nQt * g.occw);
+  w.full = c.take<uint64_t>((size_t)g.H * g.nQt * g.occw);
+  w.tile_cnt = c.take<int>((size_t)g.H * g.nQt);
+  const int nrows = p->row_end > p->row_begin ? p->row_end - p->row_begin : 0;
+  w.row_cnt = c.take<int>((size_t)g.H * (size_t)(nrows > 0 ? nrows : 1));
+  w.bytes = c.off;
+  return w;
+}
+
+}  // namespace
+
+extern "C" size_t dam_mask_build_workspace(const dam_mask_params *p) {
+  if (!p || p->n_maps < 1 || p->seq < 1 || p->pcl < 0 || p->tile_m < 64 || p->tile_n < 64 ||
+      p->tile_m % 64 || p->tile_n % 64)
+    return 0;
+  return carve(p, nullptr).bytes;
+}
+
+extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, const float *attn_cnt,
+                              const uint8_t *diag_in, const uint8_t *vert_in, const dam_mask_out *o,
+                              void *ws, size_t ws_bytes, void *stream_v) {
+  const int bad = validate(p, attn_sum, diag_in, vert_in, o);
+  if (bad != DAM_OK) return bad;
+  if (!ws || ws_bytes < dam_mask_build_workspace(p)) return DAM_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  const Geom g = geometry(p);
+  const Workspace w = carve(p, ws);
+  const uint8_t *dflag = diag_in, *vflag = vert_in;
+  const uint64_t *true_bits = g.L > 0 ? o->true_bits : nullptr;
+
+  if (p->mode == DAM_FROM_ATTN_MAP) {
+    const bool half = p->lambda == 0.5f;
+    // a1: the global minimum of the Box-Cox map
+    if (!isnan(p->bmin_override)) {
+      k_set_f32<<<1, 64, 0, stream>>>(w.bmin, p->bmin_override);
+    } else if (!attn_cnt && g.L >= 2) {
+      if (half) k_bmin_closed<1><<<1, 64, 0, stream>>>(p->eps, w.bmin);
+      else k_bmin_closed<2><<<1, 64, 0, stream>>>(p->eps, w.bmin);
+    } else {
+      const int64_t n = (int64_t)g.H * g.L * g.L;
+      k_fill_u32<<<1, 64, 0, stream>>>(w.xmin_bits, 1, 0x7F800000u);
+      const int blocks = (int)std::min<int64_t>((n + 1023) / 1024, 256 * 16);
+      k_min_x<<<blocks, 256, 0, stream>>>(attn_sum, attn_cnt, n, g.L, p->eps, w.xmin_bits);
+      if (half) k_bmin_from_x<1><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
+      else k_bmin_from_x<2><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
+    }
+    // a2: true mask
+    {
+      dim3 grid((g.tbw + 3) / 4, (g.L + kTmRows - 1) / kTmRows, g.H);
+      if (half)
+        k_true_mask<1><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, p->tau, w.bmin, o->true_bits);
+      else
+        k_true_mask<2><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, p->tau, w.bmin, o->true_bits);
+    }
+    // a3: match scores
+    int *dcnt = o->diag_cnt ? o->diag_cnt : w.diag_cnt;
+    int *vcnt = o->vert_cnt ? o->vert_cnt : w.vert_cnt;
+    uint8_t *df = o->diag_flag ? o->diag_flag : w.diag_flag;
+    uint8_t *vf = o->vert_flag ? o->vert_flag : w.vert_flag;
+    const int64_t HL = (int64_t)g.H * g.L;
+    const int fb = (int)std::min<int64_t>((HL + 255) / 256, 4096);
+    k_fill_u32<<<fb, 256, 0, stream>>>(reinterpret_cast<unsigned *>(dcnt), HL, 0u);
+    k_fill_u32<<<fb, 256, 0, stream>>>(reinterpret_cast<unsigned *>(vcnt), HL, 0u);
+    k_pattern_counts<<<dim3(g.tbw, (g.L + 255) / 256, g.H), 256, 0, stream>>>(o->true_bits, g.L, g.tbw, vcnt, dcnt);
+    k_pattern_flags<<<(int)((HL + 255) / 256), 256, 0, stream>>>(dcnt, vcnt, g.H, g.L, p->mu, df, vf);
+    dflag = df;
+    vflag = vf;
+    if (o->bmin) k_copy_f32<<<1, 64, 0, stream>>>(o->bmin, w.bmin);
+  }
+
+  const bool want_blocks = o->blk_row_ptr != nullptr;
+  const bool want_lists = o->kept_ptr != nullptr;
+  if (want_blocks || want_lists || o->dense_bits) {
+    k_pattern_bitsets<<<dim3((g.pw + 3) / 4, g.H), 256, 0, stream>>>(dflag, vflag, g.P, g.pw, w.cbits, w.rrev);
+  }
+  // a4 + a5: tile occupancy, CSR offsets, tile bits
+  if (want_blocks) {
+    k_tile_scan<<<dim3(g.nQt, g.H), 256, (size_t)g.nKt, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, w.tile_cnt);
+    k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total);
+    if (o->blk_col || o->blk_kind || o->tile_bits)
+      k_tile_fill<<<dim3(g.nQt, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,
+                                                        o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity);
+  }
+  if (o->dense_bits) {
+    const int sw = (g.S + 63) / 64;
+    k_dense_bits<<<dim3((sw + 255) / 256, g.S, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, sw, o->dense_bits);
+  }
+  if (want_lists) {
+    const int nrows = p->row_end - p->row_begin;
+    if (nrows > 0) {
+      k_row_count<<<dim3(nrows, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, nrows, w.row_cnt);
+      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)g.H * nrows, 0, o->kept_ptr, o->kept_total);
+      if (o->kept_idx && o->kept_capacity > 0)
+        k_row_fill<<<dim3(nrows, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, nrows, o->kept_ptr,
+                                                         o->kept_idx, o->kept_capacity);
+    } else {
+      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, 0, 0, o->kept_ptr, o->kept_total);
+    }
+  }
+  return launch_status();
+}

@@ -1,0 +1,126 @@
+"""Host-side checks that need no GPU: the library loads, exports every function the header
+declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_11104_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "dam.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(dam_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = B.lib()
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+    assert L.dam_version() >= 1
+
+
+def mask_params(**kw):
+    d = dict(mode=B.DAM_FROM_ATTN_MAP, n_maps=2, pcl=64, seq=256, tile_m=64, tile_n=64, row_begin=0, row_end=0, lam=0.5,
+             eps=1e-8, tau=0.3, mu=0.8, bmin_override=float("nan"))
+    d.update(kw)
+    return B.MaskParams(*d.values())
+
+
+def call_mask(p, attn=4096, diag=None, vert=None, out=None, ws=4096, ws_bytes=1 << 30):
+    o = out or B.MaskOut()
+    if out is None:
+        o.true_bits = 4096
+    return B.lib().dam_mask_build(ctypes.byref(p), attn, None, diag, vert, ctypes.byref(o), ws, ws_bytes, None)
+
+
+def test_mask_build_argument_errors():
+    L = B.lib()
+    assert L.dam_mask_build(None, None, None, None, None, None, None, 0, None) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(), attn=None) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(n_maps=0)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(pcl=0)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(tile_n=96)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(tile_m=512)) == B.DAM_ERR_UNSUPPORTED
+    assert call_mask(mask_params(eps=0.0)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(lam=0.3)) == B.DAM_ERR_UNSUPPORTED      # bit-exactness is unpinned for powf
+    assert call_mask(mask_params(lam=0.0)) == B.DAM_ERR_UNSUPPORTED
+    assert call_mask(mask_params(), ws_bytes=16) == B.DAM_ERR_WORKSPACE
+    assert call_mask(mask_params(), ws=None) == B.DAM_ERR_WORKSPACE
+    assert call_mask(mask_params(mode=7)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(mode=B.DAM_FROM_PATTERNS, pcl=0), attn=None) == B.DAM_ERR_INVALID_ARG  # no flags
+    o = B.MaskOut()
+    o.true_bits, o.blk_col = 4096, 4096                                   # block output without row_ptr / total
+    assert call_mask(mask_params(), out=o) == B.DAM_ERR_INVALID_ARG
+    o = B.MaskOut()
+    o.true_bits, o.kept_ptr, o.kept_total = 4096, 4096, 4096
+    assert call_mask(mask_params(row_begin=5, row_end=3), out=o) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(row_begin=0, row_end=257), out=o) == B.DAM_ERR_INVALID_ARG
+    assert L.dam_mask_build_workspace(ctypes.byref(mask_params())) > 0
+    assert L.dam_mask_build_workspace(ctypes.byref(mask_params(seq=0))) == 0
+
+
+def attn_params(**kw):
+    p = B.AttnParams()
+    p.batch, p.hq, p.hkv, p.seq, p.head_dim, p.dtype, p.scale, p.tile_m, p.tile_n = 1, 4, 2, 256, 128, B.DAM_BF16, 0.0, 128, 128
+    for n in ("q_stride", "k_stride", "v_stride", "o_stride"):
+        setattr(p, n, (ctypes.c_int64 * 3)(4 * 256 * 128, 256 * 128, 128))
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def call_prefill(p, q=4096, mv=None, ws=4096, ws_bytes=1 << 40):
+    mv = mv or B.MaskView(4096, 4096, 4096, 4096)
+    return B.lib().dam_sparse_attn_prefill(ctypes.byref(p), q, 4096, 4096, ctypes.byref(mv), 4096, None, ws, ws_bytes, None)
+
+
+def test_prefill_argument_errors():
+    assert call_prefill(attn_params(), q=None) == B.DAM_ERR_INVALID_ARG
+    assert call_prefill(attn_params(hq=3)) == B.DAM_ERR_INVALID_ARG                  # hq % hkv != 0
+    assert call_prefill(attn_params(head_dim=96)) == B.DAM_ERR_UNSUPPORTED
+    assert call_prefill(attn_params(tile_m=64)) == B.DAM_ERR_UNSUPPORTED             # bf16 kernel: 128 x 128 only
+    assert call_prefill(attn_params(dtype=5)) == B.DAM_ERR_UNSUPPORTED
+    assert call_prefill(attn_params(scale=-1.0)) == B.DAM_ERR_INVALID_ARG
+    assert call_prefill(attn_params(), mv=B.MaskView(4096, None, 4096, 4096)) == B.DAM_ERR_INVALID_ARG
+    assert call_prefill(attn_params(q_stride=(ctypes.c_int64 * 3)(0, 0, 130))) == B.DAM_ERR_INVALID_ARG  # unaligned rows
+    assert call_prefill(attn_params(), ws_bytes=1024) == B.DAM_ERR_WORKSPACE
+    p = attn_params()
+    assert B.lib().dam_sparse_attn_prefill_workspace(ctypes.byref(p)) == 1 * 2 * 128 * 256 * 2
+    assert B.lib().dam_sparse_attn_prefill_workspace(ctypes.byref(attn_params(dtype=B.DAM_F32))) == 0
+
+
+def test_decode_argument_errors():
+    L = B.lib()
+    p = B.DecodeParams()
+    p.batch, p.hq, p.hkv, p.kv_capacity, p.head_dim, p.dtype, p.scale = 2, 4, 2, 1024, 128, B.DAM_BF16, 0.0
+    p.q_stride = (ctypes.c_int64 * 2)(512, 128)
+    p.kv_stride = (ctypes.c_int64 * 3)(2 * 1024 * 128, 1024 * 128, 128)
+    p.o_stride = (ctypes.c_int64 * 2)(512, 128)
+
+    def call(pp, q=4096, idx=4096, max_kept=100, ws=4096, ws_bytes=1 << 30):
+        return L.dam_sparse_attn_decode(ctypes.byref(pp), q, 4096, 4096, 4096, idx, max_kept, 4096, None, ws, ws_bytes, None)
+
+    assert call(p, q=None) == B.DAM_ERR_INVALID_ARG
+    assert call(p, idx=None) == B.DAM_ERR_INVALID_ARG
+    assert call(p, max_kept=-1) == B.DAM_ERR_INVALID_ARG
+    assert call(p, ws_bytes=8) == B.DAM_ERR_WORKSPACE
+    p.head_dim = 80
+    assert call(p) == B.DAM_ERR_UNSUPPORTED
+    p.head_dim, p.hq = 128, 5
+    assert call(p) == B.DAM_ERR_INVALID_ARG
+    p.hq = 4
+    assert L.dam_sparse_attn_decode_workspace(ctypes.byref(p), 4000) > 0
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libdam.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        B.lib()

@@ -1,0 +1,77 @@
+"""dam_sparse_attn_decode on the GPU against the oracle's list-form attention."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from dam_testlib import dev
+from paper_2506_11104_amd import binding as B
+from paper_2506_11104_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def run_case(rng, dtype, Bn, Hq, Hkv, d, T, lens):
+    """lens: kept-list length per (b, hq) item."""
+    q = wl.to_storage(rng.standard_normal((Bn, Hq, d)).astype(np.float32) * 1.5, dtype)
+    Kc = wl.to_storage(rng.standard_normal((Bn, Hkv, T, d)).astype(np.float32), dtype)
+    Vc = wl.to_storage(rng.standard_normal((Bn, Hkv, T, d)).astype(np.float32), dtype)
+    lists = [np.sort(rng.choice(T, int(n), replace=False)).astype(np.int32) for n in lens]
+    ptr = np.concatenate([[0], np.cumsum([len(x) for x in lists])]).astype(np.int64)
+    idx = np.concatenate(lists) if ptr[-1] else np.empty(0, np.int32)
+    G = Hq // Hkv
+    kv_of = np.array([b * Hkv + h // G for b in range(Bn) for h in range(Hq)], np.int32)
+    O, LSE = oracle.attend_lists(q.reshape(Bn * Hq, d), Kc.reshape(Bn * Hkv, T, d), Vc.reshape(Bn * Hkv, T, d), kv_of,
+                                 ptr, idx)
+    out, lse = B.dam_sparse_attn_decode(dev(q, dtype), dev(Kc, dtype), dev(Vc, dtype),
+                                        torch.from_numpy(ptr.astype(np.int32)).cuda(),
+                                        torch.from_numpy(idx).cuda() if len(idx) else torch.zeros(1, dtype=torch.int32, device="cuda"),
+                                        int(max(lens)) if len(lens) else 0, want_lse=True)
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy().reshape(Bn * Hq, d)
+    lse = lse.cpu().numpy().reshape(-1)
+    assert not np.isnan(out).any()
+    fin = np.isfinite(LSE)
+    assert np.array_equal(np.isneginf(lse), ~fin)
+    assert np.abs(out - O).max() <= TOL[dtype]
+    if fin.any():
+        assert np.abs(lse[fin] - LSE[fin]).max() <= TOL[dtype]
+    assert (out[~fin] == 0).all()
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+def test_small_and_ragged_lists(dtype, d):
+    rng = np.random.default_rng(41)
+    Bn, Hq, Hkv, T = 3, 4, 2, 700
+    lens = rng.integers(0, 300, Bn * Hq)
+    lens[0], lens[1], lens[2], lens[3] = 0, 1, 3, 700       # empty, single key, tiny, everything
+    run_case(rng, dtype, Bn, Hq, Hkv, d, T, lens)
+
+
+def test_long_lists_use_many_splits():
+    rng = np.random.default_rng(42)
+    lens = np.array([9000, 1, 4097, 0, 5000, 6000, 7000, 8191])
+    run_case(rng, "bf16", 1, 8, 2, 128, 9000, lens)
+
+
+def test_decode_lists_from_mask_build_match_prefill_row():
+    """Row p of the mask as a kept list (dam_mask_build, list form) fed to decode equals the oracle's
+    attention of row p."""
+    rng = np.random.default_rng(43)
+    Hq, Hkv, d, S = 4, 2, 128, 900
+    dflag = (rng.random((Hq, S)) < 0.02).astype(np.uint8)
+    vflag = (rng.random((Hq, S)) < 0.02).astype(np.uint8)
+    dflag[:, :30] = 1
+    art = oracle.from_patterns(dflag, vflag)
+    p = S - 1
+    mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=S, diag_in=torch.from_numpy(dflag).cuda(),
+                        vert_in=torch.from_numpy(vflag).cuda(), blocks=False, rows=(p, p + 1))
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), "bf16")
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    O, _ = oracle.attend_rows(Q[:, p], K, V, art, Hq, np.arange(Hq, dtype=np.int32), np.full(Hq, p, np.int64))
+    out = B.dam_sparse_attn_decode(dev(Q[:, p].copy(), "bf16")[None], dev(K, "bf16")[None], dev(V, "bf16")[None],
+                                   mask.kept_ptr, mask.kept_idx, S)
+    torch.cuda.synchronize()
+    assert np.abs(out[0].float().cpu().numpy() - O).max() <= TOL["bf16"]

@@ -1,0 +1,182 @@
+"""dam_mask_build on the GPU against the oracle, bit for bit (masks, counts, flags, block index,
+tile bits, dense bits, kept lists)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from dam_testlib import pack_rows_u64, u64
+from paper_2506_11104_amd import binding as B
+from paper_2506_11104_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def check_against_oracle(art, S, tm, tn, mask, rows=None, dense=True, heads=None):
+    """Compare every S-sized output of a Mask with the oracle's for the same artefact."""
+    H = art.H
+    heads = list(range(H)) if heads is None else heads
+    nQt = (S + tm - 1) // tm
+    row_ptr, col, kind, bits = oracle.block_index(art, S, tm, tn)
+    g_ptr = mask.blk_row_ptr.cpu().numpy().astype(np.int64)
+    assert np.array_equal(g_ptr, row_ptr), "blk_row_ptr"
+    n = int(row_ptr[-1, -1])
+    assert mask.n_tiles == n
+    if n:
+        assert np.array_equal(mask.blk_col.cpu().numpy(), col), "blk_col"
+        assert np.array_equal(mask.blk_kind.cpu().numpy(), kind), "blk_kind"
+        assert np.array_equal(u64(mask.tile_bits), bits), "tile_bits"
+    if dense:
+        gd = u64(mask.dense_bits)
+        for h in heads:
+            assert np.array_equal(gd[h], pack_rows_u64(oracle.rows(art, h, S, 0, S))), f"dense_bits head {h}"
+    if rows:
+        ptr = mask.kept_ptr.cpu().numpy()
+        idx = mask.kept_idx.cpu().numpy() if mask.kept_idx is not None else np.empty(0, np.int32)
+        nr = rows[1] - rows[0]
+        assert ptr[0] == 0 and ptr[-1] == mask.n_kept
+        for h in heads:
+            for r in range(nr):
+                want = oracle.kept_list(art, h, rows[0] + r)
+                got = idx[ptr[h * nr + r]:ptr[h * nr + r + 1]]
+                assert np.array_equal(got, want), f"kept list head {h} row {rows[0] + r}"
+
+
+def run_from_map(A, C, S, tm, tn, lam, eps, tau, mu, rows=None, dense=True, bmin_override=None):
+    H, L, _ = A.shape
+    art = oracle.derive(A, C, lam, eps, tau, mu, bmin_override)
+    mask = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, tile_m=tm, tile_n=tn, lam=lam, eps=eps, tau=tau, mu=mu,
+                        bmin_override=float("nan") if bmin_override is None else bmin_override,
+                        attn_sum=torch.from_numpy(A).cuda(), attn_cnt=None if C is None else torch.from_numpy(C).cuda(),
+                        dense=dense, rows=rows)
+    torch.cuda.synchronize()
+    assert np.float32(mask.bmin.item()) == np.float32(art.bmin), "bmin"
+    assert np.array_equal(u64(mask.true_bits), pack_rows_u64(art.true_mask)), "true_bits"
+    assert np.array_equal(mask.diag_cnt.cpu().numpy(), art.diag_cnt), "diag_cnt"
+    assert np.array_equal(mask.vert_cnt.cpu().numpy(), art.vert_cnt), "vert_cnt"
+    assert np.array_equal(mask.diag_flag.cpu().numpy(), art.diag_flag), "diag_flag"
+    assert np.array_equal(mask.vert_flag.cpu().numpy(), art.vert_flag), "vert_flag"
+    check_against_oracle(art, S, tm, tn, mask, rows=rows, dense=dense)
+    return art, mask
+
+
+@pytest.mark.parametrize("tau,mu", [(0.257, 0.8), (0.3, 0.8), (0.0, 0.8), (0.257, 1.5), (0.257, 0.0), (-1.0, 1.0)])
+@pytest.mark.parametrize("tile", [64, 128])
+def test_c1_mask_bit_exact(tau, mu, tile):
+    w = wl.WORKLOADS["c1"]
+    Q, K, V = wl.qkv_iid(w, std=1 / 8)
+    A = wl.capture_map(Q, K, w.pcl, 1)
+    art, mask = run_from_map(A, None, w.seq, tile, tile, w.lam, w.eps, tau, mu, rows=(0, w.seq))
+    if tau == 0.3:      # the paper's defaults on near-uniform attention: no pattern matches
+        assert art.diag_flag.sum() == 0 and art.vert_flag.sum() == 0
+
+
+def synth_map(rng, H, L):
+    s = rng.standard_normal((H, L, L)) * 2.0
+    s[:, :, 0] += 3.0
+    band = np.subtract.outer(np.arange(L), np.arange(L))
+    s += 4.0 * np.exp(-np.abs(band) / 12.0)
+    s[:, ~np.tril(np.ones((L, L), bool))] = -np.inf
+    e = np.exp(s - s.max(-1, keepdims=True))
+    return (e / e.sum(-1, keepdims=True)).astype(np.float32)
+
+
+@pytest.mark.parametrize("lam", [0.5, 1.0])
+def test_ragged_sizes_counts_given_and_general_min(lam):
+    rng = np.random.default_rng(21)
+    H, L, S = 3, 200, 1000                     # L and S are no multiples of 64 / of the tiles
+    A1 = synth_map(rng, H, L)
+    # several captures of different lengths: C varies per pair, A is the sum
+    C = np.zeros((H, L, L), np.float32)
+    A = np.zeros((H, L, L), np.float32)
+    for n in (L, 150, 77):
+        C[:, :n, :n] += np.tril(np.ones((n, n), np.float32))
+        A[:, :n, :n] += A1[:, :n, :n]
+    C[0, 10, 50] = 2.0                          # a counted pair above the diagonal: still masked
+    A[0, 10, 50] = 1.5
+    tau = 0.12 if lam == 0.5 else 0.004
+    run_from_map(A, C, S, 128, 64, lam, 1e-8, tau, 0.7, rows=(990, 1000))
+    run_from_map(A, C, S, 64, 128, lam, 1e-6, tau, 0.7, rows=(0, 3), bmin_override=-1.9)
+    # Case 1 (S <= L) and S == L
+    run_from_map(A1, None, 150, 64, 64, lam, 1e-8, tau, 0.7, rows=(0, 150))
+    run_from_map(A1, None, L, 128, 128, lam, 1e-8, tau, 0.7)
+    # L == 1: the minimum comes from the single valid entry
+    run_from_map(A1[:, :1, :1].copy(), None, 70, 64, 64, lam, 1e-8, tau, 0.7, rows=(0, 70))
+
+
+def test_threshold_boundary_values_round_like_the_oracle():
+    # values packed around theta = (tau/2 + sqrt(eps))^2 in steps of one ulp, and around eps
+    L = 256
+    theta = np.float32((0.3 / 2 + np.sqrt(1e-8)) ** 2)
+    vals = [theta]
+    for _ in range(127):
+        vals.append(np.nextafter(vals[-1], np.float32(1)))
+    lo = [theta]
+    for _ in range(127):
+        lo.append(np.nextafter(lo[-1], np.float32(0)))
+    row = np.array(lo[::-1] + vals, np.float32)
+    A = np.zeros((2, L, L), np.float32)
+    A[0] = np.tril(np.tile(row, (L, 1)))
+    rng = np.random.default_rng(5)
+    A[1] = np.tril(rng.random((L, L)).astype(np.float32) ** 8)
+    A[1, :, :64] = np.tril(np.float32(1e-8) * (1 + rng.random((L, 64)).astype(np.float32)))[:, :64]
+    run_from_map(A, None, 300, 64, 64, 0.5, 1e-8, 0.3, 0.8)
+    run_from_map(A, None, 300, 64, 64, 1.0, 1e-8, float(theta) - 1e-8, 0.8)
+
+
+def test_from_patterns_with_and_without_true_mask():
+    rng = np.random.default_rng(22)
+    H, S, L = 4, 1000, 100
+    d = (rng.random((H, S)) < 0.02).astype(np.uint8)
+    v = (rng.random((H, S)) < 0.01).astype(np.uint8)
+    d[:, :40] = 1
+    v[:, :4] = 1
+    d[3] = 0
+    v[3] = 0                                                   # an empty head
+    tm_ = (rng.random((H, L, L)) < 0.3).astype(np.uint8) * np.tril(np.ones((L, L), np.uint8))
+    for with_true in (False, True):
+        art = oracle.from_patterns(d, v, tm_ if with_true else None)
+        tb = torch.from_numpy(pack_rows_u64(tm_).view(np.int64)).cuda() if with_true else None
+        mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=H, L=L if with_true else 0, S=S, tile_m=128, tile_n=128,
+                            diag_in=torch.from_numpy(d).cuda(), vert_in=torch.from_numpy(v).cuda(), true_bits=tb,
+                            dense=True, rows=(S - 5, S))
+        torch.cuda.synchronize()
+        check_against_oracle(art, S, 128, 128, mask, rows=(S - 5, S))
+
+
+def test_capacity_overflow_reports_total_and_writes_nothing_past_it():
+    rng = np.random.default_rng(23)
+    H, S = 2, 640
+    d = np.zeros((H, S), np.uint8)
+    v = np.zeros((H, S), np.uint8)
+    d[:, :70] = 1
+    art = oracle.from_patterns(d, v)
+    row_ptr, col, kind, bits = oracle.block_index(art, S, 128, 128)
+    n = len(col)
+    cap = n // 2
+    p = B.MaskParams(B.DAM_FROM_PATTERNS, H, 0, S, 128, 128, 0, 0, 0.5, 1e-8, 0.3, 0.8, float("nan"))
+    ws = B.mask_workspace(p, "cuda")
+    o = B.MaskOut()
+    rp = torch.empty((H, 6), dtype=torch.int32, device="cuda")
+    bc = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    bk = torch.full((n,), 9, dtype=torch.uint8, device="cuda")
+    tb = torch.full((n, 128, 2), -1, dtype=torch.int64, device="cuda")
+    tot = torch.zeros(1, dtype=torch.int64, device="cuda")
+    o.blk_row_ptr, o.blk_col, o.blk_kind, o.tile_bits = rp.data_ptr(), bc.data_ptr(), bk.data_ptr(), tb.data_ptr()
+    o.blk_capacity, o.blk_total = cap, tot.data_ptr()
+    B.dam_mask_build(p, None, None, torch.from_numpy(d).cuda(), torch.from_numpy(v).cuda(), o, ws)
+    torch.cuda.synchronize()
+    assert int(tot.item()) == n
+    assert np.array_equal(bc.cpu().numpy()[:cap], col[:cap]) and (bc.cpu().numpy()[cap:] == -7).all()
+    assert (bk.cpu().numpy()[cap:] == 9).all() and (tb.cpu().numpy()[cap:] == -1).all()
+    assert np.array_equal(u64(tb)[:cap], bits[:cap])
+
+
+def test_c2_mask_full_size_bit_exact():
+    w = wl.WORKLOADS["c2"]
+    Q, K, V = wl.qkv_structured(w)
+    A = wl.capture_map(Q, K, w.pcl, w.hq // w.hkv)
+    art, mask = run_from_map(A, None, w.seq, w.tile_m, w.tile_n, w.lam, w.eps, w.tau, w.mu, rows=(w.seq - 1, w.seq),
+                             dense=False)
+    dens = sum(int(np.unpackbits(u64(mask.tile_bits).view(np.uint8)).sum()) for _ in [0]) / (w.hq * w.seq * (w.seq + 1) / 2)
+    assert 0.05 < dens < 0.2, dens

@@ -1,0 +1,157 @@
+"""dam_sparse_attn_prefill on the GPU against the oracle (fp64 masked softmax attention).
+Tolerances: max-abs 1e-4 for the fp32 kernel, 2e-2 for bf16 inputs/outputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from dam_testlib import dev
+from paper_2506_11104_amd import binding as B
+from paper_2506_11104_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def gpu_mask_from_art(art, S, tm, tn):
+    """Mask buffers for the kernels from an oracle-side artefact's *inputs* (flags / true mask are
+    inputs of the FROM_PATTERNS mode; the S-sized outputs are built by the GPU)."""
+    from dam_testlib import pack_rows_u64
+    tb = None
+    if art.true_mask is not None:
+        tb = torch.from_numpy(pack_rows_u64(art.true_mask).view(np.int64)).cuda()
+    d = np.zeros((art.H, S), np.uint8)
+    v = np.zeros((art.H, S), np.uint8)
+    n = min(S, art.P)
+    d[:, :n], v[:, :n] = art.diag_flag[:, :n], art.vert_flag[:, :n]
+    return B.build_mask(mode=B.DAM_FROM_PATTERNS, H=art.H, L=art.L, S=S, tile_m=tm, tile_n=tn,
+                        diag_in=torch.from_numpy(d).cuda(), vert_in=torch.from_numpy(v).cuda(), true_bits=tb)
+
+
+def compare(Q, K, V, art, mask, dtype, batch=1, heads_rows=None):
+    Hq, S, d = Q.shape
+    q, k, v = dev(Q, dtype)[None], dev(K, dtype)[None], dev(V, dtype)[None]
+    if batch > 1:   # the mask is shared over the batch: entry b gets the inputs rolled by b heads
+        q = torch.cat([q.roll(b, 1) for b in range(batch)], 0).contiguous()
+        k = k.expand(batch, -1, -1, -1).contiguous()
+        v = v.expand(batch, -1, -1, -1).contiguous()
+    out, lse = B.dam_sparse_attn_prefill(q, k, v, mask, want_lse=True)
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    lse = lse.cpu().numpy()
+    assert not np.isnan(out).any()
+    if heads_rows is None:
+        O, LSE = oracle.attend_prefill(Q, K, V, art)
+        err = np.abs(out[0] - O).max()
+        fin = np.isfinite(LSE)
+        assert np.array_equal(np.isneginf(lse[0]), ~fin)
+        lerr = np.abs(lse[0][fin] - LSE[fin]).max() if fin.any() else 0.0
+        assert (out[0][~fin] == 0).all()
+    else:
+        hs, rs = heads_rows
+        O, LSE = oracle.attend_rows(Q[hs, rs], K, V, art, Hq, hs, rs)
+        err = np.abs(out[0][hs, rs] - O).max()
+        fin = np.isfinite(LSE)
+        lerr = np.abs(lse[0][hs, rs][fin] - LSE[fin]).max() if fin.any() else 0.0
+    assert err <= TOL[dtype], f"max abs err {err}"
+    assert lerr <= TOL[dtype], f"lse err {lerr}"
+    return err
+
+
+@pytest.mark.parametrize("tau,mu", [(0.257, 0.8), (0.3, 0.8), (0.0, 0.8), (0.257, 1.5)])
+@pytest.mark.parametrize("tile", [64, 128])
+def test_c1_fp32(tau, mu, tile):
+    w = wl.WORKLOADS["c1"]
+    Q, K, V = wl.qkv_iid(w, std=1 / 8)
+    A = wl.capture_map(Q, K, w.pcl, 1)
+    art = oracle.derive(A, None, w.lam, w.eps, tau, mu)
+    mask = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=w.hq, L=w.pcl, S=w.seq, tile_m=tile, tile_n=tile, lam=w.lam,
+                        eps=w.eps, tau=tau, mu=mu, attn_sum=torch.from_numpy(A).cuda())
+    compare(Q, K, V, art, mask, "f32")
+
+
+def random_patterns(rng, H, S, L=0):
+    d = (rng.random((H, S)) < 0.01).astype(np.uint8)
+    v = (rng.random((H, S)) < 0.01).astype(np.uint8)
+    for h in range(H):
+        d[h, :int(rng.integers(1, 200))] = 1
+        v[h, :int(rng.integers(1, 9))] = 1
+    if H > 2:
+        d[2], v[2] = 0, 0
+        d[2, 300] = 1                      # rows < 300 of head 2 are empty
+    tm = None
+    if L:
+        tm = (rng.random((H, L, L)) < 0.3).astype(np.uint8) * np.tril(np.ones((L, L), np.uint8))
+    return oracle.from_patterns(d, v, tm)
+
+
+@pytest.mark.parametrize("dtype,d,S,tile", [("bf16", 128, 1000, 128), ("bf16", 128, 384, 128), ("f32", 128, 700, 128),
+                                            ("f32", 64, 333, 64)])
+def test_mid_size_ragged_gqa_batch(dtype, d, S, tile):
+    rng = np.random.default_rng(31)
+    Hq, Hkv = 4, 2
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32) * 1.5, dtype)
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), dtype)
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), dtype)
+    art = random_patterns(rng, Hq, S, L=90)
+    mask = gpu_mask_from_art(art, S, tile, tile)
+    compare(Q, K, V, art, mask, dtype)
+    # batch of 3 sharing the mask: check entry 2 (inputs rolled by two heads) against the oracle
+    q = torch.cat([dev(Q, dtype)[None].roll(b, 1) for b in range(3)], 0).contiguous()
+    k = dev(K, dtype)[None].expand(3, -1, -1, -1).contiguous()
+    v = dev(V, dtype)[None].expand(3, -1, -1, -1).contiguous()
+    out = B.dam_sparse_attn_prefill(q, k, v, mask)
+    torch.cuda.synchronize()
+    O2, _ = oracle.attend_prefill(np.roll(Q, 2, 0), K, V, art)
+    assert np.abs(out[2].float().cpu().numpy() - O2).max() <= TOL[dtype]
+
+
+def test_dense_causal_bf16_matches_oracle_and_is_all_full_tiles():
+    rng = np.random.default_rng(32)
+    Hq, Hkv, S, d = 2, 1, 512, 128
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), "bf16")
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    art = oracle.from_patterns(np.ones((Hq, S), np.uint8), np.zeros((Hq, S), np.uint8))
+    mask = gpu_mask_from_art(art, S, 128, 128)
+    assert int(mask.blk_kind.sum().item()) == Hq * 6          # 4*3/2 strictly-below-diagonal tiles per head
+    compare(Q, K, V, art, mask, "bf16")
+
+
+def test_large_logits_do_not_overflow():
+    # a masked-out key with a huge logit must not disturb the kept ones (mask before the max)
+    rng = np.random.default_rng(33)
+    Hq, S, d = 1, 256, 128
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), "bf16")
+    K = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), "bf16")
+    K[0, 5] = Q[0].mean(0) * 400.0
+    K[0, 5] = wl.to_storage(K[0, 5], "bf16")
+    dflag = np.zeros((1, S), np.uint8)
+    dflag[0, :3] = 1                       # window of 3: key 5 is masked for rows >= 8
+    art = oracle.from_patterns(dflag, np.zeros((1, S), np.uint8))
+    mask = gpu_mask_from_art(art, S, 128, 128)
+    compare(Q, K, V, art, mask, "bf16")
+
+
+def test_c2_full_size():
+    w = wl.WORKLOADS["c2"]
+    Q, K, V = wl.qkv_structured(w)
+    A = wl.capture_map(Q, K, w.pcl, w.hq // w.hkv)
+    art = oracle.derive(A, None, w.lam, w.eps, w.tau, w.mu)
+    mask = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=w.hq, L=w.pcl, S=w.seq, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu,
+                        attn_sum=torch.from_numpy(A).cuda())
+    compare(Q, K, V, art, mask, "bf16")
+
+
+def test_c3_full_size_sampled_rows():
+    w = wl.WORKLOADS["c3"]
+    Q, K, V = wl.qkv_iid(w)
+    dflag, vflag = wl.patterns_c3(w)
+    art = oracle.from_patterns(dflag, vflag)
+    mask = gpu_mask_from_art(art, w.seq, 128, 128)
+    rng = np.random.default_rng(34)
+    n = 1536
+    hs = rng.integers(0, w.hq, n).astype(np.int32)
+    rs = np.concatenate([rng.integers(0, w.seq, n - 256), np.arange(w.seq - 128, w.seq), np.arange(128)]).astype(np.int64)
+    compare(Q, K, V, art, mask, "bf16", heads_rows=(hs, rs))
