@@ -30,21 +30,23 @@ struct Geom {
 };
 
 // ------------------------------------------------------------------------------------------------
-// Sec. 4.2.2 in the fixed fp32 sequence (each op rounded to nearest, nothing contracted).
+// Sec. 4.2.2 in the fixed fp32 sequence (each op rounded to nearest, nothing contracted: this file
+// is compiled with contraction off and with correctly rounded fp32 divide and square root; the
+// __fsqrt_rn / __fdiv_rn intrinsics are NOT used because they map to the approximate forms).
 __device__ __forceinline__ float clamp_mean(float a, float c, float eps) {
-  const float denom = __fadd_rn(c, eps);
-  const float abar = __fdiv_rn(a, denom);
+  const float denom = c + eps;
+  const float abar = a / denom;
   return fmaxf(abar, eps);
 }
 
 template <int LAMBDA2>  // 2 * lambda: 1 -> lambda 0.5, 2 -> lambda 1
 __device__ __forceinline__ float box_cox(float x) {
   if (LAMBDA2 == 1) {
-    const float root = __fsqrt_rn(x);
-    const float num = __fsub_rn(root, 1.0f);
-    return __fdiv_rn(num, 0.5f);
+    const float root = sqrtf(x);
+    const float num = root - 1.0f;
+    return num / 0.5f;
   }
-  return __fsub_rn(x, 1.0f);
+  return x - 1.0f;
 }
 
 // Single causal capture with L >= 2: some pair was never computed, its X is the clamp eps, and no
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A,
       const int i = r0 + r, j = (w0 + k) * 64 + lane;
       const bool live = i < L && j <= i;
       const float b = box_cox<LAMBDA2>(clamp_mean(a[r][k], c[r][k], eps));
-      const float bstar = __fsub_rn(b, bmin);
+      const float bstar = b - bmin;
       const uint64_t word = __ballot(live && bstar >= tau);
       if (lane == 0 && i < L && w0 + k < tbw) true_bits[((int64_t)h * L + i) * tbw + w0 + k] = word;
     }
@@ -168,8 +170,8 @@ __global__ void k_pattern_flags(const int *__restrict__ diag_cnt, const int *__r
   if (e >= (int64_t)H * L) return;
   const int p = (int)(e % L);
   const float size = (float)(L - p);
-  diag_flag[e] = (uint8_t)(__fdiv_rn((float)diag_cnt[e], size) >= mu);
-  vert_flag[e] = (uint8_t)(__fdiv_rn((float)vert_cnt[e], size) >= mu);
+  diag_flag[e] = (uint8_t)((float)diag_cnt[e] / size >= mu);
+  vert_flag[e] = (uint8_t)((float)vert_cnt[e] / size >= mu);
 }
 
 // Flags -> bitsets. cbits bit c = column c matched. rrev bit q = diagonal (pw*64 - 1 - q) matched,
