@@ -1,0 +1,313 @@
+#!/usr/bin/env python3
+"""Benchmark of the DAM hot path on one MI355X.
+
+A step is one pass of the hot path over one synthetic batch of the 32k prefill workload (c3):
+dam_mask_build (matched patterns -> tile pool + block index at S = 32768) followed by
+dam_sparse_attn_prefill over the listed tiles. `value` is effective TFLOP/s on kept entries,
+4 * head_dim * nnz / step time, with every input resident in HBM before the timed region.
+The same run also reports (extra keys of the one JSON line) the prefill kernel against the bf16
+MFMA roofline, the decode workload (c5) and the attention-map mask build (c2 shape) against the
+HBM roofline, and the CPU oracle timed on a bounded sample of the same prefill workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2] [--no-decode] [--no-cpu]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c3", "c2"])
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-maskmap", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def bench_prefill(args, w, torch, B, wl):
+    """Returns the result dict of the prefill workload (mask build + sparse prefill per step)."""
+    dev = "cuda"
+    H, S, d = w.hq, w.seq, w.head_dim
+    Q, K, V = wl.qkv_iid(w) if w.kind == "prefill_patterns" else wl.qkv_structured(w)
+    if w.kind == "prefill_patterns":
+        dflag, vflag = wl.patterns_c3(w)
+        mode, L = B.DAM_FROM_PATTERNS, 0
+        A = None
+    else:
+        A = torch.from_numpy(wl.capture_map(Q, K, w.pcl, w.hq // w.hkv)).to(dev)
+        mode, L = B.DAM_FROM_ATTN_MAP, w.pcl
+        dflag = vflag = None
+    to_dev = lambda x: torch.from_numpy(x).to(torch.bfloat16)[None].to(dev)
+    q, k, v = to_dev(Q), to_dev(K), to_dev(V)
+    d_in = torch.from_numpy(dflag).to(dev) if dflag is not None else None
+    v_in = torch.from_numpy(vflag).to(dev) if vflag is not None else None
+
+    # sizing call (outside the timed region): how many tiles does the pool need
+    sized = B.build_mask(mode=mode, H=H, L=L, S=S, tile_m=w.tile_m, tile_n=w.tile_n, lam=w.lam, eps=w.eps, tau=w.tau,
+                         mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in)
+    torch.cuda.synchronize()
+    n_tiles = sized.n_tiles
+    kinds = sized.blk_kind.cpu().numpy()
+    n_full = int(kinds.sum())
+    # kept entries: popcount of the tile pool (chunked on the device as bytes through a lookup table)
+    lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=dev)
+    nnz = 0
+    tb = sized.tile_bits.view(torch.uint8).reshape(-1)
+    for off in range(0, tb.numel(), 1 << 28):
+        nnz += int(lut[tb[off:off + (1 << 28)].long()].sum().item())
+    causal = H * S * (S + 1) // 2
+
+    # preallocated outputs for the timed steps
+    p = B.MaskParams(mode, H, L, S, w.tile_m, w.tile_n, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
+    ws_mask = B.mask_workspace(p, dev)
+    o = B.MaskOut()
+    for name in ("true_bits", "diag_cnt", "vert_cnt", "diag_flag", "vert_flag", "bmin"):
+        t = getattr(sized, name)
+        if mode == B.DAM_FROM_ATTN_MAP and t is not None:
+            setattr(o, name, t.data_ptr())
+    total = torch.zeros(1, dtype=torch.int64, device=dev)
+    o.blk_row_ptr, o.blk_col, o.blk_kind = sized.blk_row_ptr.data_ptr(), sized.blk_col.data_ptr(), sized.blk_kind.data_ptr()
+    o.tile_bits, o.blk_capacity, o.blk_total = sized.tile_bits.data_ptr(), n_tiles, total.data_ptr()
+    out = torch.empty_like(q)
+    ap_ = B.attn_params(q, k, v, out, w.tile_m, w.tile_n)
+    ws_attn = B.prefill_workspace(ap_, dev)
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        B.dam_mask_build(p, A, None, d_in, v_in, o, ws_mask)
+        if ev:
+            ev[1].record()
+        B.dam_sparse_attn_prefill(q, k, v, sized, out=out, ws=ws_attn)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [events(3) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    mask_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    attn_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    step_ms = wall * 1e3 / args.steps
+    assert int(total.item()) == n_tiles
+
+    flops_kept = 4.0 * d * nnz
+    flops_tiles = 4.0 * d * w.tile_m * w.tile_n * n_tiles
+    mask_bytes = n_tiles * (w.tile_m * w.tile_n // 8 + 5) + 4 * H * (sized.blk_row_ptr.shape[1]) + 2 * H * S
+    if A is not None:
+        mask_bytes += 2 * H * L * (L + 1) + H * L * L // 8
+    res = {
+        "step_ms": step_ms, "mask_build_ms": mask_ms, "prefill_ms": attn_ms, "nnz": nnz, "n_tiles": n_tiles,
+        "n_full_tiles": n_full, "density": nnz / causal, "tile_fill": nnz / (n_tiles * w.tile_m * w.tile_n),
+        "tflops_kept_step": flops_kept / (step_ms * 1e-3) / 1e12,
+        "tflops_kept_prefill": flops_kept / (attn_ms * 1e-3) / 1e12,
+        "tflops_tiles_prefill": flops_tiles / (attn_ms * 1e-3) / 1e12,
+        "mask_build_gbs": mask_bytes / (mask_ms * 1e-3) / 1e9, "mask_build_bytes": mask_bytes,
+    }
+    ctx = dict(Q=Q, K=K, V=V, dflag=dflag, vflag=vflag, A=A, sized=sized)
+    return res, ctx
+
+
+def bench_cpu_oracle(args, w, ctx, wl):
+    """The oracle (fp64, OpenMP over rows) timed on a bounded random sample of rows of the same
+    workload; reported in the metric's unit (TFLOP/s on kept entries)."""
+    import oracle
+    if ctx["dflag"] is not None:
+        art = oracle.from_patterns(ctx["dflag"], ctx["vflag"])
+    else:
+        art = oracle.derive(ctx["A"].cpu().numpy(), None, w.lam, w.eps, w.tau, w.mu)
+    rng = np.random.default_rng(1234)
+
+    def run(n):
+        hs = rng.integers(0, w.hq, n).astype(np.int32)
+        rs = rng.integers(0, w.seq, n).astype(np.int64)
+        t0 = time.perf_counter()
+        _, _ = oracle.attend_rows(ctx["Q"][hs, rs], ctx["K"], ctx["V"], art, w.hq, hs, rs)
+        dt = time.perf_counter() - t0
+        kept = sum(len(oracle.kept_list(art, int(h), int(r))) for h, r in zip(hs[:256], rs[:256])) / min(n, 256) * n
+        return dt, kept
+
+    dt, kept = run(512)
+    n = int(min(200000, max(512, 512 * args.cpu_seconds / max(dt, 1e-3))))
+    dt, kept = run(n)
+    return {"value": 4.0 * w.head_dim * kept / dt / 1e12, "unit": "TFLOP/s (kept entries)", "cores": oracle.threads(),
+            "kind": "oracle", "sample": f"{n} random (head,row) pairs of {w.name}, {dt:.1f} s, fp64, kept entries "
+                                        f"estimated from 256 of them"}
+
+
+def bench_decode(args, torch, B, wl):
+    w = wl.WORKLOADS["c5"]
+    dev = "cuda"
+    steps = args.decode_steps
+    cap = w.seq + steps
+    g = torch.Generator(device=dev).manual_seed(w.seed)
+    kc = torch.randn((w.batch, w.hkv, cap, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vc = torch.randn((w.batch, w.hkv, cap, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    qs = torch.randn((steps, w.batch, w.hq, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    dflag, vflag = wl.patterns_c5(wl.scaled(w, steps=steps))
+    # one "map" per (sequence, head): every sequence sits at the same position here, but the ABI does
+    # not assume it
+    d_in = torch.from_numpy(np.tile(dflag, (w.batch, 1))).to(dev)
+    v_in = torch.from_numpy(np.tile(vflag, (w.batch, 1))).to(dev)
+    items = w.batch * w.hq
+    max_kept = int((dflag.sum(1) + vflag.sum(1)).max())
+    kept_ptr = torch.empty(items + 1, dtype=torch.int32, device=dev)
+    kept_idx = torch.empty(items * max_kept, dtype=torch.int32, device=dev)
+    total = torch.zeros(1, dtype=torch.int64, device=dev)
+    out = torch.empty((w.batch, w.hq, w.head_dim), dtype=torch.bfloat16, device=dev)
+    dp = B.decode_params(qs[0], kc, out)
+    ws_dec = B.decode_workspace(dp, max_kept, dev)
+    o = B.MaskOut()
+    o.kept_ptr, o.kept_idx, o.kept_capacity, o.kept_total = kept_ptr.data_ptr(), kept_idx.data_ptr(), kept_idx.numel(), total.data_ptr()
+
+    def step(s, ev=None):
+        pos = w.seq - 1 + s
+        # rows of the mask do not depend on the problem length it is built for (the extension only
+        # continues patterns), so the lists are taken from the length-`cap` mask the flags are sized for
+        p = B.MaskParams(B.DAM_FROM_PATTERNS, items, 0, cap, 128, 128, pos, pos + 1, 0.5, 1e-8, 0.3, 0.8, float("nan"))
+        if ev:
+            ev[0].record()
+        B.dam_mask_build(p, None, None, d_in, v_in, o, ws_mask)
+        if ev:
+            ev[1].record()
+        B.dam_sparse_attn_decode(qs[s], kc, vc, kept_ptr, kept_idx, max_kept, out=out, ws=ws_dec)
+        if ev:
+            ev[2].record()
+
+    pmax = B.MaskParams(B.DAM_FROM_PATTERNS, items, 0, cap, 128, 128, cap - 1, cap, 0.5, 1e-8, 0.3, 0.8, float("nan"))
+    ws_mask = B.mask_workspace(pmax, dev)
+    for s in range(3):
+        step(s)
+    torch.cuda.synchronize()
+
+    def union_bytes():
+        ptr = kept_ptr.cpu().numpy()
+        idx = kept_idx[:int(total.item())].cpu().numpy()
+        G = w.hq // w.hkv
+        rows = 0
+        for b in range(w.batch):
+            for gk in range(w.hkv):
+                parts = [idx[ptr[b * w.hq + gk * G + x]:ptr[b * w.hq + gk * G + x + 1]] for x in range(G)]
+                rows += len(np.unique(np.concatenate(parts)))
+        return rows * w.head_dim * 2 * 2, int(total.item()) * w.head_dim * 2 * 2
+
+    evs = [events(3) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for s in range(steps):
+        step(s, evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ub_last, sum_last = union_bytes()
+    step(0)
+    torch.cuda.synchronize()
+    ub_first, sum_first = union_bytes()
+    ub, sb = 0.5 * (ub_first + ub_last), 0.5 * (sum_first + sum_last)
+    list_us = float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e3
+    dec_us = float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e3
+    return {"workload": "c5", "steps": steps, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
+            "decode_us": dec_us, "kept_per_list": sb / (items * w.head_dim * 4), "union_bytes": ub, "sum_bytes": sb,
+            "gbs_union": ub / (dec_us * 1e-6) / 1e9, "gbs_sum": sb / (dec_us * 1e-6) / 1e9,
+            "roofline": {"bound": "hbm", "achieved": ub / (dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+
+
+def bench_mask_from_map(args, torch, B, wl):
+    """a1-a3 (+ extension) from a captured attention map: the c2 shape, 32 maps of 1024 x 1024."""
+    w = wl.WORKLOADS["c2"]
+    Q, K, V = wl.qkv_structured(w)
+    A = torch.from_numpy(wl.capture_map(Q, K, w.pcl, w.hq // w.hkv)).cuda()
+    H, L = w.hq, w.pcl
+    p = B.MaskParams(B.DAM_FROM_ATTN_MAP, H, L, L, 128, 128, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
+    ws = B.mask_workspace(p, "cuda")
+    o = B.MaskOut()
+    tb = torch.empty((H, L, L // 64), dtype=torch.int64, device="cuda")
+    fl = [torch.empty((H, L), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    o.true_bits, o.diag_flag, o.vert_flag = tb.data_ptr(), fl[0].data_ptr(), fl[1].data_ptr()
+    for _ in range(3):
+        B.dam_mask_build(p, A, None, None, None, o, ws)
+    torch.cuda.synchronize()
+    n = 20
+    ev = events(2)
+    ev[0].record()
+    for _ in range(n):
+        B.dam_mask_build(p, A, None, None, None, o, ws)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / n
+    nbytes = 2 * H * L * (L + 1) + H * L * L // 8      # lower triangle of A once + true bits
+    return {"workload": "c2 map (32 x 1024 x 1024 fp32) -> true mask + matched patterns", "ms": ms, "bytes": nbytes,
+            "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2506_11104_amd import binding as B
+    from paper_2506_11104_amd import workloads as wl
+    B.lib()                                   # fails loudly when libdam.so is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    res, ctx = bench_prefill(args, w, torch, B, wl)
+    line = {
+        "metric": "effective TFLOP/s on kept entries (mask build + sparse prefill per step, 32k prefill)",
+        "value": res["tflops_kept_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["step_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: 1 layer, {w.hq} Q / {w.hkv} KV heads, head_dim {w.head_dim}, seq {w.seq}, "
+                               f"bf16, batch 1, heterogeneous per-head masks, tiles {w.tile_m}x{w.tile_n}",
+                   "density": res["density"], "nnz": res["nnz"], "listed_tiles": res["n_tiles"],
+                   "full_tiles": res["n_full_tiles"], "tile_fill": res["tile_fill"]},
+        "ms_per_layer_prefill": res["prefill_ms"], "mask_build_ms": res["mask_build_ms"],
+        "mask_build_gbs": res["mask_build_gbs"],
+        "tflops_kept_entries_prefill_only": res["tflops_kept_prefill"],
+        "tflops_listed_tiles_prefill_only": res["tflops_tiles_prefill"],
+        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16", "achieved": res["tflops_kept_prefill"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": res["tflops_kept_prefill"] / PEAK_BF16_TFLOPS,
+                     "traffic": None, "achieved_listed_tiles": res["tflops_tiles_prefill"],
+                     "frac_listed_tiles": res["tflops_tiles_prefill"] / PEAK_BF16_TFLOPS},
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = bench_cpu_oracle(args, w, ctx, wl)
+    del ctx
+    torch.cuda.empty_cache()
+    if not args.no_maskmap:
+        line["mask_build_from_map"] = bench_mask_from_map(args, torch, B, wl)
+    if not args.no_decode:
+        line["decode"] = bench_decode(args, torch, B, wl)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

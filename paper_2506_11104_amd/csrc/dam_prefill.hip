@@ -167,7 +167,7 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned, r);
 }
 
-__global__ __launch_bounds__(256) void k_prefill_bf16(AttnArgs a, const __hip_bfloat16 *__restrict__ q,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16(AttnArgs a, const __hip_bfloat16 *__restrict__ q,
                                                       const __hip_bfloat16 *__restrict__ k,
                                                       const __hip_bfloat16 *__restrict__ vt,
                                                       const int *__restrict__ row_ptr,
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256) void k_prefill_bf16(AttnArgs a, const __hip_bf
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m_run, mx);
     const float m_ref = m_new == -INFINITY ? 0.0f : m_new;
-    const float corr = exp2f((m_run - m_ref) * c2);
+    const float corr = __builtin_amdgcn_exp2f((m_run - m_ref) * c2);
     const float off = m_ref * c2;
     m_run = m_new;
     float psum = 0.0f;
@@ -274,8 +274,8 @@ __global__ __launch_bounds__(256) void k_prefill_bf16(AttnArgs a, const __hip_bf
     for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        const float p0 = exp2f(sacc[kb][e] * c2 - off);
-        const float p1 = exp2f(sacc[kb][e + 1] * c2 - off);
+        const float p0 = __builtin_amdgcn_exp2f(sacc[kb][e] * c2 - off);
+        const float p1 = __builtin_amdgcn_exp2f(sacc[kb][e + 1] * c2 - off);
         psum += p0 + p1;
         pk[kb][e / 2] = pack_bf16(p0, p1);
       }
