@@ -70,7 +70,7 @@ def bench_prefill(args, w, torch, B, wl):
     torch.cuda.synchronize()
     n_tiles = sized.n_tiles
     kinds = sized.blk_kind.cpu().numpy()
-    n_full = int(kinds.sum())
+    n_full = int((kinds & 1).sum())
     # kept entries: popcount of the tile pool (chunked on the device as bytes through a lookup table)
     lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=dev)
     nnz = 0

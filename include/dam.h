@@ -104,10 +104,13 @@ typedef struct {
  *                                       nQt = ceil(S / tile_m). Required for any block output.
  *   blk_col    [blk_capacity] i32       key-tile index of each listed tile, ascending per query tile.
  *                                       A tile is listed iff it holds at least one kept entry.
- *   blk_kind   [blk_capacity] u8        1 = every entry of the tile is kept and the tile lies
- *                                       strictly below the diagonal and inside S; else 0.
+ *   blk_kind   [blk_capacity] u8        bit 0: every entry of the tile is kept (the tile then lies
+ *                                       strictly below the diagonal and inside S). Bits 1..4: key
+ *                                       quarter q of the tile, columns [q tile_n/4, (q+1) tile_n/4),
+ *                                       holds a kept entry (bit 1 + q); the attention kernel skips
+ *                                       empty quarters.
  *   tile_bits  [blk_capacity][tile_m][tile_n / 64] u64   element bits of listed tile t at index t
- *                                       (also for kind 1 tiles: all ones); bits beyond S are 0.
+ *                                       (also for full tiles: all ones); bits beyond S are 0.
  *   blk_total  [1] i64                  number of listed tiles, valid even when it exceeds
  *                                       blk_capacity (nothing is written past the capacity). Call
  *                                       with blk_col == NULL to size the buffers.

@@ -174,8 +174,10 @@ int64_t dam_oracle_kept_list(const uint8_t *true_mask, int32_t L, const uint8_t 
 /* Block index of one head for query tiles [qt0, qt1): a tile (qt, kt) of tile_m x tile_n entries is
  * listed iff it holds a kept entry; listed tiles of a query tile are in ascending kt.
  *   row_cnt[qt - qt0]   listed tiles of that query tile
- *   col / kind / tile_bits   per listed tile, in order; kind = 1 iff all tile_m * tile_n entries
- *                       are kept (which needs the tile inside S and strictly below the diagonal)
+ *   col / kind / tile_bits   per listed tile, in order; kind bit 0 = 1 iff all tile_m * tile_n
+ *                       entries are kept (which needs the tile inside S and strictly below the
+ *                       diagonal); kind bit 1 + q = 1 iff key quarter q of the tile, columns
+ *                       [q tile_n / 4, (q + 1) tile_n / 4), holds a kept entry
  *   tile_bits           [tile][tile_m][tile_n / 64] words, bit (j % 64) of word j / 64 of row i
  * Returns the number of listed tiles; writes at most cap of them (col, kind, tile_bits may be
  * NULL to count only). */
@@ -194,18 +196,20 @@ int64_t dam_oracle_block_index(const uint8_t *true_mask, int32_t L, const uint8_
     for (int64_t kt = 0; kt < nKt; ++kt) {
       memset(bits, 0, (size_t)tile_words * sizeof(uint64_t));
       int64_t kept = 0;
+      int quarters = 0;
       for (int64_t ii = 0; ii < tile_m; ++ii)
         for (int64_t jj = 0; jj < tile_n; ++jj) {
           const int64_t i = qt * tile_m + ii, j = kt * tile_n + jj;
           if (i < S && j < S && kept_entry(&hd, i, j)) {
             bits[ii * wpr + jj / 64] |= (uint64_t)1 << (jj % 64);
+            quarters |= 1 << (jj / (tile_n / 4));
             ++kept;
           }
         }
       if (kept == 0) continue;
       if (total < cap) {
         if (col) col[total] = (int32_t)kt;
-        if (kind) kind[total] = (uint8_t)(kept == (int64_t)tile_m * tile_n);
+        if (kind) kind[total] = (uint8_t)((kept == (int64_t)tile_m * tile_n) | (quarters << 1));
         if (tile_bits)
           memcpy(tile_bits + total * tile_words, bits, (size_t)tile_words * sizeof(uint64_t));
       }

@@ -347,14 +347,29 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
     for (int w = 0; w < (kt >> 6); ++w) rank += __popcll(oc[w]);
     const int64_t t = first + rank;
     if (t >= capacity) continue;
+    // element words, and which key quarters of the tile hold a kept entry
+    const int qw = g.tile_n / 4;  // quarter width in keys, a multiple of 16
+    int quarters = 0;
+    for (int w = lane; w < words; w += 64) {
+      const int wi = w % g.wpr;
+      const uint64_t m = mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + wi);
+      if (tile_bits) tile_bits[t * words + w] = m;
+      for (int q = 0; q < 4; ++q) {
+        // bits of this word that fall into quarter q: keys [q qw, (q + 1) qw) minus the word base
+        const int lo = max(q * qw - wi * 64, 0), hi = min((q + 1) * qw - wi * 64, 64);
+        if (hi > lo) {
+          const uint64_t span = (hi - lo == 64 ? ~0ull : ((1ull << (hi - lo)) - 1)) << lo;
+          if (m & span) quarters |= 1 << q;
+        }
+      }
+    }
+    int kind = (int)((fl[kt >> 6] >> (kt & 63)) & 1);
+    for (int q = 0; q < 4; ++q)
+      if (__ballot(quarters & (1 << q))) kind |= 2 << q;
     if (lane == 0) {
       if (blk_col) blk_col[t] = kt;
-      if (blk_kind) blk_kind[t] = (uint8_t)((fl[kt >> 6] >> (kt & 63)) & 1);
+      if (blk_kind) blk_kind[t] = (uint8_t)kind;
     }
-    if (tile_bits)
-      for (int w = lane; w < words; w += 64)
-        tile_bits[t * words + w] =
-            mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + w % g.wpr);
   }
 }
 

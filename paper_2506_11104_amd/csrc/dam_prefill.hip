@@ -12,9 +12,13 @@
 //     two half-waves.
 //   O^T += V^T P^T on the same instruction: the accumulator layout of S^T is, up to a fixed
 //     permutation of each 16-key group, already the B-operand layout, so P never leaves
-//     registers. V is transposed once per call into the workspace with that permutation baked in
-//     (padded with zeros to whole tiles), which makes the V^T tile a plain row copy into LDS.
-//   Tiles not in the block index are never touched; kind-1 (full) tiles skip the element mask.
+//     registers; V stays row-major in LDS and its transposed A operand comes from the
+//     transposing LDS read (ds_read_b64_tr_b16), addressed with the same permutation.
+//   K / V move in stages of 64 keys through a double-buffered LDS ring filled by load-to-LDS
+//     instructions (no registers in between): the next stage is in flight while the current one
+//     is computed, one barrier per stage.
+//   Tiles not in the block index are never touched, empty halves of a tile are never loaded, empty
+//     32-key blocks are not multiplied, and full tiles skip the element mask.
 // fp32 kernel (the 1e-4 variant): plain ALU code, one query row per group of head_dim/4 lanes,
 // iterating only over the set bits of the row's tile words.
 #include <hip/hip_bf16.h>
@@ -30,7 +34,7 @@ using namespace dam;
 constexpr int kXcd = 8;
 
 struct AttnArgs {
-  int B, Hq, Hkv, S, nQt, tile_m, tile_n, wpr, s_pad;
+  int B, Hq, Hkv, S, nQt, tile_m, tile_n, wpr;
   float scale;
   int64_t q_sb, q_sh, q_ss, k_sb, k_sh, k_ss, v_sb, v_sh, v_ss, o_sb, o_sh, o_ss;
 };
@@ -122,75 +126,249 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
 // ================================================================================================
 // bf16 MFMA variant
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-constexpr int kD = 128;            // head dim
 constexpr int kBM = 128, kBN = 128;
-constexpr int kRowBytes = 272;     // 256 B of bf16 + 16 B pad: 16-byte reads of 16 consecutive rows
-                                   // fall into 16 different bank groups
-constexpr int kTileLds = 128 * kRowBytes;
+constexpr int kStageKeys = 64;               // keys per pipeline stage (half a tile)
+constexpr int kStageK = kStageKeys * 256;    // K part of a stage: 64 rows x 256 B, no padding
+constexpr int kStageBytes = 2 * kStageK;     // + the V part
+constexpr int kLdsBytes = 2 * kStageBytes;   // double buffered: 64 KiB, two workgroups per CU
 
-// Position of key offset o (0..15) inside its 16-key group of the transposed V: the two middle
-// groups of four are swapped so that the S^T accumulators of one lane are, in register order, the
-// eight consecutive k-slots the B operand of the P V product expects.
-__host__ __device__ constexpr int vt_slot(int o) { return 8 * ((o % 8) / 4) + 4 * (o / 8) + o % 4; }
-
-// V [b][hkv][s][d] -> VT [b*Hkv + hkv][d][s_pad] with keys permuted inside groups of 16 and zeros
-// beyond S. 64 x 64 element patches through LDS.
-__global__ __launch_bounds__(256) void k_transpose_v(AttnArgs a, const __hip_bfloat16 *__restrict__ v,
-                                                     __hip_bfloat16 *__restrict__ vt) {
-  __shared__ unsigned short patch[64][66];
-  const int s0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
-  const int pair = blockIdx.z, b = pair / a.Hkv, hkv = pair % a.Hkv;
-  const unsigned short *src = reinterpret_cast<const unsigned short *>(v) + b * a.v_sb + hkv * a.v_sh;
-  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-    const int r = e / 64, c = e % 64;  // r: key, c: dim
-    patch[r][c] = (s0 + r < a.S) ? src[(int64_t)(s0 + r) * a.v_ss + d0 + c] : (unsigned short)0;
-  }
-  __syncthreads();
-  unsigned short *dst = reinterpret_cast<unsigned short *>(vt) + (int64_t)pair * kD * a.s_pad;
-  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-    const int c = e / 64, pos = e % 64;  // c: dim, pos: position inside the 64-key patch
-    const int grp = pos / 16, slot = pos % 16;
-    // inverse of vt_slot: slot -> key offset
-    const int o = 8 * ((slot % 8) / 4) + 4 * (slot / 8) + slot % 4;
-    dst[(int64_t)(d0 + c) * a.s_pad + s0 + pos] = patch[grp * 16 + o][c];
-  }
-}
+// LDS layout. Rows are 256 B = 16 chunks of 16 B and are not padded, because the global -> LDS
+// copies are done by the load-to-LDS instruction, which writes the 64 lanes of a wave to 1 KiB of
+// consecutive LDS. Bank conflicts are avoided by permuting the chunks of a row instead:
+//   K row r: chunk c lives at position c ^ (r & 15)        (16-byte reads of 16 consecutive rows
+//            and one logical chunk then cover all 64 banks once)
+//   V row r: chunk c lives at position c ^ ((r & 3) << 2)  (a transposing read touches 4 rows x 64 B
+//            per half-wave; the four 64-byte groups land in different bank quarters)
+// The permutation is applied on the global side of the copy (which chunk a lane fetches).
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-  // round to nearest even on both halves
-  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   typedef __attribute__((ext_vector_type(2))) float f32x2;
-  const bf16x2 r = __builtin_convertvector((f32x2){lo, hi}, bf16x2);
+  const bf16x2 r = __builtin_convertvector((f32x2){lo, hi}, bf16x2);  // round to nearest even
   return __builtin_bit_cast(unsigned, r);
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16(AttnArgs a, const __hip_bfloat16 *__restrict__ q,
-                                                      const __hip_bfloat16 *__restrict__ k,
-                                                      const __hip_bfloat16 *__restrict__ vt,
-                                                      const int *__restrict__ row_ptr,
-                                                      const int *__restrict__ blk_col,
-                                                      const uint8_t *__restrict__ blk_kind,
-                                                      const uint64_t *__restrict__ tile_bits,
-                                                      __hip_bfloat16 *__restrict__ out,
-                                                      float *__restrict__ lse) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  unsigned char *ldsK = lds, *ldsV = lds + kTileLds;
+__device__ __forceinline__ bf16x8 lds_read_b128(const unsigned char *lds, int byte) {
+  return *reinterpret_cast<const bf16x8 *>(lds + byte);
+}
 
-  const WorkItem w = decode_work(a, blockIdx.x);
-  if (!w.valid) return;
+__device__ __forceinline__ s16x4 lds_read_tr(const unsigned char *lds, int byte) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4 *)(const_cast<unsigned char *>(lds + byte)));
+}
+
+// One pipeline stage = one occupied half (64 keys) of a listed tile.
+struct Stage {
+  int t, half;
+};
+
+// Scheduling hints: instruction classes of __builtin_amdgcn_sched_group_barrier.
+#define DAM_SCHED_MFMA 0x008
+#define DAM_SCHED_DSREAD 0x100
+
+// Softmax + P V of one stage for the key blocks named by ACT (bit kb set = the 32-key block kb of
+// the stage is computed; the other one holds no kept entry for this wave's 32 rows).
+template <int ACT>
+__device__ __forceinline__ void stage_compute(const unsigned char *__restrict__ ldsK,
+                                              const unsigned char *__restrict__ ldsV, const bf16x8 (&qf)[8],
+                                              f32x16 (&oacc)[4], float &m_run, float &l_run, bool full,
+                                              u32x2 bits, float c2, const int (&kaddr)[8],
+                                              const int (&vaddr)[4], int hf) {
+  constexpr int NB = (ACT == 3) ? 2 : 1;          // active key blocks
+  constexpr int KB0 = (ACT == 2) ? 1 : 0;         // first active block
+  f32x16 sacc[NB];
+  // accumulator e of block kb is key 32 kb + 8 (e / 4) + 4 hf + e % 4: start it at 0 (kept) or -inf
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int inv = (int)~(bits[KB0 + b] >> (4 * hf));  // all zero for a full tile
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      sacc[b][e] = __int_as_float(__builtin_amdgcn_sbfe(inv, 8 * (e / 4) + e % 4, 1) << 23);  // 0 or 0xFF800000
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // S^T = K Q^T, operands fetched a few MFMAs ahead
+  {
+    bf16x8 kf[8][NB];
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+      for (int b = 0; b < NB; ++b) kf[c][b] = lds_read_b128(ldsK, kaddr[c] + (KB0 + b) * 32 * 256);
+    if (full) {
+      // a full tile needs no element mask: the first product starts from a literal zero
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][b], qf[0], zero, 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][b], qf[0], sacc[b], 0, 0, 0);
+    }
+#pragma unroll
+    for (int c = 1; c < 8; ++c)
+#pragma unroll
+      for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c][b], qf[c], sacc[b], 0, 0, 0);
+    constexpr int N = 8 * NB, AHEAD = 4;
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, AHEAD, 0);
+#pragma unroll
+    for (int x = 0; x < N - AHEAD; ++x) {
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, AHEAD, 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // online softmax; one query per lane pair (lane, lane ^ 32)
+  float mx = -INFINITY;
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) mx = fmaxf(fmaxf(sacc[b][e], sacc[b][e + 1]), mx);
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m_run, mx);
+  const float m_ref = m_new == -INFINITY ? 0.0f : m_new;
+  const float corr = __builtin_amdgcn_exp2f((m_run - m_ref) * c2);
+  const float off = m_ref * c2;
+  m_run = m_new;
+  float psum = 0.0f;
+  unsigned pk[NB][8];
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][e], c2, -off));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][e + 1], c2, -off));
+      pk[b][e / 2] = pack_bf16(p0, p1);
+      // the row sum is taken over the rounded weights the P V product uses
+      psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[b][e / 2]), ones, psum, false);
+    }
+  l_run = l_run * corr + psum;
+  if (__ballot(corr != 1.0f)) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[db][e] *= corr;
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // O^T += V^T P^T. B operand: accumulators 8a .. 8a+7 of block kb as bf16, i.e. k-slot 8 hf + j is key
+  // 32 kb + 16 a + 8 (j / 4) + 4 hf + j % 4. A operand: those keys of V at dim 32 db + (lane % 32), fetched
+  // with two transposing LDS reads (each returns 4 consecutive keys of one dim; within a group of 16
+  // lanes, lane s supplies the address of key s / 4, dims 4 (s % 4) .. + 3).
+  {
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x4 vr[NB][2][4][2];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int u = 0; u < 2; ++u)
+            vr[b][a2][db][u] = lds_read_tr(ldsV, vaddr[db] + ((KB0 + b) * 32 + a2 * 16 + u * 8) * 256);
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int a2 = 0; a2 < 2; ++a2) {
+        const u32x4 praw = {pk[b][4 * a2], pk[b][4 * a2 + 1], pk[b][4 * a2 + 2], pk[b][4 * a2 + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, praw);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const s16x8 both = __builtin_shufflevector(vr[b][a2][db][0], vr[b][a2][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, oacc[db], 0, 0, 0);
+        }
+      }
+    constexpr int N = 8 * NB, AHEAD = 4;
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 2 * AHEAD, 0);
+#pragma unroll
+    for (int x = 0; x < N - AHEAD; ++x) {
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, AHEAD, 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16(
+    AttnArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ k,
+    const __hip_bfloat16 *__restrict__ v, const int *__restrict__ row_ptr, const int *__restrict__ blk_col,
+    const uint8_t *__restrict__ blk_kind, const uint64_t *__restrict__ tile_bits, __hip_bfloat16 *__restrict__ out,
+    float *__restrict__ lse, int *__restrict__ queue_next) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  __shared__ int s_item[2];
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hf = lane >> 5;
-  const int t0 = row_ptr[(int64_t)w.hq * (a.nQt + 1) + w.qt];
-  const int t1 = row_ptr[(int64_t)w.hq * (a.nQt + 1) + w.qt + 1];
-  const int qrow_l = wave * 32 + n;              // this lane's query row inside the tile
+  const float c2 = a.scale * 1.4426950408889634f;
+
+  // LDS byte offsets of this lane's operand fragments inside a stage (see the layout note above)
+  int kaddr[8], vaddr[4];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) kaddr[c] = n * 256 + (((2 * c + hf) ^ (n & 15)) << 4);
+  {
+    const int i16 = n & 15, rl = i16 >> 2;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+      vaddr[db] = kStageK + (4 * hf + rl) * 256 + ((db ^ rl) << 6) + 32 * (n >> 4) + 8 * (i16 & 3);
+  }
+  // per-lane byte offsets of the load-to-LDS copies inside a stage (see copy_in below): instruction
+  // `it` of wave w fills rows 16 it + 4 w .. + 3, so that a lane's row permutation is the same for
+  // every `it` and one offset per tensor serves all four instructions
+  const int sub = lane >> 4, pos = lane & 15;
+  const int row0 = wave * 4 + sub;
+  const unsigned koff = (unsigned)(row0 * (int)a.k_ss * 2 + ((pos ^ (row0 & 15)) << 4));
+  const unsigned voff = (unsigned)(row0 * (int)a.v_ss * 2 + ((pos ^ (sub << 2)) << 4));
+
+  // Persistent workgroups pull (head, query tile) items from eight queues, one per XCD: queue x
+  // holds the (batch, KV head) pairs with pair % 8 == x, so that the query heads sharing a KV
+  // head run on one XCD and share its L2 copy of K / V; items of a queue go longest-row first.
+  // A workgroup drains the queue of the XCD it runs on, then helps the others, and exits when
+  // all eight are empty.
+  const int G = a.Hq / a.Hkv, n_pairs = a.B * a.Hkv, per_pair = G * a.nQt;
+  const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);  // XCC_ID, 4 bits
+  int hop = 0;
+  while (true) {
+  __syncthreads();  // previous item: every wave is done with the LDS ring and with s_item
+  if (tid == 0) {
+    int item = -1, queue = 0;
+    for (; hop < kXcd; ++hop) {
+      queue = (my_xcd + hop) & (kXcd - 1);
+      const int pairs_here = (n_pairs - queue + kXcd - 1) / kXcd;  // pairs p with p % 8 == queue
+      const int got = atomicAdd(&queue_next[queue], 1);
+      if (got < pairs_here * per_pair) {
+        item = got;
+        break;
+      }
+    }
+    s_item[0] = item;
+    s_item[1] = queue;
+  }
+  __syncthreads();
+  const int item = s_item[0], queue = s_item[1];
+  if (item < 0) break;
+  if (queue != ((my_xcd + hop) & (kXcd - 1))) hop = (queue - my_xcd) & (kXcd - 1);  // other threads follow thread 0
+  WorkItem w;
+  {
+    const int pair = (item / per_pair) * kXcd + queue, within = item % per_pair;
+    w.b = pair / a.Hkv;
+    w.hkv = pair % a.Hkv;
+    w.qt = a.nQt - 1 - within / G;
+    w.hq = w.hkv * G + within % G;
+    w.valid = true;
+  }
+  const int t0 = __builtin_amdgcn_readfirstlane(row_ptr[(int64_t)w.hq * (a.nQt + 1) + w.qt]);
+  const int t1 = __builtin_amdgcn_readfirstlane(row_ptr[(int64_t)w.hq * (a.nQt + 1) + w.qt + 1]);
+  const int qrow_l = wave * 32 + n;  // this lane's query row inside the tile
   const int qrow = w.qt * kBM + qrow_l;
   const bool qlive = qrow < a.S;
 
-  // Q fragments: B operand of S^T = K Q^T. Chunk c covers dims 16c .. 16c+15; this lane holds
-  // dims 16c + 8 hf .. + 7 of its query row.
+  // Q fragments: B operand of S^T = K Q^T. Chunk c covers dims 16c .. 16c+15; this lane holds dims
+  // 16c + 8 hf .. + 7 of its query row.
   bf16x8 qf[8];
   {
     const __hip_bfloat16 *qp = q + w.b * a.q_sb + w.hq * a.q_sh + (int64_t)qrow * a.q_ss + 8 * hf;
@@ -201,110 +379,115 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       qf[c] = __builtin_bit_cast(bf16x8, raw);
     }
   }
-
   f32x16 oacc[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
-  float m_run = -INFINITY, l_run = 0.0f;   // running max (raw logit units) and this lane's part of the sum
-  const float c2 = a.scale * 1.4426950408889634f;
+  float m_run = -INFINITY, l_run = 0.0f;  // running max (raw logits) and this lane's part of the row sum
 
   const unsigned char *kg = reinterpret_cast<const unsigned char *>(k + w.b * a.k_sb + w.hkv * a.k_sh);
-  const unsigned char *vg =
-      reinterpret_cast<const unsigned char *>(vt + (int64_t)(w.b * a.Hkv + w.hkv) * kD * a.s_pad);
+  const unsigned char *vg = reinterpret_cast<const unsigned char *>(v + w.b * a.v_sb + w.hkv * a.v_sh);
 
-  for (int t = t0; t < t1; ++t) {
-    const int kt = blk_col[t];
-    const bool full = blk_kind[t] != 0;
-    __syncthreads();  // every wave is done with the previous tile
-    // K tile: 128 rows x 256 B; V^T tile: 128 dims x 256 B. 16 lanes copy one row.
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int chunk = tid + 256 * it, r = chunk >> 4, c16 = chunk & 15;
-      const int key = kt * kBN + r;
-      u32x4 kv = {0u, 0u, 0u, 0u};
-      if (key < a.S) kv = *reinterpret_cast<const u32x4 *>(kg + (int64_t)key * a.k_ss * 2 + c16 * 16);
-      const u32x4 vv = *reinterpret_cast<const u32x4 *>(vg + ((int64_t)r * a.s_pad + kt * kBN) * 2 + c16 * 16);
-      *reinterpret_cast<u32x4 *>(ldsK + r * kRowBytes + c16 * 16) = kv;
-      *reinterpret_cast<u32x4 *>(ldsV + r * kRowBytes + c16 * 16) = vv;
+  // next occupied half at or after (t, half)
+  auto seek = [&](Stage s) {
+    while (s.t < t1) {
+      const int quarters = __builtin_amdgcn_readfirstlane((int)blk_kind[s.t]) >> 1;
+      if (s.half == 0 && (quarters & 3)) break;
+      if (s.half <= 1 && (quarters & 12)) {
+        s.half = 1;
+        break;
+      }
+      ++s.t;
+      s.half = 0;
     }
-    // this lane's mask words: row qrow_l of the tile, 128 keys = 4 dwords
-    u32x4 mw = {~0u, ~0u, ~0u, ~0u};
-    if (!full) mw = *reinterpret_cast<const u32x4 *>(tile_bits + ((int64_t)t * kBM + qrow_l) * 2);
+    return s;
+  };
+  auto after = [&](Stage s) {
+    if (s.half == 0) return seek(Stage{s.t, 1});
+    return seek(Stage{s.t + 1, 0});
+  };
+  // Global -> LDS copy of one stage: every wave issues 4 + 4 load-to-LDS instructions of 1 KiB
+  // (4 rows) each. Lane L of an instruction fills one row at position L % 16 and therefore
+  // fetches the chunk that the row's permutation puts there. A copy is a scalar base (the first
+  // key of the instruction) plus the constant per-lane offset. The one stage that can reach past
+  // the end of the sequence redirects such keys to the last row (they are masked anyway; this
+  // keeps the tile finite).
+  auto copy_in = [&](Stage s, int buf) {
+    const int key0 = __builtin_amdgcn_readfirstlane(blk_col[s.t]) * kBN + s.half * kStageKeys;
+    unsigned char *base = lds + buf * kStageBytes + wave * 1024;
+    if (key0 + kStageKeys <= a.S) {
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const unsigned char *kst = kg + (int64_t)(key0 + 16 * it) * a.k_ss * 2;
+        const unsigned char *vst = vg + (int64_t)(key0 + 16 * it) * a.v_ss * 2;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kst + koff),
+                                         (__attribute__((address_space(3))) void *)(base + it * 4096), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vst + voff),
+                                         (__attribute__((address_space(3))) void *)(base + kStageK + it * 4096), 16, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = 16 * it + row0;
+        const int key = min(key0 + row, a.S - 1);
+        const int kc = pos ^ (row0 & 15), vc = pos ^ (sub << 2);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(kg + (int64_t)key * a.k_ss * 2 + kc * 16),
+            (__attribute__((address_space(3))) void *)(base + it * 4096), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void *)(vg + (int64_t)key * a.v_ss * 2 + vc * 16),
+            (__attribute__((address_space(3))) void *)(base + kStageK + it * 4096), 16, 0, 0);
+      }
+    }
+  };
+  auto load_bits = [&](Stage s) {
+    u32x2 r = {~0u, ~0u};
+    if (!(__builtin_amdgcn_readfirstlane((int)blk_kind[s.t]) & 1))
+      r = *reinterpret_cast<const u32x2 *>(tile_bits + ((int64_t)s.t * kBM + qrow_l) * 2 + s.half);
+    return r;
+  };
+
+  Stage cur = seek(Stage{t0, 0});
+  if (cur.t < t1) {
+    copy_in(cur, 0);
+    u32x2 bits = load_bits(cur);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-
-    // S^T = K Q^T: block kb holds keys 32 kb .. 32 kb + 31 (rows) x 32 queries (columns)
-    f32x16 sacc[4];
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.0f;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ldsK + (kb * 32 + n) * kRowBytes + c * 32 + hf * 16);
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], sacc[kb], 0, 0, 0);
+    int buf = 0;
+    while (true) {
+      const Stage nxt = after(cur);
+      const bool more = nxt.t < t1;
+      u32x2 bits_next = {0u, 0u};
+      if (more) {
+        copy_in(nxt, buf ^ 1);
+        bits_next = load_bits(nxt);
       }
+      {
+        const int kind = __builtin_amdgcn_readfirstlane((int)blk_kind[cur.t]);
+        const bool full = kind & 1;
+        const int quarters = (kind >> (1 + 2 * cur.half)) & 3;
+        const bool act0 = (quarters & 1) && __ballot(bits[0] != 0u);
+        const bool act1 = (quarters & 2) && __ballot(bits[1] != 0u);
+        const unsigned char *ldsS = lds + buf * kStageBytes;
+        if (act0 && act1)
+          stage_compute<3>(ldsS, ldsS, qf, oacc, m_run, l_run, full, bits, c2, kaddr, vaddr, hf);
+        else if (act0)
+          stage_compute<1>(ldsS, ldsS, qf, oacc, m_run, l_run, full, bits, c2, kaddr, vaddr, hf);
+        else if (act1)
+          stage_compute<2>(ldsS, ldsS, qf, oacc, m_run, l_run, full, bits, c2, kaddr, vaddr, hf);
+      }
+      if (!more) break;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      bits = bits_next;
+      cur = nxt;
+      buf ^= 1;
     }
-    // element mask: accumulator e of block kb is key 32 kb + 8 (e / 4) + 4 hf + e % 4
-    if (!full) {
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb) {
-        const unsigned bits = mw[kb] >> (4 * hf);
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (!((bits >> (8 * (e / 4) + e % 4)) & 1u)) sacc[kb][e] = -INFINITY;
-      }
-    }
-    // online softmax, one query per lane pair (lane, lane ^ 32)
-    float mx = sacc[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[kb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_ref = m_new == -INFINITY ? 0.0f : m_new;
-    const float corr = __builtin_amdgcn_exp2f((m_run - m_ref) * c2);
-    const float off = m_ref * c2;
-    m_run = m_new;
-    float psum = 0.0f;
-    unsigned pk[4][8];
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(sacc[kb][e] * c2 - off);
-        const float p1 = __builtin_amdgcn_exp2f(sacc[kb][e + 1] * c2 - off);
-        psum += p0 + p1;
-        pk[kb][e / 2] = pack_bf16(p0, p1);
-      }
-    l_run = l_run * corr + psum;
-    if (__ballot(corr != 1.0f)) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[db][e] *= corr;
-    }
-    // O^T += V^T P^T: for key block kb and half a, the B operand is accumulators 8a .. 8a+7 of
-    // block kb (as bf16); the A operand is 16 bytes of row (32 db + n) of the V^T tile.
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2) {
-        const u32x4 praw = {pk[kb][4 * h2], pk[kb][4 * h2 + 1], pk[kb][4 * h2 + 2], pk[kb][4 * h2 + 3]};
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, praw);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(ldsV + (db * 32 + n) * kRowBytes +
-                                                             (kb * 32 + h2 * 16) * 2 + hf * 16);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
-        }
-      }
   }
 
-  // finish: total sum over both half-waves, normalise, store. Accumulator e of block db is
-  // dim 32 db + 8 (e / 4) + 4 hf + e % 4 of this lane's query.
+  // finish: total sum over both half-waves, normalise, store. Accumulator e of block db is dim
+  // 32 db + 8 (e / 4) + 4 hf + e % 4 of this lane's query.
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
   if (qlive) {
@@ -322,6 +505,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       lse[((int64_t)w.b * a.Hq + w.hq) * a.S + qrow] =
           l_tot > 0.0f ? (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
   }
+  }  // next work item
+}
+
+__global__ void k_zero_queues(int *queue_next) {
+  if (threadIdx.x < kXcd) queue_next[threadIdx.x] = 0;
 }
 
 int validate(const dam_attn_params *p, const void *q, const void *k, const void *v, const dam_mask_view *mk,
@@ -353,7 +541,6 @@ AttnArgs make_args(const dam_attn_params *p) {
   a.tile_m = p->tile_m; a.tile_n = p->tile_n;
   a.nQt = (p->seq + p->tile_m - 1) / p->tile_m;
   a.wpr = p->tile_n / 64;
-  a.s_pad = (p->seq + kBN - 1) / kBN * kBN;
   a.scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf((float)p->head_dim);
   a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1]; a.q_ss = p->q_stride[2];
   a.k_sb = p->k_stride[0]; a.k_sh = p->k_stride[1]; a.k_ss = p->k_stride[2];
@@ -366,9 +553,7 @@ AttnArgs make_args(const dam_attn_params *p) {
 
 extern "C" size_t dam_sparse_attn_prefill_workspace(const dam_attn_params *p) {
   if (!p || p->batch < 1 || p->hkv < 1 || p->seq < 1) return 0;
-  if (p->dtype != DAM_BF16) return 0;
-  const size_t s_pad = ((size_t)p->seq + kBN - 1) / kBN * kBN;
-  return align_up((size_t)p->batch * p->hkv * kD * s_pad * 2, 256);  // transposed V
+  return p->dtype == DAM_BF16 ? 256 : 0;  // the eight work-queue counters of the bf16 kernel
 }
 
 extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, const void *k, const void *v,
@@ -390,18 +575,27 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
                                                 mk->blk_col, mk->tile_bits, (float *)out, lse);
     return launch_status();
   }
-  __hip_bfloat16 *vt = static_cast<__hip_bfloat16 *>(ws);
-  k_transpose_v<<<dim3(a.s_pad / 64, kD / 64, a.B * a.Hkv), 256, 0, st>>>(a, (const __hip_bfloat16 *)v, vt);
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_prefill_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * kTileLds) != hipSuccess)
+                            kLdsBytes) != hipSuccess)
       return DAM_ERR_DEVICE;
     attr_set = true;
   }
-  k_prefill_bf16<<<blocks, 256, 2 * kTileLds, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k, vt,
+  static int n_cu = 0;
+  if (!n_cu) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return DAM_ERR_DEVICE;
+    n_cu = prop.multiProcessorCount;
+  }
+  int *queue_next = static_cast<int *>(ws);
+  k_zero_queues<<<1, 64, 0, st>>>(queue_next);
+  const int persistent = std::min(blocks, 2 * n_cu);  // two workgroups fit a CU (registers and LDS)
+  k_prefill_bf16<<<persistent, 256, kLdsBytes, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
+                                                (const __hip_bfloat16 *)v,
                                                    mk->blk_row_ptr, mk->blk_col, mk->blk_kind, mk->tile_bits,
-                                                   (__hip_bfloat16 *)out, lse);
+                                                   (__hip_bfloat16 *)out, lse, queue_next);
   return launch_status();
 }
 

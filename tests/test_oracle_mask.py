@@ -310,7 +310,12 @@ def test_block_index_reexpansion(S, tm, tn):
             assert np.all(np.diff(cols) > 0)                 # ascending, no duplicates
         pc = np.array([int(np.unpackbits(bits[t].view(np.uint8)).sum()) for t in range(lo, hi)])
         assert pc.sum() == M.sum() and (pc > 0).all()
-        assert np.array_equal(kind[lo:hi], (pc == tm * tn).astype(np.uint8))
+        assert np.array_equal(kind[lo:hi] & 1, (pc == tm * tn).astype(np.uint8))
+        for t in range(lo, hi):                              # quarter-occupancy bits, from the dense mask
+            qt = int(np.searchsorted(row_ptr[h], t, side="right") - 1)
+            blk = M[qt * tm:(qt + 1) * tm, col[t] * tn:(col[t] + 1) * tn]
+            want = sum((1 << (1 + q)) for q in range(4) if blk[:, q * tn // 4:(q + 1) * tn // 4].any())
+            assert (kind[t] & 0x1E) == want and kind[t] < 32
 
 
 def test_block_index_full_tiles_only_below_diagonal():
@@ -324,4 +329,5 @@ def test_block_index_full_tiles_only_below_diagonal():
     for qt in range(n):
         sl = slice(row_ptr[0, qt], row_ptr[0, qt + 1])
         assert np.array_equal(col[sl], np.arange(qt + 1))
-        assert np.array_equal(kind[sl], [1] * qt + [0])      # the diagonal tile is partial
+        assert np.array_equal(kind[sl] & 1, [1] * qt + [0])  # the diagonal tile is partial
+        assert np.all(kind[sl] >> 1 == 15)
