@@ -5,7 +5,7 @@
 //
 // HBM-bound gather of 2 * head_dim * sizeof(T) bytes per kept key. A K or V row is read by LPR
 // adjacent lanes with one 16-byte load each (a whole row per load instruction group, fully
-// coalesced); every lane keeps 4 keys in flight. The kept list is split over several workgroups
+// coalesced); every lane keeps 8 keys in flight. The kept list is split over several workgroups
 // per head so that all 256 CUs stream; partial (max, sum, O) triples are merged by log-sum-exp.
 // Workgroups are numbered so that all query heads sharing a KV head run on the same XCD and hit
 // the same L2 for the rows their lists have in common.
@@ -20,7 +20,7 @@ namespace {
 using namespace dam;
 
 constexpr int kXcd = 8;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 8;  // keys in flight per lane (K and V fragment each)
 
 struct DecodeArgs {
   int B, Hq, Hkv, cap, splits;
@@ -28,31 +28,65 @@ struct DecodeArgs {
   int64_t q_sb, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_sh;
 };
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// 16 bytes of a row, kept as loaded; dot() and axpy() interpret them.
 template <typename T>
-struct Frag;  // 16 bytes of a row as floats
+struct Frag;
 
 template <>
 struct Frag<float> {
-  static constexpr int N = 4;
-  __device__ static void load(const float *p, float (&f)[4]) {
-    const float4 v = *reinterpret_cast<const float4 *>(p);
-    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  static constexpr int N = 4;  // elements per 16 bytes
+  __device__ static float dot(const uint4 &a, const uint4 &b) {
+    float d = __uint_as_float(a.x) * __uint_as_float(b.x);
+    d = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), d);
+    d = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), d);
+    return fmaf(__uint_as_float(a.w), __uint_as_float(b.w), d);
+  }
+  __device__ static void axpy(float (&o)[4], float w, const uint4 &v) {
+    o[0] = fmaf(w, __uint_as_float(v.x), o[0]);
+    o[1] = fmaf(w, __uint_as_float(v.y), o[1]);
+    o[2] = fmaf(w, __uint_as_float(v.z), o[2]);
+    o[3] = fmaf(w, __uint_as_float(v.w), o[3]);
   }
 };
 
 template <>
 struct Frag<__hip_bfloat16> {
   static constexpr int N = 8;
-  __device__ static void load(const __hip_bfloat16 *p, float (&f)[8]) {
-    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+  // exact fp32 products of bf16 pairs, fp32 accumulation (v_dot2_f32_bf16)
+  __device__ static float dot(const uint4 &a, const uint4 &b) {
+    float d = 0.0f;
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.x), __builtin_bit_cast(bf16x2, b.x), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.y), __builtin_bit_cast(bf16x2, b.y), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.z), __builtin_bit_cast(bf16x2, b.z), d, false);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.w), __builtin_bit_cast(bf16x2, b.w), d, false);
+  }
+  __device__ static void axpy(float (&o)[8], float w, const uint4 &v) {
     const unsigned u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      f[2 * k] = __uint_as_float(u[k] << 16);
-      f[2 * k + 1] = __uint_as_float(u[k] & 0xFFFF0000u);
+      o[2 * k] = fmaf(w, __uint_as_float(u[k] << 16), o[2 * k]);
+      o[2 * k + 1] = fmaf(w, __uint_as_float(u[k] & 0xFFFF0000u), o[2 * k + 1]);
     }
   }
 };
+
+// Sum over the LPR adjacent lanes that share a row (LPR = 8, 16 or 32), on the DPP network.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+
+template <int LPR>
+__device__ __forceinline__ float row_sum(float d) {
+  d += dpp_move<0xB1>(d);   // quad_perm [1,0,3,2]
+  d += dpp_move<0x4E>(d);   // quad_perm [2,3,0,1]
+  d += dpp_move<0x141>(d);  // row_half_mirror: the other quad of the 8
+  if (LPR >= 16) d += dpp_move<0x140>(d);  // row_mirror: the other half of the 16
+  if (LPR >= 32) d += __shfl_xor(d, 16);
+  return d;
+}
 
 __device__ __forceinline__ void store_out(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(__hip_bfloat16 *p, float v) { *p = __float2bfloat16(v); }
@@ -65,7 +99,8 @@ __global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *_
                                                         const int *__restrict__ kept_ptr,
                                                         const int *__restrict__ kept_idx,
                                                         float *__restrict__ part_o,
-                                                        float *__restrict__ part_ml) {
+                                                        float *__restrict__ part_ml, T *__restrict__ out,
+                                                        float *__restrict__ lse) {
   constexpr int N = Frag<T>::N;        // elements per lane
   constexpr int LPR = D / N;           // lanes per row
   constexpr int GROUPS = 256 / LPR;    // rows in flight per pass of the block
@@ -94,8 +129,7 @@ __global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *_
   const int64_t beg = lo + (int64_t)split * chunk;
   const int64_t end = std::min<int64_t>(hi, beg + chunk);
 
-  float qf[N];
-  Frag<T>::load(q + b * a.q_sb + hq * a.q_sh + sub * N, qf);
+  const uint4 qf = *reinterpret_cast<const uint4 *>(q + b * a.q_sb + hq * a.q_sh + sub * N);
   const T *kb = kc + b * a.kv_sb + hkv * a.kv_sh + sub * N;
   const T *vb = vc + b * a.kv_sb + hkv * a.kv_sh + sub * N;
   const float sl2 = a.scale * 1.4426950408889634f;  // logits in log2 units
@@ -104,37 +138,41 @@ __global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *_
 #pragma unroll
   for (int e = 0; e < N; ++e) o[e] = 0.0f;
 
-  for (int64_t p0 = beg + group * kUnroll; p0 < end; p0 += GROUPS * kUnroll) {
-    float kf[kUnroll][N], vf[kUnroll][N], s[kUnroll];
-    bool live[kUnroll];
+  // The key indices of the next pass are fetched while the rows of the current one are in flight,
+  // so that a pass costs one memory round trip, not two.
+  int rows[kUnroll];
+  int64_t p0 = beg + group * kUnroll;
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) rows[u] = p0 < end ? kept_idx[p0 + u < end ? p0 + u : p0] : 0;
+  for (; p0 < end; p0 += GROUPS * kUnroll) {
+    uint4 kf[kUnroll], vf[kUnroll];
+    float s[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      live[u] = p0 + u < end;
-      const int64_t row = live[u] ? kept_idx[p0 + u] : kept_idx[p0];
-      Frag<T>::load(kb + row * a.kv_ss, kf[u]);
-      Frag<T>::load(vb + row * a.kv_ss, vf[u]);
+      kf[u] = *reinterpret_cast<const uint4 *>(kb + (int64_t)rows[u] * a.kv_ss);
+      vf[u] = *reinterpret_cast<const uint4 *>(vb + (int64_t)rows[u] * a.kv_ss);
+    }
+    const int64_t pn = p0 + GROUPS * kUnroll;
+    if (pn < end) {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) rows[u] = kept_idx[pn + u < end ? pn + u : pn];
     }
     float mx = m;
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      float d = 0.0f;
-#pragma unroll
-      for (int e = 0; e < N; ++e) d = fmaf(qf[e], kf[u][e], d);
-#pragma unroll
-      for (int off = LPR / 2; off; off >>= 1) d += __shfl_xor(d, off);
-      s[u] = live[u] ? d * sl2 : -INFINITY;
+      const float d = row_sum<LPR>(Frag<T>::dot(qf, kf[u]));
+      s[u] = p0 + u < end ? d * sl2 : -INFINITY;
       mx = fmaxf(mx, s[u]);
     }
-    const float corr = exp2f(m - mx);  // m = -inf, mx finite -> 0; p0 < end guarantees mx finite
+    const float corr = __builtin_amdgcn_exp2f(m - mx);  // m = -inf, mx finite -> 0; p0 < end guarantees mx finite
     l *= corr;
 #pragma unroll
     for (int e = 0; e < N; ++e) o[e] *= corr;
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const float w = exp2f(s[u] - mx);
+      const float w = __builtin_amdgcn_exp2f(s[u] - mx);
       l += w;
-#pragma unroll
-      for (int e = 0; e < N; ++e) o[e] = fmaf(w, vf[u][e], o[e]);
+      Frag<T>::axpy(o, w, vf[u]);
     }
     m = mx;
   }
@@ -157,11 +195,17 @@ __global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *_
         Lsum += w * s_l[g];
         acc += w * s_o[g][threadIdx.x];
       }
-    const int64_t slot_out = (int64_t)item * a.splits + split;
-    part_o[slot_out * D + threadIdx.x] = acc;
-    if (threadIdx.x == 0) {
-      part_ml[slot_out * 2] = M;
-      part_ml[slot_out * 2 + 1] = Lsum;
+    if (a.splits == 1) {  // the whole list was handled here: normalise and store, no merge pass
+      store_out(out + b * a.o_sb + hq * a.o_sh + threadIdx.x, Lsum > 0.0f ? acc / Lsum : 0.0f);
+      if (lse && threadIdx.x == 0)
+        lse[item] = Lsum > 0.0f ? (M + log2f(Lsum)) * 0.6931471805599453f : -INFINITY;
+    } else {
+      const int64_t slot_out = (int64_t)item * a.splits + split;
+      part_o[slot_out * D + threadIdx.x] = acc;
+      if (threadIdx.x == 0) {
+        part_ml[slot_out * 2] = M;
+        part_ml[slot_out * 2 + 1] = Lsum;
+      }
     }
   }
 }
@@ -190,10 +234,11 @@ __global__ void k_decode_merge(DecodeArgs a, const float *__restrict__ part_o,
 }
 
 int pick_splits(const dam_decode_params *p, int64_t max_kept) {
+  // Enough workgroups to put two on every CU (512), each with at least 256 keys; one split (and no
+  // merge pass) when the batch alone provides them.
   const int64_t items = (int64_t)p->batch * p->hq;
-  int64_t s = (max_kept + 511) / 512;                       // about 512 keys per workgroup
-  s = std::max<int64_t>(s, (1024 + items - 1) / items);     // at least ~4 workgroups per CU
-  s = std::min<int64_t>(s, std::max<int64_t>(1, max_kept / 64));
+  int64_t s = (512 + items - 1) / items;
+  s = std::min<int64_t>(s, std::max<int64_t>(1, max_kept / 256));
   return (int)std::min<int64_t>(std::max<int64_t>(s, 1), 64);
 }
 
@@ -221,8 +266,9 @@ void launch(const DecodeArgs &a, const void *q, const void *kc, const void *vc, 
   const int rounds = (n_pairs + kXcd - 1) / kXcd;
   const int blocks = rounds * kXcd * G * a.splits;
   k_decode_partial<T, D><<<blocks, 256, 0, st>>>(a, static_cast<const T *>(q), static_cast<const T *>(kc),
-                                                static_cast<const T *>(vc), kept_ptr, kept_idx, part_o, part_ml);
-  k_decode_merge<T, D><<<a.B * a.Hq, D, 0, st>>>(a, part_o, part_ml, static_cast<T *>(out), lse);
+                                                static_cast<const T *>(vc), kept_ptr, kept_idx, part_o, part_ml,
+                                                static_cast<T *>(out), lse);
+  if (a.splits > 1) k_decode_merge<T, D><<<a.B * a.Hq, D, 0, st>>>(a, part_o, part_ml, static_cast<T *>(out), lse);
 }
 
 }  // namespace

@@ -176,21 +176,48 @@ __global__ void k_pattern_flags(const int *__restrict__ diag_cnt, const int *__r
 
 // Flags -> bitsets. cbits bit c = column c matched. rrev bit q = diagonal (pw*64 - 1 - q) matched,
 // i.e. the diagonal set reversed, so that the 64 offsets i-j, i-j-1, ... of one mask word are 64
-// consecutive ascending bits.
-__global__ void k_pattern_bitsets(const uint8_t *__restrict__ diag_flag,
-                                  const uint8_t *__restrict__ vert_flag, int P, int pw,
-                                  uint64_t *__restrict__ cbits, uint64_t *__restrict__ rrev) {
-  const int lane = threadIdx.x & 63;
-  const int w = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+// consecutive ascending bits. Four lanes build one word: each turns 16 flag bytes (one 16-byte
+// load when the row is aligned) into 16 bits.
+__device__ __forceinline__ unsigned flags16(const uint8_t *__restrict__ row, int first, int P, bool aligned) {
+  unsigned bits = 0;
+  if (aligned && first + 16 <= P) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(row + first);
+    const unsigned x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      // per byte: non-zero -> 1, then gather the four 0/1 bytes into four adjacent bits
+      const unsigned nz = ((((x[k] & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x[k]) & 0x80808080u) >> 7;
+      bits |= (((nz * 0x00204081u) >> 21) & 0xFu) << (4 * k);
+    }
+  } else {
+    for (int k = 0; k < 16; ++k)
+      if (first + k < P && row[first + k] != 0) bits |= 1u << k;
+  }
+  return bits;
+}
+
+__global__ __launch_bounds__(256) void k_pattern_bitsets(const uint8_t *__restrict__ diag_flag,
+                                                         const uint8_t *__restrict__ vert_flag, int P, int pw,
+                                                         uint64_t *__restrict__ cbits,
+                                                         uint64_t *__restrict__ rrev) {
+  const int part = threadIdx.x & 3;
+  const int w = blockIdx.x * 64 + (threadIdx.x >> 2);
   const int h = blockIdx.y;
-  if (w >= pw) return;
-  const int q = w * 64 + lane;
-  const int r = pw * 64 - 1 - q;
-  const uint64_t cw = __ballot(q < P && vert_flag[(int64_t)h * P + q] != 0);
-  const uint64_t rw = __ballot(r < P && diag_flag[(int64_t)h * P + r] != 0);
-  if (lane == 0) {
+  const bool live = w < pw;
+  const uint8_t *drow = diag_flag + (int64_t)h * P, *vrow = vert_flag + (int64_t)h * P;
+  const bool d_al = (reinterpret_cast<uintptr_t>(drow) & 15) == 0, v_al = (reinterpret_cast<uintptr_t>(vrow) & 15) == 0;
+  uint64_t cw = 0, rw = 0;
+  if (live) {
+    cw = (uint64_t)flags16(vrow, w * 64 + part * 16, P, v_al) << (16 * part);
+    rw = (uint64_t)flags16(drow, (pw - 1 - w) * 64 + part * 16, P, d_al) << (16 * part);  // ascending offsets
+  }
+  cw |= __shfl_xor(cw, 1);
+  cw |= __shfl_xor(cw, 2);
+  rw |= __shfl_xor(rw, 1);
+  rw |= __shfl_xor(rw, 2);
+  if (live && part == 0) {
     cbits[(int64_t)h * pw + w] = cw;
-    rrev[(int64_t)h * pw + w] = rw;
+    rrev[(int64_t)h * pw + w] = __brevll(rw);  // bit q of the word <- offset (pw*64 - 1) - (64 w + q)
   }
 }
 
@@ -226,14 +253,78 @@ __device__ __forceinline__ uint64_t mask_word(const Geom &g, const uint64_t *__r
   return pat & causal;
 }
 
+// Any set bit among positions [lo, hi] of a bitset of nw words (positions outside it read as 0).
+__device__ __forceinline__ bool range_any(const uint64_t *__restrict__ bs, int nw, int64_t lo, int64_t hi) {
+  lo = max(lo, (int64_t)0);
+  hi = min(hi, (int64_t)nw * 64 - 1);
+  if (lo > hi) return false;
+  for (int64_t w = lo >> 6; w <= (hi >> 6); ++w) {
+    uint64_t m = bs[w];
+    if (w == (lo >> 6)) m &= ~0ull << (lo & 63);
+    if (w == (hi >> 6)) m &= ~0ull >> (63 - (hi & 63));
+    if (m) return true;
+  }
+  return false;
+}
+
+// Every bit set among positions [lo, hi] (all inside the bitset).
+__device__ __forceinline__ bool range_all(const uint64_t *__restrict__ bs, int64_t lo, int64_t hi) {
+  for (int64_t w = lo >> 6; w <= (hi >> 6); ++w) {
+    uint64_t need = ~0ull;
+    if (w == (lo >> 6)) need &= ~0ull << (lo & 63);
+    if (w == (hi >> 6)) need &= ~0ull >> (63 - (hi & 63));
+    if ((bs[w] & need) != need) return false;
+  }
+  return true;
+}
+
+// A tile strictly below the diagonal and outside the true-mask block holds only pattern entries:
+// (i, j) is kept iff column j is matched or offset i - j is. Rows [i0, i1], columns [j0, j1].
+//   any:  some column of the tile is matched, or some offset in [i0 - j1, i1 - j0] is;
+//   full: every offset of that range is matched, or every column is, or every unmatched offset u
+//         ("hole") only meets matched columns: columns [max(j0, i0 - u), min(j1, i1 - u)].
+// Both are decided by one lane from a handful of bitset words. Returns bit0 any, bit1 full.
+__device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_t *__restrict__ rr, int pw,
+                                  int i0, int i1, int j0, int j1) {
+  const int64_t Q = (int64_t)pw * 64 - 1;  // offset u sits at position Q - u of the reversed set
+  const int a = i0 - j1, b = i1 - j0;      // offsets met by the tile, 0 <= a <= b
+  const bool cols_in = j0 <= Q;            // columns past the bitset are never matched
+  const int jc1 = (int)min((int64_t)j1, Q);
+  const bool any_c = cols_in && range_any(cb, pw, j0, jc1);
+  const bool any_r = range_any(rr, pw, Q - b, Q - a);
+  if (!any_c && !any_r) return 0;
+  if (cols_in && j1 <= Q && range_all(cb, j0, j1)) return 3;
+  // holes: offsets of [a, b] that are not matched (those past the bitset are all holes)
+  bool full = true;
+  if (b > Q) {  // offsets Q+1 .. b: their entries lie in columns [max(j0, i0 - b), min(j1, i1 - (Q + 1))]
+    const int64_t lo = max((int64_t)j0, (int64_t)i0 - b), hi = min((int64_t)j1, (int64_t)i1 - (Q + 1));
+    if (lo <= hi) full = hi <= Q && range_all(cb, lo, hi);
+  }
+  const int64_t p_lo = max(Q - b, (int64_t)0), p_hi = Q - a;
+  for (int64_t w = p_lo >> 6; full && w <= (p_hi >> 6); ++w) {
+    uint64_t holes = ~rr[w];
+    if (w == (p_lo >> 6)) holes &= ~0ull << (p_lo & 63);
+    if (w == (p_hi >> 6)) holes &= ~0ull >> (63 - (p_hi & 63));
+    while (holes && full) {
+      const int64_t u = Q - (w * 64 + (__ffsll((unsigned long long)holes) - 1));
+      holes &= holes - 1;
+      const int64_t lo = max((int64_t)j0, (int64_t)i0 - u), hi = min((int64_t)j1, (int64_t)i1 - u);
+      if (lo <= hi) full = hi <= Q && range_all(cb, lo, hi);
+    }
+  }
+  return full ? 3 : 1;
+}
+
 // Pass 1 of the block index: which key tiles of query tile (h, qt) hold a kept entry / are full.
-// One wave evaluates one tile (lanes cover its tile_m x wpr words).
+// Tiles strictly below the diagonal and outside the true-mask block are decided by one lane each
+// (pattern_tile_flags); only the tiles on the diagonal or inside the true-mask block are evaluated
+// word by word by a whole wave.
 __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__restrict__ true_bits,
                                                    const uint64_t *__restrict__ cbits,
                                                    const uint64_t *__restrict__ rrev,
                                                    uint64_t *__restrict__ occ,
                                                    uint64_t *__restrict__ full, int *__restrict__ cnt) {
-  extern __shared__ uint8_t flags[];  // [nKt] bit0 occupied, bit1 full
+  extern __shared__ uint8_t flags[];  // [nKt] bit0 occupied, bit1 full, bit2 still to be evaluated
   __shared__ int total;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qt = blockIdx.x, h = blockIdx.y;
@@ -245,8 +336,21 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
   if (threadIdx.x == 0) total = 0;
   for (int kt = threadIdx.x; kt < g.nKt; kt += blockDim.x) flags[kt] = 0;
   __syncthreads();
+  const int i0 = qt * g.tile_m;
+  for (int kt = threadIdx.x; kt <= kmax; kt += blockDim.x) {
+    const int j0 = kt * g.tile_n, j1 = min(j0 + g.tile_n - 1, g.S - 1);
+    uint8_t f = 4;  // evaluate word by word
+    if (i0 >= g.L && j1 <= i0) {
+      f = (uint8_t)pattern_tile_flags(cb, rr, g.pw, i0, i_last, j0, j1);
+      // a tile cut by the end of the sequence is never full (its bits past S are zero)
+      if (j0 + g.tile_n > g.S || i0 + g.tile_m > g.S) f &= 1;
+    }
+    flags[kt] = f;
+  }
+  __syncthreads();
   const int words = g.tile_m * g.wpr;
   for (int kt = wave; kt <= kmax; kt += 4) {
+    if (!(flags[kt] & 4)) continue;
     bool any = false, all = true;
     for (int w = lane; w < words; w += 64) {
       const uint64_t m = mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + w % g.wpr);
@@ -340,35 +444,46 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int i_last = min(g.S - 1, qt * g.tile_m + g.tile_m - 1);
   const int kmax = i_last / g.tile_n;
   const int words = g.tile_m * g.wpr;
-  for (int kt = wave; kt <= kmax; kt += 4) {
-    const uint64_t ow = oc[kt >> 6];
-    if (!((ow >> (kt & 63)) & 1)) continue;
-    int rank = __popcll(ow & (((uint64_t)1 << (kt & 63)) - 1));
-    for (int w = 0; w < (kt >> 6); ++w) rank += __popcll(oc[w]);
-    const int64_t t = first + rank;
-    if (t >= capacity) continue;
-    // element words, and which key quarters of the tile hold a kept entry
-    const int qw = g.tile_n / 4;  // quarter width in keys, a multiple of 16
-    int quarters = 0;
-    for (int w = lane; w < words; w += 64) {
-      const int wi = w % g.wpr;
-      const uint64_t m = mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + wi);
-      if (tile_bits) tile_bits[t * words + w] = m;
-      for (int q = 0; q < 4; ++q) {
-        // bits of this word that fall into quarter q: keys [q qw, (q + 1) qw) minus the word base
-        const int lo = max(q * qw - wi * 64, 0), hi = min((q + 1) * qw - wi * 64, 64);
-        if (hi > lo) {
-          const uint64_t span = (hi - lo == 64 ? ~0ull : ((1ull << (hi - lo)) - 1)) << lo;
-          if (m & span) quarters |= 1 << q;
+  const int qw = g.tile_n / 4;  // quarter width in keys, a multiple of 16
+  // walk the listed tiles of this query tile in ascending order; wave w takes every fourth one
+  int rank = 0;
+  for (int ow_i = 0; ow_i <= (kmax >> 6); ++ow_i) {
+    uint64_t ow = oc[ow_i];
+    while (ow) {
+      const int kt = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
+      ow &= ow - 1;
+      const int64_t t = first + rank;
+      const bool mine = (rank & 3) == wave;
+      ++rank;
+      if (!mine || t >= capacity) continue;
+      // element words, and which key quarters of the tile hold a kept entry
+      const bool is_full = (fl[kt >> 6] >> (kt & 63)) & 1;
+      int quarters = 0;
+      for (int w = lane; w < words; w += 64) {
+        const int wi = w % g.wpr;
+        const uint64_t m = is_full ? ~0ull : mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + wi);
+        if (tile_bits) tile_bits[t * words + w] = m;
+        if (qw == 32) {  // 128-key tiles: a quarter is half a word
+          if ((uint32_t)m) quarters |= 1 << (2 * wi);
+          if (m >> 32) quarters |= 2 << (2 * wi);
+        } else {
+          for (int q = 0; q < 4; ++q) {
+            // bits of this word that fall into quarter q: keys [q qw, (q + 1) qw) minus the word base
+            const int lo = max(q * qw - wi * 64, 0), hi = min((q + 1) * qw - wi * 64, 64);
+            if (hi > lo) {
+              const uint64_t span = (hi - lo == 64 ? ~0ull : ((1ull << (hi - lo)) - 1)) << lo;
+              if (m & span) quarters |= 1 << q;
+            }
+          }
         }
       }
-    }
-    int kind = (int)((fl[kt >> 6] >> (kt & 63)) & 1);
-    for (int q = 0; q < 4; ++q)
-      if (__ballot(quarters & (1 << q))) kind |= 2 << q;
-    if (lane == 0) {
-      if (blk_col) blk_col[t] = kt;
-      if (blk_kind) blk_kind[t] = (uint8_t)kind;
+      int kind = is_full ? 1 : 0;
+      for (int q = 0; q < 4; ++q)
+        if (__ballot(quarters & (1 << q))) kind |= 2 << q;
+      if (lane == 0) {
+        if (blk_col) blk_col[t] = kt;
+        if (blk_kind) blk_kind[t] = (uint8_t)kind;
+      }
     }
   }
 }
@@ -585,7 +700,7 @@ extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, c
   const bool want_blocks = o->blk_row_ptr != nullptr;
   const bool want_lists = o->kept_ptr != nullptr;
   if (want_blocks || want_lists || o->dense_bits) {
-    k_pattern_bitsets<<<dim3((g.pw + 3) / 4, g.H), 256, 0, stream>>>(dflag, vflag, g.P, g.pw, w.cbits, w.rrev);
+    k_pattern_bitsets<<<dim3((g.pw + 63) / 64, g.H), 256, 0, stream>>>(dflag, vflag, g.P, g.pw, w.cbits, w.rrev);
   }
   // a4 + a5: tile occupancy, CSR offsets, tile bits
   if (want_blocks) {

@@ -144,6 +144,34 @@ def test_from_patterns_with_and_without_true_mask():
         check_against_oracle(art, S, 128, 128, mask, rows=(S - 5, S))
 
 
+@pytest.mark.parametrize("tm,tn", [(64, 64), (128, 128), (64, 128), (128, 64)])
+def test_full_and_nearly_full_tiles_from_pattern_mixtures(tm, tn):
+    """Tiles that are full only through the union of diagonals and columns (every unmatched offset of
+    the tile meets matched columns only), next to tiles that miss fullness by a single entry."""
+    rng = np.random.default_rng(24)
+    H, S = 6, 900
+    d = np.zeros((H, S), np.uint8)
+    v = np.zeros((H, S), np.uint8)
+    for h in range(H):
+        d[h] = rng.random(S) < (0.9 + 0.02 * h)
+        v[h] = rng.random(S) < (0.9 + 0.02 * h)
+    d[0] = 1
+    d[0, 300] = 0                      # one hole: tiles meeting offset 300 are full only where v covers it
+    v[0] = 0
+    v[0, 100:164] = 1
+    d[1] = 0
+    v[1] = 1
+    v[1, 77] = 0                       # all columns but one
+    d[2, :] = 1
+    v[2, :] = 0                        # dense causal
+    art = oracle.from_patterns(d, v)
+    mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=H, L=0, S=S, tile_m=tm, tile_n=tn, diag_in=torch.from_numpy(d).cuda(),
+                        vert_in=torch.from_numpy(v).cuda(), dense=True)
+    torch.cuda.synchronize()
+    check_against_oracle(art, S, tm, tn, mask)
+    assert int((mask.blk_kind & 1).sum().item()) > 20
+
+
 def test_capacity_overflow_reports_total_and_writes_nothing_past_it():
     rng = np.random.default_rng(23)
     H, S = 2, 640
