@@ -28,9 +28,6 @@
 
 #include "dam_internal.h"
 
-
-
-#define DAM_TMP_SLEEP 0
 namespace {
 using namespace dam;
 
@@ -335,13 +332,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int G = a.Hq / a.Hkv, n_pairs = a.B * a.Hkv, per_pair = G * a.nQt;
   const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);  // XCC_ID, 4 bits
   int hop = 0;
-  if (a.tile_n > 128000) {}  // placeholder
-  {
-    const int slot = __builtin_amdgcn_s_getreg((3 << 11) | 4) & 15;  // HW_ID.WAVE_ID
-    if (slot & 1) {
-      for (int x = 0; x < DAM_TMP_SLEEP; ++x) __builtin_amdgcn_s_sleep(8);
-    }
-  }
   while (true) {
   __syncthreads();  // previous item: every wave is done with the LDS ring and with s_item
   if (tid == 0) {
