@@ -162,6 +162,14 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char *lds, int byte)
       (__attribute__((address_space(3))) s16x4 *)(const_cast<unsigned char *>(lds + byte)));
 }
 
+// blk_kind[t] for a wave-uniform t, fetched as part of its aligned 32-bit word so that it is a
+// scalar load: a byte load would go through the vector memory path and waiting for it would also
+// wait for every load-to-LDS copy in flight. (Device allocations are 4-byte granular.)
+__device__ __forceinline__ int kind_of(const uint8_t *__restrict__ blk_kind, int t) {
+  const unsigned word = reinterpret_cast<const unsigned *>(blk_kind)[t >> 2];
+  return (int)((word >> (8 * (t & 3))) & 0xFFu);
+}
+
 // One pipeline stage = one occupied half (64 keys) of a listed tile.
 struct Stage {
   int t, half;
@@ -392,7 +400,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // next occupied half at or after (t, half)
   auto seek = [&](Stage s) {
     while (s.t < t1) {
-      const int quarters = __builtin_amdgcn_readfirstlane((int)blk_kind[s.t]) >> 1;
+      const int quarters = kind_of(blk_kind, s.t) >> 1;
       if (s.half == 0 && (quarters & 3)) break;
       if (s.half <= 1 && (quarters & 12)) {
         s.half = 1;
@@ -443,7 +451,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
   auto load_bits = [&](Stage s) {
     u32x2 r = {~0u, ~0u};
-    if (!(__builtin_amdgcn_readfirstlane((int)blk_kind[s.t]) & 1))
+    if (!(kind_of(blk_kind, s.t) & 1))
       r = *reinterpret_cast<const u32x2 *>(tile_bits + ((int64_t)s.t * kBM + qrow_l) * 2 + s.half);
     return r;
   };
@@ -464,7 +472,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         bits_next = load_bits(nxt);
       }
       {
-        const int kind = __builtin_amdgcn_readfirstlane((int)blk_kind[cur.t]);
+        const int kind = kind_of(blk_kind, cur.t);
         const bool full = kind & 1;
         const int quarters = (kind >> (1 + 2 * cur.half)) & 3;
         const bool act0 = (quarters & 1) && __ballot(bits[0] != 0u);
