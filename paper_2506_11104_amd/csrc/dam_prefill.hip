@@ -25,6 +25,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "dam_internal.h"
 
@@ -329,8 +330,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // every `it` and one offset per tensor serves all four instructions
   const int sub = lane >> 4, pos = lane & 15;
   const int row0 = wave * 4 + sub;
-  const unsigned koff = (unsigned)(row0 * (int)a.k_ss * 2 + ((pos ^ (row0 & 15)) << 4));
-  const unsigned voff = (unsigned)(row0 * (int)a.v_ss * 2 + ((pos ^ (sub << 2)) << 4));
+  const unsigned kss2 = (unsigned)a.k_ss * 2u, vss2 = (unsigned)a.v_ss * 2u;  // row strides in bytes
+  const unsigned koff = (unsigned)row0 * kss2 + ((pos ^ (row0 & 15)) << 4);
+  const unsigned voff = (unsigned)row0 * vss2 + ((pos ^ (sub << 2)) << 4);
 
   // Persistent workgroups pull (head, query tile) items from eight queues, one per XCD: queue x
   // holds the (batch, KV head) pairs with pair % 8 == x, so that the query heads sharing a KV
@@ -516,6 +518,362 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }  // next work item
 }
 
+
+// ================================================================================================
+// Block-pipelined bf16 kernel. The unit of work is a block of 32 keys (one occupied key quarter of
+// a listed tile). In iteration b a wave issues, interleaved in one instruction stream,
+//     the 8 MFMAs of S_{b+1} = K_{b+1} Q^T   (one dependent chain),
+//     the 8 MFMAs of O^T += V_{b-1}^T P_{b-1}^T (four independent accumulators),
+//     the softmax arithmetic of block b (VALU) on S_b, which finished one iteration earlier,
+// so that the matrix pipe and the vector ALU of a SIMD are busy at the same time from within one
+// wave. K and V blocks live in two LDS rings of four 8 KiB slots each, filled by load-to-LDS
+// copies issued three iterations ahead (K_{b+4} and V_{b+2} in iteration b); one barrier per
+// iteration. The stream is padded with "dummy" blocks (mask bits all zero, so S = -inf and P = 0)
+// at both ends, which keeps every iteration identical.
+constexpr int kBlkKeys = 32;
+constexpr int kBlkBytes = kBlkKeys * 256;
+constexpr int kRing = 4;
+constexpr int kVRing = kRing * kBlkBytes;  // byte offset of the V ring; K ring at 0
+constexpr int kBitsRing = 2 * kRing * kBlkBytes;  // mask words: 4 slots x 4 waves x 64 lanes x 4 B
+constexpr int kPipeLds = kBitsRing + kRing * 1024;
+
+// Load-to-LDS copies as inline assembly: lane L of the wave writes `bytes` bytes to LDS address
+// m0 + L * bytes. Written as assembly so that the compiler neither tracks them (it would make every
+// later LDS read wait for all copies in flight) nor counts them: the kernel waits for them itself
+// with explicit s_waitcnt vmcnt(n), and issues no other vector-memory loads inside the pipeline.
+__device__ __forceinline__ void lds_copy16(unsigned lds_addr, const void *gbase, unsigned voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(gbase)
+               : "memory");
+}
+__device__ __forceinline__ void lds_copy4(unsigned lds_addr, const void *gbase, unsigned voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :
+               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(gbase)
+               : "memory");
+}
+
+struct Blk {
+  int key0;   // first key of the block
+  int tq;     // 4 * listed tile + key quarter: row 0's mask word for the block is at byte (tq >> 2) * 2048 + 4 * (tq & 3)
+  int flags;  // bit 0: tile is full (no mask), bit 1: dummy
+};
+
+template <int PH>
+__device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds, const bf16x8 (&qf)[8],
+                                          f32x16 (&oacc)[4], const f32x16 &sA, f32x16 &sB,
+                                          const unsigned (&pPrev)[8], unsigned (&pCur)[8], float &m_run,
+                                          float &l_run, int flags_next, int bits_addr, float c2, int kbase,
+                                          int vbase, int hf) {
+  // kbase ^ (c << 5) is this lane's address of chunk pair c of its K row, vbase ^ (db << 6) that of
+  // dim block db in its V rows (the chunk permutations are XORs, see the layout note)
+  int kaddr[8], vaddr[4];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) kaddr[c] = kbase ^ (c << 5);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) vaddr[db] = vbase ^ (db << 6);
+  constexpr int KS = PH * kBlkBytes;                          // slot of K_{b+1}
+  constexpr int VS = kVRing + ((PH + 2) & 3) * kBlkBytes;     // slot of V_{b-1}
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  // accumulator e is key 8 (e / 4) + 4 hf + e % 4 of the block: it starts at 0 (kept) or -inf (masked).
+  // A full tile needs no mask words (wave-uniform branch).
+  if (flags_next & 1) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sB[e] = 0.0f;
+  } else {
+    unsigned bits_next = *reinterpret_cast<const unsigned *>(lds + kBitsRing + PH * 1024 + bits_addr);
+    if (flags_next & 2) bits_next = 0u;  // dummy block: nothing kept
+    const int inv = (int)~(bits_next >> (4 * hf));
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      sB[e] = __int_as_float(__builtin_amdgcn_sbfe(inv, 8 * (e / 4) + e % 4, 1) & (int)0xFF800000);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- operand fetches, in the order the MFMAs consume them
+  bf16x8 kf[8];
+  s16x8 vf[2][4];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    kf[x] = lds_read_b128(lds, KS + kaddr[x]);
+    const int a2 = x >> 2, db = x & 3;
+    const s16x4 r0 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16) * 256);
+    const s16x4 r1 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16 + 8) * 256);
+    vf[a2][db] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+  // ---- matrix work: S_{b+1} chain and P_{b-1} V_{b-1}, alternating
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], sB, 0, 0, 0);
+    const int a2 = x >> 2, db = x & 3;
+    const u32x4 praw = {pPrev[4 * a2], pPrev[4 * a2 + 1], pPrev[4 * a2 + 2], pPrev[4 * a2 + 3]};
+    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[a2][db]),
+                                                       __builtin_bit_cast(bf16x8, praw), oacc[db], 0, 0, 0);
+  }
+  // ---- vector work: online softmax of block b; one query per lane pair (lane, lane ^ 32)
+  float mx = fmaxf(fmaxf(sA[0], sA[1]), sA[2]);
+#pragma unroll
+  for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(sA[e], sA[e + 1]), mx);
+  mx = fmaxf(mx, sA[15]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m_run, mx);
+  const float m_ref = m_new == -INFINITY ? 0.0f : m_new;
+  const float corr = __builtin_amdgcn_exp2f((m_run - m_ref) * c2);
+  const float off = m_ref * c2;
+  m_run = m_new;
+  float psum = 0.0f;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+  for (int e = 0; e < 16; e += 2) {
+    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sA[e], c2, -off));
+    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sA[e + 1], c2, -off));
+    pCur[e / 2] = pack_bf16(p0, p1);
+    // the row sum is taken over the rounded weights the P V product uses
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pCur[e / 2]), ones, psum, false);
+  }
+  l_run = l_run * corr + psum;
+  // keep the weights of block b inside this block of code (they are only consumed an iteration later
+  // and would otherwise be sunk below the matrix work)
+#pragma unroll
+  for (int e = 0; e < 8; ++e) asm volatile("" ::"v"(pCur[e]));
+  // ---- interleave: a few operand reads ahead, then per MFMA pair three reads and eight VALU ops
+  __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 3, 0);
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 1, 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // O was accumulated against the old maximum: rescale once P_{b-1} V_{b-1} is in (rarely needed
+  // after the first few blocks of a row)
+  if (__ballot(corr != 1.0f)) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[db][e] *= corr;
+  }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16_pipe(
+    AttnArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ k,
+    const __hip_bfloat16 *__restrict__ v, const int *__restrict__ row_ptr, const int *__restrict__ blk_col,
+    const uint8_t *__restrict__ blk_kind, const uint64_t *__restrict__ tile_bits, __hip_bfloat16 *__restrict__ out,
+    float *__restrict__ lse, int *__restrict__ queue_next) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+  __shared__ int s_item[2];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, hf = lane >> 5;
+  const float c2 = a.scale * 1.4426950408889634f;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds;
+
+  // LDS byte offsets of this lane's operand fragments inside a block (layout note above), chunk pair 0
+  // and dim block 0; the others differ by an XOR
+  const int kbase = n * 256 + ((hf ^ (n & 15)) << 4);
+  const int vbase = (4 * hf + ((n & 15) >> 2)) * 256 + (((n & 15) >> 2) << 6) + 32 * (n >> 4) + 8 * (n & 3);
+  // load-to-LDS copies of a block: instruction `it` (0, 1) of wave w fills rows 16 it + 4 w .. + 3; a
+  // lane's byte offset from the block's first row is constant
+  const int sub = lane >> 4, pos = lane & 15;
+  const int row0 = wave * 4 + sub;
+  const unsigned kss2 = (unsigned)a.k_ss * 2u, vss2 = (unsigned)a.v_ss * 2u;  // row strides in bytes
+  const unsigned koff = (unsigned)row0 * kss2 + ((pos ^ (row0 & 15)) << 4);
+  const unsigned voff = (unsigned)row0 * vss2 + ((pos ^ (sub << 2)) << 4);
+  const unsigned boff = (unsigned)((wave * 32 + n) * 16);  // this lane's row in a tile's mask words
+  const int bits_addr = wave * 256 + lane * 4;             // where its copy lands inside a bits slot
+
+  const int G = a.Hq / a.Hkv, n_pairs = a.B * a.Hkv, per_pair = G * a.nQt;
+  const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);  // XCC_ID, 4 bits
+  int hop = 0;
+  while (true) {
+    __syncthreads();  // previous item: every wave is done with the LDS rings and with s_item
+    if (tid == 0) {
+      int item = -1, queue = 0;
+      for (; hop < kXcd; ++hop) {
+        queue = (my_xcd + hop) & (kXcd - 1);
+        const int pairs_here = (n_pairs - queue + kXcd - 1) / kXcd;  // pairs p with p % 8 == queue
+        const int got = atomicAdd(&queue_next[queue], 1);
+        if (got < pairs_here * per_pair) {
+          item = got;
+          break;
+        }
+      }
+      s_item[0] = item;
+      s_item[1] = queue;
+    }
+    __syncthreads();
+    const int item = __builtin_amdgcn_readfirstlane(s_item[0]), queue = __builtin_amdgcn_readfirstlane(s_item[1]);
+    if (item < 0) break;
+    const int pair = (item / per_pair) * kXcd + queue, within = item % per_pair;
+    const int wb = pair / a.Hkv, whkv = pair % a.Hkv;
+    const int wqt = a.nQt - 1 - within / G, whq = whkv * G + within % G;
+    const int t0 = __builtin_amdgcn_readfirstlane(row_ptr[(int64_t)whq * (a.nQt + 1) + wqt]);
+    const int t1 = __builtin_amdgcn_readfirstlane(row_ptr[(int64_t)whq * (a.nQt + 1) + wqt + 1]);
+    const int qrow_l = wave * 32 + n;  // this lane's query row inside the tile
+    const int qrow = wqt * kBM + qrow_l;
+    const bool qlive = qrow < a.S;
+    const unsigned char *kg = reinterpret_cast<const unsigned char *>(k + wb * a.k_sb + whkv * a.k_sh);
+    const unsigned char *vg = reinterpret_cast<const unsigned char *>(v + wb * a.v_sb + whkv * a.v_sh);
+
+    // ---- the stream of occupied 32-key blocks of this query tile (wave-uniform cursor). `quarters`
+    // holds the not yet visited occupied quarters of tile cur_t; the metadata of tile cur_t + 1 is
+    // fetched ahead (scalar loads, issued by prefetch_meta() just before an iteration's barrier so that
+    // their latency falls into the barrier wait and no LDS wait in the pipeline has to cover them).
+    int cur_t = t0 - 1, quarters = 0, cur_full = 0, cur_col = 0, last_key0 = 0, last_tq = 0;
+    int pre_kind = 0, pre_col = 0;
+    auto prefetch_meta = [&]() {
+      if (quarters == 0 && cur_t + 1 < t1) {
+        pre_kind = kind_of(blk_kind, cur_t + 1);
+        pre_col = blk_col[cur_t + 1];
+      }
+    };
+    auto next_blk = [&]() {
+      if (quarters == 0) {
+        if (cur_t + 1 >= t1) return Blk{last_key0, last_tq, 2};
+        ++cur_t;
+        quarters = __builtin_amdgcn_readfirstlane((pre_kind >> 1) & 15);  // never 0 for a listed tile
+        cur_full = __builtin_amdgcn_readfirstlane(pre_kind & 1);
+        cur_col = __builtin_amdgcn_readfirstlane(pre_col);
+      }
+      const int qq = __builtin_ctz(quarters);
+      quarters &= quarters - 1;
+      last_key0 = cur_col * kBN + kBlkKeys * qq;
+      last_tq = 4 * cur_t + qq;
+      return Blk{last_key0, last_tq, cur_full};
+    };
+    // K or V block -> ring slot: two 1 KiB copies per wave. A block that reaches past the sequence end
+    // redirects such keys (masked anyway) to the last row, which keeps the slot finite.
+    auto copy_blk = [&](const unsigned char *g, unsigned stride2, unsigned off, int chunk_xor, int key0, unsigned dst) {
+      if (key0 + kBlkKeys <= a.S) {
+        // 32 x 32 -> 64 bit product from its two halves (both scalar instructions)
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)key0 * stride2);
+        const unsigned hi = __builtin_amdgcn_readfirstlane(__umulhi((unsigned)key0, stride2));
+        const unsigned char *g0 = g + (((uint64_t)hi << 32) | lo);
+        lds_copy16(dst + wave * 1024, g0, off);
+        lds_copy16(dst + 4096 + wave * 1024, g0 + (uint64_t)stride2 * 16, off);
+      } else {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          const int key = min(key0 + 16 * it + row0, a.S - 1);
+          lds_copy16(dst + it * 4096 + wave * 1024, g, (unsigned)key * stride2 + ((pos ^ chunk_xor) << 4));  // < 4 GiB (host check)
+        }
+      }
+    };
+    auto copy_k = [&](const Blk &d, int slot) { copy_blk(kg, kss2, koff, row0 & 15, d.key0, lds_base + slot * kBlkBytes); };
+    auto copy_v = [&](const Blk &d, int slot) {
+      copy_blk(vg, vss2, voff, sub << 2, d.key0, lds_base + kVRing + slot * kBlkBytes);
+    };
+    // the block's mask word of every row of this wave (also issued for full and dummy blocks, so that
+    // every iteration has the same number of copies in flight)
+    auto copy_bits = [&](const Blk &d, int slot) {
+      lds_copy4(lds_base + kBitsRing + slot * 1024 + wave * 256, reinterpret_cast<const unsigned char *>(tile_bits) + ((int64_t)(d.tq >> 2) * (kBM * 16) + 4 * (d.tq & 3)),
+                boff);
+    };
+
+    prefetch_meta();
+    Blk d0 = next_blk();
+    f32x16 oacc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;  // running max (raw logits) and this lane's part of the row sum
+
+    if (!(d0.flags & 2)) {
+      // Q fragments: B operand of S^T = K Q^T. Chunk c covers dims 16c .. 16c+15; this lane holds dims
+      // 16c + 8 hf .. + 7 of its query row.
+      bf16x8 qf[8];
+      {
+        const __hip_bfloat16 *qp = q + wb * a.q_sb + whq * a.q_sh + (int64_t)qrow * a.q_ss + 8 * hf;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          u32x4 raw = {0u, 0u, 0u, 0u};
+          if (qlive) raw = *reinterpret_cast<const u32x4 *>(qp + 16 * c);
+          qf[c] = __builtin_bit_cast(bf16x8, raw);
+        }
+      }
+      prefetch_meta();
+      Blk d1 = next_blk();
+      prefetch_meta();
+      Blk d2 = next_blk();
+      prefetch_meta();
+      copy_k(d0, 0);
+      copy_bits(d0, 0);
+      copy_k(d1, 1);
+      copy_bits(d1, 1);
+      copy_k(d2, 2);
+      copy_bits(d2, 2);
+      copy_v(d0, 0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      // the Q fragments have arrived with that wait; passing them through an empty statement tells the
+      // compiler so (it cannot see the wait, and would otherwise wait for every copy in flight at the
+      // first use of a fragment in each iteration)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) asm volatile("" : "+v"(qf[c]));
+      __syncthreads();
+      // S_b lives in sbuf[PH & 1] and S_{b+1} is written to the other one; P_b goes to pbuf[PH & 1] and
+      // P_{b-1} is read from the other one, so nothing is copied between iterations
+      f32x16 sbuf[2];
+      unsigned pbuf[2][8];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sbuf[0][e] = -INFINITY;  // block -1 is a dummy
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pbuf[1][e] = 0u;
+      int flag_cur = 0;   // flags of block b; the leading dummy must not end the loop
+      // iteration b with (b + 1) % 4 == PH; d0..d2 describe blocks b+1..b+3; returns true when done
+      auto step = [&](auto ph) {
+        constexpr int PH = decltype(ph)::value;
+        const Blk d3 = next_blk();          // block b+4
+        copy_k(d3, (PH + 3) & 3);           // five copies per wave and iteration, always
+        copy_bits(d3, (PH + 3) & 3);
+        copy_v(d1, (PH + 1) & 3);
+        pipe_iter<PH>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], m_run,
+                      l_run, d0.flags, bits_addr, c2, kbase, vbase, hf);
+        if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
+        prefetch_meta();
+        // K_{b+2}, its mask words and V_b (issued two iterations ago) must have landed; the ten
+        // youngest copies (this iteration's and the previous one's) may stay in flight
+        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        __syncthreads();
+        flag_cur = d0.flags;
+        d0 = d1;
+        d1 = d2;
+        d2 = d3;
+        return false;
+      };
+      while (true) {
+        if (step(std::integral_constant<int, 0>{})) break;
+        if (step(std::integral_constant<int, 1>{})) break;
+        if (step(std::integral_constant<int, 2>{})) break;
+        if (step(std::integral_constant<int, 3>{})) break;
+      }
+    }
+
+    // finish: total sum over both half-waves, normalise, store. Accumulator e of block db is dim
+    // 32 db + 8 (e / 4) + 4 hf + e % 4 of this lane's query.
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    if (qlive) {
+      __hip_bfloat16 *op = out + wb * a.o_sb + whq * a.o_sh + (int64_t)qrow * a.o_ss;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 pr;
+          pr.x = pack_bf16(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
+          pr.y = pack_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
+          *reinterpret_cast<uint2 *>(op + 32 * db + 8 * g + 4 * hf) = pr;
+        }
+      if (lse && hf == 0)
+        lse[((int64_t)wb * a.Hq + whq) * a.S + qrow] =
+            l_tot > 0.0f ? (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+    }
+  }  // next work item
+}
+
 __global__ void k_zero_queues(int *queue_next) {
   if (threadIdx.x < kXcd) queue_next[threadIdx.x] = 0;
 }
@@ -534,6 +892,9 @@ int validate(const dam_attn_params *p, const void *q, const void *k, const void 
       if (s[x] < 0 || s[x] % align) return DAM_ERR_INVALID_ARG;
   if (p->dtype == DAM_BF16) {
     if (p->head_dim != 128 || p->tile_m != 128 || p->tile_n != 128) return DAM_ERR_UNSUPPORTED;
+    // the bf16 kernel addresses the rows of one K or V head with 32-bit byte offsets
+    if ((int64_t)p->seq * p->k_stride[2] * 2 >= (int64_t(1) << 32) || (int64_t)p->seq * p->v_stride[2] * 2 >= (int64_t(1) << 32))
+      return DAM_ERR_UNSUPPORTED;
   } else if (p->dtype == DAM_F32) {
     if (p->head_dim != 64 && p->head_dim != 128) return DAM_ERR_UNSUPPORTED;
     if (p->tile_m > 128 || p->tile_n > 128) return DAM_ERR_UNSUPPORTED;
@@ -600,6 +961,15 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   int *queue_next = static_cast<int *>(ws);
   k_zero_queues<<<1, 64, 0, st>>>(queue_next);
   const int persistent = std::min(blocks, 2 * n_cu);  // two workgroups fit a CU (registers and LDS)
+#ifndef DAM_PREFILL_STAGED
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_prefill_bf16_pipe), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kPipeLds) != hipSuccess)
+    return DAM_ERR_DEVICE;
+  k_prefill_bf16_pipe<<<persistent, 256, kPipeLds, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
+                                                      (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col, mk->blk_kind,
+                                                      mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next);
+  return launch_status();
+#endif
   k_prefill_bf16<<<persistent, 256, kLdsBytes, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
                                                 (const __hip_bfloat16 *)v,
                                                    mk->blk_row_ptr, mk->blk_col, mk->blk_kind, mk->tile_bits,
