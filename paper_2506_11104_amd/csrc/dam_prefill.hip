@@ -26,6 +26,7 @@
 
 #include <algorithm>
 #include <type_traits>
+#include <utility>
 
 #include "dam_internal.h"
 
@@ -537,28 +538,45 @@ constexpr int kVRing = kRing * kBlkBytes;  // byte offset of the V ring; K ring 
 constexpr int kBitsRing = 2 * kRing * kBlkBytes;  // mask words: 4 slots x 4 waves x 64 lanes x 4 B
 constexpr int kPipeLds = kBitsRing + kRing * 1024;
 
-// Load-to-LDS copies as inline assembly: lane L of the wave writes `bytes` bytes to LDS address
-// m0 + L * bytes. Written as assembly so that the compiler neither tracks them (it would make every
-// later LDS read wait for all copies in flight) nor counts them: the kernel waits for them itself
-// with explicit s_waitcnt vmcnt(n), and issues no other vector-memory loads inside the pipeline.
-__device__ __forceinline__ void lds_copy16(unsigned lds_addr, const void *gbase, unsigned voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+// Load-to-LDS copies as inline assembly: lane L of the wave fetches `bytes` bytes from gbase + voff
+// and writes them to LDS address m0 + L * bytes, m0 = lds_at + IMM. Written as assembly so that the
+// compiler neither tracks them (it would make every later LDS read wait for all copies in flight) nor
+// counts them: the kernel waits for them itself with explicit s_waitcnt vmcnt(n), and issues no other
+// vector-memory loads inside the pipeline. gbase and lds_at are wave-uniform.
+template <int IMM>
+__device__ __forceinline__ void lds_copy16(unsigned lds_at, const void *gbase, unsigned voff) {
+  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
                :
-               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(gbase)
-               : "memory");
+               : "s"(lds_at), "n"(IMM), "v"(voff), "s"(gbase)
+               : "memory", "scc");
 }
-__device__ __forceinline__ void lds_copy4(unsigned lds_addr, const void *gbase, unsigned voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+template <int IMM>
+__device__ __forceinline__ void lds_copy4(unsigned lds_at, const void *gbase, unsigned voff) {
+  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3"
                :
-               : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(gbase)
-               : "memory");
+               : "s"(lds_at), "n"(IMM), "v"(voff), "s"(gbase)
+               : "memory", "scc");
 }
 
 struct Blk {
-  int key0;   // first key of the block
-  int tq;     // 4 * listed tile + key quarter: row 0's mask word for the block is at byte (tq >> 2) * 2048 + 4 * (tq & 3)
-  int flags;  // bit 0: tile is full (no mask), bit 1: dummy
+  int key0;        // first key of the block
+  unsigned k_off;  // byte offset of that key's row from the head's first K row, and
+  unsigned v_off;  //   from its first V row
+  int bits_off;    // byte offset of row 0's mask word for the block from the tile row's first mask word
+  int flags;       // bit 0: tile is full (no mask), bit 1: dummy
 };
+
+// 0 or -inf for bit POS of `inv` clear or set
+template <int POS>
+__device__ __forceinline__ float neg_inf_if_bit(int inv) {
+  int field;
+  asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(field) : "v"(inv), "n"(POS));
+  return __int_as_float(field & (int)0xFF800000);
+}
+template <int... E>
+__device__ __forceinline__ void mask_init(f32x16 &s, int inv, std::integer_sequence<int, E...>) {
+  ((s[E] = neg_inf_if_bit<8 * (E / 4) + E % 4>(inv)), ...);
+}
 
 template <int PH>
 __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds, const bf16x8 (&qf)[8],
@@ -585,9 +603,9 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
     unsigned bits_next = *reinterpret_cast<const unsigned *>(lds + kBitsRing + PH * 1024 + bits_addr);
     if (flags_next & 2) bits_next = 0u;  // dummy block: nothing kept
     const int inv = (int)~(bits_next >> (4 * hf));
-#pragma unroll
-    for (int e = 0; e < 16; ++e)
-      sB[e] = __int_as_float(__builtin_amdgcn_sbfe(inv, 8 * (e / 4) + e % 4, 1) & (int)0xFF800000);
+    // sign-extended one-bit field (0 or all ones), then the bits of -inf; the extract is written as an
+    // instruction because the compiler turns the builtin into a three-operation compare and select
+    mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
   }
   __builtin_amdgcn_sched_barrier(0);
   // ---- operand fetches, in the order the MFMAs consume them
@@ -658,6 +676,9 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   }
 }
 
+// RAGGED: the sequence length is not a multiple of the block size, so the last block of a row of tiles
+// may reach past the end of K and V.
+template <bool RAGGED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16_pipe(
     AttnArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ k,
     const __hip_bfloat16 *__restrict__ v, const int *__restrict__ row_ptr, const int *__restrict__ blk_col,
@@ -684,6 +705,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const unsigned voff = (unsigned)row0 * vss2 + ((pos ^ (sub << 2)) << 4);
   const unsigned boff = (unsigned)((wave * 32 + n) * 16);  // this lane's row in a tile's mask words
   const int bits_addr = wave * 256 + lane * 4;             // where its copy lands inside a bits slot
+  const unsigned lds_kv = __builtin_amdgcn_readfirstlane(lds_base + wave * 1024);              // this wave's part of a K/V slot
+  const unsigned lds_bits = __builtin_amdgcn_readfirstlane(lds_base + kBitsRing + wave * 256);  // ... of a bits slot
 
   const int G = a.Hq / a.Hkv, n_pairs = a.B * a.Hkv, per_pair = G * a.nQt;
   const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);  // XCC_ID, 4 bits
@@ -722,7 +745,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // holds the not yet visited occupied quarters of tile cur_t; the metadata of tile cur_t + 1 is
     // fetched ahead (scalar loads, issued by prefetch_meta() just before an iteration's barrier so that
     // their latency falls into the barrier wait and no LDS wait in the pipeline has to cover them).
-    int cur_t = t0 - 1, quarters = 0, cur_full = 0, cur_col = 0, last_key0 = 0, last_tq = 0;
+    int cur_t = t0 - 1, quarters = 0, cur_full = 0, cur_col = 0;
+    Blk last = {0, 0u, 0u, 0, 2};
     int pre_kind = 0, pre_col = 0;
     auto prefetch_meta = [&]() {
       if (quarters == 0 && cur_t + 1 < t1) {
@@ -732,7 +756,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
     auto next_blk = [&]() {
       if (quarters == 0) {
-        if (cur_t + 1 >= t1) return Blk{last_key0, last_tq, 2};
+        if (cur_t + 1 >= t1) return Blk{last.key0, last.k_off, last.v_off, last.bits_off, 2};
         ++cur_t;
         quarters = __builtin_amdgcn_readfirstlane((pre_kind >> 1) & 15);  // never 0 for a listed tile
         cur_full = __builtin_amdgcn_readfirstlane(pre_kind & 1);
@@ -740,41 +764,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
       const int qq = __builtin_ctz(quarters);
       quarters &= quarters - 1;
-      last_key0 = cur_col * kBN + kBlkKeys * qq;
-      last_tq = 4 * cur_t + qq;
-      return Blk{last_key0, last_tq, cur_full};
+      const int key0 = cur_col * kBN + kBlkKeys * qq;
+      last = Blk{key0, (unsigned)key0 * kss2, (unsigned)key0 * vss2, (cur_t - t0) * (kBM * 16) + 4 * qq, cur_full};
+      return last;
     };
-    // K or V block -> ring slot: two 1 KiB copies per wave. A block that reaches past the sequence end
-    // redirects such keys (masked anyway) to the last row, which keeps the slot finite.
-    auto copy_blk = [&](const unsigned char *g, unsigned stride2, unsigned off, int chunk_xor, int key0, unsigned dst) {
-      if (key0 + kBlkKeys <= a.S) {
-        // 32 x 32 -> 64 bit product from its two halves (both scalar instructions)
-        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)key0 * stride2);
-        const unsigned hi = __builtin_amdgcn_readfirstlane(__umulhi((unsigned)key0, stride2));
-        const unsigned char *g0 = g + (((uint64_t)hi << 32) | lo);
-        lds_copy16(dst + wave * 1024, g0, off);
-        lds_copy16(dst + 4096 + wave * 1024, g0 + (uint64_t)stride2 * 16, off);
+    // K or V block -> ring slot: two 1 KiB copies per wave; every address is the head's base plus a
+    // 32-bit byte offset (the host checks that a head's rows span less than 4 GiB). In the ragged case
+    // a block that reaches past the sequence end redirects such keys (masked anyway) to the last row,
+    // which keeps the slot finite.
+    auto copy_blk = [&](auto slot_off, const unsigned char *g, unsigned stride2, unsigned lane_off, int chunk_xor, int key0,
+                        unsigned blk_off) {
+      constexpr int SO = decltype(slot_off)::value;
+      if (!RAGGED || key0 + kBlkKeys <= a.S) {
+        const unsigned o0 = lane_off + blk_off;
+        lds_copy16<SO>(lds_kv, g, o0);
+        lds_copy16<SO + 4096>(lds_kv, g, o0 + 16u * stride2);
       } else {
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-          const int key = min(key0 + 16 * it + row0, a.S - 1);
-          lds_copy16(dst + it * 4096 + wave * 1024, g, (unsigned)key * stride2 + ((pos ^ chunk_xor) << 4));  // < 4 GiB (host check)
-        }
+        const unsigned c = (unsigned)((pos ^ chunk_xor) << 4);
+        lds_copy16<SO>(lds_kv, g, (unsigned)min(key0 + row0, a.S - 1) * stride2 + c);
+        lds_copy16<SO + 4096>(lds_kv, g, (unsigned)min(key0 + 16 + row0, a.S - 1) * stride2 + c);
       }
     };
-    auto copy_k = [&](const Blk &d, int slot) { copy_blk(kg, kss2, koff, row0 & 15, d.key0, lds_base + slot * kBlkBytes); };
-    auto copy_v = [&](const Blk &d, int slot) {
-      copy_blk(vg, vss2, voff, sub << 2, d.key0, lds_base + kVRing + slot * kBlkBytes);
+    auto copy_k = [&](const Blk &d, auto slot) {
+      copy_blk(std::integral_constant<int, decltype(slot)::value * kBlkBytes>{}, kg, kss2, koff, row0 & 15, d.key0, d.k_off);
+    };
+    auto copy_v = [&](const Blk &d, auto slot) {
+      copy_blk(std::integral_constant<int, kVRing + decltype(slot)::value * kBlkBytes>{}, vg, vss2, voff, sub << 2, d.key0, d.v_off);
     };
     // the block's mask word of every row of this wave (also issued for full and dummy blocks, so that
     // every iteration has the same number of copies in flight)
-    auto copy_bits = [&](const Blk &d, int slot) {
-      lds_copy4(lds_base + kBitsRing + slot * 1024 + wave * 256, reinterpret_cast<const unsigned char *>(tile_bits) + ((int64_t)(d.tq >> 2) * (kBM * 16) + 4 * (d.tq & 3)),
-                boff);
+    const unsigned char *bits_row = reinterpret_cast<const unsigned char *>(tile_bits) + (int64_t)t0 * (kBM * 16);
+    auto copy_bits = [&](const Blk &d, auto slot) {
+      lds_copy4<decltype(slot)::value * 1024>(lds_bits, bits_row, boff + (unsigned)d.bits_off);
     };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
 
+    // block i of the stream is described by d[i & 3]
+    Blk d[4];
     prefetch_meta();
-    Blk d0 = next_blk();
+    d[0] = next_blk();
     f32x16 oacc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -782,7 +813,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;  // running max (raw logits) and this lane's part of the row sum
 
-    if (!(d0.flags & 2)) {
+    if (!(d[0].flags & 2)) {
       // Q fragments: B operand of S^T = K Q^T. Chunk c covers dims 16c .. 16c+15; this lane holds dims
       // 16c + 8 hf .. + 7 of its query row.
       bf16x8 qf[8];
@@ -796,17 +827,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
       }
       prefetch_meta();
-      Blk d1 = next_blk();
+      d[1] = next_blk();
       prefetch_meta();
-      Blk d2 = next_blk();
+      d[2] = next_blk();
       prefetch_meta();
-      copy_k(d0, 0);
-      copy_bits(d0, 0);
-      copy_k(d1, 1);
-      copy_bits(d1, 1);
-      copy_k(d2, 2);
-      copy_bits(d2, 2);
-      copy_v(d0, 0);
+      copy_k(d[0], I0{});
+      copy_bits(d[0], I0{});
+      copy_k(d[1], I1{});
+      copy_bits(d[1], I1{});
+      copy_k(d[2], I2{});
+      copy_bits(d[2], I2{});
+      copy_v(d[0], I0{});
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       // the Q fragments have arrived with that wait; passing them through an empty statement tells the
       // compiler so (it cannot see the wait, and would otherwise wait for every copy in flight at the
@@ -822,33 +853,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int e = 0; e < 16; ++e) sbuf[0][e] = -INFINITY;  // block -1 is a dummy
 #pragma unroll
       for (int e = 0; e < 8; ++e) pbuf[1][e] = 0u;
-      int flag_cur = 0;   // flags of block b; the leading dummy must not end the loop
-      // iteration b with (b + 1) % 4 == PH; d0..d2 describe blocks b+1..b+3; returns true when done
+      d[3].flags = 0;  // stands for block -1: the leading dummy must not end the loop
+      // iteration b with (b + 1) % 4 == PH; returns true when the stream is finished
       auto step = [&](auto ph) {
         constexpr int PH = decltype(ph)::value;
-        const Blk d3 = next_blk();          // block b+4
-        copy_k(d3, (PH + 3) & 3);           // five copies per wave and iteration, always
-        copy_bits(d3, (PH + 3) & 3);
-        copy_v(d1, (PH + 1) & 3);
+        const int flag_cur = d[(PH + 3) & 3].flags;  // block b, whose descriptor is replaced now
+        d[(PH + 3) & 3] = next_blk();                // block b+4
+        copy_k(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});  // five copies per wave and iteration, always
+        copy_bits(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});
+        copy_v(d[(PH + 1) & 3], std::integral_constant<int, (PH + 1) & 3>{});  // block b+2
         pipe_iter<PH>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], m_run,
-                      l_run, d0.flags, bits_addr, c2, kbase, vbase, hf);
+                      l_run, d[PH].flags, bits_addr, c2, kbase, vbase, hf);
         if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
         prefetch_meta();
         // K_{b+2}, its mask words and V_b (issued two iterations ago) must have landed; the ten
         // youngest copies (this iteration's and the previous one's) may stay in flight
         asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
         __syncthreads();
-        flag_cur = d0.flags;
-        d0 = d1;
-        d1 = d2;
-        d2 = d3;
         return false;
       };
       while (true) {
-        if (step(std::integral_constant<int, 0>{})) break;
-        if (step(std::integral_constant<int, 1>{})) break;
-        if (step(std::integral_constant<int, 2>{})) break;
-        if (step(std::integral_constant<int, 3>{})) break;
+        if (step(I0{})) break;
+        if (step(I1{})) break;
+        if (step(I2{})) break;
+        if (step(I3{})) break;
       }
     }
 
@@ -962,12 +990,18 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   k_zero_queues<<<1, 64, 0, st>>>(queue_next);
   const int persistent = std::min(blocks, 2 * n_cu);  // two workgroups fit a CU (registers and LDS)
 #ifndef DAM_PREFILL_STAGED
-  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_prefill_bf16_pipe), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          kPipeLds) != hipSuccess)
-    return DAM_ERR_DEVICE;
-  k_prefill_bf16_pipe<<<persistent, 256, kPipeLds, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
-                                                      (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col, mk->blk_kind,
-                                                      mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next);
+  const bool ragged = p->seq % kBlkKeys != 0;
+  const void *fn = ragged ? reinterpret_cast<const void *>(k_prefill_bf16_pipe<true>)
+                          : reinterpret_cast<const void *>(k_prefill_bf16_pipe<false>);
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kPipeLds) != hipSuccess) return DAM_ERR_DEVICE;
+  if (ragged)
+    k_prefill_bf16_pipe<true><<<persistent, 256, kPipeLds, st>>>(
+        a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col,
+        mk->blk_kind, mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next);
+  else
+    k_prefill_bf16_pipe<false><<<persistent, 256, kPipeLds, st>>>(
+        a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col,
+        mk->blk_kind, mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next);
   return launch_status();
 #endif
   k_prefill_bf16<<<persistent, 256, kLdsBytes, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
