@@ -594,11 +594,13 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   constexpr int KS = PH * kBlkBytes;                          // slot of K_{b+1}
   constexpr int VS = kVRing + ((PH + 2) & 3) * kBlkBytes;     // slot of V_{b-1}
   typedef __attribute__((ext_vector_type(8))) short s16x8;
-  // accumulator e is key 8 (e / 4) + 4 hf + e % 4 of the block: it starts at 0 (kept) or -inf (masked).
-  // A full tile needs no mask words (wave-uniform branch).
+  // The first product of the S_{b+1} chain. Accumulator e is key 8 (e / 4) + 4 hf + e % 4 of the block
+  // and starts at 0 (kept) or -inf (masked); a full tile needs no mask words and starts from a literal
+  // zero (wave-uniform branch).
+  const bf16x8 kf0 = lds_read_b128(lds, KS + kaddr[0]);
   if (flags_next & 1) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) sB[e] = 0.0f;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[0], zero, 0, 0, 0);
   } else {
     unsigned bits_next = *reinterpret_cast<const unsigned *>(lds + kBitsRing + PH * 1024 + bits_addr);
     if (flags_next & 2) bits_next = 0u;  // dummy block: nothing kept
@@ -606,6 +608,7 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
     // sign-extended one-bit field (0 or all ones), then the bits of -inf; the extract is written as an
     // instruction because the compiler turns the builtin into a three-operation compare and select
     mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
+    sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[0], sB, 0, 0, 0);
   }
   __builtin_amdgcn_sched_barrier(0);
   // ---- operand fetches, in the order the MFMAs consume them
@@ -613,16 +616,16 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   s16x8 vf[2][4];
 #pragma unroll
   for (int x = 0; x < 8; ++x) {
-    kf[x] = lds_read_b128(lds, KS + kaddr[x]);
+    if (x > 0) kf[x] = lds_read_b128(lds, KS + kaddr[x]);
     const int a2 = x >> 2, db = x & 3;
     const s16x4 r0 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16) * 256);
     const s16x4 r1 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16 + 8) * 256);
     vf[a2][db] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
   }
-  // ---- matrix work: S_{b+1} chain and P_{b-1} V_{b-1}, alternating
+  // ---- matrix work: the rest of the S_{b+1} chain and P_{b-1} V_{b-1}, alternating
 #pragma unroll
   for (int x = 0; x < 8; ++x) {
-    sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], sB, 0, 0, 0);
+    if (x > 0) sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], sB, 0, 0, 0);
     const int a2 = x >> 2, db = x & 3;
     const u32x4 praw = {pPrev[4 * a2], pPrev[4 * a2 + 1], pPrev[4 * a2 + 2], pPrev[4 * a2 + 3]};
     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[a2][db]),
@@ -658,8 +661,10 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 3, 0);
 #pragma unroll
   for (int x = 0; x < 8; ++x) {
-    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+    if (x > 0) {
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+    }
     __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 2, 0);
     __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
     __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
