@@ -658,7 +658,7 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
 #pragma unroll
   for (int e = 0; e < 8; ++e) asm volatile("" ::"v"(pCur[e]));
   // ---- interleave: a few operand reads ahead, then per MFMA pair three reads and eight VALU ops
-  __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 3, 0);
+  __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 12, 0);
 #pragma unroll
   for (int x = 0; x < 8; ++x) {
     if (x > 0) {
