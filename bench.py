@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-maskmap", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain device copies of 1 GiB (a kernel of known traffic, for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
     return ap.parse_args()
 
 
@@ -154,8 +157,9 @@ def bench_cpu_oracle(args, w, ctx, wl):
         kept = sum(len(oracle.kept_list(art, int(h), int(r))) for h, r in zip(hs[:256], rs[:256])) / min(n, 256) * n
         return dt, kept
 
-    dt, kept = run(512)
-    n = int(min(200000, max(512, 512 * args.cpu_seconds / max(dt, 1e-3))))
+    run(512)                                   # thread start-up, page faults
+    dt, kept = run(16384)
+    n = int(min(2_000_000, max(16384, 16384 * args.cpu_seconds / max(dt, 1e-3))))
     dt, kept = run(n)
     return {"value": 4.0 * w.head_dim * kept / dt / 1e12, "unit": "TFLOP/s (kept entries)", "cores": oracle.threads(),
             "kind": "oracle", "sample": f"{n} random (head,row) pairs of {w.name}, {dt:.1f} s, fp64, kept entries "
@@ -279,6 +283,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = wl.WORKLOADS[args.workload]
+    if args.copy_calibration:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")   # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     res, ctx = bench_prefill(args, w, torch, B, wl)
     line = {
         "metric": "effective TFLOP/s on kept entries (mask build + sparse prefill per step, 32k prefill)",
@@ -293,7 +304,7 @@ def main():
         "mask_build_gbs": res["mask_build_gbs"],
         "tflops_kept_entries_prefill_only": res["tflops_kept_prefill"],
         "tflops_listed_tiles_prefill_only": res["tflops_tiles_prefill"],
-        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16", "achieved": res["tflops_kept_prefill"],
+        "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16_pipe", "achieved": res["tflops_kept_prefill"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": res["tflops_kept_prefill"] / PEAK_BF16_TFLOPS,
                      "traffic": None, "achieved_listed_tiles": res["tflops_tiles_prefill"],
                      "frac_listed_tiles": res["tflops_tiles_prefill"] / PEAK_BF16_TFLOPS},

@@ -14,11 +14,12 @@
 //     permutation of each 16-key group, already the B-operand layout, so P never leaves
 //     registers; V stays row-major in LDS and its transposed A operand comes from the
 //     transposing LDS read (ds_read_b64_tr_b16), addressed with the same permutation.
-//   K / V move in stages of 64 keys through a double-buffered LDS ring filled by load-to-LDS
-//     instructions (no registers in between): the next stage is in flight while the current one
-//     is computed, one barrier per stage.
-//   Tiles not in the block index are never touched, empty halves of a tile are never loaded, empty
-//     32-key blocks are not multiplied, and full tiles skip the element mask.
+//   The unit of work is a block of 32 keys (an occupied key quarter of a listed tile). K / V blocks
+//     move through two LDS rings of four slots filled by load-to-LDS instructions (no registers in
+//     between), three blocks ahead of their use; one barrier per block. Within a wave the products
+//     of three consecutive blocks are interleaved with the softmax arithmetic (see the kernel).
+//   Tiles not in the block index are never touched, key quarters of a tile without a kept entry are
+//     never loaded, and full tiles skip the element mask.
 // fp32 kernel (the 1e-4 variant): plain ALU code, one query row per group of head_dim/4 lanes,
 // iterating only over the set bits of the row's tile words.
 #include <hip/hip_bf16.h>
@@ -135,10 +136,6 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kBM = 128, kBN = 128;
-constexpr int kStageKeys = 64;               // keys per pipeline stage (half a tile)
-constexpr int kStageK = kStageKeys * 256;    // K part of a stage: 64 rows x 256 B, no padding
-constexpr int kStageBytes = 2 * kStageK;     // + the V part
-constexpr int kLdsBytes = 2 * kStageBytes;   // double buffered: 64 KiB, two workgroups per CU
 
 // LDS layout. Rows are 256 B = 16 chunks of 16 B and are not padded, because the global -> LDS
 // copies are done by the load-to-LDS instruction, which writes the 64 lanes of a wave to 1 KiB of
@@ -172,353 +169,9 @@ __device__ __forceinline__ int kind_of(const uint8_t *__restrict__ blk_kind, int
   return (int)((word >> (8 * (t & 3))) & 0xFFu);
 }
 
-// One pipeline stage = one occupied half (64 keys) of a listed tile.
-struct Stage {
-  int t, half;
-};
-
 // Scheduling hints: instruction classes of __builtin_amdgcn_sched_group_barrier.
 #define DAM_SCHED_MFMA 0x008
 #define DAM_SCHED_DSREAD 0x100
-
-// Softmax + P V of one stage for the key blocks named by ACT (bit kb set = the 32-key block kb of
-// the stage is computed; the other one holds no kept entry for this wave's 32 rows).
-template <int ACT>
-__device__ __forceinline__ void stage_compute(const unsigned char *__restrict__ ldsK,
-                                              const unsigned char *__restrict__ ldsV, const bf16x8 (&qf)[8],
-                                              f32x16 (&oacc)[4], float &m_run, float &l_run, bool full,
-                                              u32x2 bits, float c2, const int (&kaddr)[8],
-                                              const int (&vaddr)[4], int hf) {
-  constexpr int NB = (ACT == 3) ? 2 : 1;          // active key blocks
-  constexpr int KB0 = (ACT == 2) ? 1 : 0;         // first active block
-  f32x16 sacc[NB];
-  // accumulator e of block kb is key 32 kb + 8 (e / 4) + 4 hf + e % 4: start it at 0 (kept) or -inf
-#pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    const int inv = (int)~(bits[KB0 + b] >> (4 * hf));  // all zero for a full tile
-#pragma unroll
-    for (int e = 0; e < 16; ++e)
-      sacc[b][e] = __int_as_float(__builtin_amdgcn_sbfe(inv, 8 * (e / 4) + e % 4, 1) << 23);  // 0 or 0xFF800000
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  // S^T = K Q^T, operands fetched a few MFMAs ahead
-  {
-    bf16x8 kf[8][NB];
-#pragma unroll
-    for (int c = 0; c < 8; ++c)
-#pragma unroll
-      for (int b = 0; b < NB; ++b) kf[c][b] = lds_read_b128(ldsK, kaddr[c] + (KB0 + b) * 32 * 256);
-    if (full) {
-      // a full tile needs no element mask: the first product starts from a literal zero
-      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][b], qf[0], zero, 0, 0, 0);
-    } else {
-#pragma unroll
-      for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][b], qf[0], sacc[b], 0, 0, 0);
-    }
-#pragma unroll
-    for (int c = 1; c < 8; ++c)
-#pragma unroll
-      for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c][b], qf[c], sacc[b], 0, 0, 0);
-    constexpr int N = 8 * NB, AHEAD = 4;
-    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, AHEAD, 0);
-#pragma unroll
-    for (int x = 0; x < N - AHEAD; ++x) {
-      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, AHEAD, 0);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  // online softmax; one query per lane pair (lane, lane ^ 32)
-  float mx = -INFINITY;
-#pragma unroll
-  for (int b = 0; b < NB; ++b)
-#pragma unroll
-    for (int e = 0; e < 16; e += 2) mx = fmaxf(fmaxf(sacc[b][e], sacc[b][e + 1]), mx);
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m_run, mx);
-  const float m_ref = m_new == -INFINITY ? 0.0f : m_new;
-  const float corr = __builtin_amdgcn_exp2f((m_run - m_ref) * c2);
-  const float off = m_ref * c2;
-  m_run = m_new;
-  float psum = 0.0f;
-  unsigned pk[NB][8];
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-  for (int b = 0; b < NB; ++b)
-#pragma unroll
-    for (int e = 0; e < 16; e += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][e], c2, -off));
-      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][e + 1], c2, -off));
-      pk[b][e / 2] = pack_bf16(p0, p1);
-      // the row sum is taken over the rounded weights the P V product uses
-      psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[b][e / 2]), ones, psum, false);
-    }
-  l_run = l_run * corr + psum;
-  if (__ballot(corr != 1.0f)) {
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[db][e] *= corr;
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  // O^T += V^T P^T. B operand: accumulators 8a .. 8a+7 of block kb as bf16, i.e. k-slot 8 hf + j is key
-  // 32 kb + 16 a + 8 (j / 4) + 4 hf + j % 4. A operand: those keys of V at dim 32 db + (lane % 32), fetched
-  // with two transposing LDS reads (each returns 4 consecutive keys of one dim; within a group of 16
-  // lanes, lane s supplies the address of key s / 4, dims 4 (s % 4) .. + 3).
-  {
-    typedef __attribute__((ext_vector_type(8))) short s16x8;
-    s16x4 vr[NB][2][4][2];
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-      for (int a2 = 0; a2 < 2; ++a2)
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int u = 0; u < 2; ++u)
-            vr[b][a2][db][u] = lds_read_tr(ldsV, vaddr[db] + ((KB0 + b) * 32 + a2 * 16 + u * 8) * 256);
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-      for (int a2 = 0; a2 < 2; ++a2) {
-        const u32x4 praw = {pk[b][4 * a2], pk[b][4 * a2 + 1], pk[b][4 * a2 + 2], pk[b][4 * a2 + 3]};
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, praw);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const s16x8 both = __builtin_shufflevector(vr[b][a2][db][0], vr[b][a2][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, oacc[db], 0, 0, 0);
-        }
-      }
-    constexpr int N = 8 * NB, AHEAD = 4;
-    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 2 * AHEAD, 0);
-#pragma unroll
-    for (int x = 0; x < N - AHEAD; ++x) {
-      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 2, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, AHEAD, 0);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16(
-    AttnArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ k,
-    const __hip_bfloat16 *__restrict__ v, const int *__restrict__ row_ptr, const int *__restrict__ blk_col,
-    const uint8_t *__restrict__ blk_kind, const uint64_t *__restrict__ tile_bits, __hip_bfloat16 *__restrict__ out,
-    float *__restrict__ lse, int *__restrict__ queue_next) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-  __shared__ int s_item[2];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = lane & 31, hf = lane >> 5;
-  const float c2 = a.scale * 1.4426950408889634f;
-
-  // LDS byte offsets of this lane's operand fragments inside a stage (see the layout note above)
-  int kaddr[8], vaddr[4];
-#pragma unroll
-  for (int c = 0; c < 8; ++c) kaddr[c] = n * 256 + (((2 * c + hf) ^ (n & 15)) << 4);
-  {
-    const int i16 = n & 15, rl = i16 >> 2;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-      vaddr[db] = kStageK + (4 * hf + rl) * 256 + ((db ^ rl) << 6) + 32 * (n >> 4) + 8 * (i16 & 3);
-  }
-  // per-lane byte offsets of the load-to-LDS copies inside a stage (see copy_in below): instruction
-  // `it` of wave w fills rows 16 it + 4 w .. + 3, so that a lane's row permutation is the same for
-  // every `it` and one offset per tensor serves all four instructions
-  const int sub = lane >> 4, pos = lane & 15;
-  const int row0 = wave * 4 + sub;
-  const unsigned kss2 = (unsigned)a.k_ss * 2u, vss2 = (unsigned)a.v_ss * 2u;  // row strides in bytes
-  const unsigned koff = (unsigned)row0 * kss2 + ((pos ^ (row0 & 15)) << 4);
-  const unsigned voff = (unsigned)row0 * vss2 + ((pos ^ (sub << 2)) << 4);
-
-  // Persistent workgroups pull (head, query tile) items from eight queues, one per XCD: queue x
-  // holds the (batch, KV head) pairs with pair % 8 == x, so that the query heads sharing a KV
-  // head run on one XCD and share its L2 copy of K / V; items of a queue go longest-row first.
-  // A workgroup drains the queue of the XCD it runs on, then helps the others, and exits when
-  // all eight are empty.
-  const int G = a.Hq / a.Hkv, n_pairs = a.B * a.Hkv, per_pair = G * a.nQt;
-  const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);  // XCC_ID, 4 bits
-  int hop = 0;
-  while (true) {
-  __syncthreads();  // previous item: every wave is done with the LDS ring and with s_item
-  if (tid == 0) {
-    int item = -1, queue = 0;
-    for (; hop < kXcd; ++hop) {
-      queue = (my_xcd + hop) & (kXcd - 1);
-      const int pairs_here = (n_pairs - queue + kXcd - 1) / kXcd;  // pairs p with p % 8 == queue
-      const int got = atomicAdd(&queue_next[queue], 1);
-      if (got < pairs_here * per_pair) {
-        item = got;
-        break;
-      }
-    }
-    s_item[0] = item;
-    s_item[1] = queue;
-  }
-  __syncthreads();
-  const int item = s_item[0], queue = s_item[1];
-  if (item < 0) break;
-  if (queue != ((my_xcd + hop) & (kXcd - 1))) hop = (queue - my_xcd) & (kXcd - 1);  // other threads follow thread 0
-  WorkItem w;
-  {
-    const int pair = (item / per_pair) * kXcd + queue, within = item % per_pair;
-    w.b = pair / a.Hkv;
-    w.hkv = pair % a.Hkv;
-    w.qt = a.nQt - 1 - within / G;
-    w.hq = w.hkv * G + within % G;
-    w.valid = true;
-  }
-  const int t0 = __builtin_amdgcn_readfirstlane(row_ptr[(int64_t)w.hq * (a.nQt + 1) + w.qt]);
-  const int t1 = __builtin_amdgcn_readfirstlane(row_ptr[(int64_t)w.hq * (a.nQt + 1) + w.qt + 1]);
-  const int qrow_l = wave * 32 + n;  // this lane's query row inside the tile
-  const int qrow = w.qt * kBM + qrow_l;
-  const bool qlive = qrow < a.S;
-
-  // Q fragments: B operand of S^T = K Q^T. Chunk c covers dims 16c .. 16c+15; this lane holds dims
-  // 16c + 8 hf .. + 7 of its query row.
-  bf16x8 qf[8];
-  {
-    const __hip_bfloat16 *qp = q + w.b * a.q_sb + w.hq * a.q_sh + (int64_t)qrow * a.q_ss + 8 * hf;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      u32x4 raw = {0u, 0u, 0u, 0u};
-      if (qlive) raw = *reinterpret_cast<const u32x4 *>(qp + 16 * c);
-      qf[c] = __builtin_bit_cast(bf16x8, raw);
-    }
-  }
-  f32x16 oacc[4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
-  float m_run = -INFINITY, l_run = 0.0f;  // running max (raw logits) and this lane's part of the row sum
-
-  const unsigned char *kg = reinterpret_cast<const unsigned char *>(k + w.b * a.k_sb + w.hkv * a.k_sh);
-  const unsigned char *vg = reinterpret_cast<const unsigned char *>(v + w.b * a.v_sb + w.hkv * a.v_sh);
-
-  // next occupied half at or after (t, half)
-  auto seek = [&](Stage s) {
-    while (s.t < t1) {
-      const int quarters = kind_of(blk_kind, s.t) >> 1;
-      if (s.half == 0 && (quarters & 3)) break;
-      if (s.half <= 1 && (quarters & 12)) {
-        s.half = 1;
-        break;
-      }
-      ++s.t;
-      s.half = 0;
-    }
-    return s;
-  };
-  auto after = [&](Stage s) {
-    if (s.half == 0) return seek(Stage{s.t, 1});
-    return seek(Stage{s.t + 1, 0});
-  };
-  // Global -> LDS copy of one stage: every wave issues 4 + 4 load-to-LDS instructions of 1 KiB
-  // (4 rows) each. Lane L of an instruction fills one row at position L % 16 and therefore
-  // fetches the chunk that the row's permutation puts there. A copy is a scalar base (the first
-  // key of the instruction) plus the constant per-lane offset. The one stage that can reach past
-  // the end of the sequence redirects such keys to the last row (they are masked anyway; this
-  // keeps the tile finite).
-  auto copy_in = [&](Stage s, int buf) {
-    const int key0 = __builtin_amdgcn_readfirstlane(blk_col[s.t]) * kBN + s.half * kStageKeys;
-    unsigned char *base = lds + buf * kStageBytes + wave * 1024;
-    if (key0 + kStageKeys <= a.S) {
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const unsigned char *kst = kg + (int64_t)(key0 + 16 * it) * a.k_ss * 2;
-        const unsigned char *vst = vg + (int64_t)(key0 + 16 * it) * a.v_ss * 2;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kst + koff),
-                                         (__attribute__((address_space(3))) void *)(base + it * 4096), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vst + voff),
-                                         (__attribute__((address_space(3))) void *)(base + kStageK + it * 4096), 16, 0, 0);
-      }
-    } else {
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int row = 16 * it + row0;
-        const int key = min(key0 + row, a.S - 1);
-        const int kc = pos ^ (row0 & 15), vc = pos ^ (sub << 2);
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(kg + (int64_t)key * a.k_ss * 2 + kc * 16),
-            (__attribute__((address_space(3))) void *)(base + it * 4096), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void *)(vg + (int64_t)key * a.v_ss * 2 + vc * 16),
-            (__attribute__((address_space(3))) void *)(base + kStageK + it * 4096), 16, 0, 0);
-      }
-    }
-  };
-  auto load_bits = [&](Stage s) {
-    u32x2 r = {~0u, ~0u};
-    if (!(kind_of(blk_kind, s.t) & 1))
-      r = *reinterpret_cast<const u32x2 *>(tile_bits + ((int64_t)s.t * kBM + qrow_l) * 2 + s.half);
-    return r;
-  };
-
-  Stage cur = seek(Stage{t0, 0});
-  if (cur.t < t1) {
-    copy_in(cur, 0);
-    u32x2 bits = load_bits(cur);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    int buf = 0;
-    while (true) {
-      const Stage nxt = after(cur);
-      const bool more = nxt.t < t1;
-      u32x2 bits_next = {0u, 0u};
-      if (more) {
-        copy_in(nxt, buf ^ 1);
-        bits_next = load_bits(nxt);
-      }
-      {
-        const int kind = kind_of(blk_kind, cur.t);
-        const bool full = kind & 1;
-        const int quarters = (kind >> (1 + 2 * cur.half)) & 3;
-        const bool act0 = (quarters & 1) && __ballot(bits[0] != 0u);
-        const bool act1 = (quarters & 2) && __ballot(bits[1] != 0u);
-        const unsigned char *ldsS = lds + buf * kStageBytes;
-        if (act0 && act1)
-          stage_compute<3>(ldsS, ldsS, qf, oacc, m_run, l_run, full, bits, c2, kaddr, vaddr, hf);
-        else if (act0)
-          stage_compute<1>(ldsS, ldsS, qf, oacc, m_run, l_run, full, bits, c2, kaddr, vaddr, hf);
-        else if (act1)
-          stage_compute<2>(ldsS, ldsS, qf, oacc, m_run, l_run, full, bits, c2, kaddr, vaddr, hf);
-      }
-      if (!more) break;
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      bits = bits_next;
-      cur = nxt;
-      buf ^= 1;
-    }
-  }
-
-  // finish: total sum over both half-waves, normalise, store. Accumulator e of block db is dim
-  // 32 db + 8 (e / 4) + 4 hf + e % 4 of this lane's query.
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-  if (qlive) {
-    __hip_bfloat16 *op = out + w.b * a.o_sb + w.hq * a.o_sh + (int64_t)qrow * a.o_ss;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint2 pr;
-        pr.x = pack_bf16(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
-        pr.y = pack_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
-        *reinterpret_cast<uint2 *>(op + 32 * db + 8 * g + 4 * hf) = pr;
-      }
-    if (lse && hf == 0)
-      lse[((int64_t)w.b * a.Hq + w.hq) * a.S + qrow] =
-          l_tot > 0.0f ? (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
-  }
-  }  // next work item
-}
-
 
 // ================================================================================================
 // Block-pipelined bf16 kernel. The unit of work is a block of 32 keys (one occupied key quarter of
@@ -977,13 +630,6 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
                                                 mk->blk_col, mk->tile_bits, (float *)out, lse);
     return launch_status();
   }
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_prefill_bf16), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kLdsBytes) != hipSuccess)
-      return DAM_ERR_DEVICE;
-    attr_set = true;
-  }
   static int n_cu = 0;
   if (!n_cu) {
     int dev = 0;
@@ -994,11 +640,14 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   int *queue_next = static_cast<int *>(ws);
   k_zero_queues<<<1, 64, 0, st>>>(queue_next);
   const int persistent = std::min(blocks, 2 * n_cu);  // two workgroups fit a CU (registers and LDS)
-#ifndef DAM_PREFILL_STAGED
   const bool ragged = p->seq % kBlkKeys != 0;
-  const void *fn = ragged ? reinterpret_cast<const void *>(k_prefill_bf16_pipe<true>)
-                          : reinterpret_cast<const void *>(k_prefill_bf16_pipe<false>);
-  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kPipeLds) != hipSuccess) return DAM_ERR_DEVICE;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[ragged]) {
+    const void *fn = ragged ? reinterpret_cast<const void *>(k_prefill_bf16_pipe<true>)
+                            : reinterpret_cast<const void *>(k_prefill_bf16_pipe<false>);
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kPipeLds) != hipSuccess) return DAM_ERR_DEVICE;
+    attr_set[ragged] = true;
+  }
   if (ragged)
     k_prefill_bf16_pipe<true><<<persistent, 256, kPipeLds, st>>>(
         a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col,
@@ -1007,12 +656,6 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
     k_prefill_bf16_pipe<false><<<persistent, 256, kPipeLds, st>>>(
         a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col,
         mk->blk_kind, mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next);
-  return launch_status();
-#endif
-  k_prefill_bf16<<<persistent, 256, kLdsBytes, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
-                                                (const __hip_bfloat16 *)v,
-                                                   mk->blk_row_ptr, mk->blk_col, mk->blk_kind, mk->tile_bits,
-                                                   (__hip_bfloat16 *)out, lse, queue_next);
   return launch_status();
 }
 
