@@ -12,7 +12,7 @@ import ctypes
 import os
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
-from typing import Optional, Sequence
+from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -188,15 +188,18 @@ def kept_list(art: MaskArtefact, h: int, i: int) -> np.ndarray:
 
 
 def block_index(art: MaskArtefact, S: int, tile_m: int, tile_n: int, heads: Optional[Sequence[int]] = None,
-                want_bits: bool = True, workers: int = 8):
+                want_bits: bool = True, workers: int = 8, qt_range: Optional[Tuple[int, int]] = None):
     """Block index of the given heads (default all): returns
     (row_ptr [n_heads][nQt+1] i64 with offsets global over the given heads in order,
-     col i32 [n_tiles], kind u8 [n_tiles], tile_bits u64 [n_tiles][tile_m][tile_n//64] or None)."""
+     col i32 [n_tiles], kind u8 [n_tiles], tile_bits u64 [n_tiles][tile_m][tile_n//64] or None).
+    qt_range = (q0, q1) restricts every head to its query-tile rows q0 .. q1-1 (row_ptr then has
+    q1 - q0 + 1 entries per head)."""
     heads = list(range(art.H)) if heads is None else list(heads)
-    nQt = (S + tile_m - 1) // tile_m
+    qa, qb = (0, (S + tile_m - 1) // tile_m) if qt_range is None else qt_range
+    nQt = qb - qa
     wpr = tile_n // 64
     chunk = max(1, nQt // 16)
-    jobs = [(h, q0, min(nQt, q0 + chunk)) for h in heads for q0 in range(0, nQt, chunk)]
+    jobs = [(h, q0, min(qb, q0 + chunk)) for h in heads for q0 in range(qa, qb, chunk)]
 
     def run(job):
         h, q0, q1 = job

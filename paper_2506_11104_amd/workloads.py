@@ -49,7 +49,8 @@ WORKLOADS: Dict[str, Workload] = {
     "c1": Workload("c1", "prefill_map", 1, 2, 2, 64, 256, 64, "f32", 64, 64, tau=0.257, seed=BASE_SEED + 0),
     "c2": Workload("c2", "prefill_map", 1, 32, 8, 128, 4096, 1024, "bf16", tau=0.02, seed=BASE_SEED + 1),
     "c3": Workload("c3", "prefill_patterns", 1, 32, 8, 128, 32768, 0, "bf16", seed=BASE_SEED + 2),
-    "c4": Workload("c4", "prefill_map", 1, 64, 8, 128, 131072, 4096, "bf16", tau=0.0, seed=BASE_SEED + 3),
+    "c4": Workload("c4", "prefill_map", 1, 64, 8, 128, 131072, 4096, "bf16", tau=0.005, seed=BASE_SEED + 3,
+                   extra={"win_lo": 300.0, "win_hi": 2500.0}),
     "c5": Workload("c5", "decode", 16, 32, 8, 128, 65536, 0, "bf16", seed=BASE_SEED + 4, steps=256),
 }
 

@@ -1,0 +1,200 @@
+"""The largest configurations at full size, in the launch shapes bench.py uses: c3 (32k prefill,
+masks from patterns), c4 (128k prefill, masks from a 4096 x 4096 capture map) and c5 (decode at
+64k, batch 16). What the oracle cannot recompute whole within a test's time is checked on seeded
+samples it computes one by one: query-tile rows of the block index for every head, (head, row)
+pairs of the attention output for every head, plus the ragged ends.
+
+Progress lines are printed with pytest's capture switched off: the c4 case is quiet for a while."""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from dam_testlib import dev, pack_rows_u64, u64
+from paper_2506_11104_amd import binding as B
+from paper_2506_11104_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL_BF16 = 2e-2
+WORKERS = 16
+T0 = time.time()
+
+
+_CAPSYS = None
+
+
+@pytest.fixture(autouse=True)
+def _progress_output(capsys):
+    global _CAPSYS
+    _CAPSYS = capsys
+    yield
+    _CAPSYS = None
+
+
+def say(msg):
+    with _CAPSYS.disabled():
+        print(f"[fullsize {time.time() - T0:6.1f}s] {msg}", file=sys.stderr, flush=True)
+
+
+def check_tile_rows(art, mask, S, jobs):
+    """Block index and tile bits of the (head, query-tile row) pairs in jobs against the oracle."""
+    from concurrent.futures import ThreadPoolExecutor
+    g_ptr = mask.blk_row_ptr.cpu().numpy().astype(np.int64)
+    col = mask.blk_col.cpu().numpy()
+    kind = mask.blk_kind.cpu().numpy()
+
+    def want(job):
+        h, qt = job
+        return oracle.block_index(art, S, 128, 128, heads=[h], qt_range=(qt, qt + 1), workers=1)
+
+    with ThreadPoolExecutor(max_workers=WORKERS) as ex:
+        res = list(ex.map(want, jobs))
+    for (h, qt), (rp, c, k, bits) in zip(jobs, res):
+        a, b = g_ptr[h, qt], g_ptr[h, qt + 1]
+        assert b - a == rp[0, 1], f"tile count head {h} row {qt}"
+        assert np.array_equal(col[a:b], c), f"blk_col head {h} row {qt}"
+        assert np.array_equal(kind[a:b], k), f"blk_kind head {h} row {qt}"
+        if b > a:
+            assert np.array_equal(u64(mask.tile_bits[a:b]), bits), f"tile_bits head {h} row {qt}"
+
+
+def check_heads_in_full(art, mask, S, heads):
+    g_ptr = mask.blk_row_ptr.cpu().numpy().astype(np.int64)
+    for h in heads:
+        rp, c, k, bits = oracle.block_index(art, S, 128, 128, heads=[h], workers=WORKERS)
+        a, b = g_ptr[h, 0], g_ptr[h, -1]
+        assert np.array_equal(g_ptr[h] - a, rp[0]), f"blk_row_ptr head {h}"
+        assert np.array_equal(mask.blk_col[a:b].cpu().numpy(), c), f"blk_col head {h}"
+        assert np.array_equal(mask.blk_kind[a:b].cpu().numpy(), k), f"blk_kind head {h}"
+        assert np.array_equal(u64(mask.tile_bits[a:b]), bits), f"tile_bits head {h}"
+        say(f"head {h}: {b - a} tiles identical")
+
+
+def check_rows(Q, K, V, art, out, lse, hs, rs):
+    O, LSE = oracle.attend_rows(Q[hs, rs], K, V, art, Q.shape[0], hs, rs)
+    hs_t, rs_t = torch.from_numpy(hs.astype(np.int64)).cuda(), torch.from_numpy(rs).cuda()
+    got = out[0][hs_t, rs_t].float().cpu().numpy()
+    got_lse = lse[0][hs_t, rs_t].cpu().numpy()
+    assert not np.isnan(got).any()
+    fin = np.isfinite(LSE)
+    assert np.array_equal(np.isneginf(got_lse), ~fin)
+    err = np.abs(got - O).max()
+    assert err <= TOL_BF16, f"max abs err {err}"
+    if fin.any():
+        assert np.abs(got_lse[fin] - LSE[fin]).max() <= TOL_BF16
+    assert (got[~fin] == 0).all()
+    return err
+
+
+def test_c3_mask_whole_block_index_bit_exact():
+    """Every tile of every head of the 32k pattern masks: row pointers, columns, kinds, bits."""
+    w = wl.WORKLOADS["c3"]
+    dflag, vflag = wl.patterns_c3(w)
+    art = oracle.from_patterns(dflag, vflag)
+    mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=w.seq, diag_in=torch.from_numpy(dflag).cuda(),
+                        vert_in=torch.from_numpy(vflag).cuda())
+    torch.cuda.synchronize()
+    say(f"c3: {mask.n_tiles} tiles listed")
+    row_ptr, col, kind, bits = oracle.block_index(art, w.seq, 128, 128, workers=WORKERS)
+    assert np.array_equal(mask.blk_row_ptr.cpu().numpy().astype(np.int64), row_ptr)
+    assert np.array_equal(mask.blk_col.cpu().numpy(), col)
+    assert np.array_equal(mask.blk_kind.cpu().numpy(), kind)
+    assert np.array_equal(u64(mask.tile_bits), bits)
+
+
+def test_c4_full_size():
+    w = wl.WORKLOADS["c4"]
+    S, L, H = w.seq, w.pcl, w.hq
+    say("c4: generating Q, K, V (about 5 GiB of normals)")
+    Q, K, V = wl.qkv_structured(w)
+    say("c4: capture map")
+    A = wl.capture_map(Q[:, :L], K[:, :L], L, w.hq // w.hkv)
+    say("c4: oracle stage one")
+    art = oracle.derive(A, None, w.lam, w.eps, w.tau, w.mu)
+    say("c4: GPU mask build")
+    mask = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu,
+                        attn_sum=torch.from_numpy(A).cuda())
+    torch.cuda.synchronize()
+    del A
+    # stage one, whole: threshold bits, match counts and flags
+    assert np.float32(mask.bmin.item()) == np.float32(art.bmin)
+    for h in range(H):
+        assert np.array_equal(u64(mask.true_bits[h]), pack_rows_u64(art.true_mask[h])), f"true_bits head {h}"
+    assert np.array_equal(mask.diag_cnt.cpu().numpy(), art.diag_cnt)
+    assert np.array_equal(mask.vert_cnt.cpu().numpy(), art.vert_cnt)
+    assert np.array_equal(mask.diag_flag.cpu().numpy(), art.diag_flag)
+    assert np.array_equal(mask.vert_flag.cpu().numpy(), art.vert_flag)
+    # density over the S x S triangle, from the block index' own bits
+    nnz = 0
+    for a in range(0, mask.n_tiles, 1 << 17):
+        nnz += int(np.unpackbits(u64(mask.tile_bits[a:a + (1 << 17)]).view(np.uint8)).sum(dtype=np.int64))
+    dens = nnz / (H * S * (S + 1) / 2)
+    say(f"c4: stage one identical; {mask.n_tiles} tiles, density {dens:.4f}")
+    assert 0.01 <= dens <= 0.05, dens
+    # the S-sized outputs: one head in full, and for every head the tile rows around the L boundary,
+    # the last one and seeded random ones
+    check_heads_in_full(art, mask, S, [int(np.random.default_rng(44).integers(0, H))])
+    rng = np.random.default_rng(45)
+    nQt = S // 128
+    jobs = [(h, int(qt)) for h in range(H)
+            for qt in np.concatenate([[0, L // 128 - 1, L // 128, nQt - 1], rng.integers(0, nQt, 4)])]
+    check_tile_rows(art, mask, S, jobs)
+    say("c4: sampled tile rows of every head identical; prefill")
+    q, k, v = dev(Q, "bf16")[None], dev(K, "bf16")[None], dev(V, "bf16")[None]
+    out, lse = B.dam_sparse_attn_prefill(q, k, v, mask, want_lse=True)
+    torch.cuda.synchronize()
+    say("c4: prefill done; oracle rows")
+    n = 64 * H
+    hs = np.repeat(np.arange(H, dtype=np.int32), 64)
+    rs = rng.integers(0, S, n).astype(np.int64)
+    rs[::64] = S - 1
+    rs[1::64] = 0
+    rs[2::64] = L - 1
+    rs[3::64] = L
+    err = check_rows(Q, K, V, art, out, lse, hs, rs)
+    say(f"c4: {n} sampled rows, max abs err {err:.2e}")
+
+
+def test_c5_full_size_lists_and_decode():
+    """Four consecutive positions of the 64k decode workload: the kept lists built on the GPU equal
+    the oracle's rows of the mask, and the decode outputs of every (sequence, head) match."""
+    w = wl.scaled(wl.WORKLOADS["c5"], steps=4)
+    cap = w.seq + w.steps
+    dflag, vflag = wl.patterns_c5(w)
+    art = oracle.from_patterns(dflag, vflag)
+    say("c5: generating caches")
+    qs, kc, vc = wl.decode_inputs(w)
+    Kf = kc.float().numpy().reshape(w.batch * w.hkv, cap, w.head_dim)
+    Vf = vc.float().numpy().reshape(w.batch * w.hkv, cap, w.head_dim)
+    kc_d, vc_d = kc.cuda(), vc.cuda()
+    G = w.hq // w.hkv
+    kv_of = np.array([b * w.hkv + h // G for b in range(w.batch) for h in range(w.hq)], np.int32)
+    d_in, v_in = torch.from_numpy(dflag).cuda(), torch.from_numpy(vflag).cuda()
+    for step in range(w.steps):
+        p = w.seq - 1 + step
+        mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False,
+                            rows=(p, p + 1))
+        torch.cuda.synchronize()
+        ptr = mask.kept_ptr.cpu().numpy().astype(np.int64)
+        idx = mask.kept_idx.cpu().numpy()
+        lists = [oracle.kept_list(art, h, p) for h in range(w.hq)]
+        for h in range(w.hq):
+            assert np.array_equal(idx[ptr[h]:ptr[h + 1]], lists[h]), f"kept list head {h} position {p}"
+        # the same per-head lists serve every sequence of the batch
+        lens = np.array([len(x) for x in lists])
+        ptr_all = np.concatenate([[0], np.cumsum(np.tile(lens, w.batch))]).astype(np.int64)
+        idx_all = np.tile(np.concatenate(lists), w.batch).astype(np.int32)
+        qf = qs[step].float().numpy().reshape(w.batch * w.hq, w.head_dim)
+        O, LSE = oracle.attend_lists(qf, Kf, Vf, kv_of, ptr_all, idx_all)
+        out, lse = B.dam_sparse_attn_decode(qs[step].cuda(), kc_d, vc_d, torch.from_numpy(ptr_all.astype(np.int32)).cuda(),
+                                            torch.from_numpy(idx_all).cuda(), int(lens.max()), want_lse=True)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().reshape(w.batch * w.hq, w.head_dim)
+        assert not np.isnan(got).any()
+        err = np.abs(got - O).max()
+        assert err <= TOL_BF16, f"position {p}: max abs err {err}"
+        assert np.abs(lse.cpu().numpy().reshape(-1) - LSE).max() <= TOL_BF16
+        say(f"c5: position {p}: {int(lens.sum())} kept keys per sequence, max abs err {err:.2e}")
