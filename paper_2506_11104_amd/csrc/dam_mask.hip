@@ -100,78 +100,251 @@ __global__ void k_fill_u32(unsigned *p, int64_t n, unsigned v) {
 // Sec. 4.2.3: m[i][j] = (B - bmin >= tau) and j <= i. One wave = 4 rows x 4 words (256 keys); each
 // lane owns one key per word so every load is a fully coalesced 256-byte row segment, and the
 // 16 loads of a lane are independent. Entries above the diagonal are never kept, so never read.
-constexpr int kTmRows = 16;  // rows per block (4 per wave)
+constexpr int kTmRows = 64;  // rows per block (4 passes of 4 rows per wave)
 
-template <int LAMBDA2>
-__global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A,
-                                                   const float *__restrict__ C, int L, int tbw,
-                                                   float eps, float tau,
-                                                   const float *__restrict__ bmin_p,
+// Every operation of the fixed fp32 sequence (divide by a positive constant, max, square root,
+// subtract, compare) is rounded to nearest and therefore non-decreasing in its input, so the keep
+// decision (Sec. 4.2.3) is a step function of the mean attention abar (of A itself when no count
+// matrix is given: then abar = A / (1 + eps)): keep <=> value >= theta for one fp32 number theta.
+// k_threshold finds theta by bisection over the ordered bit patterns of fp32, evaluating the exact
+// sequence at each probe; k_true_mask then needs one comparison per element and stays bit-exact.
+// Ordered key: increasing with the value over [-inf, +inf]; a NaN is treated as -inf, which is what
+// the sequence does with it (fmaxf(NaN, eps) = eps, the smallest clamped value).
+__device__ __forceinline__ unsigned key_of(float x) {
+  const unsigned b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float value_of(unsigned k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+constexpr unsigned kKeyNegInf = 0x007FFFFFu, kKeyPosInf = 0xFF800000u;
+constexpr unsigned kKeepAll = 0u, kKeepNone = 0xFFFFFFFFu;
+
+template <int LAMBDA2, bool FROM_A>
+__device__ __forceinline__ bool keep_at(float v, float eps, float tau, float bmin) {
+  const float x = FROM_A ? clamp_mean(v, 1.0f, eps) : fmaxf(v, eps);
+  const float bstar = box_cox<LAMBDA2>(x) - bmin;
+  return bstar >= tau;
+}
+
+template <int LAMBDA2, bool FROM_A>
+__global__ void k_threshold(float eps, float tau, const float *__restrict__ bmin_p, unsigned *__restrict__ theta_key) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const float bmin = *bmin_p;
+  unsigned lo = kKeyNegInf, hi = kKeyPosInf;
+  if (!keep_at<LAMBDA2, FROM_A>(value_of(hi), eps, tau, bmin)) {
+    *theta_key = kKeepNone;
+    return;
+  }
+  if (keep_at<LAMBDA2, FROM_A>(value_of(lo), eps, tau, bmin)) {
+    *theta_key = kKeepAll;
+    return;
+  }
+  while (hi - lo > 1u) {  // keep(lo) false, keep(hi) true
+    const unsigned mid = lo + (hi - lo) / 2u;
+    if (keep_at<LAMBDA2, FROM_A>(value_of(mid), eps, tau, bmin)) hi = mid;
+    else lo = mid;
+  }
+  *theta_key = hi;
+}
+
+template <bool FROM_A>
+__global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A, const float *__restrict__ C, int L,
+                                                   int tbw, float eps, const unsigned *__restrict__ theta_key,
                                                    uint64_t *__restrict__ true_bits) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = blockIdx.z;
   const int w0 = blockIdx.x * 4;
-  const int r0 = blockIdx.y * kTmRows + wave * 4;
-  const float bmin = *bmin_p;
+  const unsigned theta = *theta_key;
   const float *Ah = A + (int64_t)h * L * L;
-  const float *Ch = C ? C + (int64_t)h * L * L : nullptr;
-  float a[4][4], c[4][4];
+  const float *Ch = FROM_A ? nullptr : C + (int64_t)h * L * L;
+  constexpr int kIter = kTmRows / 16;  // passes of 4 rows per wave
+#pragma unroll 2
+  for (int it = 0; it < kIter; ++it) {
+    const int r0 = blockIdx.y * kTmRows + (it * 4 + wave) * 4;
+    float a[4][4], c[4][4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int i = r0 + r, j = (w0 + k) * 64 + lane;
-      const bool live = i < L && j <= i;
-      a[r][k] = live ? Ah[(int64_t)i * L + j] : 0.0f;
-      c[r][k] = live ? (Ch ? Ch[(int64_t)i * L + j] : 1.0f) : 0.0f;
-    }
+      for (int k = 0; k < 4; ++k) {
+        const int i = r0 + r, j = (w0 + k) * 64 + lane;
+        const bool live = i < L && j <= i;
+        a[r][k] = live ? Ah[(int64_t)i * L + j] : 0.0f;
+        if (!FROM_A) c[r][k] = live ? Ch[(int64_t)i * L + j] : 0.0f;
+      }
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int i = r0 + r, j = (w0 + k) * 64 + lane;
-      const bool live = i < L && j <= i;
-      const float b = box_cox<LAMBDA2>(clamp_mean(a[r][k], c[r][k], eps));
-      const float bstar = b - bmin;
-      const uint64_t word = __ballot(live && bstar >= tau);
-      if (lane == 0 && i < L && w0 + k < tbw) true_bits[((int64_t)h * L + i) * tbw + w0 + k] = word;
-    }
+      for (int k = 0; k < 4; ++k) {
+        const int i = r0 + r, j = (w0 + k) * 64 + lane;
+        const bool live = i < L && j <= i;
+        float v = a[r][k];
+        if (!FROM_A) v = v / (c[r][k] + eps);
+        if (v != v) v = -INFINITY;
+        const uint64_t word = __ballot(live && key_of(v) >= theta);
+        if (lane == 0 && i < L && w0 + k < tbw) true_bits[((int64_t)h * L + i) * tbw + w0 + k] = word;
+      }
+  }
 }
 
-// Sec. 4.2.4 numerators: kept entries per column and per diagonal of the true mask. Each wave
-// walks 64 rows; lane = column (vertical) or offset (diagonal). Integer atomics: order-free.
-__global__ __launch_bounds__(256) void k_pattern_counts(const uint64_t *__restrict__ true_bits, int L,
-                                                        int tbw, int *__restrict__ vert_cnt,
-                                                        int *__restrict__ diag_cnt) {
+// The same for the common case (no count matrix, L a multiple of 4) at streaming speed: one wave per
+// row, 16-byte loads, every live 256-key segment of a 4096-key span in flight at once, and the row's
+// words gathered into lanes so that they leave as one coalesced store (single 8-byte stores from one
+// lane made the store path the bottleneck). Short and long rows are paired across blocks.
+__global__ __launch_bounds__(256) void k_true_mask_rows(const float *__restrict__ A, int L, int tbw,
+                                                        const unsigned *__restrict__ theta_key,
+                                                        uint64_t *__restrict__ true_bits) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.y;
+  const int half = (L + 1) / 2;
+  const int base = (blockIdx.x >> 1) * 4 + wave;
+  const int i = (blockIdx.x & 1) ? L - 1 - base : base;
+  if (base >= half || ((blockIdx.x & 1) && i < half)) return;
+  const unsigned theta = *theta_key;
+  const float4 *row = reinterpret_cast<const float4 *>(A + ((int64_t)h * L + i) * L);
+  uint64_t *out = true_bits + ((int64_t)h * L + i) * tbw;
+  const int nseg = i / 256 + 1;  // segments with a key <= i
+  const int c = lane & 3;
+  for (int s0 = 0; s0 * 4 < tbw; s0 += 16) {
+    float4 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int j0 = (s0 + u) * 256 + lane * 4;
+      v[u] = (s0 + u < nseg && j0 < L) ? row[(s0 + u) * 64 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    uint64_t mine = 0;  // word s0 * 4 + lane of the row
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      if (s0 + u < nseg) {  // wave-uniform
+        const int j0 = (s0 + u) * 256 + lane * 4;
+        float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        uint64_t b[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float val = x[e] != x[e] ? -INFINITY : x[e];
+          b[e] = __ballot(j0 + e <= i && key_of(val) >= theta);  // bit l: key 4 l + e of the segment
+        }
+        // lane l of word w is key 64 w + l = component l % 4 of lane 16 w + l / 4
+        const uint64_t sel = c == 0 ? b[0] : c == 1 ? b[1] : c == 2 ? b[2] : b[3];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint64_t word = __ballot((sel >> (16 * w + (lane >> 2))) & 1);
+          if (lane == u * 4 + w) mine = word;
+        }
+      }
+    }
+    if (s0 * 4 + lane < tbw) out[s0 * 4 + lane] = mine;
+  }
+}
+
+// Sec. 4.2.4 numerators: kept entries per column and per diagonal of the true mask, counted with
+// carry-save adders on whole 64-bit words. A wave takes a chunk of 64 rows; lane l owns word l of
+// every row (64 columns) and adds the 64 row words into a bit-sliced counter (slice k holds bit k of
+// the 64 column counts), two logic operations per full adder. For the diagonals the row word is first
+// re-aligned: word l of row i then holds m[i][i - r] for r = 64 l .. 64 l + 63 (a funnel shift of two
+// adjacent words and a bit reversal), after which diagonals are columns. The slices of every chunk
+// go to the workspace; k_pattern_finish sums them per pattern and applies the ratio test. No atomics.
+constexpr int kSlices = 7;      // counts 0 .. 64
+constexpr int kChunkRows = 64;
+
+__device__ __forceinline__ void csa(uint64_t &carry, uint64_t &sum, uint64_t a, uint64_t b, uint64_t c) {
+  const uint64_t u = a ^ b;
+  carry = (a & b) | (u & c);
+  sum = u ^ c;
+}
+
+template <bool DIAG>
+__global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restrict__ true_bits, int L, int tbw,
+                                                        int n_chunks, uint64_t *__restrict__ slices) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = blockIdx.z;
-  const int p = blockIdx.x * 64 + lane;  // column c, and also offset r
-  const int i0 = blockIdx.y * 256 + wave * 64;
+  const int chunk = blockIdx.y * 4 + wave;
+  const int wl = blockIdx.x * 64 + lane;  // word of columns (or of diagonal offsets) owned by this lane
+  if (chunk >= n_chunks || wl >= tbw) return;
+  const int i0 = chunk * kChunkRows;
   const uint64_t *tb = true_bits + (int64_t)h * L * tbw;
-  int nv = 0, nd = 0;
-  const int i1 = min(L, i0 + 64);
-  for (int i = i0; i < i1; ++i) {
-    const uint64_t wv = tb[(int64_t)i * tbw + blockIdx.x];
-    nv += (int)((wv >> lane) & 1);
-    const int j = i - p;
-    if (j >= 0) nd += (int)((tb[(int64_t)i * tbw + (j >> 6)] >> (j & 63)) & 1);
+  uint64_t s[kSlices];
+#pragma unroll
+  for (int k = 0; k < kSlices; ++k) s[k] = 0;
+  // a column (offset) block that starts beyond the chunk's last row holds no kept entry
+  if (64 * wl <= i0 + kChunkRows - 1) {
+    for (int g = 0; g < kChunkRows; g += 8) {
+      uint64_t w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + g + u;
+        uint64_t x = 0;
+        if (i < L) {
+          if (!DIAG) {
+            x = tb[(int64_t)i * tbw + wl];
+          } else {
+            const int jhi = i - 64 * wl;  // the column of offset r = 64 wl in this row
+            if (jhi >= 0) {
+              const int wj = jhi >> 6, sh = (jhi & 63) + 1;  // window = bits jhi-63 .. jhi of the row
+              const uint64_t hi = tb[(int64_t)i * tbw + wj];
+              const uint64_t lo = wj > 0 ? tb[(int64_t)i * tbw + wj - 1] : 0;
+              const uint64_t win = sh == 64 ? hi : ((hi << (64 - sh)) | (lo >> sh));
+              x = __brevll(win);                             // offset r = 64 wl + t at bit t
+            }
+          }
+        }
+        w[u] = x;
+      }
+      uint64_t t0, t1, f0, f1, e;
+      csa(t0, s[0], s[0], w[0], w[1]);
+      csa(t1, s[0], s[0], w[2], w[3]);
+      csa(f0, s[1], s[1], t0, t1);
+      csa(t0, s[0], s[0], w[4], w[5]);
+      csa(t1, s[0], s[0], w[6], w[7]);
+      csa(f1, s[1], s[1], t0, t1);
+      csa(e, s[2], s[2], f0, f1);
+      // add the eights into slices 3 .. 6 (ripple)
+#pragma unroll
+      for (int k = 3; k < kSlices; ++k) {
+        const uint64_t c = s[k] & e;
+        s[k] ^= e;
+        e = c;
+      }
+    }
   }
-  if (p < L) {
-    if (nv) atomicAdd(&vert_cnt[(int64_t)h * L + p], nv);
-    if (nd) atomicAdd(&diag_cnt[(int64_t)h * L + p], nd);
-  }
+  uint64_t *out = slices + (((int64_t)h * n_chunks + chunk) * kSlices) * tbw + wl;
+#pragma unroll
+  for (int k = 0; k < kSlices; ++k) out[(int64_t)k * tbw] = s[k];
 }
 
-// gamma = kept / size, matched iff gamma >= mu; pattern p has L - p entries.
-__global__ void k_pattern_flags(const int *__restrict__ diag_cnt, const int *__restrict__ vert_cnt,
-                                int H, int L, float mu, uint8_t *__restrict__ diag_flag,
-                                uint8_t *__restrict__ vert_flag) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= (int64_t)H * L) return;
-  const int p = (int)(e % L);
+// gamma = count / size >= mu for pattern p of head h (Sec. 4.2.4), counts summed over the row chunks.
+// One block per (head, word of 64 patterns): lane = pattern, the four waves share the chunks.
+__global__ __launch_bounds__(256) void k_pattern_finish(const uint64_t *__restrict__ vslices,
+                                                        const uint64_t *__restrict__ dslices, int L, int tbw,
+                                                        int n_chunks, float mu, int *__restrict__ vert_cnt,
+                                                        int *__restrict__ diag_cnt, uint8_t *__restrict__ vert_flag,
+                                                        uint8_t *__restrict__ diag_flag) {
+  __shared__ int s_v[4][64], s_d[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.y, word = blockIdx.x;
+  const int p = word * 64 + lane;
+  int nv = 0, nd = 0;
+  // rows above p hold nothing of pattern p: start at the chunk of the word's first pattern
+  for (int chunk = word * 64 / kChunkRows + wave; chunk < n_chunks; chunk += 4) {
+    const int64_t at = (((int64_t)h * n_chunks + chunk) * kSlices) * tbw + word;
+#pragma unroll
+    for (int k = 0; k < kSlices; ++k) {
+      nv += (int)((vslices[at + (int64_t)k * tbw] >> lane) & 1) << k;
+      nd += (int)((dslices[at + (int64_t)k * tbw] >> lane) & 1) << k;
+    }
+  }
+  s_v[wave][lane] = nv;
+  s_d[wave][lane] = nd;
+  __syncthreads();
+  if (wave != 0 || p >= L) return;
+  nv = s_v[0][lane] + s_v[1][lane] + s_v[2][lane] + s_v[3][lane];
+  nd = s_d[0][lane] + s_d[1][lane] + s_d[2][lane] + s_d[3][lane];
+  const int64_t e = (int64_t)h * L + p;
+  if (vert_cnt) vert_cnt[e] = nv;
+  if (diag_cnt) diag_cnt[e] = nd;
   const float size = (float)(L - p);
-  diag_flag[e] = (uint8_t)((float)diag_cnt[e] / size >= mu);
-  vert_flag[e] = (uint8_t)((float)vert_cnt[e] / size >= mu);
+  vert_flag[e] = (uint8_t)((float)nv / size >= mu);
+  diag_flag[e] = (uint8_t)((float)nd / size >= mu);
 }
 
 // Flags -> bitsets. cbits bit c = column c matched. rrev bit q = diagonal (pw*64 - 1 - q) matched,
@@ -589,8 +762,8 @@ int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *dia
 
 struct Workspace {
   float *bmin;
-  unsigned *xmin_bits;
-  int *diag_cnt, *vert_cnt;
+  unsigned *xmin_bits, *theta_key;
+  uint64_t *vslices, *dslices;
   uint8_t *diag_flag, *vert_flag;
   uint64_t *cbits, *rrev, *occ, *full;
   int *tile_cnt, *row_cnt;
@@ -621,8 +794,12 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   const size_t HL = (size_t)g.H * (size_t)(g.L > 0 ? g.L : 1);
   w.bmin = c.take<float>(1);
   w.xmin_bits = c.take<unsigned>(1);
-  w.diag_cnt = c.take<int>(HL);
-  w.vert_cnt = c.take<int>(HL);
+  w.theta_key = c.take<unsigned>(1);
+  const size_t n_slices = p->mode == DAM_FROM_ATTN_MAP
+                              ? (size_t)g.H * (size_t)((g.L + kChunkRows - 1) / kChunkRows) * kSlices * (size_t)g.tbw
+                              : 1;
+  w.vslices = c.take<uint64_t>(n_slices);
+  w.dslices = c.take<uint64_t>(n_slices);
   w.diag_flag = c.take<uint8_t>(HL);
   w.vert_flag = c.take<uint8_t>(HL);
   w.cbits = c.take<uint64_t>((size_t)g.H * g.pw);
@@ -673,25 +850,33 @@ extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, c
       if (half) k_bmin_from_x<1><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
       else k_bmin_from_x<2><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
     }
-    // a2: true mask
+    // a2: true mask (threshold found once, then one comparison per element)
     {
+      if (half) {
+        if (attn_cnt) k_threshold<1, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+        else k_threshold<1, true><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+      } else {
+        if (attn_cnt) k_threshold<2, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+        else k_threshold<2, true><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+      }
       dim3 grid((g.tbw + 3) / 4, (g.L + kTmRows - 1) / kTmRows, g.H);
-      if (half)
-        k_true_mask<1><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, p->tau, w.bmin, o->true_bits);
+      if (attn_cnt)
+        k_true_mask<false><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
+      else if (g.L % 4 == 0 && (reinterpret_cast<uintptr_t>(attn_sum) & 15) == 0)
+        k_true_mask_rows<<<dim3(2 * ((((g.L + 1) / 2) + 3) / 4), g.H), 256, 0, stream>>>(attn_sum, g.L, g.tbw, w.theta_key,
+                                                                                     o->true_bits);
       else
-        k_true_mask<2><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, p->tau, w.bmin, o->true_bits);
+        k_true_mask<true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
     }
     // a3: match scores
-    int *dcnt = o->diag_cnt ? o->diag_cnt : w.diag_cnt;
-    int *vcnt = o->vert_cnt ? o->vert_cnt : w.vert_cnt;
     uint8_t *df = o->diag_flag ? o->diag_flag : w.diag_flag;
     uint8_t *vf = o->vert_flag ? o->vert_flag : w.vert_flag;
-    const int64_t HL = (int64_t)g.H * g.L;
-    const int fb = (int)std::min<int64_t>((HL + 255) / 256, 4096);
-    k_fill_u32<<<fb, 256, 0, stream>>>(reinterpret_cast<unsigned *>(dcnt), HL, 0u);
-    k_fill_u32<<<fb, 256, 0, stream>>>(reinterpret_cast<unsigned *>(vcnt), HL, 0u);
-    k_pattern_counts<<<dim3(g.tbw, (g.L + 255) / 256, g.H), 256, 0, stream>>>(o->true_bits, g.L, g.tbw, vcnt, dcnt);
-    k_pattern_flags<<<(int)((HL + 255) / 256), 256, 0, stream>>>(dcnt, vcnt, g.H, g.L, p->mu, df, vf);
+    const int n_chunks = (g.L + kChunkRows - 1) / kChunkRows;
+    const dim3 sgrid((g.tbw + 63) / 64, (n_chunks + 3) / 4, g.H);
+    k_pattern_slices<false><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices);
+    k_pattern_slices<true><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.dslices);
+    k_pattern_finish<<<dim3(g.tbw, g.H), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, p->mu, o->vert_cnt,
+                                                          o->diag_cnt, vf, df);
     dflag = df;
     vflag = vf;
     if (o->bmin) k_copy_f32<<<1, 64, 0, stream>>>(o->bmin, w.bmin);

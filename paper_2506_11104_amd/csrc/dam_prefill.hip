@@ -405,10 +405,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // their latency falls into the barrier wait and no LDS wait in the pipeline has to cover them).
     int cur_t = t0 - 1, quarters = 0, cur_full = 0, cur_col = 0;
     Blk last = {0, 0u, 0u, 0, 2};
-    int pre_kind = 0, pre_col = 0;
+    unsigned pre_kinds = 0;  // the aligned word of blk_kind that holds tile cur_t + 1 (shifted when used, so
+    int pre_col = 0;         // that nothing waits for the load before the barrier)
     auto prefetch_meta = [&]() {
       if (quarters == 0 && cur_t + 1 < t1) {
-        pre_kind = kind_of(blk_kind, cur_t + 1);
+        pre_kinds = reinterpret_cast<const unsigned *>(blk_kind)[(cur_t + 1) >> 2];
         pre_col = blk_col[cur_t + 1];
       }
     };
@@ -416,9 +417,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       if (quarters == 0) {
         if (cur_t + 1 >= t1) return Blk{last.key0, last.k_off, last.v_off, last.bits_off, 2};
         ++cur_t;
-        quarters = __builtin_amdgcn_readfirstlane((pre_kind >> 1) & 15);  // never 0 for a listed tile
-        cur_full = __builtin_amdgcn_readfirstlane(pre_kind & 1);
-        cur_col = __builtin_amdgcn_readfirstlane(pre_col);
+        const int pre_kind = (int)((pre_kinds >> (8 * (cur_t & 3))) & 0xFFu);
+        quarters = (pre_kind >> 1) & 15;  // never 0 for a listed tile
+        cur_full = pre_kind & 1;
+        cur_col = pre_col;
       }
       const int qq = __builtin_ctz(quarters);
       quarters &= quarters - 1;
@@ -461,7 +463,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     using I3 = std::integral_constant<int, 3>;
 
     // block i of the stream is described by d[i & 3]
-    Blk d[4];
+    Blk d[4] = {};
     prefetch_meta();
     d[0] = next_blk();
     f32x16 oacc[4];
@@ -526,8 +528,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         prefetch_meta();
         // K_{b+2}, its mask words and V_b (issued two iterations ago) must have landed; the ten
         // youngest copies (this iteration's and the previous one's) may stay in flight
-        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-        __syncthreads();
+        // (wait and barrier as one statement: the library barrier would add a fence that waits for the
+        // metadata loads just issued; the LDS rings are only written by the copies counted here)
+        asm volatile("s_waitcnt vmcnt(10)\n\ts_barrier" ::: "memory");
         return false;
       };
       while (true) {
