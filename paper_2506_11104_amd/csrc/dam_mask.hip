@@ -488,6 +488,45 @@ __device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_
   return full ? 3 : 1;
 }
 
+// Classes of whole tiles for square tiles of width T, per head (pattern region, tile strictly below
+// the diagonal): the entries of tile (qt, kt) have the columns of key tile kt and exactly the offsets
+// T d - (T - 1) .. T d + (T - 1), d = qt - kt. So "some column matched" / "all columns matched" is a
+// property of kt alone and "some offset matched" / "all offsets matched" of d alone. The d classes
+// are stored reversed (d at position 64 dw - 1 - d), like the diagonal set, so that the 64 key tiles
+// of an occupancy word are 64 consecutive bits.
+__global__ void k_tile_classes(Geom g, const uint64_t *__restrict__ cbits, const uint64_t *__restrict__ rrev,
+                               uint64_t *__restrict__ col_any, uint64_t *__restrict__ col_all,
+                               uint64_t *__restrict__ off_any, uint64_t *__restrict__ off_all) {
+  const int lane = threadIdx.x, w = blockIdx.x, h = blockIdx.y;
+  const uint64_t *cb = cbits + (int64_t)h * g.pw;
+  const uint64_t *rr = rrev + (int64_t)h * g.pw;
+  const int T = g.tile_n;
+  const int64_t Q = (int64_t)g.pw * 64 - 1;
+  {
+    const int kt = w * 64 + lane;
+    const int64_t j0 = (int64_t)kt * T, j1 = j0 + T - 1;
+    const bool any = kt < g.nKt && range_any(cb, g.pw, j0, j1);
+    const bool all = kt < g.nKt && j1 <= Q && range_all(cb, j0, j1);
+    const uint64_t wa = __ballot(any), wf = __ballot(all);
+    if (lane == 0) {
+      col_any[(int64_t)h * g.occw + w] = wa;
+      col_all[(int64_t)h * g.occw + w] = wf;
+    }
+  }
+  {
+    const int64_t d = (int64_t)g.occw * 64 - 1 - ((int64_t)w * 64 + lane);
+    const int64_t a = d * T - (T - 1), b = d * T + (T - 1);  // offsets of the tile, a >= 1 when d >= 1
+    const bool live = d >= 1 && d < g.nQt;
+    const bool any = live && range_any(rr, g.pw, Q - b, Q - a);
+    const bool all = live && b <= Q && range_all(rr, Q - b, Q - a);
+    const uint64_t wa = __ballot(any), wf = __ballot(all);
+    if (lane == 0) {
+      off_any[(int64_t)h * g.occw + w] = wa;
+      off_all[(int64_t)h * g.occw + w] = wf;
+    }
+  }
+}
+
 // Pass 1 of the block index: which key tiles of query tile (h, qt) hold a kept entry / are full.
 // Tiles strictly below the diagonal and outside the true-mask block are decided by one lane each
 // (pattern_tile_flags); only the tiles on the diagonal or inside the true-mask block are evaluated
@@ -495,6 +534,10 @@ __device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_
 __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__restrict__ true_bits,
                                                    const uint64_t *__restrict__ cbits,
                                                    const uint64_t *__restrict__ rrev,
+                                                   const uint64_t *__restrict__ col_any,
+                                                   const uint64_t *__restrict__ col_all,
+                                                   const uint64_t *__restrict__ off_any,
+                                                   const uint64_t *__restrict__ off_all,
                                                    uint64_t *__restrict__ occ,
                                                    uint64_t *__restrict__ full, int *__restrict__ cnt) {
   extern __shared__ uint8_t flags[];  // [nKt] bit0 occupied, bit1 full, bit2 still to be evaluated
@@ -510,29 +553,57 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
   for (int kt = threadIdx.x; kt < g.nKt; kt += blockDim.x) flags[kt] = 0;
   __syncthreads();
   const int i0 = qt * g.tile_m;
+  // Square tiles, a whole row of tiles in the pattern region: 64 tiles at a time from the per-head
+  // class bitsets. Only a tile that has matched and unmatched columns AND matched and unmatched
+  // offsets needs the exact one-lane test for "full".
+  const bool by_class = g.tile_m == g.tile_n && i0 >= g.L && i0 + g.tile_m <= g.S;
   for (int kt = threadIdx.x; kt <= kmax; kt += blockDim.x) {
     const int j0 = kt * g.tile_n, j1 = min(j0 + g.tile_n - 1, g.S - 1);
     uint8_t f = 4;  // evaluate word by word
     if (i0 >= g.L && j1 <= i0) {
-      f = (uint8_t)pattern_tile_flags(cb, rr, g.pw, i0, i_last, j0, j1);
-      // a tile cut by the end of the sequence is never full (its bits past S are zero)
-      if (j0 + g.tile_n > g.S || i0 + g.tile_m > g.S) f &= 1;
+      bool exact = true;
+      if (by_class) {
+        const int d = qt - kt;  // >= 1 here
+        const int64_t pos = (int64_t)g.occw * 64 - 1 - d;
+        const uint64_t *ca = col_any + (int64_t)h * g.occw, *cf = col_all + (int64_t)h * g.occw;
+        const uint64_t *da = off_any + (int64_t)h * g.occw, *df = off_all + (int64_t)h * g.occw;
+        const bool c_any = (ca[kt >> 6] >> (kt & 63)) & 1, c_all = (cf[kt >> 6] >> (kt & 63)) & 1;
+        const bool d_any = (da[pos >> 6] >> (pos & 63)) & 1, d_all = (df[pos >> 6] >> (pos & 63)) & 1;
+        if (!(c_any && !c_all && d_any && !d_all)) {
+          exact = false;
+          f = (uint8_t)(((c_any || d_any) ? 1 : 0) | ((c_all || d_all) ? 3 : 0));
+        }
+      }
+      if (exact) {
+        f = (uint8_t)pattern_tile_flags(cb, rr, g.pw, i0, i_last, j0, j1);
+        // a tile cut by the end of the sequence is never full (its bits past S are zero)
+        if (j0 + g.tile_n > g.S || i0 + g.tile_m > g.S) f &= 1;
+      }
     }
     flags[kt] = f;
   }
   __syncthreads();
   const int words = g.tile_m * g.wpr;
-  for (int kt = wave; kt <= kmax; kt += 4) {
-    if (!(flags[kt] & 4)) continue;
-    bool any = false, all = true;
-    for (int w = lane; w < words; w += 64) {
-      const uint64_t m = mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + w % g.wpr);
-      any |= m != 0;
-      all &= m == ~0ull;
+  // the tiles still to be evaluated, found 64 at a time (one flag per lane, one ballot) and dealt to
+  // the four waves in turn
+  int dealt = 0;
+  for (int base = 0; base <= kmax; base += 64) {
+    uint64_t need = __ballot(base + lane <= kmax && (flags[base + lane] & 4));
+    while (need) {
+      const int kt = base + __ffsll((unsigned long long)need) - 1;
+      need &= need - 1;
+      if ((dealt++ & 3) != wave) continue;
+      bool any = false, all = true;
+      for (int w = lane; w < words; w += 64) {
+        const uint64_t m = mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + w % g.wpr);
+        any |= m != 0;
+        all &= m == ~0ull;
+      }
+      const bool t_any = __ballot(any) != 0;
+      const bool t_all = __ballot(!all) == 0;
+      // bit 2 stays set: the other waves may still be reading it to deal out the same tiles
+      if (lane == 0) flags[kt] = (uint8_t)(4 | (t_any ? 1 : 0) | (t_all ? 2 : 0));
     }
-    const bool t_any = __ballot(any) != 0;
-    const bool t_all = __ballot(!all) == 0;
-    if (lane == 0) flags[kt] = (uint8_t)((t_any ? 1 : 0) | (t_all ? 2 : 0));
   }
   __syncthreads();
   int mine = 0;
@@ -632,6 +703,21 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       // element words, and which key quarters of the tile hold a kept entry
       const bool is_full = (fl[kt >> 6] >> (kt & 63)) & 1;
       int quarters = 0;
+      if (words == 256 && g.wpr == 2) {
+        // 128 x 128 tiles: four words per lane, evaluated together so that their loads overlap
+        uint64_t m[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int w = lane + 64 * u;
+          m[u] = is_full ? ~0ull : mask_word(g, tb, cb, rr, qt * 128 + (w >> 1), kt * 2 + (w & 1));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (tile_bits) tile_bits[t * 256 + lane + 64 * u] = m[u];
+          if ((uint32_t)m[u]) quarters |= 1 << (2 * (lane & 1));
+          if (m[u] >> 32) quarters |= 2 << (2 * (lane & 1));
+        }
+      } else
       for (int w = lane; w < words; w += 64) {
         const int wi = w % g.wpr;
         const uint64_t m = is_full ? ~0ull : mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + wi);
@@ -765,7 +851,7 @@ struct Workspace {
   unsigned *xmin_bits, *theta_key;
   uint64_t *vslices, *dslices;
   uint8_t *diag_flag, *vert_flag;
-  uint64_t *cbits, *rrev, *occ, *full;
+  uint64_t *cbits, *rrev, *occ, *full, *col_any, *col_all, *off_any, *off_all;
   int *tile_cnt, *row_cnt;
   size_t bytes;
 };
@@ -804,6 +890,10 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   w.vert_flag = c.take<uint8_t>(HL);
   w.cbits = c.take<uint64_t>((size_t)g.H * g.pw);
   w.rrev = c.take<uint64_t>((size_t)g.H * g.pw);
+  w.col_any = c.take<uint64_t>((size_t)g.H * g.occw);
+  w.col_all = c.take<uint64_t>((size_t)g.H * g.occw);
+  w.off_any = c.take<uint64_t>((size_t)g.H * g.occw);
+  w.off_all = c.take<uint64_t>((size_t)g.H * g.occw);
   w.occ = c.take<uint64_t>((size_t)g.H * g.nQt * g.occw);
   w.full = c.take<uint64_t>((size_t)g.H * g.nQt * g.occw);
   w.tile_cnt = c.take<int>((size_t)g.H * g.nQt);
@@ -889,7 +979,9 @@ extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, c
   }
   // a4 + a5: tile occupancy, CSR offsets, tile bits
   if (want_blocks) {
-    k_tile_scan<<<dim3(g.nQt, g.H), 256, (size_t)g.nKt, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, w.tile_cnt);
+    k_tile_classes<<<dim3(g.occw, g.H), 64, 0, stream>>>(g, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any, w.off_all);
+    k_tile_scan<<<dim3(g.nQt, g.H), 256, (size_t)g.nKt, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
+                                                                 w.off_all, w.occ, w.full, w.tile_cnt);
     k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total);
     if (o->blk_col || o->blk_kind || o->tile_bits)
       k_tile_fill<<<dim3(g.nQt, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,

@@ -366,6 +366,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const unsigned lds_kv = __builtin_amdgcn_readfirstlane(lds_base + wave * 1024);              // this wave's part of a K/V slot
   const unsigned lds_bits = __builtin_amdgcn_readfirstlane(lds_base + kBitsRing + wave * 256);  // ... of a bits slot
 
+  // The first two iterations of an item multiply weights that are exactly zero (the leading dummy
+  // blocks) with whatever the V ring holds: it has to be finite. Later items find the previous item's
+  // V rows there; the first one would find what an earlier kernel left in LDS, so clear the ring once.
+  for (int at = tid * 16; at < kRing * kBlkBytes; at += 256 * 16)
+    *reinterpret_cast<uint4 *>(lds + kVRing + at) = make_uint4(0u, 0u, 0u, 0u);
+
   const int G = a.Hq / a.Hkv, n_pairs = a.B * a.Hkv, per_pair = G * a.nQt;
   const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);  // XCC_ID, 4 bits
   int hop = 0;
