@@ -6,8 +6,8 @@ dam_mask_build (matched patterns -> tile pool + block index at S = 32768) follow
 dam_sparse_attn_prefill over the listed tiles. `value` is effective TFLOP/s on kept entries,
 4 * head_dim * nnz / step time, with every input resident in HBM before the timed region.
 The same run also reports (extra keys of the one JSON line) the prefill kernel against the bf16
-MFMA roofline, the decode workload (c5) and the attention-map mask build (c2 shape) against the
-HBM roofline, and the CPU oracle timed on a bounded sample of the same prefill workload.
+MFMA roofline, the decode workload (c5) and the attention-map mask build (c2 and c4 shapes) against
+the HBM roofline, and the CPU oracle timed on a bounded sample of the same prefill workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2] [--no-decode] [--no-cpu]
 """
@@ -242,33 +242,55 @@ def bench_decode(args, torch, B, wl):
                          "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
 
 
-def bench_mask_from_map(args, torch, B, wl):
-    """a1-a3 (+ extension) from a captured attention map: the c2 shape, 32 maps of 1024 x 1024."""
-    w = wl.WORKLOADS["c2"]
+def bench_mask_from_map(args, torch, B, wl, name):
+    """a1-a3 from a captured attention map (true mask + matched patterns at S = L), and for c4 also the
+    whole build at the configuration's S (extension, block index, tile pool)."""
+    w = wl.WORKLOADS[name]
     Q, K, V = wl.qkv_structured(w)
-    A = torch.from_numpy(wl.capture_map(Q, K, w.pcl, w.hq // w.hkv)).cuda()
     H, L = w.hq, w.pcl
+    A = torch.from_numpy(wl.capture_map(Q[:, :L], K[:, :L], L, w.hq // w.hkv)).cuda()
+    del Q, K, V
+
+    def timed(fn, n):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ev = events(2)
+        ev[0].record()
+        for _ in range(n):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / n
+
     p = B.MaskParams(B.DAM_FROM_ATTN_MAP, H, L, L, 128, 128, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
     ws = B.mask_workspace(p, "cuda")
     o = B.MaskOut()
     tb = torch.empty((H, L, L // 64), dtype=torch.int64, device="cuda")
     fl = [torch.empty((H, L), dtype=torch.uint8, device="cuda") for _ in range(2)]
     o.true_bits, o.diag_flag, o.vert_flag = tb.data_ptr(), fl[0].data_ptr(), fl[1].data_ptr()
-    for _ in range(3):
-        B.dam_mask_build(p, A, None, None, None, o, ws)
-    torch.cuda.synchronize()
-    n = 20
-    ev = events(2)
-    ev[0].record()
-    for _ in range(n):
-        B.dam_mask_build(p, A, None, None, None, o, ws)
-    ev[1].record()
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / n
+    ms = timed(lambda: B.dam_mask_build(p, A, None, None, None, o, ws), 20)
     nbytes = 2 * H * L * (L + 1) + H * L * L // 8      # lower triangle of A once + true bits
-    return {"workload": "c2 map (32 x 1024 x 1024 fp32) -> true mask + matched patterns", "ms": ms, "bytes": nbytes,
-            "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+    res = {"workload": f"{name} map ({H} x {L} x {L} fp32) -> true mask + matched patterns", "ms": ms, "bytes": nbytes,
+           "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+    if name == "c4":
+        S = w.seq
+        sized = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu, attn_sum=A)
+        torch.cuda.synchronize()
+        p2 = B.MaskParams(B.DAM_FROM_ATTN_MAP, H, L, S, 128, 128, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
+        ws2 = B.mask_workspace(p2, "cuda")
+        o2 = B.MaskOut()
+        o2.true_bits, o2.diag_flag, o2.vert_flag = tb.data_ptr(), fl[0].data_ptr(), fl[1].data_ptr()
+        tot = torch.zeros(1, dtype=torch.int64, device="cuda")
+        o2.blk_row_ptr, o2.blk_col, o2.blk_kind = sized.blk_row_ptr.data_ptr(), sized.blk_col.data_ptr(), sized.blk_kind.data_ptr()
+        o2.tile_bits, o2.blk_capacity, o2.blk_total = sized.tile_bits.data_ptr(), sized.n_tiles, tot.data_ptr()
+        ms2 = timed(lambda: B.dam_mask_build(p2, A, None, None, None, o2, ws2), 10)
+        nb2 = nbytes + sized.n_tiles * (128 * 128 // 8 + 5) + 4 * H * (S // 128 + 1)
+        res["whole_build"] = {"seq": S, "listed_tiles": sized.n_tiles, "ms": ms2, "bytes": nb2,
+                              "roofline": {"bound": "hbm", "achieved": nb2 / (ms2 * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                           "unit": "GB/s", "frac": nb2 / (ms2 * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+    return res
 
 
 def main():
@@ -314,7 +336,10 @@ def main():
     del ctx
     torch.cuda.empty_cache()
     if not args.no_maskmap:
-        line["mask_build_from_map"] = bench_mask_from_map(args, torch, B, wl)
+        line["mask_build_from_map"] = bench_mask_from_map(args, torch, B, wl, "c2")
+        torch.cuda.empty_cache()
+        line["mask_build_from_map_c4"] = bench_mask_from_map(args, torch, B, wl, "c4")
+        torch.cuda.empty_cache()
     if not args.no_decode:
         line["decode"] = bench_decode(args, torch, B, wl)
     print(json.dumps(line))
