@@ -26,6 +26,12 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernels, measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs of this
+# script with --copy-calibration, scaled by what the same counters read for a plain 1 GiB copy: x2.00 and x1.00);
+# the summary with the commands is profiles/prefill_c3_decode_c5_hbm_traffic_pmc.txt. They belong to the default
+# workloads (c3 prefill, c5 decode) and are reported as the roofline objects' `traffic`.
+MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.75e9, "k_decode_partial/c5": 5.32e8}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -239,7 +245,8 @@ def bench_decode(args, torch, B, wl):
             "decode_us": dec_us, "kept_per_list": sb / (items * w.head_dim * 4), "union_bytes": ub, "sum_bytes": sb,
             "gbs_union": ub / (dec_us * 1e-6) / 1e9, "gbs_sum": sb / (dec_us * 1e-6) / 1e9,
             "roofline": {"bound": "hbm", "achieved": ub / (dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+                         "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                         "traffic": MEASURED_TRAFFIC_BYTES["k_decode_partial/c5"]}}
 
 
 def bench_mask_from_map(args, torch, B, wl, name):
@@ -328,7 +335,8 @@ def main():
         "tflops_listed_tiles_prefill_only": res["tflops_tiles_prefill"],
         "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16_pipe", "achieved": res["tflops_kept_prefill"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": res["tflops_kept_prefill"] / PEAK_BF16_TFLOPS,
-                     "traffic": None, "achieved_listed_tiles": res["tflops_tiles_prefill"],
+                     "traffic": MEASURED_TRAFFIC_BYTES["k_prefill_bf16_pipe/c3"] if args.workload == "c3" else None,
+                     "achieved_listed_tiles": res["tflops_tiles_prefill"],
                      "frac_listed_tiles": res["tflops_tiles_prefill"] / PEAK_BF16_TFLOPS},
     }
     if not args.no_cpu:
