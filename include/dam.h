@@ -89,15 +89,15 @@ typedef struct {
 /* Outputs of dam_mask_build. Every pointer is a device pointer owned by the caller; any of them may
  * be NULL when that output is not wanted (exceptions are stated).
  *
- *   true_bits  [H][L][ceil(L/64)] u64   bit (j % 64) of word j / 64 of row i is m[i][j]. Written in
- *                                       FROM_ATTN_MAP mode (required there when S > 0 outputs that
- *                                       depend on it are requested: it is then also read back);
- *                                       read in FROM_PATTERNS mode when pcl > 0.
- *   diag_cnt, vert_cnt [H][L] i32       kept entries on each diagonal / column of the true mask.
- *   diag_flag, vert_flag [H][P] u8      1 = matched.  P = L in FROM_ATTN_MAP mode (written; required
- *                                       when any S-sized output is requested), P = S in
- *                                       FROM_PATTERNS mode, where they are not written: the inputs
- *                                       diag_in / vert_in are used instead.
+ *   true_bits  [H][L][ceil(L/64)] u64   bit (j % 64) of word j / 64 of row i is m[i][j].
+ *                                       FROM_ATTN_MAP: written, and required (the later steps of the
+ *                                       same call read it back). FROM_PATTERNS: an input, read when
+ *                                       pcl > 0, never written.
+ *   diag_cnt, vert_cnt [H][L] i32       kept entries on each diagonal / column of the true mask
+ *                                       (FROM_ATTN_MAP only).
+ *   diag_flag, vert_flag [H][L] u8      1 = matched (FROM_ATTN_MAP only; when NULL the flags live in
+ *                                       the workspace). In FROM_PATTERNS mode nothing is written here:
+ *                                       the matched sets are the inputs diag_in / vert_in, [H][S].
  *   bmin       [1] f32                  the minimum used by the threshold.
  *   blk_row_ptr [H][nQt + 1] i32        CSR offsets into blk_col; offsets are global over all maps
  *                                       (blk_row_ptr[h][0] == blk_row_ptr[h-1][nQt]),
@@ -108,7 +108,9 @@ typedef struct {
  *                                       strictly below the diagonal and inside S). Bits 1..4: key
  *                                       quarter q of the tile, columns [q tile_n/4, (q+1) tile_n/4),
  *                                       holds a kept entry (bit 1 + q); the attention kernel skips
- *                                       empty quarters.
+ *                                       empty quarters. The attention kernel reads this array in
+ *                                       aligned 32-bit words: 4-byte aligned, and allocated up to a
+ *                                       multiple of 4 bytes.
  *   tile_bits  [blk_capacity][tile_m][tile_n / 64] u64   element bits of listed tile t at index t
  *                                       (also for full tiles: all ones); bits beyond S are 0.
  *   blk_total  [1] i64                  number of listed tiles, valid even when it exceeds
@@ -161,7 +163,8 @@ int dam_mask_build(const dam_mask_params *params, const float *attn_sum, const f
  * mask (masked entries are -inf before the softmax). A row without kept keys gives O[i] = 0 and
  * lse[i] = -inf. Query head h reads KV head h / (hq / hkv).
  * dtype DAM_BF16: bf16 in, fp32 accumulation on the matrix cores, bf16 out (round to nearest even);
- *                 head_dim 128, tiles 128 x 128.
+ *                 head_dim 128, tiles 128 x 128; the rows of one K or V head must span less than
+ *                 4 GiB (seq * stride[2] * 2 bytes), otherwise DAM_ERR_UNSUPPORTED.
  * dtype DAM_F32:  fp32 throughout; head_dim 64 or 128, tiles of 64 or 128 in either direction.
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
