@@ -124,6 +124,29 @@ def test_threshold_boundary_values_round_like_the_oracle():
     run_from_map(A, None, 300, 64, 64, 1.0, 1e-8, float(theta) - 1e-8, 0.8)
 
 
+@pytest.mark.parametrize("L", [256, 202])       # the row-streaming kernel (L % 4 == 0) and the general one
+@pytest.mark.parametrize("tau", [0.3, 0.0, -0.5, 1e30])
+def test_special_values_in_the_map_follow_the_fixed_sequence(L, tau):
+    """NaN, infinities, negative zero, negative, denormal and huge entries: the threshold comparison
+    has to reproduce what the op-by-op fp32 sequence does with them (a NaN mean clamps to eps)."""
+    rng = np.random.default_rng(23)
+    H = 2
+    A = np.tril(rng.random((H, L, L)).astype(np.float32) ** 6)
+    special = np.array([np.nan, np.inf, -np.inf, -0.0, 0.0, -1.0, -1e-30, 1e-45, 1e-39, 3e38, 1e-8, 2e-8, 1.0],
+                       np.float32)
+    i, j = np.tril_indices(L)
+    pick = rng.choice(len(i), 4000, replace=False)
+    A[0, i[pick], j[pick]] = special[rng.integers(0, len(special), len(pick))]
+    A[1, i[pick], j[pick]] = special[rng.integers(0, len(special), len(pick))]
+    run_from_map(A, None, L + 100, 64, 64, 0.5, 1e-8, tau, 0.8)
+    run_from_map(A, None, L + 100, 64, 64, 1.0, 1e-8, tau, 0.8)
+    # with a count matrix: zero, tiny, negative and infinite counts as well
+    C = np.tril(np.ones((H, L, L), np.float32))
+    cs = np.array([0.0, 1e-45, 1e-8, 2.0, 3.0, -1.0, np.inf], np.float32)
+    C[0, i[pick], j[pick]] = cs[rng.integers(0, len(cs), len(pick))]
+    run_from_map(A, C, L + 100, 64, 64, 0.5, 1e-8, tau, 0.8)
+
+
 def test_from_patterns_with_and_without_true_mask():
     rng = np.random.default_rng(22)
     H, S, L = 4, 1000, 100
