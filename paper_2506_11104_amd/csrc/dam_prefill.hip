@@ -290,9 +290,15 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(sA[e], sA[e + 1]), mx);
   mx = fmaxf(mx, sA[15]);
   mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m_run, mx);
+  // m_run is the reference the weights are taken against, not necessarily the running maximum: it
+  // only moves when the maximum has grown past it by more than 8 in log2 units (weights then stay
+  // below 2^8, far inside the range of bf16 and of the fp32 sums), so that O rarely has to be rescaled.
+  // The quotient O / l at the end does not depend on the reference. (-inf) - (-inf) is NaN: no move.
+  const float m_top = fmaxf(m_run, mx);
+  const bool move = (m_top - m_run) * c2 > 8.0f;
+  const float m_new = move ? m_top : m_run;
   const float m_ref = m_new == -INFINITY ? 0.0f : m_new;
-  const float corr = __builtin_amdgcn_exp2f((m_run - m_ref) * c2);
+  const float corr = move ? __builtin_amdgcn_exp2f((m_run - m_ref) * c2) : 1.0f;
   const float off = m_ref * c2;
   m_run = m_new;
   float psum = 0.0f;
