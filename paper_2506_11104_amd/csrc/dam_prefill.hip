@@ -289,7 +289,13 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
 #pragma unroll
   for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(sA[e], sA[e + 1]), mx);
   mx = fmaxf(mx, sA[15]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  {
+    // the other half-wave's maximum of the same query row: one swap of the 32-lane halves (operands
+    // both mx: the results are the lower half's values in all lanes, and the upper half's)
+    typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+    const u32x2_t sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+    mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+  }
   // m_run is the reference the weights are taken against, not necessarily the running maximum: it
   // only moves when the maximum has grown past it by more than 8 in log2 units (weights then stay
   // below 2^8, far inside the range of bf16 and of the fp32 sums), so that O rarely has to be rescaled.
