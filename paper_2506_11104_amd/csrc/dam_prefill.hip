@@ -304,8 +304,8 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   const bool move = (m_top - m_run) * c2 > 8.0f;
   const float m_new = move ? m_top : m_run;
   const float m_ref = m_new == -INFINITY ? 0.0f : m_new;
-  const float corr = move ? __builtin_amdgcn_exp2f((m_run - m_ref) * c2) : 1.0f;
   const float off = m_ref * c2;
+  const float m_old = m_run;
   m_run = m_new;
   float psum = 0.0f;
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
@@ -317,7 +317,6 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
     // the row sum is taken over the rounded weights the P V product uses
     psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pCur[e / 2]), ones, psum, false);
   }
-  l_run = l_run * corr + psum;
   // keep the weights of block b inside this block of code (they are only consumed an iteration later
   // and would otherwise be sunk below the matrix work)
 #pragma unroll
@@ -336,14 +335,17 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
     __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 1, 0);
   }
   __builtin_amdgcn_sched_barrier(0);
-  // O was accumulated against the old maximum: rescale once P_{b-1} V_{b-1} is in (rarely needed
-  // after the first few blocks of a row)
-  if (__ballot(corr != 1.0f)) {
+  // O and the row sum were accumulated against the old reference: when some row's reference moved,
+  // rescale them, after P_{b-1} V_{b-1} is in (rare after the first blocks of a row)
+  if (__ballot(move)) {
+    const float corr = move ? __builtin_amdgcn_exp2f((m_old - m_ref) * c2) : 1.0f;  // old = -inf: 0
+    l_run *= corr;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[db][e] *= corr;
   }
+  l_run += psum;
 }
 
 // RAGGED: the sequence length is not a multiple of the block size, so the last block of a row of tiles
