@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A, 
 }
 
 // The same for the common case (no count matrix, L a multiple of 4) at streaming speed: one wave per
-// row, 16-byte loads, every live 256-key segment of a 4096-key span in flight at once, and the row's
+// row, 16-byte loads, the live 256-key segments of a 2048-key span in flight at once, and the row's
 // words gathered into lanes so that they leave as one coalesced store (single 8-byte stores from one
 // lane made the store path the bottleneck). Short and long rows are paired across blocks.
 __global__ __launch_bounds__(256) void k_true_mask_rows(const float *__restrict__ A, int L, int tbw,
@@ -205,16 +205,17 @@ __global__ __launch_bounds__(256) void k_true_mask_rows(const float *__restrict_
   uint64_t *out = true_bits + ((int64_t)h * L + i) * tbw;
   const int nseg = i / 256 + 1;  // segments with a key <= i
   const int c = lane & 3;
-  for (int s0 = 0; s0 * 4 < tbw; s0 += 16) {
-    float4 v[16];
+  constexpr int kSeg = 8;  // 256-key segments in flight per pass
+  for (int s0 = 0; s0 * 4 < tbw; s0 += kSeg) {
+    float4 v[kSeg];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
+    for (int u = 0; u < kSeg; ++u) {
       const int j0 = (s0 + u) * 256 + lane * 4;
       v[u] = (s0 + u < nseg && j0 < L) ? row[(s0 + u) * 64 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     uint64_t mine = 0;  // word s0 * 4 + lane of the row
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
+    for (int u = 0; u < kSeg; ++u) {
       if (s0 + u < nseg) {  // wave-uniform
         const int j0 = (s0 + u) * 256 + lane * 4;
         float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(256) void k_true_mask_rows(const float *__restrict_
         }
       }
     }
-    if (s0 * 4 + lane < tbw) out[s0 * 4 + lane] = mine;
+    if (lane < 4 * kSeg && s0 * 4 + lane < tbw) out[s0 * 4 + lane] = mine;
   }
 }
 
@@ -325,6 +326,7 @@ __global__ __launch_bounds__(256) void k_pattern_finish(const uint64_t *__restri
   const int p = word * 64 + lane;
   int nv = 0, nd = 0;
   // rows above p hold nothing of pattern p: start at the chunk of the word's first pattern
+#pragma unroll 4
   for (int chunk = word * 64 / kChunkRows + wave; chunk < n_chunks; chunk += 4) {
     const int64_t at = (((int64_t)h * n_chunks + chunk) * kSlices) * tbw + word;
 #pragma unroll
