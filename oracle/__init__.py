@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
             ctypes.c_int32, ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(ctypes.c_uint8), ctypes.c_int32,
             ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64), ctypes.c_int64, ctypes.c_double,
             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        _LIB.dam_oracle_capture.restype = None
+        _LIB.dam_oracle_capture.argtypes = [ctypes.POINTER(ctypes.c_float)] * 2 + [
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64, ctypes.c_double,
+            ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         _LIB.dam_oracle_threads.restype = ctypes.c_int
         _LIB.dam_oracle_threads.argtypes = []
     return _LIB
@@ -111,6 +115,24 @@ class MaskArtefact:
         tm = self.true_mask[h] if self.true_mask is not None else None
         return (_ptr(tm, ctypes.c_uint8), ctypes.c_int32(self.L), _ptr(self.diag_flag[h], ctypes.c_uint8),
                 _ptr(self.vert_flag[h], ctypes.c_uint8), ctypes.c_int32(self.P))
+
+
+def capture(Q, K, L: int, attn_sum: Optional[np.ndarray] = None, attn_cnt: Optional[np.ndarray] = None,
+            scale: Optional[float] = None, want_cnt: bool = True):
+    """Sec. 4.2.1 / 4.2.2: add the causal attention probabilities of one captured sequence
+    (Q [Hq][n][d], K [Hkv][n][d], n <= L) to the statistics A, C [Hq][L][L] (fp32; created as zeros
+    when not given). Returns (A, C); C is None when want_cnt is false and none was given."""
+    Q, K = _f32(Q), _f32(K)
+    Hq, n, d = Q.shape
+    Hkv = K.shape[0]
+    assert K.shape[1] == n and K.shape[2] == d and Hq % Hkv == 0 and n <= L
+    A = np.zeros((Hq, L, L), np.float32) if attn_sum is None else attn_sum
+    C = attn_cnt if attn_cnt is not None else (np.zeros((Hq, L, L), np.float32) if want_cnt else None)
+    assert A.dtype == np.float32 and A.flags.c_contiguous and A.shape == (Hq, L, L)
+    sc = float(scale) if scale else 1.0 / float(np.sqrt(np.float64(d)))
+    lib().dam_oracle_capture(_ptr(Q, ctypes.c_float), _ptr(K, ctypes.c_float), Hq, Hkv, n, d, L,
+                             ctypes.c_double(sc), _ptr(A, ctypes.c_float), _ptr(C, ctypes.c_float))
+    return A, C
 
 
 def boxcox(attn_sum: np.ndarray, attn_cnt: Optional[np.ndarray], lam: float, eps: float):

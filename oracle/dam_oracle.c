@@ -14,7 +14,8 @@
  *
  * Pins (tests/test_oracle_*.py): Box-Cox closed forms and the value 2.00 printed in the paper's
  * App. B table; threshold special cases; match scores against literally materialised pattern
- * matrices; prefix stability of the extension; re-expansion of the block index; attention against
+ * matrices; the capture against closed-form uniform attention, row sums and a library softmax;
+ * prefix stability of the extension; re-expansion of the block index; attention against
  * dense causal attention, a brute-force numpy softmax, convexity, single-key and LSE-merge
  * identities. No function here is "parity unpinned" for lambda in {0.5, 1}; lambda = 0 and general
  * lambda (logf / powf, not correctly rounded) are pinned only up to a few ulp at the threshold
@@ -298,6 +299,43 @@ void dam_oracle_attend_rows(const float *q_rows, const float *K, const float *V,
                 out + a * d, lse + a);
     free(idx);
   }
+}
+
+/* Sec. 4.2.1 / 4.2.2, pattern capture: one sequence of n <= L tokens is run with full causal
+ * attention and its attention probabilities are added to the accumulated statistics,
+ *   A[h][i][j] += softmax_j(q_i . k_j * scale)   and   C[h][i][j] += 1     for j <= i < n
+ * ("attention weights summed over batches" and "the number of times a position pair was valid").
+ * Q [Hq][n][d], K [Hkv][n][d] (query head h reads KV head h / (Hq / Hkv)); A, C [Hq][L][L] fp32,
+ * C may be NULL. The softmax is evaluated in fp64 and rounded to fp32 once, then added to the fp32
+ * sum (the paper fixes no storage precision; fp32 statistics is this build's reading). */
+void dam_oracle_capture(const float *Q, const float *K, int32_t Hq, int32_t Hkv, int64_t n, int32_t d,
+                        int64_t L, double scale, float *A, float *C) {
+  const int32_t group = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic, 8)
+  for (int64_t h = 0; h < Hq; ++h)
+    for (int64_t i = 0; i < n; ++i) {
+      const float *q = Q + (h * n + i) * d;
+      const float *Kh = K + (int64_t)(h / group) * n * d;
+      double *s = (double *)malloc((size_t)(i + 1) * sizeof(double));
+      double smax = -INFINITY;
+      for (int64_t j = 0; j <= i; ++j) {
+        double dot = 0.0;
+        for (int32_t t = 0; t < d; ++t) dot += (double)q[t] * (double)Kh[j * d + t];
+        s[j] = dot * scale;
+        if (s[j] > smax) smax = s[j];
+      }
+      double wsum = 0.0;
+      for (int64_t j = 0; j <= i; ++j) {
+        s[j] = exp(s[j] - smax);
+        wsum += s[j];
+      }
+      for (int64_t j = 0; j <= i; ++j) {
+        const int64_t at = (h * L + i) * L + j;
+        A[at] = A[at] + (float)(s[j] / wsum);
+        if (C) C[at] = C[at] + 1.0f;
+      }
+      free(s);
+    }
 }
 
 /* Threads the parallel loops above use (reported next to every oracle timing). */
