@@ -1,12 +1,15 @@
 /*
  * dam.h -- C ABI of the DAM (Dynamic Attention Mask) hot path for AMD MI355X (gfx950).
  *
- * Three operations, all enqueued on a caller-supplied HIP stream:
+ * The operations, all enqueued on a caller-supplied HIP stream:
  *
  *   dam_mask_build            attention statistics captured at length L  ->  per-head sparse mask
  *                             (paper Sec. 4.2.2 - 4.2.4 and Sec. 4.3), emitted as an element bitmask
  *                             pooled by tile plus a compressed block index, and optionally as
  *                             per-row kept-key lists and a dense bitmask.
+ *   dam_capture_accumulate    attention probabilities of a captured sequence summed into those
+ *                             statistics (paper Sec. 4.2.1 - 4.2.2); dam_mask_build_from_qk fuses one
+ *                             capture with the mask build.
  *   dam_sparse_attn_prefill   masked causal self-attention over the kept (query, key) entries only
  *                             (paper Sec. 3 and the last two equations of Sec. 4.3).
  *   dam_sparse_attn_decode    the same formula for one new query row per (sequence, head), reading
@@ -154,6 +157,53 @@ size_t dam_mask_build_workspace(const dam_mask_params *params);
 int dam_mask_build(const dam_mask_params *params, const float *attn_sum, const float *attn_cnt,
                    const uint8_t *diag_in, const uint8_t *vert_in, const dam_mask_out *out,
                    void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * dam_capture_accumulate, dam_mask_build_from_qk  (the step before the mask rule)
+ *
+ * Sec. 4.2.1 / 4.2.2: a sequence truncated to the pattern capture length is run with full causal
+ * attention and its attention probabilities are summed into the statistics,
+ *     A[h][i][j] += softmax_j(q_i . k_j * scale),   C[h][i][j] += 1      for j <= i < len,
+ * over as many sequences as the caller captures (one call each). Query head h reads KV head
+ * h / (hq / hkv). bf16 inputs use the matrix cores (head_dim 128) with fp32 accumulation, the
+ * softmax is evaluated in fp32; the sums are fp32.
+ *
+ * dam_mask_build_from_qk is dam_mask_build (DAM_FROM_ATTN_MAP, attn_cnt == NULL) for ONE captured
+ * sequence of exactly pcl tokens, fused with its capture: the probabilities are compared with the
+ * threshold as they are produced and the map A is never written. Because the probabilities are
+ * fp32 results of a different operation order than a stored map would have, true-mask bits of
+ * entries whose probability lies within rounding distance of the threshold may differ from a build
+ * that goes through a stored map; everything after the true mask is the same computation on
+ * those bits.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t hq, hkv;
+  int32_t len;          /* tokens of the captured sequence, 1 <= len <= pcl                        */
+  int32_t pcl;          /* L: side of the statistics matrices                                      */
+  int32_t head_dim;     /* 128 for the matrix-core path; any multiple of 8 up to 256 otherwise     */
+  int32_t dtype;        /* dam_dtype of q and k                                                    */
+  float scale;          /* logit scale; 0 means 1 / sqrt(head_dim)                                 */
+  int64_t q_stride[2];  /* element strides of the head and position index; head_dim contiguous,    */
+  int64_t k_stride[2];  /*   rows 16-byte aligned                                                  */
+} dam_capture_params;
+
+size_t dam_capture_workspace(const dam_capture_params *params);
+
+/* q         device [hq][len][head_dim], k device [hkv][len][head_dim] by the strides above.
+ * attn_sum  device f32 [hq][pcl][pcl], read and written (the caller zeroes it before the first
+ *           capture). attn_cnt the same for the counts, or NULL.
+ * ws        device workspace of at least dam_capture_workspace(params) bytes.
+ * pcl up to 8192. Errors as for the other entry points. */
+int dam_capture_accumulate(const dam_capture_params *params, const void *q, const void *k,
+                           float *attn_sum, float *attn_cnt, void *ws, size_t ws_bytes, void *stream);
+
+size_t dam_mask_build_from_qk_workspace(const dam_mask_params *params, const dam_capture_params *capture);
+
+/* params    as for dam_mask_build; mode must be DAM_FROM_ATTN_MAP, n_maps == capture->hq,
+ *           pcl == capture->pcl == capture->len (2 <= pcl <= 8192).
+ * q, k      as above. out, ws, stream as for dam_mask_build (out->true_bits is required and written). */
+int dam_mask_build_from_qk(const dam_mask_params *params, const dam_capture_params *capture, const void *q,
+                           const void *k, const dam_mask_out *out, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * dam_sparse_attn_prefill

@@ -67,7 +67,14 @@ class DecodeParams(ctypes.Structure):
                 ("o_stride", ctypes.c_int64 * 2)]
 
 
-EXPORTS = ["dam_mask_build_workspace", "dam_mask_build", "dam_sparse_attn_prefill_workspace",
+class CaptureParams(ctypes.Structure):
+    _fields_ = [("hq", ctypes.c_int32), ("hkv", ctypes.c_int32), ("len", ctypes.c_int32), ("pcl", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_stride", ctypes.c_int64 * 2), ("k_stride", ctypes.c_int64 * 2)]
+
+
+EXPORTS = ["dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
+           "dam_mask_build_from_qk_workspace", "dam_mask_build_from_qk", "dam_sparse_attn_prefill_workspace",
            "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode", "dam_version"]
 
 _lib = None
@@ -86,6 +93,15 @@ def lib() -> ctypes.CDLL:
         L.dam_mask_build_workspace.argtypes = [ctypes.POINTER(MaskParams)]
         L.dam_mask_build.restype = ctypes.c_int
         L.dam_mask_build.argtypes = [ctypes.POINTER(MaskParams), vp, vp, vp, vp, ctypes.POINTER(MaskOut), vp, sz, vp]
+        L.dam_capture_workspace.restype = sz
+        L.dam_capture_workspace.argtypes = [ctypes.POINTER(CaptureParams)]
+        L.dam_capture_accumulate.restype = ctypes.c_int
+        L.dam_capture_accumulate.argtypes = [ctypes.POINTER(CaptureParams), vp, vp, vp, vp, vp, sz, vp]
+        L.dam_mask_build_from_qk_workspace.restype = sz
+        L.dam_mask_build_from_qk_workspace.argtypes = [ctypes.POINTER(MaskParams), ctypes.POINTER(CaptureParams)]
+        L.dam_mask_build_from_qk.restype = ctypes.c_int
+        L.dam_mask_build_from_qk.argtypes = [ctypes.POINTER(MaskParams), ctypes.POINTER(CaptureParams), vp, vp,
+                                             ctypes.POINTER(MaskOut), vp, sz, vp]
         L.dam_sparse_attn_prefill_workspace.restype = sz
         L.dam_sparse_attn_prefill_workspace.argtypes = [ctypes.POINTER(AttnParams)]
         L.dam_sparse_attn_prefill.restype = ctypes.c_int
@@ -154,18 +170,68 @@ def dam_mask_build(params: MaskParams, attn_sum, attn_cnt, diag_in, vert_in, out
     _check("dam_mask_build", st)
 
 
+def capture_params(q: torch.Tensor, k: torch.Tensor, L: int, scale: float = 0.0) -> CaptureParams:
+    """q [Hq][n][d], k [Hkv][n][d] (d contiguous): one captured sequence of n <= L tokens."""
+    Hq, n, d = q.shape
+    assert k.shape[1] == n and k.shape[2] == d and q.stride(2) == 1 and k.stride(2) == 1
+    p = CaptureParams()
+    p.hq, p.hkv, p.len, p.pcl, p.head_dim, p.dtype, p.scale = Hq, k.shape[0], n, L, d, _dtype_code(q), scale
+    p.q_stride = (ctypes.c_int64 * 2)(*q.stride()[:2])
+    p.k_stride = (ctypes.c_int64 * 2)(*k.stride()[:2])
+    return p
+
+
+def capture_workspace(p: CaptureParams, device) -> torch.Tensor:
+    n = lib().dam_capture_workspace(ctypes.byref(p))
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def dam_capture_accumulate(q, k, attn_sum, attn_cnt=None, scale: float = 0.0, ws=None) -> None:
+    """attn_sum (and attn_cnt) [Hq][L][L] f32 += the causal attention probabilities (the valid pairs)
+    of the captured sequence q [Hq][n][d], k [Hkv][n][d]."""
+    p = capture_params(q, k, attn_sum.shape[1], scale)
+    if ws is None:
+        ws = capture_workspace(p, q.device)
+    st = lib().dam_capture_accumulate(ctypes.byref(p), _p(q), _p(k), _p(attn_sum), _p(attn_cnt), _p(ws), ws.numel(),
+                                      _stream())
+    _check("dam_capture_accumulate", st)
+
+
+def mask_from_qk_workspace(params: MaskParams, cp: CaptureParams, device) -> torch.Tensor:
+    n = lib().dam_mask_build_from_qk_workspace(ctypes.byref(params), ctypes.byref(cp))
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def dam_mask_build_from_qk(params: MaskParams, cp: CaptureParams, q, k, out: MaskOut, ws: torch.Tensor) -> None:
+    st = lib().dam_mask_build_from_qk(ctypes.byref(params), ctypes.byref(cp), _p(q), _p(k), ctypes.byref(out), _p(ws),
+                                      ws.numel(), _stream())
+    _check("dam_mask_build_from_qk", st)
+
+
 def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: int = 128, lam: float = 0.5,
                eps: float = 1e-8, tau: float = 0.3, mu: float = 0.8, bmin_override: float = float("nan"),
                attn_sum: Optional[torch.Tensor] = None, attn_cnt: Optional[torch.Tensor] = None,
                diag_in: Optional[torch.Tensor] = None, vert_in: Optional[torch.Tensor] = None,
                true_bits: Optional[torch.Tensor] = None, blocks: bool = True, tile_bits: bool = True,
-               dense: bool = False, rows: Optional[Tuple[int, int]] = None, device="cuda") -> Mask:
+               dense: bool = False, rows: Optional[Tuple[int, int]] = None, device="cuda",
+               qk: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, scale: float = 0.0) -> Mask:
     """Convenience wrapper: allocates the outputs, sizes the tile pool / kept lists with a first
-    call (blk_col == NULL), then fills them with a second. Only allocation and marshalling."""
+    call (blk_col == NULL), then fills them with a second. Only allocation and marshalling.
+    qk = (q [H][L][d], k [Hkv][L][d]) selects dam_mask_build_from_qk (one captured sequence, no map)."""
     dev = torch.device(device)
     p = MaskParams(mode, H, L, S, tile_m, tile_n, rows[0] if rows else 0, rows[1] if rows else 0, lam, eps, tau, mu,
                    bmin_override)
-    ws = mask_workspace(p, dev)
+    if qk is not None:
+        cp = capture_params(qk[0], qk[1], L, scale)
+        ws = mask_from_qk_workspace(p, cp, dev)
+
+        def call(o):
+            dam_mask_build_from_qk(p, cp, qk[0], qk[1], o, ws)
+    else:
+        ws = mask_workspace(p, dev)
+
+        def call(o):
+            dam_mask_build(p, attn_sum, attn_cnt, diag_in, vert_in, o, ws)
     m = Mask(H=H, L=L, S=S, tile_m=tile_m, tile_n=tile_n)
     nQt = (S + tile_m - 1) // tile_m
     if mode == DAM_FROM_ATTN_MAP:
@@ -193,7 +259,7 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
     if dense:
         m.dense_bits = torch.empty((H, S, (S + 63) // 64), dtype=torch.int64, device=dev)
         o.dense_bits = _p(m.dense_bits)
-    dam_mask_build(p, attn_sum, attn_cnt, diag_in, vert_in, o, ws)
+    call(o)
     if blocks or rows:
         n_tiles, n_kept = (int(x) for x in totals.cpu())
         again = False
@@ -217,7 +283,7 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
             again = True
         if again:
             o.dense_bits = None
-            dam_mask_build(p, attn_sum, attn_cnt, diag_in, vert_in, o, ws)
+            call(o)
     return m
 
 

@@ -28,4 +28,12 @@ struct Carver {
   }
 };
 
+// dam_capture.hip: argument check of a capture, bytes of its row log-sum-exp buffer, and the fused
+// form that writes the true mask of one captured sequence (bit = probability >= threshold, the
+// threshold given as the ordered fp32 key the mask builder uses).
+int capture_validate(const dam_capture_params *p, const void *q, const void *k);
+size_t capture_lse_bytes(const dam_capture_params *p);
+void launch_capture_true_bits(const dam_capture_params *p, const void *q, const void *k, float *lse2,
+                              const unsigned *theta_key, uint64_t *true_bits, hipStream_t stream);
+
 }  // namespace dam

@@ -905,75 +905,53 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   return w;
 }
 
-}  // namespace
-
-extern "C" size_t dam_mask_build_workspace(const dam_mask_params *p) {
-  if (!p || p->n_maps < 1 || p->seq < 1 || p->pcl < 0 || p->tile_m < 64 || p->tile_n < 64 ||
-      p->tile_m % 64 || p->tile_n % 64)
-    return 0;
-  return carve(p, nullptr).bytes;
+// a1 and the threshold of a2. attn_sum / attn_cnt are only read in the general minimum.
+void stage_threshold(const dam_mask_params *p, const Geom &g, const Workspace &w, const float *attn_sum,
+                     const float *attn_cnt, hipStream_t stream) {
+  const bool half = p->lambda == 0.5f;
+  // a1: the global minimum of the Box-Cox map
+  if (!isnan(p->bmin_override)) {
+    k_set_f32<<<1, 64, 0, stream>>>(w.bmin, p->bmin_override);
+  } else if (!attn_cnt && g.L >= 2) {
+    if (half) k_bmin_closed<1><<<1, 64, 0, stream>>>(p->eps, w.bmin);
+    else k_bmin_closed<2><<<1, 64, 0, stream>>>(p->eps, w.bmin);
+  } else {
+    const int64_t n = (int64_t)g.H * g.L * g.L;
+    k_fill_u32<<<1, 64, 0, stream>>>(w.xmin_bits, 1, 0x7F800000u);
+    const int blocks = (int)std::min<int64_t>((n + 1023) / 1024, 256 * 16);
+    k_min_x<<<blocks, 256, 0, stream>>>(attn_sum, attn_cnt, n, g.L, p->eps, w.xmin_bits);
+    if (half) k_bmin_from_x<1><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
+    else k_bmin_from_x<2><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
+  }
+  // a2: the threshold, found once
+  if (half) {
+    if (attn_cnt) k_threshold<1, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+    else k_threshold<1, true><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+  } else {
+    if (attn_cnt) k_threshold<2, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+    else k_threshold<2, true><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
+  }
 }
 
-extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, const float *attn_cnt,
-                              const uint8_t *diag_in, const uint8_t *vert_in, const dam_mask_out *o,
-                              void *ws, size_t ws_bytes, void *stream_v) {
-  const int bad = validate(p, attn_sum, diag_in, vert_in, o);
-  if (bad != DAM_OK) return bad;
-  if (!ws || ws_bytes < dam_mask_build_workspace(p)) return DAM_ERR_WORKSPACE;
-  hipStream_t stream = static_cast<hipStream_t>(stream_v);
-  const Geom g = geometry(p);
-  const Workspace w = carve(p, ws);
-  const uint8_t *dflag = diag_in, *vflag = vert_in;
-  const uint64_t *true_bits = g.L > 0 ? o->true_bits : nullptr;
+// a3: match scores of the true mask in o->true_bits; returns where the flags were written.
+void stage_patterns(const dam_mask_params *p, const Geom &g, const Workspace &w, const dam_mask_out *o,
+                    hipStream_t stream, const uint8_t **dflag, const uint8_t **vflag) {
+  uint8_t *df = o->diag_flag ? o->diag_flag : w.diag_flag;
+  uint8_t *vf = o->vert_flag ? o->vert_flag : w.vert_flag;
+  const int n_chunks = (g.L + kChunkRows - 1) / kChunkRows;
+  const dim3 sgrid((g.tbw + 63) / 64, (n_chunks + 3) / 4, g.H);
+  k_pattern_slices<false><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices);
+  k_pattern_slices<true><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.dslices);
+  k_pattern_finish<<<dim3(g.tbw, g.H), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, p->mu, o->vert_cnt,
+                                                        o->diag_cnt, vf, df);
+  *dflag = df;
+  *vflag = vf;
+  if (o->bmin) k_copy_f32<<<1, 64, 0, stream>>>(o->bmin, w.bmin);
+}
 
-  if (p->mode == DAM_FROM_ATTN_MAP) {
-    const bool half = p->lambda == 0.5f;
-    // a1: the global minimum of the Box-Cox map
-    if (!isnan(p->bmin_override)) {
-      k_set_f32<<<1, 64, 0, stream>>>(w.bmin, p->bmin_override);
-    } else if (!attn_cnt && g.L >= 2) {
-      if (half) k_bmin_closed<1><<<1, 64, 0, stream>>>(p->eps, w.bmin);
-      else k_bmin_closed<2><<<1, 64, 0, stream>>>(p->eps, w.bmin);
-    } else {
-      const int64_t n = (int64_t)g.H * g.L * g.L;
-      k_fill_u32<<<1, 64, 0, stream>>>(w.xmin_bits, 1, 0x7F800000u);
-      const int blocks = (int)std::min<int64_t>((n + 1023) / 1024, 256 * 16);
-      k_min_x<<<blocks, 256, 0, stream>>>(attn_sum, attn_cnt, n, g.L, p->eps, w.xmin_bits);
-      if (half) k_bmin_from_x<1><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
-      else k_bmin_from_x<2><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
-    }
-    // a2: true mask (threshold found once, then one comparison per element)
-    {
-      if (half) {
-        if (attn_cnt) k_threshold<1, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
-        else k_threshold<1, true><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
-      } else {
-        if (attn_cnt) k_threshold<2, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
-        else k_threshold<2, true><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
-      }
-      dim3 grid((g.tbw + 3) / 4, (g.L + kTmRows - 1) / kTmRows, g.H);
-      if (attn_cnt)
-        k_true_mask<false><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
-      else if (g.L % 4 == 0 && (reinterpret_cast<uintptr_t>(attn_sum) & 15) == 0)
-        k_true_mask_rows<<<dim3(2 * ((((g.L + 1) / 2) + 3) / 4), g.H), 256, 0, stream>>>(attn_sum, g.L, g.tbw, w.theta_key,
-                                                                                     o->true_bits);
-      else
-        k_true_mask<true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
-    }
-    // a3: match scores
-    uint8_t *df = o->diag_flag ? o->diag_flag : w.diag_flag;
-    uint8_t *vf = o->vert_flag ? o->vert_flag : w.vert_flag;
-    const int n_chunks = (g.L + kChunkRows - 1) / kChunkRows;
-    const dim3 sgrid((g.tbw + 63) / 64, (n_chunks + 3) / 4, g.H);
-    k_pattern_slices<false><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices);
-    k_pattern_slices<true><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.dslices);
-    k_pattern_finish<<<dim3(g.tbw, g.H), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, p->mu, o->vert_cnt,
-                                                          o->diag_cnt, vf, df);
-    dflag = df;
-    vflag = vf;
-    if (o->bmin) k_copy_f32<<<1, 64, 0, stream>>>(o->bmin, w.bmin);
-  }
-
+// a4 + a5 and the kept lists: everything downstream of the stored artefact.
+void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w, const dam_mask_out *o,
+                     const uint64_t *true_bits, const uint8_t *dflag, const uint8_t *vflag, hipStream_t stream) {
   const bool want_blocks = o->blk_row_ptr != nullptr;
   const bool want_lists = o->kept_ptr != nullptr;
   if (want_blocks || want_lists || o->dense_bits) {
@@ -1005,5 +983,74 @@ extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, c
       k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, 0, 0, o->kept_ptr, o->kept_total);
     }
   }
+}
+
+}  // namespace
+
+extern "C" size_t dam_mask_build_workspace(const dam_mask_params *p) {
+  if (!p || p->n_maps < 1 || p->seq < 1 || p->pcl < 0 || p->tile_m < 64 || p->tile_n < 64 ||
+      p->tile_m % 64 || p->tile_n % 64)
+    return 0;
+  return carve(p, nullptr).bytes;
+}
+
+extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, const float *attn_cnt,
+                              const uint8_t *diag_in, const uint8_t *vert_in, const dam_mask_out *o,
+                              void *ws, size_t ws_bytes, void *stream_v) {
+  const int bad = validate(p, attn_sum, diag_in, vert_in, o);
+  if (bad != DAM_OK) return bad;
+  if (!ws || ws_bytes < dam_mask_build_workspace(p)) return DAM_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  const Geom g = geometry(p);
+  const Workspace w = carve(p, ws);
+  const uint8_t *dflag = diag_in, *vflag = vert_in;
+  const uint64_t *true_bits = g.L > 0 ? o->true_bits : nullptr;
+
+  if (p->mode == DAM_FROM_ATTN_MAP) {
+    stage_threshold(p, g, w, attn_sum, attn_cnt, stream);
+    // a2: true mask, one comparison per element
+    dim3 grid((g.tbw + 3) / 4, (g.L + kTmRows - 1) / kTmRows, g.H);
+    if (attn_cnt)
+      k_true_mask<false><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
+    else if (g.L % 4 == 0 && (reinterpret_cast<uintptr_t>(attn_sum) & 15) == 0)
+      k_true_mask_rows<<<dim3(2 * ((((g.L + 1) / 2) + 3) / 4), g.H), 256, 0, stream>>>(attn_sum, g.L, g.tbw, w.theta_key,
+                                                                                   o->true_bits);
+    else
+      k_true_mask<true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
+    stage_patterns(p, g, w, o, stream, &dflag, &vflag);
+  }
+  stage_extension(p, g, w, o, true_bits, dflag, vflag, stream);
+  return launch_status();
+}
+
+// Sec. 4.2.1 - 4.3 for one captured sequence, from its Q and K: the probabilities are thresholded
+// as the capture kernels produce them (dam_capture.hip); the rest is the path above.
+extern "C" size_t dam_mask_build_from_qk_workspace(const dam_mask_params *p, const dam_capture_params *cp) {
+  const size_t base = dam_mask_build_workspace(p);
+  if (!base || !cp || cp->hq < 1 || cp->pcl < 1) return 0;
+  return base + capture_lse_bytes(cp);
+}
+
+extern "C" int dam_mask_build_from_qk(const dam_mask_params *p, const dam_capture_params *cp, const void *q,
+                                      const void *k, const dam_mask_out *o, void *ws, size_t ws_bytes,
+                                      void *stream_v) {
+  if (!p || !o || !cp) return DAM_ERR_INVALID_ARG;
+  if (p->mode != DAM_FROM_ATTN_MAP) return DAM_ERR_INVALID_ARG;
+  const float dummy_map = 0.0f;  // validate() only checks that a map pointer is present
+  int bad = validate(p, &dummy_map, nullptr, nullptr, o);
+  if (bad != DAM_OK) return bad;
+  bad = capture_validate(cp, q, k);
+  if (bad != DAM_OK) return bad;
+  if (p->n_maps != cp->hq || p->pcl != cp->pcl || cp->len != cp->pcl || p->pcl < 2) return DAM_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < dam_mask_build_from_qk_workspace(p, cp)) return DAM_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  const Geom g = geometry(p);
+  const Workspace w = carve(p, ws);
+  float *lse2 = reinterpret_cast<float *>(static_cast<char *>(ws) + w.bytes);
+  const uint8_t *dflag = nullptr, *vflag = nullptr;
+  stage_threshold(p, g, w, nullptr, nullptr, stream);
+  launch_capture_true_bits(cp, q, k, lse2, w.theta_key, o->true_bits, stream);
+  stage_patterns(p, g, w, o, stream, &dflag, &vflag);
+  stage_extension(p, g, w, o, o->true_bits, dflag, vflag, stream);
   return launch_status();
 }

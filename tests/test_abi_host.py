@@ -118,6 +118,50 @@ def test_decode_argument_errors():
     assert L.dam_sparse_attn_decode_workspace(ctypes.byref(p), 4000) > 0
 
 
+def capture_params(**kw):
+    p = B.CaptureParams()
+    p.hq, p.hkv, p.len, p.pcl, p.head_dim, p.dtype, p.scale = 2, 1, 64, 64, 128, B.DAM_BF16, 0.0
+    p.q_stride = (ctypes.c_int64 * 2)(64 * 128, 128)
+    p.k_stride = (ctypes.c_int64 * 2)(64 * 128, 128)
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_capture_argument_errors():
+    L = B.lib()
+
+    def call(cp, q=4096, a=4096, ws=4096, ws_bytes=1 << 30):
+        return L.dam_capture_accumulate(ctypes.byref(cp), q, 4096, a, None, ws, ws_bytes, None)
+
+    assert call(capture_params(), q=None) == B.DAM_ERR_INVALID_ARG
+    assert call(capture_params(), a=None) == B.DAM_ERR_INVALID_ARG
+    assert call(capture_params(hq=3, hkv=2)) == B.DAM_ERR_INVALID_ARG
+    assert call(capture_params(len=65)) == B.DAM_ERR_INVALID_ARG           # longer than the statistics
+    assert call(capture_params(len=0)) == B.DAM_ERR_INVALID_ARG
+    assert call(capture_params(head_dim=100)) == B.DAM_ERR_UNSUPPORTED
+    assert call(capture_params(dtype=3)) == B.DAM_ERR_UNSUPPORTED
+    assert call(capture_params(len=64, pcl=16384)) == B.DAM_ERR_UNSUPPORTED
+    assert call(capture_params(q_stride=(ctypes.c_int64 * 2)(64 * 128, 132))) == B.DAM_ERR_INVALID_ARG
+    assert call(capture_params(), ws_bytes=8) == B.DAM_ERR_WORKSPACE
+    assert L.dam_capture_workspace(ctypes.byref(capture_params())) >= 2 * 64 * 4
+
+    def fused(mp, cp, q=4096, ws=4096, ws_bytes=1 << 30):
+        o = B.MaskOut()
+        o.true_bits = 4096
+        return L.dam_mask_build_from_qk(ctypes.byref(mp), ctypes.byref(cp), q, 4096, ctypes.byref(o), ws, ws_bytes, None)
+
+    assert fused(mask_params(), capture_params(), q=None) == B.DAM_ERR_INVALID_ARG
+    assert fused(mask_params(mode=B.DAM_FROM_PATTERNS), capture_params()) == B.DAM_ERR_INVALID_ARG
+    assert fused(mask_params(n_maps=3), capture_params()) == B.DAM_ERR_INVALID_ARG        # n_maps != hq
+    assert fused(mask_params(pcl=128), capture_params()) == B.DAM_ERR_INVALID_ARG         # pcl mismatch
+    assert fused(mask_params(), capture_params(len=32)) == B.DAM_ERR_INVALID_ARG          # one full-length capture
+    assert fused(mask_params(lam=0.3), capture_params()) == B.DAM_ERR_UNSUPPORTED
+    assert fused(mask_params(), capture_params(), ws_bytes=64) == B.DAM_ERR_WORKSPACE
+    both = L.dam_mask_build_from_qk_workspace(ctypes.byref(mask_params()), ctypes.byref(capture_params()))
+    assert both > L.dam_mask_build_workspace(ctypes.byref(mask_params()))
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libdam.so"))
