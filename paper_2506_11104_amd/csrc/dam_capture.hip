@@ -132,26 +132,28 @@ __global__ __launch_bounds__(256) void k_capture_rows(CapArgs a, const T *__rest
 
 // ================================================================================================
 // Matrix-core kernels (bf16, head_dim 128). One workgroup of 4 waves per (head, tile of 128 query
-// rows), each wave owning 32 rows; K moves through LDS in blocks of 32 keys (8 KiB), double
-// buffered. A K row is 16 chunks of 16 bytes; chunk c of row r is stored at position c ^ (r & 15),
-// so that the 16-byte operand reads of 16 consecutive rows cover all banks once.
+// rows), each wave owning 32 rows; K moves through LDS in stages of 64 keys (16 KiB), double
+// buffered, one barrier per stage. A K row is 16 chunks of 16 bytes; chunk c of row r is stored at
+// position c ^ (r & 15), so that the 16-byte operand reads of 16 consecutive rows cover all banks.
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int kRows = 128, kBlk = 32, kBlkBytes = kBlk * 256;
+constexpr int kStageKeys = 64, kStageBytes = kStageKeys * 256;
+constexpr int kPadRow = 36;  // floats per row of a wave's 32 x 32 transposition tile (16-byte aligned, conflict-free)
 
 struct KStage {
-  uint4 r[2];
+  uint4 r[4];
 };
 
-// This thread's two 16-byte pieces of the K block starting at key0 (rows past the sequence end are
+// This thread's four 16-byte pieces of the 64 keys starting at key0 (rows past the sequence end are
 // redirected to the last row: such keys are masked by causality anyway).
 __device__ __forceinline__ KStage k_fetch(const __hip_bfloat16 *__restrict__ kh, int64_t k_ss, int key0, int n_keys) {
   KStage st;
   const int row = threadIdx.x >> 4, chunk = threadIdx.x & 15;
 #pragma unroll
-  for (int it = 0; it < 2; ++it) {
+  for (int it = 0; it < 4; ++it) {
     const int key = min(key0 + row + 16 * it, n_keys - 1);
     st.r[it] = *reinterpret_cast<const uint4 *>(kh + (int64_t)key * k_ss + chunk * 8);
   }
@@ -161,14 +163,14 @@ __device__ __forceinline__ KStage k_fetch(const __hip_bfloat16 *__restrict__ kh,
 __device__ __forceinline__ void k_stash(unsigned char *buf, const KStage &st) {
   const int row = threadIdx.x >> 4, chunk = threadIdx.x & 15;
 #pragma unroll
-  for (int it = 0; it < 2; ++it) {
+  for (int it = 0; it < 4; ++it) {
     const int r = row + 16 * it;
     *reinterpret_cast<uint4 *>(buf + r * 256 + ((chunk ^ (r & 15)) << 4)) = st.r[it];
   }
 }
 
-// S^T block: accumulator e of lane (n = lane & 31, hf = lane >> 5) is the logit of query row n of
-// the wave with key 8 (e / 4) + 4 hf + e % 4 of the block.
+// S^T block of 32 keys: accumulator e of lane (n = lane & 31, hf = lane >> 5) is the raw logit
+// (before the scale) of query row n of the wave with key 8 (e / 4) + 4 hf + e % 4 of the block.
 __device__ __forceinline__ f32x16 s_block(const unsigned char *buf, const bf16x8 (&qf)[8], int kbase) {
   f32x16 s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -179,6 +181,12 @@ __device__ __forceinline__ f32x16 s_block(const unsigned char *buf, const bf16x8
   return s;
 }
 
+// Bits 0 .. 31 of a 32-key block starting at key0 that are causal for row i (key <= i).
+__device__ __forceinline__ unsigned causal_bits(int i, int key0) {
+  const int u = i - key0;
+  return u >= 31 ? 0xFFFFFFFFu : (u < 0 ? 0u : ((2u << u) - 1u));
+}
+
 // PASS 0: log-sum-exp (log2 units) of every row. PASS 1: emission (MODE).
 template <int PASS, int MODE>
 __global__ __launch_bounds__(256) void k_capture_mfma(CapArgs a, const __hip_bfloat16 *__restrict__ q,
@@ -186,14 +194,16 @@ __global__ __launch_bounds__(256) void k_capture_mfma(CapArgs a, const __hip_bfl
                                                       const unsigned *__restrict__ theta_key,
                                                       uint64_t *__restrict__ true_bits, float *__restrict__ attn_sum,
                                                       float *__restrict__ attn_cnt) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBlkBytes];
+  constexpr bool kSum = PASS == 1 && MODE == kEmitSum;
+  constexpr bool kBits = PASS == 1 && MODE == kEmitBits;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStageBytes + (kSum ? 4 * 32 * kPadRow * 4 : 0)];
   const int nQt = (a.n + kRows - 1) / kRows;
   const int qt = nQt - 1 - blockIdx.x, h = blockIdx.y;  // long rows first
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, hf = lane >> 5;
-  const int i = qt * kRows + wave * 32 + n;  // this lane's query row
+  const int wave_first = qt * kRows + wave * 32;
+  const int i = wave_first + n;  // this lane's query row
   const bool live = i < a.n;
-  const int wave_last = qt * kRows + wave * 32 + 31;
   const int kbase = n * 256 + ((hf ^ (n & 15)) << 4);
   const __hip_bfloat16 *kh = k + (int64_t)(h / (a.Hq / a.Hkv)) * a.k_sh;
 
@@ -207,93 +217,156 @@ __global__ __launch_bounds__(256) void k_capture_mfma(CapArgs a, const __hip_bfl
       qf[c] = __builtin_bit_cast(bf16x8, raw);
     }
   }
-  // key blocks that hold a key <= the tile's last live row
+  // stages that hold a key <= the tile's last live row
   const int last_row = min(qt * kRows + kRows - 1, a.n - 1);
-  const int nkb = last_row / kBlk + 1;
+  const int n_stage = last_row / kStageKeys + 1;
 
-  float m_run = -INFINITY, l_run = 0.0f;                      // PASS 0
+  // PASS 0 state: reference m_ref (log2 units; moves only when a maximum outgrows it by more than 8,
+  // so that the sum rarely has to be rescaled) and the sum of exp2(t - m_ref) over this lane's keys
+  float m_ref = -INFINITY, l_run = 0.0f;
+  // PASS 1
   const float my_lse = (PASS == 1 && live) ? lse2[(int64_t)h * a.L + i] : 0.0f;
-  const unsigned theta = (PASS == 1 && MODE == kEmitBits) ? *theta_key : 0u;
-  unsigned words[4] = {0u, 0u, 0u, 0u};                        // bits of the current 128-key group
+  // bits: p >= theta  <=>  raw logit >= (lse + log2 theta) / c2 up to rounding. The threshold arrives as an
+  // ordered key: 0 keeps every causal entry, all ones keeps none; so do theta <= 0 and theta = +inf.
+  float thr = 0.0f;
+  if (kBits) {
+    const unsigned tk = *theta_key;
+    const float theta = __uint_as_float((tk & 0x80000000u) ? (tk & 0x7FFFFFFFu) : ~tk);
+    if (tk == 0u || theta <= 0.0f) thr = -INFINITY;
+    else if (tk == 0xFFFFFFFFu || !(theta < INFINITY)) thr = INFINITY;
+    else thr = (my_lse + __builtin_amdgcn_logf(theta)) / a.c2;
+  }
+  unsigned words[4] = {0u, 0u, 0u, 0u};  // bits of the current 128-key group of this lane's row
   unsigned *out32 = reinterpret_cast<unsigned *>(true_bits + ((int64_t)h * a.L + (live ? i : 0)) * a.tbw);
   const int nw32 = a.tbw * 2;
+  float *tile = reinterpret_cast<float *>(lds + 2 * kStageBytes) + wave * 32 * kPadRow;  // kSum only
 
   k_stash(lds, k_fetch(kh, a.k_ss, 0, a.n));
   __syncthreads();
-  for (int kb = 0; kb < nkb; ++kb) {
-    const unsigned char *buf = lds + (kb & 1) * kBlkBytes;
+  for (int st = 0; st < n_stage; ++st) {
+    const unsigned char *buf = lds + (st & 1) * kStageBytes;
     KStage next;
-    const bool more = kb + 1 < nkb;
-    if (more) next = k_fetch(kh, a.k_ss, (kb + 1) * kBlk, a.n);
-    const int key0 = kb * kBlk;
-    if (key0 <= wave_last) {  // wave-uniform: otherwise the whole block lies above this wave's rows
-      const f32x16 s = s_block(buf, qf, kbase);
+    const bool more = st + 1 < n_stage;
+    if (more) next = k_fetch(kh, a.k_ss, (st + 1) * kStageKeys, a.n);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int key0 = st * kStageKeys + half * kBlk;
+      if (key0 > wave_first + 31) continue;  // wave-uniform: the block lies above all rows of this wave
+      const f32x16 s = s_block(buf + half * kBlkBytes, qf, kbase);
+      const bool below = key0 + 31 <= wave_first;  // wave-uniform: every entry of the block is causal
       if (PASS == 0) {
-        float t[16], mx = m_run;
+        float t[16];
+        float mx = -INFINITY;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int j = key0 + 8 * (e / 4) + 4 * hf + (e % 4);
-          t[e] = j <= i ? s[e] * a.c2 : -INFINITY;
-          mx = fmaxf(mx, t[e]);
+          t[e] = s[e];
+          if (!below && key0 + 8 * (e / 4) + 4 * hf + (e % 4) > i) t[e] = -INFINITY;
         }
-        const float ref = mx == -INFINITY ? 0.0f : mx;
-        float add = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) add += __builtin_amdgcn_exp2f(t[e] - ref);
-        l_run = l_run * __builtin_amdgcn_exp2f(m_run - ref) + add;
-        m_run = mx;
-      } else if (MODE == kEmitBits) {
+        for (int e = 0; e < 16; e += 2) mx = fmaxf(fmaxf(t[e], t[e + 1]), mx);
+        mx *= a.c2;  // c2 > 0
+        const bool move = mx - m_ref > 8.0f;  // false while both are -inf (NaN)
+        if (__ballot(move)) {
+          if (move) {
+            l_run *= __builtin_amdgcn_exp2f(m_ref - mx);  // m_ref = -inf: 0
+            m_ref = mx;
+          }
+        }
+        const float off = m_ref == -INFINITY ? 0.0f : m_ref;
+        float add0 = 0.0f, add1 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+          add0 += __builtin_amdgcn_exp2f(__builtin_fmaf(t[e], a.c2, -off));
+          add1 += __builtin_amdgcn_exp2f(__builtin_fmaf(t[e + 1], a.c2, -off));
+        }
+        l_run += add0 + add1;
+      } else if (kBits) {
         unsigned mine = 0u;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = key0 + 8 * (e / 4) + 4 * hf + (e % 4);
-          const float p = __builtin_amdgcn_exp2f(s[e] * a.c2 - my_lse);
-          if (j <= i && key_of(p) >= theta) mine |= 1u << (8 * (e / 4) + 4 * hf + (e % 4));
-        }
+        for (int e = 0; e < 16; ++e) mine |= (s[e] >= thr ? 1u : 0u) << (8 * (e / 4) + (e % 4));
+        mine <<= 4 * hf;
         mine |= (unsigned)__shfl_xor((int)mine, 32);
-        const int slot = kb & 3;
+        mine &= causal_bits(i, key0);
+        const int slot = (2 * st + half) & 3;
         words[0] = slot == 0 ? mine : words[0];
         words[1] = slot == 1 ? mine : words[1];
         words[2] = slot == 2 ? mine : words[2];
         words[3] = slot == 3 ? mine : words[3];
       } else {
-        float *arow = attn_sum + ((int64_t)h * a.L + (live ? i : 0)) * a.L;
-        float *crow = attn_cnt ? attn_cnt + ((int64_t)h * a.L + (live ? i : 0)) * a.L : nullptr;
+        // probabilities of the wave's 32 x 32 block, transposed through LDS so that a row's 32 keys
+        // are read and written as one 128-byte line
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int j0 = key0 + 8 * g + 4 * hf;
+          float4 pv;
+          pv.x = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * g], a.c2, -my_lse));
+          pv.y = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * g + 1], a.c2, -my_lse));
+          pv.z = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * g + 2], a.c2, -my_lse));
+          pv.w = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * g + 3], a.c2, -my_lse));
+          *reinterpret_cast<float4 *>(tile + n * kPadRow + 8 * g + 4 * hf) = pv;
+        }
+        // the tile is private to the wave, whose LDS operations complete in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int col = (lane & 7) * 4, j0 = key0 + col;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            if (live && j0 + r <= i) {
-              arow[j0 + r] += __builtin_amdgcn_exp2f(s[4 * g + r] * a.c2 - my_lse);
-              if (crow) crow[j0 + r] += 1.0f;
+        for (int pass = 0; pass < 4; ++pass) {
+          const int r = (lane >> 3) + 8 * pass, row = wave_first + r;
+          const float4 pv = *reinterpret_cast<const float4 *>(tile + r * kPadRow + col);
+          if (row < a.n && j0 <= row) {
+            float *ap = attn_sum + ((int64_t)h * a.L + row) * a.L + j0;
+            float *cp = attn_cnt ? attn_cnt + ((int64_t)h * a.L + row) * a.L + j0 : nullptr;
+            if (j0 + 3 <= row && (a.L & 3) == 0) {
+              float4 av = *reinterpret_cast<float4 *>(ap);
+              av.x += pv.x; av.y += pv.y; av.z += pv.z; av.w += pv.w;
+              *reinterpret_cast<float4 *>(ap) = av;
+              if (cp) {
+                float4 cv = *reinterpret_cast<float4 *>(cp);
+                cv.x += 1.0f; cv.y += 1.0f; cv.z += 1.0f; cv.w += 1.0f;
+                *reinterpret_cast<float4 *>(cp) = cv;
+              }
+            } else {
+              const float pe[4] = {pv.x, pv.y, pv.z, pv.w};
+#pragma unroll
+              for (int x = 0; x < 4; ++x)
+                if (j0 + x <= row) {
+                  ap[x] += pe[x];
+                  if (cp) cp[x] += 1.0f;
+                }
             }
           }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
     }
-    if (PASS == 1 && MODE == kEmitBits && ((kb & 3) == 3 || kb + 1 == nkb)) {
-      // the 128-key group is complete (blocks above this wave's rows contribute zeros)
+    if (kBits && ((st & 1) == 1 || !more)) {
+      // the 128-key group is complete (blocks above this wave's rows contributed zeros)
       if (live && hf == 0) {
-        const int w0 = (kb >> 2) * 4;
+        const int w0 = (st >> 1) * 4;
+        if (w0 + 3 < nw32 && (a.tbw & 1) == 0) {
+          *reinterpret_cast<uint4 *>(out32 + w0) = make_uint4(words[0], words[1], words[2], words[3]);
+        } else {
 #pragma unroll
-        for (int x = 0; x < 4; ++x)
-          if (w0 + x < nw32) out32[w0 + x] = words[x];
+          for (int x = 0; x < 4; ++x)
+            if (w0 + x < nw32) out32[w0 + x] = words[x];
+        }
       }
       words[0] = words[1] = words[2] = words[3] = 0u;
     }
-    if (more) k_stash(lds + ((kb + 1) & 1) * kBlkBytes, next);
+    if (more) k_stash(lds + ((st + 1) & 1) * kStageBytes, next);
     __syncthreads();
   }
   if (PASS == 0) {
-    const float m_o = __shfl_xor(m_run, 32), l_o = __shfl_xor(l_run, 32);
-    const float M = fmaxf(m_run, m_o);  // finite: every live row holds key 0
-    const float tot = l_run * __builtin_amdgcn_exp2f(m_run - M) + l_o * __builtin_amdgcn_exp2f(m_o - M);
+    const float m_o = __shfl_xor(m_ref, 32), l_o = __shfl_xor(l_run, 32);
+    const float M = fmaxf(m_ref, m_o);  // finite: every live row holds key 0
+    const float tot = l_run * __builtin_amdgcn_exp2f(m_ref - M) + l_o * __builtin_amdgcn_exp2f(m_o - M);
     if (live && hf == 0) lse2[(int64_t)h * a.L + i] = M + __builtin_amdgcn_logf(tot);
-  } else if (MODE == kEmitBits) {
-    // words of the row past the tile's last key block: all zero (keys above the diagonal)
+  } else if (kBits) {
+    // words of the row past the tile's last 128-key group: all zero (keys above the diagonal)
     if (live) {
-      const int w_done = ((nkb + 3) / 4) * 4;
+      const int w_done = ((n_stage + 1) / 2) * 4;
       for (int w = w_done + hf; w < nw32; w += 2) out32[w] = 0u;
     }
   }

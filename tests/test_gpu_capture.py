@@ -21,6 +21,9 @@ pytestmark = pytest.mark.gpu
 # accumulation of 128 products, scale, subtraction of a log-sum-exp of magnitude up to ~50), which is
 # the relative error of its probability; the hardware exp2 / log2 add a few ulp.
 RTOL, ATOL = 2e-4, 1e-7
+# the fused build: true-mask bits may differ only where |p - theta| <= BAND * theta (purely relative: the
+# threshold sits far above the absolute floor)
+BAND = 1e-4
 
 
 def seq_pair(seed, Hq, Hkv, n, d, dtype, std=1.0):
@@ -91,7 +94,7 @@ def fused_against_oracle(Q, K, w, S, tm, tn, tau, mu, dtype, rows=None):
     if kept_vals.size and dropped_vals.size:
         theta = 0.5 * (float(kept_vals.min()) + float(dropped_vals.max()))
         assert dropped_vals.max() <= kept_vals.min()
-        near = np.abs(A - theta) <= ATOL + RTOL * theta
+        near = np.abs(A - theta) <= BAND * theta
         assert not (diff & ~near).any(), f"{int((diff & ~near).sum())} true-mask bits differ away from the threshold"
         assert diff.sum() <= max(8, 0.01 * near.sum() + 8) or near.sum() < 64, (int(diff.sum()), int(near.sum()))
     else:  # everything kept or everything dropped: no boundary, the masks must be identical
@@ -120,6 +123,15 @@ def test_fused_build_c2_shape_scaled():
     Q, K, _ = wl.qkv_structured(w)
     ndiff, art, art_gpu = fused_against_oracle(Q, K, w, w.seq, 128, 128, w.tau, w.mu, "bf16", rows=(1000, 1003))
     assert art.vert_flag.sum() > 0 and art.diag_flag.sum() > 0     # the recipe produces both pattern kinds
+
+
+@pytest.mark.parametrize("tau", [0.0, -1.0, 3.0])
+def test_fused_build_keep_all_and_keep_none_on_the_matrix_core_path(tau):
+    w = wl.scaled(wl.WORKLOADS["c2"], hq=4, hkv=2, seq=512, pcl=256)
+    Q, K, _ = wl.qkv_structured(w)
+    ndiff, art, _ = fused_against_oracle(Q, K, w, w.seq, 128, 128, tau, 0.8, "bf16")
+    assert ndiff == 0
+    assert art.true_mask.sum() == (0 if tau > 2 else 4 * 256 * 257 // 2)
 
 
 def test_fused_build_ragged_capture_length():

@@ -118,7 +118,6 @@ def test_c4_full_size():
     mask = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu,
                         attn_sum=torch.from_numpy(A).cuda())
     torch.cuda.synchronize()
-    del A
     # stage one, whole: threshold bits, match counts and flags
     assert np.float32(mask.bmin.item()) == np.float32(art.bmin)
     for h in range(H):
@@ -134,6 +133,34 @@ def test_c4_full_size():
     dens = nnz / (H * S * (S + 1) / 2)
     say(f"c4: stage one identical; {mask.n_tiles} tiles, density {dens:.4f}")
     assert 0.01 <= dens <= 0.05, dens
+    # the same stage one fused with its capture (dam_mask_build_from_qk, no map): true-mask bits may
+    # differ from the map-based ones only where the probability is within the fp32 tolerance of the
+    # threshold; counts and flags must be exactly what the oracle derives from the GPU's own bits
+    fused = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu, blocks=False,
+                         qk=(dev(np.ascontiguousarray(Q[:, :L]), "bf16"), dev(np.ascontiguousarray(K[:, :L]), "bf16")))
+    torch.cuda.synchronize()
+    tri = np.tril(np.ones((L, L), bool))
+    theta_lo = max(float(A[h][(art.true_mask[h] == 0) & tri].max()) for h in range(H))
+    theta_hi = min(float(A[h][art.true_mask[h] == 1].min()) for h in range(H))
+    assert theta_lo <= theta_hi
+    theta = 0.5 * (theta_lo + theta_hi)
+    n_diff = n_near = 0
+    f_dc, f_vc = fused.diag_cnt.cpu().numpy(), fused.vert_cnt.cpu().numpy()
+    f_df, f_vf = fused.diag_flag.cpu().numpy(), fused.vert_flag.cpu().numpy()
+    for h in range(H):
+        got = np.ascontiguousarray(np.unpackbits(u64(fused.true_bits[h]).view(np.uint8), axis=-1, bitorder="little")[:, :L])
+        diff = got != art.true_mask[h]
+        near = np.abs(A[h] - theta) <= 1e-4 * theta
+        assert not (diff & ~near).any(), f"fused true mask head {h}: bits differ away from the threshold"
+        n_diff += int(diff.sum())
+        n_near += int(near.sum())
+        dc, vc, df, vf = oracle.match(got[None], w.mu)
+        assert np.array_equal(f_dc[h], dc[0]) and np.array_equal(f_vc[h], vc[0]), f"fused counts head {h}"
+        assert np.array_equal(f_df[h], df[0]) and np.array_equal(f_vf[h], vf[0]), f"fused flags head {h}"
+    say(f"c4: fused capture: {n_diff} of {H * L * (L + 1) // 2} true-mask bits differ, all among the {n_near} entries "
+        f"within tolerance of the threshold {theta:.3e}")
+    assert n_diff <= 0.05 * n_near + 64
+    del A, fused
     # the S-sized outputs: one head in full, and for every head the tile rows around the L boundary,
     # the last one and seeded random ones
     check_heads_in_full(art, mask, S, [int(np.random.default_rng(44).integers(0, H))])
