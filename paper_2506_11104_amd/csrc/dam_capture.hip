@@ -140,6 +140,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int kRows = 128, kBlk = 32, kBlkBytes = kBlk * 256;
+constexpr int kXcd = 8;
 constexpr int kStageKeys = 64, kStageBytes = kStageKeys * 256;
 constexpr int kPadRow = 36;  // floats per row of a wave's 32 x 32 transposition tile (16-byte aligned, conflict-free)
 
@@ -197,15 +198,22 @@ __global__ __launch_bounds__(256) void k_capture_mfma(CapArgs a, const __hip_bfl
   constexpr bool kSum = PASS == 1 && MODE == kEmitSum;
   constexpr bool kBits = PASS == 1 && MODE == kEmitBits;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStageBytes + (kSum ? 4 * 32 * kPadRow * 4 : 0)];
+  // Workgroup numbering: workgroup g runs on XCD g % 8; all query heads and query tiles of one KV head
+  // get ids with the same g % 8, so that one XCD's L2 holds that head's K; within a KV head the long
+  // rows come first.
   const int nQt = (a.n + kRows - 1) / kRows;
-  const int qt = nQt - 1 - blockIdx.x, h = blockIdx.y;  // long rows first
+  const int G = a.Hq / a.Hkv, per_kv = G * nQt;
+  const int xcd = blockIdx.x % kXcd, slot = blockIdx.x / kXcd;
+  const int kv = (slot / per_kv) * kXcd + xcd, within = slot % per_kv;
+  if (kv >= a.Hkv) return;
+  const int qt = nQt - 1 - within / G, h = kv * G + within % G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, hf = lane >> 5;
   const int wave_first = qt * kRows + wave * 32;
   const int i = wave_first + n;  // this lane's query row
   const bool live = i < a.n;
   const int kbase = n * 256 + ((hf ^ (n & 15)) << 4);
-  const __hip_bfloat16 *kh = k + (int64_t)(h / (a.Hq / a.Hkv)) * a.k_sh;
+  const __hip_bfloat16 *kh = k + (int64_t)kv * a.k_sh;
 
   bf16x8 qf[8];
   {
@@ -389,7 +397,8 @@ void launch(const dam_capture_params *p, const void *q, const void *k, float *ls
             uint64_t *true_bits, float *attn_sum, float *attn_cnt, hipStream_t st) {
   const CapArgs a = make_args(p);
   if (mfma_path(p)) {
-    const dim3 grid((a.n + kRows - 1) / kRows, a.Hq);
+    const int nQt = (a.n + kRows - 1) / kRows;
+    const dim3 grid((a.Hkv + kXcd - 1) / kXcd * kXcd * (a.Hq / a.Hkv) * nQt);
     const __hip_bfloat16 *qb = static_cast<const __hip_bfloat16 *>(q), *kb = static_cast<const __hip_bfloat16 *>(k);
     k_capture_mfma<0, MODE><<<grid, 256, 0, st>>>(a, qb, kb, lse2, theta_key, true_bits, attn_sum, attn_cnt);
     k_capture_mfma<1, MODE><<<grid, 256, 0, st>>>(a, qb, kb, lse2, theta_key, true_bits, attn_sum, attn_cnt);
