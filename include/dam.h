@@ -75,7 +75,8 @@ typedef enum {
 typedef struct {
   int32_t mode;      /* dam_mask_mode                                                              */
   int32_t n_maps;    /* H: number of (layer, head) maps handled by this call                        */
-  int32_t pcl;       /* L: pattern capture length. FROM_PATTERNS: side of the supplied true mask, or
+  int32_t pcl;       /* L: pattern capture length (FROM_ATTN_MAP: below 131072, else
+                        DAM_ERR_UNSUPPORTED). FROM_PATTERNS: side of the supplied true mask, or
                         0 when there is none (then the pattern rule applies everywhere)             */
   int32_t seq;       /* S: length of the problem the mask is built for                              */
   int32_t tile_m;    /* block-index tile, query rows;  multiple of 64, at most 256                  */

@@ -314,39 +314,81 @@ __global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restri
 }
 
 // gamma = count / size >= mu for pattern p of head h (Sec. 4.2.4), counts summed over the row chunks.
-// One block per (head, word of 64 patterns): lane = pattern, the four waves share the chunks.
-__global__ __launch_bounds__(256) void k_pattern_finish(const uint64_t *__restrict__ vslices,
-                                                        const uint64_t *__restrict__ dslices, int L, int tbw,
-                                                        int n_chunks, float mu, int *__restrict__ vert_cnt,
-                                                        int *__restrict__ diag_cnt, uint8_t *__restrict__ vert_flag,
-                                                        uint8_t *__restrict__ diag_flag) {
-  __shared__ int s_v[4][64], s_d[4][64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int h = blockIdx.y, word = blockIdx.x;
-  const int p = word * 64 + lane;
-  int nv = 0, nd = 0;
-  // rows above p hold nothing of pattern p: start at the chunk of the word's first pattern
-#pragma unroll 4
-  for (int chunk = word * 64 / kChunkRows + wave; chunk < n_chunks; chunk += 4) {
-    const int64_t at = (((int64_t)h * n_chunks + chunk) * kSlices) * tbw + word;
+// The chunk counts stay bit-sliced while they are added: lane = word of 64 patterns (coalesced loads
+// of the slices), each wave ripple-adds the 7-slice counts of its share of the chunks into a wider
+// bit-sliced sum (a full adder is five logic operations on 64 patterns at once), the four sums are
+// added once more, and only then every thread extracts the integer counts of its patterns.
+// blockIdx.z: 0 vertical, 1 diagonal patterns; blockIdx.x: group of 64 words.
+constexpr int kAccSlices = 17;  // counts below 2^17: pcl is limited accordingly
+
+template <int NIN>
+__device__ __forceinline__ void sliced_add(uint64_t (&acc)[kAccSlices], const uint64_t (&in)[NIN], int nb) {
+  uint64_t carry = 0;
 #pragma unroll
-    for (int k = 0; k < kSlices; ++k) {
-      nv += (int)((vslices[at + (int64_t)k * tbw] >> lane) & 1) << k;
-      nd += (int)((dslices[at + (int64_t)k * tbw] >> lane) & 1) << k;
+  for (int k = 0; k < kAccSlices; ++k) {
+    if (k < nb) {  // wave-uniform
+      const uint64_t x = k < NIN ? in[k < NIN ? k : 0] : 0;
+      const uint64_t u = acc[k] ^ x;
+      const uint64_t c = (acc[k] & x) | (u & carry);
+      acc[k] = u ^ carry;
+      carry = c;
     }
   }
-  s_v[wave][lane] = nv;
-  s_d[wave][lane] = nd;
+}
+
+__global__ __launch_bounds__(256) void k_pattern_finish(const uint64_t *__restrict__ vslices,
+                                                        const uint64_t *__restrict__ dslices, int L, int tbw,
+                                                        int n_chunks, int nb, float mu, int *__restrict__ vert_cnt,
+                                                        int *__restrict__ diag_cnt, uint8_t *__restrict__ vert_flag,
+                                                        uint8_t *__restrict__ diag_flag) {
+  __shared__ uint64_t part[3][kAccSlices][64];
+  __shared__ uint64_t total[kAccSlices][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.y, word0 = blockIdx.x * 64;
+  const bool diag = blockIdx.z == 1;
+  const uint64_t *slices = diag ? dslices : vslices;
+  int *cnt_out = diag ? diag_cnt : vert_cnt;
+  uint8_t *flag_out = diag ? diag_flag : vert_flag;
+  const int wl = word0 + lane;
+  uint64_t acc[kAccSlices];
+#pragma unroll
+  for (int k = 0; k < kAccSlices; ++k) acc[k] = 0;
+  // rows above pattern p hold nothing of it: start at the chunk of the group's first pattern
+  for (int chunk = word0 * 64 / kChunkRows + wave; chunk < n_chunks; chunk += 4) {
+    uint64_t in[kSlices];
+    const int64_t at = (((int64_t)h * n_chunks + chunk) * kSlices) * tbw + wl;
+#pragma unroll
+    for (int k = 0; k < kSlices; ++k) in[k] = wl < tbw ? slices[at + (int64_t)k * tbw] : 0;
+    sliced_add(acc, in, nb);
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int k = 0; k < kAccSlices; ++k) part[wave - 1][k][lane] = acc[k];
+  }
   __syncthreads();
-  if (wave != 0 || p >= L) return;
-  nv = s_v[0][lane] + s_v[1][lane] + s_v[2][lane] + s_v[3][lane];
-  nd = s_d[0][lane] + s_d[1][lane] + s_d[2][lane] + s_d[3][lane];
-  const int64_t e = (int64_t)h * L + p;
-  if (vert_cnt) vert_cnt[e] = nv;
-  if (diag_cnt) diag_cnt[e] = nd;
-  const float size = (float)(L - p);
-  vert_flag[e] = (uint8_t)((float)nv / size >= mu);
-  diag_flag[e] = (uint8_t)((float)nd / size >= mu);
+  if (wave == 0) {
+    for (int w = 0; w < 3; ++w) {
+      uint64_t in[kAccSlices];
+#pragma unroll
+      for (int k = 0; k < kAccSlices; ++k) in[k] = part[w][k][lane];
+      sliced_add(acc, in, nb);
+    }
+#pragma unroll
+    for (int k = 0; k < kAccSlices; ++k) total[k][lane] = acc[k];
+  }
+  __syncthreads();
+  const int p_end = min(L, (word0 + 64) * 64);
+  for (int p = word0 * 64 + threadIdx.x; p < p_end; p += 256) {
+    const int wd = (p >> 6) - word0, t = p & 63;
+    int cnt = 0;
+#pragma unroll
+    for (int k = 0; k < kAccSlices; ++k)
+      if (k < nb) cnt |= (int)((total[k][wd] >> t) & 1) << k;
+    const int64_t e = (int64_t)h * L + p;
+    if (cnt_out) cnt_out[e] = cnt;
+    const float size = (float)(L - p);
+    flag_out[e] = (uint8_t)((float)cnt / size >= mu);
+  }
 }
 
 // Flags -> bitsets. cbits bit c = column c matched. rrev bit q = diagonal (pw*64 - 1 - q) matched,
@@ -829,6 +871,7 @@ int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *dia
   if ((int64_t)(p->seq + p->tile_n - 1) / p->tile_n > 32768) return DAM_ERR_UNSUPPORTED;
   if (p->mode == DAM_FROM_ATTN_MAP) {
     if (p->pcl < 1 || !attn_sum || !o->true_bits) return DAM_ERR_INVALID_ARG;
+    if (p->pcl >= (1 << kAccSlices)) return DAM_ERR_UNSUPPORTED;  // the match counts are summed in kAccSlices bits
     if (!(p->eps > 0.0f)) return DAM_ERR_INVALID_ARG;
     if (p->lambda != 0.5f && p->lambda != 1.0f) return DAM_ERR_UNSUPPORTED;
     if (isnan(p->tau) || isnan(p->mu)) return DAM_ERR_INVALID_ARG;
@@ -942,8 +985,10 @@ void stage_patterns(const dam_mask_params *p, const Geom &g, const Workspace &w,
   const dim3 sgrid((g.tbw + 63) / 64, (n_chunks + 3) / 4, g.H);
   k_pattern_slices<false><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices);
   k_pattern_slices<true><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.dslices);
-  k_pattern_finish<<<dim3(g.tbw, g.H), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, p->mu, o->vert_cnt,
-                                                        o->diag_cnt, vf, df);
+  int nb = 1;  // bits of the largest possible count, L
+  while ((g.L >> nb) != 0) ++nb;
+  k_pattern_finish<<<dim3((g.tbw + 63) / 64, g.H, 2), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, nb, p->mu,
+                                                                       o->vert_cnt, o->diag_cnt, vf, df);
   *dflag = df;
   *vflag = vf;
   if (o->bmin) k_copy_f32<<<1, 64, 0, stream>>>(o->bmin, w.bmin);
