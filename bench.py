@@ -256,6 +256,8 @@ def bench_mask_from_map(args, torch, B, wl, name):
     Q, K, V = wl.qkv_structured(w)
     H, L = w.hq, w.pcl
     A = torch.from_numpy(wl.capture_map(Q[:, :L], K[:, :L], L, w.hq // w.hkv)).cuda()
+    q_cap = torch.from_numpy(np.ascontiguousarray(Q[:, :L])).to(torch.bfloat16).cuda()
+    k_cap = torch.from_numpy(np.ascontiguousarray(K[:, :L])).to(torch.bfloat16).cuda()
     del Q, K, V
 
     def timed(fn, n):
@@ -281,6 +283,27 @@ def bench_mask_from_map(args, torch, B, wl, name):
     res = {"workload": f"{name} map ({H} x {L} x {L} fp32) -> true mask + matched patterns", "ms": ms, "bytes": nbytes,
            "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+    # the same stage one fused with its capture (no map), and the capture alone summed into A and C
+    cp = B.capture_params(q_cap, k_cap, L)
+    ws_f = B.mask_from_qk_workspace(p, cp, "cuda")
+    ms_f = timed(lambda: B.dam_mask_build_from_qk(p, cp, q_cap, k_cap, o, ws_f), 20)
+    flops = 2.0 * w.head_dim * H * L * (L + 1) / 2     # one Q K^T over the causal triangle (the kernels take two)
+    res["fused_capture"] = {"workload": f"{name} capture (Q, K of {L} tokens, {H} heads) -> true mask + matched patterns, no map",
+                            "ms": ms_f, "flops": flops,
+                            "roofline": {"bound": "mfma", "achieved": flops / (ms_f * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                                         "unit": "TFLOP/s", "frac": flops / (ms_f * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                         "traffic": None}}
+    a_sum = torch.zeros((H, L, L), dtype=torch.float32, device="cuda")
+    a_cnt = torch.zeros((H, L, L), dtype=torch.float32, device="cuda")
+    ws_c = B.capture_workspace(cp, "cuda")
+    ms_a = timed(lambda: B.dam_capture_accumulate(q_cap, k_cap, a_sum, a_cnt, ws=ws_c), 5)
+    acc_bytes = 16.0 * H * L * (L + 1) / 2             # A and C, lower triangle, read and written
+    res["capture_accumulate"] = {"workload": f"{name} capture summed into A and C ({H} x {L} x {L} fp32 each)", "ms": ms_a,
+                                 "bytes": acc_bytes,
+                                 "roofline": {"bound": "hbm", "achieved": acc_bytes / (ms_a * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                              "unit": "GB/s", "frac": acc_bytes / (ms_a * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                              "traffic": None}}
+    del a_sum, a_cnt, q_cap, k_cap
     if name == "c4":
         S = w.seq
         sized = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu, attn_sum=A)
