@@ -74,22 +74,26 @@ def bench_prefill(args, w, torch, B, wl):
     v_in = torch.from_numpy(vflag).to(dev) if vflag is not None else None
 
     # sizing call (outside the timed region): how many tiles does the pool need
+    # (full tiles carry no bits in the pool: DAM_MASK_SKIP_FULL_TILE_BITS, the attention kernel takes them from blk_kind)
     sized = B.build_mask(mode=mode, H=H, L=L, S=S, tile_m=w.tile_m, tile_n=w.tile_n, lam=w.lam, eps=w.eps, tau=w.tau,
-                         mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in)
+                         mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in, flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
     torch.cuda.synchronize()
     n_tiles = sized.n_tiles
     kinds = sized.blk_kind.cpu().numpy()
     n_full = int((kinds & 1).sum())
-    # kept entries: popcount of the tile pool (chunked on the device as bytes through a lookup table)
+    # kept entries: popcount of the partial tiles of the pool (chunked on the device as bytes through a lookup
+    # table) plus the area of the full tiles
     lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=dev)
-    nnz = 0
-    tb = sized.tile_bits.view(torch.uint8).reshape(-1)
+    nnz = n_full * w.tile_m * w.tile_n
+    tb = sized.tile_bits[(sized.blk_kind & 1) == 0].view(torch.uint8).reshape(-1)
     for off in range(0, tb.numel(), 1 << 28):
         nnz += int(lut[tb[off:off + (1 << 28)].long()].sum().item())
+    del tb
     causal = H * S * (S + 1) // 2
 
     # preallocated outputs for the timed steps
-    p = B.MaskParams(mode, H, L, S, w.tile_m, w.tile_n, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
+    p = B.MaskParams(mode, H, L, S, w.tile_m, w.tile_n, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"),
+                     B.DAM_MASK_SKIP_FULL_TILE_BITS)
     ws_mask = B.mask_workspace(p, dev)
     o = B.MaskOut()
     for name in ("true_bits", "diag_cnt", "vert_cnt", "diag_flag", "vert_flag", "bmin"):
@@ -129,7 +133,7 @@ def bench_prefill(args, w, torch, B, wl):
 
     flops_kept = 4.0 * d * nnz
     flops_tiles = 4.0 * d * w.tile_m * w.tile_n * n_tiles
-    mask_bytes = n_tiles * (w.tile_m * w.tile_n // 8 + 5) + 4 * H * (sized.blk_row_ptr.shape[1]) + 2 * H * S
+    mask_bytes = (n_tiles - n_full) * (w.tile_m * w.tile_n // 8) + 5 * n_tiles + 4 * H * (sized.blk_row_ptr.shape[1]) + 2 * H * S
     if A is not None:
         mask_bytes += 2 * H * L * (L + 1) + H * L * L // 8
     res = {

@@ -49,6 +49,14 @@ typedef enum {
 
 typedef enum { DAM_F32 = 0, DAM_BF16 = 1 } dam_dtype;
 
+/* dam_mask_params.flags */
+typedef enum {
+  DAM_MASK_SKIP_FULL_TILE_BITS = 1 /* do not write tile_bits of full tiles (blk_kind bit 0): the attention
+                                      kernels never read them, and at long sequences they are a large part
+                                      of the bytes written. Their slots in the pool stay reserved and keep
+                                      whatever they held.                                                  */
+} dam_mask_flags;
+
 typedef enum {
   DAM_FROM_ATTN_MAP = 0, /* derive the true mask and the matched patterns from A (and C)          */
   DAM_FROM_PATTERNS = 1  /* matched patterns (and optionally a true mask) are supplied            */
@@ -88,6 +96,7 @@ typedef struct {
   float tau;         /* true-mask threshold (paper: 0.3)                                            */
   float mu;          /* pattern-match threshold (paper: 0.8)                                        */
   float bmin_override; /* NaN: use the minimum over this call's maps; otherwise this value is bmin  */
+  int32_t flags;     /* bit set of dam_mask_flags                                                   */
 } dam_mask_params;
 
 /* Outputs of dam_mask_build. Every pointer is a device pointer owned by the caller; any of them may
@@ -116,7 +125,8 @@ typedef struct {
  *                                       aligned 32-bit words: 4-byte aligned, and allocated up to a
  *                                       multiple of 4 bytes.
  *   tile_bits  [blk_capacity][tile_m][tile_n / 64] u64   element bits of listed tile t at index t
- *                                       (also for full tiles: all ones); bits beyond S are 0.
+ *                                       (also for full tiles: all ones, unless the flag
+ *                                       DAM_MASK_SKIP_FULL_TILE_BITS is set); bits beyond S are 0.
  *   blk_total  [1] i64                  number of listed tiles, valid even when it exceeds
  *                                       blk_capacity (nothing is written past the capacity). Call
  *                                       with blk_col == NULL to size the buffers.

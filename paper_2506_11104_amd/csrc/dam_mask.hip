@@ -572,9 +572,10 @@ __global__ void k_tile_classes(Geom g, const uint64_t *__restrict__ cbits, const
 }
 
 // Pass 1 of the block index: which key tiles of query tile (h, qt) hold a kept entry / are full.
-// Tiles strictly below the diagonal and outside the true-mask block are decided by one lane each
-// (pattern_tile_flags); only the tiles on the diagonal or inside the true-mask block are evaluated
-// word by word by a whole wave.
+// One wave per query tile, 64 key tiles (one occupancy word) at a time, one lane per key tile. Tiles
+// strictly below the diagonal and outside the true-mask block are decided by their lane alone (from
+// the class bitsets, or by pattern_tile_flags); only the tiles on the diagonal or inside the
+// true-mask block are then evaluated word by word by the whole wave. No LDS, no barrier.
 __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__restrict__ true_bits,
                                                    const uint64_t *__restrict__ cbits,
                                                    const uint64_t *__restrict__ rrev,
@@ -584,129 +585,129 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
                                                    const uint64_t *__restrict__ off_all,
                                                    uint64_t *__restrict__ occ,
                                                    uint64_t *__restrict__ full, int *__restrict__ cnt) {
-  extern __shared__ uint8_t flags[];  // [nKt] bit0 occupied, bit1 full, bit2 still to be evaluated
-  __shared__ int total;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int qt = blockIdx.x, h = blockIdx.y;
+  const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+  if (item >= (int64_t)g.H * g.nQt) return;
+  const int h = (int)(item / g.nQt), qt = (int)(item % g.nQt);
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
-  const int i_last = min(g.S - 1, qt * g.tile_m + g.tile_m - 1);
-  const int kmax = i_last / g.tile_n;
-  if (threadIdx.x == 0) total = 0;
-  for (int kt = threadIdx.x; kt < g.nKt; kt += blockDim.x) flags[kt] = 0;
-  __syncthreads();
   const int i0 = qt * g.tile_m;
+  const int i_last = min(g.S - 1, i0 + g.tile_m - 1);
+  const int kmax = i_last / g.tile_n;
   // Square tiles, a whole row of tiles in the pattern region: 64 tiles at a time from the per-head
   // class bitsets. Only a tile that has matched and unmatched columns AND matched and unmatched
   // offsets needs the exact one-lane test for "full".
   const bool by_class = g.tile_m == g.tile_n && i0 >= g.L && i0 + g.tile_m <= g.S;
-  for (int kt = threadIdx.x; kt <= kmax; kt += blockDim.x) {
-    const int j0 = kt * g.tile_n, j1 = min(j0 + g.tile_n - 1, g.S - 1);
-    uint8_t f = 4;  // evaluate word by word
-    if (i0 >= g.L && j1 <= i0) {
-      bool exact = true;
-      if (by_class) {
-        const int d = qt - kt;  // >= 1 here
-        const int64_t pos = (int64_t)g.occw * 64 - 1 - d;
-        const uint64_t *ca = col_any + (int64_t)h * g.occw, *cf = col_all + (int64_t)h * g.occw;
-        const uint64_t *da = off_any + (int64_t)h * g.occw, *df = off_all + (int64_t)h * g.occw;
-        const bool c_any = (ca[kt >> 6] >> (kt & 63)) & 1, c_all = (cf[kt >> 6] >> (kt & 63)) & 1;
-        const bool d_any = (da[pos >> 6] >> (pos & 63)) & 1, d_all = (df[pos >> 6] >> (pos & 63)) & 1;
-        if (!(c_any && !c_all && d_any && !d_all)) {
-          exact = false;
-          f = (uint8_t)(((c_any || d_any) ? 1 : 0) | ((c_all || d_all) ? 3 : 0));
+  const uint64_t *ca = col_any + (int64_t)h * g.occw, *cf = col_all + (int64_t)h * g.occw;
+  const uint64_t *da = off_any + (int64_t)h * g.occw, *df = off_all + (int64_t)h * g.occw;
+  const int words = g.tile_m * g.wpr;
+  int total = 0;
+  for (int w = 0; w < g.occw; ++w) {
+    const int kt = w * 64 + lane;
+    int f = 0;
+    if (kt <= kmax) {
+      const int j0 = kt * g.tile_n, j1 = min(j0 + g.tile_n - 1, g.S - 1);
+      f = 4;  // evaluate word by word
+      if (i0 >= g.L && j1 <= i0) {
+        bool exact = true;
+        if (by_class) {
+          const int d = qt - kt;  // >= 1 here
+          const int64_t pos = (int64_t)g.occw * 64 - 1 - d;
+          const bool c_any = (ca[w] >> lane) & 1, c_all = (cf[w] >> lane) & 1;
+          const bool d_any = (da[pos >> 6] >> (pos & 63)) & 1, d_all = (df[pos >> 6] >> (pos & 63)) & 1;
+          if (!(c_any && !c_all && d_any && !d_all)) {
+            exact = false;
+            f = ((c_any || d_any) ? 1 : 0) | ((c_all || d_all) ? 3 : 0);
+          }
+        }
+        if (exact) {
+          f = pattern_tile_flags(cb, rr, g.pw, i0, i_last, j0, j1);
+          // a tile cut by the end of the sequence is never full (its bits past S are zero)
+          if (j0 + g.tile_n > g.S || i0 + g.tile_m > g.S) f &= 1;
         }
       }
-      if (exact) {
-        f = (uint8_t)pattern_tile_flags(cb, rr, g.pw, i0, i_last, j0, j1);
-        // a tile cut by the end of the sequence is never full (its bits past S are zero)
-        if (j0 + g.tile_n > g.S || i0 + g.tile_m > g.S) f &= 1;
-      }
     }
-    flags[kt] = f;
-  }
-  __syncthreads();
-  const int words = g.tile_m * g.wpr;
-  // the tiles still to be evaluated, found 64 at a time (one flag per lane, one ballot) and dealt to
-  // the four waves in turn
-  int dealt = 0;
-  for (int base = 0; base <= kmax; base += 64) {
-    uint64_t need = __ballot(base + lane <= kmax && (flags[base + lane] & 4));
-    while (need) {
-      const int kt = base + __ffsll((unsigned long long)need) - 1;
+    uint64_t ow = __ballot(f & 1), fw = __ballot(f & 2);
+    uint64_t need = __ballot(f & 4);
+    while (need) {  // wave-uniform
+      const int b = __ffsll((unsigned long long)need) - 1;
       need &= need - 1;
-      if ((dealt++ & 3) != wave) continue;
       bool any = false, all = true;
-      for (int w = lane; w < words; w += 64) {
-        const uint64_t m = mask_word(g, tb, cb, rr, qt * g.tile_m + w / g.wpr, kt * g.wpr + w % g.wpr);
+      for (int x = lane; x < words; x += 64) {
+        const uint64_t m = mask_word(g, tb, cb, rr, i0 + x / g.wpr, (w * 64 + b) * g.wpr + x % g.wpr);
         any |= m != 0;
         all &= m == ~0ull;
       }
-      const bool t_any = __ballot(any) != 0;
-      const bool t_all = __ballot(!all) == 0;
-      // bit 2 stays set: the other waves may still be reading it to deal out the same tiles
-      if (lane == 0) flags[kt] = (uint8_t)(4 | (t_any ? 1 : 0) | (t_all ? 2 : 0));
+      if (__ballot(any) != 0) ow |= 1ull << b;
+      if (__ballot(!all) == 0) fw |= 1ull << b;
     }
-  }
-  __syncthreads();
-  int mine = 0;
-  for (int w = wave; w < g.occw; w += 4) {
-    const int kt = w * 64 + lane;
-    const uint8_t f = kt < g.nKt ? flags[kt] : 0;
-    const uint64_t ow = __ballot(f & 1), fw = __ballot(f & 2);
     if (lane == 0) {
       occ[((int64_t)h * g.nQt + qt) * g.occw + w] = ow;
       full[((int64_t)h * g.nQt + qt) * g.occw + w] = fw;
-      mine += __popcll(ow);
     }
+    total += __popcll(ow);
   }
-  if (lane == 0 && mine) atomicAdd(&total, mine);
-  __syncthreads();
-  if (threadIdx.x == 0) cnt[(int64_t)h * g.nQt + qt] = total;
+  if (lane == 0) cnt[(int64_t)h * g.nQt + qt] = total;
 }
 
 // Exclusive scan of n counts by one block. group > 0: the result is laid out as [n / group]
 // rows of group + 1 offsets (row r ends where row r + 1 begins); group == 0: plain [n + 1].
+// Every thread takes kScanItems consecutive counts per pass, so that the block-wide part (a wave
+// scan, one exchange of the wave totals) is paid once per 8192 counts.
+constexpr int kScanItems = 8;
+
 __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__ cnt, int64_t n,
                                                          int group, int *__restrict__ ptr,
                                                          int64_t *__restrict__ total) {
-  __shared__ int64_t wave_sum[16];
-  __shared__ int64_t carry;
+  __shared__ int64_t wave_sum[2][16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (threadIdx.x == 0) carry = 0;
-  __syncthreads();
-  for (int64_t base = 0; base < n; base += 1024) {
-    const int64_t e = base + threadIdx.x;
-    const int64_t v = e < n ? cnt[e] : 0;
-    int64_t incl = v;
+  int64_t carry = 0;  // the same value in every thread
+  int pass = 0;
+  for (int64_t base = 0; base < n; base += 1024 * kScanItems, ++pass) {
+    const int64_t e0 = base + (int64_t)threadIdx.x * kScanItems;
+    int v[kScanItems];
+#pragma unroll
+    for (int x = 0; x < kScanItems; ++x) v[x] = e0 + x < n ? cnt[e0 + x] : 0;
+    int64_t mine = 0;
+#pragma unroll
+    for (int x = 0; x < kScanItems; ++x) mine += v[x];
+    int64_t incl = mine;
     for (int off = 1; off < 64; off <<= 1) {
       const int64_t up = __shfl_up(incl, off);
       if (lane >= off) incl += up;
     }
-    if (lane == 63) wave_sum[wave] = incl;
-    __syncthreads();
-    int64_t before = carry;
-    for (int w = 0; w < wave; ++w) before += wave_sum[w];
-    const int64_t excl = before + incl - v;
-    if (e < n) {
-      if (group > 0) {
-        const int64_t r = e / group, q = e % group;
-        ptr[r * (group + 1) + q] = (int)excl;
-        if (q == 0 && r > 0) ptr[(r - 1) * (group + 1) + group] = (int)excl;
-      } else {
-        ptr[e] = (int)excl;
-      }
+    if (lane == 63) wave_sum[pass & 1][wave] = incl;
+    __syncthreads();  // one barrier per pass: the totals of consecutive passes live in alternating buffers
+    int64_t before = carry, all = 0;
+    for (int w = 0; w < 16; ++w) {
+      const int64_t ws = wave_sum[pass & 1][w];
+      if (w < wave) before += ws;
+      all += ws;
     }
-    __syncthreads();
-    if (threadIdx.x == 1023) carry = excl + v;
-    __syncthreads();
+    int64_t excl = before + incl - mine;
+#pragma unroll
+    for (int x = 0; x < kScanItems; ++x) {
+      const int64_t e = e0 + x;
+      if (e < n) {
+        if (group > 0) {
+          const int64_t r = e / group, q = e % group;
+          ptr[r * (group + 1) + q] = (int)excl;
+          if (q == 0 && r > 0) ptr[(r - 1) * (group + 1) + group] = (int)excl;
+        } else {
+          ptr[e] = (int)excl;
+        }
+      }
+      excl += v[x];
+    }
+    carry += all;
   }
   if (threadIdx.x == 0) {
-    if (group > 0)
-      ptr[(n / group - 1) * (group + 1) + group] = (int)carry;
-    else
+    if (group > 0) {
+      if (n > 0) ptr[(n / group - 1) * (group + 1) + group] = (int)carry;
+    } else {
       ptr[n] = (int)carry;
+    }
     if (total) *total = carry;
   }
 }
@@ -720,7 +721,8 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
                                                    const int *__restrict__ row_ptr,
                                                    int *__restrict__ blk_col,
                                                    uint8_t *__restrict__ blk_kind,
-                                                   uint64_t *__restrict__ tile_bits, int64_t capacity) {
+                                                   uint64_t *__restrict__ tile_bits, int64_t capacity,
+                                                   bool skip_full_bits) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qt = blockIdx.x, h = blockIdx.y;
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
@@ -747,6 +749,13 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       // element words, and which key quarters of the tile hold a kept entry
       const bool is_full = (fl[kt >> 6] >> (kt & 63)) & 1;
       int quarters = 0;
+      if (is_full && skip_full_bits) {  // wave-uniform: column and kind only
+        if (lane == 0) {
+          if (blk_col) blk_col[t] = kt;
+          if (blk_kind) blk_kind[t] = (uint8_t)31;
+        }
+        continue;
+      }
       if (words == 256 && g.wpr == 2) {
         // 128 x 128 tiles: four words per lane, evaluated together so that their loads overlap
         uint64_t m[4];
@@ -866,6 +875,7 @@ int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *dia
   if (!p || !o) return DAM_ERR_INVALID_ARG;
   if (p->mode != DAM_FROM_ATTN_MAP && p->mode != DAM_FROM_PATTERNS) return DAM_ERR_INVALID_ARG;
   if (p->n_maps < 1 || p->seq < 1) return DAM_ERR_INVALID_ARG;
+  if (p->flags & ~DAM_MASK_SKIP_FULL_TILE_BITS) return DAM_ERR_INVALID_ARG;
   if (p->tile_m < 64 || p->tile_n < 64 || p->tile_m % 64 || p->tile_n % 64) return DAM_ERR_INVALID_ARG;
   if (p->tile_m > 256 || p->tile_n > 256) return DAM_ERR_UNSUPPORTED;
   if ((int64_t)(p->seq + p->tile_n - 1) / p->tile_n > 32768) return DAM_ERR_UNSUPPORTED;
@@ -1005,12 +1015,13 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
   // a4 + a5: tile occupancy, CSR offsets, tile bits
   if (want_blocks) {
     k_tile_classes<<<dim3(g.occw, g.H), 64, 0, stream>>>(g, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any, w.off_all);
-    k_tile_scan<<<dim3(g.nQt, g.H), 256, (size_t)g.nKt, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
-                                                                 w.off_all, w.occ, w.full, w.tile_cnt);
+    k_tile_scan<<<(unsigned)(((int64_t)g.H * g.nQt + 3) / 4), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all,
+                                                                              w.off_any, w.off_all, w.occ, w.full, w.tile_cnt);
     k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total);
     if (o->blk_col || o->blk_kind || o->tile_bits)
       k_tile_fill<<<dim3(g.nQt, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,
-                                                        o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity);
+                                                        o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
+                                                        (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0);
   }
   if (o->dense_bits) {
     const int sw = (g.S + 63) / 64;

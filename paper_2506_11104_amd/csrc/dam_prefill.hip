@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
                                                      const float *__restrict__ v,
                                                      const int *__restrict__ row_ptr,
                                                      const int *__restrict__ blk_col,
+                                                     const uint8_t *__restrict__ blk_kind,
                                                      const uint64_t *__restrict__ tile_bits,
                                                      float *__restrict__ out, float *__restrict__ lse) {
   constexpr int N = 4, LPR = D / N, GROUPS = 256 / LPR;
@@ -96,8 +97,9 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int t = t0; t < t1; ++t) {
       const int j0 = blk_col[t] * a.tile_n;
+      const bool full = blk_kind[t] & 1;  // every entry kept: the tile's words are not read (they may be unwritten)
       for (int wd = 0; wd < a.wpr; ++wd) {
-        uint64_t bits = tile_bits[((int64_t)t * a.tile_m + rl) * a.wpr + wd];
+        uint64_t bits = full ? ~0ull : tile_bits[((int64_t)t * a.tile_m + rl) * a.wpr + wd];
         while (bits) {
           const int j = j0 + wd * 64 + __ffsll((unsigned long long)bits) - 1;
           bits &= bits - 1;
@@ -647,10 +649,10 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   if (p->dtype == DAM_F32) {
     if (p->head_dim == 64)
       k_prefill_f32<64><<<blocks, 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
-                                               mk->blk_col, mk->tile_bits, (float *)out, lse);
+                                               mk->blk_col, mk->blk_kind, mk->tile_bits, (float *)out, lse);
     else
       k_prefill_f32<128><<<blocks, 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
-                                                mk->blk_col, mk->tile_bits, (float *)out, lse);
+                                                mk->blk_col, mk->blk_kind, mk->tile_bits, (float *)out, lse);
     return launch_status();
   }
   static int n_cu = 0;

@@ -103,6 +103,16 @@ def test_c3_mask_whole_block_index_bit_exact():
     assert np.array_equal(mask.blk_col.cpu().numpy(), col)
     assert np.array_equal(mask.blk_kind.cpu().numpy(), kind)
     assert np.array_equal(u64(mask.tile_bits), bits)
+    # the build bench.py times (full tiles carry no bits): everything else identical
+    lean = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=w.seq, diag_in=torch.from_numpy(dflag).cuda(),
+                        vert_in=torch.from_numpy(vflag).cuda(), flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    torch.cuda.synchronize()
+    partial = (kind & 1) == 0
+    assert np.array_equal(lean.blk_row_ptr.cpu().numpy().astype(np.int64), row_ptr)
+    assert np.array_equal(lean.blk_col.cpu().numpy(), col) and np.array_equal(lean.blk_kind.cpu().numpy(), kind)
+    assert np.array_equal(u64(lean.tile_bits)[partial], bits[partial])
+    assert (bits[~partial] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()
+    say(f"c3: {int(partial.sum())} partial tiles identical without the bits of the {int((~partial).sum())} full tiles")
 
 
 def test_c4_full_size():

@@ -195,6 +195,50 @@ def test_full_and_nearly_full_tiles_from_pattern_mixtures(tm, tn):
     assert int((mask.blk_kind & 1).sum().item()) > 20
 
 
+def test_skip_full_tile_bits_leaves_full_tiles_untouched_and_the_rest_identical():
+    """DAM_MASK_SKIP_FULL_TILE_BITS: row pointers, columns and kinds as without the flag; bits of partial
+    tiles identical to the oracle's; slots of full tiles keep what they held (here a marker)."""
+    rng = np.random.default_rng(25)
+    H, S = 3, 2000
+    d = np.zeros((H, S), np.uint8)
+    v = np.zeros((H, S), np.uint8)
+    d[0, :700] = 1
+    d[1, :300] = 1
+    d[1, 900:1300] = 1
+    v[1, :5] = 1
+    d[2] = rng.random(S) < 0.3
+    v[2, 100:400] = 1
+    art = oracle.from_patterns(d, v)
+    row_ptr, col, kind, bits = oracle.block_index(art, S, 128, 128)
+    n = len(col)
+    p = B.MaskParams(B.DAM_FROM_PATTERNS, H, 0, S, 128, 128, 0, 0, 0.5, 1e-8, 0.3, 0.8, float("nan"),
+                     B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    ws = B.mask_workspace(p, "cuda")
+    o = B.MaskOut()
+    rp = torch.empty((H, (S + 127) // 128 + 1), dtype=torch.int32, device="cuda")
+    bc = torch.empty(n, dtype=torch.int32, device="cuda")
+    bk = torch.empty(n, dtype=torch.uint8, device="cuda")
+    marker = 0x5A5A5A5A5A5A5A5A
+    tb = torch.full((n, 128, 2), marker, dtype=torch.int64, device="cuda")
+    tot = torch.zeros(1, dtype=torch.int64, device="cuda")
+    o.blk_row_ptr, o.blk_col, o.blk_kind, o.tile_bits = rp.data_ptr(), bc.data_ptr(), bk.data_ptr(), tb.data_ptr()
+    o.blk_capacity, o.blk_total = n, tot.data_ptr()
+    B.dam_mask_build(p, None, None, torch.from_numpy(d).cuda(), torch.from_numpy(v).cuda(), o, ws)
+    torch.cuda.synchronize()
+    assert int(tot.item()) == n
+    assert np.array_equal(rp.cpu().numpy().astype(np.int64), row_ptr)
+    assert np.array_equal(bc.cpu().numpy(), col) and np.array_equal(bk.cpu().numpy(), kind)
+    full = (kind & 1) == 1
+    assert full.sum() > 30 and (~full).sum() > 30
+    got = u64(tb)
+    assert np.array_equal(got[~full], bits[~full])
+    assert (got[full] == np.uint64(marker)).all()
+    assert (bits[full] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()      # what the flag leaves out is implied by the kind
+    p_bad = B.MaskParams(B.DAM_FROM_PATTERNS, H, 0, S, 128, 128, 0, 0, 0.5, 1e-8, 0.3, 0.8, float("nan"), 6)
+    assert B.lib().dam_mask_build(__import__("ctypes").byref(p_bad), None, None, 4096, 4096, __import__("ctypes").byref(o),
+                                  ws.data_ptr(), ws.numel(), None) == B.DAM_ERR_INVALID_ARG
+
+
 def test_capacity_overflow_reports_total_and_writes_nothing_past_it():
     rng = np.random.default_rng(23)
     H, S = 2, 640

@@ -118,6 +118,30 @@ def test_dense_causal_bf16_matches_oracle_and_is_all_full_tiles():
     compare(Q, K, V, art, mask, "bf16")
 
 
+@pytest.mark.parametrize("dtype,d,tile", [("bf16", 128, 128), ("f32", 64, 64)])
+def test_full_tiles_are_never_read(dtype, d, tile):
+    """With DAM_MASK_SKIP_FULL_TILE_BITS the pool slots of full tiles are unwritten: both kernels must
+    take such tiles from blk_kind alone. The slots are filled with a pattern that would wreck the result."""
+    rng = np.random.default_rng(35)
+    Hq, Hkv, S = 2, 1, 900
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), dtype)
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), dtype)
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), dtype)
+    dflag = np.zeros((Hq, S), np.uint8)
+    vflag = np.zeros((Hq, S), np.uint8)
+    dflag[0, :500] = 1
+    dflag[1, :333] = 1
+    vflag[1, :3] = 1
+    art = oracle.from_patterns(dflag, vflag)
+    mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=S, tile_m=tile, tile_n=tile,
+                        diag_in=torch.from_numpy(dflag).cuda(), vert_in=torch.from_numpy(vflag).cuda(),
+                        flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    full = (mask.blk_kind & 1).bool()
+    assert int(full.sum()) >= 6
+    mask.tile_bits[full] = 0x0F0F0F0F00000000
+    compare(Q, K, V, art, mask, dtype)
+
+
 def test_large_logits_do_not_overflow():
     # a masked-out key with a huge logit must not disturb the kept ones (mask before the max)
     rng = np.random.default_rng(33)
@@ -149,7 +173,10 @@ def test_c3_full_size_sampled_rows():
     Q, K, V = wl.qkv_iid(w)
     dflag, vflag = wl.patterns_c3(w)
     art = oracle.from_patterns(dflag, vflag)
-    mask = gpu_mask_from_art(art, w.seq, 128, 128)
+    # as bench.py builds it: full tiles carry no bits
+    mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=w.seq, diag_in=torch.from_numpy(dflag).cuda(),
+                        vert_in=torch.from_numpy(vflag).cuda(), flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    mask.tile_bits[(mask.blk_kind & 1).bool()] = 0
     rng = np.random.default_rng(34)
     n = 1536
     hs = rng.integers(0, w.hq, n).astype(np.int32)
