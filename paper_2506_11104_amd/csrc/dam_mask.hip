@@ -438,6 +438,15 @@ __global__ __launch_bounds__(256) void k_pattern_bitsets(const uint8_t *__restri
   }
 }
 
+// Word w of a bitset of pw words, 0 outside it. The index is clamped before the address is formed: the
+// set may live in LDS, and an address formed below the start of the LDS window is not an LDS address
+// any more, even if an instruction offset would bring it back inside.
+__device__ __forceinline__ uint64_t set_word(const uint64_t *__restrict__ bs, int w, int pw) {
+  const bool ok = (unsigned)w < (unsigned)pw;
+  const uint64_t v = bs[ok ? w : 0];
+  return ok ? v : 0;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Sec. 4.3: the 64 mask bits of row i, keys [64 wj, 64 wj + 64) of one head.
 __device__ __forceinline__ uint64_t diag_window(const uint64_t *__restrict__ rrev, int pw, int64_t u) {
@@ -447,9 +456,9 @@ __device__ __forceinline__ uint64_t diag_window(const uint64_t *__restrict__ rre
   if (s0 > Q || s0 + 63 < 0) return 0;
   const int64_t w0 = s0 >> 6;
   const int sh = (int)(s0 & 63);
-  const uint64_t lo = (w0 >= 0 && w0 < pw) ? rrev[w0] : 0;
+  const uint64_t lo = set_word(rrev, (int)w0, pw);
   if (sh == 0) return lo;
-  const uint64_t hi = (w0 + 1 >= 0 && w0 + 1 < pw) ? rrev[w0 + 1] : 0;
+  const uint64_t hi = set_word(rrev, (int)w0 + 1, pw);
   return (lo >> sh) | (hi << (64 - sh));
 }
 
@@ -571,6 +580,28 @@ __global__ void k_tile_classes(Geom g, const uint64_t *__restrict__ cbits, const
   }
 }
 
+// The column bitset and the reversed diagonal bitset of one head, copied into LDS by the whole
+// workgroup when they fit (lds_words = 2 pw, else 0): every mask word then costs LDS reads instead
+// of dependent global loads. Returns the pointers to use; contains a barrier.
+constexpr size_t kMaxStagedBytes = 48 * 1024;
+
+inline size_t staged_bytes(const Geom &g) {
+  const size_t b = (size_t)g.pw * 2 * sizeof(uint64_t);
+  return b <= kMaxStagedBytes ? b : 0;
+}
+
+__device__ __forceinline__ void stage_sets(uint64_t *lds_sets, bool staged, int pw, const uint64_t *&cb,
+                                           const uint64_t *&rr) {
+  if (!staged) return;  // uniform over the grid
+  for (int x = threadIdx.x; x < pw; x += blockDim.x) {
+    lds_sets[x] = cb[x];
+    lds_sets[pw + x] = rr[x];
+  }
+  __syncthreads();
+  cb = lds_sets;
+  rr = lds_sets + pw;
+}
+
 // Pass 1 of the block index: which key tiles of query tile (h, qt) hold a kept entry / are full.
 // One wave per query tile, 64 key tiles (one occupancy word) at a time, one lane per key tile. Tiles
 // strictly below the diagonal and outside the true-mask block are decided by their lane alone (from
@@ -584,14 +615,15 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
                                                    const uint64_t *__restrict__ off_any,
                                                    const uint64_t *__restrict__ off_all,
                                                    uint64_t *__restrict__ occ,
-                                                   uint64_t *__restrict__ full, int *__restrict__ cnt) {
+                                                   uint64_t *__restrict__ full, int *__restrict__ cnt, bool staged) {
+  extern __shared__ uint64_t lds_sets[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t item = (int64_t)blockIdx.x * 4 + wave;
-  if (item >= (int64_t)g.H * g.nQt) return;
-  const int h = (int)(item / g.nQt), qt = (int)(item % g.nQt);
+  const int h = blockIdx.y, qt = blockIdx.x * 4 + wave;
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
+  stage_sets(lds_sets, staged, g.pw, cb, rr);
+  if (qt >= g.nQt) return;
   const int i0 = qt * g.tile_m;
   const int i_last = min(g.S - 1, i0 + g.tile_m - 1);
   const int kmax = i_last / g.tile_n;
@@ -722,12 +754,14 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
                                                    int *__restrict__ blk_col,
                                                    uint8_t *__restrict__ blk_kind,
                                                    uint64_t *__restrict__ tile_bits, int64_t capacity,
-                                                   bool skip_full_bits) {
+                                                   bool skip_full_bits, bool staged) {
+  extern __shared__ uint64_t lds_sets[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qt = blockIdx.x, h = blockIdx.y;
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
+  stage_sets(lds_sets, staged, g.pw, cb, rr);
   const uint64_t *oc = occ + ((int64_t)h * g.nQt + qt) * g.occw;
   const uint64_t *fl = full + ((int64_t)h * g.nQt + qt) * g.occw;
   const int64_t first = row_ptr[(int64_t)h * (g.nQt + 1) + qt];
@@ -756,7 +790,45 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
         }
         continue;
       }
-      if (words == 256 && g.wpr == 2) {
+      if (words == 256 && g.wpr == 2 && qt * 128 >= g.L && qt * 128 + 128 <= g.S) {
+        // 128 x 128 tile with every row in the pattern region: a lane takes rows lane and lane + 64 whole
+        // (128 keys = two words). The offsets i - j of a row's 128 keys are 128 consecutive positions of
+        // the reversed diagonal set, starting at Q - (i - 128 kt): two funnel shifts over three words.
+        const int Q = g.pw * 64 - 1;
+        const uint64_t c0 = set_word(cb, 2 * kt, g.pw), c1 = set_word(cb, 2 * kt + 1, g.pw);
+        uint64_t m[2][2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int u0 = (qt - kt) * 128 + lane + 64 * u;  // offset of the tile's first key in this row, >= 0
+          const int s0 = Q - u0;
+          const int w0 = s0 >> 6, sh = s0 & 63;             // floor division also for negative positions
+          const uint64_t a = set_word(rr, w0, g.pw), b = set_word(rr, w0 + 1, g.pw), c = set_word(rr, w0 + 2, g.pw);
+          uint64_t d0 = a, d1 = b;
+          if (sh) {
+            d0 = (a >> sh) | (b << (64 - sh));
+            d1 = (b >> sh) | (c << (64 - sh));
+          }
+          m[u][0] = is_full ? ~0ull : (d0 | c0);
+          m[u][1] = is_full ? ~0ull : (d1 | c1);
+          if (kt == qt) {  // the diagonal tile (wave-uniform): keys up to u0 only
+            m[u][0] &= u0 >= 63 ? ~0ull : ((2ull << u0) - 1);
+            m[u][1] &= u0 >= 127 ? ~0ull : (u0 < 64 ? 0ull : ((2ull << (u0 - 64)) - 1));
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          if (tile_bits) {
+            uint4 st;
+            st.x = (uint32_t)m[u][0]; st.y = (uint32_t)(m[u][0] >> 32);
+            st.z = (uint32_t)m[u][1]; st.w = (uint32_t)(m[u][1] >> 32);
+            *reinterpret_cast<uint4 *>(tile_bits + t * 256 + 2 * (lane + 64 * u)) = st;
+          }
+          if ((uint32_t)m[u][0]) quarters |= 1;
+          if (m[u][0] >> 32) quarters |= 2;
+          if ((uint32_t)m[u][1]) quarters |= 4;
+          if (m[u][1] >> 32) quarters |= 8;
+        }
+      } else if (words == 256 && g.wpr == 2) {
         // 128 x 128 tiles: four words per lane, evaluated together so that their loads overlap
         uint64_t m[4];
 #pragma unroll
@@ -1015,13 +1087,14 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
   // a4 + a5: tile occupancy, CSR offsets, tile bits
   if (want_blocks) {
     k_tile_classes<<<dim3(g.occw, g.H), 64, 0, stream>>>(g, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any, w.off_all);
-    k_tile_scan<<<(unsigned)(((int64_t)g.H * g.nQt + 3) / 4), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all,
-                                                                              w.off_any, w.off_all, w.occ, w.full, w.tile_cnt);
+    const size_t lds_sets = staged_bytes(g);
+    k_tile_scan<<<dim3((g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
+                                                                     w.off_all, w.occ, w.full, w.tile_cnt, lds_sets > 0);
     k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total);
     if (o->blk_col || o->blk_kind || o->tile_bits)
-      k_tile_fill<<<dim3(g.nQt, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,
-                                                        o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
-                                                        (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0);
+      k_tile_fill<<<dim3(g.nQt, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,
+                                                               o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
+                                                               (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0);
   }
   if (o->dense_bits) {
     const int sw = (g.S + 63) / 64;
