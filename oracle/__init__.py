@@ -299,3 +299,53 @@ def attend_lists(q, kcache, vcache, kv_of, kept_ptr, kept_idx, scale: Optional[f
                                   _ptr(kept_idx, ctypes.c_int32), n, ctypes.c_double(sc),
                                   _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double))
     return out, lse
+
+
+# ---------------------------------------------------------------------------------------------
+@dataclass
+class EvictionPlan:
+    """Which cached keys a KV head still needs at position p, and where they live in a compacted
+    cache (Sec. 2: local patterns allow evicting the cache beyond the attention span; Sec. 4.3: a row
+    i of the pattern region keeps key j iff i - j is a matched diagonal or j a matched column)."""
+    window: np.ndarray        # [Hkv] i32: W_g = 1 + largest matched diagonal offset of the group's heads (0: none)
+    col_ptr: np.ndarray       # [Hkv + 1] i32 offsets into cols
+    cols: np.ndarray          # i32: matched columns <= p of the group's heads (union), ascending per group
+
+
+def eviction_plan(diag_flag, vert_flag, Hkv: int, p: int) -> EvictionPlan:
+    """Pattern-only masks (flags over 0..P-1, rows in the pattern region). For the query heads h of KV
+    head g: a key j <= p is attended by some row i >= p of some h  iff  j is a matched column of such
+    an h, or  p - j <= r for a matched diagonal r of such an h, i.e. j >= p - r_max(g)."""
+    df, vf = _u8(diag_flag), _u8(vert_flag)
+    Hq, P = df.shape
+    G = Hq // Hkv
+    window = np.zeros(Hkv, np.int32)
+    ptr = np.zeros(Hkv + 1, np.int32)
+    cols = []
+    for g in range(Hkv):
+        rmax = -1
+        live_cols = set()
+        for h in range(g * G, (g + 1) * G):
+            for r in range(P):
+                if df[h, r] and r > rmax:
+                    rmax = r
+            for c in range(min(P, p + 1)):
+                if vf[h, c]:
+                    live_cols.add(c)
+        window[g] = rmax + 1
+        cols.extend(sorted(live_cols))
+        ptr[g + 1] = len(cols)
+    return EvictionPlan(window=window, col_ptr=ptr, cols=np.array(cols, np.int32))
+
+
+def eviction_slot(plan: EvictionPlan, g: int, j: int) -> int:
+    """Row of key j in KV head g's compacted cache: matched columns first, in ascending order, then a
+    ring of W_g rows in which key j sits at position j mod W_g (so a key never moves as p advances).
+    -1 for a key that is neither a live column nor representable in the ring (W_g = 0)."""
+    a, b = int(plan.col_ptr[g]), int(plan.col_ptr[g + 1])
+    seg = plan.cols[a:b]
+    k = int(np.searchsorted(seg, j))
+    if k < len(seg) and seg[k] == j:
+        return k
+    W = int(plan.window[g])
+    return (b - a) + j % W if W > 0 else -1
