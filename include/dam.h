@@ -14,6 +14,8 @@
  *                             (paper Sec. 3 and the last two equations of Sec. 4.3).
  *   dam_sparse_attn_decode    the same formula for one new query row per (sequence, head), reading
  *                             only the kept K/V rows.
+ *   dam_kv_evict_plan, dam_kv_compact, dam_kv_remap_lists   drop the cached keys no future row of a
+ *                             pattern mask attends and decode from the compacted cache (paper Sec. 2).
  *
  * Conventions shared by every entry point
  *   - Plain C. "device" pointers are HIP device addresses, "host" pointers are ordinary host memory.
@@ -288,6 +290,59 @@ int dam_sparse_attn_decode(const dam_decode_params *params, const void *q, const
                            const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
                            int64_t max_kept, void *out, float *lse, void *ws, size_t ws_bytes,
                            void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * dam_kv_evict_plan, dam_kv_compact, dam_kv_remap_lists: KV-cache eviction for decode
+ *
+ * Sec. 2 (local attention patterns allow evicting the KV cache beyond the attention span) applied to
+ * the mask of Sec. 4.3: in the pattern region row i keeps key j iff i - j is a matched diagonal or j is
+ * a matched column. For the query heads of KV head g, a cached key j <= pos is still attended by some
+ * row i >= pos iff j is a matched column of one of them, or j >= pos - r_max(g) (r_max: their largest
+ * matched diagonal). Everything else can be dropped. The compacted cache of (sequence, g) holds
+ *     rows [0, n_col(g))                 the live columns, ascending,
+ *     rows [n_col(g), n_col(g) + W(g))   a ring, W = r_max + 1: key j at row n_col + j mod W,
+ * so no row moves while the position advances: the caller writes the K / V row of a new key j to row
+ * n_col + j mod W (it overwrites the key that has just left the window). Matched columns that first
+ * become <= pos later change n_col: plan and compact again then (stripe columns lie below the capture
+ * length, so this does not happen once pos has passed it).
+ * Valid for rows of the pattern region only (pos >= pcl; masks given as patterns: always).
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t batch, hq, hkv;
+  int32_t n_flags;            /* P: length of each flag array                                      */
+  int32_t pos;                /* position of the newest cached key                                 */
+  int32_t head_dim, dtype;    /* of the caches (dam_compact only); a row must be a multiple of 16 B */
+  int32_t kv_capacity;        /* rows per (sequence, KV head) of the full caches                   */
+  int32_t compact_capacity;   /* rows per (sequence, KV head) of the compacted caches              */
+  int64_t kv_stride[3];       /* element strides of batch, KV head, position (full caches)         */
+  int64_t compact_stride[3];  /* the same for the compacted caches                                 */
+} dam_evict_params;
+
+size_t dam_kv_evict_workspace(const dam_evict_params *params);
+
+/* diag_flag, vert_flag  device u8 [hq][n_flags]: matched diagonals / columns per query head.
+ * window    device i32 [hkv]: W(g) (0 when the group has no matched diagonal).
+ * col_ptr   device i32 [hkv + 1], cols device i32 [col_capacity]: live columns per KV head, ascending.
+ * rows      device i32 [hkv] or NULL: n_col(g) + W(g), the rows the compacted cache of g needs.
+ * col_total device i64 [1]: number of live columns over all KV heads, valid even when it exceeds
+ *           col_capacity (nothing is written past it); call with cols == NULL to size. */
+int dam_kv_evict_plan(const dam_evict_params *params, const uint8_t *diag_flag, const uint8_t *vert_flag,
+                      int32_t *window, int32_t *col_ptr, int32_t *cols, int64_t col_capacity, int32_t *rows,
+                      int64_t *col_total, void *ws, size_t ws_bytes, void *stream);
+
+/* Gathers the live rows of the full caches [batch][hkv][kv_capacity][head_dim] into the compacted
+ * ones [batch][hkv][compact_capacity][head_dim] (device pointers, strides in params). Ring rows whose
+ * key does not exist yet (pos + 1 < W) are left untouched. */
+int dam_kv_compact(const dam_evict_params *params, const int32_t *window, const int32_t *col_ptr,
+                   const int32_t *cols, const void *kcache, const void *vcache, void *kcompact, void *vcompact,
+                   void *stream);
+
+/* kept_slot[e] = row of key kept_idx[e] in its KV head's compacted cache, for the lists of
+ * dam_sparse_attn_decode (kept_ptr device i32 [batch*hq + 1]); the order of a list is kept, so decode
+ * from the compacted cache adds the same terms in the same order. */
+int dam_kv_remap_lists(const dam_evict_params *params, const int32_t *window, const int32_t *col_ptr,
+                       const int32_t *cols, const int32_t *kept_ptr, const int32_t *kept_idx,
+                       int32_t *kept_slot, void *stream);
 
 /* Library version, for the loader's sanity check. */
 int dam_version(void);

@@ -74,7 +74,14 @@ class CaptureParams(ctypes.Structure):
                 ("q_stride", ctypes.c_int64 * 2), ("k_stride", ctypes.c_int64 * 2)]
 
 
-EXPORTS = ["dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
+class EvictParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32), ("n_flags", ctypes.c_int32),
+                ("pos", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("kv_capacity", ctypes.c_int32), ("compact_capacity", ctypes.c_int32),
+                ("kv_stride", ctypes.c_int64 * 3), ("compact_stride", ctypes.c_int64 * 3)]
+
+
+EXPORTS = ["dam_kv_evict_workspace", "dam_kv_evict_plan", "dam_kv_compact", "dam_kv_remap_lists", "dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
            "dam_mask_build_from_qk_workspace", "dam_mask_build_from_qk", "dam_sparse_attn_prefill_workspace",
            "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode", "dam_version"]
 
@@ -112,6 +119,14 @@ def lib() -> ctypes.CDLL:
         L.dam_sparse_attn_decode_workspace.argtypes = [ctypes.POINTER(DecodeParams), i64]
         L.dam_sparse_attn_decode.restype = ctypes.c_int
         L.dam_sparse_attn_decode.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dam_kv_evict_workspace.restype = sz
+        L.dam_kv_evict_workspace.argtypes = [ctypes.POINTER(EvictParams)]
+        L.dam_kv_evict_plan.restype = ctypes.c_int
+        L.dam_kv_evict_plan.argtypes = [ctypes.POINTER(EvictParams), vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dam_kv_compact.restype = ctypes.c_int
+        L.dam_kv_compact.argtypes = [ctypes.POINTER(EvictParams), vp, vp, vp, vp, vp, vp, vp, vp]
+        L.dam_kv_remap_lists.restype = ctypes.c_int
+        L.dam_kv_remap_lists.argtypes = [ctypes.POINTER(EvictParams), vp, vp, vp, vp, vp, vp, vp]
         L.dam_version.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -362,3 +377,67 @@ def dam_sparse_attn_decode(q, kcache, vcache, kept_ptr, kept_idx, max_kept: int,
                                       max_kept, _p(out), _p(lse), _p(ws), ws.numel(), _stream())
     _check("dam_sparse_attn_decode", st)
     return (out, lse) if (want_lse or lse is not None) else out
+
+
+# ---------------------------------------------------------------------------------------------
+@dataclass
+class EvictionPlan:
+    """Device buffers written by dam_kv_evict_plan."""
+    params: EvictParams
+    window: torch.Tensor      # [hkv] i32
+    col_ptr: torch.Tensor     # [hkv + 1] i32
+    cols: torch.Tensor        # [n_cols] i32 (at least one element is allocated)
+    rows: torch.Tensor        # [hkv] i32: rows the compacted cache of each KV head needs
+    n_cols: int
+
+
+def kv_evict_plan(diag_flag: torch.Tensor, vert_flag: torch.Tensor, hkv: int, pos: int, batch: int = 1) -> EvictionPlan:
+    """Two calls: size the column list, then fill it. diag_flag, vert_flag u8 [hq][P] on the device."""
+    hq, P = diag_flag.shape
+    dev = diag_flag.device
+    p = EvictParams()
+    p.batch, p.hq, p.hkv, p.n_flags, p.pos = batch, hq, hkv, P, pos
+    n = lib().dam_kv_evict_workspace(ctypes.byref(p))
+    ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
+    window = torch.empty(hkv, dtype=torch.int32, device=dev)
+    col_ptr = torch.empty(hkv + 1, dtype=torch.int32, device=dev)
+    rows = torch.empty(hkv, dtype=torch.int32, device=dev)
+    total = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def call(cols, cap):
+        st = lib().dam_kv_evict_plan(ctypes.byref(p), _p(diag_flag), _p(vert_flag), _p(window), _p(col_ptr), _p(cols), cap,
+                                     _p(rows), _p(total), _p(ws), ws.numel(), _stream())
+        _check("dam_kv_evict_plan", st)
+
+    call(None, 0)
+    n_cols = int(total.item())
+    cols = torch.empty(max(n_cols, 1), dtype=torch.int32, device=dev)
+    if n_cols:
+        call(cols, n_cols)
+    return EvictionPlan(p, window, col_ptr, cols, rows, n_cols)
+
+
+def kv_compact(plan: EvictionPlan, kcache: torch.Tensor, vcache: torch.Tensor, kcompact: torch.Tensor,
+               vcompact: torch.Tensor) -> None:
+    """caches [B][Hkv][cap][d], compacted caches [B][Hkv][ccap][d] (d contiguous, K and V alike)."""
+    assert kcache.stride() == vcache.stride() and kcompact.stride() == vcompact.stride()
+    p = plan.params
+    p.batch, p.head_dim, p.dtype = kcache.shape[0], kcache.shape[3], _dtype_code(kcache)
+    p.kv_capacity, p.compact_capacity = kcache.shape[2], kcompact.shape[2]
+    p.kv_stride = (ctypes.c_int64 * 3)(*kcache.stride()[:3])
+    p.compact_stride = (ctypes.c_int64 * 3)(*kcompact.stride()[:3])
+    st = lib().dam_kv_compact(ctypes.byref(p), _p(plan.window), _p(plan.col_ptr), _p(plan.cols), _p(kcache), _p(vcache),
+                              _p(kcompact), _p(vcompact), _stream())
+    _check("dam_kv_compact", st)
+
+
+def kv_remap_lists(plan: EvictionPlan, kept_ptr: torch.Tensor, kept_idx: torch.Tensor, batch: int,
+                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty_like(kept_idx)
+    p = plan.params
+    p.batch = batch
+    st = lib().dam_kv_remap_lists(ctypes.byref(p), _p(plan.window), _p(plan.col_ptr), _p(plan.cols), _p(kept_ptr),
+                                  _p(kept_idx), _p(out), _stream())
+    _check("dam_kv_remap_lists", st)
+    return out

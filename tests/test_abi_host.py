@@ -162,6 +162,32 @@ def test_capture_argument_errors():
     assert both > L.dam_mask_build_workspace(ctypes.byref(mask_params()))
 
 
+def test_eviction_argument_errors():
+    L = B.lib()
+    p = B.EvictParams()
+    p.batch, p.hq, p.hkv, p.n_flags, p.pos, p.head_dim, p.dtype, p.kv_capacity, p.compact_capacity = 2, 4, 2, 512, 300, 128, B.DAM_BF16, 512, 64
+    p.kv_stride = (ctypes.c_int64 * 3)(2 * 512 * 128, 512 * 128, 128)
+    p.compact_stride = (ctypes.c_int64 * 3)(2 * 64 * 128, 64 * 128, 128)
+
+    def plan(pp, flags=4096, ws=4096, ws_bytes=1 << 20, cols=None, cap=0):
+        return L.dam_kv_evict_plan(ctypes.byref(pp), flags, 4096, 4096, 4096, cols, cap, None, 4096, ws, ws_bytes, None)
+
+    assert plan(p, flags=None) == B.DAM_ERR_INVALID_ARG
+    assert plan(p, ws_bytes=1) == B.DAM_ERR_WORKSPACE
+    assert plan(p, cap=5) == B.DAM_ERR_INVALID_ARG                     # a capacity without a column buffer
+    p.hq = 5
+    assert plan(p) == B.DAM_ERR_INVALID_ARG
+    p.hq = 4
+    assert L.dam_kv_compact(ctypes.byref(p), 4096, 4096, 4096, 4096, 4096, 4096, None, None) == B.DAM_ERR_INVALID_ARG
+    p.head_dim = 100                                                   # 200-byte rows
+    assert L.dam_kv_compact(ctypes.byref(p), 4096, 4096, 4096, 4096, 4096, 4096, 4096, None) == B.DAM_ERR_UNSUPPORTED
+    p.head_dim, p.pos = 128, 512                                       # newest key beyond the cache
+    assert L.dam_kv_compact(ctypes.byref(p), 4096, 4096, 4096, 4096, 4096, 4096, 4096, None) == B.DAM_ERR_INVALID_ARG
+    p.pos = 300
+    assert L.dam_kv_remap_lists(ctypes.byref(p), 4096, 4096, 4096, None, 4096, 4096, None) == B.DAM_ERR_INVALID_ARG
+    assert L.dam_kv_evict_workspace(ctypes.byref(p)) > 0
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libdam.so"))
