@@ -245,7 +245,42 @@ def bench_decode(args, torch, B, wl):
     ub, sb = 0.5 * (ub_first + ub_last), 0.5 * (sum_first + sum_last)
     list_us = float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e3
     dec_us = float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e3
-    return {"workload": "c5", "steps": steps, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
+
+    # KV eviction at the first timed position: plan, gather into the compacted cache, remap the lists, decode from it
+    pos0 = w.seq - 1
+    dq, vq = torch.from_numpy(dflag).to(dev), torch.from_numpy(vflag).to(dev)
+    plan = B.kv_evict_plan(dq, vq, w.hkv, pos0, batch=w.batch)
+    ccap = int(plan.rows.max().item())
+    kcmp = torch.empty((w.batch, w.hkv, ccap, w.head_dim), dtype=torch.bfloat16, device=dev)
+    vcmp = torch.empty_like(kcmp)
+    slot = torch.empty_like(kept_idx)
+
+    def timed(fn, n):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ev = events(2)
+        ev[0].record()
+        for _ in range(n):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / n * 1e3
+
+    compact_us = timed(lambda: B.kv_compact(plan, kc, vc, kcmp, vcmp), 20)
+    live_rows = int(plan.rows.sum().item()) * w.batch
+    compact_bytes = live_rows * w.head_dim * 2 * 2 * 2                  # K and V rows, read and written
+    remap_us = timed(lambda: B.kv_remap_lists(plan, kept_ptr, kept_idx, w.batch, out=slot), 20)
+    dpc = B.decode_params(qs[0], kcmp, out)
+    ws_c = B.decode_workspace(dpc, max_kept, dev)
+    dec_c_us = timed(lambda: B.dam_sparse_attn_decode(qs[0], kcmp, vcmp, kept_ptr, slot, max_kept, out=out, ws=ws_c), 50)
+    evict = {"rows_kept_per_kv_head": [int(x) for x in plan.rows.cpu()], "cache_rows": cap,
+             "cache_bytes_ratio": ccap / cap, "compact_us": compact_us, "compact_bytes": compact_bytes,
+             "remap_us": remap_us, "decode_from_compacted_us": dec_c_us,
+             "roofline": {"bound": "hbm", "achieved": compact_bytes / (compact_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
+                          "unit": "GB/s", "frac": compact_bytes / (compact_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+    del kcmp, vcmp
+    return {"workload": "c5", "steps": steps, "kv_eviction": evict, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
             "decode_us": dec_us, "kept_per_list": sb / (items * w.head_dim * 4), "union_bytes": ub, "sum_bytes": sb,
             "gbs_union": ub / (dec_us * 1e-6) / 1e9, "gbs_sum": sb / (dec_us * 1e-6) / 1e9,
             "roofline": {"bound": "hbm", "achieved": ub / (dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
