@@ -36,6 +36,10 @@ def lib() -> ctypes.CDLL:
         _LIB.dam_oracle_boxcox.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
                                            ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                            ctypes.POINTER(ctypes.c_float)]
+        _LIB.dam_oracle_transform.restype = ctypes.c_float
+        _LIB.dam_oracle_transform.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
+                                              ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                              ctypes.c_float, ctypes.POINTER(ctypes.c_float)]
         _LIB.dam_oracle_true_mask.restype = None
         _LIB.dam_oracle_true_mask.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_float, ctypes.c_float, ctypes.POINTER(ctypes.c_uint8)]
@@ -146,6 +150,22 @@ def boxcox(attn_sum: np.ndarray, attn_cnt: Optional[np.ndarray], lam: float, eps
     return B, np.float32(bmin)
 
 
+TRANSFORMS = {"boxcox": 0, "raw_sum": 1, "average": 2, "log": 3, "yeo_johnson": 4, "zscore": 5, "minmax": 6,
+              "sqrt": 7, "arcsinh": 8}
+
+
+def transform(attn_sum: np.ndarray, attn_cnt: Optional[np.ndarray], kind: str, lam: float, eps: float):
+    """App. B: one of the nine feature-amplification transforms. Returns (T [H][L][L] f32, tmin);
+    T - tmin is the normalised map the threshold of Sec. 4.2.3 is applied to."""
+    A = _f32(attn_sum)
+    H, L, _ = A.shape
+    C = _f32(attn_cnt) if attn_cnt is not None else None
+    T = np.empty_like(A)
+    tmin = lib().dam_oracle_transform(_ptr(A, ctypes.c_float), _ptr(C, ctypes.c_float), H, L, TRANSFORMS[kind],
+                                      ctypes.c_float(lam), ctypes.c_float(eps), _ptr(T, ctypes.c_float))
+    return T, np.float32(tmin)
+
+
 def true_mask(B: np.ndarray, bmin, tau: float) -> np.ndarray:
     """Sec. 4.2.3: m = (B - bmin >= tau) and causal, [H][L][L] u8."""
     B = _f32(B)
@@ -170,9 +190,10 @@ def match(m: np.ndarray, mu: float):
 
 
 def derive(attn_sum, attn_cnt, lam: float, eps: float, tau: float, mu: float,
-           bmin_override: Optional[float] = None) -> MaskArtefact:
-    """Stage one end to end (Sec. 4.2.2 - 4.2.4): statistics at length L -> stored artefact."""
-    B, bmin = boxcox(attn_sum, attn_cnt, lam, eps)
+           bmin_override: Optional[float] = None, kind: str = "boxcox") -> MaskArtefact:
+    """Stage one end to end (Sec. 4.2.2 - 4.2.4): statistics at length L -> stored artefact.
+    kind selects the transform (App. B); the default is the method's Box-Cox."""
+    B, bmin = boxcox(attn_sum, attn_cnt, lam, eps) if kind == "boxcox" else transform(attn_sum, attn_cnt, kind, lam, eps)
     if bmin_override is not None:
         bmin = np.float32(bmin_override)
     m = true_mask(B, bmin, tau)

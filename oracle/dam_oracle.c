@@ -19,7 +19,10 @@
  * dense causal attention, a brute-force numpy softmax, convexity, single-key and LSE-merge
  * identities. No function here is "parity unpinned" for lambda in {0.5, 1}; lambda = 0 and general
  * lambda (logf / powf, not correctly rounded) are pinned only up to a few ulp at the threshold
- * boundary and are marked "parity unpinned" for bit-exactness.
+ * boundary and are marked "parity unpinned" for bit-exactness. The same holds for the alternative
+ * transforms of App. B: raw sum, average, min-max and square root are exact sequences; log,
+ * Yeo-Johnson, arcsinh (library functions) and z-score (fp64 sums) are "parity unpinned" for
+ * bit-exactness and compared up to a band around the threshold.
  */
 #include <math.h>
 #include <stddef.h>
@@ -77,6 +80,89 @@ float dam_oracle_boxcox(const float *attn_sum, const float *attn_cnt, int32_t H,
         if (b < bmin) bmin = b;
       }
   return bmin;
+}
+
+/* App. B, "Feature Amplification Transformation Methods": the nine alternatives for the step
+ * between the mean map and the threshold. With Abar = A / (C + eps) and X = max(Abar, eps):
+ *   0 Box-Cox (lambda)  (X^lambda - 1) / lambda, ln X at lambda = 0      (the method's default)
+ *   1 raw sum           A
+ *   2 average           Abar
+ *   3 log               ln X
+ *   4 Yeo-Johnson (lambda)  ((X + 1)^lambda - 1) / lambda, ln(X + 1) at lambda = 0   (X >= eps > 0: the
+ *                       branches for negative inputs never apply)
+ *   5 z-score           (X - mu) / (sigma + eps), mu and sigma (population) over every stored entry of
+ *                       every map of the call, accumulated in fp64 and rounded to fp32
+ *   6 min-max           (X - min X) / ((max X - min X) + eps), min and max over the same scope
+ *   7 square root       sqrt X
+ *   8 arcsinh           asinh X
+ * each an fp32 sequence of individually rounded operations, and "unless otherwise stated" the global
+ * minimum of the result is subtracted afterwards (App. B): this function writes T and returns that
+ * minimum, exactly like dam_oracle_boxcox. cnt == NULL as there (one causal capture). */
+float dam_oracle_transform(const float *attn_sum, const float *attn_cnt, int32_t H, int32_t L,
+                           int32_t kind, float lambda, float eps, float *T) {
+  if (kind == 0) return dam_oracle_boxcox(attn_sum, attn_cnt, H, L, lambda, eps, T);
+  const int64_t n = (int64_t)H * L * L;
+  /* pass 1: X (into T), and the statistics of X that z-score and min-max need */
+  double sum = 0.0, sumsq = 0.0;
+  float xmin = INFINITY, xmax = -INFINITY;
+  for (int64_t h = 0; h < H; ++h)
+    for (int64_t i = 0; i < L; ++i)
+      for (int64_t j = 0; j < L; ++j) {
+        const int64_t at = (h * L + i) * L + j;
+        float a, c;
+        if (attn_cnt) {
+          a = attn_sum[at];
+          c = attn_cnt[at];
+        } else {
+          a = (j <= i) ? attn_sum[at] : 0.0f;
+          c = (j <= i) ? 1.0f : 0.0f;
+        }
+        const float denom = c + eps;
+        const float abar = a / denom;
+        const float x = fmaxf(abar, eps);
+        sum += (double)x;
+        sumsq += (double)x * (double)x;
+        if (x < xmin) xmin = x;
+        if (x > xmax) xmax = x;
+        T[at] = kind == 1 ? a : (kind == 2 ? abar : x);
+      }
+  const double mean = sum / (double)n;
+  double var = sumsq / (double)n - mean * mean;
+  if (var < 0.0) var = 0.0;
+  const float mu = (float)mean, sigma = (float)sqrt(var);
+  float tmin = INFINITY;
+  for (int64_t at = 0; at < n; ++at) {
+    const float x = T[at];
+    float t = x; /* kinds 1 and 2 */
+    if (kind == 3) {
+      t = logf(x);
+    } else if (kind == 4) {
+      const float x1 = x + 1.0f;
+      if (lambda == 0.0f) {
+        t = logf(x1);
+      } else {
+        const float p = powf(x1, lambda);
+        const float num = p - 1.0f;
+        t = num / lambda;
+      }
+    } else if (kind == 5) {
+      const float num = x - mu;
+      const float den = sigma + eps;
+      t = num / den;
+    } else if (kind == 6) {
+      const float num = x - xmin;
+      const float range = xmax - xmin;
+      const float den = range + eps;
+      t = num / den;
+    } else if (kind == 7) {
+      t = sqrtf(x);
+    } else if (kind == 8) {
+      t = asinhf(x);
+    }
+    T[at] = t;
+    if (t < tmin) tmin = t;
+  }
+  return tmin;
 }
 
 /* Sec. 4.2.2 last equation and Sec. 4.2.3: Bstar = B - bmin; m[i][j] = 1 iff Bstar >= tau.
