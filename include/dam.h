@@ -51,6 +51,21 @@ typedef enum {
 
 typedef enum { DAM_F32 = 0, DAM_BF16 = 1 } dam_dtype;
 
+/* dam_mask_params.transform: the method's Box-Cox, or one of the alternatives of App. B ("Feature
+ * Amplification Transformation Methods"), with X = max(Abar, eps); the global minimum of the result is
+ * subtracted before the threshold in every case.
+ *   raw sum A; average Abar; log ln X; Yeo-Johnson ((X+1)^lambda - 1)/lambda, ln(X+1) at lambda 0;
+ *   z-score (X - mean X)/(std X + eps) and min-max (X - min X)/((max X - min X) + eps), statistics over
+ *   every stored entry of every map of the call; square root; arcsinh.
+ * raw sum, average, min-max and square root are exact fp32 sequences like the Box-Cox path; log,
+ * Yeo-Johnson, arcsinh (library functions) and z-score (fp64 sums in no fixed order) can decide
+ * entries within rounding of the threshold differently from another implementation. Any lambda is
+ * accepted for Yeo-Johnson. FROM_ATTN_MAP only; dam_mask_build_from_qk takes Box-Cox only. */
+typedef enum {
+  DAM_T_BOXCOX = 0, DAM_T_RAW_SUM = 1, DAM_T_AVERAGE = 2, DAM_T_LOG = 3, DAM_T_YEO_JOHNSON = 4,
+  DAM_T_ZSCORE = 5, DAM_T_MINMAX = 6, DAM_T_SQRT = 7, DAM_T_ARCSINH = 8
+} dam_transform;
+
 /* dam_mask_params.flags */
 typedef enum {
   DAM_MASK_SKIP_FULL_TILE_BITS = 1 /* do not write tile_bits of full tiles (blk_kind bit 0): the attention
@@ -99,6 +114,7 @@ typedef struct {
   float mu;          /* pattern-match threshold (paper: 0.8)                                        */
   float bmin_override; /* NaN: use the minimum over this call's maps; otherwise this value is bmin  */
   int32_t flags;     /* bit set of dam_mask_flags                                                   */
+  int32_t transform; /* dam_transform: the step between the mean map and the threshold (0: Box-Cox)  */
 } dam_mask_params;
 
 /* Outputs of dam_mask_build. Every pointer is a device pointer owned by the caller; any of them may

@@ -21,6 +21,8 @@ DAM_OK, DAM_ERR_INVALID_ARG, DAM_ERR_UNSUPPORTED, DAM_ERR_WORKSPACE, DAM_ERR_CAP
 DAM_F32, DAM_BF16 = 0, 1
 DAM_FROM_ATTN_MAP, DAM_FROM_PATTERNS = 0, 1
 DAM_MASK_SKIP_FULL_TILE_BITS = 1
+TRANSFORMS = {"boxcox": 0, "raw_sum": 1, "average": 2, "log": 3, "yeo_johnson": 4, "zscore": 5, "minmax": 6,
+              "sqrt": 7, "arcsinh": 8}
 
 _STATUS = {0: "DAM_OK", -1: "DAM_ERR_INVALID_ARG", -2: "DAM_ERR_UNSUPPORTED", -3: "DAM_ERR_WORKSPACE",
            -4: "DAM_ERR_CAPACITY", -5: "DAM_ERR_DEVICE"}
@@ -37,7 +39,8 @@ class MaskParams(ctypes.Structure):
                 ("seq", ctypes.c_int32), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
                 ("row_begin", ctypes.c_int32), ("row_end", ctypes.c_int32), ("lam", ctypes.c_float),
                 ("eps", ctypes.c_float), ("tau", ctypes.c_float), ("mu", ctypes.c_float),
-                ("bmin_override", ctypes.c_float), ("flags", ctypes.c_int32)]
+                ("bmin_override", ctypes.c_float), ("flags", ctypes.c_int32),
+                ("transform", ctypes.c_int32)]
 
 
 class MaskOut(ctypes.Structure):
@@ -230,13 +233,13 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
                diag_in: Optional[torch.Tensor] = None, vert_in: Optional[torch.Tensor] = None,
                true_bits: Optional[torch.Tensor] = None, blocks: bool = True, tile_bits: bool = True,
                dense: bool = False, rows: Optional[Tuple[int, int]] = None, device="cuda",
-               qk: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, scale: float = 0.0, flags: int = 0) -> Mask:
+               qk: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, scale: float = 0.0, flags: int = 0, transform: int = 0) -> Mask:
     """Convenience wrapper: allocates the outputs, sizes the tile pool / kept lists with a first
     call (blk_col == NULL), then fills them with a second. Only allocation and marshalling.
     qk = (q [H][L][d], k [Hkv][L][d]) selects dam_mask_build_from_qk (one captured sequence, no map)."""
     dev = torch.device(device)
     p = MaskParams(mode, H, L, S, tile_m, tile_n, rows[0] if rows else 0, rows[1] if rows else 0, lam, eps, tau, mu,
-                   bmin_override, flags)
+                   bmin_override, flags, transform)
     if qk is not None:
         cp = capture_params(qk[0], qk[1], L, scale)
         ws = mask_from_qk_workspace(p, cp, dev)

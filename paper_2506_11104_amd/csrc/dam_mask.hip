@@ -148,7 +148,167 @@ __global__ void k_threshold(float eps, float tau, const float *__restrict__ bmin
   *theta_key = hi;
 }
 
-template <bool FROM_A>
+// ------------------------------------------------------------------------------------------------
+// App. B: the alternative transforms between the mean map and the threshold (dam_transform other
+// than Box-Cox). Every one of them is non-decreasing in the mean (raw sum: in the sum), so the same
+// scheme applies: the statistics the transform needs are reduced over every stored entry, the
+// minimum of the transformed map is the transform of the smallest input, and one thread bisects for
+// the smallest input value that is kept. raw sum, average, min-max and square root are exact fp32
+// sequences; log, Yeo-Johnson, arcsinh use the device's library functions and z-score sums in fp64
+// with atomics, so their decisions can differ from another implementation's within rounding of the
+// threshold.
+struct TransformStats {
+  unsigned xmin_bits, xmax_bits;  // X > 0: its bit pattern orders like an unsigned integer
+  unsigned amin_key, abarmin_key; // ordered keys (see key_of) of the smallest sum and the smallest mean
+  double sum, sumsq;              // of X
+};
+
+struct TransformCtx {
+  int kind;
+  float lambda, eps, tau, tmin, p0, p1;  // p0, p1: (mu, sigma) for z-score, (min X, max X) for min-max
+};
+
+__global__ void k_stats_init(TransformStats *st) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    st->xmin_bits = 0x7F800000u;
+    st->xmax_bits = 0u;
+    st->amin_key = kKeyPosInf;
+    st->abarmin_key = kKeyPosInf;
+    st->sum = 0.0;
+    st->sumsq = 0.0;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_stats(const float *__restrict__ A, const float *__restrict__ C, int64_t n, int L,
+                                               float eps, TransformStats *st) {
+  float xmin = INFINITY, xmax = 0.0f;
+  unsigned amin = kKeyPosInf, abarmin = kKeyPosInf;
+  double sum = 0.0, sumsq = 0.0;
+  const int64_t LL = (int64_t)L * L;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x) {
+    float a, c;
+    if (C) {
+      a = A[e];
+      c = C[e];
+    } else {
+      const int64_t r = e % LL;
+      const bool causal = r % L <= r / L;
+      a = causal ? A[e] : 0.0f;
+      c = causal ? 1.0f : 0.0f;
+    }
+    const float denom = c + eps;
+    const float abar = a / denom;
+    const float x = fmaxf(abar, eps);
+    xmin = fminf(xmin, x);
+    xmax = fmaxf(xmax, x);
+    amin = min(amin, key_of(a != a ? -INFINITY : a));
+    abarmin = min(abarmin, key_of(abar != abar ? -INFINITY : abar));
+    sum += (double)x;
+    sumsq += (double)x * (double)x;
+  }
+  for (int off = 32; off; off >>= 1) {
+    xmin = fminf(xmin, __shfl_xor(xmin, off));
+    xmax = fmaxf(xmax, __shfl_xor(xmax, off));
+    amin = min(amin, (unsigned)__shfl_xor((int)amin, off));
+    abarmin = min(abarmin, (unsigned)__shfl_xor((int)abarmin, off));
+    sum += __shfl_xor(sum, off);
+    sumsq += __shfl_xor(sumsq, off);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    atomicMin(&st->xmin_bits, __float_as_uint(xmin));
+    atomicMax(&st->xmax_bits, __float_as_uint(xmax));
+    atomicMin(&st->amin_key, amin);
+    atomicMin(&st->abarmin_key, abarmin);
+    atomicAdd(&st->sum, sum);
+    atomicAdd(&st->sumsq, sumsq);
+  }
+}
+
+// The transform of a mean value abar (raw sum: of a sum) in the fixed fp32 sequence.
+__device__ float transform_of(const TransformCtx &c, float v) {
+  if (c.kind == DAM_T_RAW_SUM || c.kind == DAM_T_AVERAGE) return v;
+  const float x = fmaxf(v, c.eps);
+  switch (c.kind) {
+    case DAM_T_LOG:
+      return logf(x);
+    case DAM_T_YEO_JOHNSON: {
+      const float x1 = x + 1.0f;
+      if (c.lambda == 0.0f) return logf(x1);
+      const float p = powf(x1, c.lambda);
+      const float num = p - 1.0f;
+      return num / c.lambda;
+    }
+    case DAM_T_ZSCORE: {
+      const float num = x - c.p0;
+      const float den = c.p1 + c.eps;
+      return num / den;
+    }
+    case DAM_T_MINMAX: {
+      const float num = x - c.p0;
+      const float range = c.p1 - c.p0;
+      const float den = range + c.eps;
+      return num / den;
+    }
+    case DAM_T_SQRT:
+      return sqrtf(x);
+    default:  // DAM_T_ARCSINH
+      return asinhf(x);
+  }
+}
+
+// Context of the transform and the threshold key. from_a: the compared value is the sum of a single
+// capture (the mean is sum / (1 + eps)); otherwise it is the mean itself (raw sum: always the sum).
+__global__ void k_transform_threshold(int kind, float lambda, float eps, float tau, float tmin_override,
+                                      const TransformStats *__restrict__ st, bool from_a, float n_entries,
+                                      double n_exact, float *__restrict__ bmin, unsigned *__restrict__ theta_key) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  TransformCtx c;
+  c.kind = kind; c.lambda = lambda; c.eps = eps; c.tau = tau; c.p0 = 0.0f; c.p1 = 0.0f;
+  const float xmin = __uint_as_float(st->xmin_bits), xmax = __uint_as_float(st->xmax_bits);
+  if (kind == DAM_T_ZSCORE) {
+    const double mean = st->sum / n_exact;
+    double var = st->sumsq / n_exact - mean * mean;
+    if (var < 0.0) var = 0.0;
+    c.p0 = (float)mean;
+    c.p1 = (float)sqrt(var);
+  } else if (kind == DAM_T_MINMAX) {
+    c.p0 = xmin;
+    c.p1 = xmax;
+  }
+  // every transform is non-decreasing: the minimum of the map is the transform of the smallest input
+  float tmin;
+  if (kind == DAM_T_RAW_SUM) tmin = value_of(st->amin_key);
+  else if (kind == DAM_T_AVERAGE) tmin = value_of(st->abarmin_key);
+  else tmin = transform_of(c, xmin);
+  if (tmin_override == tmin_override) tmin = tmin_override;
+  c.tmin = tmin;
+  *bmin = tmin;
+  auto keep = [&](float v) {
+    if (kind != DAM_T_RAW_SUM && from_a) {
+      const float denom = 1.0f + eps;
+      v = v / denom;
+    }
+    const float t = transform_of(c, v);
+    return t - c.tmin >= tau;
+  };
+  unsigned lo = kKeyNegInf, hi = kKeyPosInf;
+  if (!keep(value_of(hi))) {
+    *theta_key = kKeepNone;
+    return;
+  }
+  if (keep(value_of(lo))) {
+    *theta_key = kKeepAll;
+    return;
+  }
+  while (hi - lo > 1u) {
+    const unsigned mid = lo + (hi - lo) / 2u;
+    if (keep(value_of(mid))) hi = mid;
+    else lo = mid;
+  }
+  *theta_key = hi;
+}
+
+template <bool FROM_A, bool RAW = false>
 __global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A, const float *__restrict__ C, int L,
                                                    int tbw, float eps, const unsigned *__restrict__ theta_key,
                                                    uint64_t *__restrict__ true_bits) {
@@ -179,7 +339,7 @@ __global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A, 
         const int i = r0 + r, j = (w0 + k) * 64 + lane;
         const bool live = i < L && j <= i;
         float v = a[r][k];
-        if (!FROM_A) v = v / (c[r][k] + eps);
+        if (!FROM_A && !RAW) v = v / (c[r][k] + eps);
         if (v != v) v = -INFINITY;
         const uint64_t word = __ballot(live && key_of(v) >= theta);
         if (lane == 0 && i < L && w0 + k < tbw) true_bits[((int64_t)h * L + i) * tbw + w0 + k] = word;
@@ -955,7 +1115,9 @@ int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *dia
     if (p->pcl < 1 || !attn_sum || !o->true_bits) return DAM_ERR_INVALID_ARG;
     if (p->pcl >= (1 << kAccSlices)) return DAM_ERR_UNSUPPORTED;  // the match counts are summed in kAccSlices bits
     if (!(p->eps > 0.0f)) return DAM_ERR_INVALID_ARG;
-    if (p->lambda != 0.5f && p->lambda != 1.0f) return DAM_ERR_UNSUPPORTED;
+    if (p->transform < DAM_T_BOXCOX || p->transform > DAM_T_ARCSINH) return DAM_ERR_INVALID_ARG;
+    if (p->transform == DAM_T_BOXCOX && p->lambda != 0.5f && p->lambda != 1.0f) return DAM_ERR_UNSUPPORTED;
+    if (isnan(p->lambda)) return DAM_ERR_INVALID_ARG;
     if (isnan(p->tau) || isnan(p->mu)) return DAM_ERR_INVALID_ARG;
   } else {
     if (p->pcl < 0 || !diag_in || !vert_in) return DAM_ERR_INVALID_ARG;
@@ -976,6 +1138,7 @@ int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *dia
 struct Workspace {
   float *bmin;
   unsigned *xmin_bits, *theta_key;
+  TransformStats *stats;
   uint64_t *vslices, *dslices;
   uint8_t *diag_flag, *vert_flag;
   uint64_t *cbits, *rrev, *occ, *full, *col_any, *col_all, *off_any, *off_all;
@@ -1008,6 +1171,7 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   w.bmin = c.take<float>(1);
   w.xmin_bits = c.take<unsigned>(1);
   w.theta_key = c.take<unsigned>(1);
+  w.stats = c.take<TransformStats>(1);
   const size_t n_slices = p->mode == DAM_FROM_ATTN_MAP
                               ? (size_t)g.H * (size_t)((g.L + kChunkRows - 1) / kChunkRows) * kSlices * (size_t)g.tbw
                               : 1;
@@ -1033,6 +1197,16 @@ Workspace carve(const dam_mask_params *p, void *ws) {
 // a1 and the threshold of a2. attn_sum / attn_cnt are only read in the general minimum.
 void stage_threshold(const dam_mask_params *p, const Geom &g, const Workspace &w, const float *attn_sum,
                      const float *attn_cnt, hipStream_t stream) {
+  if (p->transform != DAM_T_BOXCOX) {
+    // App. B alternatives: one reduction pass for the statistics, then minimum and threshold together
+    const int64_t n = (int64_t)g.H * g.L * g.L;
+    k_stats_init<<<1, 64, 0, stream>>>(w.stats);
+    const int blocks = (int)std::min<int64_t>((n + 1023) / 1024, 256 * 16);
+    k_stats<<<blocks, 256, 0, stream>>>(attn_sum, attn_cnt, n, g.L, p->eps, w.stats);
+    k_transform_threshold<<<1, 64, 0, stream>>>(p->transform, p->lambda, p->eps, p->tau, p->bmin_override, w.stats,
+                                                attn_cnt == nullptr, (float)n, (double)n, w.bmin, w.theta_key);
+    return;
+  }
   const bool half = p->lambda == 0.5f;
   // a1: the global minimum of the Box-Cox map
   if (!isnan(p->bmin_override)) {
@@ -1139,7 +1313,9 @@ extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, c
     stage_threshold(p, g, w, attn_sum, attn_cnt, stream);
     // a2: true mask, one comparison per element
     dim3 grid((g.tbw + 3) / 4, (g.L + kTmRows - 1) / kTmRows, g.H);
-    if (attn_cnt)
+    if (attn_cnt && p->transform == DAM_T_RAW_SUM)
+      k_true_mask<false, true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
+    else if (attn_cnt)
       k_true_mask<false><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
     else if (g.L % 4 == 0 && (reinterpret_cast<uintptr_t>(attn_sum) & 15) == 0)
       k_true_mask_rows<<<dim3(2 * ((((g.L + 1) / 2) + 3) / 4), g.H), 256, 0, stream>>>(attn_sum, g.L, g.tbw, w.theta_key,
@@ -1171,6 +1347,7 @@ extern "C" int dam_mask_build_from_qk(const dam_mask_params *p, const dam_captur
   bad = capture_validate(cp, q, k);
   if (bad != DAM_OK) return bad;
   if (p->n_maps != cp->hq || p->pcl != cp->pcl || cp->len != cp->pcl || p->pcl < 2) return DAM_ERR_INVALID_ARG;
+  if (p->transform != DAM_T_BOXCOX) return DAM_ERR_UNSUPPORTED;  // the other transforms need statistics of the whole map
   if (!ws || ws_bytes < dam_mask_build_from_qk_workspace(p, cp)) return DAM_ERR_WORKSPACE;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   const Geom g = geometry(p);

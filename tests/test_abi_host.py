@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported():
 
 def mask_params(**kw):
     d = dict(mode=B.DAM_FROM_ATTN_MAP, n_maps=2, pcl=64, seq=256, tile_m=64, tile_n=64, row_begin=0, row_end=0, lam=0.5,
-             eps=1e-8, tau=0.3, mu=0.8, bmin_override=float("nan"))
+             eps=1e-8, tau=0.3, mu=0.8, bmin_override=float("nan"), flags=0, transform=0)
     d.update(kw)
     return B.MaskParams(*d.values())
 
@@ -54,6 +54,9 @@ def test_mask_build_argument_errors():
     assert call_mask(mask_params(), ws_bytes=16) == B.DAM_ERR_WORKSPACE
     assert call_mask(mask_params(), ws=None) == B.DAM_ERR_WORKSPACE
     assert call_mask(mask_params(mode=7)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(transform=9)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(transform=-1)) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(flags=2)) == B.DAM_ERR_INVALID_ARG
     assert call_mask(mask_params(mode=B.DAM_FROM_PATTERNS, pcl=0), attn=None) == B.DAM_ERR_INVALID_ARG  # no flags
     o = B.MaskOut()
     o.true_bits, o.blk_col = 4096, 4096                                   # block output without row_ptr / total
@@ -157,6 +160,7 @@ def test_capture_argument_errors():
     assert fused(mask_params(pcl=128), capture_params()) == B.DAM_ERR_INVALID_ARG         # pcl mismatch
     assert fused(mask_params(), capture_params(len=32)) == B.DAM_ERR_INVALID_ARG          # one full-length capture
     assert fused(mask_params(lam=0.3), capture_params()) == B.DAM_ERR_UNSUPPORTED
+    assert fused(mask_params(transform=B.TRANSFORMS["sqrt"]), capture_params()) == B.DAM_ERR_UNSUPPORTED
     assert fused(mask_params(), capture_params(), ws_bytes=64) == B.DAM_ERR_WORKSPACE
     both = L.dam_mask_build_from_qk_workspace(ctypes.byref(mask_params()), ctypes.byref(capture_params()))
     assert both > L.dam_mask_build_workspace(ctypes.byref(mask_params()))
