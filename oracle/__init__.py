@@ -65,6 +65,14 @@ def lib() -> ctypes.CDLL:
                                                        ctypes.POINTER(ctypes.c_int32),
                                                        ctypes.POINTER(ctypes.c_uint8),
                                                        ctypes.POINTER(ctypes.c_uint64), ctypes.c_int64]
+        _LIB.dam_oracle_block_index_gathered.restype = ctypes.c_int64
+        _LIB.dam_oracle_block_index_gathered.argtypes = head + [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                                ctypes.c_int64, ctypes.c_int64,
+                                                                ctypes.POINTER(ctypes.c_int32), ctypes.c_int64,
+                                                                ctypes.POINTER(ctypes.c_int32),
+                                                                ctypes.POINTER(ctypes.c_int32),
+                                                                ctypes.POINTER(ctypes.c_uint8),
+                                                                ctypes.POINTER(ctypes.c_uint64), ctypes.c_int64]
         _LIB.dam_oracle_attend_lists.restype = None
         _LIB.dam_oracle_attend_lists.argtypes = [ctypes.POINTER(ctypes.c_float)] * 3 + [
             ctypes.POINTER(ctypes.c_int32), ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64),
@@ -230,8 +238,22 @@ def kept_list(art: MaskArtefact, h: int, i: int) -> np.ndarray:
     return idx[:n].copy()
 
 
+def gathered_columns(art: MaskArtefact, S: int, tile_n: int):
+    """The matched columns below S of every head, ascending (the keys the gathered tiles hold):
+    (ptr [H + 1] i64, idx i32), each head's stretch padded with -1 to a multiple of tile_n."""
+    ptr = [0]
+    out = []
+    for h in range(art.H):
+        cols = [c for c in range(min(S, art.P)) if art.vert_flag[h, c]]
+        pad = (-len(cols)) % tile_n
+        out.extend(cols + [-1] * pad)
+        ptr.append(len(out))
+    return np.array(ptr, np.int64), np.array(out, np.int32)
+
+
 def block_index(art: MaskArtefact, S: int, tile_m: int, tile_n: int, heads: Optional[Sequence[int]] = None,
-                want_bits: bool = True, workers: int = 8, qt_range: Optional[Tuple[int, int]] = None):
+                want_bits: bool = True, workers: int = 8, qt_range: Optional[Tuple[int, int]] = None,
+                gather: bool = False):
     """Block index of the given heads (default all): returns
     (row_ptr [n_heads][nQt+1] i64 with offsets global over the given heads in order,
      col i32 [n_tiles], kind u8 [n_tiles], tile_bits u64 [n_tiles][tile_m][tile_n//64] or None).
@@ -243,20 +265,30 @@ def block_index(art: MaskArtefact, S: int, tile_m: int, tile_n: int, heads: Opti
     wpr = tile_n // 64
     chunk = max(1, nQt // 16)
     jobs = [(h, q0, min(qb, q0 + chunk)) for h in heads for q0 in range(qa, qb, chunk)]
+    gcols = {}
+    if gather:   # "gather = True": the layout with the matched columns in tiles of their own (see the C source)
+        for h in heads:
+            gcols[h] = np.array([c for c in range(min(S, art.P)) if art.vert_flag[h, c]], np.int32)
+
+    def call(h, q0, q1, cnt, col, kind, bits, cap):
+        args = art.head_args(h)
+        if gather:
+            return lib().dam_oracle_block_index_gathered(*args, S, tile_m, tile_n, q0, q1, _ptr(gcols[h], ctypes.c_int32),
+                                                         len(gcols[h]), _ptr(cnt, ctypes.c_int32),
+                                                         _ptr(col, ctypes.c_int32), _ptr(kind, ctypes.c_uint8),
+                                                         _ptr(bits, ctypes.c_uint64), cap)
+        return lib().dam_oracle_block_index(*args, S, tile_m, tile_n, q0, q1, _ptr(cnt, ctypes.c_int32),
+                                            _ptr(col, ctypes.c_int32), _ptr(kind, ctypes.c_uint8),
+                                            _ptr(bits, ctypes.c_uint64), cap)
 
     def run(job):
         h, q0, q1 = job
         cnt = np.zeros(q1 - q0, np.int32)
-        args = art.head_args(h)
-        n = lib().dam_oracle_block_index(*args, S, tile_m, tile_n, q0, q1, _ptr(cnt, ctypes.c_int32),
-                                         _ptr(None, ctypes.c_int32), _ptr(None, ctypes.c_uint8),
-                                         _ptr(None, ctypes.c_uint64), 0)
+        n = call(h, q0, q1, cnt, None, None, None, 0)
         col = np.empty(n, np.int32)
         kind = np.empty(n, np.uint8)
         bits = np.empty((n, tile_m, wpr), np.uint64) if want_bits else None
-        lib().dam_oracle_block_index(*args, S, tile_m, tile_n, q0, q1, _ptr(cnt, ctypes.c_int32),
-                                     _ptr(col, ctypes.c_int32), _ptr(kind, ctypes.c_uint8),
-                                     _ptr(bits, ctypes.c_uint64), n)
+        call(h, q0, q1, cnt, col, kind, bits, n)
         return cnt, col, kind, bits
 
     with ThreadPoolExecutor(max_workers=workers) as ex:

@@ -309,6 +309,76 @@ int64_t dam_oracle_block_index(const uint8_t *true_mask, int32_t L, const uint8_
   return total;
 }
 
+/* Block index with the matched columns gathered into tiles of their own (a layout of this build for
+ * the attention kernel; the mask it describes is the one of Sec. 4.3, unchanged). gcols[n_g]: the
+ * head's matched columns below S, ascending. For a query tile that lies wholly in the pattern region
+ * (its first row >= L) the entries of a row i are split into two disjoint parts:
+ *   diagonal part   key j <= i with i - j a matched diagonal              -> ordinary tiles kt < nKt
+ *   column part     gathered column c = gcols[s], c <= i, i - c NOT a matched diagonal
+ *                   -> gathered tiles nKt + v, v = s / tile_n, bit s % tile_n of the row
+ * Query tiles that start inside the true-mask block are listed exactly as by dam_oracle_block_index.
+ * Listing, order (ascending tile index, gathered tiles after the ordinary ones), kind and bits follow
+ * the same rules as there. */
+int64_t dam_oracle_block_index_gathered(const uint8_t *true_mask, int32_t L, const uint8_t *diag_flag,
+                                        const uint8_t *vert_flag, int32_t P, int64_t S, int32_t tile_m,
+                                        int32_t tile_n, int64_t qt0, int64_t qt1, const int32_t *gcols,
+                                        int64_t n_g, int32_t *row_cnt, int32_t *col, uint8_t *kind,
+                                        uint64_t *tile_bits, int64_t cap) {
+  dam_oracle_head hd = {true_mask, diag_flag, vert_flag, L, P};
+  const int64_t nKt = (S + tile_n - 1) / tile_n;
+  const int64_t nGt = (n_g + tile_n - 1) / tile_n;
+  const int64_t wpr = tile_n / 64;
+  const int64_t tile_words = (int64_t)tile_m * wpr;
+  uint64_t *bits = (uint64_t *)malloc((size_t)tile_words * sizeof(uint64_t));
+  int64_t total = 0;
+  for (int64_t qt = qt0; qt < qt1; ++qt) {
+    int32_t listed = 0;
+    const int split = qt * tile_m >= L;
+    for (int64_t kt = 0; kt < nKt + (split ? nGt : 0); ++kt) {
+      memset(bits, 0, (size_t)tile_words * sizeof(uint64_t));
+      int64_t kept = 0;
+      int quarters = 0;
+      for (int64_t ii = 0; ii < tile_m; ++ii)
+        for (int64_t jj = 0; jj < tile_n; ++jj) {
+          const int64_t i = qt * tile_m + ii;
+          int on = 0;
+          if (i < S) {
+            if (kt < nKt) {
+              const int64_t j = kt * tile_n + jj;
+              if (j < S) {
+                if (!split) on = kept_entry(&hd, i, j);
+                else on = j <= i && i - j < P && diag_flag[i - j];
+              }
+            } else {
+              const int64_t s_at = (kt - nKt) * tile_n + jj;
+              if (s_at < n_g) {
+                const int64_t c = gcols[s_at];
+                on = c <= i && !(i - c < P && diag_flag[i - c]);
+              }
+            }
+          }
+          if (on) {
+            bits[ii * wpr + jj / 64] |= (uint64_t)1 << (jj % 64);
+            quarters |= 1 << (jj / (tile_n / 4));
+            ++kept;
+          }
+        }
+      if (kept == 0) continue;
+      if (total < cap) {
+        if (col) col[total] = (int32_t)kt;
+        if (kind) kind[total] = (uint8_t)((kept == (int64_t)tile_m * tile_n) | (quarters << 1));
+        if (tile_bits)
+          memcpy(tile_bits + total * tile_words, bits, (size_t)tile_words * sizeof(uint64_t));
+      }
+      ++total;
+      ++listed;
+    }
+    row_cnt[qt - qt0] = listed;
+  }
+  free(bits);
+  return total;
+}
+
 /* Sec. 3 with the -inf reading of Sec. 4.3's last paragraph: attention of one query over an explicit
  * list of kept keys.
  *   s_j = (q . k_j) * scale;  w_j = exp(s_j - max s);  O = sum w_j v_j / sum w_j;

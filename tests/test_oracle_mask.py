@@ -331,3 +331,66 @@ def test_block_index_full_tiles_only_below_diagonal():
         assert np.array_equal(col[sl], np.arange(qt + 1))
         assert np.array_equal(kind[sl] & 1, [1] * qt + [0])  # the diagonal tile is partial
         assert np.all(kind[sl] >> 1 == 15)
+
+
+# ------------------------------------------------- gathered column tiles (a layout, not a new mask)
+@pytest.mark.parametrize("S,tm,tn,L", [(300, 64, 64, 0), (300, 64, 64, 48), (520, 128, 128, 100), (256, 64, 128, 64)])
+def test_gathered_block_index_reexpands_to_the_same_mask(S, tm, tn, L):
+    """With the matched columns gathered into tiles of their own, scattering the ordinary tiles back by
+    position and the gathered tiles back through the column list must give the mask itself, every kept
+    entry exactly once."""
+    rng = np.random.default_rng(18)
+    H = 3
+    d = (rng.random((H, S)) < 0.02).astype(np.uint8)
+    v = (rng.random((H, S)) < 0.03).astype(np.uint8)
+    d[:, :20] = 1
+    v[:, :5] = 1
+    v[2] = 0                                                  # a head without columns
+    tm_ = (rng.random((H, L, L)) < 0.3).astype(np.uint8) * np.tril(np.ones((L, L), np.uint8)) if L else None
+    art = oracle.from_patterns(d, v, tm_)
+    row_ptr, col, kind, bits = oracle.block_index(art, S, tm, tn, gather=True)
+    gptr, gidx = oracle.gathered_columns(art, S, tn)
+    nQt, nKt = (S + tm - 1) // tm, (S + tn - 1) // tn
+    plain_ptr, plain_col, _, _ = oracle.block_index(art, S, tm, tn)
+    for h in range(H):
+        M = oracle.rows(art, h, S, 0, S)
+        hits = np.zeros((nQt * tm, max(S, nKt * tn)), np.int32)
+        cols_h = gidx[gptr[h]:gptr[h + 1]]
+        assert len(cols_h) % tn == 0 and np.array_equal(cols_h[cols_h >= 0], np.flatnonzero(v[h]))
+        for qt in range(nQt):
+            ts = range(row_ptr[h, qt], row_ptr[h, qt + 1])
+            assert np.all(np.diff(col[list(ts)]) > 0)
+            for t in ts:
+                b = np.unpackbits(bits[t].view(np.uint8), bitorder="little").reshape(tm, tn)
+                assert b.any()
+                assert (kind[t] & 1) == int(b.all())
+                assert (kind[t] >> 1) == sum((1 << q) for q in range(4) if b[:, q * tn // 4:(q + 1) * tn // 4].any())
+                if col[t] < nKt:
+                    hits[qt * tm:(qt + 1) * tm, col[t] * tn:(col[t] + 1) * tn] += b
+                else:
+                    assert qt * tm >= L                       # gathered tiles only in the pattern region
+                    seg = cols_h[(col[t] - nKt) * tn:(col[t] - nKt + 1) * tn]
+                    for s_at, c in enumerate(seg):
+                        if c >= 0:
+                            hits[qt * tm:(qt + 1) * tm, c] += b[:, s_at]
+                        else:
+                            assert not b[:, s_at].any()
+            if qt * tm < L:                                   # tiles touching the true-mask block: the plain listing
+                assert np.array_equal(col[row_ptr[h, qt]:row_ptr[h, qt + 1]], plain_col[plain_ptr[h, qt]:plain_ptr[h, qt + 1]])
+        assert hits.max() <= 1                                # nothing is counted twice
+        assert np.array_equal(hits[:S, :S], M)
+        assert hits[S:].sum() == 0 and hits[:, S:].sum() == 0
+
+
+def test_gathered_tiles_shrink_a_striped_mask():
+    # 40 stripe columns scattered over 2000 keys and a short window: plain listing needs one tile per stripe
+    # and query tile, the gathered layout one tile per query tile
+    S, t = 2048, 128
+    d = np.zeros((1, S), np.uint8)
+    v = np.zeros((1, S), np.uint8)
+    d[0, :64] = 1
+    v[0, np.arange(40) * 50] = 1
+    art = oracle.from_patterns(d, v)
+    plain = oracle.block_index(art, S, t, t)[1]
+    gath = oracle.block_index(art, S, t, t, gather=True)[1]
+    assert len(gath) < len(plain) // 2
