@@ -68,10 +68,22 @@ typedef enum {
 
 /* dam_mask_params.flags */
 typedef enum {
-  DAM_MASK_SKIP_FULL_TILE_BITS = 1 /* do not write tile_bits of full tiles (blk_kind bit 0): the attention
+  DAM_MASK_SKIP_FULL_TILE_BITS = 1, /* do not write tile_bits of full tiles (blk_kind bit 0): the attention
                                       kernels never read them, and at long sequences they are a large part
                                       of the bytes written. Their slots in the pool stay reserved and keep
                                       whatever they held.                                                  */
+  DAM_MASK_GATHER_COLUMNS = 2       /* list the matched columns in tiles of their own. The mask is the same;
+                                      in every query tile that lies wholly in the pattern region (first row
+                                      >= pcl) its entries are split into
+                                        a diagonal part: key j <= i with i - j a matched diagonal, listed in
+                                          the ordinary tiles (tile index < nKt = ceil(S / tile_n)), and
+                                        a column part: matched column c <= i with i - c NOT a matched
+                                          diagonal, listed in "gathered" tiles with index nKt + v: key slot
+                                          s of gathered tile v stands for column gather_idx[h][v tile_n + s].
+                                      A vertical stripe then costs its share of one dense tile per query
+                                      tile instead of a tile of its own. Query tiles that start inside the
+                                      true-mask block are listed as without the flag. Requires the outputs
+                                      gather_idx and gather_cnt.                                          */
 } dam_mask_flags;
 
 typedef enum {
@@ -167,7 +179,14 @@ typedef struct {
   int32_t *kept_ptr, *kept_idx;
   int64_t kept_capacity;
   int64_t *kept_total;
+  int32_t *gather_idx; /* [H][dam_gather_stride(params)] i32: DAM_MASK_GATHER_COLUMNS, the matched columns
+                          below S of each map, ascending, then -1 up to the stride                        */
+  int32_t *gather_cnt; /* [H] i32: how many                                                                */
 } dam_mask_out;
+
+/* Row length of gather_idx: min(P, S) rounded up to a multiple of tile_n, P the length of the pattern
+ * flags (pcl from a map, S when patterns are given). 0 on invalid parameters. */
+int32_t dam_gather_stride(const dam_mask_params *params);
 
 /* Bytes of device workspace dam_mask_build needs for these parameters (0 on invalid parameters). */
 size_t dam_mask_build_workspace(const dam_mask_params *params);

@@ -21,6 +21,7 @@ DAM_OK, DAM_ERR_INVALID_ARG, DAM_ERR_UNSUPPORTED, DAM_ERR_WORKSPACE, DAM_ERR_CAP
 DAM_F32, DAM_BF16 = 0, 1
 DAM_FROM_ATTN_MAP, DAM_FROM_PATTERNS = 0, 1
 DAM_MASK_SKIP_FULL_TILE_BITS = 1
+DAM_MASK_GATHER_COLUMNS = 2
 TRANSFORMS = {"boxcox": 0, "raw_sum": 1, "average": 2, "log": 3, "yeo_johnson": 4, "zscore": 5, "minmax": 6,
               "sqrt": 7, "arcsinh": 8}
 
@@ -49,7 +50,8 @@ class MaskOut(ctypes.Structure):
                 ("blk_row_ptr", ctypes.c_void_p), ("blk_col", ctypes.c_void_p), ("blk_kind", ctypes.c_void_p),
                 ("tile_bits", ctypes.c_void_p), ("blk_capacity", ctypes.c_int64), ("blk_total", ctypes.c_void_p),
                 ("dense_bits", ctypes.c_void_p), ("kept_ptr", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
-                ("kept_capacity", ctypes.c_int64), ("kept_total", ctypes.c_void_p)]
+                ("kept_capacity", ctypes.c_int64), ("kept_total", ctypes.c_void_p), ("gather_idx", ctypes.c_void_p),
+                ("gather_cnt", ctypes.c_void_p)]
 
 
 class AttnParams(ctypes.Structure):
@@ -61,7 +63,8 @@ class AttnParams(ctypes.Structure):
 
 class MaskView(ctypes.Structure):
     _fields_ = [("blk_row_ptr", ctypes.c_void_p), ("blk_col", ctypes.c_void_p), ("blk_kind", ctypes.c_void_p),
-                ("tile_bits", ctypes.c_void_p)]
+                ("tile_bits", ctypes.c_void_p), ("gather_idx", ctypes.c_void_p), ("gather_cnt", ctypes.c_void_p),
+                ("gather_stride", ctypes.c_int32)]
 
 
 class DecodeParams(ctypes.Structure):
@@ -84,7 +87,7 @@ class EvictParams(ctypes.Structure):
                 ("kv_stride", ctypes.c_int64 * 3), ("compact_stride", ctypes.c_int64 * 3)]
 
 
-EXPORTS = ["dam_kv_evict_workspace", "dam_kv_evict_plan", "dam_kv_compact", "dam_kv_remap_lists", "dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
+EXPORTS = ["dam_gather_stride", "dam_kv_evict_workspace", "dam_kv_evict_plan", "dam_kv_compact", "dam_kv_remap_lists", "dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
            "dam_mask_build_from_qk_workspace", "dam_mask_build_from_qk", "dam_sparse_attn_prefill_workspace",
            "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode", "dam_version"]
 
@@ -122,6 +125,8 @@ def lib() -> ctypes.CDLL:
         L.dam_sparse_attn_decode_workspace.argtypes = [ctypes.POINTER(DecodeParams), i64]
         L.dam_sparse_attn_decode.restype = ctypes.c_int
         L.dam_sparse_attn_decode.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dam_gather_stride.restype = ctypes.c_int32
+        L.dam_gather_stride.argtypes = [ctypes.POINTER(MaskParams)]
         L.dam_kv_evict_workspace.restype = sz
         L.dam_kv_evict_workspace.argtypes = [ctypes.POINTER(EvictParams)]
         L.dam_kv_evict_plan.restype = ctypes.c_int
@@ -172,9 +177,14 @@ class Mask:
     kept_ptr: Optional[torch.Tensor] = None
     kept_idx: Optional[torch.Tensor] = None
     n_kept: int = 0
+    gather_idx: Optional[torch.Tensor] = None   # [H][gather_stride] i32 (DAM_MASK_GATHER_COLUMNS)
+    gather_cnt: Optional[torch.Tensor] = None   # [H] i32
+    gather_rows: int = 0                        # largest padded column count of a head: rows of the gathered K / V
 
     def view(self) -> MaskView:
-        return MaskView(_p(self.blk_row_ptr), _p(self.blk_col), _p(self.blk_kind), _p(self.tile_bits))
+        return MaskView(_p(self.blk_row_ptr), _p(self.blk_col), _p(self.blk_kind), _p(self.tile_bits),
+                        _p(self.gather_idx), _p(self.gather_cnt),
+                        0 if self.gather_idx is None else self.gather_idx.shape[1])
 
 
 def mask_workspace(params: MaskParams, device) -> torch.Tensor:
@@ -269,6 +279,10 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
     if mode == DAM_FROM_ATTN_MAP:
         o.diag_cnt, o.vert_cnt, o.diag_flag, o.vert_flag, o.bmin = (_p(m.diag_cnt), _p(m.vert_cnt), _p(m.diag_flag),
                                                                     _p(m.vert_flag), _p(m.bmin))
+    if flags & DAM_MASK_GATHER_COLUMNS:
+        m.gather_idx = torch.empty((H, lib().dam_gather_stride(ctypes.byref(p))), dtype=torch.int32, device=dev)
+        m.gather_cnt = torch.empty(H, dtype=torch.int32, device=dev)
+        o.gather_idx, o.gather_cnt = _p(m.gather_idx), _p(m.gather_cnt)
     if blocks:
         m.blk_row_ptr = torch.empty((H, nQt + 1), dtype=torch.int32, device=dev)
         o.blk_row_ptr, o.blk_total = _p(m.blk_row_ptr), totals[0:1].data_ptr()
@@ -279,6 +293,8 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
         m.dense_bits = torch.empty((H, S, (S + 63) // 64), dtype=torch.int64, device=dev)
         o.dense_bits = _p(m.dense_bits)
     call(o)
+    if m.gather_cnt is not None:
+        m.gather_rows = (int(m.gather_cnt.max().item()) + tile_n - 1) // tile_n * tile_n
     if blocks or rows:
         n_tiles, n_kept = (int(x) for x in totals.cpu())
         again = False

@@ -634,7 +634,7 @@ __device__ __forceinline__ uint64_t mask_word(const Geom &g, const uint64_t *__r
     const uint64_t inside = left >= 64 ? ~0ull : ((1ull << left) - 1);
     return tb_h[(int64_t)i * g.tbw + wj] & causal & inside;
   }
-  uint64_t pat = wj < g.pw ? cb_h[wj] : 0;
+  uint64_t pat = cb_h ? set_word(cb_h, wj, g.pw) : 0;  // cb_h == nullptr: the diagonal part alone
   pat |= diag_window(rr_h, g.pw, u);
   return pat & causal;
 }
@@ -674,7 +674,7 @@ __device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_
                                   int i0, int i1, int j0, int j1) {
   const int64_t Q = (int64_t)pw * 64 - 1;  // offset u sits at position Q - u of the reversed set
   const int a = i0 - j1, b = i1 - j0;      // offsets met by the tile, 0 <= a <= b
-  const bool cols_in = j0 <= Q;            // columns past the bitset are never matched
+  const bool cols_in = cb && j0 <= Q;      // columns past the bitset are never matched; cb == nullptr: no columns
   const int jc1 = (int)min((int64_t)j1, Q);
   const bool any_c = cols_in && range_any(cb, pw, j0, jc1);
   const bool any_r = range_any(rr, pw, Q - b, Q - a);
@@ -684,7 +684,7 @@ __device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_
   bool full = true;
   if (b > Q) {  // offsets Q+1 .. b: their entries lie in columns [max(j0, i0 - b), min(j1, i1 - (Q + 1))]
     const int64_t lo = max((int64_t)j0, (int64_t)i0 - b), hi = min((int64_t)j1, (int64_t)i1 - (Q + 1));
-    if (lo <= hi) full = hi <= Q && range_all(cb, lo, hi);
+    if (lo <= hi) full = cb && hi <= Q && range_all(cb, lo, hi);
   }
   const int64_t p_lo = max(Q - b, (int64_t)0), p_hi = Q - a;
   for (int64_t w = p_lo >> 6; full && w <= (p_hi >> 6); ++w) {
@@ -695,7 +695,7 @@ __device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_
       const int64_t u = Q - (w * 64 + (__ffsll((unsigned long long)holes) - 1));
       holes &= holes - 1;
       const int64_t lo = max((int64_t)j0, (int64_t)i0 - u), hi = min((int64_t)j1, (int64_t)i1 - u);
-      if (lo <= hi) full = hi <= Q && range_all(cb, lo, hi);
+      if (lo <= hi) full = cb && hi <= Q && range_all(cb, lo, hi);
     }
   }
   return full ? 3 : 1;
@@ -762,6 +762,64 @@ __device__ __forceinline__ void stage_sets(uint64_t *lds_sets, bool staged, int 
   rr = lds_sets + pw;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Gathered column tiles (flag DAM_MASK_GATHER_COLUMNS). The mask is unchanged; its entries in query
+// tiles of the pattern region are split into a diagonal part, listed in ordinary tiles, and a column
+// part, listed in tiles whose 128 (tile_n) "keys" are matched columns taken in ascending order:
+// gathered tile v of head h holds columns gidx[h][v tile_n ..], and row i keeps slot s iff
+// c = gidx[s] <= i and i - c is not a matched diagonal (those entries belong to the diagonal part).
+// A vertical stripe then costs its share of one dense tile per query tile instead of a whole tile.
+
+// The matched columns below S of one head, ascending, padded with -1 up to the stride. One wave per head.
+__global__ void k_gather_columns(Geom g, const uint64_t *__restrict__ cbits, int stride, int *__restrict__ gidx,
+                                 int *__restrict__ gcnt) {
+  const int h = blockIdx.x, lane = threadIdx.x;
+  const uint64_t *cb = cbits + (int64_t)h * g.pw;
+  int *out = gidx + (int64_t)h * stride;
+  const int n_cols = min(g.P, g.S);
+  int base = 0;
+  for (int w0 = 0; w0 * 64 < n_cols; w0 += 64) {
+    const int w = w0 + lane;
+    uint64_t m = (w < g.pw && w * 64 < n_cols) ? cb[w] : 0;
+    if (w * 64 + 64 > n_cols && w * 64 < n_cols) m &= ~0ull >> (64 - (n_cols - w * 64));
+    const int v = __popcll(m);
+    int incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    int at = base + incl - v;
+    while (m) {
+      out[at++] = w * 64 + __ffsll((unsigned long long)m) - 1;
+      m &= m - 1;
+    }
+    base += __shfl(incl, 63);
+  }
+  for (int x = base + lane; x < stride; x += 64) out[x] = -1;
+  if (lane == 0) gcnt[h] = base;
+}
+
+// Row bitmap of one gathered slot for the rows of query tile qt: bit r of word k is row 64 k + r of the
+// tile. c < 0: an empty slot.
+__device__ __forceinline__ void slot_rows(const Geom &g, const uint64_t *__restrict__ rr, int i0, int c,
+                                          uint64_t (&keep)[4]) {
+  const int row_words = g.tile_m / 64;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    keep[k] = 0;
+    if (k < row_words && c >= 0) {
+      const int r0 = 64 * k;                       // first row of the word
+      const int first = c - i0 - r0;               // rows of the word from `first` on are causal
+      uint64_t m = first <= 0 ? ~0ull : (first >= 64 ? 0ull : ~0ull << first);
+      const int live = g.S - i0 - r0;              // rows of the word below `live` exist
+      m &= live >= 64 ? ~0ull : (live <= 0 ? 0ull : ~0ull >> (64 - live));
+      // offsets i - c of the word's rows, highest first, are 64 consecutive bits of the reversed set
+      const uint64_t diag = __brevll(diag_window(rr, g.pw, (int64_t)i0 + r0 + 63 - c));
+      keep[k] = m & ~diag;
+    }
+  }
+}
+
 // Pass 1 of the block index: which key tiles of query tile (h, qt) hold a kept entry / are full.
 // One wave per query tile, 64 key tiles (one occupancy word) at a time, one lane per key tile. Tiles
 // strictly below the diagonal and outside the true-mask block are decided by their lane alone (from
@@ -775,7 +833,10 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
                                                    const uint64_t *__restrict__ off_any,
                                                    const uint64_t *__restrict__ off_all,
                                                    uint64_t *__restrict__ occ,
-                                                   uint64_t *__restrict__ full, int *__restrict__ cnt, bool staged) {
+                                                   uint64_t *__restrict__ full, int *__restrict__ cnt, bool staged,
+                                                   const int *__restrict__ gidx, const int *__restrict__ gcnt,
+                                                   int gstride, uint64_t *__restrict__ vocc,
+                                                   uint64_t *__restrict__ vfull) {
   extern __shared__ uint64_t lds_sets[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = blockIdx.y, qt = blockIdx.x * 4 + wave;
@@ -791,6 +852,9 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
   // class bitsets. Only a tile that has matched and unmatched columns AND matched and unmatched
   // offsets needs the exact one-lane test for "full".
   const bool by_class = g.tile_m == g.tile_n && i0 >= g.L && i0 + g.tile_m <= g.S;
+  // gathered columns: in a query tile of the pattern region the ordinary tiles hold the diagonal part only
+  const bool split = gidx != nullptr && i0 >= g.L;
+  const uint64_t *cbw = split ? nullptr : cb;
   const uint64_t *ca = col_any + (int64_t)h * g.occw, *cf = col_all + (int64_t)h * g.occw;
   const uint64_t *da = off_any + (int64_t)h * g.occw, *df = off_all + (int64_t)h * g.occw;
   const int words = g.tile_m * g.wpr;
@@ -806,7 +870,7 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
         if (by_class) {
           const int d = qt - kt;  // >= 1 here
           const int64_t pos = (int64_t)g.occw * 64 - 1 - d;
-          const bool c_any = (ca[w] >> lane) & 1, c_all = (cf[w] >> lane) & 1;
+          const bool c_any = !split && ((ca[w] >> lane) & 1), c_all = !split && ((cf[w] >> lane) & 1);
           const bool d_any = (da[pos >> 6] >> (pos & 63)) & 1, d_all = (df[pos >> 6] >> (pos & 63)) & 1;
           if (!(c_any && !c_all && d_any && !d_all)) {
             exact = false;
@@ -814,7 +878,7 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
           }
         }
         if (exact) {
-          f = pattern_tile_flags(cb, rr, g.pw, i0, i_last, j0, j1);
+          f = pattern_tile_flags(cbw, rr, g.pw, i0, i_last, j0, j1);
           // a tile cut by the end of the sequence is never full (its bits past S are zero)
           if (j0 + g.tile_n > g.S || i0 + g.tile_m > g.S) f &= 1;
         }
@@ -827,7 +891,7 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
       need &= need - 1;
       bool any = false, all = true;
       for (int x = lane; x < words; x += 64) {
-        const uint64_t m = mask_word(g, tb, cb, rr, i0 + x / g.wpr, (w * 64 + b) * g.wpr + x % g.wpr);
+        const uint64_t m = mask_word(g, tb, cbw, rr, i0 + x / g.wpr, (w * 64 + b) * g.wpr + x % g.wpr);
         any |= m != 0;
         all &= m == ~0ull;
       }
@@ -839,6 +903,36 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
       full[((int64_t)h * g.nQt + qt) * g.occw + w] = fw;
     }
     total += __popcll(ow);
+  }
+  if (gidx) {
+    // the gathered tiles of this query tile: one lane per slot, the rows of the tile as a bitmap
+    const int n_gt = split ? (gcnt[h] + g.tile_n - 1) / g.tile_n : 0;
+    const int *gi = gidx + (int64_t)h * gstride;
+    const int row_words = g.tile_m / 64;
+    for (int w = 0; w < g.occw; ++w) {
+      uint64_t ow = 0, fw = 0;
+      for (int v = w * 64; v < min(n_gt, w * 64 + 64); ++v) {
+        bool any = false, all = true;
+        for (int wg = 0; wg < g.wpr; ++wg) {
+          const int c = gi[v * g.tile_n + wg * 64 + lane];
+          uint64_t keep[4];
+          slot_rows(g, rr, i0, c, keep);
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (k < row_words) {
+              any |= keep[k] != 0;
+              all &= keep[k] == ~0ull;
+            }
+        }
+        if (__ballot(any) != 0) ow |= 1ull << (v & 63);
+        if (__ballot(!all) == 0) fw |= 1ull << (v & 63);
+      }
+      if (lane == 0) {
+        vocc[((int64_t)h * g.nQt + qt) * g.occw + w] = ow;
+        vfull[((int64_t)h * g.nQt + qt) * g.occw + w] = fw;
+      }
+      total += __popcll(ow);
+    }
   }
   if (lane == 0) cnt[(int64_t)h * g.nQt + qt] = total;
 }
@@ -914,7 +1008,10 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
                                                    int *__restrict__ blk_col,
                                                    uint8_t *__restrict__ blk_kind,
                                                    uint64_t *__restrict__ tile_bits, int64_t capacity,
-                                                   bool skip_full_bits, bool staged) {
+                                                   bool skip_full_bits, bool staged,
+                                                   const int *__restrict__ gidx, const int *__restrict__ gcnt,
+                                                   int gstride, const uint64_t *__restrict__ vocc,
+                                                   const uint64_t *__restrict__ vfull) {
   extern __shared__ uint64_t lds_sets[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qt = blockIdx.x, h = blockIdx.y;
@@ -929,6 +1026,9 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int kmax = i_last / g.tile_n;
   const int words = g.tile_m * g.wpr;
   const int qw = g.tile_n / 4;  // quarter width in keys, a multiple of 16
+  // gathered columns: the ordinary tiles of a query tile of the pattern region hold the diagonal part only
+  const bool split = gidx != nullptr && qt * g.tile_m >= g.L;
+  if (split) cb = nullptr;
   // walk the listed tiles of this query tile in ascending order; wave w takes every fourth one
   int rank = 0;
   for (int ow_i = 0; ow_i <= (kmax >> 6); ++ow_i) {
@@ -955,7 +1055,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
         // (128 keys = two words). The offsets i - j of a row's 128 keys are 128 consecutive positions of
         // the reversed diagonal set, starting at Q - (i - 128 kt): two funnel shifts over three words.
         const int Q = g.pw * 64 - 1;
-        const uint64_t c0 = set_word(cb, 2 * kt, g.pw), c1 = set_word(cb, 2 * kt + 1, g.pw);
+        const uint64_t c0 = cb ? set_word(cb, 2 * kt, g.pw) : 0, c1 = cb ? set_word(cb, 2 * kt + 1, g.pw) : 0;
         uint64_t m[2][2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -1026,6 +1126,59 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
         if (__ballot(quarters & (1 << q))) kind |= 2 << q;
       if (lane == 0) {
         if (blk_col) blk_col[t] = kt;
+        if (blk_kind) blk_kind[t] = (uint8_t)kind;
+      }
+    }
+  }
+  if (!split) return;
+  // the gathered tiles, after the ordinary ones: tile index nKt + v
+  const uint64_t *voc = vocc + ((int64_t)h * g.nQt + qt) * g.occw;
+  const uint64_t *vfl = vfull + ((int64_t)h * g.nQt + qt) * g.occw;
+  const int n_gt = (gcnt[h] + g.tile_n - 1) / g.tile_n;
+  const int *gi = gidx + (int64_t)h * gstride;
+  const int i0 = qt * g.tile_m;
+  for (int ow_i = 0; ow_i * 64 < n_gt; ++ow_i) {
+    uint64_t ow = voc[ow_i];
+    while (ow) {
+      const int v = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
+      ow &= ow - 1;
+      const int64_t t = first + rank;
+      const bool mine = (rank & 3) == wave;
+      ++rank;
+      if (!mine || t >= capacity) continue;
+      const bool is_full = (vfl[v >> 6] >> (v & 63)) & 1;
+      int kind = is_full ? 1 : 0;
+      for (int wg = 0; wg < g.wpr; ++wg) {
+        const int slot = wg * 64 + lane;  // slot of this lane inside the tile
+        uint64_t keep[4];
+        slot_rows(g, rr, i0, gi[v * g.tile_n + slot], keep);
+        const bool any = (keep[0] | keep[1] | keep[2] | keep[3]) != 0;
+        const uint64_t lanes_any = __ballot(any);
+        for (int q = 0; q < 4; ++q) {  // quarter q: slots [q qw, (q + 1) qw)
+          const int lo = q * qw - wg * 64, hi = lo + qw;
+          if (hi > 0 && lo < 64) {
+            const int a = max(lo, 0), b = min(hi, 64);
+            const uint64_t span = (b - a == 64 ? ~0ull : ((1ull << (b - a)) - 1)) << a;
+            if (lanes_any & span) kind |= 2 << q;
+          }
+        }
+        if (tile_bits && !(is_full && skip_full_bits)) {
+          // transpose: word (row r, group wg) = the lanes' bit r; lane r % 64 keeps it, 64 rows per store
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if (k < g.tile_m / 64) {  // wave-uniform
+              uint64_t mine_word = 0;
+              for (int r = 0; r < 64; ++r) {
+                const uint64_t word = __ballot((keep[k] >> r) & 1);
+                if (lane == r) mine_word = word;
+              }
+              tile_bits[t * words + (int64_t)(64 * k + lane) * g.wpr + wg] = mine_word;
+            }
+          }
+        }
+      }
+      if (lane == 0) {
+        if (blk_col) blk_col[t] = g.nKt + v;
         if (blk_kind) blk_kind[t] = (uint8_t)kind;
       }
     }
@@ -1107,7 +1260,8 @@ int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *dia
   if (!p || !o) return DAM_ERR_INVALID_ARG;
   if (p->mode != DAM_FROM_ATTN_MAP && p->mode != DAM_FROM_PATTERNS) return DAM_ERR_INVALID_ARG;
   if (p->n_maps < 1 || p->seq < 1) return DAM_ERR_INVALID_ARG;
-  if (p->flags & ~DAM_MASK_SKIP_FULL_TILE_BITS) return DAM_ERR_INVALID_ARG;
+  if (p->flags & ~(DAM_MASK_SKIP_FULL_TILE_BITS | DAM_MASK_GATHER_COLUMNS)) return DAM_ERR_INVALID_ARG;
+  if ((p->flags & DAM_MASK_GATHER_COLUMNS) && (!o->gather_idx || !o->gather_cnt)) return DAM_ERR_INVALID_ARG;
   if (p->tile_m < 64 || p->tile_n < 64 || p->tile_m % 64 || p->tile_n % 64) return DAM_ERR_INVALID_ARG;
   if (p->tile_m > 256 || p->tile_n > 256) return DAM_ERR_UNSUPPORTED;
   if ((int64_t)(p->seq + p->tile_n - 1) / p->tile_n > 32768) return DAM_ERR_UNSUPPORTED;
@@ -1141,7 +1295,7 @@ struct Workspace {
   TransformStats *stats;
   uint64_t *vslices, *dslices;
   uint8_t *diag_flag, *vert_flag;
-  uint64_t *cbits, *rrev, *occ, *full, *col_any, *col_all, *off_any, *off_all;
+  uint64_t *cbits, *rrev, *occ, *full, *col_any, *col_all, *off_any, *off_all, *vocc, *vfull;
   int *tile_cnt, *row_cnt;
   size_t bytes;
 };
@@ -1187,6 +1341,9 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   w.off_all = c.take<uint64_t>((size_t)g.H * g.occw);
   w.occ = c.take<uint64_t>((size_t)g.H * g.nQt * g.occw);
   w.full = c.take<uint64_t>((size_t)g.H * g.nQt * g.occw);
+  const bool gather = (p->flags & DAM_MASK_GATHER_COLUMNS) != 0;
+  w.vocc = c.take<uint64_t>(gather ? (size_t)g.H * g.nQt * g.occw : 1);
+  w.vfull = c.take<uint64_t>(gather ? (size_t)g.H * g.nQt * g.occw : 1);
   w.tile_cnt = c.take<int>((size_t)g.H * g.nQt);
   const int nrows = p->row_end > p->row_begin ? p->row_end - p->row_begin : 0;
   w.row_cnt = c.take<int>((size_t)g.H * (size_t)(nrows > 0 ? nrows : 1));
@@ -1262,13 +1419,19 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
   if (want_blocks) {
     k_tile_classes<<<dim3(g.occw, g.H), 64, 0, stream>>>(g, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any, w.off_all);
     const size_t lds_sets = staged_bytes(g);
+    const bool gather = (p->flags & DAM_MASK_GATHER_COLUMNS) != 0;
+    const int gstride = dam_gather_stride(p);
+    const int *gidx = gather ? o->gather_idx : nullptr, *gcnt = gather ? o->gather_cnt : nullptr;
+    if (gather) k_gather_columns<<<g.H, 64, 0, stream>>>(g, w.cbits, gstride, o->gather_idx, o->gather_cnt);
     k_tile_scan<<<dim3((g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
-                                                                     w.off_all, w.occ, w.full, w.tile_cnt, lds_sets > 0);
+                                                                     w.off_all, w.occ, w.full, w.tile_cnt, lds_sets > 0, gidx,
+                                                                     gcnt, gstride, w.vocc, w.vfull);
     k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total);
     if (o->blk_col || o->blk_kind || o->tile_bits)
       k_tile_fill<<<dim3(g.nQt, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,
                                                                o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
-                                                               (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0);
+                                                               (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0,
+                                                               gidx, gcnt, gstride, w.vocc, w.vfull);
   }
   if (o->dense_bits) {
     const int sw = (g.S + 63) / 64;
@@ -1289,6 +1452,13 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
 }
 
 }  // namespace
+
+extern "C" int32_t dam_gather_stride(const dam_mask_params *p) {
+  if (!p || p->seq < 1 || p->tile_n < 64 || p->pcl < 0) return 0;
+  const int64_t P = p->mode == DAM_FROM_ATTN_MAP ? p->pcl : p->seq;
+  const int64_t n = std::min<int64_t>(P, p->seq);
+  return (int32_t)((n + p->tile_n - 1) / p->tile_n * p->tile_n);
+}
 
 extern "C" size_t dam_mask_build_workspace(const dam_mask_params *p) {
   if (!p || p->n_maps < 1 || p->seq < 1 || p->pcl < 0 || p->tile_m < 64 || p->tile_n < 64 ||

@@ -275,3 +275,65 @@ def test_c2_mask_full_size_bit_exact():
                              dense=False)
     dens = sum(int(np.unpackbits(u64(mask.tile_bits).view(np.uint8)).sum()) for _ in [0]) / (w.hq * w.seq * (w.seq + 1) / 2)
     assert 0.05 < dens < 0.2, dens
+
+
+def check_gathered(art, S, tm, tn, mask, skip_full=False):
+    """Block index in the gathered-column layout against the oracle's: column lists, row pointers,
+    tile indices, kinds and bits."""
+    gptr, gidx = oracle.gathered_columns(art, S, tn)
+    stride = mask.gather_idx.shape[1]
+    got_idx, got_cnt = mask.gather_idx.cpu().numpy(), mask.gather_cnt.cpu().numpy()
+    for h in range(art.H):
+        seg = gidx[gptr[h]:gptr[h + 1]]
+        assert got_cnt[h] == int((seg >= 0).sum()), f"gather_cnt head {h}"
+        assert np.array_equal(got_idx[h, :len(seg)], seg) and (got_idx[h, len(seg):] == -1).all(), f"gather_idx head {h}"
+    assert stride == (min(S, art.P) + tn - 1) // tn * tn
+    row_ptr, col, kind, bits = oracle.block_index(art, S, tm, tn, gather=True)
+    assert np.array_equal(mask.blk_row_ptr.cpu().numpy().astype(np.int64), row_ptr), "blk_row_ptr"
+    assert mask.n_tiles == len(col)
+    assert np.array_equal(mask.blk_col.cpu().numpy(), col), "blk_col"
+    assert np.array_equal(mask.blk_kind.cpu().numpy(), kind), "blk_kind"
+    sel = (kind & 1) == 0 if skip_full else np.ones(len(kind), bool)
+    assert np.array_equal(u64(mask.tile_bits)[sel], bits[sel]), "tile_bits"
+    return col
+
+
+@pytest.mark.parametrize("S,tm,tn,L", [(1000, 128, 128, 0), (1000, 128, 128, 100), (700, 64, 64, 64), (900, 128, 64, 0),
+                                        (600, 64, 128, 130)])
+def test_gathered_column_tiles_match_oracle(S, tm, tn, L):
+    rng = np.random.default_rng(26)
+    H = 5
+    d = (rng.random((H, S)) < 0.01).astype(np.uint8)
+    v = (rng.random((H, S)) < 0.02).astype(np.uint8)
+    d[:, :30] = 1
+    v[:, :6] = 1
+    v[1] = 0                                                   # no columns at all
+    d[2] = 0                                                   # columns only
+    v[3, :] = 0
+    v[3, :200] = 1                                             # more than one gathered tile, all of them sinks
+    d[3, :400] = 1                                             # ... most of them swallowed by the window
+    d[4] = 1                                                   # dense causal: the column part is empty
+    tm_ = (rng.random((H, L, L)) < 0.3).astype(np.uint8) * np.tril(np.ones((L, L), np.uint8)) if L else None
+    art = oracle.from_patterns(d, v, tm_)
+    tb = torch.from_numpy(pack_rows_u64(tm_).view(np.int64)).cuda() if L else None
+    for flags in (B.DAM_MASK_GATHER_COLUMNS, B.DAM_MASK_GATHER_COLUMNS | B.DAM_MASK_SKIP_FULL_TILE_BITS):
+        mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=H, L=L, S=S, tile_m=tm, tile_n=tn, diag_in=torch.from_numpy(d).cuda(),
+                            vert_in=torch.from_numpy(v).cuda(), true_bits=tb, flags=flags)
+        torch.cuda.synchronize()
+        col = check_gathered(art, S, tm, tn, mask, skip_full=bool(flags & B.DAM_MASK_SKIP_FULL_TILE_BITS))
+    assert (col >= (S + tn - 1) // tn).any()
+
+
+def test_gathered_column_tiles_from_a_map():
+    # the columns come out of the match step of the same call (c2's recipe, scaled)
+    w = wl.scaled(wl.WORKLOADS["c2"], hq=8, hkv=2, seq=2048, pcl=512)
+    Q, K, V = wl.qkv_structured(w)
+    A = wl.capture_map(Q, K, w.pcl, w.hq // w.hkv)
+    art = oracle.derive(A, None, w.lam, w.eps, w.tau, w.mu)
+    mask = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=w.hq, L=w.pcl, S=w.seq, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu,
+                        attn_sum=torch.from_numpy(A).cuda(), flags=B.DAM_MASK_GATHER_COLUMNS)
+    torch.cuda.synchronize()
+    assert np.array_equal(u64(mask.true_bits), pack_rows_u64(art.true_mask))
+    check_gathered(art, w.seq, 128, 128, mask)
+    plain = oracle.block_index(art, w.seq, 128, 128, want_bits=False)[1]
+    assert mask.n_tiles < len(plain)
