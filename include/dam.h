@@ -264,6 +264,9 @@ int dam_mask_build_from_qk(const dam_mask_params *params, const dam_capture_para
  *                 head_dim 128, tiles 128 x 128; the rows of one K or V head must span less than
  *                 4 GiB (seq * stride[2] * 2 bytes), otherwise DAM_ERR_UNSUPPORTED.
  * dtype DAM_F32:  fp32 throughout; head_dim 64 or 128, tiles of 64 or 128 in either direction.
+ * A block index built with DAM_MASK_GATHER_COLUMNS is taken as it is: a tile index >= ceil(seq / tile_n)
+ * names a gathered tile whose key slots are the columns in gather_idx (the bf16 kernel first copies
+ * those K / V rows of every head into the workspace, so that such a tile is loaded like any other).
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
   int32_t batch, hq, hkv, seq, head_dim;
@@ -274,6 +277,9 @@ typedef struct {
   int64_t v_stride[3];
   int64_t o_stride[3];
   int32_t tile_m, tile_n; /* the tile the block index was built with                              */
+  int32_t gather_rows;    /* block index with gathered column tiles: an upper bound, a multiple of
+                             tile_n, of gather_cnt[h] rounded up to tile_n over all heads (the rows of
+                             the gathered K / V copies kept in the workspace); 0 otherwise           */
 } dam_attn_params;
 
 /* The block-index outputs of dam_mask_build for the hq query heads (device pointers). */
@@ -282,6 +288,9 @@ typedef struct {
   const int32_t *blk_col;
   const uint8_t *blk_kind;
   const uint64_t *tile_bits;
+  const int32_t *gather_idx;  /* [hq][gather_stride], NULL unless built with DAM_MASK_GATHER_COLUMNS */
+  const int32_t *gather_cnt;  /* [hq]                                                              */
+  int32_t gather_stride;
 } dam_mask_view;
 
 size_t dam_sparse_attn_prefill_workspace(const dam_attn_params *params);

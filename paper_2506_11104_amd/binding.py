@@ -58,7 +58,8 @@ class AttnParams(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32), ("seq", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
-                ("o_stride", ctypes.c_int64 * 3), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32)]
+                ("o_stride", ctypes.c_int64 * 3), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
+                ("gather_rows", ctypes.c_int32)]
 
 
 class MaskView(ctypes.Structure):
@@ -332,11 +333,11 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 def attn_params(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor, tile_m: int, tile_n: int,
-                scale: float = 0.0) -> AttnParams:
+                scale: float = 0.0, gather_rows: int = 0) -> AttnParams:
     B, Hq, S, d = q.shape
     p = AttnParams()
     p.batch, p.hq, p.hkv, p.seq, p.head_dim = B, Hq, k.shape[1], S, d
-    p.dtype, p.scale, p.tile_m, p.tile_n = _dtype_code(q), scale, tile_m, tile_n
+    p.dtype, p.scale, p.tile_m, p.tile_n, p.gather_rows = _dtype_code(q), scale, tile_m, tile_n, gather_rows
     for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o)):
         assert t.stride(3) == 1
         setattr(p, name, (ctypes.c_int64 * 3)(*t.stride()[:3]))
@@ -355,7 +356,7 @@ def dam_sparse_attn_prefill(q, k, v, mask: Mask, out=None, lse=None, scale: floa
         out = torch.empty_like(q)
     if lse is None and want_lse:
         lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
-    p = attn_params(q, k, v, out, mask.tile_m, mask.tile_n, scale)
+    p = attn_params(q, k, v, out, mask.tile_m, mask.tile_n, scale, mask.gather_rows)
     if ws is None:
         ws = prefill_workspace(p, q.device)
     mv = mask.view()

@@ -37,7 +37,8 @@ using namespace dam;
 constexpr int kXcd = 8;
 
 struct AttnArgs {
-  int B, Hq, Hkv, S, nQt, tile_m, tile_n, wpr;
+  int B, Hq, Hkv, S, nQt, nKt, tile_m, tile_n, wpr;
+  int gather_rows, gather_stride;  // gathered column tiles (tile index >= nKt), 0 when the index has none
   float scale;
   int64_t q_sb, q_sh, q_ss, k_sb, k_sh, k_ss, v_sb, v_sh, v_ss, o_sb, o_sh, o_ss;
 };
@@ -80,6 +81,7 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
                                                      const int *__restrict__ blk_col,
                                                      const uint8_t *__restrict__ blk_kind,
                                                      const uint64_t *__restrict__ tile_bits,
+                                                     const int *__restrict__ gather_idx,
                                                      float *__restrict__ out, float *__restrict__ lse) {
   constexpr int N = 4, LPR = D / N, GROUPS = 256 / LPR;
   const WorkItem w = decode_work(a, blockIdx.x);
@@ -96,12 +98,16 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
     float m = -INFINITY, l = 0.0f;
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int t = t0; t < t1; ++t) {
-      const int j0 = blk_col[t] * a.tile_n;
+      const int col = blk_col[t];
+      // a gathered tile (index >= nKt): slot s of the tile stands for the head's matched column gcols[s]
+      const int *gcols = col >= a.nKt ? gather_idx + (int64_t)w.hq * a.gather_stride + (col - a.nKt) * a.tile_n : nullptr;
+      const int j0 = col * a.tile_n;
       const bool full = blk_kind[t] & 1;  // every entry kept: the tile's words are not read (they may be unwritten)
       for (int wd = 0; wd < a.wpr; ++wd) {
         uint64_t bits = full ? ~0ull : tile_bits[((int64_t)t * a.tile_m + rl) * a.wpr + wd];
         while (bits) {
-          const int j = j0 + wd * 64 + __ffsll((unsigned long long)bits) - 1;
+          const int slot = wd * 64 + __ffsll((unsigned long long)bits) - 1;
+          const int j = gcols ? gcols[slot] : j0 + slot;
           bits &= bits - 1;
           const float4 kv = *reinterpret_cast<const float4 *>(kb + j * a.k_ss);
           const float4 vv = *reinterpret_cast<const float4 *>(vb + j * a.v_ss);
@@ -214,11 +220,9 @@ __device__ __forceinline__ void lds_copy4(unsigned lds_at, const void *gbase, un
 }
 
 struct Blk {
-  int key0;        // first key of the block
-  unsigned k_off;  // byte offset of that key's row from the head's first K row, and
-  unsigned v_off;  //   from its first V row
+  int key0;        // first key of the block (gathered tile: first row of the block in the gathered copy)
   int bits_off;    // byte offset of row 0's mask word for the block from the tile row's first mask word
-  int flags;       // bit 0: tile is full (no mask), bit 1: dummy
+  int flags;       // bit 0: tile is full (no mask), bit 1: dummy, bit 2: gathered tile (offsets into the gathered copies)
 };
 
 // 0 or -inf for bit POS of `inv` clear or set
@@ -352,12 +356,15 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
 
 // RAGGED: the sequence length is not a multiple of the block size, so the last block of a row of tiles
 // may reach past the end of K and V.
-template <bool RAGGED>
+// GATHER: the block index may hold gathered column tiles (tile index >= nKt), whose K / V rows come from
+// the per-head gathered copies.
+template <bool RAGGED, bool GATHER>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16_pipe(
     AttnArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ k,
     const __hip_bfloat16 *__restrict__ v, const int *__restrict__ row_ptr, const int *__restrict__ blk_col,
     const uint8_t *__restrict__ blk_kind, const uint64_t *__restrict__ tile_bits, __hip_bfloat16 *__restrict__ out,
-    float *__restrict__ lse, int *__restrict__ queue_next) {
+    float *__restrict__ lse, int *__restrict__ queue_next, const __hip_bfloat16 *__restrict__ kgath,
+    const __hip_bfloat16 *__restrict__ vgath) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int s_item[2];
 
@@ -420,13 +427,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const bool qlive = qrow < a.S;
     const unsigned char *kg = reinterpret_cast<const unsigned char *>(k + wb * a.k_sb + whkv * a.k_sh);
     const unsigned char *vg = reinterpret_cast<const unsigned char *>(v + wb * a.v_sb + whkv * a.v_sh);
+    // the head's gathered column rows (tiles with index >= nKt): [gather_rows] rows at the row stride of K
+    // (of V), so that a block of them is addressed exactly like a block of the cache
+    const int64_t g_rows = ((int64_t)wb * a.Hq + whq) * a.gather_rows;
+    const unsigned char *kgg = reinterpret_cast<const unsigned char *>(kgath) + g_rows * kss2;
+    const unsigned char *vgg = reinterpret_cast<const unsigned char *>(vgath) + g_rows * vss2;
 
     // ---- the stream of occupied 32-key blocks of this query tile (wave-uniform cursor). `quarters`
     // holds the not yet visited occupied quarters of tile cur_t; the metadata of tile cur_t + 1 is
     // fetched ahead (scalar loads, issued by prefetch_meta() just before an iteration's barrier so that
     // their latency falls into the barrier wait and no LDS wait in the pipeline has to cover them).
     int cur_t = t0 - 1, quarters = 0, cur_full = 0, cur_col = 0;
-    Blk last = {0, 0u, 0u, 0, 2};
+    Blk last = {0, 0, 2};
     unsigned pre_kinds = 0;  // the aligned word of blk_kind that holds tile cur_t + 1 (shifted when used, so
     int pre_col = 0;         // that nothing waits for the load before the barrier)
     auto prefetch_meta = [&]() {
@@ -437,7 +449,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
     auto next_blk = [&]() {
       if (quarters == 0) {
-        if (cur_t + 1 >= t1) return Blk{last.key0, last.k_off, last.v_off, last.bits_off, 2};
+        if (cur_t + 1 >= t1) return Blk{last.key0, last.bits_off, 2 | (last.flags & 4)};
         ++cur_t;
         const int pre_kind = (int)((pre_kinds >> (8 * (cur_t & 3))) & 0xFFu);
         quarters = (pre_kind >> 1) & 15;  // never 0 for a listed tile
@@ -446,8 +458,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
       const int qq = __builtin_ctz(quarters);
       quarters &= quarters - 1;
+      if (GATHER && cur_col >= a.nKt) {  // gathered tile: rows of the head's gathered copy (flag 4)
+        const int key0 = min((cur_col - a.nKt) * kBN + kBlkKeys * qq, a.gather_rows - kBlkKeys);
+        last = Blk{key0, (cur_t - t0) * (kBM * 16) + 4 * qq, cur_full | 4};
+        return last;
+      }
       const int key0 = cur_col * kBN + kBlkKeys * qq;
-      last = Blk{key0, (unsigned)key0 * kss2, (unsigned)key0 * vss2, (cur_t - t0) * (kBM * 16) + 4 * qq, cur_full};
+      last = Blk{key0, (cur_t - t0) * (kBM * 16) + 4 * qq, cur_full};
       return last;
     };
     // K or V block -> ring slot: two 1 KiB copies per wave; every address is the head's base plus a
@@ -455,9 +472,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // a block that reaches past the sequence end redirects such keys (masked anyway) to the last row,
     // which keeps the slot finite.
     auto copy_blk = [&](auto slot_off, const unsigned char *g, unsigned stride2, unsigned lane_off, int chunk_xor, int key0,
-                        unsigned blk_off) {
+                        unsigned blk_off, bool gathered) {
       constexpr int SO = decltype(slot_off)::value;
-      if (!RAGGED || key0 + kBlkKeys <= a.S) {
+      if (!RAGGED || gathered || key0 + kBlkKeys <= a.S) {
         const unsigned o0 = lane_off + blk_off;
         lds_copy16<SO>(lds_kv, g, o0);
         lds_copy16<SO + 4096>(lds_kv, g, o0 + 16u * stride2);
@@ -468,10 +485,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
     };
     auto copy_k = [&](const Blk &d, auto slot) {
-      copy_blk(std::integral_constant<int, decltype(slot)::value * kBlkBytes>{}, kg, kss2, koff, row0 & 15, d.key0, d.k_off);
+      const bool gth = GATHER && (d.flags & 4) != 0;  // wave-uniform
+      copy_blk(std::integral_constant<int, decltype(slot)::value * kBlkBytes>{}, gth ? kgg : kg, kss2, koff, row0 & 15, d.key0,
+               (unsigned)d.key0 * kss2, gth);
     };
     auto copy_v = [&](const Blk &d, auto slot) {
-      copy_blk(std::integral_constant<int, kVRing + decltype(slot)::value * kBlkBytes>{}, vg, vss2, voff, sub << 2, d.key0, d.v_off);
+      const bool gth = GATHER && (d.flags & 4) != 0;
+      copy_blk(std::integral_constant<int, kVRing + decltype(slot)::value * kBlkBytes>{}, gth ? vgg : vg, vss2, voff, sub << 2, d.key0,
+               (unsigned)d.key0 * vss2, gth);
     };
     // the block's mask word of every row of this wave (also issued for full and dummy blocks, so that
     // every iteration has the same number of copies in flight)
@@ -585,6 +606,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }  // next work item
 }
 
+// Copies of the K and V rows of every head's matched columns (gather_idx, -1 = empty slot -> zeros) as
+// [batch][hq][gather_rows] rows at the row stride of K (of V), so that a gathered tile is loaded like any other.
+__global__ __launch_bounds__(256) void k_gather_kv(AttnArgs a, const __hip_bfloat16 *__restrict__ k,
+                                                   const __hip_bfloat16 *__restrict__ v, const int *__restrict__ gather_idx,
+                                                   __hip_bfloat16 *__restrict__ kgath, __hip_bfloat16 *__restrict__ vgath) {
+  const int bh = blockIdx.y, b = bh / a.Hq, hq = bh % a.Hq, hkv = hq / (a.Hq / a.Hkv);
+  const int s = blockIdx.x * 16 + (threadIdx.x >> 4), chunk = threadIdx.x & 15;
+  if (s >= a.gather_rows) return;
+  const int c = s < a.gather_stride ? gather_idx[(int64_t)hq * a.gather_stride + s] : -1;
+  uint4 kv = make_uint4(0u, 0u, 0u, 0u), vv = kv;
+  if (c >= 0 && c < a.S) {
+    kv = *reinterpret_cast<const uint4 *>(k + b * a.k_sb + hkv * a.k_sh + (int64_t)c * a.k_ss + chunk * 8);
+    vv = *reinterpret_cast<const uint4 *>(v + b * a.v_sb + hkv * a.v_sh + (int64_t)c * a.v_ss + chunk * 8);
+  }
+  const int64_t row = (int64_t)bh * a.gather_rows + s;
+  *reinterpret_cast<uint4 *>(kgath + row * a.k_ss + chunk * 8) = kv;
+  *reinterpret_cast<uint4 *>(vgath + row * a.v_ss + chunk * 8) = vv;
+}
+
 __global__ void k_zero_queues(int *queue_next) {
   if (threadIdx.x < kXcd) queue_next[threadIdx.x] = 0;
 }
@@ -593,6 +633,13 @@ int validate(const dam_attn_params *p, const void *q, const void *k, const void 
              const void *out) {
   if (!p || !q || !k || !v || !mk || !out) return DAM_ERR_INVALID_ARG;
   if (!mk->blk_row_ptr || !mk->blk_col || !mk->blk_kind || !mk->tile_bits) return DAM_ERR_INVALID_ARG;
+  if (mk->gather_idx) {  // gathered column tiles
+    if (!mk->gather_cnt || mk->gather_stride < 1 || p->gather_rows < 0 || p->gather_rows % p->tile_n ||
+        p->gather_rows > mk->gather_stride)
+      return DAM_ERR_INVALID_ARG;
+  } else if (p->gather_rows != 0) {
+    return DAM_ERR_INVALID_ARG;
+  }
   if (p->batch < 1 || p->hq < 1 || p->hkv < 1 || p->hq % p->hkv || p->seq < 1) return DAM_ERR_INVALID_ARG;
   if (p->tile_m < 64 || p->tile_n < 64 || p->tile_m % 64 || p->tile_n % 64) return DAM_ERR_INVALID_ARG;
   if (!(p->scale >= 0.0f)) return DAM_ERR_INVALID_ARG;
@@ -620,6 +667,9 @@ AttnArgs make_args(const dam_attn_params *p) {
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.S = p->seq;
   a.tile_m = p->tile_m; a.tile_n = p->tile_n;
   a.nQt = (p->seq + p->tile_m - 1) / p->tile_m;
+  a.nKt = (p->seq + p->tile_n - 1) / p->tile_n;
+  a.gather_rows = 0;
+  a.gather_stride = 0;
   a.wpr = p->tile_n / 64;
   a.scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf((float)p->head_dim);
   a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1]; a.q_ss = p->q_stride[2];
@@ -632,8 +682,10 @@ AttnArgs make_args(const dam_attn_params *p) {
 }  // namespace
 
 extern "C" size_t dam_sparse_attn_prefill_workspace(const dam_attn_params *p) {
-  if (!p || p->batch < 1 || p->hkv < 1 || p->seq < 1) return 0;
-  return p->dtype == DAM_BF16 ? 256 : 0;  // the eight work-queue counters of the bf16 kernel
+  if (!p || p->batch < 1 || p->hkv < 1 || p->hq < 1 || p->seq < 1 || p->gather_rows < 0) return 0;
+  if (p->dtype != DAM_BF16) return 0;
+  // the eight work-queue counters of the bf16 kernel, then the gathered K and V copies (rows at the caches' strides)
+  return 256 + (size_t)p->batch * p->hq * p->gather_rows * (size_t)(p->k_stride[2] + p->v_stride[2]) * sizeof(__hip_bfloat16);
 }
 
 extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, const void *k, const void *v,
@@ -644,15 +696,19 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   const size_t need = dam_sparse_attn_prefill_workspace(p);
   if (need && (!ws || ws_bytes < need)) return DAM_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream_v);
-  const AttnArgs a = make_args(p);
+  AttnArgs a = make_args(p);
+  if (mk->gather_idx) {
+    a.gather_rows = p->gather_rows;
+    a.gather_stride = mk->gather_stride;
+  }
   const int blocks = work_blocks(a);
   if (p->dtype == DAM_F32) {
     if (p->head_dim == 64)
       k_prefill_f32<64><<<blocks, 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
-                                               mk->blk_col, mk->blk_kind, mk->tile_bits, (float *)out, lse);
+                                               mk->blk_col, mk->blk_kind, mk->tile_bits, mk->gather_idx, (float *)out, lse);
     else
       k_prefill_f32<128><<<blocks, 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
-                                                mk->blk_col, mk->blk_kind, mk->tile_bits, (float *)out, lse);
+                                                mk->blk_col, mk->blk_kind, mk->tile_bits, mk->gather_idx, (float *)out, lse);
     return launch_status();
   }
   static int n_cu = 0;
@@ -663,24 +719,31 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
     n_cu = prop.multiProcessorCount;
   }
   int *queue_next = static_cast<int *>(ws);
+  __hip_bfloat16 *kgath = reinterpret_cast<__hip_bfloat16 *>(static_cast<char *>(ws) + 256);
+  __hip_bfloat16 *vgath = kgath + (size_t)p->batch * p->hq * a.gather_rows * (size_t)a.k_ss;
+  if (a.gather_rows > 0)
+    k_gather_kv<<<dim3((a.gather_rows + 15) / 16, p->batch * p->hq), 256, 0, st>>>(
+        a, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->gather_idx,
+        kgath, vgath);
   k_zero_queues<<<1, 64, 0, st>>>(queue_next);
   const int persistent = std::min(blocks, 2 * n_cu);  // two workgroups fit a CU (registers and LDS)
-  const bool ragged = p->seq % kBlkKeys != 0;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[ragged]) {
-    const void *fn = ragged ? reinterpret_cast<const void *>(k_prefill_bf16_pipe<true>)
-                            : reinterpret_cast<const void *>(k_prefill_bf16_pipe<false>);
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kPipeLds) != hipSuccess) return DAM_ERR_DEVICE;
-    attr_set[ragged] = true;
+  const bool ragged = p->seq % kBlkKeys != 0, gather = a.gather_rows > 0;
+  using Kernel = void (*)(AttnArgs, const __hip_bfloat16 *, const __hip_bfloat16 *, const __hip_bfloat16 *, const int *,
+                          const int *, const uint8_t *, const uint64_t *, __hip_bfloat16 *, float *, int *,
+                          const __hip_bfloat16 *, const __hip_bfloat16 *);
+  static const Kernel kernels[4] = {k_prefill_bf16_pipe<false, false>, k_prefill_bf16_pipe<true, false>,
+                                    k_prefill_bf16_pipe<false, true>, k_prefill_bf16_pipe<true, true>};
+  const int which = (ragged ? 1 : 0) + (gather ? 2 : 0);
+  static bool attr_set[4] = {false, false, false, false};
+  if (!attr_set[which]) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[which]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kPipeLds) != hipSuccess)
+      return DAM_ERR_DEVICE;
+    attr_set[which] = true;
   }
-  if (ragged)
-    k_prefill_bf16_pipe<true><<<persistent, 256, kPipeLds, st>>>(
-        a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col,
-        mk->blk_kind, mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next);
-  else
-    k_prefill_bf16_pipe<false><<<persistent, 256, kPipeLds, st>>>(
-        a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col,
-        mk->blk_kind, mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next);
+  kernels[which]<<<persistent, 256, kPipeLds, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
+                                                    (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col, mk->blk_kind,
+                                                    mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next, kgath, vgath);
   return launch_status();
 }
 

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
-def gpu_mask_from_art(art, S, tm, tn):
+def gpu_mask_from_art(art, S, tm, tn, flags=0):
     """Mask buffers for the kernels from an oracle-side artefact's *inputs* (flags / true mask are
     inputs of the FROM_PATTERNS mode; the S-sized outputs are built by the GPU)."""
     from dam_testlib import pack_rows_u64
@@ -25,7 +25,7 @@ def gpu_mask_from_art(art, S, tm, tn):
     n = min(S, art.P)
     d[:, :n], v[:, :n] = art.diag_flag[:, :n], art.vert_flag[:, :n]
     return B.build_mask(mode=B.DAM_FROM_PATTERNS, H=art.H, L=art.L, S=S, tile_m=tm, tile_n=tn,
-                        diag_in=torch.from_numpy(d).cuda(), vert_in=torch.from_numpy(v).cuda(), true_bits=tb)
+                        diag_in=torch.from_numpy(d).cuda(), vert_in=torch.from_numpy(v).cuda(), true_bits=tb, flags=flags)
 
 
 def compare(Q, K, V, art, mask, dtype, batch=1, heads_rows=None):
@@ -142,6 +142,26 @@ def test_full_tiles_are_never_read(dtype, d, tile):
     compare(Q, K, V, art, mask, dtype)
 
 
+@pytest.mark.parametrize("dtype,d,S,tile,L", [("bf16", 128, 1000, 128, 90), ("bf16", 128, 1300, 128, 0), ("f32", 64, 500, 64, 70),
+                                              ("f32", 128, 700, 128, 0)])
+def test_gathered_column_tiles_give_the_same_attention(dtype, d, S, tile, L):
+    """The block index with the matched columns gathered into tiles of their own describes the same
+    mask: outputs against the oracle, GQA, batch of two, many columns (several gathered tiles)."""
+    rng = np.random.default_rng(36)
+    Hq, Hkv = 4, 2
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32) * 1.5, dtype)
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), dtype)
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), dtype)
+    art = random_patterns(rng, Hq, S, L=L)
+    art.vert_flag[1, rng.choice(S, size=300, replace=False)] = 1       # three gathered tiles for head 1
+    art.vert_flag[3] = 0                                                # none for head 3
+    mask = gpu_mask_from_art(art, S, tile, tile, flags=B.DAM_MASK_GATHER_COLUMNS | B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    nKt = (S + tile - 1) // tile
+    assert int((mask.blk_col >= nKt).sum()) > 0 and mask.gather_rows >= 300
+    mask.tile_bits[(mask.blk_kind & 1).bool()] = 0x0F0F0F0F00000000    # unwritten slots of full tiles
+    compare(Q, K, V, art, mask, dtype, batch=2)
+
+
 def test_large_logits_do_not_overflow():
     # a masked-out key with a huge logit must not disturb the kept ones (mask before the max)
     rng = np.random.default_rng(33)
@@ -175,7 +195,8 @@ def test_c3_full_size_sampled_rows():
     art = oracle.from_patterns(dflag, vflag)
     # as bench.py builds it: full tiles carry no bits
     mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=w.seq, diag_in=torch.from_numpy(dflag).cuda(),
-                        vert_in=torch.from_numpy(vflag).cuda(), flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
+                        vert_in=torch.from_numpy(vflag).cuda(),
+                        flags=B.DAM_MASK_SKIP_FULL_TILE_BITS | B.DAM_MASK_GATHER_COLUMNS)
     mask.tile_bits[(mask.blk_kind & 1).bool()] = 0
     rng = np.random.default_rng(34)
     n = 1536
