@@ -74,9 +74,11 @@ def bench_prefill(args, w, torch, B, wl):
     v_in = torch.from_numpy(vflag).to(dev) if vflag is not None else None
 
     # sizing call (outside the timed region): how many tiles does the pool need
-    # (full tiles carry no bits in the pool: DAM_MASK_SKIP_FULL_TILE_BITS, the attention kernel takes them from blk_kind)
+    # (full tiles carry no bits in the pool: DAM_MASK_SKIP_FULL_TILE_BITS, the attention kernel takes them from blk_kind;
+    # the matched columns are listed in tiles of their own: DAM_MASK_GATHER_COLUMNS)
+    FLAGS = B.DAM_MASK_SKIP_FULL_TILE_BITS | B.DAM_MASK_GATHER_COLUMNS
     sized = B.build_mask(mode=mode, H=H, L=L, S=S, tile_m=w.tile_m, tile_n=w.tile_n, lam=w.lam, eps=w.eps, tau=w.tau,
-                         mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in, flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
+                         mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in, flags=FLAGS)
     torch.cuda.synchronize()
     n_tiles = sized.n_tiles
     kinds = sized.blk_kind.cpu().numpy()
@@ -92,8 +94,7 @@ def bench_prefill(args, w, torch, B, wl):
     causal = H * S * (S + 1) // 2
 
     # preallocated outputs for the timed steps
-    p = B.MaskParams(mode, H, L, S, w.tile_m, w.tile_n, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"),
-                     B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    p = B.MaskParams(mode, H, L, S, w.tile_m, w.tile_n, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"), FLAGS)
     ws_mask = B.mask_workspace(p, dev)
     o = B.MaskOut()
     for name in ("true_bits", "diag_cnt", "vert_cnt", "diag_flag", "vert_flag", "bmin"):
@@ -103,8 +104,9 @@ def bench_prefill(args, w, torch, B, wl):
     total = torch.zeros(1, dtype=torch.int64, device=dev)
     o.blk_row_ptr, o.blk_col, o.blk_kind = sized.blk_row_ptr.data_ptr(), sized.blk_col.data_ptr(), sized.blk_kind.data_ptr()
     o.tile_bits, o.blk_capacity, o.blk_total = sized.tile_bits.data_ptr(), n_tiles, total.data_ptr()
+    o.gather_idx, o.gather_cnt = sized.gather_idx.data_ptr(), sized.gather_cnt.data_ptr()
     out = torch.empty_like(q)
-    ap_ = B.attn_params(q, k, v, out, w.tile_m, w.tile_n)
+    ap_ = B.attn_params(q, k, v, out, w.tile_m, w.tile_n, gather_rows=sized.gather_rows)
     ws_attn = B.prefill_workspace(ap_, dev)
 
     def step(ev=None):
@@ -131,6 +133,24 @@ def bench_prefill(args, w, torch, B, wl):
     step_ms = wall * 1e3 / args.steps
     assert int(total.item()) == n_tiles
 
+    # the same prefill over the plain layout (every matched column in the ordinary tile it falls into), kernel alone
+    plain = B.build_mask(mode=mode, H=H, L=L, S=S, tile_m=w.tile_m, tile_n=w.tile_n, lam=w.lam, eps=w.eps, tau=w.tau,
+                         mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in, flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    ws_plain = B.prefill_workspace(B.attn_params(q, k, v, out, w.tile_m, w.tile_n), dev)
+    for _ in range(2):
+        B.dam_sparse_attn_prefill(q, k, v, plain, out=out, ws=ws_plain)
+    torch.cuda.synchronize()
+    ev = events(2)
+    ev[0].record()
+    for _ in range(10):
+        B.dam_sparse_attn_prefill(q, k, v, plain, out=out, ws=ws_plain)
+    ev[1].record()
+    torch.cuda.synchronize()
+    plain_ms = ev[0].elapsed_time(ev[1]) / 10
+    plain_tiles = plain.n_tiles
+    n_blocks = int(np.unpackbits((kinds >> 1)[:, None].astype(np.uint8), axis=1).sum())
+    del plain
+
     flops_kept = 4.0 * d * nnz
     flops_tiles = 4.0 * d * w.tile_m * w.tile_n * n_tiles
     mask_bytes = (n_tiles - n_full) * (w.tile_m * w.tile_n // 8) + 5 * n_tiles + 4 * H * (sized.blk_row_ptr.shape[1]) + 2 * H * S
@@ -143,6 +163,11 @@ def bench_prefill(args, w, torch, B, wl):
         "tflops_kept_prefill": flops_kept / (attn_ms * 1e-3) / 1e12,
         "tflops_tiles_prefill": flops_tiles / (attn_ms * 1e-3) / 1e12,
         "mask_build_gbs": mask_bytes / (mask_ms * 1e-3) / 1e9, "mask_build_bytes": mask_bytes,
+        "n_blocks": n_blocks, "tflops_blocks_prefill": 4.0 * d * w.tile_m * 32 * n_blocks / (attn_ms * 1e-3) / 1e12,
+        "gathered_tiles": int((sized.blk_col >= (S + w.tile_n - 1) // w.tile_n).sum().item()),
+        "plain_layout": {"listed_tiles": plain_tiles, "prefill_ms_back_to_back": plain_ms,
+                         "tflops_listed_tiles": 4.0 * d * w.tile_m * w.tile_n * plain_tiles / (plain_ms * 1e-3) / 1e12,
+                         "frac_listed_tiles": 4.0 * d * w.tile_m * w.tile_n * plain_tiles / (plain_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
     }
     ctx = dict(Q=Q, K=K, V=V, dflag=dflag, vflag=vflag, A=A, sized=sized)
     return res, ctx
@@ -390,7 +415,8 @@ def main():
         "config": {"workload": f"{w.name}: 1 layer, {w.hq} Q / {w.hkv} KV heads, head_dim {w.head_dim}, seq {w.seq}, "
                                f"bf16, batch 1, heterogeneous per-head masks, tiles {w.tile_m}x{w.tile_n}",
                    "density": res["density"], "nnz": res["nnz"], "listed_tiles": res["n_tiles"],
-                   "full_tiles": res["n_full_tiles"], "tile_fill": res["tile_fill"]},
+                   "full_tiles": res["n_full_tiles"], "tile_fill": res["tile_fill"],
+                   "gathered_column_tiles": res["gathered_tiles"], "key_blocks_of_32": res["n_blocks"]},
         "ms_per_layer_prefill": res["prefill_ms"], "mask_build_ms": res["mask_build_ms"],
         "mask_build_gbs": res["mask_build_gbs"],
         "tflops_kept_entries_prefill_only": res["tflops_kept_prefill"],
@@ -399,7 +425,10 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": res["tflops_kept_prefill"] / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES["k_prefill_bf16_pipe/c3"] if args.workload == "c3" else None,
                      "achieved_listed_tiles": res["tflops_tiles_prefill"],
-                     "frac_listed_tiles": res["tflops_tiles_prefill"] / PEAK_BF16_TFLOPS},
+                     "frac_listed_tiles": res["tflops_tiles_prefill"] / PEAK_BF16_TFLOPS,
+                     "achieved_issued_blocks": res["tflops_blocks_prefill"],
+                     "frac_issued_blocks": res["tflops_blocks_prefill"] / PEAK_BF16_TFLOPS,
+                     "plain_layout": res["plain_layout"]},
     }
     if not args.no_cpu:
         line["cpu_baseline"] = bench_cpu_oracle(args, w, ctx, wl)

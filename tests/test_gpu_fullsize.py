@@ -113,6 +113,24 @@ def test_c3_mask_whole_block_index_bit_exact():
     assert np.array_equal(u64(lean.tile_bits)[partial], bits[partial])
     assert (bits[~partial] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()
     say(f"c3: {int(partial.sum())} partial tiles identical without the bits of the {int((~partial).sum())} full tiles")
+    # ... and with the matched columns gathered into tiles of their own, the layout the benchmark step uses
+    del mask, lean, bits
+    gath = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=w.seq, diag_in=torch.from_numpy(dflag).cuda(),
+                        vert_in=torch.from_numpy(vflag).cuda(),
+                        flags=B.DAM_MASK_SKIP_FULL_TILE_BITS | B.DAM_MASK_GATHER_COLUMNS)
+    torch.cuda.synchronize()
+    row_ptr, col, kind, bits = oracle.block_index(art, w.seq, 128, 128, workers=WORKERS, gather=True)
+    gptr, gidx = oracle.gathered_columns(art, w.seq, 128)
+    got_idx, got_cnt = gath.gather_idx.cpu().numpy(), gath.gather_cnt.cpu().numpy()
+    for h in range(w.hq):
+        seg = gidx[gptr[h]:gptr[h + 1]]
+        assert got_cnt[h] == int((seg >= 0).sum()) and np.array_equal(got_idx[h, :len(seg)], seg)
+        assert (got_idx[h, len(seg):] == -1).all()
+    partial = (kind & 1) == 0
+    assert np.array_equal(gath.blk_row_ptr.cpu().numpy().astype(np.int64), row_ptr)
+    assert np.array_equal(gath.blk_col.cpu().numpy(), col) and np.array_equal(gath.blk_kind.cpu().numpy(), kind)
+    assert np.array_equal(u64(gath.tile_bits)[partial], bits[partial])
+    say(f"c3: gathered layout: {len(col)} tiles ({int((col >= w.seq // 128).sum())} of them gathered) identical")
 
 
 def test_c4_full_size():
