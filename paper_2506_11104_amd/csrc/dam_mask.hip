@@ -770,14 +770,17 @@ __device__ __forceinline__ void stage_sets(uint64_t *lds_sets, bool staged, int 
 // c = gidx[s] <= i and i - c is not a matched diagonal (those entries belong to the diagonal part).
 // A vertical stripe then costs its share of one dense tile per query tile instead of a whole tile.
 
-// The matched columns below S of one head, ascending, padded with -1 up to the stride. One wave per head.
-__global__ void k_gather_columns(Geom g, const uint64_t *__restrict__ cbits, int stride, int *__restrict__ gidx,
-                                 int *__restrict__ gcnt) {
-  const int h = blockIdx.x, lane = threadIdx.x;
+// The matched columns below S of one head, ascending, padded with -1 up to the stride. One workgroup per
+// head: its first wave walks the column bitset (the columns are few), then all waves write the padding.
+__global__ __launch_bounds__(1024) void k_gather_columns(Geom g, const uint64_t *__restrict__ cbits, int stride,
+                                                         int *__restrict__ gidx, int *__restrict__ gcnt) {
+  __shared__ int s_count;
+  const int h = blockIdx.x, lane = threadIdx.x & 63;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   int *out = gidx + (int64_t)h * stride;
   const int n_cols = min(g.P, g.S);
   int base = 0;
+  if (threadIdx.x < 64)
   for (int w0 = 0; w0 * 64 < n_cols; w0 += 64) {
     const int w = w0 + lane;
     uint64_t m = (w < g.pw && w * 64 < n_cols) ? cb[w] : 0;
@@ -795,8 +798,25 @@ __global__ void k_gather_columns(Geom g, const uint64_t *__restrict__ cbits, int
     }
     base += __shfl(incl, 63);
   }
-  for (int x = base + lane; x < stride; x += 64) out[x] = -1;
-  if (lane == 0) gcnt[h] = base;
+  if (threadIdx.x == 0) {
+    s_count = base;
+    gcnt[h] = base;
+  }
+  __syncthreads();
+  for (int x = s_count + threadIdx.x; x < stride; x += blockDim.x) out[x] = -1;
+}
+
+// Transpose of the 64 x 64 bit matrix whose row l is the word x of lane l: lane r returns the word whose
+// bit l is bit r of lane l's x. Six exchange steps on blocks of 32, 16, ... 1 bits.
+__device__ __forceinline__ uint64_t transpose64(uint64_t x, int lane) {
+  uint64_t m = 0x00000000FFFFFFFFull;
+#pragma unroll
+  for (int j = 32; j > 0; j >>= 1) {
+    const uint64_t other = __shfl_xor(x, j);
+    x = (lane & j) ? (((other >> j) & m) | (x & ~m)) : ((x & m) | ((other & m) << j));
+    m ^= m << (j >> 1);
+  }
+  return x;
 }
 
 // Row bitmap of one gathered slot for the rows of query tile qt: bit r of word k is row 64 k + r of the
@@ -1163,16 +1183,11 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
           }
         }
         if (tile_bits && !(is_full && skip_full_bits)) {
-          // transpose: word (row r, group wg) = the lanes' bit r; lane r % 64 keeps it, 64 rows per store
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
             if (k < g.tile_m / 64) {  // wave-uniform
-              uint64_t mine_word = 0;
-              for (int r = 0; r < 64; ++r) {
-                const uint64_t word = __ballot((keep[k] >> r) & 1);
-                if (lane == r) mine_word = word;
-              }
-              tile_bits[t * words + (int64_t)(64 * k + lane) * g.wpr + wg] = mine_word;
+              // transpose: lane r gets the word (row 64 k + r, group wg), whose bit l is slot l of the group
+              tile_bits[t * words + (int64_t)(64 * k + lane) * g.wpr + wg] = transpose64(keep[k], lane);
             }
           }
         }
@@ -1422,7 +1437,7 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
     const bool gather = (p->flags & DAM_MASK_GATHER_COLUMNS) != 0;
     const int gstride = dam_gather_stride(p);
     const int *gidx = gather ? o->gather_idx : nullptr, *gcnt = gather ? o->gather_cnt : nullptr;
-    if (gather) k_gather_columns<<<g.H, 64, 0, stream>>>(g, w.cbits, gstride, o->gather_idx, o->gather_cnt);
+    if (gather) k_gather_columns<<<g.H, 1024, 0, stream>>>(g, w.cbits, gstride, o->gather_idx, o->gather_cnt);
     k_tile_scan<<<dim3((g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
                                                                      w.off_all, w.occ, w.full, w.tile_cnt, lds_sets > 0, gidx,
                                                                      gcnt, gstride, w.vocc, w.vfull);
