@@ -25,17 +25,25 @@ struct EvictArgs {
   int64_t kv_sb, kv_sh, kv_ss, c_sb, c_sh, c_ss;  // strides in 16-byte pieces
 };
 
-// Per KV head: W = 1 + largest matched diagonal of its query heads, and the number of matched columns
-// <= pos of their union.
+// The flag arrays are walked in chunks of kChunk columns, one workgroup per (chunk, KV head).
+constexpr int kChunk = 4096;
+
+__global__ void k_evict_init(int Hkv, int *__restrict__ window) {
+  for (int g = threadIdx.x; g < Hkv; g += blockDim.x) window[g] = 0;
+}
+
+// Per KV head: W = 1 + largest matched diagonal of its query heads (maximum over the chunks), and per
+// chunk the number of matched columns <= pos of their union.
 __global__ __launch_bounds__(256) void k_evict_count(EvictArgs a, const uint8_t *__restrict__ diag_flag,
                                                      const uint8_t *__restrict__ vert_flag, int *__restrict__ window,
-                                                     int *__restrict__ cnt) {
+                                                     int *__restrict__ chunk_cnt) {
   __shared__ int s_max[4], s_cnt[4];
-  const int g = blockIdx.x, G = a.Hq / a.Hkv;
+  const int chunk = blockIdx.x, g = blockIdx.y, G = a.Hq / a.Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int rmax = -1, n = 0;
   const int last = min(a.P - 1, a.pos);
-  for (int x = threadIdx.x; x < a.P; x += 256) {
+  const int x_end = min(a.P, (chunk + 1) * kChunk);
+  for (int x = chunk * kChunk + threadIdx.x; x < x_end; x += 256) {
     bool any_d = false, any_c = false;
     for (int q = 0; q < G; ++q) {
       any_d |= diag_flag[(int64_t)(g * G + q) * a.P + x] != 0;
@@ -54,41 +62,49 @@ __global__ __launch_bounds__(256) void k_evict_count(EvictArgs a, const uint8_t 
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    window[g] = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3])) + 1;
-    cnt[g] = (s_cnt[0] + s_cnt[1]) + (s_cnt[2] + s_cnt[3]);
+    const int w = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3])) + 1;
+    if (w > 0) atomicMax(&window[g], w);  // an integer maximum: the order of the chunks does not matter
+    chunk_cnt[g * gridDim.x + chunk] = (s_cnt[0] + s_cnt[1]) + (s_cnt[2] + s_cnt[3]);
   }
 }
 
-__global__ void k_evict_offsets(int Hkv, const int *__restrict__ cnt, const int *__restrict__ window,
+// Offsets of every chunk's columns (chunk_cnt becomes an exclusive prefix), col_ptr, rows, total.
+__global__ void k_evict_offsets(int Hkv, int n_chunks, int *__restrict__ chunk_cnt, const int *__restrict__ window,
                                 int *__restrict__ col_ptr, int *__restrict__ rows, int64_t *__restrict__ col_total) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   int64_t at = 0;
   for (int g = 0; g < Hkv; ++g) {
     col_ptr[g] = (int)at;
-    if (rows) rows[g] = cnt[g] + window[g];
-    at += cnt[g];
+    for (int c = 0; c < n_chunks; ++c) {
+      const int n = chunk_cnt[g * n_chunks + c];
+      chunk_cnt[g * n_chunks + c] = (int)at;
+      at += n;
+    }
+    if (rows) rows[g] = (int)(at - col_ptr[g]) + window[g];
   }
   col_ptr[Hkv] = (int)at;
   *col_total = at;
 }
 
-// The live columns of one KV head, ascending. Thread t owns a contiguous stretch of the columns.
+// The live columns of one chunk of one KV head, ascending, from the chunk's offset on. Thread t owns a
+// contiguous stretch of the chunk.
 __global__ __launch_bounds__(256) void k_evict_fill(EvictArgs a, const uint8_t *__restrict__ vert_flag,
-                                                    const int *__restrict__ col_ptr, int *__restrict__ cols,
+                                                    const int *__restrict__ chunk_base, int *__restrict__ cols,
                                                     int64_t capacity) {
   __shared__ int s_wave[4];
-  const int g = blockIdx.x, G = a.Hq / a.Hkv;
+  const int chunk = blockIdx.x, g = blockIdx.y, G = a.Hq / a.Hkv;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_cols = min(a.P, a.pos + 1);
-  const int per = (n_cols + 255) / 256;
-  const int x0 = threadIdx.x * per, x1 = min(n_cols, x0 + per);
+  constexpr int per = kChunk / 256;
+  const int x0 = chunk * kChunk + threadIdx.x * per, x1 = min(n_cols, x0 + per);
   auto live = [&](int x) {
     bool any = false;
     for (int q = 0; q < G; ++q) any |= vert_flag[(int64_t)(g * G + q) * a.P + x] != 0;
     return any;
   };
-  int mine = 0;
-  for (int x = x0; x < x1; ++x) mine += live(x) ? 1 : 0;
+  unsigned mine_bits = 0;  // the stretch is 16 columns long
+  for (int x = x0; x < x1; ++x) mine_bits |= (live(x) ? 1u : 0u) << (x - x0);
+  const int mine = __popc(mine_bits);
   int incl = mine;
   for (int off = 1; off < 64; off <<= 1) {
     const int up = __shfl_up(incl, off);
@@ -98,12 +114,13 @@ __global__ __launch_bounds__(256) void k_evict_fill(EvictArgs a, const uint8_t *
   __syncthreads();
   int before = 0;
   for (int w = 0; w < wave; ++w) before += s_wave[w];
-  int64_t at = (int64_t)col_ptr[g] + before + incl - mine;
-  for (int x = x0; x < x1; ++x)
-    if (live(x)) {
-      if (at < capacity) cols[at] = x;
-      ++at;
-    }
+  int64_t at = (int64_t)chunk_base[g * gridDim.x + chunk] + before + incl - mine;
+  while (mine_bits) {
+    const int b = __ffs(mine_bits) - 1;
+    mine_bits &= mine_bits - 1;
+    if (at < capacity) cols[at] = x0 + b;
+    ++at;
+  }
 }
 
 // Gather of the live rows of (sequence b, KV head g) into the compacted caches: row s of the
@@ -194,7 +211,8 @@ EvictArgs make_args(const dam_evict_params *p, bool caches) {
 
 extern "C" size_t dam_kv_evict_workspace(const dam_evict_params *p) {
   if (validate(p) != DAM_OK) return 0;
-  return align_up((size_t)p->hkv * sizeof(int), 256);
+  const size_t n_chunks = ((size_t)p->n_flags + kChunk - 1) / kChunk;
+  return align_up((size_t)p->hkv * n_chunks * sizeof(int), 256);
 }
 
 extern "C" int dam_kv_evict_plan(const dam_evict_params *p, const uint8_t *diag_flag, const uint8_t *vert_flag,
@@ -207,10 +225,13 @@ extern "C" int dam_kv_evict_plan(const dam_evict_params *p, const uint8_t *diag_
   if (!ws || ws_bytes < dam_kv_evict_workspace(p)) return DAM_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream_v);
   const EvictArgs a = make_args(p, false);
-  int *cnt = static_cast<int *>(ws);
-  k_evict_count<<<p->hkv, 256, 0, st>>>(a, diag_flag, vert_flag, window, cnt);
-  k_evict_offsets<<<1, 64, 0, st>>>(p->hkv, cnt, window, col_ptr, rows, col_total);
-  if (cols && col_capacity > 0) k_evict_fill<<<p->hkv, 256, 0, st>>>(a, vert_flag, col_ptr, cols, col_capacity);
+  int *chunk_cnt = static_cast<int *>(ws);
+  const int n_chunks = (p->n_flags + kChunk - 1) / kChunk;
+  k_evict_init<<<1, 64, 0, st>>>(p->hkv, window);
+  k_evict_count<<<dim3(n_chunks, p->hkv), 256, 0, st>>>(a, diag_flag, vert_flag, window, chunk_cnt);
+  k_evict_offsets<<<1, 64, 0, st>>>(p->hkv, n_chunks, chunk_cnt, window, col_ptr, rows, col_total);
+  if (cols && col_capacity > 0)
+    k_evict_fill<<<dim3(n_chunks, p->hkv), 256, 0, st>>>(a, vert_flag, chunk_cnt, cols, col_capacity);
   return launch_status();
 }
 
