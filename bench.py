@@ -55,6 +55,21 @@ def events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
+def timed_ms(fn, n, warm=3):
+    """Mean duration of n back-to-back calls of fn on torch's current stream (HIP events), after `warm` untimed ones."""
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ev = events(2)
+    ev[0].record()
+    for _ in range(n):
+        fn()
+    ev[1].record()
+    torch.cuda.synchronize()
+    return ev[0].elapsed_time(ev[1]) / n
+
+
 def bench_prefill(args, w, torch, B, wl):
     """Returns the result dict of the prefill workload (mask build + sparse prefill per step)."""
     dev = "cuda"
@@ -137,16 +152,7 @@ def bench_prefill(args, w, torch, B, wl):
     plain = B.build_mask(mode=mode, H=H, L=L, S=S, tile_m=w.tile_m, tile_n=w.tile_n, lam=w.lam, eps=w.eps, tau=w.tau,
                          mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in, flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
     ws_plain = B.prefill_workspace(B.attn_params(q, k, v, out, w.tile_m, w.tile_n), dev)
-    for _ in range(2):
-        B.dam_sparse_attn_prefill(q, k, v, plain, out=out, ws=ws_plain)
-    torch.cuda.synchronize()
-    ev = events(2)
-    ev[0].record()
-    for _ in range(10):
-        B.dam_sparse_attn_prefill(q, k, v, plain, out=out, ws=ws_plain)
-    ev[1].record()
-    torch.cuda.synchronize()
-    plain_ms = ev[0].elapsed_time(ev[1]) / 10
+    plain_ms = timed_ms(lambda: B.dam_sparse_attn_prefill(q, k, v, plain, out=out, ws=ws_plain), 10, warm=2)
     plain_tiles = plain.n_tiles
     n_blocks = int(np.unpackbits((kinds >> 1)[:, None].astype(np.uint8), axis=1).sum())
     del plain
@@ -281,16 +287,7 @@ def bench_decode(args, torch, B, wl):
     slot = torch.empty_like(kept_idx)
 
     def timed(fn, n):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        ev = events(2)
-        ev[0].record()
-        for _ in range(n):
-            fn()
-        ev[1].record()
-        torch.cuda.synchronize()
-        return ev[0].elapsed_time(ev[1]) / n * 1e3
+        return timed_ms(fn, n) * 1e3
 
     compact_us = timed(lambda: B.kv_compact(plan, kc, vc, kcmp, vcmp), 20)
     live_rows = int(plan.rows.sum().item()) * w.batch
@@ -322,19 +319,12 @@ def bench_mask_from_map(args, torch, B, wl, name):
     A = torch.from_numpy(wl.capture_map(Q[:, :L], K[:, :L], L, w.hq // w.hkv)).cuda()
     q_cap = torch.from_numpy(np.ascontiguousarray(Q[:, :L])).to(torch.bfloat16).cuda()
     k_cap = torch.from_numpy(np.ascontiguousarray(K[:, :L])).to(torch.bfloat16).cuda()
+    qkv_full = None
+    if name == "c4":   # the whole sequence, for the prefill over the extended masks
+        qkv_full = tuple(torch.from_numpy(x).to(torch.bfloat16)[None].cuda() for x in (Q, K, V))
     del Q, K, V
 
-    def timed(fn, n):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        ev = events(2)
-        ev[0].record()
-        for _ in range(n):
-            fn()
-        ev[1].record()
-        torch.cuda.synchronize()
-        return ev[0].elapsed_time(ev[1]) / n
+    timed = timed_ms
 
     p = B.MaskParams(B.DAM_FROM_ATTN_MAP, H, L, L, 128, 128, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
     ws = B.mask_workspace(p, "cuda")
@@ -384,6 +374,31 @@ def bench_mask_from_map(args, torch, B, wl, name):
         res["whole_build"] = {"seq": S, "listed_tiles": sized.n_tiles, "ms": ms2, "bytes": nb2,
                               "roofline": {"bound": "hbm", "achieved": nb2 / (ms2 * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                                            "unit": "GB/s", "frac": nb2 / (ms2 * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+        # prefill over the 128k masks: plain layout, and with the matched columns gathered (the method's stripes)
+        qf, kf, vf = qkv_full
+        outf = torch.empty_like(qf)
+        lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device="cuda")
+        pre = {}
+        for label, mk in (("plain", sized), ("gathered", None)):
+            if mk is None:
+                del sized
+                torch.cuda.empty_cache()
+                mk = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu, attn_sum=A,
+                                  flags=B.DAM_MASK_SKIP_FULL_TILE_BITS | B.DAM_MASK_GATHER_COLUMNS)
+                torch.cuda.synchronize()
+            wsf = B.prefill_workspace(B.attn_params(qf, kf, vf, outf, 128, 128, gather_rows=mk.gather_rows), "cuda")
+            ms_p = timed(lambda: B.dam_sparse_attn_prefill(qf, kf, vf, mk, out=outf, ws=wsf), 5)
+            kd = mk.blk_kind.cpu().numpy()
+            part = (mk.blk_kind & 1) == 0
+            nnz = int((kd & 1).sum()) * 128 * 128
+            for a0 in range(0, mk.n_tiles, 1 << 17):
+                tb = mk.tile_bits[a0:a0 + (1 << 17)][part[a0:a0 + (1 << 17)]].view(torch.uint8).reshape(-1)
+                nnz += int(lut[tb.long()].sum().item())
+            pre[label] = {"listed_tiles": mk.n_tiles, "key_blocks_of_32": int(np.unpackbits((kd >> 1)[:, None].astype(np.uint8), axis=1).sum()),
+                          "prefill_ms": ms_p, "nnz": nnz, "tflops_kept_entries": 4.0 * w.head_dim * nnz / (ms_p * 1e-3) / 1e12,
+                          "frac_of_bf16_peak": 4.0 * w.head_dim * nnz / (ms_p * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+            del wsf
+        res["prefill_128k"] = pre
     return res
 
 

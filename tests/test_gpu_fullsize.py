@@ -211,6 +211,27 @@ def test_c4_full_size():
     rs[3::64] = L
     err = check_rows(Q, K, V, art, out, lse, hs, rs)
     say(f"c4: {n} sampled rows, max abs err {err:.2e}")
+    # the same with the matched columns gathered into tiles of their own (the method's stripes are many here)
+    n_plain = mask.n_tiles
+    del mask, out, lse
+    gath = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=H, L=L, S=S, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu,
+                        attn_sum=torch.from_numpy(wl.capture_map(Q[:, :L], K[:, :L], L, w.hq // w.hkv)).cuda(),
+                        flags=B.DAM_MASK_GATHER_COLUMNS | B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    torch.cuda.synchronize()
+    jobs = [(h, int(qt)) for h in range(0, H, 4) for qt in (L // 128 - 1, L // 128, nQt - 1, int(rng.integers(0, nQt)))]
+    g_ptr = gath.blk_row_ptr.cpu().numpy().astype(np.int64)
+    g_col, g_kind = gath.blk_col.cpu().numpy(), gath.blk_kind.cpu().numpy()
+    for h, qt in jobs:
+        rp, c, k_, bits = oracle.block_index(art, S, 128, 128, heads=[h], qt_range=(qt, qt + 1), workers=1, gather=True)
+        a, b = g_ptr[h, qt], g_ptr[h, qt + 1]
+        assert b - a == rp[0, 1] and np.array_equal(g_col[a:b], c) and np.array_equal(g_kind[a:b], k_), (h, qt)
+        part = (k_ & 1) == 0
+        assert np.array_equal(u64(gath.tile_bits[a:b])[part], bits[part]), (h, qt)
+    out, lse = B.dam_sparse_attn_prefill(q, k, v, gath, want_lse=True)
+    torch.cuda.synchronize()
+    err = check_rows(Q, K, V, art, out, lse, hs, rs)
+    say(f"c4: gathered layout: {gath.n_tiles} tiles instead of {n_plain}, sampled tile rows identical, "
+        f"{n} sampled rows, max abs err {err:.2e}")
 
 
 def test_c5_full_size_lists_and_decode():
