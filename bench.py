@@ -217,17 +217,17 @@ def bench_decode(args, torch, B, wl):
     vc = torch.randn((w.batch, w.hkv, cap, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     qs = torch.randn((steps, w.batch, w.hq, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     dflag, vflag = wl.patterns_c5(wl.scaled(w, steps=steps))
-    # one "map" per (sequence, head): every sequence sits at the same position here, but the ABI does
-    # not assume it
-    d_in = torch.from_numpy(np.tile(dflag, (w.batch, 1))).to(dev)
-    v_in = torch.from_numpy(np.tile(vflag, (w.batch, 1))).to(dev)
-    items = w.batch * w.hq
+    # every sequence of the batch sits at the same position, and a mask belongs to its head, not to an input:
+    # one kept list per head, shared by the batch (dam_decode_params.shared_lists)
+    d_in = torch.from_numpy(dflag).to(dev)
+    v_in = torch.from_numpy(vflag).to(dev)
+    items = w.hq
     max_kept = int((dflag.sum(1) + vflag.sum(1)).max())
     kept_ptr = torch.empty(items + 1, dtype=torch.int32, device=dev)
     kept_idx = torch.empty(items * max_kept, dtype=torch.int32, device=dev)
     total = torch.zeros(1, dtype=torch.int64, device=dev)
     out = torch.empty((w.batch, w.hq, w.head_dim), dtype=torch.bfloat16, device=dev)
-    dp = B.decode_params(qs[0], kc, out)
+    dp = B.decode_params(qs[0], kc, out, shared_lists=True)
     ws_dec = B.decode_workspace(dp, max_kept, dev)
     o = B.MaskOut()
     o.kept_ptr, o.kept_idx, o.kept_capacity, o.kept_total = kept_ptr.data_ptr(), kept_idx.data_ptr(), kept_idx.numel(), total.data_ptr()
@@ -242,7 +242,7 @@ def bench_decode(args, torch, B, wl):
         B.dam_mask_build(p, None, None, d_in, v_in, o, ws_mask)
         if ev:
             ev[1].record()
-        B.dam_sparse_attn_decode(qs[s], kc, vc, kept_ptr, kept_idx, max_kept, out=out, ws=ws_dec)
+        B.dam_sparse_attn_decode(qs[s], kc, vc, kept_ptr, kept_idx, max_kept, out=out, ws=ws_dec, shared_lists=True)
         if ev:
             ev[2].record()
 
@@ -257,11 +257,10 @@ def bench_decode(args, torch, B, wl):
         idx = kept_idx[:int(total.item())].cpu().numpy()
         G = w.hq // w.hkv
         rows = 0
-        for b in range(w.batch):
-            for gk in range(w.hkv):
-                parts = [idx[ptr[b * w.hq + gk * G + x]:ptr[b * w.hq + gk * G + x + 1]] for x in range(G)]
-                rows += len(np.unique(np.concatenate(parts)))
-        return rows * w.head_dim * 2 * 2, int(total.item()) * w.head_dim * 2 * 2
+        for gk in range(w.hkv):
+            parts = [idx[ptr[gk * G + x]:ptr[gk * G + x + 1]] for x in range(G)]
+            rows += len(np.unique(np.concatenate(parts)))
+        return rows * w.batch * w.head_dim * 2 * 2, int(total.item()) * w.batch * w.head_dim * 2 * 2
 
     evs = [events(3) for _ in range(steps)]
     t0 = time.perf_counter()
@@ -281,6 +280,7 @@ def bench_decode(args, torch, B, wl):
     pos0 = w.seq - 1
     dq, vq = torch.from_numpy(dflag).to(dev), torch.from_numpy(vflag).to(dev)
     plan = B.kv_evict_plan(dq, vq, w.hkv, pos0, batch=w.batch)
+    plan_us = timed_ms(lambda: B.kv_evict_plan(dq, vq, w.hkv, pos0, batch=w.batch), 5, warm=1) * 1e3
     ccap = int(plan.rows.max().item())
     kcmp = torch.empty((w.batch, w.hkv, ccap, w.head_dim), dtype=torch.bfloat16, device=dev)
     vcmp = torch.empty_like(kcmp)
@@ -292,18 +292,19 @@ def bench_decode(args, torch, B, wl):
     compact_us = timed(lambda: B.kv_compact(plan, kc, vc, kcmp, vcmp), 20)
     live_rows = int(plan.rows.sum().item()) * w.batch
     compact_bytes = live_rows * w.head_dim * 2 * 2 * 2                  # K and V rows, read and written
-    remap_us = timed(lambda: B.kv_remap_lists(plan, kept_ptr, kept_idx, w.batch, out=slot), 20)
-    dpc = B.decode_params(qs[0], kcmp, out)
+    remap_us = timed(lambda: B.kv_remap_lists(plan, kept_ptr, kept_idx, 1, out=slot), 20)
+    dpc = B.decode_params(qs[0], kcmp, out, shared_lists=True)
     ws_c = B.decode_workspace(dpc, max_kept, dev)
-    dec_c_us = timed(lambda: B.dam_sparse_attn_decode(qs[0], kcmp, vcmp, kept_ptr, slot, max_kept, out=out, ws=ws_c), 50)
+    dec_c_us = timed(lambda: B.dam_sparse_attn_decode(qs[0], kcmp, vcmp, kept_ptr, slot, max_kept, out=out, ws=ws_c,
+                                                      shared_lists=True), 50)
     evict = {"rows_kept_per_kv_head": [int(x) for x in plan.rows.cpu()], "cache_rows": cap,
-             "cache_bytes_ratio": ccap / cap, "compact_us": compact_us, "compact_bytes": compact_bytes,
+             "cache_bytes_ratio": ccap / cap, "plan_us_incl_two_host_syncs": plan_us, "compact_us": compact_us, "compact_bytes": compact_bytes,
              "remap_us": remap_us, "decode_from_compacted_us": dec_c_us,
              "roofline": {"bound": "hbm", "achieved": compact_bytes / (compact_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
                           "unit": "GB/s", "frac": compact_bytes / (compact_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
     del kcmp, vcmp
     return {"workload": "c5", "steps": steps, "kv_eviction": evict, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
-            "decode_us": dec_us, "kept_per_list": sb / (items * w.head_dim * 4), "union_bytes": ub, "sum_bytes": sb,
+            "decode_us": dec_us, "kept_per_list": sb / (w.batch * items * w.head_dim * 4), "union_bytes": ub, "sum_bytes": sb,
             "gbs_union": ub / (dec_us * 1e-6) / 1e9, "gbs_sum": sb / (dec_us * 1e-6) / 1e9,
             "roofline": {"bound": "hbm", "achieved": ub / (dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS,

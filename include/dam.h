@@ -319,6 +319,10 @@ typedef struct {
   int64_t q_stride[2];   /* element strides of batch and head; head_dim contiguous                */
   int64_t kv_stride[3];  /* element strides of batch, KV head and position, for both caches       */
   int64_t o_stride[2];
+  int32_t shared_lists;  /* 0: one kept list per (sequence, head), kept_ptr has batch*hq + 1 entries;
+                            1: one list per head, used by every sequence of the batch (all of them
+                            sit at the same position: the mask belongs to the head, not to the input),
+                            kept_ptr has hq + 1 entries                                             */
 } dam_decode_params;
 
 /* max_kept: upper bound of the kept keys of one (sequence, head) list. */
@@ -326,7 +330,7 @@ size_t dam_sparse_attn_decode_workspace(const dam_decode_params *params, int64_t
 
 /* q, out      device [batch][hq][head_dim] by the strides above.
  * kcache, vcache  device [batch][hkv][kv_capacity][head_dim] by kv_stride.
- * kept_ptr    device i32 [batch*hq + 1]; kept_idx device i32.
+ * kept_ptr    device i32 [batch*hq + 1] ([hq + 1] with shared_lists); kept_idx device i32.
  * max_kept    the bound given to the workspace query (the library does not read kept_ptr on the
  *             host); every list must be no longer than it and every index < kv_capacity.
  * lse         device f32 [batch][hq] or NULL. */

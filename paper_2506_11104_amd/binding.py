@@ -72,7 +72,7 @@ class DecodeParams(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32),
                 ("kv_capacity", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("scale", ctypes.c_float), ("q_stride", ctypes.c_int64 * 2), ("kv_stride", ctypes.c_int64 * 3),
-                ("o_stride", ctypes.c_int64 * 2)]
+                ("o_stride", ctypes.c_int64 * 2), ("shared_lists", ctypes.c_int32)]
 
 
 class CaptureParams(ctypes.Structure):
@@ -366,7 +366,8 @@ def dam_sparse_attn_prefill(q, k, v, mask: Mask, out=None, lse=None, scale: floa
     return (out, lse) if (want_lse or lse is not None) else out
 
 
-def decode_params(q: torch.Tensor, kc: torch.Tensor, out: torch.Tensor, scale: float = 0.0) -> DecodeParams:
+def decode_params(q: torch.Tensor, kc: torch.Tensor, out: torch.Tensor, scale: float = 0.0,
+                  shared_lists: bool = False) -> DecodeParams:
     B, Hq, d = q.shape
     p = DecodeParams()
     p.batch, p.hq, p.hkv, p.kv_capacity, p.head_dim = B, Hq, kc.shape[1], kc.shape[2], d
@@ -374,6 +375,7 @@ def decode_params(q: torch.Tensor, kc: torch.Tensor, out: torch.Tensor, scale: f
     p.q_stride = (ctypes.c_int64 * 2)(*q.stride()[:2])
     p.kv_stride = (ctypes.c_int64 * 3)(*kc.stride()[:3])
     p.o_stride = (ctypes.c_int64 * 2)(*out.stride()[:2])
+    p.shared_lists = 1 if shared_lists else 0
     return p
 
 
@@ -383,14 +385,15 @@ def decode_workspace(p: DecodeParams, max_kept: int, device) -> torch.Tensor:
 
 
 def dam_sparse_attn_decode(q, kcache, vcache, kept_ptr, kept_idx, max_kept: int, out=None, lse=None,
-                           scale: float = 0.0, ws=None, want_lse: bool = False):
-    """q [B][Hq][d]; caches [B][Hkv][cap][d] with identical strides; CSR kept lists per (b, hq)."""
+                           scale: float = 0.0, ws=None, want_lse: bool = False, shared_lists: bool = False):
+    """q [B][Hq][d]; caches [B][Hkv][cap][d] with identical strides; CSR kept lists per (b, hq), or per
+    head for the whole batch with shared_lists."""
     if out is None:
         out = torch.empty_like(q)
     if lse is None and want_lse:
         lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
     assert kcache.stride() == vcache.stride()
-    p = decode_params(q, kcache, out, scale)
+    p = decode_params(q, kcache, out, scale, shared_lists)
     if ws is None:
         ws = decode_workspace(p, max_kept, q.device)
     st = lib().dam_sparse_attn_decode(ctypes.byref(p), _p(q), _p(kcache), _p(vcache), _p(kept_ptr), _p(kept_idx),

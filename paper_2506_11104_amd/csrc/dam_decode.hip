@@ -23,7 +23,7 @@ constexpr int kXcd = 8;
 constexpr int kUnroll = 8;  // keys in flight per lane (K and V fragment each)
 
 struct DecodeArgs {
-  int B, Hq, Hkv, cap, splits;
+  int B, Hq, Hkv, cap, splits, shared_lists;
   float scale;
   int64_t q_sb, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_sh;
 };
@@ -123,7 +123,8 @@ __global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *_
   const int item = b * a.Hq + hq;
 
   const int group = threadIdx.x / LPR, sub = threadIdx.x % LPR;
-  const int64_t lo = kept_ptr[item], hi = kept_ptr[item + 1];
+  const int list = a.shared_lists ? hq : item;  // one list per head for the whole batch, or one per (sequence, head)
+  const int64_t lo = kept_ptr[list], hi = kept_ptr[list + 1];
   const int64_t len = hi - lo;
   const int64_t chunk = (len + a.splits - 1) / a.splits;
   const int64_t beg = lo + (int64_t)split * chunk;
@@ -292,6 +293,7 @@ extern "C" int dam_sparse_attn_decode(const dam_decode_params *p, const void *q,
   DecodeArgs a;
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity;
   a.splits = pick_splits(p, max_kept);
+  a.shared_lists = p->shared_lists != 0;
   a.scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf((float)p->head_dim);
   a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1];
   a.kv_sb = p->kv_stride[0]; a.kv_sh = p->kv_stride[1]; a.kv_ss = p->kv_stride[2];

@@ -75,3 +75,30 @@ def test_decode_lists_from_mask_build_match_prefill_row():
                                    mask.kept_ptr, mask.kept_idx, S)
     torch.cuda.synchronize()
     assert np.abs(out[0].float().cpu().numpy() - O).max() <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("lens", [[700, 33, 0, 1500], [9000, 5000, 1, 8191]])
+def test_lists_shared_by_the_batch_equal_lists_per_sequence(lens):
+    """shared_lists: one list per head for every sequence of the batch. The outputs are bit for bit those
+    of the same lists replicated per sequence (same keys, same order, same splits)."""
+    rng = np.random.default_rng(44)
+    Bn, Hq, Hkv, d, T = 3, 4, 2, 128, 9500
+    g = torch.Generator().manual_seed(6)
+    kc = torch.randn((Bn, Hkv, T, d), generator=g).to(torch.bfloat16).cuda()
+    vc = torch.randn((Bn, Hkv, T, d), generator=g).to(torch.bfloat16).cuda()
+    q = torch.randn((Bn, Hq, d), generator=g).to(torch.bfloat16).cuda()
+    lists = [np.sort(rng.choice(T, n, replace=False)).astype(np.int32) for n in lens]
+    ptr1 = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+    idx1 = torch.from_numpy(np.concatenate(lists)).cuda()
+    ptrB = torch.from_numpy(np.concatenate([[0], np.cumsum(np.tile(lens, Bn))]).astype(np.int32)).cuda()
+    idxB = torch.from_numpy(np.tile(np.concatenate(lists), Bn)).cuda()
+    shared, lse_s = B.dam_sparse_attn_decode(q, kc, vc, ptr1, idx1, max(lens), want_lse=True, shared_lists=True)
+    each, lse_e = B.dam_sparse_attn_decode(q, kc, vc, ptrB, idxB, max(lens), want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(shared, each) and torch.equal(lse_s, lse_e)
+    # and against the oracle, sequence 2
+    kv_of = np.array([2 * Hkv + h // (Hq // Hkv) for h in range(Hq)], np.int32)
+    O, _ = oracle.attend_lists(q[2].float().cpu().numpy(), kc.float().cpu().numpy().reshape(Bn * Hkv, T, d),
+                               vc.float().cpu().numpy().reshape(Bn * Hkv, T, d), kv_of,
+                               np.concatenate([[0], np.cumsum(lens)]).astype(np.int64), np.concatenate(lists))
+    assert np.abs(shared[2].float().cpu().numpy() - O).max() <= TOL["bf16"]
