@@ -84,6 +84,16 @@ typedef enum {
                                       tile instead of a tile of its own. Query tiles that start inside the
                                       true-mask block are listed as without the flag. Requires the outputs
                                       gather_idx and gather_cnt.                                          */
+  DAM_MASK_GROUP_LISTS = 4          /* kept lists for grouped-query decoding: one list per group of
+                                      `group` consecutive maps (the query heads of one KV head) instead of
+                                      one per map, so that a decode step reads every cached row once for
+                                      the whole group. The list of a group holds each key kept by any of
+                                      its maps once, in G + 1 runs, each ascending: the keys kept by two or
+                                      more of the maps, then those kept by map 0 of the group alone, by map
+                                      1 alone, ... kept_member[e] has bit x set iff map x of the group
+                                      keeps key kept_idx[e]. One row only (row_end = row_begin + 1);
+                                      n_maps a multiple of group, 1 <= group <= 8; requires kept_member
+                                      when kept_idx is given.                                              */
 } dam_mask_flags;
 
 typedef enum {
@@ -127,6 +137,7 @@ typedef struct {
   float bmin_override; /* NaN: use the minimum over this call's maps; otherwise this value is bmin  */
   int32_t flags;     /* bit set of dam_mask_flags                                                   */
   int32_t transform; /* dam_transform: the step between the mean map and the threshold (0: Box-Cox)  */
+  int32_t group;     /* DAM_MASK_GROUP_LISTS: maps per group (query heads per KV head); else ignored */
 } dam_mask_params;
 
 /* Outputs of dam_mask_build. Every pointer is a device pointer owned by the caller; any of them may
@@ -164,6 +175,8 @@ typedef struct {
  *   kept_ptr   [H * (row_end - row_begin) + 1] i32   CSR offsets into kept_idx, map-major.
  *   kept_idx   [kept_capacity] i32      kept keys of each emitted row, ascending, no duplicates.
  *   kept_total [1] i64                  number of kept keys over the emitted rows (as blk_total).
+ *   With DAM_MASK_GROUP_LISTS: kept_ptr [H / group + 1], one list per group; kept_member
+ *   [kept_capacity] u8 beside kept_idx.
  */
 typedef struct {
   uint64_t *true_bits;
@@ -182,6 +195,7 @@ typedef struct {
   int32_t *gather_idx; /* [H][dam_gather_stride(params)] i32: DAM_MASK_GATHER_COLUMNS, the matched columns
                           below S of each map, ascending, then -1 up to the stride                        */
   int32_t *gather_cnt; /* [H] i32: how many                                                                */
+  uint8_t *kept_member; /* [kept_capacity] u8: DAM_MASK_GROUP_LISTS, which maps of the group keep each entry */
 } dam_mask_out;
 
 /* Row length of gather_idx: min(P, S) rounded up to a multiple of tile_n, P the length of the pattern
@@ -338,6 +352,23 @@ int dam_sparse_attn_decode(const dam_decode_params *params, const void *q, const
                            const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
                            int64_t max_kept, void *out, float *lse, void *ws, size_t ws_bytes,
                            void *stream);
+
+/* dam_sparse_attn_decode for all query heads of a KV head at once (grouped-query attention: hq / hkv
+ * query heads share the K and V rows of one KV head). The lists are those of dam_mask_build with
+ * DAM_MASK_GROUP_LISTS and group = hq / hkv (<= 8): one per (sequence, KV head), or one per KV head with
+ * shared_lists, holding every key that some head of the group keeps once, and kept_member[e] naming the
+ * heads that keep it (bit x: query head hkv_index * group + x). A workgroup reads each listed row once
+ * and updates the softmax state of exactly the heads named; the results equal those of
+ * dam_sparse_attn_decode on the per-head lists up to the order of the fp32 sums.
+ * kept_ptr  device i32 [batch*hkv + 1] ([hkv + 1] with shared_lists); kept_idx i32 and kept_member u8
+ *           device arrays of the same length. Entries of one list may come in any order, without
+ *           duplicates; runs of entries with equal kept_member cost no arithmetic for the other heads.
+ * max_kept  upper bound of the length of one list. Everything else as dam_sparse_attn_decode. */
+size_t dam_sparse_attn_decode_grouped_workspace(const dam_decode_params *params, int64_t max_kept);
+int dam_sparse_attn_decode_grouped(const dam_decode_params *params, const void *q, const void *kcache,
+                                   const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
+                                   const uint8_t *kept_member, int64_t max_kept, void *out, float *lse,
+                                   void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * dam_kv_evict_plan, dam_kv_compact, dam_kv_remap_lists: KV-cache eviction for decode

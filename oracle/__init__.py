@@ -354,6 +354,30 @@ def attend_lists(q, kcache, vcache, kv_of, kept_ptr, kept_idx, scale: Optional[f
     return out, lse
 
 
+def group_lists(lists: Sequence[np.ndarray], group: int):
+    """Kept lists of one decode row merged per KV head (grouped-query attention: `group` consecutive
+    query heads read the K / V rows of one KV head; the mask row of each head is that of Sec. 4.3).
+    lists: one ascending key array per query head. Returns (ptr [n_kv + 1] i64, idx i32, member u8):
+    the list of a KV head holds every key some head of its group keeps exactly once, as group + 1 runs,
+    each ascending: keys kept by two or more of the heads, then keys kept by head 0 of the group only,
+    by head 1 only, ...; bit x of member[e] says that head x of the group keeps key idx[e]."""
+    assert len(lists) % group == 0 and 1 <= group <= 8
+    ptr, idx, member = [0], [], []
+    for kv in range(len(lists) // group):
+        who = {}
+        for x in range(group):
+            for j in lists[kv * group + x]:
+                who[int(j)] = who.get(int(j), 0) | (1 << x)
+        runs = [sorted(j for j, m in who.items() if bin(m).count("1") >= 2)]
+        for x in range(group):
+            runs.append(sorted(j for j, m in who.items() if m == 1 << x))
+        for run in runs:
+            idx.extend(run)
+            member.extend(who[j] for j in run)
+        ptr.append(len(idx))
+    return np.array(ptr, np.int64), np.array(idx, np.int32), np.array(member, np.uint8)
+
+
 # ---------------------------------------------------------------------------------------------
 @dataclass
 class EvictionPlan:

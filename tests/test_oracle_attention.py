@@ -155,3 +155,38 @@ def test_decode_row_equals_prefill_row():
     Od, ld = oracle.attend_lists(Q[:, p], K, V, [h // 2 for h in range(Hq)], ptr, np.concatenate(lists))
     np.testing.assert_allclose(Od, O[:, p], atol=1e-13)
     np.testing.assert_allclose(ld, lse[:, p], atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------------
+# kept lists merged per KV head (grouped-query decode)
+def test_group_lists_worked_example():
+    # two KV heads of two query heads each, written out by hand
+    lists = [np.array([0, 1, 5, 9], np.int32), np.array([1, 2, 9], np.int32),
+             np.array([], np.int32), np.array([3, 4], np.int32)]
+    ptr, idx, member = oracle.group_lists(lists, 2)
+    assert ptr.tolist() == [0, 5, 7]
+    # KV head 0: kept by both {1, 9}; by head 0 alone {0, 5}; by head 1 alone {2}. KV head 1: head 1 alone.
+    assert idx.tolist() == [1, 9, 0, 5, 2, 3, 4]
+    assert member.tolist() == [3, 3, 1, 1, 2, 2, 2]
+
+
+def test_group_lists_expand_back_to_the_lists_of_the_heads():
+    rng = np.random.default_rng(7)
+    for group in (1, 2, 3, 4, 8):
+        n_kv = 3
+        lists = [np.sort(rng.choice(300, size=int(rng.integers(0, 120)), replace=False)).astype(np.int32)
+                 for _ in range(n_kv * group)]
+        lists[1 % len(lists)] = lists[0].copy()  # two heads with the same list
+        ptr, idx, member = oracle.group_lists(lists, group)
+        for kv in range(n_kv):
+            seg, mem = idx[ptr[kv]:ptr[kv + 1]], member[ptr[kv]:ptr[kv + 1]]
+            assert len(np.unique(seg)) == len(seg)  # every key once
+            assert (mem != 0).all() and (mem >> group == 0).all()
+            for x in range(group):
+                assert np.array_equal(np.sort(seg[(mem >> x) & 1 == 1]), lists[kv * group + x])
+            # the runs: shared keys first, then one run per head, each ascending
+            n_heads = np.array([bin(int(m)).count("1") for m in mem])
+            run = np.where(n_heads >= 2, 0, 1 + np.log2(np.maximum(mem, 1)).astype(int))
+            assert (np.diff(run) >= 0).all()
+            for r in range(group + 1):
+                assert (np.diff(seg[run == r]) > 0).all()
