@@ -72,7 +72,7 @@ typedef enum {
                                       kernels never read them, and at long sequences they are a large part
                                       of the bytes written. Their slots in the pool stay reserved and keep
                                       whatever they held.                                                  */
-  DAM_MASK_GATHER_COLUMNS = 2       /* list the matched columns in tiles of their own. The mask is the same;
+  DAM_MASK_GATHER_COLUMNS = 2,      /* list the matched columns in tiles of their own. The mask is the same;
                                       in every query tile that lies wholly in the pattern region (first row
                                       >= pcl) its entries are split into
                                         a diagonal part: key j <= i with i - j a matched diagonal, listed in

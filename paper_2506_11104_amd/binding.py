@@ -22,6 +22,7 @@ DAM_F32, DAM_BF16 = 0, 1
 DAM_FROM_ATTN_MAP, DAM_FROM_PATTERNS = 0, 1
 DAM_MASK_SKIP_FULL_TILE_BITS = 1
 DAM_MASK_GATHER_COLUMNS = 2
+DAM_MASK_GROUP_LISTS = 4
 TRANSFORMS = {"boxcox": 0, "raw_sum": 1, "average": 2, "log": 3, "yeo_johnson": 4, "zscore": 5, "minmax": 6,
               "sqrt": 7, "arcsinh": 8}
 
@@ -41,7 +42,7 @@ class MaskParams(ctypes.Structure):
                 ("row_begin", ctypes.c_int32), ("row_end", ctypes.c_int32), ("lam", ctypes.c_float),
                 ("eps", ctypes.c_float), ("tau", ctypes.c_float), ("mu", ctypes.c_float),
                 ("bmin_override", ctypes.c_float), ("flags", ctypes.c_int32),
-                ("transform", ctypes.c_int32)]
+                ("transform", ctypes.c_int32), ("group", ctypes.c_int32)]
 
 
 class MaskOut(ctypes.Structure):
@@ -51,7 +52,7 @@ class MaskOut(ctypes.Structure):
                 ("tile_bits", ctypes.c_void_p), ("blk_capacity", ctypes.c_int64), ("blk_total", ctypes.c_void_p),
                 ("dense_bits", ctypes.c_void_p), ("kept_ptr", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
                 ("kept_capacity", ctypes.c_int64), ("kept_total", ctypes.c_void_p), ("gather_idx", ctypes.c_void_p),
-                ("gather_cnt", ctypes.c_void_p)]
+                ("gather_cnt", ctypes.c_void_p), ("kept_member", ctypes.c_void_p)]
 
 
 class AttnParams(ctypes.Structure):
@@ -90,7 +91,8 @@ class EvictParams(ctypes.Structure):
 
 EXPORTS = ["dam_gather_stride", "dam_kv_evict_workspace", "dam_kv_evict_plan", "dam_kv_compact", "dam_kv_remap_lists", "dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
            "dam_mask_build_from_qk_workspace", "dam_mask_build_from_qk", "dam_sparse_attn_prefill_workspace",
-           "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode", "dam_version"]
+           "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode",
+           "dam_sparse_attn_decode_grouped_workspace", "dam_sparse_attn_decode_grouped", "dam_version"]
 
 _lib = None
 
@@ -126,6 +128,11 @@ def lib() -> ctypes.CDLL:
         L.dam_sparse_attn_decode_workspace.argtypes = [ctypes.POINTER(DecodeParams), i64]
         L.dam_sparse_attn_decode.restype = ctypes.c_int
         L.dam_sparse_attn_decode.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dam_sparse_attn_decode_grouped_workspace.restype = sz
+        L.dam_sparse_attn_decode_grouped_workspace.argtypes = [ctypes.POINTER(DecodeParams), i64]
+        L.dam_sparse_attn_decode_grouped.restype = ctypes.c_int
+        L.dam_sparse_attn_decode_grouped.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, vp, i64, vp, vp,
+                                                     vp, sz, vp]
         L.dam_gather_stride.restype = ctypes.c_int32
         L.dam_gather_stride.argtypes = [ctypes.POINTER(MaskParams)]
         L.dam_kv_evict_workspace.restype = sz
@@ -177,6 +184,7 @@ class Mask:
     dense_bits: Optional[torch.Tensor] = None
     kept_ptr: Optional[torch.Tensor] = None
     kept_idx: Optional[torch.Tensor] = None
+    kept_member: Optional[torch.Tensor] = None  # u8 beside kept_idx (DAM_MASK_GROUP_LISTS)
     n_kept: int = 0
     gather_idx: Optional[torch.Tensor] = None   # [H][gather_stride] i32 (DAM_MASK_GATHER_COLUMNS)
     gather_cnt: Optional[torch.Tensor] = None   # [H] i32
@@ -244,13 +252,17 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
                diag_in: Optional[torch.Tensor] = None, vert_in: Optional[torch.Tensor] = None,
                true_bits: Optional[torch.Tensor] = None, blocks: bool = True, tile_bits: bool = True,
                dense: bool = False, rows: Optional[Tuple[int, int]] = None, device="cuda",
-               qk: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, scale: float = 0.0, flags: int = 0, transform: int = 0) -> Mask:
+               qk: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, scale: float = 0.0, flags: int = 0, transform: int = 0,
+               group: int = 0) -> Mask:
     """Convenience wrapper: allocates the outputs, sizes the tile pool / kept lists with a first
     call (blk_col == NULL), then fills them with a second. Only allocation and marshalling.
-    qk = (q [H][L][d], k [Hkv][L][d]) selects dam_mask_build_from_qk (one captured sequence, no map)."""
+    qk = (q [H][L][d], k [Hkv][L][d]) selects dam_mask_build_from_qk (one captured sequence, no map).
+    group > 0 sets DAM_MASK_GROUP_LISTS: rows must name one row; kept_ptr has H / group + 1 entries."""
+    if group > 0:
+        flags |= DAM_MASK_GROUP_LISTS
     dev = torch.device(device)
     p = MaskParams(mode, H, L, S, tile_m, tile_n, rows[0] if rows else 0, rows[1] if rows else 0, lam, eps, tau, mu,
-                   bmin_override, flags, transform)
+                   bmin_override, flags, transform, group)
     if qk is not None:
         cp = capture_params(qk[0], qk[1], L, scale)
         ws = mask_from_qk_workspace(p, cp, dev)
@@ -288,7 +300,8 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
         m.blk_row_ptr = torch.empty((H, nQt + 1), dtype=torch.int32, device=dev)
         o.blk_row_ptr, o.blk_total = _p(m.blk_row_ptr), totals[0:1].data_ptr()
     if rows:
-        m.kept_ptr = torch.empty(H * (rows[1] - rows[0]) + 1, dtype=torch.int32, device=dev)
+        n_lists = H // group if group > 0 else H * (rows[1] - rows[0])
+        m.kept_ptr = torch.empty(n_lists + 1, dtype=torch.int32, device=dev)
         o.kept_ptr, o.kept_total = _p(m.kept_ptr), totals[1:2].data_ptr()
     if dense:
         m.dense_bits = torch.empty((H, S, (S + 63) // 64), dtype=torch.int64, device=dev)
@@ -316,6 +329,9 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
             m.n_kept = n_kept
             m.kept_idx = torch.empty(n_kept, dtype=torch.int32, device=dev)
             o.kept_idx, o.kept_capacity = _p(m.kept_idx), n_kept
+            if group > 0:
+                m.kept_member = torch.empty(n_kept, dtype=torch.uint8, device=dev)
+                o.kept_member = _p(m.kept_member)
             again = True
         if again:
             o.dense_bits = None
@@ -399,6 +415,31 @@ def dam_sparse_attn_decode(q, kcache, vcache, kept_ptr, kept_idx, max_kept: int,
     st = lib().dam_sparse_attn_decode(ctypes.byref(p), _p(q), _p(kcache), _p(vcache), _p(kept_ptr), _p(kept_idx),
                                       max_kept, _p(out), _p(lse), _p(ws), ws.numel(), _stream())
     _check("dam_sparse_attn_decode", st)
+    return (out, lse) if (want_lse or lse is not None) else out
+
+
+def decode_grouped_workspace(p: DecodeParams, max_kept: int, device) -> torch.Tensor:
+    n = lib().dam_sparse_attn_decode_grouped_workspace(ctypes.byref(p), max_kept)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def dam_sparse_attn_decode_grouped(q, kcache, vcache, kept_ptr, kept_idx, kept_member, max_kept: int, out=None,
+                                   lse=None, scale: float = 0.0, ws=None, want_lse: bool = False,
+                                   shared_lists: bool = False):
+    """As dam_sparse_attn_decode, with one merged list per (b, KV head) (per KV head with shared_lists) and
+    a byte of member bits per entry (dam_mask_build with DAM_MASK_GROUP_LISTS)."""
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    assert kcache.stride() == vcache.stride()
+    p = decode_params(q, kcache, out, scale, shared_lists)
+    if ws is None:
+        ws = decode_grouped_workspace(p, max_kept, q.device)
+    st = lib().dam_sparse_attn_decode_grouped(ctypes.byref(p), _p(q), _p(kcache), _p(vcache), _p(kept_ptr),
+                                              _p(kept_idx), _p(kept_member), max_kept, _p(out), _p(lse), _p(ws),
+                                              ws.numel(), _stream())
+    _check("dam_sparse_attn_decode_grouped", st)
     return (out, lse) if (want_lse or lse is not None) else out
 
 

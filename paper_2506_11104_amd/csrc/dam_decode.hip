@@ -211,6 +211,151 @@ __global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *_
   }
 }
 
+// Grouped-query form: one workgroup per (sequence, KV head, split) walks the merged list of the KV
+// head's query heads; every listed K / V row is read once and enters the softmax state of exactly
+// the heads whose member bit is set. A wave's 32 consecutive entries mostly belong to one run of the
+// list (kept by several heads, or by one head only), so a head with no member bit in the wave's
+// entries of a pass is skipped for the whole pass (wave-uniform branch).
+template <typename T, int D, int GM>
+__global__ __launch_bounds__(256) void k_decode_group(DecodeArgs a, const T *__restrict__ q,
+                                                      const T *__restrict__ kc, const T *__restrict__ vc,
+                                                      const int *__restrict__ kept_ptr,
+                                                      const int *__restrict__ kept_idx,
+                                                      const uint8_t *__restrict__ kept_member,
+                                                      float *__restrict__ part_o, float *__restrict__ part_ml,
+                                                      T *__restrict__ out, float *__restrict__ lse) {
+  constexpr int N = Frag<T>::N;
+  constexpr int LPR = D / N;
+  constexpr int GROUPS = 256 / LPR;
+  __shared__ float s_o[GROUPS][D];
+  __shared__ float s_m[GROUPS], s_l[GROUPS];
+
+  const int G = a.Hq / a.Hkv;  // <= GM
+  const int split = blockIdx.x % a.splits, pair = blockIdx.x / a.splits;
+  const int b = pair / a.Hkv, hkv = pair % a.Hkv;
+  const int group = threadIdx.x / LPR, sub = threadIdx.x % LPR;
+  const int list = a.shared_lists ? hkv : pair;
+  const int64_t lo = kept_ptr[list], hi = kept_ptr[list + 1];
+  const int64_t len = hi - lo;
+  const int64_t chunk = (len + a.splits - 1) / a.splits;
+  const int64_t beg = lo + (int64_t)split * chunk;
+  const int64_t end = std::min<int64_t>(hi, beg + chunk);
+
+  uint4 qf[GM];
+#pragma unroll
+  for (int x = 0; x < GM; ++x)
+    qf[x] = x < G ? *reinterpret_cast<const uint4 *>(q + b * a.q_sb + (hkv * G + x) * a.q_sh + sub * N)
+                  : uint4{0u, 0u, 0u, 0u};
+  const T *kb = kc + b * a.kv_sb + hkv * a.kv_sh + sub * N;
+  const T *vb = vc + b * a.kv_sb + hkv * a.kv_sh + sub * N;
+  const float sl2 = a.scale * 1.4426950408889634f;
+
+  float m[GM], l[GM], o[GM][N];
+#pragma unroll
+  for (int x = 0; x < GM; ++x) {
+    m[x] = -INFINITY;
+    l[x] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < N; ++e) o[x][e] = 0.0f;
+  }
+
+  int rows[kUnroll];
+  unsigned who[kUnroll];  // member bits; 0 past the end of the stretch
+  int64_t p0 = beg + group * kUnroll;
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const bool ok = p0 + u < end;
+    rows[u] = p0 < end ? kept_idx[ok ? p0 + u : p0] : 0;
+    who[u] = ok ? kept_member[p0 + u] : 0u;
+  }
+  for (; p0 < end; p0 += GROUPS * kUnroll) {
+    uint4 kf[kUnroll], vf[kUnroll];
+    unsigned cur[kUnroll], anyone = 0;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      kf[u] = *reinterpret_cast<const uint4 *>(kb + (int64_t)rows[u] * a.kv_ss);
+      vf[u] = *reinterpret_cast<const uint4 *>(vb + (int64_t)rows[u] * a.kv_ss);
+      cur[u] = who[u];
+      anyone |= who[u];
+    }
+    const int64_t pn = p0 + GROUPS * kUnroll;
+    if (pn < end) {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const bool ok = pn + u < end;
+        rows[u] = kept_idx[ok ? pn + u : pn];
+        who[u] = ok ? kept_member[pn + u] : 0u;
+      }
+    }
+#pragma unroll
+    for (int x = 0; x < GM; ++x) {
+      if (x < G && __ballot((anyone >> x) & 1)) {  // some entry of this wave's pass is kept by head x
+        float s[kUnroll];
+        float mx = m[x];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          const float d = row_sum<LPR>(Frag<T>::dot(qf[x], kf[u]));
+          s[u] = (cur[u] >> x) & 1 ? d * sl2 : -INFINITY;
+          mx = fmaxf(mx, s[u]);
+        }
+        // a lane whose entries all belong to other heads, before its first own one: mx = -inf, state stays 0
+        const float ref = mx == -INFINITY ? 0.0f : mx;
+        const float corr = __builtin_amdgcn_exp2f(m[x] - ref);  // m = -inf -> 0
+        l[x] *= corr;
+#pragma unroll
+        for (int e = 0; e < N; ++e) o[x][e] *= corr;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          const float w = __builtin_amdgcn_exp2f(s[u] - ref);
+          l[x] += w;
+          Frag<T>::axpy(o[x], w, vf[u]);
+        }
+        m[x] = mx;
+      }
+    }
+  }
+
+  // merge the row groups of this block, one head after the other through the same staging area
+#pragma unroll
+  for (int x = 0; x < GM; ++x) {
+    if (x < G) {
+      __syncthreads();
+      if (sub == 0) {
+        s_m[group] = m[x];
+        s_l[group] = l[x];
+      }
+#pragma unroll
+      for (int e = 0; e < N; ++e) s_o[group][sub * N + e] = o[x][e];
+      __syncthreads();
+      if (threadIdx.x < D) {
+        const int hq = hkv * G + x;
+        const int item = b * a.Hq + hq;
+        float M = -INFINITY;
+        for (int gI = 0; gI < GROUPS; ++gI) M = fmaxf(M, s_m[gI]);
+        float Lsum = 0.0f, acc = 0.0f;
+        if (M > -INFINITY)
+          for (int gI = 0; gI < GROUPS; ++gI) {
+            const float w = exp2f(s_m[gI] - M);  // a group that saw no key of this head: m = -inf, w = 0
+            Lsum += w * s_l[gI];
+            acc += w * s_o[gI][threadIdx.x];
+          }
+        if (a.splits == 1) {
+          store_out(out + b * a.o_sb + hq * a.o_sh + threadIdx.x, Lsum > 0.0f ? acc / Lsum : 0.0f);
+          if (lse && threadIdx.x == 0)
+            lse[item] = Lsum > 0.0f ? (M + log2f(Lsum)) * 0.6931471805599453f : -INFINITY;
+        } else {
+          const int64_t slot_out = (int64_t)item * a.splits + split;
+          part_o[slot_out * D + threadIdx.x] = acc;
+          if (threadIdx.x == 0) {
+            part_ml[slot_out * 2] = M;
+            part_ml[slot_out * 2 + 1] = Lsum;
+          }
+        }
+      }
+    }
+  }
+}
+
 template <typename T, int D>
 __global__ void k_decode_merge(DecodeArgs a, const float *__restrict__ part_o,
                                const float *__restrict__ part_ml, T *__restrict__ out,
@@ -234,10 +379,9 @@ __global__ void k_decode_merge(DecodeArgs a, const float *__restrict__ part_o,
     lse[item] = L > 0.0f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
 }
 
-int pick_splits(const dam_decode_params *p, int64_t max_kept) {
+int pick_splits(int64_t items, int64_t max_kept) {
   // Enough workgroups to put two on every CU (512), each with at least 256 keys; one split (and no
   // merge pass) when the batch alone provides them.
-  const int64_t items = (int64_t)p->batch * p->hq;
   int64_t s = (512 + items - 1) / items;
   s = std::min<int64_t>(s, std::max<int64_t>(1, max_kept / 256));
   return (int)std::min<int64_t>(std::max<int64_t>(s, 1), 64);
@@ -276,7 +420,7 @@ void launch(const DecodeArgs &a, const void *q, const void *kc, const void *vc, 
 
 extern "C" size_t dam_sparse_attn_decode_workspace(const dam_decode_params *p, int64_t max_kept) {
   if (!p || p->batch < 1 || p->hq < 1 || p->head_dim < 1 || max_kept < 0) return 0;
-  const int splits = pick_splits(p, max_kept);
+  const int splits = pick_splits((int64_t)p->batch * p->hq, max_kept);
   Carver c(nullptr);
   c.take<float>((size_t)p->batch * p->hq * splits * p->head_dim);
   c.take<float>((size_t)p->batch * p->hq * splits * 2);
@@ -292,7 +436,7 @@ extern "C" int dam_sparse_attn_decode(const dam_decode_params *p, const void *q,
   if (!ws || ws_bytes < dam_sparse_attn_decode_workspace(p, max_kept)) return DAM_ERR_WORKSPACE;
   DecodeArgs a;
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity;
-  a.splits = pick_splits(p, max_kept);
+  a.splits = pick_splits((int64_t)p->batch * p->hq, max_kept);
   a.shared_lists = p->shared_lists != 0;
   a.scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf((float)p->head_dim);
   a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1];
@@ -308,6 +452,66 @@ extern "C" int dam_sparse_attn_decode(const dam_decode_params *p, const void *q,
   } else {
     if (p->head_dim == 128) launch<float, 128>(a, q, kcache, vcache, kept_ptr, kept_idx, out, lse, part_o, part_ml, st);
     else launch<float, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, out, lse, part_o, part_ml, st);
+  }
+  return launch_status();
+}
+
+namespace {
+
+template <typename T, int D>
+void launch_group(const DecodeArgs &a, const void *q, const void *kc, const void *vc, const int32_t *kept_ptr,
+                  const int32_t *kept_idx, const uint8_t *kept_member, void *out, float *lse, float *part_o,
+                  float *part_ml, hipStream_t st) {
+  const int blocks = a.B * a.Hkv * a.splits;
+  if (a.Hq / a.Hkv <= 4)
+    k_decode_group<T, D, 4><<<blocks, 256, 0, st>>>(a, static_cast<const T *>(q), static_cast<const T *>(kc),
+                                                    static_cast<const T *>(vc), kept_ptr, kept_idx, kept_member, part_o,
+                                                    part_ml, static_cast<T *>(out), lse);
+  else
+    k_decode_group<T, D, 8><<<blocks, 256, 0, st>>>(a, static_cast<const T *>(q), static_cast<const T *>(kc),
+                                                    static_cast<const T *>(vc), kept_ptr, kept_idx, kept_member, part_o,
+                                                    part_ml, static_cast<T *>(out), lse);
+  if (a.splits > 1) k_decode_merge<T, D><<<a.B * a.Hq, D, 0, st>>>(a, part_o, part_ml, static_cast<T *>(out), lse);
+}
+
+}  // namespace
+
+extern "C" size_t dam_sparse_attn_decode_grouped_workspace(const dam_decode_params *p, int64_t max_kept) {
+  if (!p || p->batch < 1 || p->hq < 1 || p->hkv < 1 || p->head_dim < 1 || max_kept < 0) return 0;
+  const int splits = pick_splits((int64_t)p->batch * p->hkv, max_kept);
+  Carver c(nullptr);
+  c.take<float>((size_t)p->batch * p->hq * splits * p->head_dim);
+  c.take<float>((size_t)p->batch * p->hq * splits * 2);
+  return c.off;
+}
+
+extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const void *q, const void *kcache,
+                                              const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
+                                              const uint8_t *kept_member, int64_t max_kept, void *out, float *lse,
+                                              void *ws, size_t ws_bytes, void *stream_v) {
+  const int bad = validate(p, q, kcache, vcache, kept_ptr, kept_idx, max_kept, out);
+  if (bad != DAM_OK) return bad;
+  if (max_kept > 0 && !kept_member) return DAM_ERR_INVALID_ARG;
+  if (p->hq / p->hkv > 8) return DAM_ERR_UNSUPPORTED;  // member bits are a byte
+  if (!ws || ws_bytes < dam_sparse_attn_decode_grouped_workspace(p, max_kept)) return DAM_ERR_WORKSPACE;
+  DecodeArgs a;
+  a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity;
+  a.splits = pick_splits((int64_t)p->batch * p->hkv, max_kept);
+  a.shared_lists = p->shared_lists != 0;
+  a.scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf((float)p->head_dim);
+  a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1];
+  a.kv_sb = p->kv_stride[0]; a.kv_sh = p->kv_stride[1]; a.kv_ss = p->kv_stride[2];
+  a.o_sb = p->o_stride[0]; a.o_sh = p->o_stride[1];
+  Carver c(ws);
+  float *part_o = c.take<float>((size_t)a.B * a.Hq * a.splits * p->head_dim);
+  float *part_ml = c.take<float>((size_t)a.B * a.Hq * a.splits * 2);
+  hipStream_t st = static_cast<hipStream_t>(stream_v);
+  if (p->dtype == DAM_BF16) {
+    if (p->head_dim == 128) launch_group<__hip_bfloat16, 128>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
+    else launch_group<__hip_bfloat16, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
+  } else {
+    if (p->head_dim == 128) launch_group<float, 128>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
+    else launch_group<float, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
   }
   return launch_status();
 }

@@ -1270,12 +1270,151 @@ __global__ __launch_bounds__(256) void k_row_fill(Geom g, const uint64_t *__rest
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Kept lists of one row for grouped-query decoding (DAM_MASK_GROUP_LISTS): one list per group of G
+// consecutive maps, holding each key some map of the group keeps once, in G + 1 runs (kept by two or
+// more maps; by map 0 alone; by map 1 alone; ...), each ascending, with a byte of member bits per
+// entry. A wave owns a chunk of 64 mask words (4096 keys) of one group; the count kernel writes the
+// G + 1 run sizes of every chunk, the fill kernel derives its write positions from them.
+constexpr int kMaxGroup = 8;
+
+// Word w of row i for the maps of group kv (m[x], zero for x >= G and beyond the row), and the bits
+// set in at least two of them.
+__device__ __forceinline__ void group_words(const Geom &g, const uint64_t *__restrict__ true_bits,
+                                            const uint64_t *__restrict__ cbits, const uint64_t *__restrict__ rrev,
+                                            int kv, int G, int i, int w, uint64_t (&m)[kMaxGroup],
+                                            uint64_t &shared) {
+  uint64_t any = 0;
+  shared = 0;
+#pragma unroll
+  for (int x = 0; x < kMaxGroup; ++x) {
+    m[x] = 0;
+    if (x < G && w <= (i >> 6)) {
+      const int h = kv * G + x;
+      m[x] = mask_word(g, true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr, cbits + (int64_t)h * g.pw,
+                       rrev + (int64_t)h * g.pw, i, w);
+    }
+    shared |= any & m[x];
+    any |= m[x];
+  }
+}
+
+__device__ __forceinline__ int wave_total(int v) {
+  for (int off = 32; off; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+__device__ __forceinline__ uint64_t read_lane64(uint64_t v, int src) {  // src wave-uniform
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, src);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), src);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// cnt[(kv * nchunks + chunk) * (G + 1) + run]
+__global__ __launch_bounds__(256) void k_group_count(Geom g, const uint64_t *__restrict__ true_bits,
+                                                     const uint64_t *__restrict__ cbits,
+                                                     const uint64_t *__restrict__ rrev, int row, int G,
+                                                     int nchunks, int *__restrict__ cnt) {
+  const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), kv = blockIdx.y;
+  if (chunk >= nchunks) return;  // whole waves
+  uint64_t m[kMaxGroup], shared;
+  group_words(g, true_bits, cbits, rrev, kv, G, row, chunk * 64 + lane, m, shared);
+  int *out = cnt + ((int64_t)kv * nchunks + chunk) * (G + 1);
+  const int c0 = wave_total(__popcll(shared));
+  if (lane == 0) out[0] = c0;
+#pragma unroll
+  for (int x = 0; x < kMaxGroup; ++x) {
+    if (x < G) {
+      const int c = wave_total(__popcll(m[x] & ~shared));
+      if (lane == 0) out[1 + x] = c;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_group_fill(Geom g, const uint64_t *__restrict__ true_bits,
+                                                    const uint64_t *__restrict__ cbits,
+                                                    const uint64_t *__restrict__ rrev, int row, int G,
+                                                    int nchunks, int n_groups, const int *__restrict__ cnt,
+                                                    int *__restrict__ kept_ptr, int *__restrict__ kept_idx,
+                                                    uint8_t *__restrict__ kept_member, int64_t capacity,
+                                                    int64_t *__restrict__ kept_total) {
+  const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), kv = blockIdx.y;
+  if (chunk >= nchunks) return;  // whole waves
+  // entries written before this wave's, per run: all of the groups before, the runs before of this
+  // group, the chunks before of the same run
+  const int per_group = nchunks * (G + 1);
+  int all = 0, before_group = 0, before_run[kMaxGroup + 1];
+#pragma unroll
+  for (int r = 0; r <= kMaxGroup; ++r) before_run[r] = 0;
+  for (int e = lane; e < n_groups * per_group; e += 64) {
+    const int c = cnt[e];
+    const int kv2 = e / per_group, rest = e % per_group, chunk2 = rest / (G + 1), run2 = rest % (G + 1);
+    all += c;
+    if (kv2 < kv) before_group += c;
+    if (kv2 == kv) {
+#pragma unroll
+      for (int r = 0; r <= kMaxGroup; ++r)
+        if (run2 < r || (run2 == r && chunk2 < chunk)) before_run[r] += c;
+    }
+  }
+  all = wave_total(all);
+  before_group = wave_total(before_group);
+  if (chunk == 0 && lane == 0) {
+    kept_ptr[kv] = before_group;
+    if (kv == n_groups - 1) {
+      kept_ptr[n_groups] = all;
+      if (kept_total) *kept_total = all;
+    }
+  }
+  if (!kept_idx) return;
+  uint64_t m[kMaxGroup], shared;
+  group_words(g, true_bits, cbits, rrev, kv, G, row, chunk * 64 + lane, m, shared);
+  const uint64_t below = (1ull << lane) - 1;
+#pragma unroll
+  for (int r = 0; r <= kMaxGroup; ++r) {
+    if (r <= G) {
+      const uint64_t mine = r == 0 ? shared : m[r - 1] & ~shared;  // lane's word of run r
+      const int v = __popcll(mine);
+      int incl = v;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+      }
+      const int excl = incl - v;
+      const int64_t base = (int64_t)before_group + wave_total(before_run[r]);
+      for (int x = 0; x < 64; ++x) {
+        const uint64_t word = read_lane64(mine, x);
+        if (!word) continue;  // wave-uniform
+        const int first = __builtin_amdgcn_readlane(excl, x);
+        unsigned who = r == 0 ? 0u : 1u << (r - 1);
+        if (r == 0) {
+#pragma unroll
+          for (int y = 0; y < kMaxGroup; ++y)
+            if (y < G) who |= (unsigned)((read_lane64(m[y], x) >> lane) & 1) << y;
+        }
+        if ((word >> lane) & 1) {
+          const int64_t at = base + first + __popcll(word & below);
+          if (at < capacity) {
+            kept_idx[at] = (chunk * 64 + x) * 64 + lane;
+            kept_member[at] = (uint8_t)who;
+          }
+        }
+      }
+    }
+  }
+}
+
 int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *diag_in,
              const uint8_t *vert_in, const dam_mask_out *o) {
   if (!p || !o) return DAM_ERR_INVALID_ARG;
   if (p->mode != DAM_FROM_ATTN_MAP && p->mode != DAM_FROM_PATTERNS) return DAM_ERR_INVALID_ARG;
   if (p->n_maps < 1 || p->seq < 1) return DAM_ERR_INVALID_ARG;
-  if (p->flags & ~(DAM_MASK_SKIP_FULL_TILE_BITS | DAM_MASK_GATHER_COLUMNS)) return DAM_ERR_INVALID_ARG;
+  if (p->flags & ~(DAM_MASK_SKIP_FULL_TILE_BITS | DAM_MASK_GATHER_COLUMNS | DAM_MASK_GROUP_LISTS)) return DAM_ERR_INVALID_ARG;
+  if ((p->flags & DAM_MASK_GROUP_LISTS) && o->kept_ptr) {
+    if (p->group < 1 || p->group > kMaxGroup || p->n_maps % p->group) return DAM_ERR_INVALID_ARG;
+    if (p->row_end != p->row_begin + 1) return DAM_ERR_UNSUPPORTED;
+    if (o->kept_idx && !o->kept_member) return DAM_ERR_INVALID_ARG;
+  }
   if ((p->flags & DAM_MASK_GATHER_COLUMNS) && (!o->gather_idx || !o->gather_cnt)) return DAM_ERR_INVALID_ARG;
   if (p->tile_m < 64 || p->tile_n < 64 || p->tile_m % 64 || p->tile_n % 64) return DAM_ERR_INVALID_ARG;
   if (p->tile_m > 256 || p->tile_n > 256) return DAM_ERR_UNSUPPORTED;
@@ -1314,6 +1453,9 @@ struct Workspace {
   int *tile_cnt, *row_cnt;
   size_t bytes;
 };
+
+// Chunks of 64 mask words (4096 keys) covering keys 0..row.
+int group_chunks(int row) { return ((row >> 6) + 1 + 63) / 64; }
 
 Geom geometry(const dam_mask_params *p) {
   Geom g;
@@ -1361,7 +1503,10 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   w.vfull = c.take<uint64_t>(gather ? (size_t)g.H * g.nQt * g.occw : 1);
   w.tile_cnt = c.take<int>((size_t)g.H * g.nQt);
   const int nrows = p->row_end > p->row_begin ? p->row_end - p->row_begin : 0;
-  w.row_cnt = c.take<int>((size_t)g.H * (size_t)(nrows > 0 ? nrows : 1));
+  size_t n_cnt = (size_t)g.H * (size_t)(nrows > 0 ? nrows : 1);
+  if ((p->flags & DAM_MASK_GROUP_LISTS) && p->group >= 1 && p->row_begin >= 0)  // run sizes per chunk of 64 words
+    n_cnt = std::max(n_cnt, (size_t)(g.H / p->group) * (size_t)group_chunks(p->row_begin) * (size_t)(p->group + 1));
+  w.row_cnt = c.take<int>(n_cnt);
   w.bytes = c.off;
   return w;
 }
@@ -1454,7 +1599,14 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
   }
   if (want_lists) {
     const int nrows = p->row_end - p->row_begin;
-    if (nrows > 0) {
+    if (p->flags & DAM_MASK_GROUP_LISTS) {
+      const int G = p->group, n_groups = g.H / G, nchunks = group_chunks(p->row_begin);
+      const dim3 grid((nchunks + 3) / 4, n_groups);
+      k_group_count<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, w.row_cnt);
+      k_group_fill<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, n_groups, w.row_cnt,
+                                             o->kept_ptr, o->kept_capacity > 0 ? o->kept_idx : nullptr, o->kept_member,
+                                             o->kept_capacity, o->kept_total);
+    } else if (nrows > 0) {
       k_row_count<<<dim3(nrows, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, nrows, w.row_cnt);
       k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)g.H * nrows, 0, o->kept_ptr, o->kept_total);
       if (o->kept_idx && o->kept_capacity > 0)

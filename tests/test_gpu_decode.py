@@ -102,3 +102,137 @@ def test_lists_shared_by_the_batch_equal_lists_per_sequence(lens):
                                vc.float().cpu().numpy().reshape(Bn * Hkv, T, d), kv_of,
                                np.concatenate([[0], np.cumsum(lens)]).astype(np.int64), np.concatenate(lists))
     assert np.abs(shared[2].float().cpu().numpy() - O).max() <= TOL["bf16"]
+
+
+# ---------------------------------------------------------------------------------------------
+# grouped-query form: one merged list per KV head (DAM_MASK_GROUP_LISTS) and dam_sparse_attn_decode_grouped
+def run_grouped(rng, dtype, Bn, Hq, Hkv, d, T, lists, shared):
+    """lists: one ascending key array per (b, hq) item (per hq with `shared`). The merged lists are the
+    oracle's; the expected outputs are the oracle's attention over each head's own list."""
+    G = Hq // Hkv
+    q = wl.to_storage(rng.standard_normal((Bn, Hq, d)).astype(np.float32) * 1.5, dtype)
+    Kc = wl.to_storage(rng.standard_normal((Bn, Hkv, T, d)).astype(np.float32), dtype)
+    Vc = wl.to_storage(rng.standard_normal((Bn, Hkv, T, d)).astype(np.float32), dtype)
+    per_item = [lists[h] for _ in range(Bn) for h in range(Hq)] if shared else lists
+    ptr = np.concatenate([[0], np.cumsum([len(x) for x in per_item])]).astype(np.int64)
+    idx = np.concatenate(per_item).astype(np.int32) if ptr[-1] else np.empty(0, np.int32)
+    kv_of = np.array([b * Hkv + h // G for b in range(Bn) for h in range(Hq)], np.int32)
+    O, LSE = oracle.attend_lists(q.reshape(Bn * Hq, d), Kc.reshape(Bn * Hkv, T, d), Vc.reshape(Bn * Hkv, T, d), kv_of,
+                                 ptr, idx)
+    gptr, gidx, gmem = oracle.group_lists(lists, G)
+    longest = int(np.diff(gptr).max()) if len(gptr) > 1 else 0
+    pad = lambda a, t: torch.from_numpy(a.astype(t)).cuda() if len(a) else torch.zeros(1, dtype=getattr(torch, np.dtype(t).name), device="cuda")
+    out, lse = B.dam_sparse_attn_decode_grouped(dev(q, dtype), dev(Kc, dtype), dev(Vc, dtype), pad(gptr, np.int32),
+                                                pad(gidx, np.int32), pad(gmem, np.uint8), longest, want_lse=True,
+                                                shared_lists=shared)
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy().reshape(Bn * Hq, d)
+    lse = lse.cpu().numpy().reshape(-1)
+    assert not np.isnan(out).any()
+    fin = np.isfinite(LSE)
+    assert np.array_equal(np.isneginf(lse), ~fin)
+    assert np.abs(out - O).max() <= TOL[dtype]
+    if fin.any():
+        assert np.abs(lse[fin] - LSE[fin]).max() <= TOL[dtype]
+    assert (out[~fin] == 0).all()
+
+
+def overlapping_lists(rng, n, T, lens):
+    """Lists that share a recent window and a few sink keys and add stripes of their own."""
+    out = []
+    for i in range(n):
+        k = int(lens[i])
+        if k == 0:
+            out.append(np.empty(0, np.int32))
+            continue
+        win = np.arange(max(0, T - k // 2), T)
+        own = rng.choice(T, k - len(win), replace=False) if k > len(win) else np.empty(0, int)
+        out.append(np.unique(np.concatenate([win, own, np.arange(min(4, k))])).astype(np.int32))
+    return out
+
+
+@pytest.mark.parametrize("dtype,d,G", [("bf16", 128, 4), ("bf16", 64, 2), ("f32", 64, 4), ("f32", 128, 8),
+                                       ("bf16", 128, 1), ("bf16", 128, 3), ("bf16", 128, 8)])
+def test_grouped_decode_small_and_ragged(dtype, d, G):
+    rng = np.random.default_rng(51)
+    Bn, Hkv, T = 2, 3, 700
+    Hq = Hkv * G
+    lens = rng.integers(0, 300, Bn * Hq)
+    lens[0] = 0                      # a head that keeps nothing
+    lens[Hq - 1] = 700               # a head that keeps everything
+    if G > 1:
+        lens[G:2 * G] = 0            # a whole group that keeps nothing
+        lens[G] = 1
+    run_grouped(rng, dtype, Bn, Hq, Hkv, d, T, overlapping_lists(rng, Bn * Hq, T, lens), shared=False)
+
+
+def test_grouped_decode_long_shared_lists_many_splits():
+    rng = np.random.default_rng(52)
+    Bn, Hq, Hkv, T = 3, 8, 2, 9000
+    lens = np.array([9000, 1, 4097, 0, 5000, 6000, 7000, 8191])
+    run_grouped(rng, "bf16", Bn, Hq, Hkv, 128, T, overlapping_lists(rng, Hq, T, lens), shared=True)
+
+
+def group_lists_case(H, G, S, row, dflag, vflag, L=0, true_mask=None):
+    art = oracle.from_patterns(dflag, vflag, true_mask)
+    want = oracle.group_lists([oracle.kept_list(art, h, row) for h in range(H)], G)
+    tb = None
+    if true_mask is not None:
+        words = np.zeros((H, L, (L + 63) // 64), np.uint64)
+        for h, i, j in zip(*np.nonzero(true_mask)):
+            words[h, i, j // 64] |= np.uint64(1) << np.uint64(j % 64)
+        tb = torch.from_numpy(words.view(np.int64)).cuda()
+    m = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=H, L=L, S=S, diag_in=torch.from_numpy(dflag).cuda(),
+                     vert_in=torch.from_numpy(vflag).cuda(), true_bits=tb, blocks=False, rows=(row, row + 1), group=G)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.kept_ptr.cpu().numpy().astype(np.int64), want[0])
+    n = int(want[0][-1])
+    assert m.n_kept == n
+    if n:
+        assert np.array_equal(m.kept_idx.cpu().numpy()[:n], want[1])
+        assert np.array_equal(m.kept_member.cpu().numpy()[:n], want[2])
+
+
+@pytest.mark.parametrize("G,H,S,row", [(4, 8, 9000, 8999), (4, 8, 9000, 4095), (2, 6, 5000, 4096), (1, 3, 700, 63),
+                                       (8, 16, 13000, 12345), (3, 3, 300, 0), (4, 4, 20000, 16383)])
+def test_group_lists_equal_the_oracle(G, H, S, row):
+    rng = np.random.default_rng(53 + G + row)
+    dflag = (rng.random((H, S)) < 0.01).astype(np.uint8)
+    vflag = (rng.random((H, S)) < 0.01).astype(np.uint8)
+    for h in range(H):
+        dflag[h, :int(rng.integers(0, 600))] = 1     # windows of different widths (nested across heads)
+        vflag[h, :int(rng.integers(0, 8))] = 1       # sinks
+    dflag[H - 1] = 0
+    vflag[H - 1] = 0                                  # a head that keeps nothing
+    group_lists_case(H, G, S, row, dflag, vflag)
+
+
+def test_group_lists_of_a_true_mask_row():
+    rng = np.random.default_rng(59)
+    H, G, L, S = 4, 2, 200, 500
+    tm = np.tril(rng.random((H, L, L)) < 0.2).astype(np.uint8)
+    dflag = (rng.random((H, S)) < 0.1).astype(np.uint8)
+    vflag = (rng.random((H, S)) < 0.1).astype(np.uint8)
+    for row in (150, 199, 200, 499):
+        group_lists_case(H, G, S, row, dflag, vflag, L=L, true_mask=tm)
+
+
+def test_grouped_decode_from_mask_build_matches_the_prefill_row():
+    rng = np.random.default_rng(60)
+    Hq, Hkv, d, S = 8, 2, 128, 5000
+    dflag = (rng.random((Hq, S)) < 0.01).astype(np.uint8)
+    vflag = (rng.random((Hq, S)) < 0.01).astype(np.uint8)
+    for h in range(Hq):
+        dflag[h, :100 + 50 * h] = 1
+    art = oracle.from_patterns(dflag, vflag)
+    p = S - 1
+    mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=S, diag_in=torch.from_numpy(dflag).cuda(),
+                        vert_in=torch.from_numpy(vflag).cuda(), blocks=False, rows=(p, p + 1), group=Hq // Hkv)
+    Q = wl.to_storage(rng.standard_normal((Hq, d)).astype(np.float32), "bf16")
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    O, _ = oracle.attend_rows(Q, K, V, art, Hq, np.arange(Hq, dtype=np.int32), np.full(Hq, p, np.int64))
+    out = B.dam_sparse_attn_decode_grouped(dev(Q, "bf16")[None], dev(K, "bf16")[None], dev(V, "bf16")[None],
+                                           mask.kept_ptr, mask.kept_idx, mask.kept_member, S)
+    torch.cuda.synchronize()
+    assert np.abs(out[0].float().cpu().numpy() - O).max() <= TOL["bf16"]
