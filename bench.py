@@ -303,7 +303,29 @@ def bench_decode(args, torch, B, wl):
              "roofline": {"bound": "hbm", "achieved": compact_bytes / (compact_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
                           "unit": "GB/s", "frac": compact_bytes / (compact_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
     del kcmp, vcmp
-    return {"workload": "c5", "steps": steps, "kv_eviction": evict, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
+
+    # grouped-query form at the same position: one merged list per KV head, every cached row read once per group
+    G = w.hq // w.hkv
+    pg = B.MaskParams(B.DAM_FROM_PATTERNS, items, 0, cap, 128, 128, pos0, pos0 + 1, 0.5, 1e-8, 0.3, 0.8, float("nan"),
+                      B.DAM_MASK_GROUP_LISTS, 0, G)
+    ws_g = B.mask_workspace(pg, dev)
+    g_ptr = torch.empty(w.hkv + 1, dtype=torch.int32, device=dev)
+    g_idx = torch.empty(items * max_kept, dtype=torch.int32, device=dev)
+    g_mem = torch.empty(items * max_kept, dtype=torch.uint8, device=dev)
+    og = B.MaskOut()
+    og.kept_ptr, og.kept_idx, og.kept_member, og.kept_capacity, og.kept_total = (g_ptr.data_ptr(), g_idx.data_ptr(), g_mem.data_ptr(),
+                                                                                 g_idx.numel(), total.data_ptr())
+    g_list_us = timed(lambda: B.dam_mask_build(pg, None, None, d_in, v_in, og, ws_g), 50)
+    g_max = int((g_ptr[1:] - g_ptr[:-1]).max().item())
+    g_rows = int(g_ptr[-1].item())
+    ws_gd = B.decode_grouped_workspace(dp, g_max, dev)
+    g_dec_us = timed(lambda: B.dam_sparse_attn_decode_grouped(qs[0], kc, vc, g_ptr, g_idx, g_mem, g_max, out=out, ws=ws_gd,
+                                                              shared_lists=True), 50)
+    g_bytes = g_rows * w.batch * w.head_dim * 2 * 2
+    grouped = {"list_entries": g_rows, "list_build_us": g_list_us, "decode_us": g_dec_us, "bytes": g_bytes,
+               "roofline": {"bound": "hbm", "achieved": g_bytes / (g_dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": g_bytes / (g_dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
+    return {"workload": "c5", "steps": steps, "kv_eviction": evict, "grouped_query_form": grouped, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
             "decode_us": dec_us, "kept_per_list": sb / (w.batch * items * w.head_dim * 4), "union_bytes": ub, "sum_bytes": sb,
             "gbs_union": ub / (dec_us * 1e-6) / 1e9, "gbs_sum": sb / (dec_us * 1e-6) / 1e9,
             "roofline": {"bound": "hbm", "achieved": ub / (dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",

@@ -235,11 +235,10 @@ __global__ __launch_bounds__(256) void k_decode_group(DecodeArgs a, const T *__r
   const int b = pair / a.Hkv, hkv = pair % a.Hkv;
   const int group = threadIdx.x / LPR, sub = threadIdx.x % LPR;
   const int list = a.shared_lists ? hkv : pair;
-  const int64_t lo = kept_ptr[list], hi = kept_ptr[list + 1];
-  const int64_t len = hi - lo;
-  const int64_t chunk = (len + a.splits - 1) / a.splits;
-  const int64_t beg = lo + (int64_t)split * chunk;
-  const int64_t end = std::min<int64_t>(hi, beg + chunk);
+  // the splits take the list's blocks of GROUPS * kUnroll entries in turn, so that each gets its share of
+  // every run (the run kept by several heads costs several times the arithmetic of the others)
+  const int64_t end = kept_ptr[list + 1];
+  const int64_t stride = (int64_t)a.splits * GROUPS * kUnroll;
 
   uint4 qf[GM];
 #pragma unroll
@@ -261,14 +260,14 @@ __global__ __launch_bounds__(256) void k_decode_group(DecodeArgs a, const T *__r
 
   int rows[kUnroll];
   unsigned who[kUnroll];  // member bits; 0 past the end of the stretch
-  int64_t p0 = beg + group * kUnroll;
+  int64_t p0 = kept_ptr[list] + ((int64_t)split * GROUPS + group) * kUnroll;
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const bool ok = p0 + u < end;
     rows[u] = p0 < end ? kept_idx[ok ? p0 + u : p0] : 0;
     who[u] = ok ? kept_member[p0 + u] : 0u;
   }
-  for (; p0 < end; p0 += GROUPS * kUnroll) {
+  for (; p0 < end; p0 += stride) {
     uint4 kf[kUnroll], vf[kUnroll];
     unsigned cur[kUnroll], anyone = 0;
 #pragma unroll
@@ -278,7 +277,7 @@ __global__ __launch_bounds__(256) void k_decode_group(DecodeArgs a, const T *__r
       cur[u] = who[u];
       anyone |= who[u];
     }
-    const int64_t pn = p0 + GROUPS * kUnroll;
+    const int64_t pn = p0 + stride;
     if (pn < end) {
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {

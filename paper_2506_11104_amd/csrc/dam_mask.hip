@@ -1274,25 +1274,34 @@ __global__ __launch_bounds__(256) void k_row_fill(Geom g, const uint64_t *__rest
 // Kept lists of one row for grouped-query decoding (DAM_MASK_GROUP_LISTS): one list per group of G
 // consecutive maps, holding each key some map of the group keeps once, in G + 1 runs (kept by two or
 // more maps; by map 0 alone; by map 1 alone; ...), each ascending, with a byte of member bits per
-// entry. A wave owns a chunk of 64 mask words (4096 keys) of one group; the count kernel writes the
-// G + 1 run sizes of every chunk, the fill kernel derives its write positions from them.
+// entry. A lane owns kPieceBits consecutive keys, a wave a chunk of 64 such pieces; the work is spread
+// thin on purpose: the lists are short, so the time is the latency of the longest chain of dependent
+// steps in one wave (its fullest piece), not throughput. Count per (group, run, chunk), exclusive
+// scan in that order (which is the order of the output), fill.
 constexpr int kMaxGroup = 8;
+constexpr int kPieceBits = 8;
+constexpr int kPiecesPerWord = 64 / kPieceBits;
+constexpr int kChunkWords = 64 / kPiecesPerWord;  // mask words per wave
 
-// Word w of row i for the maps of group kv (m[x], zero for x >= G and beyond the row), and the bits
-// set in at least two of them.
-__device__ __forceinline__ void group_words(const Geom &g, const uint64_t *__restrict__ true_bits,
-                                            const uint64_t *__restrict__ cbits, const uint64_t *__restrict__ rrev,
-                                            int kv, int G, int i, int w, uint64_t (&m)[kMaxGroup],
-                                            uint64_t &shared) {
-  uint64_t any = 0;
+// This lane's piece of row i for the maps of group kv (m[x], zero for x >= G and beyond the row), and
+// the bits set in at least two of them. Lane l: piece l % kPiecesPerWord of word chunk * kChunkWords +
+// l / kPiecesPerWord.
+__device__ __forceinline__ void group_pieces(const Geom &g, const uint64_t *__restrict__ true_bits,
+                                             const uint64_t *__restrict__ cbits, const uint64_t *__restrict__ rrev,
+                                             int kv, int G, int i, int chunk, int lane, unsigned (&m)[kMaxGroup],
+                                             unsigned &shared) {
+  const int w = chunk * kChunkWords + lane / kPiecesPerWord;
+  const int shift = (lane % kPiecesPerWord) * kPieceBits;
+  unsigned any = 0;
   shared = 0;
 #pragma unroll
   for (int x = 0; x < kMaxGroup; ++x) {
     m[x] = 0;
     if (x < G && w <= (i >> 6)) {
       const int h = kv * G + x;
-      m[x] = mask_word(g, true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr, cbits + (int64_t)h * g.pw,
-                       rrev + (int64_t)h * g.pw, i, w);
+      const uint64_t word = mask_word(g, true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr,
+                                      cbits + (int64_t)h * g.pw, rrev + (int64_t)h * g.pw, i, w);
+      m[x] = (unsigned)(word >> shift) & ((1u << kPieceBits) - 1);
     }
     shared |= any & m[x];
     any |= m[x];
@@ -1304,101 +1313,69 @@ __device__ __forceinline__ int wave_total(int v) {
   return v;
 }
 
-__device__ __forceinline__ uint64_t read_lane64(uint64_t v, int src) {  // src wave-uniform
-  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, src);
-  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), src);
-  return ((uint64_t)hi << 32) | lo;
-}
-
-// cnt[(kv * nchunks + chunk) * (G + 1) + run]
+// cnt[(kv * (G + 1) + run) * nchunks + chunk]
 __global__ __launch_bounds__(256) void k_group_count(Geom g, const uint64_t *__restrict__ true_bits,
                                                      const uint64_t *__restrict__ cbits,
                                                      const uint64_t *__restrict__ rrev, int row, int G,
                                                      int nchunks, int *__restrict__ cnt) {
   const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), kv = blockIdx.y;
   if (chunk >= nchunks) return;  // whole waves
-  uint64_t m[kMaxGroup], shared;
-  group_words(g, true_bits, cbits, rrev, kv, G, row, chunk * 64 + lane, m, shared);
-  int *out = cnt + ((int64_t)kv * nchunks + chunk) * (G + 1);
-  const int c0 = wave_total(__popcll(shared));
+  unsigned m[kMaxGroup], shared;
+  group_pieces(g, true_bits, cbits, rrev, kv, G, row, chunk, lane, m, shared);
+  int *out = cnt + (int64_t)kv * (G + 1) * nchunks + chunk;
+  const int c0 = wave_total(__popc(shared));
   if (lane == 0) out[0] = c0;
 #pragma unroll
   for (int x = 0; x < kMaxGroup; ++x) {
     if (x < G) {
-      const int c = wave_total(__popcll(m[x] & ~shared));
-      if (lane == 0) out[1 + x] = c;
+      const int c = wave_total(__popc(m[x] & ~shared));
+      if (lane == 0) out[(int64_t)(1 + x) * nchunks] = c;
     }
   }
 }
 
+// first[e]: exclusive scan of cnt (n_groups * (G + 1) * nchunks + 1 entries)
 __global__ __launch_bounds__(256) void k_group_fill(Geom g, const uint64_t *__restrict__ true_bits,
                                                     const uint64_t *__restrict__ cbits,
                                                     const uint64_t *__restrict__ rrev, int row, int G,
-                                                    int nchunks, int n_groups, const int *__restrict__ cnt,
+                                                    int nchunks, int n_groups, const int *__restrict__ first,
                                                     int *__restrict__ kept_ptr, int *__restrict__ kept_idx,
-                                                    uint8_t *__restrict__ kept_member, int64_t capacity,
-                                                    int64_t *__restrict__ kept_total) {
+                                                    uint8_t *__restrict__ kept_member, int64_t capacity) {
   const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), kv = blockIdx.y;
   if (chunk >= nchunks) return;  // whole waves
-  // entries written before this wave's, per run: all of the groups before, the runs before of this
-  // group, the chunks before of the same run
-  const int per_group = nchunks * (G + 1);
-  int all = 0, before_group = 0, before_run[kMaxGroup + 1];
-#pragma unroll
-  for (int r = 0; r <= kMaxGroup; ++r) before_run[r] = 0;
-  for (int e = lane; e < n_groups * per_group; e += 64) {
-    const int c = cnt[e];
-    const int kv2 = e / per_group, rest = e % per_group, chunk2 = rest / (G + 1), run2 = rest % (G + 1);
-    all += c;
-    if (kv2 < kv) before_group += c;
-    if (kv2 == kv) {
-#pragma unroll
-      for (int r = 0; r <= kMaxGroup; ++r)
-        if (run2 < r || (run2 == r && chunk2 < chunk)) before_run[r] += c;
-    }
-  }
-  all = wave_total(all);
-  before_group = wave_total(before_group);
+  const int *mine_first = first + (int64_t)kv * (G + 1) * nchunks + chunk;
   if (chunk == 0 && lane == 0) {
-    kept_ptr[kv] = before_group;
-    if (kv == n_groups - 1) {
-      kept_ptr[n_groups] = all;
-      if (kept_total) *kept_total = all;
-    }
+    kept_ptr[kv] = mine_first[0];
+    if (kv == n_groups - 1) kept_ptr[n_groups] = first[(int64_t)n_groups * (G + 1) * nchunks];
   }
   if (!kept_idx) return;
-  uint64_t m[kMaxGroup], shared;
-  group_words(g, true_bits, cbits, rrev, kv, G, row, chunk * 64 + lane, m, shared);
-  const uint64_t below = (1ull << lane) - 1;
+  unsigned m[kMaxGroup], shared;
+  group_pieces(g, true_bits, cbits, rrev, kv, G, row, chunk, lane, m, shared);
+  const int key0 = (chunk * kChunkWords + lane / kPiecesPerWord) * 64 + (lane % kPiecesPerWord) * kPieceBits;
 #pragma unroll
   for (int r = 0; r <= kMaxGroup; ++r) {
     if (r <= G) {
-      const uint64_t mine = r == 0 ? shared : m[r - 1] & ~shared;  // lane's word of run r
-      const int v = __popcll(mine);
+      unsigned left = r == 0 ? shared : m[r - 1] & ~shared;  // lane's piece of run r
+      const int v = __popc(left);
       int incl = v;
       for (int off = 1; off < 64; off <<= 1) {
         const int up = __shfl_up(incl, off);
         if (lane >= off) incl += up;
       }
-      const int excl = incl - v;
-      const int64_t base = (int64_t)before_group + wave_total(before_run[r]);
-      for (int x = 0; x < 64; ++x) {
-        const uint64_t word = read_lane64(mine, x);
-        if (!word) continue;  // wave-uniform
-        const int first = __builtin_amdgcn_readlane(excl, x);
+      int64_t at = (int64_t)mine_first[(int64_t)r * nchunks] + incl - v;
+      while (left) {
+        const int bit = __ffs(left) - 1;
+        left &= left - 1;
         unsigned who = r == 0 ? 0u : 1u << (r - 1);
         if (r == 0) {
 #pragma unroll
-          for (int y = 0; y < kMaxGroup; ++y)
-            if (y < G) who |= (unsigned)((read_lane64(m[y], x) >> lane) & 1) << y;
+          for (int y = 0; y < kMaxGroup; ++y) who |= ((m[y] >> bit) & 1u) << y;  // m[y] = 0 for y >= G
         }
-        if ((word >> lane) & 1) {
-          const int64_t at = base + first + __popcll(word & below);
-          if (at < capacity) {
-            kept_idx[at] = (chunk * 64 + x) * 64 + lane;
-            kept_member[at] = (uint8_t)who;
-          }
+        if (at < capacity) {
+          kept_idx[at] = key0 + bit;
+          kept_member[at] = (uint8_t)who;
         }
+        ++at;
       }
     }
   }
@@ -1450,12 +1427,12 @@ struct Workspace {
   uint64_t *vslices, *dslices;
   uint8_t *diag_flag, *vert_flag;
   uint64_t *cbits, *rrev, *occ, *full, *col_any, *col_all, *off_any, *off_all, *vocc, *vfull;
-  int *tile_cnt, *row_cnt;
+  int *tile_cnt, *row_cnt, *group_first;
   size_t bytes;
 };
 
-// Chunks of 64 mask words (4096 keys) covering keys 0..row.
-int group_chunks(int row) { return ((row >> 6) + 1 + 63) / 64; }
+// Chunks of kChunkWords mask words covering keys 0..row (one wave each in the group-list kernels).
+int group_chunks(int row) { return ((row >> 6) + 1 + kChunkWords - 1) / kChunkWords; }
 
 Geom geometry(const dam_mask_params *p) {
   Geom g;
@@ -1504,9 +1481,13 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   w.tile_cnt = c.take<int>((size_t)g.H * g.nQt);
   const int nrows = p->row_end > p->row_begin ? p->row_end - p->row_begin : 0;
   size_t n_cnt = (size_t)g.H * (size_t)(nrows > 0 ? nrows : 1);
-  if ((p->flags & DAM_MASK_GROUP_LISTS) && p->group >= 1 && p->row_begin >= 0)  // run sizes per chunk of 64 words
-    n_cnt = std::max(n_cnt, (size_t)(g.H / p->group) * (size_t)group_chunks(p->row_begin) * (size_t)(p->group + 1));
+  size_t n_first = 1;
+  if ((p->flags & DAM_MASK_GROUP_LISTS) && p->group >= 1 && p->row_begin >= 0) {  // run sizes per chunk, and their scan
+    n_first = (size_t)(g.H / p->group) * (size_t)group_chunks(p->row_begin) * (size_t)(p->group + 1) + 1;
+    n_cnt = std::max(n_cnt, n_first);
+  }
   w.row_cnt = c.take<int>(n_cnt);
+  w.group_first = c.take<int>(n_first);
   w.bytes = c.off;
   return w;
 }
@@ -1603,9 +1584,10 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
       const int G = p->group, n_groups = g.H / G, nchunks = group_chunks(p->row_begin);
       const dim3 grid((nchunks + 3) / 4, n_groups);
       k_group_count<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, w.row_cnt);
-      k_group_fill<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, n_groups, w.row_cnt,
+      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)n_groups * (G + 1) * nchunks, 0, w.group_first, o->kept_total);
+      k_group_fill<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, n_groups, w.group_first,
                                              o->kept_ptr, o->kept_capacity > 0 ? o->kept_idx : nullptr, o->kept_member,
-                                             o->kept_capacity, o->kept_total);
+                                             o->kept_capacity);
     } else if (nrows > 0) {
       k_row_count<<<dim3(nrows, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, nrows, w.row_cnt);
       k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)g.H * nrows, 0, o->kept_ptr, o->kept_total);

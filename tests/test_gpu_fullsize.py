@@ -273,4 +273,17 @@ def test_c5_full_size_lists_and_decode():
         err = np.abs(got - O).max()
         assert err <= TOL_BF16, f"position {p}: max abs err {err}"
         assert np.abs(lse.cpu().numpy().reshape(-1) - LSE).max() <= TOL_BF16
-        say(f"c5: position {p}: {int(lens.sum())} kept keys per sequence, max abs err {err:.2e}")
+        # the grouped-query form in the launch configuration the bench times: merged lists per KV head, shared by the batch
+        mg = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False,
+                          rows=(p, p + 1), group=G)
+        torch.cuda.synchronize()
+        want = oracle.group_lists(lists, G)
+        assert np.array_equal(mg.kept_ptr.cpu().numpy().astype(np.int64), want[0])
+        assert np.array_equal(mg.kept_idx.cpu().numpy(), want[1]) and np.array_equal(mg.kept_member.cpu().numpy(), want[2])
+        out_g, lse_g = B.dam_sparse_attn_decode_grouped(qs[step].cuda(), kc_d, vc_d, mg.kept_ptr, mg.kept_idx, mg.kept_member,
+                                                        int(np.diff(want[0]).max()), want_lse=True, shared_lists=True)
+        torch.cuda.synchronize()
+        err_g = np.abs(out_g.float().cpu().numpy().reshape(w.batch * w.hq, w.head_dim) - O).max()
+        assert err_g <= TOL_BF16, f"position {p}, grouped: max abs err {err_g}"
+        assert np.abs(lse_g.cpu().numpy().reshape(-1) - LSE).max() <= TOL_BF16
+        say(f"c5: position {p}: {int(lens.sum())} kept keys per sequence, max abs err {err:.2e} (grouped {err_g:.2e})")
