@@ -65,6 +65,15 @@ def test_mask_build_argument_errors():
     o.true_bits, o.kept_ptr, o.kept_total = 4096, 4096, 4096
     assert call_mask(mask_params(row_begin=5, row_end=3), out=o) == B.DAM_ERR_INVALID_ARG
     assert call_mask(mask_params(row_begin=0, row_end=257), out=o) == B.DAM_ERR_INVALID_ARG
+    # merged lists for grouped-query decoding: group size, one row only, member bytes beside the indices
+    GL = B.DAM_MASK_GROUP_LISTS
+    assert call_mask(mask_params(flags=GL, group=0, row_begin=3, row_end=4), out=o) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(flags=GL, group=9, row_begin=3, row_end=4), out=o) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(flags=GL, group=2, row_begin=3, row_end=5), out=o) == B.DAM_ERR_UNSUPPORTED
+    assert call_mask(mask_params(flags=GL, group=2, n_maps=3, row_begin=3, row_end=4), out=o) == B.DAM_ERR_INVALID_ARG
+    o.kept_idx, o.kept_capacity = 4096, 10
+    assert call_mask(mask_params(flags=GL, group=2, n_maps=4, row_begin=3, row_end=4), out=o) == B.DAM_ERR_INVALID_ARG
+    assert call_mask(mask_params(flags=8)) == B.DAM_ERR_INVALID_ARG
     assert L.dam_mask_build_workspace(ctypes.byref(mask_params())) > 0
     assert L.dam_mask_build_workspace(ctypes.byref(mask_params(seq=0))) == 0
 
@@ -119,6 +128,17 @@ def test_decode_argument_errors():
     assert call(p) == B.DAM_ERR_INVALID_ARG
     p.hq = 4
     assert L.dam_sparse_attn_decode_workspace(ctypes.byref(p), 4000) > 0
+
+    def grouped(pp, member=4096, max_kept=100, ws_bytes=1 << 30):
+        return L.dam_sparse_attn_decode_grouped(ctypes.byref(pp), 4096, 4096, 4096, 4096, 4096, member, max_kept, 4096, None,
+                                                4096, ws_bytes, None)
+
+    assert grouped(p, member=None) == B.DAM_ERR_INVALID_ARG
+    assert grouped(p, ws_bytes=8) == B.DAM_ERR_WORKSPACE
+    p.hq, p.hkv = 18, 2
+    assert grouped(p) == B.DAM_ERR_UNSUPPORTED          # nine heads per KV head: the member bits are a byte
+    p.hq, p.hkv = 4, 2
+    assert L.dam_sparse_attn_decode_grouped_workspace(ctypes.byref(p), 4000) > 0
 
 
 def capture_params(**kw):
