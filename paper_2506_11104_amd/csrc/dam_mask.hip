@@ -1038,10 +1038,13 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
-  stage_sets(lds_sets, staged, g.pw, cb, rr);
   const uint64_t *oc = occ + ((int64_t)h * g.nQt + qt) * g.occw;
   const uint64_t *fl = full + ((int64_t)h * g.nQt + qt) * g.occw;
+  // the walk below is a chain of dependent steps: its index words are fetched one word of 64 tiles ahead,
+  // the first ones before the sets are staged, so that no step of the chain waits for memory alone
   const int64_t first = row_ptr[(int64_t)h * (g.nQt + 1) + qt];
+  uint64_t ow_next = oc[0], fw_next = fl[0];
+  stage_sets(lds_sets, staged, g.pw, cb, rr);
   const int i_last = min(g.S - 1, qt * g.tile_m + g.tile_m - 1);
   const int kmax = i_last / g.tile_n;
   const int words = g.tile_m * g.wpr;
@@ -1052,7 +1055,12 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   // walk the listed tiles of this query tile in ascending order; wave w takes every fourth one
   int rank = 0;
   for (int ow_i = 0; ow_i <= (kmax >> 6); ++ow_i) {
-    uint64_t ow = oc[ow_i];
+    uint64_t ow = ow_next;
+    const uint64_t fw = fw_next;
+    if (ow_i + 1 <= (kmax >> 6)) {
+      ow_next = oc[ow_i + 1];
+      fw_next = fl[ow_i + 1];
+    }
     while (ow) {
       const int kt = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
       ow &= ow - 1;
@@ -1061,7 +1069,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       ++rank;
       if (!mine || t >= capacity) continue;
       // element words, and which key quarters of the tile hold a kept entry
-      const bool is_full = (fl[kt >> 6] >> (kt & 63)) & 1;
+      const bool is_full = (fw >> (kt & 63)) & 1;
       int quarters = 0;
       if (is_full && skip_full_bits) {  // wave-uniform: column and kind only
         if (lane == 0) {
@@ -1159,6 +1167,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int i0 = qt * g.tile_m;
   for (int ow_i = 0; ow_i * 64 < n_gt; ++ow_i) {
     uint64_t ow = voc[ow_i];
+    const uint64_t vfw = vfl[ow_i];
     while (ow) {
       const int v = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
       ow &= ow - 1;
@@ -1166,7 +1175,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       const bool mine = (rank & 3) == wave;
       ++rank;
       if (!mine || t >= capacity) continue;
-      const bool is_full = (vfl[v >> 6] >> (v & 63)) & 1;
+      const bool is_full = (vfw >> (v & 63)) & 1;
       int kind = is_full ? 1 : 0;
       for (int wg = 0; wg < g.wpr; ++wg) {
         const int slot = wg * 64 + lane;  // slot of this lane inside the tile
