@@ -70,6 +70,18 @@ def timed_ms(fn, n, warm=3):
     return ev[0].elapsed_time(ev[1]) / n
 
 
+def graph_replay_ms(fn, n):
+    """fn captured once into a HIP graph (the entry points allocate nothing and never synchronise), then the mean
+    duration of n replays: what a launch-bound sequence costs without the host's part."""
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    return timed_ms(g.replay, n)
+
+
 def bench_prefill(args, w, torch, B, wl):
     """Returns the result dict of the prefill workload (mask build + sparse prefill per step)."""
     dev = "cuda"
@@ -322,7 +334,14 @@ def bench_decode(args, torch, B, wl):
     g_dec_us = timed(lambda: B.dam_sparse_attn_decode_grouped(qs[0], kc, vc, g_ptr, g_idx, g_mem, g_max, out=out, ws=ws_gd,
                                                               shared_lists=True), 50)
     g_bytes = g_rows * w.batch * w.head_dim * 2 * 2
-    grouped = {"list_entries": g_rows, "list_build_us": g_list_us, "decode_us": g_dec_us, "bytes": g_bytes,
+    def grouped_step():
+        B.dam_mask_build(pg, None, None, d_in, v_in, og, ws_g)
+        B.dam_sparse_attn_decode_grouped(qs[0], kc, vc, g_ptr, g_idx, g_mem, g_max, out=out, ws=ws_gd, shared_lists=True)
+
+    g_step_us = timed(grouped_step, 50)
+    g_step_graph_us = graph_replay_ms(grouped_step, 50) * 1e3
+    grouped = {"list_entries": g_rows, "list_build_us": g_list_us, "decode_us": g_dec_us, "step_us": g_step_us,
+               "step_us_graph_replay": g_step_graph_us, "bytes": g_bytes,
                "roofline": {"bound": "hbm", "achieved": g_bytes / (g_dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                             "frac": g_bytes / (g_dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
     return {"workload": "c5", "steps": steps, "kv_eviction": evict, "grouped_query_form": grouped, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
@@ -357,7 +376,9 @@ def bench_mask_from_map(args, torch, B, wl, name):
     o.true_bits, o.diag_flag, o.vert_flag = tb.data_ptr(), fl[0].data_ptr(), fl[1].data_ptr()
     ms = timed(lambda: B.dam_mask_build(p, A, None, None, None, o, ws), 20)
     nbytes = 2 * H * L * (L + 1) + H * L * L // 8      # lower triangle of A once + true bits
-    res = {"workload": f"{name} map ({H} x {L} x {L} fp32) -> true mask + matched patterns", "ms": ms, "bytes": nbytes,
+    ms_graph = graph_replay_ms(lambda: B.dam_mask_build(p, A, None, None, None, o, ws), 20)
+    res = {"workload": f"{name} map ({H} x {L} x {L} fp32) -> true mask + matched patterns", "ms": ms, "ms_graph_replay": ms_graph,
+           "bytes": nbytes,
            "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
     # the same stage one fused with its capture (no map), and the capture alone summed into A and C
