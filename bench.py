@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-maskmap", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timings (profiler runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain device copies of 1 GiB (a kernel of known traffic, for scaling "
@@ -339,7 +340,7 @@ def bench_decode(args, torch, B, wl):
         B.dam_sparse_attn_decode_grouped(qs[0], kc, vc, g_ptr, g_idx, g_mem, g_max, out=out, ws=ws_gd, shared_lists=True)
 
     g_step_us = timed(grouped_step, 50)
-    g_step_graph_us = graph_replay_ms(grouped_step, 50) * 1e3
+    g_step_graph_us = None if args.no_graph else graph_replay_ms(grouped_step, 50) * 1e3
     grouped = {"list_entries": g_rows, "list_build_us": g_list_us, "decode_us": g_dec_us, "step_us": g_step_us,
                "step_us_graph_replay": g_step_graph_us, "bytes": g_bytes,
                "roofline": {"bound": "hbm", "achieved": g_bytes / (g_dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -376,7 +377,7 @@ def bench_mask_from_map(args, torch, B, wl, name):
     o.true_bits, o.diag_flag, o.vert_flag = tb.data_ptr(), fl[0].data_ptr(), fl[1].data_ptr()
     ms = timed(lambda: B.dam_mask_build(p, A, None, None, None, o, ws), 20)
     nbytes = 2 * H * L * (L + 1) + H * L * L // 8      # lower triangle of A once + true bits
-    ms_graph = graph_replay_ms(lambda: B.dam_mask_build(p, A, None, None, None, o, ws), 20)
+    ms_graph = None if args.no_graph else graph_replay_ms(lambda: B.dam_mask_build(p, A, None, None, None, o, ws), 20)
     res = {"workload": f"{name} map ({H} x {L} x {L} fp32) -> true mask + matched patterns", "ms": ms, "ms_graph_replay": ms_graph,
            "bytes": nbytes,
            "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
