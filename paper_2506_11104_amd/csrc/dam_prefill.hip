@@ -18,6 +18,8 @@
 //     move through two LDS rings of four slots filled by load-to-LDS instructions (no registers in
 //     between), three blocks ahead of their use; one barrier per block. Within a wave the products
 //     of three consecutive blocks are interleaved with the softmax arithmetic (see the kernel).
+//     The blocks of a query tile are listed in LDS first (its tiles expanded 128 at a time by the whole
+//     workgroup), so that an iteration reads one descriptor instead of walking tiles in scalar code.
 //   Tiles not in the block index are never touched, key quarters of a tile without a kept entry are
 //     never loaded, and full tiles skip the element mask.
 // fp32 kernel (the 1e-4 variant): plain ALU code, one query row per group of head_dim/4 lanes,
@@ -197,7 +199,10 @@ constexpr int kBlkBytes = kBlkKeys * 256;
 constexpr int kRing = 4;
 constexpr int kVRing = kRing * kBlkBytes;  // byte offset of the V ring; K ring at 0
 constexpr int kBitsRing = 2 * kRing * kBlkBytes;  // mask words: 4 slots x 4 waves x 64 lanes x 4 B
-constexpr int kPipeLds = kBitsRing + kRing * 1024;
+constexpr int kBlkList = kBitsRing + kRing * 1024;  // the block list of the current segment of tiles
+constexpr int kSegTiles = 128;                      // listed tiles expanded into the list at a time
+constexpr int kListEntries = kSegTiles * 4 + 1;     // up to four blocks per tile, and the dummy that ends the list
+constexpr int kPipeLds = kBlkList + kListEntries * 8;
 
 // Load-to-LDS copies as inline assembly: lane L of the wave fetches `bytes` bytes from gbase + voff
 // and writes them to LDS address m0 + L * bytes, m0 = lds_at + IMM. Written as assembly so that the
@@ -367,6 +372,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const __hip_bfloat16 *__restrict__ vgath) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int s_item[2];
+  __shared__ int s_wsum[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hf = lane >> 5;
@@ -433,39 +439,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const unsigned char *kgg = reinterpret_cast<const unsigned char *>(kgath) + g_rows * kss2;
     const unsigned char *vgg = reinterpret_cast<const unsigned char *>(vgath) + g_rows * vss2;
 
-    // ---- the stream of occupied 32-key blocks of this query tile (wave-uniform cursor). `quarters`
-    // holds the not yet visited occupied quarters of tile cur_t; the metadata of tile cur_t + 1 is
-    // fetched ahead (scalar loads, issued by prefetch_meta() just before an iteration's barrier so that
-    // their latency falls into the barrier wait and no LDS wait in the pipeline has to cover them).
-    int cur_t = t0 - 1, quarters = 0, cur_full = 0, cur_col = 0;
-    Blk last = {0, 0, 2};
-    unsigned pre_kinds = 0;  // the aligned word of blk_kind that holds tile cur_t + 1 (shifted when used, so
-    int pre_col = 0;         // that nothing waits for the load before the barrier)
-    auto prefetch_meta = [&]() {
-      if (quarters == 0 && cur_t + 1 < t1) {
-        pre_kinds = reinterpret_cast<const unsigned *>(blk_kind)[(cur_t + 1) >> 2];
-        pre_col = blk_col[cur_t + 1];
-      }
+    // ---- the stream of occupied 32-key blocks of this query tile. The listed tiles are expanded, kSegTiles at
+    // a time, into a list of block descriptors in LDS (two words: first key, and mask offset | flags << 28),
+    // closed by a dummy entry that every read past the end returns. The pipeline then reads one descriptor per
+    // iteration (fetched before the previous iteration's barrier, so that nothing waits for it) instead of
+    // walking tiles and quarters in scalar code, which cost a sixth of the instructions of an iteration.
+    uint2 *blk_list = reinterpret_cast<uint2 *>(lds + kBlkList);
+    int n_blk = 0;      // entries of the current list before the dummy
+    int cursor = 0;     // index of the descriptor held in pre_raw
+    uint2 pre_raw = make_uint2(0u, 2u << 28);
+    auto list_read = [&](int i) { return blk_list[min(i, n_blk)]; };  // the same address in every lane
+    auto decode = [&](const uint2 &raw) {
+      const int key0 = __builtin_amdgcn_readfirstlane((int)raw.x);
+      const unsigned meta = (unsigned)__builtin_amdgcn_readfirstlane((int)raw.y);
+      return Blk{key0, (int)(meta & 0x0FFFFFFFu), (int)(meta >> 28)};
     };
-    auto next_blk = [&]() {
-      if (quarters == 0) {
-        if (cur_t + 1 >= t1) return Blk{last.key0, last.bits_off, 2 | (last.flags & 4)};
-        ++cur_t;
-        const int pre_kind = (int)((pre_kinds >> (8 * (cur_t & 3))) & 0xFFu);
-        quarters = (pre_kind >> 1) & 15;  // never 0 for a listed tile
-        cur_full = pre_kind & 1;
-        cur_col = pre_col;
+    // tiles [seg0, seg0 + n_seg) -> list; called by the whole workgroup, ends with a barrier
+    auto expand = [&](int seg0, int n_seg) {
+      int quarters = 0, col = 0, full = 0;
+      if (tid < n_seg) {
+        const int kind = blk_kind[seg0 + tid];
+        col = blk_col[seg0 + tid];
+        quarters = (kind >> 1) & 15;
+        full = kind & 1;
       }
-      const int qq = __builtin_ctz(quarters);
-      quarters &= quarters - 1;
-      if (GATHER && cur_col >= a.nKt) {  // gathered tile: rows of the head's gathered copy (flag 4)
-        const int key0 = min((cur_col - a.nKt) * kBN + kBlkKeys * qq, a.gather_rows - kBlkKeys);
-        last = Blk{key0, (cur_t - t0) * (kBM * 16) + 4 * qq, cur_full | 4};
-        return last;
+      const int cnt = __popc(quarters);
+      int incl = cnt;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
       }
-      const int key0 = cur_col * kBN + kBlkKeys * qq;
-      last = Blk{key0, (cur_t - t0) * (kBM * 16) + 4 * qq, cur_full};
-      return last;
+      if (lane == 63) s_wsum[wave] = incl;  // kSegTiles = 128: only waves 0 and 1 hold tiles
+      __syncthreads();
+      int at = incl - cnt + (wave == 1 ? s_wsum[0] : 0);
+      while (quarters) {
+        const int qq = __builtin_ctz(quarters);
+        quarters &= quarters - 1;
+        const bool gth = GATHER && col >= a.nKt;  // gathered tile: rows of the head's gathered copy (flag 4)
+        const int key0 = gth ? min((col - a.nKt) * kBN + kBlkKeys * qq, a.gather_rows - kBlkKeys) : col * kBN + kBlkKeys * qq;
+        const unsigned off_bits = (unsigned)((seg0 + tid - t0) * (kBM * 16) + 4 * qq);
+        blk_list[at++] = make_uint2((unsigned)key0, off_bits | (unsigned)(full | (gth ? 4 : 0)) << 28);
+      }
+      const int total = s_wsum[0] + s_wsum[1];
+      if (tid == 0) blk_list[total] = make_uint2(0u, 2u << 28);  // dummy: key 0, the item's first mask words, nothing kept
+      __syncthreads();
+      n_blk = __builtin_amdgcn_readfirstlane(total);
     };
     // K or V block -> ring slot: two 1 KiB copies per wave; every address is the head's base plus a
     // 32-bit byte offset (the host checks that a head's rows span less than 4 GiB). In the ragged case
@@ -507,8 +525,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     // block i of the stream is described by d[i & 3]
     Blk d[4] = {};
-    prefetch_meta();
-    d[0] = next_blk();
     f32x16 oacc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -516,7 +532,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;  // running max (raw logits) and this lane's part of the row sum
 
-    if (!(d[0].flags & 2)) {
+    if (t1 > t0) {
       // Q fragments: B operand of S^T = K Q^T. Chunk c covers dims 16c .. 16c+15; this lane holds dims
       // 16c + 8 hf .. + 7 of its query row.
       bf16x8 qf[8];
@@ -529,58 +545,64 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           qf[c] = __builtin_bit_cast(bf16x8, raw);
         }
       }
-      prefetch_meta();
-      d[1] = next_blk();
-      prefetch_meta();
-      d[2] = next_blk();
-      prefetch_meta();
-      copy_k(d[0], I0{});
-      copy_bits(d[0], I0{});
-      copy_k(d[1], I1{});
-      copy_bits(d[1], I1{});
-      copy_k(d[2], I2{});
-      copy_bits(d[2], I2{});
-      copy_v(d[0], I0{});
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      // the Q fragments have arrived with that wait; passing them through an empty statement tells the
-      // compiler so (it cannot see the wait, and would otherwise wait for every copy in flight at the
-      // first use of a fragment in each iteration)
+      // one pass of the pipeline per segment of kSegTiles listed tiles (a query tile of c3 has at most 32;
+      // the accumulators, the softmax state and the Q fragments carry over)
+      for (int seg0 = t0; seg0 < t1; seg0 += kSegTiles) {
+        if (seg0 > t0) __syncthreads();  // every wave is done with the previous list and with the rings
+        expand(seg0, min(kSegTiles, t1 - seg0));
+        d[0] = decode(list_read(0));
+        d[1] = decode(list_read(1));
+        d[2] = decode(list_read(2));
+        cursor = 3;
+        pre_raw = list_read(cursor);
+        copy_k(d[0], I0{});
+        copy_bits(d[0], I0{});
+        copy_k(d[1], I1{});
+        copy_bits(d[1], I1{});
+        copy_k(d[2], I2{});
+        copy_bits(d[2], I2{});
+        copy_v(d[0], I0{});
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // the Q fragments have arrived with that wait; passing them through an empty statement tells the
+        // compiler so (it cannot see the wait, and would otherwise wait for every copy in flight at the
+        // first use of a fragment in each iteration)
 #pragma unroll
-      for (int c = 0; c < 8; ++c) asm volatile("" : "+v"(qf[c]));
-      __syncthreads();
-      // S_b lives in sbuf[PH & 1] and S_{b+1} is written to the other one; P_b goes to pbuf[PH & 1] and
-      // P_{b-1} is read from the other one, so nothing is copied between iterations
-      f32x16 sbuf[2];
-      unsigned pbuf[2][8];
+        for (int c = 0; c < 8; ++c) asm volatile("" : "+v"(qf[c]));
+        __syncthreads();
+        // S_b lives in sbuf[PH & 1] and S_{b+1} is written to the other one; P_b goes to pbuf[PH & 1] and
+        // P_{b-1} is read from the other one, so nothing is copied between iterations
+        f32x16 sbuf[2];
+        unsigned pbuf[2][8];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) sbuf[0][e] = -INFINITY;  // block -1 is a dummy
+        for (int e = 0; e < 16; ++e) sbuf[0][e] = -INFINITY;  // block -1 is a dummy
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pbuf[1][e] = 0u;
-      d[3].flags = 0;  // stands for block -1: the leading dummy must not end the loop
-      // iteration b with (b + 1) % 4 == PH; returns true when the stream is finished
-      auto step = [&](auto ph) {
-        constexpr int PH = decltype(ph)::value;
-        const int flag_cur = d[(PH + 3) & 3].flags;  // block b, whose descriptor is replaced now
-        d[(PH + 3) & 3] = next_blk();                // block b+4
-        copy_k(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});  // five copies per wave and iteration, always
-        copy_bits(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});
-        copy_v(d[(PH + 1) & 3], std::integral_constant<int, (PH + 1) & 3>{});  // block b+2
-        pipe_iter<PH>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], m_run,
-                      l_run, d[PH].flags, bits_addr, c2, kbase, vbase, hf);
-        if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
-        prefetch_meta();
-        // K_{b+2}, its mask words and V_b (issued two iterations ago) must have landed; the ten
-        // youngest copies (this iteration's and the previous one's) may stay in flight
-        // (wait and barrier as one statement: the library barrier would add a fence that waits for the
-        // metadata loads just issued; the LDS rings are only written by the copies counted here)
-        asm volatile("s_waitcnt vmcnt(10)\n\ts_barrier" ::: "memory");
-        return false;
-      };
-      while (true) {
-        if (step(I0{})) break;
-        if (step(I1{})) break;
-        if (step(I2{})) break;
-        if (step(I3{})) break;
+        for (int e = 0; e < 8; ++e) pbuf[1][e] = 0u;
+        d[3].flags = 0;  // stands for block -1: the leading dummy must not end the loop
+        // iteration b with (b + 1) % 4 == PH; returns true when the stream is finished
+        auto step = [&](auto ph) {
+          constexpr int PH = decltype(ph)::value;
+          const int flag_cur = d[(PH + 3) & 3].flags;  // block b, whose descriptor is replaced now
+          d[(PH + 3) & 3] = decode(pre_raw);           // block b+4
+          copy_k(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});  // five copies per wave and iteration, always
+          copy_bits(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});
+          copy_v(d[(PH + 1) & 3], std::integral_constant<int, (PH + 1) & 3>{});  // block b+2
+          pipe_iter<PH>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], m_run,
+                        l_run, d[PH].flags, bits_addr, c2, kbase, vbase, hf);
+          if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
+          pre_raw = list_read(++cursor);      // block b+5, decoded at the start of the next iteration
+          // K_{b+2}, its mask words and V_b (issued two iterations ago) must have landed; the ten
+          // youngest copies (this iteration's and the previous one's) may stay in flight
+          // (wait and barrier as one statement: the library barrier would add a fence that waits for
+          // everything in flight; the LDS rings are only written by the copies counted here)
+          asm volatile("s_waitcnt vmcnt(10)\n\ts_barrier" ::: "memory");
+          return false;
+        };
+        while (true) {
+          if (step(I0{})) break;
+          if (step(I1{})) break;
+          if (step(I2{})) break;
+          if (step(I3{})) break;
+        }
       }
     }
 

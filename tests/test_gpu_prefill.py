@@ -203,3 +203,30 @@ def test_c3_full_size_sampled_rows():
     hs = rng.integers(0, w.hq, n).astype(np.int32)
     rs = np.concatenate([rng.integers(0, w.seq, n - 256), np.arange(w.seq - 128, w.seq), np.arange(128)]).astype(np.int64)
     compare(Q, K, V, art, mask, "bf16", heads_rows=(hs, rs))
+
+
+@pytest.mark.parametrize("S,flags", [(128 * 300, 0), (128 * 131 - 37, B.DAM_MASK_GATHER_COLUMNS)])
+def test_query_tiles_with_more_listed_tiles_than_one_list_segment(S, flags):
+    """The bf16 kernel expands the listed tiles of a query tile 128 at a time. Head 0 is dense causal (up to
+    S / 128 tiles per query tile), head 1 keeps every fourth diagonal block and scattered columns (partial
+    tiles in every segment); rows around the segment boundaries and the last rows are checked."""
+    rng = np.random.default_rng(35)
+    Hq, Hkv, d = 2, 1, 128
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), "bf16")
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    dflag = np.ones((Hq, S), np.uint8)
+    dflag[1] = (np.arange(S) // 96) % 4 == 0
+    vflag = np.zeros((Hq, S), np.uint8)
+    vflag[1, rng.choice(S, 200, replace=False)] = 1
+    art = oracle.from_patterns(dflag, vflag)
+    mask = gpu_mask_from_art(art, S, 128, 128, flags=flags | B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    nQt = (S + 127) // 128
+    per_row = (mask.blk_row_ptr[:, 1:] - mask.blk_row_ptr[:, :-1]).cpu().numpy()
+    assert per_row.max() > 128        # at least two segments in the longest rows (three at S = 38400)
+    rows = np.unique(np.concatenate([np.arange(S - 130, S), 128 * 127 + np.arange(0, 260), 128 * 255 + np.arange(0, 260),
+                                     rng.integers(0, S, 200)]))
+    rows = rows[rows < S]
+    hs = np.concatenate([np.zeros(len(rows), np.int32), np.ones(len(rows), np.int32)])
+    rs = np.concatenate([rows, rows]).astype(np.int64)
+    compare(Q, K, V, art, mask, "bf16", heads_rows=(hs, rs))
