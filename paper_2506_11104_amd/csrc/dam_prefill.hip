@@ -233,9 +233,11 @@ struct Blk {
 // 0 or -inf for bit POS of `inv` clear or set
 template <int POS>
 __device__ __forceinline__ float neg_inf_if_bit(int inv) {
+  // (both instructions in one statement: after a statement of one instruction whose result is used at once
+  // the compiler pads with a no-op)
   int field;
-  asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(field) : "v"(inv), "n"(POS));
-  return __int_as_float(field & (int)0xFF800000);
+  asm("v_bfe_i32 %0, %1, %2, 1\n\tv_and_b32 %0, 0xff800000, %0" : "=&v"(field) : "v"(inv), "n"(POS));
+  return __int_as_float(field);
 }
 template <int... E>
 __device__ __forceinline__ void mask_init(f32x16 &s, int inv, std::integer_sequence<int, E...>) {
