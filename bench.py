@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # script with --copy-calibration, scaled by what the same counters read for a plain 1 GiB copy: x2.00 and x1.00);
 # the summary with the commands is profiles/prefill_c3_decode_c5_hbm_traffic_pmc.txt. They belong to the default
 # workloads (c3 prefill, c5 decode) and are reported as the roofline objects' `traffic`.
-MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.33e9, "k_decode_partial/c5": 5.33e8}
+MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.31e9, "k_decode_partial/c5": 5.25e8}
 
 
 def parse():
