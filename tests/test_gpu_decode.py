@@ -236,3 +236,32 @@ def test_grouped_decode_from_mask_build_matches_the_prefill_row():
                                            mask.kept_ptr, mask.kept_idx, mask.kept_member, S)
     torch.cuda.synchronize()
     assert np.abs(out[0].float().cpu().numpy() - O).max() <= TOL["bf16"]
+
+
+def test_group_lists_respect_the_capacity():
+    """kept_total and kept_ptr are right whatever the capacity; nothing is written at or past it."""
+    rng = np.random.default_rng(61)
+    H, G, S = 8, 4, 6000
+    dflag = (rng.random((H, S)) < 0.02).astype(np.uint8)
+    vflag = (rng.random((H, S)) < 0.02).astype(np.uint8)
+    dflag[:, :300] = 1
+    row = S - 1
+    art = oracle.from_patterns(dflag, vflag)
+    want = oracle.group_lists([oracle.kept_list(art, h, row) for h in range(H)], G)
+    n = int(want[0][-1])
+    cap = n // 2
+    p = B.MaskParams(B.DAM_FROM_PATTERNS, H, 0, S, 128, 128, row, row + 1, 0.5, 1e-8, 0.3, 0.8, float("nan"),
+                     B.DAM_MASK_GROUP_LISTS, 0, G)
+    ws = B.mask_workspace(p, "cuda")
+    ptr = torch.zeros(H // G + 1, dtype=torch.int32, device="cuda")
+    idx = torch.full((n + 64,), -7, dtype=torch.int32, device="cuda")
+    mem = torch.full((n + 64,), 0xEE, dtype=torch.uint8, device="cuda")
+    total = torch.zeros(1, dtype=torch.int64, device="cuda")
+    o = B.MaskOut()
+    o.kept_ptr, o.kept_idx, o.kept_member, o.kept_capacity, o.kept_total = ptr.data_ptr(), idx.data_ptr(), mem.data_ptr(), cap, total.data_ptr()
+    B.dam_mask_build(p, None, None, torch.from_numpy(dflag).cuda(), torch.from_numpy(vflag).cuda(), o, ws)
+    torch.cuda.synchronize()
+    assert int(total.item()) == n
+    assert np.array_equal(ptr.cpu().numpy().astype(np.int64), want[0])
+    assert np.array_equal(idx.cpu().numpy()[:cap], want[1][:cap]) and np.array_equal(mem.cpu().numpy()[:cap], want[2][:cap])
+    assert (idx[cap:] == -7).all() and (mem[cap:] == 0xEE).all()
