@@ -162,9 +162,7 @@ typedef struct {
  *                                       strictly below the diagonal and inside S). Bits 1..4: key
  *                                       quarter q of the tile, columns [q tile_n/4, (q+1) tile_n/4),
  *                                       holds a kept entry (bit 1 + q); the attention kernel skips
- *                                       empty quarters. The attention kernel reads this array in
- *                                       aligned 32-bit words: 4-byte aligned, and allocated up to a
- *                                       multiple of 4 bytes.
+ *                                       empty quarters.
  *   tile_bits  [blk_capacity][tile_m][tile_n / 64] u64   element bits of listed tile t at index t
  *                                       (also for full tiles: all ones, unless the flag
  *                                       DAM_MASK_SKIP_FULL_TILE_BITS is set); bits beyond S are 0.

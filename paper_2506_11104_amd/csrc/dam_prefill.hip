@@ -171,14 +171,6 @@ __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char *lds, int byte)
       (__attribute__((address_space(3))) s16x4 *)(const_cast<unsigned char *>(lds + byte)));
 }
 
-// blk_kind[t] for a wave-uniform t, fetched as part of its aligned 32-bit word so that it is a
-// scalar load: a byte load would go through the vector memory path and waiting for it would also
-// wait for every load-to-LDS copy in flight. (Device allocations are 4-byte granular.)
-__device__ __forceinline__ int kind_of(const uint8_t *__restrict__ blk_kind, int t) {
-  const unsigned word = reinterpret_cast<const unsigned *>(blk_kind)[t >> 2];
-  return (int)((word >> (8 * (t & 3))) & 0xFFu);
-}
-
 // Scheduling hints: instruction classes of __builtin_amdgcn_sched_group_barrier.
 #define DAM_SCHED_MFMA 0x008
 #define DAM_SCHED_DSREAD 0x100
