@@ -337,3 +337,33 @@ def test_gathered_column_tiles_from_a_map():
     check_gathered(art, w.seq, 128, 128, mask)
     plain = oracle.block_index(art, w.seq, 128, 128, want_bits=False)[1]
     assert mask.n_tiles < len(plain)
+
+
+def test_minimum_spans_the_layers_of_one_call_and_can_be_carried_between_calls():
+    """Sec. 4.2.2 takes the minimum over every layer and head. n_maps = layers x heads in one call does that;
+    a caller that builds layer by layer passes the global minimum of a first pass as bmin_override and gets the
+    same masks. Per-layer minima would give other masks."""
+    rng = np.random.default_rng(23)
+    layers, H, L, S = 2, 3, 160, 400
+    A1 = synth_map(rng, layers * H, L)
+    # counts: every pair of layer 0 was seen three times with a floor under its sums (its smallest mean stays
+    # well above eps), layer 1 has pairs never seen (mean 0 -> clamp eps): the global minimum comes from layer 1
+    # (the minimum runs over all L x L entries, also the never-computed ones above the diagonal, so layer 0 gets
+    # counts and a floor there too)
+    C = np.full((layers * H, L, L), 3.0, np.float32)
+    A = (A1 * 3.0 + 0.02).astype(np.float32)
+    C[H:, 100:, :40] = 0.0
+    A[H:, 100:, :40] = 0.0
+    tau = 0.1
+    art_all, m_all = run_from_map(A, C, S, 128, 128, 0.5, 1e-8, tau, 0.7, dense=False)
+    bmin = float(art_all.bmin)
+    own_min = []
+    for l in range(layers):
+        sl = slice(l * H, (l + 1) * H)
+        art_l, m_l = run_from_map(A[sl].copy(), C[sl].copy(), S, 128, 128, 0.5, 1e-8, tau, 0.7, dense=False, bmin_override=bmin)
+        assert torch.equal(m_l.true_bits, m_all.true_bits[sl])
+        assert torch.equal(m_l.diag_flag, m_all.diag_flag[sl]) and torch.equal(m_l.vert_flag, m_all.vert_flag[sl])
+        own_min.append(float(oracle.derive(A[sl].copy(), C[sl].copy(), 0.5, 1e-8, tau, 0.7).bmin))
+    assert min(own_min) == bmin and own_min[0] > bmin
+    alone = oracle.derive(A[:H].copy(), C[:H].copy(), 0.5, 1e-8, tau, 0.7)     # layer 0 with its own minimum
+    assert not np.array_equal(alone.true_mask, art_all.true_mask[:H])
