@@ -1401,7 +1401,7 @@ __global__ __launch_bounds__(256) void k_group_fill(Geom g, const uint64_t *__re
         }
         if (at < capacity) {
           kept_idx[at] = key0 + bit;
-          kept_member[at] = (uint8_t)who;
+          if (kept_member) kept_member[at] = (uint8_t)who;
         }
         ++at;
       }
@@ -1459,6 +1459,12 @@ struct Workspace {
   size_t bytes;
 };
 
+// Maps per list when a single row is listed: the group size with DAM_MASK_GROUP_LISTS, else 1 (a list per map is
+// the same thing with groups of one: no key is shared, the only run is "map 0 alone", ascending).
+int list_group(const dam_mask_params *p) {
+  return (p->flags & DAM_MASK_GROUP_LISTS) && p->group >= 1 && p->group <= kMaxGroup ? p->group : 1;
+}
+
 // Chunks of kChunkWords mask words covering keys 0..row (one wave each in the group-list kernels).
 int group_chunks(int row) { return ((row >> 6) + 1 + kChunkWords - 1) / kChunkWords; }
 
@@ -1510,8 +1516,9 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   const int nrows = p->row_end > p->row_begin ? p->row_end - p->row_begin : 0;
   size_t n_cnt = (size_t)g.H * (size_t)(nrows > 0 ? nrows : 1);
   size_t n_first = 1;
-  if ((p->flags & DAM_MASK_GROUP_LISTS) && p->group >= 1 && p->row_begin >= 0) {  // run sizes per chunk, and their scan
-    n_first = (size_t)(g.H / p->group) * (size_t)group_chunks(p->row_begin) * (size_t)(p->group + 1) + 1;
+  if (nrows == 1 && p->row_begin >= 0) {  // a single row goes through the group-list kernels: run sizes per chunk, and their scan
+    const int group = list_group(p);
+    n_first = (size_t)(g.H / group) * (size_t)group_chunks(p->row_begin) * (size_t)(group + 1) + 1;
     n_cnt = std::max(n_cnt, n_first);
   }
   w.row_cnt = c.take<int>(n_cnt);
@@ -1608,8 +1615,10 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
   }
   if (want_lists) {
     const int nrows = p->row_end - p->row_begin;
-    if (p->flags & DAM_MASK_GROUP_LISTS) {
-      const int G = p->group, n_groups = g.H / G, nchunks = group_chunks(p->row_begin);
+    if (nrows == 1) {
+      // one row (a decode step): the chunked kernels below, whose longest dependent chain is eight steps; lists per
+      // map are groups of one
+      const int G = list_group(p), n_groups = g.H / G, nchunks = group_chunks(p->row_begin);
       const dim3 grid((nchunks + 3) / 4, n_groups);
       k_group_count<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, w.row_cnt);
       k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)n_groups * (G + 1) * nchunks, 0, w.group_first, o->kept_total);
