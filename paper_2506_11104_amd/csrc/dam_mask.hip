@@ -786,18 +786,17 @@ __device__ __forceinline__ void stage_sets(uint64_t *lds_sets, bool staged, int 
 // A vertical stripe then costs its share of one dense tile per query tile instead of a whole tile.
 
 // The matched columns below S of one head, ascending, padded with -1 up to the stride. One workgroup per
-// head: its first wave walks the column bitset (the columns are few), then all waves write the padding.
+// head, a word of the column bitset per thread and pass.
 __global__ __launch_bounds__(1024) void k_gather_columns(Geom g, const uint64_t *__restrict__ cbits, int stride,
                                                          int *__restrict__ gidx, int *__restrict__ gcnt) {
-  __shared__ int s_count;
-  const int h = blockIdx.x, lane = threadIdx.x & 63;
+  __shared__ int s_wave[16];
+  const int h = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   int *out = gidx + (int64_t)h * stride;
   const int n_cols = min(g.P, g.S);
-  int base = 0;
-  if (threadIdx.x < 64)
-  for (int w0 = 0; w0 * 64 < n_cols; w0 += 64) {
-    const int w = w0 + lane;
+  int base = 0;  // the same value in every thread
+  for (int w0 = 0; w0 * 64 < n_cols; w0 += 1024) {  // a word of the column set per thread
+    const int w = w0 + threadIdx.x;
     uint64_t m = (w < g.pw && w * 64 < n_cols) ? cb[w] : 0;
     if (w * 64 + 64 > n_cols && w * 64 < n_cols) m &= ~0ull >> (64 - (n_cols - w * 64));
     const int v = __popcll(m);
@@ -806,19 +805,24 @@ __global__ __launch_bounds__(1024) void k_gather_columns(Geom g, const uint64_t 
       const int up = __shfl_up(incl, off);
       if (lane >= off) incl += up;
     }
-    int at = base + incl - v;
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int before = base, all = 0;
+    for (int x = 0; x < 16; ++x) {
+      const int t = s_wave[x];
+      if (x < wave) before += t;
+      all += t;
+    }
+    int at = before + incl - v;
     while (m) {
       out[at++] = w * 64 + __ffsll((unsigned long long)m) - 1;
       m &= m - 1;
     }
-    base += __shfl(incl, 63);
+    base += all;
+    __syncthreads();  // s_wave is rewritten in the next pass
   }
-  if (threadIdx.x == 0) {
-    s_count = base;
-    gcnt[h] = base;
-  }
-  __syncthreads();
-  for (int x = s_count + threadIdx.x; x < stride; x += blockDim.x) out[x] = -1;
+  if (threadIdx.x == 0) gcnt[h] = base;
+  for (int x = base + threadIdx.x; x < stride; x += blockDim.x) out[x] = -1;
 }
 
 // Transpose of the 64 x 64 bit matrix whose row l is the word x of lane l: lane r returns the word whose
@@ -1007,14 +1011,24 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__
       all += ws;
     }
     int64_t excl = before + incl - mine;
+    int64_t r = 0;
+    int q = 0;
 #pragma unroll
     for (int x = 0; x < kScanItems; ++x) {
       const int64_t e = e0 + x;
       if (e < n) {
         if (group > 0) {
-          const int64_t r = e / group, q = e % group;
+          // row and position of count e: divided once per thread and pass (x == 0), stepped after that
+          if (x == 0) {
+            r = e / group;
+            q = (int)(e - r * group);
+          }
           ptr[r * (group + 1) + q] = (int)excl;
           if (q == 0 && r > 0) ptr[(r - 1) * (group + 1) + group] = (int)excl;
+          if (++q == group) {
+            q = 0;
+            ++r;
+          }
         } else {
           ptr[e] = (int)excl;
         }
