@@ -416,7 +416,9 @@ int dam_kv_compact(const dam_evict_params *params, const int32_t *window, const 
 
 /* kept_slot[e] = row of key kept_idx[e] in its KV head's compacted cache, for the lists of
  * dam_sparse_attn_decode (kept_ptr device i32 [batch*hq + 1]); the order of a list is kept, so decode
- * from the compacted cache adds the same terms in the same order. */
+ * from the compacted cache adds the same terms in the same order. For the merged lists of
+ * dam_sparse_attn_decode_grouped (one per (sequence, KV head), kept_ptr [batch*hkv + 1]) pass params whose hq
+ * is set to hkv: a list then belongs to the KV head of its index. With lists shared by the batch, batch = 1. */
 int dam_kv_remap_lists(const dam_evict_params *params, const int32_t *window, const int32_t *col_ptr,
                        const int32_t *cols, const int32_t *kept_ptr, const int32_t *kept_idx,
                        int32_t *kept_slot, void *stream);

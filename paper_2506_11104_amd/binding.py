@@ -496,10 +496,14 @@ def kv_compact(plan: EvictionPlan, kcache: torch.Tensor, vcache: torch.Tensor, k
 
 
 def kv_remap_lists(plan: EvictionPlan, kept_ptr: torch.Tensor, kept_idx: torch.Tensor, batch: int,
-                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                   out: Optional[torch.Tensor] = None, per_kv_head: bool = False) -> torch.Tensor:
+    """per_kv_head: the lists are the merged ones of the grouped-query decode, one per (sequence, KV head)."""
     if out is None:
         out = torch.empty_like(kept_idx)
     p = plan.params
+    if per_kv_head:
+        p = EvictParams.from_buffer_copy(plan.params)
+        p.hq = p.hkv
     p.batch = batch
     st = lib().dam_kv_remap_lists(ctypes.byref(p), _p(plan.window), _p(plan.col_ptr), _p(plan.cols), _p(kept_ptr),
                                   _p(kept_idx), _p(out), _stream())

@@ -106,3 +106,49 @@ def test_c5_plan_at_full_size():
     torch.cuda.synchronize()
     check_plan(plan, oracle.eviction_plan(d, v, w.hkv, pos))
     assert int(plan.rows.max().item()) < w.seq // 4
+
+
+def test_grouped_decode_from_the_compacted_cache_is_identical_to_the_full_cache():
+    """Merged lists per KV head (dam_mask_build with DAM_MASK_GROUP_LISTS), remapped into the compacted cache
+    with the lists taken per KV head: the grouped decode gives the same bits from either cache, and the oracle's
+    attention over each head's own list within the bf16 bar."""
+    Bn, Hq, Hkv, d_head, T = 2, 8, 2, 128, 3000
+    cap = T + 1
+    G = Hq // Hkv
+    d, v = flags(6, Hq, cap, wide=True)
+    art = oracle.from_patterns(d, v)
+    g = torch.Generator().manual_seed(7)
+    kc = torch.randn((Bn, Hkv, cap, d_head), generator=g).to(torch.bfloat16).cuda()
+    vc = torch.randn((Bn, Hkv, cap, d_head), generator=g).to(torch.bfloat16).cuda()
+    q = torch.randn((Bn, Hq, d_head), generator=g).to(torch.bfloat16).cuda()
+    d_dev, v_dev = torch.from_numpy(d).cuda(), torch.from_numpy(v).cuda()
+    pos = T - 1
+    plan = B.kv_evict_plan(d_dev, v_dev, Hkv, pos, batch=Bn)
+    ccap = int(plan.rows.max().item())
+    kcmp = torch.zeros((Bn, Hkv, ccap, d_head), dtype=torch.bfloat16, device="cuda")
+    vcmp = torch.zeros_like(kcmp)
+    B.kv_compact(plan, kc, vc, kcmp, vcmp)
+    m = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=cap, diag_in=d_dev, vert_in=v_dev, blocks=False,
+                     rows=(pos, pos + 1), group=G)
+    slot = B.kv_remap_lists(plan, m.kept_ptr, m.kept_idx, 1, per_kv_head=True)
+    torch.cuda.synchronize()
+    want = oracle.eviction_plan(d, v, Hkv, pos)
+    ptr = m.kept_ptr.cpu().numpy()
+    idx = m.kept_idx.cpu().numpy()
+    want_slot = np.concatenate([[oracle.eviction_slot(want, gk, int(j)) for j in idx[ptr[gk]:ptr[gk + 1]]] for gk in range(Hkv)])
+    assert np.array_equal(slot.cpu().numpy(), want_slot)
+    longest = int(np.diff(ptr).max())
+    full, lse_f = B.dam_sparse_attn_decode_grouped(q, kc, vc, m.kept_ptr, m.kept_idx, m.kept_member, longest, want_lse=True,
+                                                   shared_lists=True)
+    comp, lse_c = B.dam_sparse_attn_decode_grouped(q, kcmp, vcmp, m.kept_ptr, slot, m.kept_member, longest, want_lse=True,
+                                                   shared_lists=True)
+    torch.cuda.synchronize()
+    assert torch.equal(full, comp) and torch.equal(lse_f, lse_c)
+    lists = [oracle.kept_list(art, h, pos) for h in range(Hq)]
+    lens = np.array([len(x) for x in lists])
+    kv_of = np.array([b * Hkv + h // G for b in range(Bn) for h in range(Hq)], np.int32)
+    O, _ = oracle.attend_lists(q.float().cpu().numpy().reshape(Bn * Hq, d_head), kc.float().cpu().numpy().reshape(Bn * Hkv, cap, d_head),
+                               vc.float().cpu().numpy().reshape(Bn * Hkv, cap, d_head), kv_of,
+                               np.concatenate([[0], np.cumsum(np.tile(lens, Bn))]).astype(np.int64),
+                               np.tile(np.concatenate(lists), Bn).astype(np.int32))
+    assert np.abs(comp.float().cpu().numpy().reshape(Bn * Hq, d_head) - O).max() <= 2e-2
