@@ -626,7 +626,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // [batch][hq][gather_rows] rows at the row stride of K (of V), so that a gathered tile is loaded like any other.
 __global__ __launch_bounds__(256) void k_gather_kv(AttnArgs a, const __hip_bfloat16 *__restrict__ k,
                                                    const __hip_bfloat16 *__restrict__ v, const int *__restrict__ gather_idx,
-                                                   __hip_bfloat16 *__restrict__ kgath, __hip_bfloat16 *__restrict__ vgath) {
+                                                   __hip_bfloat16 *__restrict__ kgath, __hip_bfloat16 *__restrict__ vgath,
+                                                   int *__restrict__ queue_next) {
+  // (also resets the work queues of the attention kernel that follows: one launch less per call)
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < kXcd) queue_next[threadIdx.x] = 0;
   const int bh = blockIdx.y, b = bh / a.Hq, hq = bh % a.Hq, hkv = hq / (a.Hq / a.Hkv);
   const int s = blockIdx.x * 16 + (threadIdx.x >> 4), chunk = threadIdx.x & 15;
   if (s >= a.gather_rows) return;
@@ -740,8 +743,9 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   if (a.gather_rows > 0)
     k_gather_kv<<<dim3((a.gather_rows + 15) / 16, p->batch * p->hq), 256, 0, st>>>(
         a, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->gather_idx,
-        kgath, vgath);
-  k_zero_queues<<<1, 64, 0, st>>>(queue_next);
+        kgath, vgath, queue_next);
+  else
+    k_zero_queues<<<1, 64, 0, st>>>(queue_next);
   const int persistent = std::min(blocks, 2 * n_cu);  // two workgroups fit a CU (registers and LDS)
   const bool ragged = p->seq % kBlkKeys != 0, gather = a.gather_rows > 0;
   using Kernel = void (*)(AttnArgs, const __hip_bfloat16 *, const __hip_bfloat16 *, const __hip_bfloat16 *, const int *,
