@@ -265,3 +265,41 @@ def test_group_lists_respect_the_capacity():
     assert np.array_equal(ptr.cpu().numpy().astype(np.int64), want[0])
     assert np.array_equal(idx.cpu().numpy()[:cap], want[1][:cap]) and np.array_equal(mem.cpu().numpy()[:cap], want[2][:cap])
     assert (idx[cap:] == -7).all() and (mem[cap:] == 0xEE).all()
+
+
+@pytest.mark.parametrize("grouped", [False, True])
+def test_strided_caches_and_queries_give_the_same_bits(grouped):
+    """Caches stored position-major ([B][cap][Hkv][d]) and q / out as slices of wider buffers: the same bits as
+    the contiguous layout."""
+    rng = np.random.default_rng(62)
+    Bn, Hq, Hkv, d, T = 3, 8, 2, 128, 2500
+    G = Hq // Hkv
+    lists = overlapping_lists(rng, Hq, T, np.array([900, 40, 0, 1500, 2500, 1, 700, 333]))
+    g = torch.Generator().manual_seed(9)
+    kc = torch.randn((Bn, Hkv, T, d), generator=g).to(torch.bfloat16).cuda()
+    vc = torch.randn((Bn, Hkv, T, d), generator=g).to(torch.bfloat16).cuda()
+    q = torch.randn((Bn, Hq, d), generator=g).to(torch.bfloat16).cuda()
+    if grouped:
+        gptr, gidx, gmem = oracle.group_lists(lists, G)
+        ptr, idx = torch.from_numpy(gptr.astype(np.int32)).cuda(), torch.from_numpy(gidx).cuda()
+        mem = torch.from_numpy(gmem).cuda()
+        longest = int(np.diff(gptr).max())
+        call = lambda q_, k_, v_, out=None: B.dam_sparse_attn_decode_grouped(q_, k_, v_, ptr, idx, mem, longest, out=out,
+                                                                              want_lse=True, shared_lists=True)
+    else:
+        lens = [len(x) for x in lists]
+        ptr = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+        idx = torch.from_numpy(np.concatenate(lists).astype(np.int32)).cuda()
+        call = lambda q_, k_, v_, out=None: B.dam_sparse_attn_decode(q_, k_, v_, ptr, idx, max(lens), out=out, want_lse=True,
+                                                                      shared_lists=True)
+    want, want_lse = call(q, kc, vc)
+    kc2 = kc.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    vc2 = vc.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    q_wide = torch.zeros((Bn, Hq, 2 * d), dtype=torch.bfloat16, device="cuda")
+    q_wide[..., :d] = q
+    o_wide = torch.full((Bn, Hq, d + 8), 5.0, dtype=torch.bfloat16, device="cuda")
+    assert not kc2.is_contiguous() and kc2.stride() == vc2.stride()
+    got, got_lse = call(q_wide[..., :d], kc2, vc2, out=o_wide[..., :d])
+    torch.cuda.synchronize()
+    assert torch.equal(got, want) and torch.equal(got_lse, want_lse)
+    assert (o_wide[..., d:] == 5.0).all()

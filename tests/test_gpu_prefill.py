@@ -230,3 +230,34 @@ def test_query_tiles_with_more_listed_tiles_than_one_list_segment(S, flags):
     hs = np.concatenate([np.zeros(len(rows), np.int32), np.ones(len(rows), np.int32)])
     rs = np.concatenate([rows, rows]).astype(np.int64)
     compare(Q, K, V, art, mask, "bf16", heads_rows=(hs, rs))
+
+
+@pytest.mark.parametrize("dtype,d,tile,S", [(torch.bfloat16, 128, 128, 700), (torch.bfloat16, 128, 128, 1024), (torch.float32, 64, 64, 333)])
+def test_strided_layouts_give_the_same_bits_as_contiguous_ones(dtype, d, tile, S):
+    """The entry point takes element strides: Q, K, V and O stored sequence-major ([B][S][H][d], the heads of a
+    token side by side) and as slices of wider buffers give the same output bits as contiguous [B][H][S][d]
+    tensors (whose parity with the oracle the other tests check). Gathered column tiles included: their copies
+    follow the row stride of K and of V."""
+    rng = np.random.default_rng(37)
+    Bn, Hq, Hkv = 2, 4, 2
+    art = random_patterns(rng, Hq, S, L=0)
+    art.vert_flag[0, rng.choice(S, size=150, replace=False)] = 1
+    mask = gpu_mask_from_art(art, S, tile, tile, flags=B.DAM_MASK_GATHER_COLUMNS if dtype == torch.bfloat16 else 0)
+    g = torch.Generator().manual_seed(8)
+    q = torch.randn((Bn, Hq, S, d), generator=g).to(dtype).cuda()
+    k = torch.randn((Bn, Hkv, S, d), generator=g).to(dtype).cuda()
+    v = torch.randn((Bn, Hkv, S, d), generator=g).to(dtype).cuda()
+    want, want_lse = B.dam_sparse_attn_prefill(q, k, v, mask, want_lse=True)
+    # sequence-major storage, K and V with different row strides (V padded), O into a slice of a wider buffer
+    q2 = q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    k2 = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    v_wide = torch.zeros((Bn, S, Hkv, 2 * d), dtype=dtype, device="cuda")
+    v_wide[..., :d] = v.permute(0, 2, 1, 3)
+    v2 = v_wide[..., :d].permute(0, 2, 1, 3)
+    o_wide = torch.full((Bn, Hq, S, d + 64), 3.0, dtype=dtype, device="cuda")
+    o2 = o_wide[..., :d]
+    assert not q2.is_contiguous() and k2.stride() != v2.stride() and not o2.is_contiguous()
+    got, got_lse = B.dam_sparse_attn_prefill(q2, k2, v2, mask, out=o2, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want) and torch.equal(got_lse, want_lse)
+    assert (o_wide[..., d:] == 3.0).all()          # nothing written outside the slice
