@@ -261,3 +261,22 @@ def test_strided_layouts_give_the_same_bits_as_contiguous_ones(dtype, d, tile, S
     torch.cuda.synchronize()
     assert torch.equal(got, want) and torch.equal(got_lse, want_lse)
     assert (o_wide[..., d:] == 3.0).all()          # nothing written outside the slice
+
+
+@pytest.mark.parametrize("S", [1, 5, 31, 33, 127, 129])
+def test_tiny_sequences_bf16(S):
+    """Sequences shorter than a key block, a tile, or just past one: the copies of a block that reaches past the
+    end are redirected to the last row, the rows past the end are never stored."""
+    rng = np.random.default_rng(38 + S)
+    Hq, Hkv, d = 2, 1, 128
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32), "bf16")
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    dflag = np.ones((Hq, S), np.uint8)                       # head 0: dense causal
+    dflag[1] = (np.arange(S) % 3 == 0)                       # head 1: every third diagonal
+    vflag = np.zeros((Hq, S), np.uint8)
+    vflag[1, 0] = 1
+    art = oracle.from_patterns(dflag, vflag)
+    for flags in (0, B.DAM_MASK_GATHER_COLUMNS):
+        mask = gpu_mask_from_art(art, S, 128, 128, flags=flags)
+        compare(Q, K, V, art, mask, "bf16")
