@@ -167,7 +167,7 @@ def test_from_patterns_with_and_without_true_mask():
         check_against_oracle(art, S, 128, 128, mask, rows=(S - 5, S))
 
 
-@pytest.mark.parametrize("tm,tn", [(64, 64), (128, 128), (64, 128), (128, 64)])
+@pytest.mark.parametrize("tm,tn", [(64, 64), (128, 128), (64, 128), (128, 64), (256, 256), (192, 64), (64, 256)])
 def test_full_and_nearly_full_tiles_from_pattern_mixtures(tm, tn):
     """Tiles that are full only through the union of diagonals and columns (every unmatched offset of
     the tile meets matched columns only), next to tiles that miss fullness by a single entry."""
@@ -192,7 +192,7 @@ def test_full_and_nearly_full_tiles_from_pattern_mixtures(tm, tn):
                         vert_in=torch.from_numpy(v).cuda(), dense=True)
     torch.cuda.synchronize()
     check_against_oracle(art, S, tm, tn, mask)
-    assert int((mask.blk_kind & 1).sum().item()) > 20
+    assert int((mask.blk_kind & 1).sum().item()) > (20 if tm * tn <= 128 * 128 else 3)
 
 
 def test_skip_full_tile_bits_leaves_full_tiles_untouched_and_the_rest_identical():
@@ -299,7 +299,7 @@ def check_gathered(art, S, tm, tn, mask, skip_full=False):
 
 
 @pytest.mark.parametrize("S,tm,tn,L", [(1000, 128, 128, 0), (1000, 128, 128, 100), (700, 64, 64, 64), (900, 128, 64, 0),
-                                        (600, 64, 128, 130)])
+                                        (600, 64, 128, 130), (1100, 256, 256, 0), (1100, 256, 128, 300), (900, 192, 192, 50)])
 def test_gathered_column_tiles_match_oracle(S, tm, tn, L):
     rng = np.random.default_rng(26)
     H = 5
