@@ -152,3 +152,35 @@ def test_grouped_decode_from_the_compacted_cache_is_identical_to_the_full_cache(
                                np.concatenate([[0], np.cumsum(np.tile(lens, Bn))]).astype(np.int64),
                                np.tile(np.concatenate(lists), Bn).astype(np.int32))
     assert np.abs(comp.float().cpu().numpy().reshape(Bn * Hq, d_head) - O).max() <= 2e-2
+
+
+def test_compaction_into_an_interleaved_cache():
+    """The compacted caches may share one buffer with the K and V row of a key side by side ([rows][2][d]): the
+    entry points take the two pointers and one set of strides. Rows are byte for byte those of the separate
+    layout, and decode from it gives the same bits."""
+    Bn, Hq, Hkv, d_head, T = 2, 4, 2, 128, 2000
+    d, v = flags(8, Hq, T, wide=True)
+    g = torch.Generator().manual_seed(10)
+    kc = torch.randn((Bn, Hkv, T, d_head), generator=g).to(torch.bfloat16).cuda()
+    vc = torch.randn((Bn, Hkv, T, d_head), generator=g).to(torch.bfloat16).cuda()
+    q = torch.randn((Bn, Hq, d_head), generator=g).to(torch.bfloat16).cuda()
+    d_dev, v_dev = torch.from_numpy(d).cuda(), torch.from_numpy(v).cuda()
+    pos = T - 1
+    plan = B.kv_evict_plan(d_dev, v_dev, Hkv, pos, batch=Bn)
+    ccap = int(plan.rows.max().item())
+    k_sep = torch.zeros((Bn, Hkv, ccap, d_head), dtype=torch.bfloat16, device="cuda")
+    v_sep = torch.zeros_like(k_sep)
+    B.kv_compact(plan, kc, vc, k_sep, v_sep)
+    both = torch.zeros((Bn, Hkv, ccap, 2, d_head), dtype=torch.bfloat16, device="cuda")
+    k_il, v_il = both[:, :, :, 0], both[:, :, :, 1]
+    B.kv_compact(plan, kc, vc, k_il, v_il)
+    torch.cuda.synchronize()
+    assert torch.equal(k_il, k_sep) and torch.equal(v_il, v_sep)
+    m = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=T, diag_in=d_dev, vert_in=v_dev, blocks=False, rows=(pos, pos + 1))
+    slot = B.kv_remap_lists(plan, m.kept_ptr, m.kept_idx, 1)
+    longest = int((m.kept_ptr[1:] - m.kept_ptr[:-1]).max().item())
+    a = B.dam_sparse_attn_decode(q, k_sep, v_sep, m.kept_ptr, slot, longest, shared_lists=True)
+    b = B.dam_sparse_attn_decode(q, k_il, v_il, m.kept_ptr, slot, longest, shared_lists=True)
+    c = B.dam_sparse_attn_decode(q, kc, vc, m.kept_ptr, m.kept_idx, longest, shared_lists=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
