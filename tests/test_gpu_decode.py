@@ -303,3 +303,31 @@ def test_strided_caches_and_queries_give_the_same_bits(grouped):
     torch.cuda.synchronize()
     assert torch.equal(got, want) and torch.equal(got_lse, want_lse)
     assert (o_wide[..., d:] == 5.0).all()
+
+
+def test_lists_of_a_row_a_million_keys_long():
+    """Row 1 048 675 of a mask given as patterns: the per-head lists and the merged lists equal the oracle's
+    (the list kernels spread such a row over two thousand waves)."""
+    rng = np.random.default_rng(63)
+    H, G, S = 4, 2, (1 << 20) + 100
+    dflag = np.zeros((H, S), np.uint8)
+    vflag = np.zeros((H, S), np.uint8)
+    for h in range(H):
+        dflag[h, :1000 * (h + 1)] = 1
+        dflag[h, rng.choice(S, 300, replace=False)] = 1
+        vflag[h, rng.choice(S, 500, replace=False)] = 1
+        vflag[h, :4] = 1
+    row = S - 1
+    art = oracle.from_patterns(dflag, vflag)
+    lists = [oracle.kept_list(art, h, row) for h in range(H)]
+    d_in, v_in = torch.from_numpy(dflag).cuda(), torch.from_numpy(vflag).cuda()
+    m = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=H, L=0, S=S, diag_in=d_in, vert_in=v_in, blocks=False, rows=(row, row + 1))
+    torch.cuda.synchronize()
+    ptr, idx = m.kept_ptr.cpu().numpy(), m.kept_idx.cpu().numpy()
+    for h in range(H):
+        assert np.array_equal(idx[ptr[h]:ptr[h + 1]], lists[h]), f"head {h}"
+    mg = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=H, L=0, S=S, diag_in=d_in, vert_in=v_in, blocks=False, rows=(row, row + 1), group=G)
+    torch.cuda.synchronize()
+    want = oracle.group_lists(lists, G)
+    assert np.array_equal(mg.kept_ptr.cpu().numpy().astype(np.int64), want[0])
+    assert np.array_equal(mg.kept_idx.cpu().numpy(), want[1]) and np.array_equal(mg.kept_member.cpu().numpy(), want[2])
