@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # script with --copy-calibration, scaled by what the same counters read for a plain 1 GiB copy: x2.00 and x1.00);
 # the summary with the commands is profiles/prefill_c3_decode_c5_hbm_traffic_pmc.txt. They belong to the default
 # workloads (c3 prefill, c5 decode) and are reported as the roofline objects' `traffic`.
-MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.31e9, "k_decode_partial/c5": 5.25e8}
+MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.31e9, "k_decode_group/c5": 5.13e8}
 
 
 def parse():
@@ -221,79 +221,95 @@ def bench_cpu_oracle(args, w, ctx, wl):
 
 
 def bench_decode(args, torch, B, wl):
+    """c5: a decode step = the kept lists of the new row (dam_mask_build, list form) + attention over them. The main
+    numbers are for the grouped-query form (one merged list per KV head, shared by the batch, every cached row read
+    once per group: the algorithmic bytes are exactly the rows it lists); the form with a list per head follows, and
+    the KV eviction at the first position."""
     w = wl.WORKLOADS["c5"]
     dev = "cuda"
     steps = args.decode_steps
     cap = w.seq + steps
+    G = w.hq // w.hkv
     g = torch.Generator(device=dev).manual_seed(w.seed)
     kc = torch.randn((w.batch, w.hkv, cap, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     vc = torch.randn((w.batch, w.hkv, cap, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     qs = torch.randn((steps, w.batch, w.hq, w.head_dim), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     dflag, vflag = wl.patterns_c5(wl.scaled(w, steps=steps))
     # every sequence of the batch sits at the same position, and a mask belongs to its head, not to an input:
-    # one kept list per head, shared by the batch (dam_decode_params.shared_lists)
+    # the lists are shared by the batch (dam_decode_params.shared_lists)
     d_in = torch.from_numpy(dflag).to(dev)
     v_in = torch.from_numpy(vflag).to(dev)
-    items = w.hq
-    max_kept = int((dflag.sum(1) + vflag.sum(1)).max())
-    kept_ptr = torch.empty(items + 1, dtype=torch.int32, device=dev)
-    kept_idx = torch.empty(items * max_kept, dtype=torch.int32, device=dev)
+    max_kept = int((dflag.sum(1) + vflag.sum(1)).max())          # bound of one head's list
+    max_group = min(G * max_kept, cap)                           # bound of a merged list
     total = torch.zeros(1, dtype=torch.int64, device=dev)
     out = torch.empty((w.batch, w.hq, w.head_dim), dtype=torch.bfloat16, device=dev)
     dp = B.decode_params(qs[0], kc, out, shared_lists=True)
-    ws_dec = B.decode_workspace(dp, max_kept, dev)
-    o = B.MaskOut()
-    o.kept_ptr, o.kept_idx, o.kept_capacity, o.kept_total = kept_ptr.data_ptr(), kept_idx.data_ptr(), kept_idx.numel(), total.data_ptr()
+    row_bytes = w.batch * w.head_dim * 2 * 2                     # a listed row: K and V, every sequence of the batch
 
-    def step(s, ev=None):
-        pos = w.seq - 1 + s
+    def params(pos, grouped):
         # rows of the mask do not depend on the problem length it is built for (the extension only
         # continues patterns), so the lists are taken from the length-`cap` mask the flags are sized for
-        p = B.MaskParams(B.DAM_FROM_PATTERNS, items, 0, cap, 128, 128, pos, pos + 1, 0.5, 1e-8, 0.3, 0.8, float("nan"))
-        if ev:
-            ev[0].record()
-        B.dam_mask_build(p, None, None, d_in, v_in, o, ws_mask)
-        if ev:
-            ev[1].record()
-        B.dam_sparse_attn_decode(qs[s], kc, vc, kept_ptr, kept_idx, max_kept, out=out, ws=ws_dec, shared_lists=True)
-        if ev:
-            ev[2].record()
+        return B.MaskParams(B.DAM_FROM_PATTERNS, w.hq, 0, cap, 128, 128, pos, pos + 1, 0.5, 1e-8, 0.3, 0.8, float("nan"),
+                            B.DAM_MASK_GROUP_LISTS if grouped else 0, 0, G if grouped else 0)
 
-    pmax = B.MaskParams(B.DAM_FROM_PATTERNS, items, 0, cap, 128, 128, cap - 1, cap, 0.5, 1e-8, 0.3, 0.8, float("nan"))
-    ws_mask = B.mask_workspace(pmax, dev)
-    for s in range(3):
-        step(s)
-    torch.cuda.synchronize()
+    def form(grouped, n_steps):
+        n_lists = w.hkv if grouped else w.hq
+        bound = max_group if grouped else max_kept
+        ptr = torch.empty(n_lists + 1, dtype=torch.int32, device=dev)
+        idx = torch.empty(n_lists * bound, dtype=torch.int32, device=dev)
+        mem = torch.empty(n_lists * bound, dtype=torch.uint8, device=dev) if grouped else None
+        o = B.MaskOut()
+        o.kept_ptr, o.kept_idx, o.kept_capacity, o.kept_total = ptr.data_ptr(), idx.data_ptr(), idx.numel(), total.data_ptr()
+        if grouped:
+            o.kept_member = mem.data_ptr()
+        ws_mask = B.mask_workspace(params(cap - 1, grouped), dev)
+        ws_dec = B.decode_grouped_workspace(dp, bound, dev) if grouped else B.decode_workspace(dp, bound, dev)
 
-    def union_bytes():
-        ptr = kept_ptr.cpu().numpy()
-        idx = kept_idx[:int(total.item())].cpu().numpy()
-        G = w.hq // w.hkv
-        rows = 0
-        for gk in range(w.hkv):
-            parts = [idx[ptr[gk * G + x]:ptr[gk * G + x + 1]] for x in range(G)]
-            rows += len(np.unique(np.concatenate(parts)))
-        return rows * w.batch * w.head_dim * 2 * 2, int(total.item()) * w.batch * w.head_dim * 2 * 2
+        def step(s, ev=None):
+            pos = w.seq - 1 + s
+            if ev:
+                ev[0].record()
+            B.dam_mask_build(params(pos, grouped), None, None, d_in, v_in, o, ws_mask)
+            if ev:
+                ev[1].record()
+            if grouped:
+                B.dam_sparse_attn_decode_grouped(qs[s], kc, vc, ptr, idx, mem, bound, out=out, ws=ws_dec, shared_lists=True)
+            else:
+                B.dam_sparse_attn_decode(qs[s], kc, vc, ptr, idx, bound, out=out, ws=ws_dec, shared_lists=True)
+            if ev:
+                ev[2].record()
 
-    evs = [events(3) for _ in range(steps)]
-    t0 = time.perf_counter()
-    for s in range(steps):
-        step(s, evs[s])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ub_last, sum_last = union_bytes()
-    step(0)
-    torch.cuda.synchronize()
-    ub_first, sum_first = union_bytes()
-    ub, sb = 0.5 * (ub_first + ub_last), 0.5 * (sum_first + sum_last)
-    list_us = float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e3
-    dec_us = float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e3
+        for s in range(3):
+            step(s)
+        torch.cuda.synchronize()
+        evs = [events(3) for _ in range(n_steps)]
+        t0 = time.perf_counter()
+        for s in range(n_steps):
+            step(s, evs[s])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        entries_last = int(total.item())
+        step(0)
+        torch.cuda.synchronize()
+        entries = 0.5 * (entries_last + int(total.item()))       # list entries per step, mean of first and last position
+        res = {"steps": n_steps, "us_per_step": wall * 1e6 / n_steps,
+               "list_build_us": float(np.mean([e[0].elapsed_time(e[1]) for e in evs])) * 1e3,
+               "decode_us": float(np.mean([e[1].elapsed_time(e[2]) for e in evs])) * 1e3, "list_entries": entries}
+        if not args.no_graph:
+            res["us_per_step_graph_replay"] = graph_replay_ms(lambda: step(0), 50) * 1e3
+        return res, (ptr, idx, bound)
+
+    main, _ = form(True, steps)
+    ub = main["list_entries"] * row_bytes                         # the union of the heads' kept rows: what must move
+    per_head, (kept_ptr, kept_idx, _) = form(False, min(steps, 64))
+    sb = per_head["list_entries"] * row_bytes                     # what moves without sharing between the heads of a group
+    per_head["gbs_union"] = ub / (per_head["decode_us"] * 1e-6) / 1e9
+    per_head["frac_of_hbm_peak"] = per_head["gbs_union"] / PEAK_HBM_GBS
 
     # KV eviction at the first timed position: plan, gather into the compacted cache, remap the lists, decode from it
     pos0 = w.seq - 1
-    dq, vq = torch.from_numpy(dflag).to(dev), torch.from_numpy(vflag).to(dev)
-    plan = B.kv_evict_plan(dq, vq, w.hkv, pos0, batch=w.batch)
-    plan_us = timed_ms(lambda: B.kv_evict_plan(dq, vq, w.hkv, pos0, batch=w.batch), 5, warm=1) * 1e3
+    plan = B.kv_evict_plan(d_in, v_in, w.hkv, pos0, batch=w.batch)
+    plan_us = timed_ms(lambda: B.kv_evict_plan(d_in, v_in, w.hkv, pos0, batch=w.batch), 5, warm=1) * 1e3
     ccap = int(plan.rows.max().item())
     kcmp = torch.empty((w.batch, w.hkv, ccap, w.head_dim), dtype=torch.bfloat16, device=dev)
     vcmp = torch.empty_like(kcmp)
@@ -312,45 +328,20 @@ def bench_decode(args, torch, B, wl):
                                                       shared_lists=True), 50)
     evict = {"rows_kept_per_kv_head": [int(x) for x in plan.rows.cpu()], "cache_rows": cap,
              "cache_bytes_ratio": ccap / cap, "plan_us_incl_two_host_syncs": plan_us, "compact_us": compact_us, "compact_bytes": compact_bytes,
-             "remap_us": remap_us, "decode_from_compacted_us": dec_c_us,
+             "remap_us": remap_us, "decode_from_compacted_us_list_per_head": dec_c_us,
              "roofline": {"bound": "hbm", "achieved": compact_bytes / (compact_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
                           "unit": "GB/s", "frac": compact_bytes / (compact_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
     del kcmp, vcmp
-
-    # grouped-query form at the same position: one merged list per KV head, every cached row read once per group
-    G = w.hq // w.hkv
-    pg = B.MaskParams(B.DAM_FROM_PATTERNS, items, 0, cap, 128, 128, pos0, pos0 + 1, 0.5, 1e-8, 0.3, 0.8, float("nan"),
-                      B.DAM_MASK_GROUP_LISTS, 0, G)
-    ws_g = B.mask_workspace(pg, dev)
-    g_ptr = torch.empty(w.hkv + 1, dtype=torch.int32, device=dev)
-    g_idx = torch.empty(items * max_kept, dtype=torch.int32, device=dev)
-    g_mem = torch.empty(items * max_kept, dtype=torch.uint8, device=dev)
-    og = B.MaskOut()
-    og.kept_ptr, og.kept_idx, og.kept_member, og.kept_capacity, og.kept_total = (g_ptr.data_ptr(), g_idx.data_ptr(), g_mem.data_ptr(),
-                                                                                 g_idx.numel(), total.data_ptr())
-    g_list_us = timed(lambda: B.dam_mask_build(pg, None, None, d_in, v_in, og, ws_g), 50)
-    g_max = int((g_ptr[1:] - g_ptr[:-1]).max().item())
-    g_rows = int(g_ptr[-1].item())
-    ws_gd = B.decode_grouped_workspace(dp, g_max, dev)
-    g_dec_us = timed(lambda: B.dam_sparse_attn_decode_grouped(qs[0], kc, vc, g_ptr, g_idx, g_mem, g_max, out=out, ws=ws_gd,
-                                                              shared_lists=True), 50)
-    g_bytes = g_rows * w.batch * w.head_dim * 2 * 2
-    def grouped_step():
-        B.dam_mask_build(pg, None, None, d_in, v_in, og, ws_g)
-        B.dam_sparse_attn_decode_grouped(qs[0], kc, vc, g_ptr, g_idx, g_mem, g_max, out=out, ws=ws_gd, shared_lists=True)
-
-    g_step_us = timed(grouped_step, 50)
-    g_step_graph_us = None if args.no_graph else graph_replay_ms(grouped_step, 50) * 1e3
-    grouped = {"list_entries": g_rows, "list_build_us": g_list_us, "decode_us": g_dec_us, "step_us": g_step_us,
-               "step_us_graph_replay": g_step_graph_us, "bytes": g_bytes,
-               "roofline": {"bound": "hbm", "achieved": g_bytes / (g_dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                            "frac": g_bytes / (g_dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
-    return {"workload": "c5", "steps": steps, "kv_eviction": evict, "grouped_query_form": grouped, "us_per_step": wall * 1e6 / steps, "list_build_us": list_us,
-            "decode_us": dec_us, "kept_per_list": sb / (w.batch * items * w.head_dim * 4), "union_bytes": ub, "sum_bytes": sb,
-            "gbs_union": ub / (dec_us * 1e-6) / 1e9, "gbs_sum": sb / (dec_us * 1e-6) / 1e9,
-            "roofline": {"bound": "hbm", "achieved": ub / (dec_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
-                         "traffic": MEASURED_TRAFFIC_BYTES["k_decode_partial/c5"]}}
+    dec_us = main["decode_us"]
+    res = {"workload": "c5, grouped-query form (one merged kept list per KV head, shared by the batch)"}
+    res.update(main)
+    res.update({"kept_per_head_list": sb / (w.hq * row_bytes), "union_bytes": ub, "sum_bytes": sb,
+                "gbs_union": ub / (dec_us * 1e-6) / 1e9,
+                "roofline": {"bound": "hbm", "kernel": "k_decode_group", "achieved": ub / (dec_us * 1e-6) / 1e9,
+                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                             "traffic": MEASURED_TRAFFIC_BYTES["k_decode_group/c5"]},
+                "list_per_head_form": per_head, "kv_eviction": evict})
+    return res
 
 
 def bench_mask_from_map(args, torch, B, wl, name):
