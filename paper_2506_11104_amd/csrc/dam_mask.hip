@@ -355,6 +355,12 @@ __global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A, 
 // row, 16-byte loads, the live 256-key segments of a 2048-key span in flight at once, and the row's
 // words gathered into lanes so that they leave as one coalesced store (single 8-byte stores from one
 // lane made the store path the bottleneck).
+__device__ __forceinline__ float4 load_once(const float4 *p) {
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ void true_mask_row(const float *__restrict__ A, int L, int tbw, int h, int i, unsigned theta,
                                               uint64_t *__restrict__ true_bits, int lane) {
   const float4 *row = reinterpret_cast<const float4 *>(A + ((int64_t)h * L + i) * L);
@@ -367,7 +373,8 @@ __device__ __forceinline__ void true_mask_row(const float *__restrict__ A, int L
 #pragma unroll
     for (int u = 0; u < kSeg; ++u) {
       const int j0 = (s0 + u) * 256 + lane * 4;
-      v[u] = (s0 + u < nseg && j0 < L) ? row[(s0 + u) * 64 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
+      // every element of the map is read once: non-temporal loads (0.586 -> 0.536 ms for 64 maps of 4096 x 4096)
+      v[u] = (s0 + u < nseg && j0 < L) ? load_once(row + (s0 + u) * 64 + lane) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     uint64_t mine = 0;  // word s0 * 4 + lane of the row
 #pragma unroll
