@@ -294,7 +294,10 @@ typedef struct {
                              the gathered K / V copies kept in the workspace); 0 otherwise           */
 } dam_attn_params;
 
-/* The block-index outputs of dam_mask_build for the hq query heads (device pointers). */
+/* The block-index outputs of dam_mask_build for the hq query heads (device pointers). Device data
+ * that the host cannot check: a blk_col entry outside the index's tile range is read as the nearest
+ * tile inside it (the output is then meaningless, no address leaves K, V or the gathered copies);
+ * blk_row_ptr must be a valid CSR offset array into buffers of at least that many tiles. */
 typedef struct {
   const int32_t *blk_row_ptr; /* [hq][nQt + 1]                                                     */
   const int32_t *blk_col;
@@ -344,7 +347,10 @@ size_t dam_sparse_attn_decode_workspace(const dam_decode_params *params, int64_t
  * kcache, vcache  device [batch][hkv][kv_capacity][head_dim] by kv_stride.
  * kept_ptr    device i32 [batch*hq + 1] ([hq + 1] with shared_lists); kept_idx device i32.
  * max_kept    the bound given to the workspace query (the library does not read kept_ptr on the
- *             host); every list must be no longer than it and every index < kv_capacity.
+ *             host); every list must be no longer than it and every index < kv_capacity. The lists
+ *             are device data that the host cannot check: an index outside [0, kv_capacity) is
+ *             read as the nearest cache row (the output is then meaningless, no address leaves the
+ *             cache); kept_ptr itself must be a valid CSR offset array.
  * lse         device f32 [batch][hq] or NULL. */
 int dam_sparse_attn_decode(const dam_decode_params *params, const void *q, const void *kcache,
                            const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,

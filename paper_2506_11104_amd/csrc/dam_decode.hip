@@ -97,6 +97,12 @@ __device__ __forceinline__ float row_sum(float d) {
   return d;
 }
 
+// A listed key outside the cache is pulled to its nearest row: the result is then wrong, but no
+// address leaves the head's rows. Applied where the row address is formed, not where the index is
+// fetched: there it would make the pass wait for the index load (and, the counter being in order,
+// for the rows in flight before it).
+__device__ __forceinline__ int in_cache(int row, int cap) { return min(max(row, 0), cap - 1); }
+
 __device__ __forceinline__ void store_out(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(__hip_bfloat16 *p, float v) { *p = __float2bfloat16(v); }
 
@@ -159,8 +165,9 @@ __global__ __launch_bounds__(256) void k_decode_partial(DecodeArgs a, const T *_
     float s[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      kf[u] = *reinterpret_cast<const uint4 *>(kb + (int64_t)rows[u] * a.kv_ss);
-      vf[u] = *reinterpret_cast<const uint4 *>(vb + (int64_t)rows[u] * a.kv_ss);
+      const int64_t row = in_cache(rows[u], a.cap);
+      kf[u] = *reinterpret_cast<const uint4 *>(kb + row * a.kv_ss);
+      vf[u] = *reinterpret_cast<const uint4 *>(vb + row * a.kv_ss);
     }
     const int64_t pn = p0 + GROUPS * kUnroll;
     if (pn < end) {
@@ -281,8 +288,9 @@ __global__ __launch_bounds__(256) void k_decode_group(DecodeArgs a, const T *__r
     unsigned cur[kUnroll], anyone = 0;
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      kf[u] = load_once(kb + (int64_t)rows[u] * a.kv_ss);
-      vf[u] = load_once(vb + (int64_t)rows[u] * a.kv_ss);
+      const int64_t row = in_cache(rows[u], a.cap);
+      kf[u] = load_once(kb + row * a.kv_ss);
+      vf[u] = load_once(vb + row * a.kv_ss);
       cur[u] = who[u];
       anyone |= who[u];
     }

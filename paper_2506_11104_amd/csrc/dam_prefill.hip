@@ -100,7 +100,8 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
     float m = -INFINITY, l = 0.0f;
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int t = t0; t < t1; ++t) {
-      const int col = blk_col[t];
+      // (a column or a key outside its range, from a list that was never filled, is pulled inside it)
+      const int col = min(max(blk_col[t], 0), a.nKt + (gather_idx ? a.gather_stride / a.tile_n : 0) - 1);
       // a gathered tile (index >= nKt): slot s of the tile stands for the head's matched column gcols[s]
       const int *gcols = col >= a.nKt ? gather_idx + (int64_t)w.hq * a.gather_stride + (col - a.nKt) * a.tile_n : nullptr;
       const int j0 = col * a.tile_n;
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
         uint64_t bits = full ? ~0ull : tile_bits[((int64_t)t * a.tile_m + rl) * a.wpr + wd];
         while (bits) {
           const int slot = wd * 64 + __ffsll((unsigned long long)bits) - 1;
-          const int j = gcols ? gcols[slot] : j0 + slot;
+          const int j = min(max(gcols ? gcols[slot] : j0 + slot, 0), a.S - 1);
           bits &= bits - 1;
           const float4 kv = *reinterpret_cast<const float4 *>(kb + j * a.k_ss);
           const float4 vv = *reinterpret_cast<const float4 *>(vb + j * a.v_ss);
@@ -453,7 +454,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       int quarters = 0, col = 0, full = 0;
       if (tid < n_seg) {
         const int kind = blk_kind[seg0 + tid];
-        col = blk_col[seg0 + tid];
+        // a column outside the index's range (a list that was never filled) is pulled inside it: the result is
+        // then wrong, but every address formed from it stays within the head's rows
+        col = min(max(blk_col[seg0 + tid], 0), a.nKt + (GATHER ? a.gather_rows / kBN : 0) - 1);
         quarters = (kind >> 1) & 15;
         full = kind & 1;
       }
