@@ -403,6 +403,17 @@ int pick_splits(int64_t items, int64_t max_kept) {
   return (int)std::min<int64_t>(std::max<int64_t>(s, 1), 64);
 }
 
+// Splits of the grouped form, and whether the call takes the matrix-core kernel (one wave per
+// workgroup: four per CU, each with at least two blocks of 32 entries).
+int group_splits(const dam_decode_params *p, int64_t max_kept, bool *mfma) {
+  const int64_t items = (int64_t)p->batch * p->hkv;
+  *mfma = decode_group_mfma_fits(p);
+  if (!*mfma) return pick_splits(items, max_kept);
+  int64_t s = (1024 + items - 1) / items;
+  s = std::min<int64_t>(s, std::max<int64_t>(1, max_kept / 64));
+  return (int)std::min<int64_t>(std::max<int64_t>(s, 1), 64);
+}
+
 int validate(const dam_decode_params *p, const void *q, const void *kc, const void *vc,
              const int32_t *kept_ptr, const int32_t *kept_idx, int64_t max_kept, const void *out) {
   if (!p || !q || !kc || !vc || !kept_ptr || !out) return DAM_ERR_INVALID_ARG;
@@ -494,7 +505,9 @@ void launch_group(const DecodeArgs &a, const void *q, const void *kc, const void
 
 extern "C" size_t dam_sparse_attn_decode_grouped_workspace(const dam_decode_params *p, int64_t max_kept) {
   if (!p || p->batch < 1 || p->hq < 1 || p->hkv < 1 || p->head_dim < 1 || max_kept < 0) return 0;
-  const int splits = pick_splits((int64_t)p->batch * p->hkv, max_kept);
+  if (p->hq % p->hkv) return 0;
+  bool mfma;
+  const int splits = group_splits(p, max_kept, &mfma);
   Carver c(nullptr);
   c.take<float>((size_t)p->batch * p->hq * splits * p->head_dim);
   c.take<float>((size_t)p->batch * p->hq * splits * 2);
@@ -512,7 +525,8 @@ extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const 
   if (!ws || ws_bytes < dam_sparse_attn_decode_grouped_workspace(p, max_kept)) return DAM_ERR_WORKSPACE;
   DecodeArgs a;
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity;
-  a.splits = pick_splits((int64_t)p->batch * p->hkv, max_kept);
+  bool mfma;
+  a.splits = group_splits(p, max_kept, &mfma);
   a.shared_lists = p->shared_lists != 0;
   a.scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf((float)p->head_dim);
   a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1];
@@ -522,7 +536,11 @@ extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const 
   float *part_o = c.take<float>((size_t)a.B * a.Hq * a.splits * p->head_dim);
   float *part_ml = c.take<float>((size_t)a.B * a.Hq * a.splits * 2);
   hipStream_t st = static_cast<hipStream_t>(stream_v);
-  if (p->dtype == DAM_BF16) {
+  if (mfma) {
+    // matrix-core partial pass, then the merge pass (also for one split: it normalises and stores)
+    launch_decode_group_mfma(p, a.splits, a.scale, q, kcache, vcache, kept_ptr, kept_idx, kept_member, part_o, part_ml, st);
+    k_decode_merge<__hip_bfloat16, 128><<<a.B * a.Hq, 128, 0, st>>>(a, part_o, part_ml, static_cast<__hip_bfloat16 *>(out), lse);
+  } else if (p->dtype == DAM_BF16) {
     if (p->head_dim == 128) launch_group<__hip_bfloat16, 128>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
     else launch_group<__hip_bfloat16, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
   } else {

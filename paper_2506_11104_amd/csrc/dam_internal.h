@@ -36,4 +36,13 @@ size_t capture_lse_bytes(const dam_capture_params *p);
 void launch_capture_true_bits(const dam_capture_params *p, const void *q, const void *k, float *lse2,
                               const unsigned *theta_key, uint64_t *true_bits, hipStream_t stream);
 
+// dam_decode_mfma.hip: the partial pass of the grouped-query decode on the matrix cores. `fits` says
+// whether a call can take it (bf16, head_dim 128, at most 8 query heads per KV head, a head's cache rows
+// within 4 GiB); the launch writes one (reference, sum, un-normalised O) triple per (sequence, query
+// head, split) in the layout the merge pass of dam_decode.hip reads.
+bool decode_group_mfma_fits(const dam_decode_params *p);
+void launch_decode_group_mfma(const dam_decode_params *p, int splits, float scale, const void *q, const void *kc,
+                              const void *vc, const int32_t *kept_ptr, const int32_t *kept_idx,
+                              const uint8_t *kept_member, float *part_o, float *part_ml, hipStream_t st);
+
 }  // namespace dam

@@ -32,6 +32,7 @@
 #include <utility>
 
 #include "dam_internal.h"
+#include "dam_mfma.h"
 
 namespace {
 using namespace dam;
@@ -139,13 +140,6 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
 
 // ================================================================================================
 // bf16 MFMA variant
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-
 constexpr int kBM = 128, kBN = 128;
 
 // LDS layout. Rows are 256 B = 16 chunks of 16 B and are not padded, because the global -> LDS
@@ -156,21 +150,6 @@ constexpr int kBM = 128, kBN = 128;
 //   V row r: chunk c lives at position c ^ ((r & 3) << 2)  (a transposing read touches 4 rows x 64 B
 //            per half-wave; the four 64-byte groups land in different bank quarters)
 // The permutation is applied on the global side of the copy (which chunk a lane fetches).
-
-__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-  typedef __attribute__((ext_vector_type(2))) float f32x2;
-  const bf16x2 r = __builtin_convertvector((f32x2){lo, hi}, bf16x2);  // round to nearest even
-  return __builtin_bit_cast(unsigned, r);
-}
-
-__device__ __forceinline__ bf16x8 lds_read_b128(const unsigned char *lds, int byte) {
-  return *reinterpret_cast<const bf16x8 *>(lds + byte);
-}
-
-__device__ __forceinline__ s16x4 lds_read_tr(const unsigned char *lds, int byte) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (__attribute__((address_space(3))) s16x4 *)(const_cast<unsigned char *>(lds + byte)));
-}
 
 // Scheduling hints: instruction classes of __builtin_amdgcn_sched_group_barrier.
 #define DAM_SCHED_MFMA 0x008
@@ -197,45 +176,11 @@ constexpr int kSegTiles = 128;                      // listed tiles expanded int
 constexpr int kListEntries = kSegTiles * 4 + 1;     // up to four blocks per tile, and the dummy that ends the list
 constexpr int kPipeLds = kBlkList + kListEntries * 8;
 
-// Load-to-LDS copies as inline assembly: lane L of the wave fetches `bytes` bytes from gbase + voff
-// and writes them to LDS address m0 + L * bytes, m0 = lds_at + IMM. Written as assembly so that the
-// compiler neither tracks them (it would make every later LDS read wait for all copies in flight) nor
-// counts them: the kernel waits for them itself with explicit s_waitcnt vmcnt(n), and issues no other
-// vector-memory loads inside the pipeline. gbase and lds_at are wave-uniform.
-template <int IMM>
-__device__ __forceinline__ void lds_copy16(unsigned lds_at, const void *gbase, unsigned voff) {
-  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
-               :
-               : "s"(lds_at), "n"(IMM), "v"(voff), "s"(gbase)
-               : "memory", "scc");
-}
-template <int IMM>
-__device__ __forceinline__ void lds_copy4(unsigned lds_at, const void *gbase, unsigned voff) {
-  asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3"
-               :
-               : "s"(lds_at), "n"(IMM), "v"(voff), "s"(gbase)
-               : "memory", "scc");
-}
-
 struct Blk {
   int key0;        // first key of the block (gathered tile: first row of the block in the gathered copy)
   int bits_off;    // byte offset of row 0's mask word for the block from the tile row's first mask word
   int flags;       // bit 0: tile is full (no mask), bit 1: dummy, bit 2: gathered tile (offsets into the gathered copies)
 };
-
-// 0 or -inf for bit POS of `inv` clear or set
-template <int POS>
-__device__ __forceinline__ float neg_inf_if_bit(int inv) {
-  // (both instructions in one statement: after a statement of one instruction whose result is used at once
-  // the compiler pads with a no-op)
-  int field;
-  asm("v_bfe_i32 %0, %1, %2, 1\n\tv_and_b32 %0, 0xff800000, %0" : "=&v"(field) : "v"(inv), "n"(POS));
-  return __int_as_float(field);
-}
-template <int... E>
-__device__ __forceinline__ void mask_init(f32x16 &s, int inv, std::integer_sequence<int, E...>) {
-  ((s[E] = neg_inf_if_bit<8 * (E / 4) + E % 4>(inv)), ...);
-}
 
 template <int PH>
 __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds, const bf16x8 (&qf)[8],
