@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # script with --copy-calibration, scaled by what the same counters read for a plain 1 GiB copy: x2.00 and x1.00);
 # the summary with the commands is profiles/prefill_c3_decode_c5_hbm_traffic_pmc.txt. They belong to the default
 # workloads (c3 prefill, c5 decode) and are reported as the roofline objects' `traffic`.
-MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.31e9, "k_decode_group/c5": 5.13e8}
+MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.31e9, "k_decode_group_mfma/c5": 5.15e8}
 
 
 def parse():
@@ -337,9 +337,9 @@ def bench_decode(args, torch, B, wl):
     res.update(main)
     res.update({"kept_per_head_list": sb / (w.hq * row_bytes), "union_bytes": ub, "sum_bytes": sb,
                 "gbs_union": ub / (dec_us * 1e-6) / 1e9,
-                "roofline": {"bound": "hbm", "kernel": "k_decode_group", "achieved": ub / (dec_us * 1e-6) / 1e9,
+                "roofline": {"bound": "hbm", "kernel": "k_decode_group_mfma", "achieved": ub / (dec_us * 1e-6) / 1e9,
                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
-                             "traffic": MEASURED_TRAFFIC_BYTES["k_decode_group/c5"]},
+                             "traffic": MEASURED_TRAFFIC_BYTES["k_decode_group_mfma/c5"]},
                 "list_per_head_form": per_head, "kv_eviction": evict})
     return res
 

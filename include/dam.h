@@ -361,9 +361,11 @@ int dam_sparse_attn_decode(const dam_decode_params *params, const void *q, const
  * query heads share the K and V rows of one KV head). The lists are those of dam_mask_build with
  * DAM_MASK_GROUP_LISTS and group = hq / hkv (<= 8): one per (sequence, KV head), or one per KV head with
  * shared_lists, holding every key that some head of the group keeps once, and kept_member[e] naming the
- * heads that keep it (bit x: query head hkv_index * group + x). A workgroup reads each listed row once
- * and updates the softmax state of exactly the heads named; the results equal those of
- * dam_sparse_attn_decode on the per-head lists up to the order of the fp32 sums.
+ * heads that keep it (bit x: query head hkv_index * group + x). Each listed row is read once and enters
+ * the softmax state of exactly the heads named; the results equal those of dam_sparse_attn_decode on
+ * the per-head lists up to the order of the fp32 sums, except for bf16 with head_dim 128, where the
+ * products run on the matrix cores with the softmax weights rounded to bf16, as in the prefill: there
+ * the two agree within the bf16 output tolerance (2e-2 max-abs), not to the last bit.
  * kept_ptr  device i32 [batch*hkv + 1] ([hkv + 1] with shared_lists); kept_idx i32 and kept_member u8
  *           device arrays of the same length. Entries of one list may come in any order, without
  *           duplicates; runs of entries with equal kept_member cost no arithmetic for the other heads.

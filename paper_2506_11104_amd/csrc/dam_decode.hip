@@ -8,7 +8,9 @@
 // coalesced); every lane keeps 4 keys in flight. The kept list is split over several workgroups
 // per head so that all 256 CUs stream; partial (max, sum, O) triples are merged by log-sum-exp.
 // Workgroups are numbered so that all query heads sharing a KV head run on the same XCD and hit
-// the same L2 for the rows their lists have in common.
+// the same L2 for the rows their lists have in common. The grouped-query form (one merged list per
+// KV head) takes the matrix-core kernel of dam_decode_mfma.hip for bf16 and head_dim 128, and the
+// plain-ALU kernel here otherwise; both feed the same merge pass.
 #include <hip/hip_bf16.h>
 #include <math.h>
 

@@ -173,6 +173,50 @@ def test_grouped_decode_long_shared_lists_many_splits():
     run_grouped(rng, "bf16", Bn, Hq, Hkv, 128, T, overlapping_lists(rng, Hq, T, lens), shared=True)
 
 
+@pytest.mark.parametrize("G", [1, 4])
+def test_grouped_decode_lists_around_the_block_size(G):
+    """bf16, head_dim 128 takes the matrix-core kernel, which walks a list in blocks of 32 entries: merged lists
+    one entry short of, at and one entry past whole blocks, an empty one, and several splits of a longer one."""
+    rng = np.random.default_rng(53)
+    lens_kv = [0, 1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 128, 1000, 1024, 1025]
+    Hkv, T = len(lens_kv), 1100
+    lists = []
+    for n in lens_kv:
+        union = np.sort(rng.choice(T, n, replace=False)).astype(np.int32)
+        for x in range(G):  # head x keeps a random part of the union; head 0 keeps what nobody else does
+            lists.append(union[rng.random(n) < 0.6] if x else union)
+        if G > 1:
+            others = np.unique(np.concatenate(lists[-G + 1:])) if n else np.empty(0, np.int32)
+            lists[-G] = np.union1d(np.setdiff1d(union, others), union[: n // 3]).astype(np.int32)
+    run_grouped(rng, "bf16", 2, Hkv * G, Hkv, 128, T, lists, shared=True)
+
+
+def test_grouped_decode_member_bytes_at_any_alignment():
+    """The member bytes of a block are fetched as aligned words: the result may not depend on where the array
+    starts."""
+    rng = np.random.default_rng(54)
+    Bn, Hkv, G, T, d = 2, 3, 4, 900, 128
+    Hq = Hkv * G
+    lists = overlapping_lists(rng, Hq, T, rng.integers(40, 400, Hq))
+    gptr, gidx, gmem = oracle.group_lists(lists, G)
+    longest = int(np.diff(gptr).max())
+    q = dev(wl.to_storage(rng.standard_normal((Bn, Hq, d)).astype(np.float32), "bf16"), "bf16")
+    Kc = dev(wl.to_storage(rng.standard_normal((Bn, Hkv, T, d)).astype(np.float32), "bf16"), "bf16")
+    Vc = dev(wl.to_storage(rng.standard_normal((Bn, Hkv, T, d)).astype(np.float32), "bf16"), "bf16")
+    ptr, idx = torch.from_numpy(gptr.astype(np.int32)).cuda(), torch.from_numpy(gidx).cuda()
+    outs = []
+    for k in range(4):
+        buf = torch.full((len(gmem) + 8,), 0xFF, dtype=torch.uint8, device="cuda")
+        mem = buf[k:k + len(gmem)]
+        mem.copy_(torch.from_numpy(gmem))
+        assert mem.data_ptr() % 4 == k
+        out, lse = B.dam_sparse_attn_decode_grouped(q, Kc, Vc, ptr, idx, mem, longest, want_lse=True, shared_lists=True)
+        torch.cuda.synchronize()
+        outs.append((out.clone(), lse.clone()))
+    for out, lse in outs[1:]:
+        assert torch.equal(out, outs[0][0]) and torch.equal(lse, outs[0][1])
+
+
 def group_lists_case(H, G, S, row, dflag, vflag, L=0, true_mask=None):
     art = oracle.from_patterns(dflag, vflag, true_mask)
     want = oracle.group_lists([oracle.kept_list(art, h, row) for h in range(H)], G)
