@@ -354,8 +354,11 @@ def bench_decode(args, torch, B, wl):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e6 / n_steps
 
-    main, _ = form(True, steps)
+    main, (g_ptr, g_idx, g_bound) = form(True, steps)
     main["us_per_step_list_build_on_a_second_stream"] = overlapped(steps)
+    # the merged lists of the first position, kept for the decode from the compacted cache below
+    mg = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False,
+                      rows=(w.seq - 1, w.seq), group=G)
     ub = main["list_entries"] * row_bytes                         # the union of the heads' kept rows: what must move
     per_head, (kept_ptr, kept_idx, _) = form(False, min(steps, 64))
     sb = per_head["list_entries"] * row_bytes                     # what moves without sharing between the heads of a group
@@ -382,9 +385,14 @@ def bench_decode(args, torch, B, wl):
     ws_c = B.decode_workspace(dpc, max_kept, dev)
     dec_c_us = timed(lambda: B.dam_sparse_attn_decode(qs[0], kcmp, vcmp, kept_ptr, slot, max_kept, out=out, ws=ws_c,
                                                       shared_lists=True), 50)
+    slot_g = B.kv_remap_lists(plan, mg.kept_ptr, mg.kept_idx, 1, per_kv_head=True)
+    ws_cg = B.decode_grouped_workspace(dpc, g_bound, dev)
+    dec_cg_us = timed(lambda: B.dam_sparse_attn_decode_grouped(qs[0], kcmp, vcmp, mg.kept_ptr, slot_g, mg.kept_member, g_bound,
+                                                              out=out, ws=ws_cg, shared_lists=True), 50)
     evict = {"rows_kept_per_kv_head": [int(x) for x in plan.rows.cpu()], "cache_rows": cap,
              "cache_bytes_ratio": ccap / cap, "plan_us_incl_two_host_syncs": plan_us, "compact_us": compact_us, "compact_bytes": compact_bytes,
              "remap_us": remap_us, "decode_from_compacted_us_list_per_head": dec_c_us,
+             "decode_from_compacted_us_grouped": dec_cg_us,
              "roofline": {"bound": "hbm", "achieved": compact_bytes / (compact_us * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
                           "unit": "GB/s", "frac": compact_bytes / (compact_us * 1e-6) / 1e9 / PEAK_HBM_GBS, "traffic": None}}
     del kcmp, vcmp
