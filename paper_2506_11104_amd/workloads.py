@@ -6,9 +6,9 @@ the model's own attention and not part of the DAM method), and given pattern set
 the DAM arithmetic (no Box-Cox, threshold, matching, extension or sparse attention) and imports
 neither the GPU binding nor the CPU oracle; both are fed the same bytes from here.
 
-The five workloads mirror the benchmark configurations of this repository (see the design doc for the
-recipe and for what they stand in for: the paper measures on LongEval / LV-Eval / Multi-News with
-LLaMA-3.2 and Vicuna weights, none of which is available here).
+The five workloads mirror the benchmark configurations of this repository; each generator below states
+its recipe. They stand in for what the paper measures on (LongEval / LV-Eval / Multi-News with
+LLaMA-3.2 and Vicuna weights, Sec. 5), none of which is available here.
 """
 from __future__ import annotations
 
