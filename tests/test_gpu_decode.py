@@ -191,6 +191,15 @@ def test_grouped_decode_lists_around_the_block_size(G):
     run_grouped(rng, "bf16", 2, Hkv * G, Hkv, 128, T, lists, shared=True)
 
 
+def test_grouped_decode_more_pairs_than_waves_fit():
+    """More (sequence, KV head) pairs than waves are resident at once: one wave per pair walks its whole list."""
+    rng = np.random.default_rng(55)
+    Bn, Hkv, G, T = 140, 8, 2, 260
+    Hq = Hkv * G
+    lists = overlapping_lists(rng, Hq, T, rng.integers(0, 200, Hq))
+    run_grouped(rng, "bf16", Bn, Hq, Hkv, 128, T, lists, shared=True)
+
+
 def test_grouped_decode_member_bytes_at_any_alignment():
     """The member bytes of a block are fetched as aligned words: the result may not depend on where the array
     starts."""
