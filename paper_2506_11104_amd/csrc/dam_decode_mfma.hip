@@ -45,7 +45,10 @@ __device__ __forceinline__ void lds_copy4_at(unsigned lds_at, uint64_t addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_at), "v"(addr) : "memory");
 }
 
-__global__ __launch_bounds__(64) void k_decode_group_mfma(MfmaArgs a, const __hip_bfloat16 *__restrict__ q,
+// (The register budget of two waves per SIMD, although LDS admits one: with all 512 registers on offer the
+// compiler keeps the O accumulators in the accumulation registers for the products and in vector registers for
+// the occasional rescaling, and moves all 64 of them both ways in every iteration.)
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_decode_group_mfma(MfmaArgs a, const __hip_bfloat16 *__restrict__ q,
                                                           const __hip_bfloat16 *__restrict__ kc,
                                                           const __hip_bfloat16 *__restrict__ vc,
                                                           const int *__restrict__ kept_ptr,
