@@ -351,11 +351,12 @@ def bench_decode(args, torch, B, wl):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         run(n_steps)
+        t_host = time.perf_counter() - t0                        # the host's part: if it is the larger one, it is the bound
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e6 / n_steps
+        return (time.perf_counter() - t0) * 1e6 / n_steps, t_host * 1e6 / n_steps
 
     main, (g_ptr, g_idx, g_bound) = form(True, steps)
-    main["us_per_step_list_build_on_a_second_stream"] = overlapped(steps)
+    main["us_per_step_list_build_on_a_second_stream"], main["host_us_per_step_of_that_loop"] = overlapped(steps)
     # the merged lists of the first position, kept for the decode from the compacted cache below
     mg = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False,
                       rows=(w.seq - 1, w.seq), group=G)
