@@ -48,13 +48,10 @@ __device__ __forceinline__ void lds_copy4_at(unsigned lds_at, uint64_t addr) {
 // (The register budget of two waves per SIMD, although LDS admits one: with all 512 registers on offer the
 // compiler keeps the O accumulators in the accumulation registers for the products and in vector registers for
 // the occasional rescaling, and moves all 64 of them both ways in every iteration.)
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_decode_group_mfma(MfmaArgs a, const __hip_bfloat16 *__restrict__ q,
-                                                          const __hip_bfloat16 *__restrict__ kc,
-                                                          const __hip_bfloat16 *__restrict__ vc,
-                                                          const int *__restrict__ kept_ptr,
-                                                          const int *__restrict__ kept_idx,
-                                                          const uint8_t *__restrict__ kept_member,
-                                                          float *__restrict__ part_o, float *__restrict__ part_ml) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_decode_group_mfma(
+    MfmaArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ kc,
+    const __hip_bfloat16 *__restrict__ vc, const int *__restrict__ kept_ptr, const int *__restrict__ kept_idx,
+    const uint8_t *__restrict__ kept_member, float *__restrict__ part_o, float *__restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   const int lane = threadIdx.x;
   const int n = lane & 31, hf = lane >> 5;     // column of the products (query head of the group), half-wave
