@@ -45,7 +45,9 @@ typedef enum {
   DAM_ERR_INVALID_ARG = -1, /* null required pointer, non-positive size, hq % hkv != 0, bad ranges */
   DAM_ERR_UNSUPPORTED = -2, /* a head_dim / dtype / tile / lambda outside the built set          */
   DAM_ERR_WORKSPACE = -3,   /* ws_bytes smaller than the matching *_workspace() query             */
-  DAM_ERR_CAPACITY = -4,    /* reserved: capacity overflow is reported through blk_total/kept_total */
+  /* -4 is not used: a capacity overflow cannot be known on the host without a synchronisation. It is
+     reported through the device scalars blk_total / kept_total / col_total, and the offsets written
+     never exceed the capacity (see dam_mask_out).                                                 */
   DAM_ERR_DEVICE = -5       /* a kernel launch failed                                              */
 } dam_status;
 
@@ -142,6 +144,13 @@ typedef struct {
 
 /* Outputs of dam_mask_build. Every pointer is a device pointer owned by the caller; any of them may
  * be NULL when that output is not wanted (exceptions are stated).
+ *
+ * Capacity: when the listed tiles (the kept keys) outnumber blk_capacity (kept_capacity), nothing is
+ * written at or past the capacity, blk_total (kept_total) still holds the number required, and every
+ * offset written to blk_row_ptr (kept_ptr) is cut to the capacity: the index then lists exactly the
+ * first `capacity` tiles (keys), in order, and is safe to hand to the attention kernels (their result
+ * is that of the truncated mask). In a sizing call (blk_col, blk_kind and tile_bits all NULL; kept_idx
+ * NULL) the offsets are the true ones.
  *
  *   true_bits  [H][L][ceil(L/64)] u64   bit (j % 64) of word j / 64 of row i is m[i][j].
  *                                       FROM_ATTN_MAP: written, and required (the later steps of the

@@ -30,7 +30,8 @@ def _ptr(a: Optional[np.ndarray], ctype):
 def lib() -> ctypes.CDLL:
     global _LIB
     if _LIB is None:
-        path = _build.build(force=False)
+        # DAM_ORACLE_SANITIZE=1: the AddressSanitizer + UBSan build (the process must have libasan preloaded)
+        path = _build.build(force=False, sanitize=os.environ.get("DAM_ORACLE_SANITIZE") == "1")
         _LIB = ctypes.CDLL(path)
         _LIB.dam_oracle_boxcox.restype = ctypes.c_float
         _LIB.dam_oracle_boxcox.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
@@ -263,7 +264,7 @@ def block_index(art: MaskArtefact, S: int, tile_m: int, tile_n: int, heads: Opti
     qa, qb = (0, (S + tile_m - 1) // tile_m) if qt_range is None else qt_range
     nQt = qb - qa
     wpr = tile_n // 64
-    chunk = max(1, nQt // 16)
+    chunk = max(1, nQt // 64)
     jobs = [(h, q0, min(qb, q0 + chunk)) for h in heads for q0 in range(qa, qb, chunk)]
     gcols = {}
     if gather:   # "gather = True": the layout with the matched columns in tiles of their own (see the C source)
@@ -281,15 +282,20 @@ def block_index(art: MaskArtefact, S: int, tile_m: int, tile_n: int, heads: Opti
                                             _ptr(col, ctypes.c_int32), _ptr(kind, ctypes.c_uint8),
                                             _ptr(bits, ctypes.c_uint64), cap)
 
+    nKt = (S + tile_n - 1) // tile_n
+    n_gt = {h: (len(gcols[h]) + tile_n - 1) // tile_n for h in heads} if gather else {}
+
     def run(job):
+        # one call with room for every tile the chunk could list (its causal tiles, plus the gathered ones)
         h, q0, q1 = job
         cnt = np.zeros(q1 - q0, np.int32)
-        n = call(h, q0, q1, cnt, None, None, None, 0)
-        col = np.empty(n, np.int32)
-        kind = np.empty(n, np.uint8)
-        bits = np.empty((n, tile_m, wpr), np.uint64) if want_bits else None
-        call(h, q0, q1, cnt, col, kind, bits, n)
-        return cnt, col, kind, bits
+        cap = sum(min(nKt, ((qt + 1) * tile_m + tile_n - 1) // tile_n) + n_gt.get(h, 0) for qt in range(q0, q1))
+        col = np.empty(cap, np.int32)
+        kind = np.empty(cap, np.uint8)
+        bits = np.empty((cap, tile_m, wpr), np.uint64) if want_bits else None
+        n = call(h, q0, q1, cnt, col, kind, bits, cap)
+        assert n <= cap
+        return cnt, col[:n].copy(), kind[:n].copy(), bits[:n].copy() if want_bits else None
 
     with ThreadPoolExecutor(max_workers=workers) as ex:
         res = list(ex.map(run, jobs))

@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdam.so")
 
-DAM_OK, DAM_ERR_INVALID_ARG, DAM_ERR_UNSUPPORTED, DAM_ERR_WORKSPACE, DAM_ERR_CAPACITY, DAM_ERR_DEVICE = 0, -1, -2, -3, -4, -5
+DAM_OK, DAM_ERR_INVALID_ARG, DAM_ERR_UNSUPPORTED, DAM_ERR_WORKSPACE, DAM_ERR_DEVICE = 0, -1, -2, -3, -5
 DAM_F32, DAM_BF16 = 0, 1
 DAM_FROM_ATTN_MAP, DAM_FROM_PATTERNS = 0, 1
 DAM_MASK_SKIP_FULL_TILE_BITS = 1
@@ -27,7 +27,7 @@ TRANSFORMS = {"boxcox": 0, "raw_sum": 1, "average": 2, "log": 3, "yeo_johnson": 
               "sqrt": 7, "arcsinh": 8}
 
 _STATUS = {0: "DAM_OK", -1: "DAM_ERR_INVALID_ARG", -2: "DAM_ERR_UNSUPPORTED", -3: "DAM_ERR_WORKSPACE",
-           -4: "DAM_ERR_CAPACITY", -5: "DAM_ERR_DEVICE"}
+           -5: "DAM_ERR_DEVICE"}
 
 
 class DamError(RuntimeError):

@@ -17,7 +17,7 @@ OBJ = os.path.join(HERE, "_build")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fhip-fp32-correctly-rounded-divide-sqrt", "-Wall", "-Wno-unused-function",
-         "-Wno-unknown-warning-option"]
+         "-Wno-unknown-warning-option", "-Wno-inline-asm"]
 
 
 def sources():

@@ -42,7 +42,7 @@ struct MfmaArgs {
 
 // Four bytes per lane from a 64-bit address of the lane's own to LDS address lds_at + 4 * lane.
 __device__ __forceinline__ void lds_copy4_at(unsigned lds_at, uint64_t addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_at), "v"(addr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_at), "v"(addr) : "memory", "m0");
 }
 
 // (The register budget of two waves per SIMD, although LDS admits one: with all 512 registers on offer the

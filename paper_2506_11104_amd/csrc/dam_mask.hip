@@ -1003,13 +1003,16 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
 
 // Exclusive scan of n counts by one block. group > 0: the result is laid out as [n / group]
 // rows of group + 1 offsets (row r ends where row r + 1 begins); group == 0: plain [n + 1].
+// Offsets are written as min(offset, clamp): with clamp = the capacity of the buffers the offsets point
+// into, an index that does not fit is truncated to its first `capacity` entries and stays consistent
+// with what the fill kernels wrote; *total is the unclamped sum.
 // Every thread takes kScanItems consecutive counts per pass, so that the block-wide part (a wave
 // scan, one exchange of the wave totals) is paid once per 8192 counts.
 constexpr int kScanItems = 8;
 
 __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__ cnt, int64_t n,
                                                          int group, int *__restrict__ ptr,
-                                                         int64_t *__restrict__ total) {
+                                                         int64_t *__restrict__ total, int64_t clamp) {
   __shared__ int64_t wave_sum[2][16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int64_t carry = 0;  // the same value in every thread
@@ -1048,14 +1051,14 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__
             r = e / group;
             q = (int)(e - r * group);
           }
-          ptr[r * (group + 1) + q] = (int)excl;
-          if (q == 0 && r > 0) ptr[(r - 1) * (group + 1) + group] = (int)excl;
+          ptr[r * (group + 1) + q] = (int)min(excl, clamp);
+          if (q == 0 && r > 0) ptr[(r - 1) * (group + 1) + group] = (int)min(excl, clamp);
           if (++q == group) {
             q = 0;
             ++r;
           }
         } else {
-          ptr[e] = (int)excl;
+          ptr[e] = (int)min(excl, clamp);
         }
       }
       excl += v[x];
@@ -1064,9 +1067,9 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__
   }
   if (threadIdx.x == 0) {
     if (group > 0) {
-      if (n > 0) ptr[(n / group - 1) * (group + 1) + group] = (int)carry;
+      if (n > 0) ptr[(n / group - 1) * (group + 1) + group] = (int)min(carry, clamp);
     } else {
-      ptr[n] = (int)carry;
+      ptr[n] = (int)min(carry, clamp);
     }
     if (total) *total = carry;
   }
@@ -1411,9 +1414,10 @@ __global__ __launch_bounds__(256) void k_group_fill(Geom g, const uint64_t *__re
   const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), kv = blockIdx.y;
   if (chunk >= nchunks) return;  // whole waves
   const int *mine_first = first + (int64_t)kv * (G + 1) * nchunks + chunk;
-  if (chunk == 0 && lane == 0) {
-    kept_ptr[kv] = mine_first[0];
-    if (kv == n_groups - 1) kept_ptr[n_groups] = first[(int64_t)n_groups * (G + 1) * nchunks];
+  if (chunk == 0 && lane == 0) {  // (offsets past the capacity of the list buffers are cut to it, like the block index')
+    const int64_t clamp = kept_idx ? capacity : INT64_MAX;
+    kept_ptr[kv] = (int)min((int64_t)mine_first[0], clamp);
+    if (kv == n_groups - 1) kept_ptr[n_groups] = (int)min((int64_t)first[(int64_t)n_groups * (G + 1) * nchunks], clamp);
   }
   if (!kept_idx) return;
   unsigned m[kMaxGroup], shared;
@@ -1641,8 +1645,10 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
     k_tile_scan<<<dim3((g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
                                                                      w.off_all, w.occ, w.full, w.tile_cnt, lds_sets > 0, gidx,
                                                                      gcnt, gstride, w.vocc, w.vfull);
-    k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total);
-    if (o->blk_col || o->blk_kind || o->tile_bits)
+    const bool fill = o->blk_col || o->blk_kind || o->tile_bits;
+    k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total,
+                                             fill ? o->blk_capacity : INT64_MAX);
+    if (fill)
       k_tile_fill<<<dim3(g.nQt, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,
                                                                o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
                                                                (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0,
@@ -1660,18 +1666,21 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
       const int G = list_group(p), n_groups = g.H / G, nchunks = group_chunks(p->row_begin);
       const dim3 grid((nchunks + 3) / 4, n_groups);
       k_group_count<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, w.row_cnt);
-      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)n_groups * (G + 1) * nchunks, 0, w.group_first, o->kept_total);
+      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)n_groups * (G + 1) * nchunks, 0, w.group_first, o->kept_total,
+                                               INT64_MAX);
       k_group_fill<<<grid, 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, G, nchunks, n_groups, w.group_first,
                                              o->kept_ptr, o->kept_capacity > 0 ? o->kept_idx : nullptr, o->kept_member,
                                              o->kept_capacity);
     } else if (nrows > 0) {
       k_row_count<<<dim3(nrows, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, nrows, w.row_cnt);
-      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)g.H * nrows, 0, o->kept_ptr, o->kept_total);
-      if (o->kept_idx && o->kept_capacity > 0)
+      const bool fill_lists = o->kept_idx && o->kept_capacity > 0;
+      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)g.H * nrows, 0, o->kept_ptr, o->kept_total,
+                                               fill_lists ? o->kept_capacity : INT64_MAX);
+      if (fill_lists)
         k_row_fill<<<dim3(nrows, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, p->row_begin, nrows, o->kept_ptr,
                                                          o->kept_idx, o->kept_capacity);
     } else {
-      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, 0, 0, o->kept_ptr, o->kept_total);
+      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, 0, 0, o->kept_ptr, o->kept_total, INT64_MAX);
     }
   }
 }

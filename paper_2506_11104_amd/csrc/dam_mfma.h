@@ -40,7 +40,7 @@ __device__ __forceinline__ void lds_copy16(unsigned lds_at, const void *gbase, u
   asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
                :
                : "s"(lds_at), "n"(IMM), "v"(voff), "s"(gbase)
-               : "memory", "scc");
+               : "memory", "scc", "m0");
 }
 // The same for rows that are read once: a non-temporal load, so that they stream past the caches.
 template <int IMM>
@@ -48,14 +48,14 @@ __device__ __forceinline__ void lds_copy16_once(unsigned lds_at, const void *gba
   asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 nt"
                :
                : "s"(lds_at), "n"(IMM), "v"(voff), "s"(gbase)
-               : "memory", "scc");
+               : "memory", "scc", "m0");
 }
 template <int IMM>
 __device__ __forceinline__ void lds_copy4(unsigned lds_at, const void *gbase, unsigned voff) {
   asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3"
                :
                : "s"(lds_at), "n"(IMM), "v"(voff), "s"(gbase)
-               : "memory", "scc");
+               : "memory", "scc", "m0");
 }
 
 // 0 or -inf for bit POS of `inv` clear or set

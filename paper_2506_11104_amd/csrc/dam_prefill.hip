@@ -600,15 +600,15 @@ int validate(const dam_attn_params *p, const void *q, const void *k, const void 
              const void *out) {
   if (!p || !q || !k || !v || !mk || !out) return DAM_ERR_INVALID_ARG;
   if (!mk->blk_row_ptr || !mk->blk_col || !mk->blk_kind || !mk->tile_bits) return DAM_ERR_INVALID_ARG;
-  if (mk->gather_idx) {  // gathered column tiles
+  if (p->batch < 1 || p->hq < 1 || p->hkv < 1 || p->hq % p->hkv || p->seq < 1) return DAM_ERR_INVALID_ARG;
+  if (p->tile_m < 64 || p->tile_n < 64 || p->tile_m % 64 || p->tile_n % 64) return DAM_ERR_INVALID_ARG;
+  if (mk->gather_idx) {  // gathered column tiles (checked after the tile sizes: the test divides by tile_n)
     if (!mk->gather_cnt || mk->gather_stride < 1 || p->gather_rows < 0 || p->gather_rows % p->tile_n ||
         p->gather_rows > mk->gather_stride)
       return DAM_ERR_INVALID_ARG;
   } else if (p->gather_rows != 0) {
     return DAM_ERR_INVALID_ARG;
   }
-  if (p->batch < 1 || p->hq < 1 || p->hkv < 1 || p->hq % p->hkv || p->seq < 1) return DAM_ERR_INVALID_ARG;
-  if (p->tile_m < 64 || p->tile_n < 64 || p->tile_m % 64 || p->tile_n % 64) return DAM_ERR_INVALID_ARG;
   if (!(p->scale >= 0.0f)) return DAM_ERR_INVALID_ARG;
   const int align = p->dtype == DAM_BF16 ? 8 : 4;
   const int64_t *sets[4] = {p->q_stride, p->k_stride, p->v_stride, p->o_stride};
@@ -678,13 +678,11 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
                                                 mk->blk_col, mk->blk_kind, mk->tile_bits, mk->gather_idx, (float *)out, lse);
     return launch_status();
   }
-  static int n_cu = 0;
-  if (!n_cu) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return DAM_ERR_DEVICE;
-    n_cu = prop.multiProcessorCount;
-  }
+  // (queried per call: the library keeps no state, and the device may differ from call to call)
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    return DAM_ERR_DEVICE;
   int *queue_next = static_cast<int *>(ws);
   __hip_bfloat16 *kgath = reinterpret_cast<__hip_bfloat16 *>(static_cast<char *>(ws) + 256);
   __hip_bfloat16 *vgath = kgath + (size_t)p->batch * p->hq * a.gather_rows * (size_t)a.k_ss;
@@ -702,13 +700,10 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   static const Kernel kernels[4] = {k_prefill_bf16_pipe<false, false>, k_prefill_bf16_pipe<true, false>,
                                     k_prefill_bf16_pipe<false, true>, k_prefill_bf16_pipe<true, true>};
   const int which = (ragged ? 1 : 0) + (gather ? 2 : 0);
-  static bool attr_set[4] = {false, false, false, false};
-  if (!attr_set[which]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[which]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kPipeLds) != hipSuccess)
-      return DAM_ERR_DEVICE;
-    attr_set[which] = true;
-  }
+  // (idempotent; set on every call rather than remembered in a static)
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[which]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kPipeLds) != hipSuccess)
+    return DAM_ERR_DEVICE;
   kernels[which]<<<persistent, 256, kPipeLds, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
                                                     (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col, mk->blk_kind,
                                                     mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next, kgath, vgath);

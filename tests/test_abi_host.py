@@ -17,6 +17,20 @@ def declared_functions():
     return sorted(set(re.findall(r"\b(dam_[a-z_]+)\s*\(", src)))
 
 
+def test_status_codes_of_the_header_and_the_binding_agree():
+    """Every status the header's enum names, with its value, is what the binding holds; -4 names nothing (a capacity
+    overflow is reported through the device totals and the clamped offsets, never through the return value)."""
+    src = open(os.path.join(ROOT, "include", "dam.h")).read()
+    enum = src[src.index("typedef enum {\n  DAM_OK"):src.index("} dam_status;")]
+    enum = re.sub(r"/\*.*?\*/", "", enum, flags=re.S)
+    codes = {n: int(v) for n, v in re.findall(r"(DAM_[A-Z_]+)\s*=\s*(-?\d+)", enum)}
+    assert codes == {"DAM_OK": 0, "DAM_ERR_INVALID_ARG": -1, "DAM_ERR_UNSUPPORTED": -2, "DAM_ERR_WORKSPACE": -3,
+                     "DAM_ERR_DEVICE": -5}
+    for n, v in codes.items():
+        assert getattr(B, n) == v
+    assert -4 not in B._STATUS and not hasattr(B, "DAM_ERR_CAPACITY")
+
+
 def test_every_declared_symbol_is_exported():
     L = B.lib()
     names = declared_functions()
@@ -102,6 +116,12 @@ def test_prefill_argument_errors():
     assert call_prefill(attn_params(scale=-1.0)) == B.DAM_ERR_INVALID_ARG
     assert call_prefill(attn_params(), mv=B.MaskView(4096, None, 4096, 4096)) == B.DAM_ERR_INVALID_ARG
     assert call_prefill(attn_params(q_stride=(ctypes.c_int64 * 3)(0, 0, 130))) == B.DAM_ERR_INVALID_ARG  # unaligned rows
+    # a zero tile size with gathered tiles present: rejected, not divided by
+    gath = B.MaskView(4096, 4096, 4096, 4096, 4096, 4096, 128)
+    assert call_prefill(attn_params(tile_n=0, gather_rows=128), mv=gath) == B.DAM_ERR_INVALID_ARG
+    assert call_prefill(attn_params(tile_m=0, tile_n=0, gather_rows=128), mv=gath) == B.DAM_ERR_INVALID_ARG
+    assert call_prefill(attn_params(gather_rows=100), mv=gath) == B.DAM_ERR_INVALID_ARG   # not a multiple of tile_n
+    assert call_prefill(attn_params(gather_rows=128)) == B.DAM_ERR_INVALID_ARG             # rows without an index
     need = B.lib().dam_sparse_attn_prefill_workspace(ctypes.byref(attn_params()))
     if need:
         assert call_prefill(attn_params(), ws_bytes=need - 1) == B.DAM_ERR_WORKSPACE

@@ -292,7 +292,8 @@ def test_grouped_decode_from_mask_build_matches_the_prefill_row():
 
 
 def test_group_lists_respect_the_capacity():
-    """kept_total and kept_ptr are right whatever the capacity; nothing is written at or past it."""
+    """kept_total is right whatever the capacity, nothing is written at or past it, and the offsets in kept_ptr are
+    cut to it (the truncated lists stay consistent and safe to decode from); a sizing call gives the true offsets."""
     rng = np.random.default_rng(61)
     H, G, S = 8, 4, 6000
     dflag = (rng.random((H, S)) < 0.02).astype(np.uint8)
@@ -315,9 +316,30 @@ def test_group_lists_respect_the_capacity():
     B.dam_mask_build(p, None, None, torch.from_numpy(dflag).cuda(), torch.from_numpy(vflag).cuda(), o, ws)
     torch.cuda.synchronize()
     assert int(total.item()) == n
-    assert np.array_equal(ptr.cpu().numpy().astype(np.int64), want[0])
+    assert np.array_equal(ptr.cpu().numpy().astype(np.int64), np.minimum(want[0], cap))
     assert np.array_equal(idx.cpu().numpy()[:cap], want[1][:cap]) and np.array_equal(mem.cpu().numpy()[:cap], want[2][:cap])
     assert (idx[cap:] == -7).all() and (mem[cap:] == 0xEE).all()
+    o.kept_idx, o.kept_member, o.kept_capacity = None, None, 0
+    B.dam_mask_build(p, None, None, torch.from_numpy(dflag).cuda(), torch.from_numpy(vflag).cuda(), o, ws)
+    torch.cuda.synchronize()
+    assert int(total.item()) == n and np.array_equal(ptr.cpu().numpy().astype(np.int64), want[0])
+    # lists of several rows (the plain count / scan / fill kernels): the same rule
+    rows = (S - 3, S)
+    lists = [oracle.kept_list(art, h, i) for h in range(H) for i in range(*rows)]
+    true_ptr = np.concatenate([[0], np.cumsum([len(x) for x in lists])]).astype(np.int64)
+    n2 = int(true_ptr[-1])
+    cap2 = n2 // 3
+    p2 = B.MaskParams(B.DAM_FROM_PATTERNS, H, 0, S, 128, 128, rows[0], rows[1], 0.5, 1e-8, 0.3, 0.8, float("nan"))
+    ws2 = B.mask_workspace(p2, "cuda")
+    ptr2 = torch.zeros(H * 3 + 1, dtype=torch.int32, device="cuda")
+    idx2 = torch.full((n2,), -7, dtype=torch.int32, device="cuda")
+    o2 = B.MaskOut()
+    o2.kept_ptr, o2.kept_idx, o2.kept_capacity, o2.kept_total = ptr2.data_ptr(), idx2.data_ptr(), cap2, total.data_ptr()
+    B.dam_mask_build(p2, None, None, torch.from_numpy(dflag).cuda(), torch.from_numpy(vflag).cuda(), o2, ws2)
+    torch.cuda.synchronize()
+    assert int(total.item()) == n2
+    assert np.array_equal(ptr2.cpu().numpy().astype(np.int64), np.minimum(true_ptr, cap2))
+    assert np.array_equal(idx2.cpu().numpy()[:cap2], np.concatenate(lists)[:cap2]) and (idx2[cap2:] == -7).all()
 
 
 @pytest.mark.parametrize("grouped", [False, True])

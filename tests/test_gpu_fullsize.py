@@ -2,7 +2,9 @@
 masks from patterns), c4 (128k prefill, masks from a 4096 x 4096 capture map) and c5 (decode at
 64k, batch 16). What the oracle cannot recompute whole within a test's time is checked on seeded
 samples it computes one by one: query-tile rows of the block index for every head, (head, row)
-pairs of the attention output for every head, plus the ragged ends.
+pairs of the attention output for every head, plus the ragged ends. c3's outputs are compared row
+by row in full in test_gpu_prefill.py; c4's block index is compared in full for every head, its
+outputs on every row of two heads and 2048 seeded rows of each head.
 
 Progress lines are printed with pytest's capture switched off: the c4 case is quiet for a while."""
 import sys
@@ -39,28 +41,6 @@ def say(msg):
         print(f"[fullsize {time.time() - T0:6.1f}s] {msg}", file=sys.stderr, flush=True)
 
 
-def check_tile_rows(art, mask, S, jobs):
-    """Block index and tile bits of the (head, query-tile row) pairs in jobs against the oracle."""
-    from concurrent.futures import ThreadPoolExecutor
-    g_ptr = mask.blk_row_ptr.cpu().numpy().astype(np.int64)
-    col = mask.blk_col.cpu().numpy()
-    kind = mask.blk_kind.cpu().numpy()
-
-    def want(job):
-        h, qt = job
-        return oracle.block_index(art, S, 128, 128, heads=[h], qt_range=(qt, qt + 1), workers=1)
-
-    with ThreadPoolExecutor(max_workers=WORKERS) as ex:
-        res = list(ex.map(want, jobs))
-    for (h, qt), (rp, c, k, bits) in zip(jobs, res):
-        a, b = g_ptr[h, qt], g_ptr[h, qt + 1]
-        assert b - a == rp[0, 1], f"tile count head {h} row {qt}"
-        assert np.array_equal(col[a:b], c), f"blk_col head {h} row {qt}"
-        assert np.array_equal(kind[a:b], k), f"blk_kind head {h} row {qt}"
-        if b > a:
-            assert np.array_equal(u64(mask.tile_bits[a:b]), bits), f"tile_bits head {h} row {qt}"
-
-
 def check_heads_in_full(art, mask, S, heads):
     g_ptr = mask.blk_row_ptr.cpu().numpy().astype(np.int64)
     for h in heads:
@@ -70,7 +50,8 @@ def check_heads_in_full(art, mask, S, heads):
         assert np.array_equal(mask.blk_col[a:b].cpu().numpy(), c), f"blk_col head {h}"
         assert np.array_equal(mask.blk_kind[a:b].cpu().numpy(), k), f"blk_kind head {h}"
         assert np.array_equal(u64(mask.tile_bits[a:b]), bits), f"tile_bits head {h}"
-        say(f"head {h}: {b - a} tiles identical")
+        if h % 8 == 7:
+            say(f"heads up to {h}: identical ({b - a} tiles in head {h})")
 
 
 def check_rows(Q, K, V, art, out, lse, hs, rs):
@@ -189,28 +170,28 @@ def test_c4_full_size():
         f"within tolerance of the threshold {theta:.3e}")
     assert n_diff <= 0.05 * n_near + 64
     del A, fused
-    # the S-sized outputs: one head in full, and for every head the tile rows around the L boundary,
-    # the last one and seeded random ones
-    check_heads_in_full(art, mask, S, [int(np.random.default_rng(44).integers(0, H))])
+    # the S-sized outputs: the block index and the tile bits of every head in full, streamed head by head (the oracle
+    # regenerates a head's tiles; the whole pool is never held twice)
+    check_heads_in_full(art, mask, S, range(H))
     rng = np.random.default_rng(45)
     nQt = S // 128
-    jobs = [(h, int(qt)) for h in range(H)
-            for qt in np.concatenate([[0, L // 128 - 1, L // 128, nQt - 1], rng.integers(0, nQt, 4)])]
-    check_tile_rows(art, mask, S, jobs)
-    say("c4: sampled tile rows of every head identical; prefill")
+    say("c4: block index and tile bits of every head identical; prefill")
     q, k, v = dev(Q, "bf16")[None], dev(K, "bf16")[None], dev(V, "bf16")[None]
     out, lse = B.dam_sparse_attn_prefill(q, k, v, mask, want_lse=True)
     torch.cuda.synchronize()
     say("c4: prefill done; oracle rows")
-    n = 64 * H
-    hs = np.repeat(np.arange(H, dtype=np.int32), 64)
-    rs = rng.integers(0, S, n).astype(np.int64)
-    rs[::64] = S - 1
-    rs[1::64] = 0
-    rs[2::64] = L - 1
-    rs[3::64] = L
+    # every row of two heads, and 2048 seeded rows of every head (the ends and the rows around L among them)
+    full_heads = [int(x) for x in rng.choice(H, 2, replace=False)]
+    hs = np.concatenate([np.repeat(np.array(full_heads, np.int32), S), np.repeat(np.arange(H, dtype=np.int32), 2048)])
+    rnd = rng.integers(0, S, 2048 * H).astype(np.int64)
+    rnd[::2048] = S - 1
+    rnd[1::2048] = 0
+    rnd[2::2048] = L - 1
+    rnd[3::2048] = L
+    rs = np.concatenate([np.tile(np.arange(S, dtype=np.int64), 2), rnd])
+    n = len(hs)
     err = check_rows(Q, K, V, art, out, lse, hs, rs)
-    say(f"c4: {n} sampled rows, max abs err {err:.2e}")
+    say(f"c4: every row of heads {full_heads} and 2048 rows of every head ({n} rows), max abs err {err:.2e}")
     # the same with the matched columns gathered into tiles of their own (the method's stripes are many here)
     n_plain = mask.n_tiles
     del mask, out, lse

@@ -248,7 +248,7 @@ def test_capacity_overflow_reports_total_and_writes_nothing_past_it():
     art = oracle.from_patterns(d, v)
     row_ptr, col, kind, bits = oracle.block_index(art, S, 128, 128)
     n = len(col)
-    cap = n // 2
+    cap = n // 3          # inside head 0's tiles
     p = B.MaskParams(B.DAM_FROM_PATTERNS, H, 0, S, 128, 128, 0, 0, 0.5, 1e-8, 0.3, 0.8, float("nan"))
     ws = B.mask_workspace(p, "cuda")
     o = B.MaskOut()
@@ -265,6 +265,28 @@ def test_capacity_overflow_reports_total_and_writes_nothing_past_it():
     assert np.array_equal(bc.cpu().numpy()[:cap], col[:cap]) and (bc.cpu().numpy()[cap:] == -7).all()
     assert (bk.cpu().numpy()[cap:] == 9).all() and (tb.cpu().numpy()[cap:] == -1).all()
     assert np.array_equal(u64(tb)[:cap], bits[:cap])
+    # the offsets are cut to the capacity: the index lists exactly the first `cap` tiles and stays consistent
+    assert np.array_equal(rp.cpu().numpy().astype(np.int64), np.minimum(row_ptr, cap))
+    # ... so it can be handed to the attention kernel as it is: rows whose query tile lies before the cut come out
+    # as from the whole index, and nothing is read past the buffers (sized to the capacity here)
+    small = B.Mask(H=H, L=0, S=S, tile_m=128, tile_n=128, blk_row_ptr=rp, blk_col=bc[:cap].clone(), blk_kind=bk[:cap].clone(),
+                   tile_bits=tb[:cap].clone(), n_tiles=cap)
+    whole = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=H, L=0, S=S, diag_in=torch.from_numpy(d).cuda(),
+                         vert_in=torch.from_numpy(v).cuda())
+    g = torch.Generator().manual_seed(3)
+    q, k, vv = (torch.randn((1, H, S, 128), generator=g).to(torch.bfloat16).cuda() for _ in range(3))
+    got = B.dam_sparse_attn_prefill(q, k, vv, small)
+    want = B.dam_sparse_attn_prefill(q, k, vv, whole)
+    torch.cuda.synchronize()
+    assert not torch.isnan(got.float()).any()
+    first_cut = next(qt for qt in range(5) if row_ptr[0, qt + 1] > cap)      # head 0's first query tile that lost tiles
+    assert first_cut >= 1 and torch.equal(got[0, 0, :128 * first_cut], want[0, 0, :128 * first_cut])
+    # a sizing call (no tile buffers) reports the true offsets
+    o2 = B.MaskOut()
+    o2.blk_row_ptr, o2.blk_total = rp.data_ptr(), tot.data_ptr()
+    B.dam_mask_build(p, None, None, torch.from_numpy(d).cuda(), torch.from_numpy(v).cuda(), o2, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(rp.cpu().numpy().astype(np.int64), row_ptr) and int(tot.item()) == n
 
 
 def test_c2_mask_full_size_bit_exact():
