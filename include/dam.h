@@ -283,12 +283,24 @@ int dam_mask_build_from_qk(const dam_mask_params *params, const dam_capture_para
  * lse[i] = -inf. Query head h reads KV head h / (hq / hkv).
  * dtype DAM_BF16: bf16 in, fp32 accumulation on the matrix cores, bf16 out (round to nearest even);
  *                 head_dim 128, tiles 128 x 128; the rows of one K or V head must span less than
- *                 4 GiB (seq * stride[2] * 2 bytes), otherwise DAM_ERR_UNSUPPORTED.
+ *                 4 GiB (seq * stride[2] * 2 bytes), otherwise DAM_ERR_UNSUPPORTED. The softmax weights
+ *                 are rounded to bf16 for the second product (see also DAM_ATTN_RUNNING_REFERENCE).
  * dtype DAM_F32:  fp32 throughout; head_dim 64 or 128, tiles of 64 or 128 in either direction.
  * A block index built with DAM_MASK_GATHER_COLUMNS is taken as it is: a tile index >= ceil(seq / tile_n)
  * names a gathered tile whose key slots are the columns in gather_idx (the bf16 kernel first copies
  * those K / V rows of every head into the workspace, so that such a tile is loaded like any other).
  * ---------------------------------------------------------------------------------------------- */
+/* dam_attn_params.flags */
+typedef enum {
+  DAM_ATTN_RUNNING_REFERENCE = 1 /* bf16 kernel: evaluate every row with the running-maximum softmax. Without the
+                                    flag the kernel first evaluates exp2(logit * log2 e) with no reference at all
+                                    (two instructions per weight; exact while the weights fit fp32 / bf16, which
+                                    share their 8 exponent bits), checks every row's sum of weights, and repeats
+                                    the query tiles in which a sum left [2^-100, 2^100] with the running maximum.
+                                    The results of that second pass are the flag's. Set it for inputs whose
+                                    scaled logits are known to lie beyond about +-60: it saves the first pass. */
+} dam_attn_flags;
+
 typedef struct {
   int32_t batch, hq, hkv, seq, head_dim;
   int32_t dtype;        /* dam_dtype of q, k, v and out                                           */
@@ -301,6 +313,7 @@ typedef struct {
   int32_t gather_rows;    /* block index with gathered column tiles: an upper bound, a multiple of
                              tile_n, of gather_cnt[h] rounded up to tile_n over all heads (the rows of
                              the gathered K / V copies kept in the workspace); 0 otherwise           */
+  int32_t flags;          /* bit set of dam_attn_flags                                            */
 } dam_attn_params;
 
 /* The block-index outputs of dam_mask_build for the hq query heads (device pointers). Device data
@@ -439,6 +452,20 @@ int dam_kv_compact(const dam_evict_params *params, const int32_t *window, const 
 int dam_kv_remap_lists(const dam_evict_params *params, const int32_t *window, const int32_t *col_ptr,
                        const int32_t *cols, const int32_t *kept_ptr, const int32_t *kept_idx,
                        int32_t *kept_slot, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Measurement helpers (no passage of the paper: they measure the chip's own ceilings, printed by the
+ * benchmark next to the published peaks its roofline fractions divide by).
+ *
+ * dam_probe_mfma: `workgroups` workgroups of four waves, each wave issuing iters * 16
+ *   v_mfma_f32_32x32x16_bf16 (32768 flop each) into four independent accumulators and nothing else.
+ *   operands: device, 8 KiB of bf16 values (the A and B fragments); sink: device, one float (never
+ *   written in practice). Flop launched: workgroups * 4 * iters * 16 * 32768.
+ * dam_probe_stream_read: reads `bytes` (a multiple of 32 KiB is read completely) from src with 16-byte
+ *   loads and discards them. src device, 16-byte aligned; sink device, one word.
+ * Both only enqueue on `stream`; the caller times them. */
+int dam_probe_mfma(const void *operands, float *sink, int32_t workgroups, int32_t iters, void *stream);
+int dam_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, int32_t workgroups, void *stream);
 
 /* Library version, for the loader's sanity check. */
 int dam_version(void);

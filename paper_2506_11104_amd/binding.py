@@ -23,6 +23,7 @@ DAM_FROM_ATTN_MAP, DAM_FROM_PATTERNS = 0, 1
 DAM_MASK_SKIP_FULL_TILE_BITS = 1
 DAM_MASK_GATHER_COLUMNS = 2
 DAM_MASK_GROUP_LISTS = 4
+DAM_ATTN_RUNNING_REFERENCE = 1
 TRANSFORMS = {"boxcox": 0, "raw_sum": 1, "average": 2, "log": 3, "yeo_johnson": 4, "zscore": 5, "minmax": 6,
               "sqrt": 7, "arcsinh": 8}
 
@@ -60,7 +61,7 @@ class AttnParams(ctypes.Structure):
                 ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3), ("v_stride", ctypes.c_int64 * 3),
                 ("o_stride", ctypes.c_int64 * 3), ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
-                ("gather_rows", ctypes.c_int32)]
+                ("gather_rows", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class MaskView(ctypes.Structure):
@@ -92,7 +93,8 @@ class EvictParams(ctypes.Structure):
 EXPORTS = ["dam_gather_stride", "dam_kv_evict_workspace", "dam_kv_evict_plan", "dam_kv_compact", "dam_kv_remap_lists", "dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
            "dam_mask_build_from_qk_workspace", "dam_mask_build_from_qk", "dam_sparse_attn_prefill_workspace",
            "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode",
-           "dam_sparse_attn_decode_grouped_workspace", "dam_sparse_attn_decode_grouped", "dam_version"]
+           "dam_sparse_attn_decode_grouped_workspace", "dam_sparse_attn_decode_grouped", "dam_probe_mfma",
+           "dam_probe_stream_read", "dam_version"]
 
 _lib = None
 
@@ -143,6 +145,10 @@ def lib() -> ctypes.CDLL:
         L.dam_kv_compact.argtypes = [ctypes.POINTER(EvictParams), vp, vp, vp, vp, vp, vp, vp, vp]
         L.dam_kv_remap_lists.restype = ctypes.c_int
         L.dam_kv_remap_lists.argtypes = [ctypes.POINTER(EvictParams), vp, vp, vp, vp, vp, vp, vp]
+        L.dam_probe_mfma.restype = ctypes.c_int
+        L.dam_probe_mfma.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp]
+        L.dam_probe_stream_read.restype = ctypes.c_int
+        L.dam_probe_stream_read.argtypes = [vp, sz, vp, ctypes.c_int32, vp]
         L.dam_version.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -349,11 +355,11 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 def attn_params(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor, tile_m: int, tile_n: int,
-                scale: float = 0.0, gather_rows: int = 0) -> AttnParams:
+                scale: float = 0.0, gather_rows: int = 0, flags: int = 0) -> AttnParams:
     B, Hq, S, d = q.shape
     p = AttnParams()
     p.batch, p.hq, p.hkv, p.seq, p.head_dim = B, Hq, k.shape[1], S, d
-    p.dtype, p.scale, p.tile_m, p.tile_n, p.gather_rows = _dtype_code(q), scale, tile_m, tile_n, gather_rows
+    p.dtype, p.scale, p.tile_m, p.tile_n, p.gather_rows, p.flags = _dtype_code(q), scale, tile_m, tile_n, gather_rows, flags
     for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o)):
         assert t.stride(3) == 1
         setattr(p, name, (ctypes.c_int64 * 3)(*t.stride()[:3]))
@@ -366,13 +372,13 @@ def prefill_workspace(p: AttnParams, device) -> torch.Tensor:
 
 
 def dam_sparse_attn_prefill(q, k, v, mask: Mask, out=None, lse=None, scale: float = 0.0, ws=None,
-                            want_lse: bool = False):
+                            want_lse: bool = False, flags: int = 0):
     """q [B][Hq][S][d], k, v [B][Hkv][S][d] (d contiguous) -> out like q (and lse [B][Hq][S] f32)."""
     if out is None:
         out = torch.empty_like(q)
     if lse is None and want_lse:
         lse = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
-    p = attn_params(q, k, v, out, mask.tile_m, mask.tile_n, scale, mask.gather_rows)
+    p = attn_params(q, k, v, out, mask.tile_m, mask.tile_n, scale, mask.gather_rows, flags)
     if ws is None:
         ws = prefill_workspace(p, q.device)
     mv = mask.view()
@@ -509,3 +515,20 @@ def kv_remap_lists(plan: EvictionPlan, kept_ptr: torch.Tensor, kept_idx: torch.T
                                   _p(kept_idx), _p(out), _stream())
     _check("dam_kv_remap_lists", st)
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+def probe_mfma(operands: torch.Tensor, sink: torch.Tensor, workgroups: int, iters: int) -> float:
+    """Enqueues the matrix-instruction probe; returns the flop it launches."""
+    assert operands.numel() * operands.element_size() >= 8192
+    st = lib().dam_probe_mfma(_p(operands), _p(sink), workgroups, iters, _stream())
+    _check("dam_probe_mfma", st)
+    return workgroups * 4.0 * iters * 16 * 32768
+
+
+def probe_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int) -> int:
+    """Enqueues the streaming-read probe over the whole tensor; returns the bytes it reads."""
+    nbytes = src.numel() * src.element_size()
+    st = lib().dam_probe_stream_read(_p(src), nbytes, _p(sink), workgroups, _stream())
+    _check("dam_probe_stream_read", st)
+    return nbytes

@@ -38,6 +38,9 @@ namespace {
 using namespace dam;
 
 constexpr int kXcd = 8;
+// control words at the start of the bf16 kernel's workspace: the eight queue counters, then the redo list's
+// length and its read cursor; the list itself (one int2 per work item at most) starts at byte kCtlBytes
+constexpr int kRedoCount = 8, kRedoNext = 9, kCtlWords = 10, kCtlBytes = 256;
 
 struct AttnArgs {
   int B, Hq, Hkv, S, nQt, nKt, tile_m, tile_n, wpr;
@@ -182,12 +185,19 @@ struct Blk {
   int flags;       // bit 0: tile is full (no mask), bit 1: dummy, bit 2: gathered tile (offsets into the gathered copies)
 };
 
-template <int PH>
+// FAST: the softmax without a running maximum. A weight is exp2(logit * scale * log2 e) itself: one multiply and
+// one exponential per entry, no row maximum, no subtraction, no rescaling of O. (Folding the factor into the
+// bf16 queries would save the multiply, but rounds every logit by up to 2^-9 of its size: 8 % in the weight of a
+// logit of 70.) That is exact as long as the weights stay inside the range of fp32 and bf16 (both have 8
+// exponent bits); the kernel checks the row sums at the end of a work item and sends the item to the variant
+// with a running reference (FAST = false) when a sum left [2^-100, 2^100].
+// seen / seen_full: does this lane's row have a kept entry at all (an empty row is not a failed one).
+template <int PH, bool FAST>
 __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds, const bf16x8 (&qf)[8],
                                           f32x16 (&oacc)[4], const f32x16 &sA, f32x16 &sB,
                                           const unsigned (&pPrev)[8], unsigned (&pCur)[8], float &m_run,
-                                          float &l_run, int flags_next, int bits_addr, float c2, int kbase,
-                                          int vbase, int hf) {
+                                          float &l_run, unsigned &seen, int &seen_full, int flags_next, int bits_addr,
+                                          float c2, int kbase, int vbase, int hf) {
   // kbase ^ (c << 5) is this lane's address of chunk pair c of its K row, vbase ^ (db << 6) that of
   // dim block db in its V rows (the chunk permutations are XORs, see the layout note)
   int kaddr[8], vaddr[4];
@@ -200,19 +210,26 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   typedef __attribute__((ext_vector_type(8))) short s16x8;
   // The first product of the S_{b+1} chain. Accumulator e is key 8 (e / 4) + 4 hf + e % 4 of the block
   // and starts at 0 (kept) or -inf (masked); a full tile needs no mask words and starts from a literal
-  // zero (wave-uniform branch).
+  // zero (wave-uniform branch), and so does a block of a partial tile whose 32 x 32 entries of this wave
+  // are all kept (a band edge crosses only some of the sixteen such squares of a tile).
   const bf16x8 kf0 = lds_read_b128(lds, KS + kaddr[0]);
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (flags_next & 1) {
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (FAST) seen_full = 1;
     sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[0], zero, 0, 0, 0);
   } else {
     unsigned bits_next = *reinterpret_cast<const unsigned *>(lds + kBitsRing + PH * 1024 + bits_addr);
     if (flags_next & 2) bits_next = 0u;  // dummy block: nothing kept
-    const int inv = (int)~(bits_next >> (4 * hf));
-    // sign-extended one-bit field (0 or all ones), then the bits of -inf; the extract is written as an
-    // instruction because the compiler turns the builtin into a three-operation compare and select
-    mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
-    sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[0], sB, 0, 0, 0);
+    if (FAST) seen |= bits_next;
+    if (__builtin_amdgcn_ballot_w64(bits_next != 0xFFFFFFFFu) == 0) {
+      sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[0], zero, 0, 0, 0);
+    } else {
+      const int inv = (int)~(bits_next >> (4 * hf));
+      // sign-extended one-bit field (0 or all ones), then the bits of -inf; the extract is written as an
+      // instruction because the compiler turns the builtin into a three-operation compare and select
+      mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
+      sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf[0], sB, 0, 0, 0);
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
   // ---- operand fetches, in the order the MFMAs consume them
@@ -234,6 +251,35 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
     const u32x4 praw = {pPrev[4 * a2], pPrev[4 * a2 + 1], pPrev[4 * a2 + 2], pPrev[4 * a2 + 3]};
     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[a2][db]),
                                                        __builtin_bit_cast(bf16x8, praw), oacc[db], 0, 0, 0);
+  }
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  if (FAST) {
+    // ---- vector work: the weights of block b and their sum, nothing else
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(sA[e] * c2);
+      const float p1 = __builtin_amdgcn_exp2f(sA[e + 1] * c2);
+      pCur[e / 2] = pack_bf16(p0, p1);
+      // the row sum is taken over the rounded weights the P V product uses
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pCur[e / 2]), ones, l_run, false);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) asm volatile("" ::"v"(pCur[e]));
+    // ---- interleave: a few operand reads ahead, then per MFMA three VALU ops and the reads it needs
+    __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 12, 0);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      if (x > 0) {
+        __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_MFMA, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(DAM_SCHED_DSREAD, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    return;
   }
   // ---- vector work: online softmax of block b; one query per lane pair (lane, lane ^ 32)
   float mx = fmaxf(fmaxf(sA[0], sA[1]), sA[2]);
@@ -259,7 +305,6 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   const float m_old = m_run;
   m_run = m_new;
   float psum = 0.0f;
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
   for (int e = 0; e < 16; e += 2) {
     const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sA[e], c2, -off));
@@ -299,24 +344,109 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
   l_run += psum;
 }
 
+// The FAST iteration laid out by hand in eight segments, one per pair of products (S chain step x, P V step x).
+// The wave issues in order, so what stands between the last product of one iteration and the first of the next
+// is time the matrix pipe of this wave idles: the bookkeeping of an iteration (decoding the next descriptor,
+// issuing the five copies, fetching the descriptor after that) therefore sits inside the stream of products,
+// one piece per segment (bk(x)), behind the operand reads (the copies are volatile statements that LDS reads do
+// not move across), and only the flag test, the wait for the copies, the barrier and the first operand reads
+// remain between two iterations.
+template <int PH, class Bk>
+__device__ __forceinline__ void pipe_iter_seg(const unsigned char *__restrict__ lds, const bf16x8 (&qf)[8],
+                                              f32x16 (&oacc)[4], const f32x16 &sA, f32x16 &sB,
+                                              const unsigned (&pPrev)[8], unsigned (&pCur)[8], float &l_run,
+                                              unsigned &seen, int &seen_full, int flags_next, int bits_addr, float c2,
+                                              int kbase, int vbase, int hf, Bk &&bk) {
+  int kaddr[8], vaddr[4];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) kaddr[c] = kbase ^ (c << 5);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) vaddr[db] = vbase ^ (db << 6);
+  constexpr int KS = PH * kBlkBytes;                          // slot of K_{b+1}
+  constexpr int VS = kVRing + ((PH + 2) & 3) * kBlkBytes;     // slot of V_{b-1}
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  bf16x8 kf[8];
+  s16x8 vf[2][4];
+  auto fetch = [&](int x) {
+    kf[x] = lds_read_b128(lds, KS + kaddr[x]);
+    const int a2 = x >> 2, db = x & 3;
+    const s16x4 r0 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16) * 256);
+    const s16x4 r1 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16 + 8) * 256);
+    vf[a2][db] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+  // ---- the operands of the first four segments, and this row's mask word of the block
+  const bool full_tile = (flags_next & 1) != 0;
+  unsigned bits_next = 0xFFFFFFFFu;
+  if (!full_tile) bits_next = *reinterpret_cast<const unsigned *>(lds + kBitsRing + PH * 1024 + bits_addr);
+#pragma unroll
+  for (int x = 0; x < 4; ++x) fetch(x);
+  __builtin_amdgcn_sched_barrier(0);
+  if (full_tile) {
+    seen_full = 1;
+  } else {
+    if (flags_next & 2) bits_next = 0u;  // dummy block: nothing kept
+    seen |= bits_next;
+  }
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    const int a2 = x >> 2, db = x & 3;
+    // P_{b-1} V_{b-1}, step x (first: it needs no mask)
+    const u32x4 praw = {pPrev[4 * a2], pPrev[4 * a2 + 1], pPrev[4 * a2 + 2], pPrev[4 * a2 + 3]};
+    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[a2][db]),
+                                                       __builtin_bit_cast(bf16x8, praw), oacc[db], 0, 0, 0);
+    // S_{b+1} chain, step x. Accumulator e is key 8 (e / 4) + 4 hf + e % 4 of the block and starts at 0 (kept)
+    // or -inf (masked); a block whose 32 x 32 entries of this wave are all kept starts from a literal zero
+    if (x == 0) {
+      if (__builtin_amdgcn_ballot_w64(bits_next != 0xFFFFFFFFu) == 0) {
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], zero, 0, 0, 0);
+      } else {
+        const int inv = (int)~(bits_next >> (4 * hf));
+        mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], sB, 0, 0, 0);
+      }
+    } else {
+      sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], sB, 0, 0, 0);
+    }
+    if (x < 4) fetch(x + 4);
+    // the weights of two entries of block b and their part of the row sum
+    {
+      const float p0 = __builtin_amdgcn_exp2f(sA[2 * x] * c2);
+      const float p1 = __builtin_amdgcn_exp2f(sA[2 * x + 1] * c2);
+      pCur[x] = pack_bf16(p0, p1);
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pCur[x]), ones, l_run, false);
+      asm volatile("" ::"v"(pCur[x]));
+    }
+    bk(std::integral_constant<int, 0>{} , x);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // RAGGED: the sequence length is not a multiple of the block size, so the last block of a row of tiles
 // may reach past the end of K and V.
 // GATHER: the block index may hold gathered column tiles (tile index >= nKt), whose K / V rows come from
 // the per-head gathered copies.
-template <bool RAGGED, bool GATHER>
+// FAST: the softmax without a running maximum (see pipe_iter). Work items come from the eight queues; an item
+// in which some row's sum of weights left the safe range is appended to the redo list (ctl[kRedoCount], then
+// `redo`), and the FAST = false instantiation, launched behind this one, takes exactly those items and overwrites
+// their rows. With well-scaled inputs the list stays empty.
+template <bool RAGGED, bool GATHER, bool FAST>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_prefill_bf16_pipe(
     AttnArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ k,
     const __hip_bfloat16 *__restrict__ v, const int *__restrict__ row_ptr, const int *__restrict__ blk_col,
     const uint8_t *__restrict__ blk_kind, const uint64_t *__restrict__ tile_bits, __hip_bfloat16 *__restrict__ out,
-    float *__restrict__ lse, int *__restrict__ queue_next, const __hip_bfloat16 *__restrict__ kgath,
+    float *__restrict__ lse, int *__restrict__ ctl, int2 *__restrict__ redo, const __hip_bfloat16 *__restrict__ kgath,
     const __hip_bfloat16 *__restrict__ vgath) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   __shared__ int s_item[2];
   __shared__ int s_wsum[4];
+  __shared__ int s_bad;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hf = lane >> 5;
   const float c2 = a.scale * 1.4426950408889634f;
+  if (FAST && tid == 0) s_bad = 0;
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds;
 
   // LDS byte offsets of this lane's operand fragments inside a block (layout note above), chunk pair 0
@@ -344,21 +474,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int G = a.Hq / a.Hkv, n_pairs = a.B * a.Hkv, per_pair = G * a.nQt;
   const int my_xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);  // XCC_ID, 4 bits
   int hop = 0;
+  int prev_item = -1, prev_queue = 0;  // (thread 0 only) the item just finished
   while (true) {
-    __syncthreads();  // previous item: every wave is done with the LDS rings and with s_item
+    __syncthreads();  // previous item: every wave is done with the LDS rings, with s_item and with s_bad
     if (tid == 0) {
       int item = -1, queue = 0;
-      for (; hop < kXcd; ++hop) {
-        queue = (my_xcd + hop) & (kXcd - 1);
-        const int pairs_here = (n_pairs - queue + kXcd - 1) / kXcd;  // pairs p with p % 8 == queue
-        const int got = atomicAdd(&queue_next[queue], 1);
-        if (got < pairs_here * per_pair) {
-          item = got;
-          break;
+      if (FAST) {
+        if (s_bad) {  // some row of the previous item needs the running reference: hand the item over
+          redo[atomicAdd(&ctl[kRedoCount], 1)] = make_int2(prev_item, prev_queue);
+          s_bad = 0;
+        }
+        for (; hop < kXcd; ++hop) {
+          queue = (my_xcd + hop) & (kXcd - 1);
+          const int pairs_here = (n_pairs - queue + kXcd - 1) / kXcd;  // pairs p with p % 8 == queue
+          const int got = atomicAdd(&ctl[queue], 1);
+          if (got < pairs_here * per_pair) {
+            item = got;
+            break;
+          }
+        }
+      } else {
+        const int got = atomicAdd(&ctl[kRedoNext], 1);
+        if (got < ctl[kRedoCount]) {  // (written by the kernel before this one)
+          const int2 e = redo[got];
+          item = e.x;
+          queue = e.y;
         }
       }
       s_item[0] = item;
       s_item[1] = queue;
+      prev_item = item;
+      prev_queue = queue;
     }
     __syncthreads();
     const int item = __builtin_amdgcn_readfirstlane(s_item[0]), queue = __builtin_amdgcn_readfirstlane(s_item[1]);
@@ -473,6 +619,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[db][e] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;  // running max (raw logits) and this lane's part of the row sum
+    unsigned seen = 0u;                     // FAST: union of the mask words of this lane's row, and whether a full
+    int seen_full = 0;                      // tile was met: together "the row has a kept entry"
 
     if (t1 > t0) {
       // Q fragments: B operand of S^T = K Q^T. Chunk c covers dims 16c .. 16c+15; this lane holds dims
@@ -524,14 +672,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         auto step = [&](auto ph) {
           constexpr int PH = decltype(ph)::value;
           const int flag_cur = d[(PH + 3) & 3].flags;  // block b, whose descriptor is replaced now
-          d[(PH + 3) & 3] = decode(pre_raw);           // block b+4
-          copy_k(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});  // five copies per wave and iteration, always
-          copy_bits(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});
-          copy_v(d[(PH + 1) & 3], std::integral_constant<int, (PH + 1) & 3>{});  // block b+2
-          pipe_iter<PH>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], m_run,
-                        l_run, d[PH].flags, bits_addr, c2, kbase, vbase, hf);
-          if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
-          pre_raw = list_read(++cursor);      // block b+5, decoded at the start of the next iteration
+          if constexpr (FAST) {
+            // the bookkeeping of this iteration, dealt out over the segments of the product stream: the copies
+            // only behind the last operand reads (segments 0 .. 3 issue those of segments 4 .. 7)
+            auto bk = [&](auto, int x) {
+              if (x == 2) d[(PH + 3) & 3] = decode(pre_raw);           // block b+4
+              if (x == 4) copy_k(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});  // five copies per wave and iteration, always
+              if (x == 5) copy_bits(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});
+              if (x == 6) copy_v(d[(PH + 1) & 3], std::integral_constant<int, (PH + 1) & 3>{});  // block b+2
+              if (x == 7) pre_raw = list_read(++cursor);               // block b+5 (a read past the list returns its dummy)
+            };
+            pipe_iter_seg<PH>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], l_run, seen,
+                              seen_full, d[PH].flags, bits_addr, c2, kbase, vbase, hf, bk);
+            if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
+          } else {
+            d[(PH + 3) & 3] = decode(pre_raw);           // block b+4
+            copy_k(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});  // five copies per wave and iteration, always
+            copy_bits(d[(PH + 3) & 3], std::integral_constant<int, (PH + 3) & 3>{});
+            copy_v(d[(PH + 1) & 3], std::integral_constant<int, (PH + 1) & 3>{});  // block b+2
+            pipe_iter<PH, FAST>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], m_run,
+                                l_run, seen, seen_full, d[PH].flags, bits_addr, c2, kbase, vbase, hf);
+            if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
+            pre_raw = list_read(++cursor);      // block b+5, decoded at the start of the next iteration
+          }
           // K_{b+2}, its mask words and V_b (issued two iterations ago) must have landed; the ten
           // youngest copies (this iteration's and the previous one's) may stay in flight
           // (wait and barrier as one statement: the library barrier would add a fence that waits for
@@ -552,6 +715,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // 32 db + 8 (e / 4) + 4 hf + e % 4 of this lane's query.
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    if (FAST) {
+      // a row with a kept entry whose sum of weights is zero, tiny, huge, infinite or NaN: its logits lie outside
+      // what exp2 without a reference can carry (|logit * log2 e| of the order of 100)
+      const bool bad = qlive && (seen != 0u || seen_full) && !(l_tot >= 0x1p-100f && l_tot <= 0x1p100f);
+      if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) s_bad = 1;  // read by thread 0 after the loop's barrier
+    }
     if (qlive) {
       __hip_bfloat16 *op = out + wb * a.o_sb + whq * a.o_sh + (int64_t)qrow * a.o_ss;
 #pragma unroll
@@ -565,7 +734,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
       if (lse && hf == 0)
         lse[((int64_t)wb * a.Hq + whq) * a.S + qrow] =
-            l_tot > 0.0f ? (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+            l_tot > 0.0f ? ((FAST ? 0.0f : m_run * c2) + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
     }
   }  // next work item
 }
@@ -577,7 +746,7 @@ __global__ __launch_bounds__(256) void k_gather_kv(AttnArgs a, const __hip_bfloa
                                                    __hip_bfloat16 *__restrict__ kgath, __hip_bfloat16 *__restrict__ vgath,
                                                    int *__restrict__ queue_next) {
   // (also resets the work queues of the attention kernel that follows: one launch less per call)
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < kXcd) queue_next[threadIdx.x] = 0;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < kCtlWords) queue_next[threadIdx.x] = 0;
   const int bh = blockIdx.y, b = bh / a.Hq, hq = bh % a.Hq, hkv = hq / (a.Hq / a.Hkv);
   const int s = blockIdx.x * 16 + (threadIdx.x >> 4), chunk = threadIdx.x & 15;
   if (s >= a.gather_rows) return;
@@ -593,7 +762,27 @@ __global__ __launch_bounds__(256) void k_gather_kv(AttnArgs a, const __hip_bfloa
 }
 
 __global__ void k_zero_queues(int *queue_next) {
-  if (threadIdx.x < kXcd) queue_next[threadIdx.x] = 0;
+  if (threadIdx.x < kCtlWords) queue_next[threadIdx.x] = 0;
+}
+
+// Every work item onto the redo list, in the order the queues would hand them out (DAM_ATTN_RUNNING_REFERENCE:
+// the caller asks for the variant with a running reference from the start).
+__global__ void k_list_all_items(AttnArgs a, int *__restrict__ ctl, int2 *__restrict__ redo) {
+  const int n_pairs = a.B * a.Hkv, per_pair = (a.Hq / a.Hkv) * a.nQt;
+  const int rounds = (n_pairs + kXcd - 1) / kXcd * per_pair;
+  int n_q[kXcd], total = 0;
+  for (int x = 0; x < kXcd; ++x) {
+    n_q[x] = (n_pairs - x + kXcd - 1) / kXcd * per_pair;  // items of queue x
+    total += n_q[x];
+  }
+  for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < rounds * kXcd; e += gridDim.x * blockDim.x) {
+    const int queue = e % kXcd, item = e / kXcd;
+    if (item >= n_q[queue]) continue;
+    int at = 0;  // valid entries before (item, queue) in round-robin order
+    for (int x = 0; x < kXcd; ++x) at += min(n_q[x], item + (x < queue ? 1 : 0));
+    redo[at] = make_int2(item, queue);
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) ctl[kRedoCount] = total;
 }
 
 int validate(const dam_attn_params *p, const void *q, const void *k, const void *v, const dam_mask_view *mk,
@@ -610,6 +799,7 @@ int validate(const dam_attn_params *p, const void *q, const void *k, const void 
     return DAM_ERR_INVALID_ARG;
   }
   if (!(p->scale >= 0.0f)) return DAM_ERR_INVALID_ARG;
+  if (p->flags & ~DAM_ATTN_RUNNING_REFERENCE) return DAM_ERR_INVALID_ARG;
   const int align = p->dtype == DAM_BF16 ? 8 : 4;
   const int64_t *sets[4] = {p->q_stride, p->k_stride, p->v_stride, p->o_stride};
   for (auto s : sets)
@@ -648,11 +838,20 @@ AttnArgs make_args(const dam_attn_params *p) {
 
 }  // namespace
 
+// bytes of the redo list: an int2 per (batch, query head, query tile), rounded up to 256
+static size_t redo_bytes(const dam_attn_params *p) {
+  const size_t items = (size_t)p->batch * p->hq * (size_t)((p->seq + p->tile_m - 1) / p->tile_m);
+  return (items * sizeof(int2) + 255) / 256 * 256;
+}
+
 extern "C" size_t dam_sparse_attn_prefill_workspace(const dam_attn_params *p) {
   if (!p || p->batch < 1 || p->hkv < 1 || p->hq < 1 || p->seq < 1 || p->gather_rows < 0) return 0;
   if (p->dtype != DAM_BF16) return 0;
-  // the eight work-queue counters of the bf16 kernel, then the gathered K and V copies (rows at the caches' strides)
-  return 256 + (size_t)p->batch * p->hq * p->gather_rows * (size_t)(p->k_stride[2] + p->v_stride[2]) * sizeof(__hip_bfloat16);
+  if (p->hq % p->hkv || p->tile_m < 64) return 0;
+  // the control words of the bf16 kernel (queue counters, redo list length and cursor), the redo list (one entry per
+  // work item at most), then the gathered K and V copies (rows at the caches' strides)
+  return kCtlBytes + redo_bytes(p) +
+         (size_t)p->batch * p->hq * p->gather_rows * (size_t)(p->k_stride[2] + p->v_stride[2]) * sizeof(__hip_bfloat16);
 }
 
 extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, const void *k, const void *v,
@@ -683,30 +882,44 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
     return DAM_ERR_DEVICE;
-  int *queue_next = static_cast<int *>(ws);
-  __hip_bfloat16 *kgath = reinterpret_cast<__hip_bfloat16 *>(static_cast<char *>(ws) + 256);
+  int *ctl = static_cast<int *>(ws);
+  int2 *redo = reinterpret_cast<int2 *>(static_cast<char *>(ws) + kCtlBytes);
+  __hip_bfloat16 *kgath = reinterpret_cast<__hip_bfloat16 *>(static_cast<char *>(ws) + kCtlBytes + redo_bytes(p));
   __hip_bfloat16 *vgath = kgath + (size_t)p->batch * p->hq * a.gather_rows * (size_t)a.k_ss;
   if (a.gather_rows > 0)
     k_gather_kv<<<dim3((a.gather_rows + 15) / 16, p->batch * p->hq), 256, 0, st>>>(
         a, (const __hip_bfloat16 *)k, (const __hip_bfloat16 *)v, mk->gather_idx,
-        kgath, vgath, queue_next);
+        kgath, vgath, ctl);
   else
-    k_zero_queues<<<1, 64, 0, st>>>(queue_next);
+    k_zero_queues<<<1, 64, 0, st>>>(ctl);
   const int persistent = std::min(blocks, 2 * n_cu);  // two workgroups fit a CU (registers and LDS)
   const bool ragged = p->seq % kBlkKeys != 0, gather = a.gather_rows > 0;
   using Kernel = void (*)(AttnArgs, const __hip_bfloat16 *, const __hip_bfloat16 *, const __hip_bfloat16 *, const int *,
-                          const int *, const uint8_t *, const uint64_t *, __hip_bfloat16 *, float *, int *,
+                          const int *, const uint8_t *, const uint64_t *, __hip_bfloat16 *, float *, int *, int2 *,
                           const __hip_bfloat16 *, const __hip_bfloat16 *);
-  static const Kernel kernels[4] = {k_prefill_bf16_pipe<false, false>, k_prefill_bf16_pipe<true, false>,
-                                    k_prefill_bf16_pipe<false, true>, k_prefill_bf16_pipe<true, true>};
+  static const Kernel kernels[2][4] = {
+      {k_prefill_bf16_pipe<false, false, false>, k_prefill_bf16_pipe<true, false, false>,
+       k_prefill_bf16_pipe<false, true, false>, k_prefill_bf16_pipe<true, true, false>},
+      {k_prefill_bf16_pipe<false, false, true>, k_prefill_bf16_pipe<true, false, true>,
+       k_prefill_bf16_pipe<false, true, true>, k_prefill_bf16_pipe<true, true, true>}};
   const int which = (ragged ? 1 : 0) + (gather ? 2 : 0);
-  // (idempotent; set on every call rather than remembered in a static)
-  if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[which]), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          kPipeLds) != hipSuccess)
-    return DAM_ERR_DEVICE;
-  kernels[which]<<<persistent, 256, kPipeLds, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
-                                                    (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col, mk->blk_kind,
-                                                    mk->tile_bits, (__hip_bfloat16 *)out, lse, queue_next, kgath, vgath);
+  const bool reference_only = (p->flags & DAM_ATTN_RUNNING_REFERENCE) != 0;
+  // first the softmax without a running maximum over every work item; then the variant with one over the items
+  // the first pass put on the redo list (none for well-scaled inputs: its workgroups then leave at once)
+  for (int fast = 1; fast >= 0; --fast) {
+    // (idempotent; set on every call rather than remembered in a static)
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernels[fast][which]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kPipeLds) != hipSuccess)
+      return DAM_ERR_DEVICE;
+    if (fast && reference_only) {
+      k_list_all_items<<<std::min((blocks + 255) / 256, 256), 256, 0, st>>>(a, ctl, redo);
+      continue;
+    }
+    kernels[fast][which]<<<persistent, 256, kPipeLds, st>>>(a, (const __hip_bfloat16 *)q, (const __hip_bfloat16 *)k,
+                                                            (const __hip_bfloat16 *)v, mk->blk_row_ptr, mk->blk_col,
+                                                            mk->blk_kind, mk->tile_bits, (__hip_bfloat16 *)out, lse, ctl,
+                                                            redo, kgath, vgath);
+  }
   return launch_status();
 }
 

@@ -28,20 +28,20 @@ def gpu_mask_from_art(art, S, tm, tn, flags=0):
                         diag_in=torch.from_numpy(d).cuda(), vert_in=torch.from_numpy(v).cuda(), true_bits=tb, flags=flags)
 
 
-def compare(Q, K, V, art, mask, dtype, batch=1, heads_rows=None):
+def compare(Q, K, V, art, mask, dtype, batch=1, heads_rows=None, flags=0, scale=0.0):
     Hq, S, d = Q.shape
     q, k, v = dev(Q, dtype)[None], dev(K, dtype)[None], dev(V, dtype)[None]
     if batch > 1:   # the mask is shared over the batch: entry b gets the inputs rolled by b heads
         q = torch.cat([q.roll(b, 1) for b in range(batch)], 0).contiguous()
         k = k.expand(batch, -1, -1, -1).contiguous()
         v = v.expand(batch, -1, -1, -1).contiguous()
-    out, lse = B.dam_sparse_attn_prefill(q, k, v, mask, want_lse=True)
+    out, lse = B.dam_sparse_attn_prefill(q, k, v, mask, want_lse=True, flags=flags, scale=scale)
     torch.cuda.synchronize()
     out = out.float().cpu().numpy()
     lse = lse.cpu().numpy()
     assert not np.isnan(out).any()
     if heads_rows is None:
-        O, LSE = oracle.attend_prefill(Q, K, V, art)
+        O, LSE = oracle.attend_prefill(Q, K, V, art, scale=scale or None)
         err = np.abs(out[0] - O).max()
         fin = np.isfinite(LSE)
         assert np.array_equal(np.isneginf(lse[0]), ~fin)
@@ -49,7 +49,7 @@ def compare(Q, K, V, art, mask, dtype, batch=1, heads_rows=None):
         assert (out[0][~fin] == 0).all()
     else:
         hs, rs = heads_rows
-        O, LSE = oracle.attend_rows(Q[hs, rs], K, V, art, Hq, hs, rs)
+        O, LSE = oracle.attend_rows(Q[hs, rs], K, V, art, Hq, hs, rs, scale=scale or None)
         err = np.abs(out[0][hs, rs] - O).max()
         fin = np.isfinite(LSE)
         lerr = np.abs(lse[0][hs, rs][fin] - LSE[fin]).max() if fin.any() else 0.0
@@ -291,3 +291,67 @@ def test_tiny_sequences_bf16(S):
     for flags in (0, B.DAM_MASK_GATHER_COLUMNS):
         mask = gpu_mask_from_art(art, S, 128, 128, flags=flags)
         compare(Q, K, V, art, mask, "bf16")
+
+
+# ---------------------------------------------------------------------------------------------
+# The bf16 kernel's two softmax variants: without a running maximum first (the weights are exp2 of the
+# logits themselves), then, for the query tiles in which a row's sum of weights left the safe range, with one.
+def _qkv(rng, Hq, Hkv, S, d=128, qs=1.0):
+    Q = wl.to_storage(rng.standard_normal((Hq, S, d)).astype(np.float32) * qs, "bf16")
+    K = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((Hkv, S, d)).astype(np.float32), "bf16")
+    return Q, K, V
+
+
+@pytest.mark.parametrize("S,L,flags", [(1000, 90, 0), (1300, 0, B.DAM_MASK_GATHER_COLUMNS), (384, 0, 0)])
+def test_running_reference_variant_alone(S, L, flags):
+    """DAM_ATTN_RUNNING_REFERENCE: every work item goes through the variant with the running maximum (ragged
+    and exact lengths, gathered tiles, GQA, a batch of two)."""
+    rng = np.random.default_rng(71)
+    Q, K, V = _qkv(rng, 4, 2, S, qs=1.5)
+    art = random_patterns(rng, 4, S, L=L)
+    mask = gpu_mask_from_art(art, S, 128, 128, flags=flags | B.DAM_MASK_SKIP_FULL_TILE_BITS)
+    compare(Q, K, V, art, mask, "bf16", batch=2, flags=B.DAM_ATTN_RUNNING_REFERENCE)
+
+
+@pytest.mark.parametrize("scale,what", [(6.0, "overflow"), (40.0, "overflow and underflow"), (0.0, "one head only")])
+def test_rows_outside_the_range_of_the_plain_exponential_are_redone(scale, what):
+    """Logits far beyond what exp2 without a reference can carry: at scale 6 the logits have a standard deviation of
+    about 68 (weights up to 2^300 and down to 2^-300), at scale 40 every row overflows or underflows. The first pass
+    flags such rows (sum of weights infinite, NaN, tiny or zero), the second pass recomputes their query tiles, and the
+    results match the oracle like any others. "one head only": head 1's queries are multiplied by 64, head 0 and the
+    other batch entry stay ordinary, so both passes contribute rows to one output."""
+    rng = np.random.default_rng(72)
+    S = 700
+    Q, K, V = _qkv(rng, 2, 1, S)
+    if what == "one head only":
+        Q[1] = wl.to_storage(Q[1] * 64.0, "bf16")
+    art = random_patterns(rng, 2, S, L=0)
+    mask = gpu_mask_from_art(art, S, 128, 128)
+    compare(Q, K, V, art, mask, "bf16", batch=2, scale=scale)
+    # the same through the flag: both routes give the same bits for the rows the second pass handles
+    q, k, v = dev(Q, "bf16")[None], dev(K, "bf16")[None], dev(V, "bf16")[None]
+    a = B.dam_sparse_attn_prefill(q, k, v, mask, scale=scale)
+    b = B.dam_sparse_attn_prefill(q, k, v, mask, scale=scale, flags=B.DAM_ATTN_RUNNING_REFERENCE)
+    torch.cuda.synchronize()
+    if what != "one head only":
+        assert torch.equal(a, b)
+    else:
+        assert torch.equal(a[0, 1], b[0, 1]) and not torch.equal(a[0, 0], b[0, 0])
+
+
+def test_all_logits_far_below_zero_underflow_is_caught():
+    """Every kept logit of a row around -200 * log2(e): all weights flush to zero without a reference; the row has
+    kept keys, so its zero sum sends the tile to the second pass (an empty row's zero sum does not)."""
+    rng = np.random.default_rng(73)
+    S, d = 300, 128
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    Q = wl.to_storage(np.tile(u * 48.0, (1, S, 1)) + 0.05 * rng.standard_normal((1, S, d)).astype(np.float32), "bf16")
+    K = wl.to_storage(np.tile(-u * 48.0, (1, S, 1)) + 0.05 * rng.standard_normal((1, S, d)).astype(np.float32), "bf16")
+    V = wl.to_storage(rng.standard_normal((1, S, d)).astype(np.float32), "bf16")
+    dflag = np.zeros((1, S), np.uint8)
+    dflag[0, 2:9] = 1                                   # rows 0 and 1 keep nothing: empty rows among failed ones
+    art = oracle.from_patterns(dflag, np.zeros((1, S), np.uint8))
+    mask = gpu_mask_from_art(art, S, 128, 128)
+    compare(Q, K, V, art, mask, "bf16")
