@@ -21,7 +21,8 @@
  *   - Plain C. "device" pointers are HIP device addresses, "host" pointers are ordinary host memory.
  *     Parameter structs are host memory and are read before the call returns.
  *   - Ownership: every buffer (inputs, outputs, workspace) is allocated and freed by the caller.
- *     The library keeps no state between calls and allocates nothing.
+ *     The library keeps no state between calls and allocates nothing (one stated exception:
+ *     dam_sparse_attn_decode_grouped_static and its fixed scratch array).
  *   - Asynchrony: all device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream). No entry point synchronises the host. Device scalars written by a call
  *     (bmin, blk_total, kept_total) are valid once the caller has synchronised the stream.
@@ -397,6 +398,25 @@ int dam_sparse_attn_decode_grouped(const dam_decode_params *params, const void *
                                    const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
                                    const uint8_t *kept_member, int64_t max_kept, void *out, float *lse,
                                    void *ws, size_t ws_bytes, void *stream);
+
+/* dam_sparse_attn_decode_grouped for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation. The same kernels, with the
+ * partial results of the list splits kept in a fixed array of DAM_DECODE_STATIC_SCRATCH_BYTES bytes of
+ * device memory that belongs to the library (every GPU the library runs on holds its own copy until the
+ * process ends). The call allocates nothing and synchronises nothing; inputs and outputs are the
+ * caller's as before. A call whose dam_sparse_attn_decode_grouped_workspace() exceeds the array returns
+ * DAM_ERR_WORKSPACE and launches nothing. All calls on one GPU share that GPU's array: calls that may
+ * overlap there (different streams, several threads) race on it; calls on one stream do not. The array keeps
+ * the last call's contents; nothing in it has to start at zero (every split writes its partial result
+ * before the merge pass reads it). The first call made with a device current looks up the array's address on
+ * that device and keeps it: the only state the library holds.
+ * dam_sparse_attn_decode_grouped_static_limit() returns DAM_DECODE_STATIC_SCRATCH_BYTES. */
+#define DAM_DECODE_STATIC_SCRATCH_BYTES (8u << 20)
+size_t dam_sparse_attn_decode_grouped_static_limit(void);
+int dam_sparse_attn_decode_grouped_static(const dam_decode_params *params, const void *q, const void *kcache,
+                                          const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
+                                          const uint8_t *kept_member, int64_t max_kept, void *out, float *lse,
+                                          void *stream);
 
 /* ------------------------------------------------------------------------------------------------
  * dam_kv_evict_plan, dam_kv_compact, dam_kv_remap_lists: KV-cache eviction for decode

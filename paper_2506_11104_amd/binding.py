@@ -93,7 +93,8 @@ class EvictParams(ctypes.Structure):
 EXPORTS = ["dam_gather_stride", "dam_kv_evict_workspace", "dam_kv_evict_plan", "dam_kv_compact", "dam_kv_remap_lists", "dam_mask_build_workspace", "dam_mask_build", "dam_capture_workspace", "dam_capture_accumulate",
            "dam_mask_build_from_qk_workspace", "dam_mask_build_from_qk", "dam_sparse_attn_prefill_workspace",
            "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode",
-           "dam_sparse_attn_decode_grouped_workspace", "dam_sparse_attn_decode_grouped", "dam_probe_mfma",
+           "dam_sparse_attn_decode_grouped_workspace", "dam_sparse_attn_decode_grouped",
+           "dam_sparse_attn_decode_grouped_static_limit", "dam_sparse_attn_decode_grouped_static", "dam_probe_mfma",
            "dam_probe_stream_read", "dam_version"]
 
 _lib = None
@@ -135,6 +136,11 @@ def lib() -> ctypes.CDLL:
         L.dam_sparse_attn_decode_grouped.restype = ctypes.c_int
         L.dam_sparse_attn_decode_grouped.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, vp, i64, vp, vp,
                                                      vp, sz, vp]
+        L.dam_sparse_attn_decode_grouped_static_limit.restype = sz
+        L.dam_sparse_attn_decode_grouped_static_limit.argtypes = []
+        L.dam_sparse_attn_decode_grouped_static.restype = ctypes.c_int
+        L.dam_sparse_attn_decode_grouped_static.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, vp, i64, vp,
+                                                            vp, vp]
         L.dam_gather_stride.restype = ctypes.c_int32
         L.dam_gather_stride.argtypes = [ctypes.POINTER(MaskParams)]
         L.dam_kv_evict_workspace.restype = sz
@@ -447,6 +453,17 @@ def dam_sparse_attn_decode_grouped(q, kcache, vcache, kept_ptr, kept_idx, kept_m
                                               ws.numel(), _stream())
     _check("dam_sparse_attn_decode_grouped", st)
     return (out, lse) if (want_lse or lse is not None) else out
+
+
+def dam_sparse_attn_decode_grouped_static(q, kcache, vcache, kept_ptr, kept_idx, kept_member, max_kept: int, out,
+                                          lse=None, scale: float = 0.0, shared_lists: bool = False) -> None:
+    """dam_sparse_attn_decode_grouped without a workspace: the library's fixed scratch array holds the partial
+    results. The caller passes every buffer (out, lse): this wrapper allocates nothing either."""
+    assert kcache.stride() == vcache.stride()
+    p = decode_params(q, kcache, out, scale, shared_lists)
+    st = lib().dam_sparse_attn_decode_grouped_static(ctypes.byref(p), _p(q), _p(kcache), _p(vcache), _p(kept_ptr),
+                                                     _p(kept_idx), _p(kept_member), max_kept, _p(out), _p(lse), _stream())
+    _check("dam_sparse_attn_decode_grouped_static", st)
 
 
 # ---------------------------------------------------------------------------------------------

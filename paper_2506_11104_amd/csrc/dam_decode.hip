@@ -15,6 +15,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "dam_internal.h"
 
@@ -516,15 +517,12 @@ extern "C" size_t dam_sparse_attn_decode_grouped_workspace(const dam_decode_para
   return c.off;
 }
 
-extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const void *q, const void *kcache,
-                                              const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
-                                              const uint8_t *kept_member, int64_t max_kept, void *out, float *lse,
-                                              void *ws, size_t ws_bytes, void *stream_v) {
-  const int bad = validate(p, q, kcache, vcache, kept_ptr, kept_idx, max_kept, out);
-  if (bad != DAM_OK) return bad;
-  if (max_kept > 0 && !kept_member) return DAM_ERR_INVALID_ARG;
-  if (p->hq / p->hkv > 8) return DAM_ERR_UNSUPPORTED;  // member bits are a byte
-  if (!ws || ws_bytes < dam_sparse_attn_decode_grouped_workspace(p, max_kept)) return DAM_ERR_WORKSPACE;
+namespace {
+
+// The grouped-query decode behind both of its entry points: arguments already validated, ws large enough.
+int decode_grouped_run(const dam_decode_params *p, const void *q, const void *kcache, const void *vcache,
+                       const int32_t *kept_ptr, const int32_t *kept_idx, const uint8_t *kept_member, int64_t max_kept,
+                       void *out, float *lse, void *ws, hipStream_t st) {
   DecodeArgs a;
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity;
   bool mfma;
@@ -537,7 +535,6 @@ extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const 
   Carver c(ws);
   float *part_o = c.take<float>((size_t)a.B * a.Hq * a.splits * p->head_dim);
   float *part_ml = c.take<float>((size_t)a.B * a.Hq * a.splits * 2);
-  hipStream_t st = static_cast<hipStream_t>(stream_v);
   if (mfma) {
     // matrix-core partial pass, then the merge pass (also for one split: it normalises and stores)
     launch_decode_group_mfma(p, a.splits, a.scale, q, kcache, vcache, kept_ptr, kept_idx, kept_member, part_o, part_ml, st);
@@ -550,4 +547,70 @@ extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const 
     else launch_group<float, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
   }
   return launch_status();
+}
+
+int validate_grouped(const dam_decode_params *p, const void *q, const void *kcache, const void *vcache,
+                     const int32_t *kept_ptr, const int32_t *kept_idx, const uint8_t *kept_member, int64_t max_kept,
+                     const void *out) {
+  const int bad = validate(p, q, kcache, vcache, kept_ptr, kept_idx, max_kept, out);
+  if (bad != DAM_OK) return bad;
+  if (max_kept > 0 && !kept_member) return DAM_ERR_INVALID_ARG;
+  if (p->hq / p->hkv > 8) return DAM_ERR_UNSUPPORTED;  // member bits are a byte
+  return DAM_OK;
+}
+
+}  // namespace
+
+extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const void *q, const void *kcache,
+                                              const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
+                                              const uint8_t *kept_member, int64_t max_kept, void *out, float *lse,
+                                              void *ws, size_t ws_bytes, void *stream_v) {
+  const int bad = validate_grouped(p, q, kcache, vcache, kept_ptr, kept_idx, kept_member, max_kept, out);
+  if (bad != DAM_OK) return bad;
+  if (!ws || ws_bytes < dam_sparse_attn_decode_grouped_workspace(p, max_kept)) return DAM_ERR_WORKSPACE;
+  return decode_grouped_run(p, q, kcache, vcache, kept_ptr, kept_idx, kept_member, max_kept, out, lse, ws,
+                            static_cast<hipStream_t>(stream_v));
+}
+
+// ------------------------------------------------------------------------------------------------
+// dam_sparse_attn_decode_grouped for callers that cannot allocate: the partial results of the splits live in
+// a fixed array in device memory that belongs to the library instead of a caller's workspace.
+constexpr size_t kStaticScratchBytes = DAM_DECODE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+// the array's device address on each GPU (every GPU holds its own copy of the array at its own address);
+// looked up once per device, at the first call made with that device current
+std::atomic<void *> g_scratch_at[kMaxDevices];
+
+int scratch_address(void **at) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DAM_ERR_DEVICE;
+  void *ptr = g_scratch_at[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return DAM_ERR_DEVICE;
+    g_scratch_at[dev].store(ptr, std::memory_order_release);  // (two threads racing here store the same address)
+  }
+  *at = ptr;
+  return DAM_OK;
+}
+}  // namespace
+
+extern "C" size_t dam_sparse_attn_decode_grouped_static_limit(void) { return kStaticScratchBytes; }
+
+extern "C" int dam_sparse_attn_decode_grouped_static(const dam_decode_params *p, const void *q, const void *kcache,
+                                                     const void *vcache, const int32_t *kept_ptr,
+                                                     const int32_t *kept_idx, const uint8_t *kept_member,
+                                                     int64_t max_kept, void *out, float *lse, void *stream_v) {
+  const int bad = validate_grouped(p, q, kcache, vcache, kept_ptr, kept_idx, kept_member, max_kept, out);
+  if (bad != DAM_OK) return bad;
+  const size_t need = dam_sparse_attn_decode_grouped_workspace(p, max_kept);
+  if (need == 0 || need > kStaticScratchBytes) return DAM_ERR_WORKSPACE;  // the call does not fit the fixed array
+  void *ws = nullptr;
+  const int st = scratch_address(&ws);
+  if (st != DAM_OK) return st;
+  // nothing to clear: every split writes its partial result before the merge pass reads it
+  return decode_grouped_run(p, q, kcache, vcache, kept_ptr, kept_idx, kept_member, max_kept, out, lse, ws,
+                            static_cast<hipStream_t>(stream_v));
 }
