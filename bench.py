@@ -26,11 +26,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
-# HBM bytes per launch of the dominant kernels, measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs of this
-# script with --copy-calibration, scaled by what the same counters read for a plain 1 GiB copy: x2.00 and x1.00);
-# the summary with the commands is profiles/prefill_c3_decode_c5_hbm_traffic_pmc.txt. They belong to the default
-# workloads (c3 prefill, c5 decode) and are reported as the roofline objects' `traffic`.
-MEASURED_TRAFFIC_BYTES = {"k_prefill_bf16_pipe/c3": 2.31e9, "k_decode_group_mfma/c5": 5.15e8}
+# `traffic` in the roofline objects is null: this script does not read hardware counters. The HBM bytes per launch of
+# the dominant kernels, from rocprofv3 --pmc runs of this script (--copy-calibration gives the counters' scale), are
+# kept with their commands under profiles/.
 
 
 def parse():
@@ -42,6 +40,7 @@ def parse():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-maskmap", action="store_true")
+    ap.add_argument("--no-small", action="store_true", help="skip the c1 and c2 lines")
     ap.add_argument("--pause-before-decode", type=float, default=4.0, help="idle seconds before the decode section")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timings (profiler runs)")
@@ -157,11 +156,15 @@ def bench_prefill(args, w, torch, B, wl):
         step(evs[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    mask_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
-    attn_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
-    step_ms = wall * 1e3 / args.steps
+    # medians over the timed steps (HIP events on the launch stream); the mean of the host's clock over the same steps
+    # is kept beside them
+    mask_ms = float(np.median([e[0].elapsed_time(e[1]) for e in evs]))
+    attn_ms = float(np.median([e[1].elapsed_time(e[2]) for e in evs]))
+    step_ms = float(np.median([e[0].elapsed_time(e[2]) for e in evs]))
+    step_ms_wall = wall * 1e3 / args.steps
     assert int(total.item()) == n_tiles
 
+    flops_kept = 4.0 * d * nnz
     # the same prefill over the plain layout (every matched column in the ordinary tile it falls into), kernel alone
     plain = B.build_mask(mode=mode, H=H, L=L, S=S, tile_m=w.tile_m, tile_n=w.tile_n, lam=w.lam, eps=w.eps, tau=w.tau,
                          mu=w.mu, attn_sum=A, diag_in=d_in, vert_in=v_in, flags=B.DAM_MASK_SKIP_FULL_TILE_BITS)
@@ -169,15 +172,15 @@ def bench_prefill(args, w, torch, B, wl):
     plain_ms = timed_ms(lambda: B.dam_sparse_attn_prefill(q, k, v, plain, out=out, ws=ws_plain), 10, warm=2)
     plain_tiles = plain.n_tiles
     n_blocks = int(np.unpackbits((kinds >> 1)[:, None].astype(np.uint8), axis=1).sum())
+    plain_blocks = int(np.unpackbits((plain.blk_kind.cpu().numpy() >> 1)[:, None].astype(np.uint8), axis=1).sum())
     del plain
 
-    flops_kept = 4.0 * d * nnz
     flops_tiles = 4.0 * d * w.tile_m * w.tile_n * n_tiles
     mask_bytes = (n_tiles - n_full) * (w.tile_m * w.tile_n // 8) + 5 * n_tiles + 4 * H * (sized.blk_row_ptr.shape[1]) + 2 * H * S
     if A is not None:
         mask_bytes += 2 * H * L * (L + 1) + H * L * L // 8
     res = {
-        "step_ms": step_ms, "mask_build_ms": mask_ms, "prefill_ms": attn_ms, "nnz": nnz, "n_tiles": n_tiles,
+        "step_ms": step_ms, "step_ms_mean_host_clock": step_ms_wall, "mask_build_ms": mask_ms, "prefill_ms": attn_ms, "nnz": nnz, "n_tiles": n_tiles,
         "n_full_tiles": n_full, "density": nnz / causal, "tile_fill": nnz / (n_tiles * w.tile_m * w.tile_n),
         "tflops_kept_step": flops_kept / (step_ms * 1e-3) / 1e12,
         "tflops_kept_prefill": flops_kept / (attn_ms * 1e-3) / 1e12,
@@ -185,9 +188,10 @@ def bench_prefill(args, w, torch, B, wl):
         "mask_build_gbs": mask_bytes / (mask_ms * 1e-3) / 1e9, "mask_build_bytes": mask_bytes,
         "n_blocks": n_blocks, "tflops_blocks_prefill": 4.0 * d * w.tile_m * 32 * n_blocks / (attn_ms * 1e-3) / 1e12,
         "gathered_tiles": int((sized.blk_col >= (S + w.tile_n - 1) // w.tile_n).sum().item()),
-        "plain_layout": {"listed_tiles": plain_tiles, "prefill_ms_back_to_back": plain_ms,
-                         "tflops_listed_tiles": 4.0 * d * w.tile_m * w.tile_n * plain_tiles / (plain_ms * 1e-3) / 1e12,
-                         "frac_listed_tiles": 4.0 * d * w.tile_m * w.tile_n * plain_tiles / (plain_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "plain_layout": {"listed_tiles": plain_tiles, "key_blocks_of_32": plain_blocks, "prefill_ms_back_to_back": plain_ms,
+                         "tflops_kept_entries": flops_kept / (plain_ms * 1e-3) / 1e12,
+                         "tflops_issued_blocks": 4.0 * d * w.tile_m * 32 * plain_blocks / (plain_ms * 1e-3) / 1e12,
+                         "frac_issued_blocks": 4.0 * d * w.tile_m * 32 * plain_blocks / (plain_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
     }
     ctx = dict(Q=Q, K=K, V=V, dflag=dflag, vflag=vflag, A=A, sized=sized)
     return res, ctx
@@ -209,7 +213,8 @@ def bench_cpu_oracle(args, w, ctx, wl):
         t0 = time.perf_counter()
         _, _ = oracle.attend_rows(ctx["Q"][hs, rs], ctx["K"], ctx["V"], art, w.hq, hs, rs)
         dt = time.perf_counter() - t0
-        kept = sum(len(oracle.kept_list(art, int(h), int(r))) for h, r in zip(hs[:256], rs[:256])) / min(n, 256) * n
+        m = min(n, 4096)
+        kept = sum(len(oracle.kept_list(art, int(h), int(r))) for h, r in zip(hs[:m], rs[:m])) / m * n
         return dt, kept
 
     run(512)                                   # thread start-up, page faults
@@ -218,7 +223,7 @@ def bench_cpu_oracle(args, w, ctx, wl):
     dt, kept = run(n)
     return {"value": 4.0 * w.head_dim * kept / dt / 1e12, "unit": "TFLOP/s (kept entries)", "cores": oracle.threads(),
             "kind": "oracle", "sample": f"{n} random (head,row) pairs of {w.name}, {dt:.1f} s, fp64, kept entries "
-                                        f"estimated from 256 of them"}
+                                        f"estimated from 4096 of them"}
 
 
 def bench_decode(args, torch, B, wl):
@@ -404,12 +409,106 @@ def bench_decode(args, torch, B, wl):
                 "gbs_union": ub / (dec_us * 1e-6) / 1e9,
                 "roofline": {"bound": "hbm", "kernel": "k_decode_group_mfma", "achieved": ub / (dec_us * 1e-6) / 1e9,
                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ub / (dec_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
-                             "traffic": MEASURED_TRAFFIC_BYTES["k_decode_group_mfma/c5"],
+                             "traffic": None,
                              # `achieved` divides by the whole call (partial pass + merge pass) as timed by events inside
                              # the 256-step loop; the same call 50 times in a row, without events in between:
                              "achieved_back_to_back": ub / (main["decode_us_back_to_back"] * 1e-6) / 1e9,
                              "frac_back_to_back": ub / (main["decode_us_back_to_back"] * 1e-6) / 1e9 / PEAK_HBM_GBS},
                 "list_per_head_form": per_head, "kv_eviction": evict})
+    return res
+
+
+def bench_measured_peaks(torch, B):
+    """What this chip sustains on nothing but bf16 matrix instructions and on nothing but streaming reads, measured
+    in this run (dam_probe_mfma, dam_probe_stream_read): context for the published peaks the fractions divide by.
+    The matrix probe is given random operands (the clock a kernel sustains depends on how many bits toggle in the
+    multipliers: the chip is power-limited) and, for comparison, zeros."""
+    dev = "cuda"
+    sink = torch.zeros(4, device=dev)
+    out = {}
+    for name, ops in (("random_operands", (torch.randn(4096, device=dev) * 0.05).to(torch.bfloat16)),
+                      ("zero_operands", torch.zeros(4096, device=dev, dtype=torch.bfloat16))):
+        flop = [0.0]
+
+        def run():
+            flop[0] = B.probe_mfma(ops, sink, 1024, 1000)
+        ms = timed_ms(run, 5, warm=2)
+        out["mfma_bf16_tflops_" + name] = flop[0] / (ms * 1e-3) / 1e12
+    src = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(1)     # 4 GiB
+    isink = torch.zeros(4, dtype=torch.int32, device=dev)
+    ms = timed_ms(lambda: B.probe_stream_read(src, isink, 8192), 5, warm=2)
+    out["hbm_stream_read_gbs"] = src.numel() * 4 / (ms * 1e-3) / 1e9
+    out["note"] = ("1024 workgroups x 4 waves x 16000 v_mfma_f32_32x32x16_bf16, two waves per SIMD; 4 GiB read with 16-byte "
+                   "non-temporal loads")
+    del src
+    return out
+
+
+def bench_small_config(args, torch, B, wl, name):
+    """c1 (fp32, S = 256) and c2 (bf16, S = 4096): a step = mask build from the captured map + sparse prefill, and the
+    oracle's time for the same outputs (c1 also on one thread)."""
+    import oracle
+    w = wl.WORKLOADS[name]
+    dev = "cuda"
+    Q, K, V = wl.qkv_iid(w, std=1 / 8) if name == "c1" else wl.qkv_structured(w)
+    A_np = wl.capture_map(Q[:, :w.pcl], K[:, :w.pcl], w.pcl, w.hq // w.hkv)
+    A = torch.from_numpy(A_np).to(dev)
+    conv = (lambda x: torch.from_numpy(x)[None].to(dev)) if w.dtype == "f32" else \
+        (lambda x: torch.from_numpy(x).to(torch.bfloat16)[None].to(dev))
+    q, k, v = conv(Q), conv(K), conv(V)
+    sized = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=w.hq, L=w.pcl, S=w.seq, tile_m=w.tile_m, tile_n=w.tile_n, lam=w.lam,
+                         eps=w.eps, tau=w.tau, mu=w.mu, attn_sum=A)
+    torch.cuda.synchronize()
+    p = B.MaskParams(B.DAM_FROM_ATTN_MAP, w.hq, w.pcl, w.seq, w.tile_m, w.tile_n, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
+    ws_mask = B.mask_workspace(p, dev)
+    o = B.MaskOut()
+    for nm in ("true_bits", "diag_cnt", "vert_cnt", "diag_flag", "vert_flag", "bmin", "blk_row_ptr", "blk_col", "blk_kind",
+               "tile_bits"):
+        setattr(o, nm, getattr(sized, nm).data_ptr())
+    total = torch.zeros(1, dtype=torch.int64, device=dev)
+    o.blk_capacity, o.blk_total = sized.n_tiles, total.data_ptr()
+    out = torch.empty_like(q)
+    ws_attn = B.prefill_workspace(B.attn_params(q, k, v, out, w.tile_m, w.tile_n), dev)
+
+    def step(ev):
+        ev[0].record()
+        B.dam_mask_build(p, A, None, None, None, o, ws_mask)
+        ev[1].record()
+        B.dam_sparse_attn_prefill(q, k, v, sized, out=out, ws=ws_attn)
+        ev[2].record()
+
+    for _ in range(3):
+        step(events(3))
+    torch.cuda.synchronize()
+    evs = [events(3) for _ in range(args.steps)]
+    for e in evs:
+        step(e)
+    torch.cuda.synchronize()
+    nnz = int(np.unpackbits(sized.tile_bits.cpu().numpy().view(np.uint8)).sum(dtype=np.int64))
+    step_ms = float(np.median([e[0].elapsed_time(e[2]) for e in evs]))
+    attn_ms = float(np.median([e[1].elapsed_time(e[2]) for e in evs]))
+    flops = 4.0 * w.head_dim * nnz
+    res = {"workload": f"{name}: {w.hq} Q / {w.hkv} KV heads, head_dim {w.head_dim}, seq {w.seq}, capture length {w.pcl}, "
+                       f"{w.dtype}, tiles {w.tile_m}x{w.tile_n}; step = mask build from the map + sparse prefill",
+           "step_ms": step_ms, "mask_build_ms": float(np.median([e[0].elapsed_time(e[1]) for e in evs])), "prefill_ms": attn_ms,
+           "nnz": nnz, "density": nnz / (w.hq * w.seq * (w.seq + 1) / 2), "listed_tiles": sized.n_tiles,
+           "tflops_kept_step": flops / (step_ms * 1e-3) / 1e12, "tflops_kept_prefill": flops / (attn_ms * 1e-3) / 1e12}
+    if not args.no_cpu:
+        art = oracle.derive(A_np, None, w.lam, w.eps, w.tau, w.mu)
+        t0 = time.perf_counter()
+        oracle.attend_prefill(Q, K, V, art)
+        dt = time.perf_counter() - t0
+        res["oracle"] = {"seconds": dt, "tflops_kept": flops / dt / 1e12, "cores": oracle.threads(), "what": "every output row, fp64"}
+        if name == "c1":
+            try:
+                from threadpoolctl import threadpool_limits
+                with threadpool_limits(limits=1, user_api="openmp"):
+                    t0 = time.perf_counter()
+                    oracle.attend_prefill(Q, K, V, art)
+                    dt1 = time.perf_counter() - t0
+                res["oracle_single_thread"] = {"seconds": dt1, "tflops_kept": flops / dt1 / 1e12, "cores": 1}
+            except Exception as e:     # the limiter is optional: without it only the all-threads time is reported
+                res["oracle_single_thread"] = {"unavailable": repr(e)}
     return res
 
 
@@ -530,7 +629,8 @@ def main():
     line = {
         "metric": "effective TFLOP/s on kept entries (mask build + sparse prefill per step, 32k prefill)",
         "value": res["tflops_kept_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": res["step_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": res["step_ms"], "ms_per_step_mean_host_clock": res["step_ms_mean_host_clock"],
+        "timing": "median of the timed steps, HIP events on the launch stream", "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 1 layer, {w.hq} Q / {w.hkv} KV heads, head_dim {w.head_dim}, seq {w.seq}, "
                                f"bf16, batch 1, heterogeneous per-head masks, tiles {w.tile_m}x{w.tile_n}",
@@ -540,12 +640,12 @@ def main():
         "ms_per_layer_prefill": res["prefill_ms"], "mask_build_ms": res["mask_build_ms"],
         "mask_build_gbs": res["mask_build_gbs"],
         "tflops_kept_entries_prefill_only": res["tflops_kept_prefill"],
-        "tflops_listed_tiles_prefill_only": res["tflops_tiles_prefill"],
+        "tflops_issued_blocks_prefill_only": res["tflops_blocks_prefill"],
         "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16_pipe", "achieved": res["tflops_kept_prefill"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": res["tflops_kept_prefill"] / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES["k_prefill_bf16_pipe/c3"] if args.workload == "c3" else None,
-                     "achieved_listed_tiles": res["tflops_tiles_prefill"],
-                     "frac_listed_tiles": res["tflops_tiles_prefill"] / PEAK_BF16_TFLOPS,
+                     "traffic": None,
+                     # the matrix work the kernel issues: 4 * head_dim * 128 * 32 per occupied 32-key block of a listed
+                     # tile (empty key quarters of a tile are skipped): the figure "on kept tiles"
                      "achieved_issued_blocks": res["tflops_blocks_prefill"],
                      "frac_issued_blocks": res["tflops_blocks_prefill"] / PEAK_BF16_TFLOPS,
                      "plain_layout": res["plain_layout"]},
@@ -554,6 +654,12 @@ def main():
         line["cpu_baseline"] = bench_cpu_oracle(args, w, ctx, wl)
     del ctx
     torch.cuda.empty_cache()
+    line["roofline"]["measured_on_this_chip"] = bench_measured_peaks(torch, B)
+    line["peaks_used"] = {"bf16_mfma_tflops": PEAK_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS, "source": "published"}
+    if not args.no_small:
+        line["c1"] = bench_small_config(args, torch, B, wl, "c1")
+        line["c2"] = bench_small_config(args, torch, B, wl, "c2")
+        torch.cuda.empty_cache()
     if not args.no_maskmap:
         line["mask_build_from_map"] = bench_mask_from_map(args, torch, B, wl, "c2")
         torch.cuda.empty_cache()

@@ -384,6 +384,63 @@ def group_lists(lists: Sequence[np.ndarray], group: int):
     return np.array(ptr, np.int64), np.array(idx, np.int32), np.array(member, np.uint8)
 
 
+def pattern_plan(diag_flag, vert_flag, group: int, S: Optional[int] = None):
+    """Merged decode lists that do not depend on the position, for rows of the pattern region (Sec. 4.3: row p
+    keeps key j <= p iff p - j is a matched diagonal or j is a matched column). diag_flag, vert_flag: [Hq][P] flags;
+    `group` consecutive query heads share a KV head; S: length of the problem (columns >= S do not exist; default P).
+    Per KV head the plan lists first every diagonal offset r matched by some head of the group, then every such
+    column c, each part in group + 1 runs, each ascending: patterns of two or more heads, then those of head 0
+    alone, of head 1 alone, ... An entry's value is -1 - r for a diagonal (it stands for key p - r at position p)
+    and c for a column; bit x of its member byte says that head x of the group has the pattern.
+    Returns (ptr [n_kv + 1] i64, val i32, member u8, table u8 [n_kv][P]) with table[g][r] = member bits of
+    diagonal r: at position p a column entry c serves the heads in member & ~table[g][p - c], the others meet
+    key c through their diagonal p - c already (Sec. 4.2.4: overlapping patterns are a union, a key counts once)."""
+    df, vf = _u8(diag_flag), _u8(vert_flag)
+    Hq, P = df.shape
+    assert Hq % group == 0 and 1 <= group <= 8
+    n_cols = P if S is None else min(P, S)
+    ptr, val, member = [0], [], []
+    table = np.zeros((Hq // group, P), np.uint8)
+    for g in range(Hq // group):
+        for part, flags, limit in (("diag", df, P), ("col", vf, n_cols)):
+            who = {}
+            for x in range(group):
+                for t in range(limit):
+                    if flags[g * group + x, t]:
+                        who[t] = who.get(t, 0) | (1 << x)
+            if part == "diag":
+                for r, m in who.items():
+                    table[g, r] = m
+            runs = [sorted(t for t, m in who.items() if bin(m).count("1") >= 2)]
+            for x in range(group):
+                runs.append(sorted(t for t, m in who.items() if m == 1 << x))
+            for run in runs:
+                val.extend((-1 - t) if part == "diag" else t for t in run)
+                member.extend(who[t] for t in run)
+        ptr.append(len(val))
+    return np.array(ptr, np.int64), np.array(val, np.int32), np.array(member, np.uint8), table
+
+
+def plan_row(plan, g: int, x: int, p: int) -> np.ndarray:
+    """The keys head x of KV head g keeps at position p according to a pattern plan: the decoding rule stated
+    in pattern_plan, ascending."""
+    ptr, val, member, table = plan
+    P = table.shape[1]
+    keys = []
+    for e in range(int(ptr[g]), int(ptr[g + 1])):
+        v, m = int(val[e]), int(member[e])
+        if v < 0:
+            j = p + 1 + v                       # p - r
+            if j >= 0 and (m >> x) & 1:
+                keys.append(j)
+        else:
+            if v <= p:
+                covered = int(table[g, p - v]) if p - v < P else 0
+                if ((m & ~covered) >> x) & 1:
+                    keys.append(v)
+    return np.array(sorted(keys), np.int32)
+
+
 # ---------------------------------------------------------------------------------------------
 @dataclass
 class EvictionPlan:

@@ -1,6 +1,7 @@
 """Pins of the oracle's masked attention (Sec. 3 and the end of Sec. 4.3) against library dense
 causal attention, a brute-force dense softmax, and identities any correct implementation obeys."""
 import numpy as np
+import pytest
 import torch
 
 import oracle
@@ -190,3 +191,60 @@ def test_group_lists_expand_back_to_the_lists_of_the_heads():
             assert (np.diff(run) >= 0).all()
             for r in range(group + 1):
                 assert (np.diff(seg[run == r]) > 0).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# Position-independent decode plans (oracle.pattern_plan): pinned by expanding them back into the rows of the
+# mask they stand for (Sec. 4.3), which the plain kept_list defines, and by a hand-worked example.
+def test_pattern_plan_worked_example():
+    P = 12
+    d = np.zeros((2, P), np.uint8)
+    v = np.zeros((2, P), np.uint8)
+    d[0, [0, 1, 5]] = 1          # head 0: diagonals 0, 1, 5
+    d[1, [0, 2]] = 1             # head 1: diagonals 0, 2
+    v[0, [0, 7]] = 1             # head 0: columns 0, 7
+    v[1, [0, 3]] = 1             # head 1: columns 0, 3
+    ptr, val, mem, table = oracle.pattern_plan(d, v, 2)
+    # diagonals: shared {0}; head 0 alone {1, 5}; head 1 alone {2}. columns: shared {0}; head 0 alone {7}; head 1 alone {3}
+    assert list(ptr) == [0, 7]
+    assert list(val) == [-1, -2, -6, -3, 0, 7, 3]
+    assert list(mem) == [3, 1, 1, 2, 3, 1, 2]
+    assert list(table[0]) == [3, 1, 2, 0, 0, 1, 0, 0, 0, 0, 0, 0]
+    plan = (ptr, val, mem, table)
+    # position 8: head 0 keeps 8, 7 (diagonals 0, 1), 3 (diagonal 5), columns 0 and 7 (7 is also its diagonal 1: once)
+    assert list(oracle.plan_row(plan, 0, 0, 8)) == [0, 3, 7, 8]
+    # head 1 keeps 8, 6 (diagonals 0, 2), columns 0 and 3
+    assert list(oracle.plan_row(plan, 0, 1, 8)) == [0, 3, 6, 8]
+    # position 1: diagonal 5 and column 7 do not exist yet; head 1's diagonal 2 neither
+    assert list(oracle.plan_row(plan, 0, 0, 1)) == [0, 1]
+    assert list(oracle.plan_row(plan, 0, 1, 1)) == [0, 1]
+
+
+@pytest.mark.parametrize("seed,G", [(1, 1), (2, 2), (3, 4), (4, 8)])
+def test_pattern_plan_expands_to_the_rows_of_the_mask(seed, G):
+    rng = np.random.default_rng(seed)
+    Hq, P = 2 * G, 300
+    d = (rng.random((Hq, P)) < 0.1).astype(np.uint8)
+    v = (rng.random((Hq, P)) < 0.1).astype(np.uint8)
+    d[:, :5] = 1                                   # a window every head has: many keys that are column and diagonal at once
+    v[:, :3] = 1
+    if Hq > 2:
+        d[2], v[2] = 0, 0                          # a head that keeps nothing
+    art = oracle.from_patterns(d, v)
+    plan = oracle.pattern_plan(d, v, G)
+    ptr, val, mem, table = plan
+    for g in range(Hq // G):
+        seg = slice(int(ptr[g]), int(ptr[g + 1]))
+        assert len(set(val[seg].tolist())) == ptr[g + 1] - ptr[g]            # every pattern once
+        assert (mem[seg] != 0).all() and (mem[seg] < (1 << G)).all()
+    for p in (0, 1, 4, 63, 64, 150, P - 1, P + 40, 2 * P + 7):
+        S = max(P, p + 1)
+        big = oracle.from_patterns(np.pad(d, ((0, 0), (0, S - P))), np.pad(v, ((0, 0), (0, S - P))))
+        for h in range(Hq):
+            want = oracle.kept_list(big, h, p)
+            got = oracle.plan_row(plan, h // G, h % G, p)
+            assert np.array_equal(got, want), (h, p)
+    # columns at or beyond the problem length are left out of a plan built for it
+    short = oracle.pattern_plan(d, v, G, S=100)
+    assert (short[1][short[1] >= 0] < 100).all() and np.array_equal(short[3], table)
+    del art
