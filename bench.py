@@ -360,7 +360,35 @@ def bench_decode(args, torch, B, wl):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e6 / n_steps, t_host * 1e6 / n_steps
 
+    def plan_form(n_steps):
+        """The same rows from a position-independent plan of the pattern masks (built once, outside the loop): a step
+        is one dam_sparse_attn_decode_patterns call, no list is built."""
+        plan = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False, group=G,
+                            plan=True)
+        torch.cuda.synchronize()
+        longest = int(np.diff(plan.kept_ptr.cpu().numpy()).max())
+        ws_p = B.decode_grouped_workspace(dp, longest, dev)
+
+        def step(s):
+            B.dam_sparse_attn_decode_patterns(qs[s], kc, vc, plan, w.seq - 1 + s, longest, out=out, ws=ws_p)
+
+        for s in range(3):
+            step(s)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(n_steps):          # (no events inside the loop: a pair per step costs 4-5 us of its ~95)
+            step(s)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        res = {"steps": n_steps, "us_per_step": wall * 1e6 / n_steps,
+               "plan_entries": int(plan.n_kept), "longest_list": longest,
+               "decode_us_back_to_back": timed_ms(lambda: step(0), 50) * 1e3}
+        if not args.no_graph:
+            res["us_per_step_graph_replay"] = graph_replay_ms(lambda: step(0), 50) * 1e3
+        return res
+
     main, (g_ptr, g_idx, g_bound) = form(True, steps)
+    planned = plan_form(steps)
     main["us_per_step_list_build_on_a_second_stream"], main["host_us_per_step_of_that_loop"] = overlapped(steps)
     # the merged lists of the first position, kept for the decode from the compacted cache below
     mg = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False,
@@ -415,6 +443,14 @@ def bench_decode(args, torch, B, wl):
                              "achieved_back_to_back": ub / (main["decode_us_back_to_back"] * 1e-6) / 1e9,
                              "frac_back_to_back": ub / (main["decode_us_back_to_back"] * 1e-6) / 1e9 / PEAK_HBM_GBS},
                 "list_per_head_form": per_head, "kv_eviction": evict})
+    # the step that builds no list: its whole duration (host clock over the loop) against the same union bytes
+    planned["gbs_union"] = ub / (planned["us_per_step"] * 1e-6) / 1e9
+    planned["roofline"] = {"bound": "hbm", "kernel": "k_decode_group_mfma<plan>", "achieved": planned["gbs_union"],
+                           "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": planned["gbs_union"] / PEAK_HBM_GBS, "traffic": None,
+                           "achieved_back_to_back": ub / (planned["decode_us_back_to_back"] * 1e-6) / 1e9,
+                           "frac_back_to_back": ub / (planned["decode_us_back_to_back"] * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                           "rows_read": planned["plan_entries"] * w.batch, "rows_in_the_union": int(ub // (w.head_dim * 2 * 2))}
+    res["pattern_plan_form"] = planned
     return res
 
 

@@ -87,7 +87,7 @@ typedef enum {
                                       tile instead of a tile of its own. Query tiles that start inside the
                                       true-mask block are listed as without the flag. Requires the outputs
                                       gather_idx and gather_cnt.                                          */
-  DAM_MASK_GROUP_LISTS = 4          /* kept lists for grouped-query decoding: one list per group of
+  DAM_MASK_GROUP_LISTS = 4,         /* kept lists for grouped-query decoding: one list per group of
                                       `group` consecutive maps (the query heads of one KV head) instead of
                                       one per map, so that a decode step reads every cached row once for
                                       the whole group. The list of a group holds each key kept by any of
@@ -97,6 +97,20 @@ typedef enum {
                                       keeps key kept_idx[e]. One row only (row_end = row_begin + 1);
                                       n_maps a multiple of group, 1 <= group <= 8; requires kept_member
                                       when kept_idx is given.                                              */
+  DAM_MASK_PATTERN_PLAN = 8         /* with DAM_MASK_GROUP_LISTS: the lists do not depend on the position and serve
+                                      every row of the pattern region (row p >= pcl keeps key j <= p iff p - j is a
+                                      matched diagonal or j is a matched column), so a decode loop builds them once
+                                      per mask instead of once per step. The list of a group holds first every
+                                      diagonal offset r matched by some map of the group, then every such column
+                                      c < min(P, seq), each part in G + 1 runs (patterns of two or more maps; of map
+                                      0 alone; of map 1 alone; ...), each run ascending in the key it stands for
+                                      (diagonals by descending offset). kept_idx[e] is -1 - r for a diagonal (key
+                                      p - r at position p) and c for a column; kept_member[e] names the maps that
+                                      have the pattern. plan_table [n_maps / group][P] u8 (required): the member
+                                      bits of every diagonal offset; at position p a column entry c serves the maps
+                                      in kept_member & ~plan_table[group][p - c], the others meet key c through
+                                      their diagonal already. row_begin / row_end are ignored. Consumed by
+                                      dam_sparse_attn_decode_patterns.                                       */
 } dam_mask_flags;
 
 typedef enum {
@@ -204,6 +218,7 @@ typedef struct {
                           below S of each map, ascending, then -1 up to the stride                        */
   int32_t *gather_cnt; /* [H] i32: how many                                                                */
   uint8_t *kept_member; /* [kept_capacity] u8: DAM_MASK_GROUP_LISTS, which maps of the group keep each entry */
+  uint8_t *plan_table;  /* [H / group][P] u8: DAM_MASK_PATTERN_PLAN, member bits of every diagonal offset       */
 } dam_mask_out;
 
 /* Row length of gather_idx: min(P, S) rounded up to a multiple of tile_n, P the length of the pattern
@@ -398,6 +413,24 @@ int dam_sparse_attn_decode_grouped(const dam_decode_params *params, const void *
                                    const void *vcache, const int32_t *kept_ptr, const int32_t *kept_idx,
                                    const uint8_t *kept_member, int64_t max_kept, void *out, float *lse,
                                    void *ws, size_t ws_bytes, void *stream);
+
+/* dam_sparse_attn_decode_grouped from a position-independent plan (dam_mask_build with DAM_MASK_GROUP_LISTS |
+ * DAM_MASK_PATTERN_PLAN and group = hq / hkv): the row at position `pos` of every head's pattern mask (Sec. 4.3:
+ * key j <= pos is kept iff pos - j is a matched diagonal or j is a matched column), evaluated without building a
+ * list for that row. Every sequence of the batch sits at position pos (the query is the token at index pos, keys
+ * 0 .. pos are cached); the plan belongs to the heads and serves the whole batch and every position of the
+ * pattern region (pos >= the capture length of the masks; masks given as patterns: any pos).
+ * plan_ptr [hkv + 1] i32, plan_val i32, plan_member u8: the kept_ptr / kept_idx / kept_member of that build;
+ * plan_table u8 [hkv][n_flags]: its plan_table; n_flags: the length P of the pattern flags.
+ * max_entries: upper bound of the length of one list of the plan. bf16, head_dim 128, hq / hkv <= 8 (otherwise
+ * DAM_ERR_UNSUPPORTED). Workspace: dam_sparse_attn_decode_grouped_workspace with shared_lists = 1 and
+ * max_kept = max_entries. Everything else as dam_sparse_attn_decode_grouped; the results are those of the
+ * list form on the lists of row pos, up to the order of the fp32 sums. */
+int dam_sparse_attn_decode_patterns(const dam_decode_params *params, const void *q, const void *kcache,
+                                    const void *vcache, const int32_t *plan_ptr, const int32_t *plan_val,
+                                    const uint8_t *plan_member, const uint8_t *plan_table, int32_t n_flags,
+                                    int32_t pos, int64_t max_entries, void *out, float *lse, void *ws,
+                                    size_t ws_bytes, void *stream);
 
 /* dam_sparse_attn_decode_grouped for callers that cannot allocate device memory or bring a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid allocation. The same kernels, with the

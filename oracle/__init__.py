@@ -389,8 +389,9 @@ def pattern_plan(diag_flag, vert_flag, group: int, S: Optional[int] = None):
     keeps key j <= p iff p - j is a matched diagonal or j is a matched column). diag_flag, vert_flag: [Hq][P] flags;
     `group` consecutive query heads share a KV head; S: length of the problem (columns >= S do not exist; default P).
     Per KV head the plan lists first every diagonal offset r matched by some head of the group, then every such
-    column c, each part in group + 1 runs, each ascending: patterns of two or more heads, then those of head 0
-    alone, of head 1 alone, ... An entry's value is -1 - r for a diagonal (it stands for key p - r at position p)
+    column c, each part in group + 1 runs: patterns of two or more heads, then those of head 0 alone, of head 1
+    alone, ... Each run is ascending in the key it stands for at any position: diagonals by descending offset,
+    columns by ascending index. An entry's value is -1 - r for a diagonal (it stands for key p - r at position p)
     and c for a column; bit x of its member byte says that head x of the group has the pattern.
     Returns (ptr [n_kv + 1] i64, val i32, member u8, table u8 [n_kv][P]) with table[g][r] = member bits of
     diagonal r: at position p a column entry c serves the heads in member & ~table[g][p - c], the others meet
@@ -411,9 +412,10 @@ def pattern_plan(diag_flag, vert_flag, group: int, S: Optional[int] = None):
             if part == "diag":
                 for r, m in who.items():
                     table[g, r] = m
-            runs = [sorted(t for t, m in who.items() if bin(m).count("1") >= 2)]
+            down = part == "diag"          # descending offsets are ascending keys
+            runs = [sorted((t for t, m in who.items() if bin(m).count("1") >= 2), reverse=down)]
             for x in range(group):
-                runs.append(sorted(t for t, m in who.items() if m == 1 << x))
+                runs.append(sorted((t for t, m in who.items() if m == 1 << x), reverse=down))
             for run in runs:
                 val.extend((-1 - t) if part == "diag" else t for t in run)
                 member.extend(who[t] for t in run)

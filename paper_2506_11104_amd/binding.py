@@ -23,6 +23,7 @@ DAM_FROM_ATTN_MAP, DAM_FROM_PATTERNS = 0, 1
 DAM_MASK_SKIP_FULL_TILE_BITS = 1
 DAM_MASK_GATHER_COLUMNS = 2
 DAM_MASK_GROUP_LISTS = 4
+DAM_MASK_PATTERN_PLAN = 8
 DAM_ATTN_RUNNING_REFERENCE = 1
 TRANSFORMS = {"boxcox": 0, "raw_sum": 1, "average": 2, "log": 3, "yeo_johnson": 4, "zscore": 5, "minmax": 6,
               "sqrt": 7, "arcsinh": 8}
@@ -53,7 +54,7 @@ class MaskOut(ctypes.Structure):
                 ("tile_bits", ctypes.c_void_p), ("blk_capacity", ctypes.c_int64), ("blk_total", ctypes.c_void_p),
                 ("dense_bits", ctypes.c_void_p), ("kept_ptr", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
                 ("kept_capacity", ctypes.c_int64), ("kept_total", ctypes.c_void_p), ("gather_idx", ctypes.c_void_p),
-                ("gather_cnt", ctypes.c_void_p), ("kept_member", ctypes.c_void_p)]
+                ("gather_cnt", ctypes.c_void_p), ("kept_member", ctypes.c_void_p), ("plan_table", ctypes.c_void_p)]
 
 
 class AttnParams(ctypes.Structure):
@@ -94,7 +95,7 @@ EXPORTS = ["dam_gather_stride", "dam_kv_evict_workspace", "dam_kv_evict_plan", "
            "dam_mask_build_from_qk_workspace", "dam_mask_build_from_qk", "dam_sparse_attn_prefill_workspace",
            "dam_sparse_attn_prefill", "dam_sparse_attn_decode_workspace", "dam_sparse_attn_decode",
            "dam_sparse_attn_decode_grouped_workspace", "dam_sparse_attn_decode_grouped",
-           "dam_sparse_attn_decode_grouped_static_limit", "dam_sparse_attn_decode_grouped_static", "dam_probe_mfma",
+           "dam_sparse_attn_decode_patterns", "dam_sparse_attn_decode_grouped_static_limit", "dam_sparse_attn_decode_grouped_static", "dam_probe_mfma",
            "dam_probe_stream_read", "dam_version"]
 
 _lib = None
@@ -136,6 +137,9 @@ def lib() -> ctypes.CDLL:
         L.dam_sparse_attn_decode_grouped.restype = ctypes.c_int
         L.dam_sparse_attn_decode_grouped.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, vp, i64, vp, vp,
                                                      vp, sz, vp]
+        L.dam_sparse_attn_decode_patterns.restype = ctypes.c_int
+        L.dam_sparse_attn_decode_patterns.argtypes = [ctypes.POINTER(DecodeParams), vp, vp, vp, vp, vp, vp, vp,
+                                                      ctypes.c_int32, ctypes.c_int32, i64, vp, vp, vp, sz, vp]
         L.dam_sparse_attn_decode_grouped_static_limit.restype = sz
         L.dam_sparse_attn_decode_grouped_static_limit.argtypes = []
         L.dam_sparse_attn_decode_grouped_static.restype = ctypes.c_int
@@ -197,6 +201,7 @@ class Mask:
     kept_ptr: Optional[torch.Tensor] = None
     kept_idx: Optional[torch.Tensor] = None
     kept_member: Optional[torch.Tensor] = None  # u8 beside kept_idx (DAM_MASK_GROUP_LISTS)
+    plan_table: Optional[torch.Tensor] = None   # u8 [H / group][P] (DAM_MASK_PATTERN_PLAN)
     n_kept: int = 0
     gather_idx: Optional[torch.Tensor] = None   # [H][gather_stride] i32 (DAM_MASK_GATHER_COLUMNS)
     gather_cnt: Optional[torch.Tensor] = None   # [H] i32
@@ -265,13 +270,17 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
                true_bits: Optional[torch.Tensor] = None, blocks: bool = True, tile_bits: bool = True,
                dense: bool = False, rows: Optional[Tuple[int, int]] = None, device="cuda",
                qk: Optional[Tuple[torch.Tensor, torch.Tensor]] = None, scale: float = 0.0, flags: int = 0, transform: int = 0,
-               group: int = 0) -> Mask:
+               group: int = 0, plan: bool = False) -> Mask:
     """Convenience wrapper: allocates the outputs, sizes the tile pool / kept lists with a first
     call (blk_col == NULL), then fills them with a second. Only allocation and marshalling.
     qk = (q [H][L][d], k [Hkv][L][d]) selects dam_mask_build_from_qk (one captured sequence, no map).
-    group > 0 sets DAM_MASK_GROUP_LISTS: rows must name one row; kept_ptr has H / group + 1 entries."""
+    group > 0 sets DAM_MASK_GROUP_LISTS: rows must name one row; kept_ptr has H / group + 1 entries.
+    plan = True (with group > 0) sets DAM_MASK_PATTERN_PLAN: position-independent lists and plan_table, no rows."""
     if group > 0:
         flags |= DAM_MASK_GROUP_LISTS
+    if plan:
+        assert group > 0 and not rows
+        flags |= DAM_MASK_PATTERN_PLAN
     dev = torch.device(device)
     p = MaskParams(mode, H, L, S, tile_m, tile_n, rows[0] if rows else 0, rows[1] if rows else 0, lam, eps, tau, mu,
                    bmin_override, flags, transform, group)
@@ -311,17 +320,20 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
     if blocks:
         m.blk_row_ptr = torch.empty((H, nQt + 1), dtype=torch.int32, device=dev)
         o.blk_row_ptr, o.blk_total = _p(m.blk_row_ptr), totals[0:1].data_ptr()
-    if rows:
+    if rows or plan:
         n_lists = H // group if group > 0 else H * (rows[1] - rows[0])
         m.kept_ptr = torch.empty(n_lists + 1, dtype=torch.int32, device=dev)
         o.kept_ptr, o.kept_total = _p(m.kept_ptr), totals[1:2].data_ptr()
+    if plan:
+        m.plan_table = torch.empty((H // group, L if mode == DAM_FROM_ATTN_MAP else S), dtype=torch.uint8, device=dev)
+        o.plan_table = _p(m.plan_table)
     if dense:
         m.dense_bits = torch.empty((H, S, (S + 63) // 64), dtype=torch.int64, device=dev)
         o.dense_bits = _p(m.dense_bits)
     call(o)
     if m.gather_cnt is not None:
         m.gather_rows = (int(m.gather_cnt.max().item()) + tile_n - 1) // tile_n * tile_n
-    if blocks or rows:
+    if blocks or rows or plan:
         n_tiles, n_kept = (int(x) for x in totals.cpu())
         again = False
         if blocks and n_tiles > 0:
@@ -337,7 +349,7 @@ def build_mask(*, mode: int, H: int, L: int, S: int, tile_m: int = 128, tile_n: 
             m.blk_col = torch.empty(1, dtype=torch.int32, device=dev)
             m.blk_kind = torch.empty(1, dtype=torch.uint8, device=dev)
             m.tile_bits = torch.empty((1, tile_m, tile_n // 64), dtype=torch.int64, device=dev)
-        if rows and n_kept > 0:
+        if (rows or plan) and n_kept > 0:
             m.n_kept = n_kept
             m.kept_idx = torch.empty(n_kept, dtype=torch.int32, device=dev)
             o.kept_idx, o.kept_capacity = _p(m.kept_idx), n_kept
@@ -452,6 +464,25 @@ def dam_sparse_attn_decode_grouped(q, kcache, vcache, kept_ptr, kept_idx, kept_m
                                               _p(kept_idx), _p(kept_member), max_kept, _p(out), _p(lse), _p(ws),
                                               ws.numel(), _stream())
     _check("dam_sparse_attn_decode_grouped", st)
+    return (out, lse) if (want_lse or lse is not None) else out
+
+
+def dam_sparse_attn_decode_patterns(q, kcache, vcache, plan: "Mask", pos: int, max_entries: int, out=None, lse=None,
+                                    scale: float = 0.0, ws=None, want_lse: bool = False):
+    """Grouped decode at position pos from a position-independent plan (build_mask(..., group=G, plan=True))."""
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    assert kcache.stride() == vcache.stride()
+    p = decode_params(q, kcache, out, scale, True)
+    if ws is None:
+        ws = decode_grouped_workspace(p, max_entries, q.device)
+    st = lib().dam_sparse_attn_decode_patterns(ctypes.byref(p), _p(q), _p(kcache), _p(vcache), _p(plan.kept_ptr),
+                                               _p(plan.kept_idx), _p(plan.kept_member), _p(plan.plan_table),
+                                               plan.plan_table.shape[1], pos, max_entries, _p(out), _p(lse), _p(ws),
+                                               ws.numel(), _stream())
+    _check("dam_sparse_attn_decode_patterns", st)
     return (out, lse) if (want_lse or lse is not None) else out
 
 

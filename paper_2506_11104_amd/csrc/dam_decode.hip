@@ -522,7 +522,8 @@ namespace {
 // The grouped-query decode behind both of its entry points: arguments already validated, ws large enough.
 int decode_grouped_run(const dam_decode_params *p, const void *q, const void *kcache, const void *vcache,
                        const int32_t *kept_ptr, const int32_t *kept_idx, const uint8_t *kept_member, int64_t max_kept,
-                       void *out, float *lse, void *ws, hipStream_t st) {
+                       void *out, float *lse, void *ws, hipStream_t st, const uint8_t *plan_table = nullptr,
+                       int n_flags = 0, int pos = 0) {
   DecodeArgs a;
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity;
   bool mfma;
@@ -537,8 +538,11 @@ int decode_grouped_run(const dam_decode_params *p, const void *q, const void *kc
   float *part_ml = c.take<float>((size_t)a.B * a.Hq * a.splits * 2);
   if (mfma) {
     // matrix-core partial pass, then the merge pass (also for one split: it normalises and stores)
-    launch_decode_group_mfma(p, a.splits, a.scale, q, kcache, vcache, kept_ptr, kept_idx, kept_member, part_o, part_ml, st);
+    launch_decode_group_mfma(p, a.splits, a.scale, q, kcache, vcache, kept_ptr, kept_idx, kept_member, part_o, part_ml, st,
+                             plan_table, n_flags, pos);
     k_decode_merge<__hip_bfloat16, 128><<<a.B * a.Hq, 128, 0, st>>>(a, part_o, part_ml, static_cast<__hip_bfloat16 *>(out), lse);
+  } else if (plan_table) {
+    return DAM_ERR_UNSUPPORTED;  // plans are decoded by the matrix-core kernel only
   } else if (p->dtype == DAM_BF16) {
     if (p->head_dim == 128) launch_group<__hip_bfloat16, 128>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
     else launch_group<__hip_bfloat16, 64>(a, q, kcache, vcache, kept_ptr, kept_idx, kept_member, out, lse, part_o, part_ml, st);
@@ -570,6 +574,23 @@ extern "C" int dam_sparse_attn_decode_grouped(const dam_decode_params *p, const 
   if (!ws || ws_bytes < dam_sparse_attn_decode_grouped_workspace(p, max_kept)) return DAM_ERR_WORKSPACE;
   return decode_grouped_run(p, q, kcache, vcache, kept_ptr, kept_idx, kept_member, max_kept, out, lse, ws,
                             static_cast<hipStream_t>(stream_v));
+}
+
+// The grouped decode from a position-independent plan of a pattern mask: no list is built per step.
+extern "C" int dam_sparse_attn_decode_patterns(const dam_decode_params *p, const void *q, const void *kcache,
+                                               const void *vcache, const int32_t *plan_ptr, const int32_t *plan_val,
+                                               const uint8_t *plan_member, const uint8_t *plan_table, int32_t n_flags,
+                                               int32_t pos, int64_t max_entries, void *out, float *lse, void *ws,
+                                               size_t ws_bytes, void *stream_v) {
+  const int bad = validate_grouped(p, q, kcache, vcache, plan_ptr, plan_val, plan_member, max_entries, out);
+  if (bad != DAM_OK) return bad;
+  if (!plan_table || n_flags < 1 || pos < 0 || pos >= p->kv_capacity) return DAM_ERR_INVALID_ARG;
+  if (!decode_group_mfma_fits(p)) return DAM_ERR_UNSUPPORTED;  // bf16, head_dim 128, rows of a head within 4 GiB
+  dam_decode_params shared = *p;
+  shared.shared_lists = 1;  // a plan belongs to the heads, not to a sequence
+  if (!ws || ws_bytes < dam_sparse_attn_decode_grouped_workspace(&shared, max_entries)) return DAM_ERR_WORKSPACE;
+  return decode_grouped_run(&shared, q, kcache, vcache, plan_ptr, plan_val, plan_member, max_entries, out, lse, ws,
+                            static_cast<hipStream_t>(stream_v), plan_table, n_flags, pos);
 }
 
 // ------------------------------------------------------------------------------------------------

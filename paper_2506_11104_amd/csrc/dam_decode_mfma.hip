@@ -31,13 +31,15 @@ constexpr int kBlk = 32;                   // keys per block
 constexpr int kSlot = kBlk * 256;          // bytes of the K (or V) rows of a block
 constexpr int kVSlots = 2 * kSlot;         // two K slots, then two V slots
 constexpr int kEntries = 4 * kSlot;        // then four 256-byte slots of list entries
-constexpr int kLds = kEntries + 4 * 256;
+constexpr int kFix = kEntries + 4 * 256;   // PLAN: four 256-byte slots of plan-table words
+constexpr int kLds = kFix + 4 * 256;
 
 struct MfmaArgs {
   int B, Hq, Hkv, cap, splits, shared_lists;
   float scale;
   int64_t q_sb, q_sh, kv_sb, kv_sh;
   unsigned row_bytes;  // byte stride of a cache row
+  int pos, n_flags;    // PLAN: position of the query row, length P of the pattern flags
 };
 
 // Four bytes per lane from a 64-bit address of the lane's own to LDS address lds_at + 4 * lane.
@@ -48,10 +50,19 @@ __device__ __forceinline__ void lds_copy4_at(unsigned lds_at, uint64_t addr) {
 // (The register budget of two waves per SIMD, although LDS admits one: with all 512 registers on offer the
 // compiler keeps the O accumulators in the accumulation registers for the products and in vector registers for
 // the occasional rescaling, and moves all 64 of them both ways in every iteration.)
+//
+// PLAN: the list is a position-independent plan of a pattern mask (DAM_MASK_PATTERN_PLAN): an entry v < 0 is the
+// diagonal -1 - v and stands for key pos + 1 + v, an entry v >= 0 is column v. A column entry serves the heads
+// in member & ~table[pos - v] (the others reach that key through their diagonal already), and no head when the
+// key does not exist yet (v > pos; a diagonal beyond pos likewise). The table byte of every column entry of a
+// block is fetched into LDS by one more copy per block, issued as soon as the block's entries have landed, two
+// blocks before its use, so that the loop still holds nothing but hand-counted copies.
+template <bool PLAN>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_decode_group_mfma(
     MfmaArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ kc,
     const __hip_bfloat16 *__restrict__ vc, const int *__restrict__ kept_ptr, const int *__restrict__ kept_idx,
-    const uint8_t *__restrict__ kept_member, float *__restrict__ part_o, float *__restrict__ part_ml) {
+    const uint8_t *__restrict__ kept_member, const uint8_t *__restrict__ plan_table, float *__restrict__ part_o,
+    float *__restrict__ part_ml) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   const int lane = threadIdx.x;
   const int n = lane & 31, hf = lane >> 5;     // column of the products (query head of the group), half-wave
@@ -90,6 +101,20 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                                       : min(first + 4u * (unsigned)min(lane - 32, 8), last);
       lds_copy4_at(__builtin_amdgcn_readfirstlane(lds_base + kEntries + (i & 3) * 256), addr);
     };
+    // PLAN: the aligned word that holds table[pos - c] for every column entry c of local block i (its entries have
+    // landed) -> fix slot i & 3, lane k < 32 for entry k; every other lane and entry fetches the table's first word
+    const uint64_t table_at = reinterpret_cast<uint64_t>(plan_table) + (uint64_t)hkv * (unsigned)a.n_flags;
+    auto table_index = [&](int v) { return (v >= 0 && v <= a.pos && a.pos - v < a.n_flags) ? a.pos - v : -1; };
+    // (a block without a column entry needs no table word and issues no copy: the copy, when there is one, is older
+    // than the block's sixteen row copies, which are all the waits below leave outstanding)
+    auto copy_fix = [&](int i) {
+      const unsigned char *entries = lds + kEntries + (i & 3) * 256;
+      const int v = *reinterpret_cast<const int *>(entries + 4 * (lane & 31));
+      const int t = lane < 32 ? table_index(v) : -1;
+      if (__builtin_amdgcn_ballot_w64(t >= 0) == 0) return;
+      const uint64_t addr = t >= 0 ? (table_at + (unsigned)t) & ~(uint64_t)3 : reinterpret_cast<uint64_t>(plan_table) & ~(uint64_t)3;
+      lds_copy4_at(__builtin_amdgcn_readfirstlane(lds_base + kFix + (i & 3) * 256), addr);
+    };
     // K and V rows of local block i -> slot i & 1: eight copies each; copy `it` moves rows 4 it .. 4 it + 3 of the
     // block, lane (sub, pos) the 16 bytes that belong at position pos of row 4 it + sub (the chunk permutations of
     // the prefill kernel: K chunk c of row r at position c ^ (r & 15), V chunk c at c ^ ((r & 3) << 2)).
@@ -102,7 +127,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       for (int it = 0; it < 8; ++it) {
         const int r = 4 * it + sub;
         // (an index outside the cache is pulled to its nearest row: no address leaves the cache)
-        const int key = min(max(*reinterpret_cast<const int *>(entries + 4 * r), 0), a.cap - 1);
+        int v = *reinterpret_cast<const int *>(entries + 4 * r);
+        if (PLAN && v < 0) v += a.pos + 1;  // diagonal -1 - v: key pos - r
+        // (PLAN: a pattern whose key does not exist yet is masked below; its row is taken from the keys that do, since
+        // rows beyond the position may hold anything, and a NaN there would survive a zero weight)
+        const int key = min(max(v, 0), PLAN ? min(a.pos, a.cap - 1) : a.cap - 1);
         koff[it] = (unsigned)key * a.row_bytes + ((pos ^ (r & 15)) << 4);
         voff[it] = (unsigned)key * a.row_bytes + ((pos ^ (sub << 2)) << 4);
       }
@@ -142,6 +171,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     // (the Q fragments have arrived with that wait; the empty statement tells the compiler so)
 #pragma unroll
     for (int c = 0; c < 8; ++c) asm volatile("" : "+v"(qf[c]));
+    if (PLAN) {
+      copy_fix(0);
+      if (nb > 1) copy_fix(1);
+    }
     if (nb > 2) copy_entries(2);
     copy_rows(0);
     if (nb > 1) copy_rows(1);
@@ -152,8 +185,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const int vbase = (4 * hf + ((n & 15) >> 2)) * 256 + (((n & 15) >> 2) << 6) + 32 * (n >> 4) + 8 * (n & 3);
 
     for (int i = 0; i < nb; ++i) {
-      // The copies were issued in the order ... rows i, entries i + 2, rows i + 1: block i's rows and the entries
-      // of block i + 2 have landed once nothing but the sixteen copies of block i + 1's rows is outstanding.
+      // The copies were issued in the order ... rows i, entries i + 2 (PLAN: table words i + 1), rows i + 1: block i's
+      // rows and the entries of block i + 2 have landed once nothing but the sixteen copies of block i + 1's rows is
+      // outstanding.
       if (i + 1 < nb) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       const unsigned char *ks = lds + (i & 1) * kSlot;
@@ -163,7 +197,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       // which heads keep which key: lane k < 32 holds the member byte of key k of the block
       const int e0 = entry0(i);
       const int shift = (int)((member_at + (unsigned)e0) & 3);
-      const unsigned mem = lane < 32 && e0 + lane < end ? entries[128 + shift + lane] : 0u;
+      unsigned mem = lane < 32 && e0 + lane < end ? entries[128 + shift + lane] : 0u;
+      if (PLAN) {
+        const int v = *reinterpret_cast<const int *>(entries + 4 * (lane & 31));
+        const bool exists = v < 0 ? a.pos + 1 + v >= 0 : v <= a.pos;
+        const int t = table_index(v);
+        unsigned covered = 0;  // heads that reach this column's key through a matched diagonal
+        if (t >= 0) {
+          const unsigned word = *reinterpret_cast<const unsigned *>(lds + kFix + (i & 3) * 256 + 4 * (lane & 31));
+          covered = (word >> (8 * (int)((table_at + (unsigned)t) & 3))) & 0xFFu;
+        }
+        mem = exists ? mem & ~covered : 0u;
+      }
       unsigned mine = 0;  // bit k: key k of the block is kept by this lane's head
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
@@ -233,6 +278,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       // every LDS read of block i has returned (the products consumed them): its slots are free for block i + 2
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       if (i + 3 < nb) copy_entries(i + 3);
+      if (PLAN && i + 2 < nb) copy_fix(i + 2);
       if (i + 2 < nb) copy_rows(i + 2);
     }
   }
@@ -268,7 +314,8 @@ bool decode_group_mfma_fits(const dam_decode_params *p) {
 
 void launch_decode_group_mfma(const dam_decode_params *p, int splits, float scale, const void *q, const void *kc,
                               const void *vc, const int32_t *kept_ptr, const int32_t *kept_idx,
-                              const uint8_t *kept_member, float *part_o, float *part_ml, hipStream_t st) {
+                              const uint8_t *kept_member, float *part_o, float *part_ml, hipStream_t st,
+                              const uint8_t *plan_table, int n_flags, int pos) {
   MfmaArgs a;
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity; a.splits = splits;
   a.shared_lists = p->shared_lists != 0;
@@ -276,9 +323,16 @@ void launch_decode_group_mfma(const dam_decode_params *p, int splits, float scal
   a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1];
   a.kv_sb = p->kv_stride[0]; a.kv_sh = p->kv_stride[1];
   a.row_bytes = (unsigned)(p->kv_stride[2] * 2);
-  k_decode_group_mfma<<<p->batch * p->hkv * splits, 64, kLds, st>>>(
-      a, static_cast<const __hip_bfloat16 *>(q), static_cast<const __hip_bfloat16 *>(kc),
-      static_cast<const __hip_bfloat16 *>(vc), kept_ptr, kept_idx, kept_member, part_o, part_ml);
+  a.pos = pos;
+  a.n_flags = n_flags;
+  if (plan_table)
+    k_decode_group_mfma<true><<<p->batch * p->hkv * splits, 64, kLds, st>>>(
+        a, static_cast<const __hip_bfloat16 *>(q), static_cast<const __hip_bfloat16 *>(kc),
+        static_cast<const __hip_bfloat16 *>(vc), kept_ptr, kept_idx, kept_member, plan_table, part_o, part_ml);
+  else
+    k_decode_group_mfma<false><<<p->batch * p->hkv * splits, 64, kLds, st>>>(
+        a, static_cast<const __hip_bfloat16 *>(q), static_cast<const __hip_bfloat16 *>(kc),
+        static_cast<const __hip_bfloat16 *>(vc), kept_ptr, kept_idx, kept_member, nullptr, part_o, part_ml);
 }
 
 }  // namespace dam

@@ -1452,15 +1452,129 @@ __global__ __launch_bounds__(256) void k_group_fill(Geom g, const uint64_t *__re
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Position-independent lists for grouped-query decoding in the pattern region (DAM_MASK_PATTERN_PLAN): per
+// group of G maps first every diagonal offset matched by some map of the group, then every such column, each
+// part in G + 1 runs (patterns of two or more maps; of map 0 alone; ...), each run ascending in the key it
+// stands for. A diagonal r is stored as -1 - r (key p - r at position p), a column c as c. The diagonal part
+// is the kept list of the last row of a P x P mask that has the group's diagonals and no columns (key j of
+// that row is offset P - 1 - j), so the chunked count / scan / fill of the merged lists serves unchanged; the
+// column part reads the column bitset itself. cnt / first: [((kv * 2 + part) * (G + 1) + run) * nchunks + chunk].
+__device__ __forceinline__ void plan_pieces(const Geom &gp, const uint64_t *__restrict__ cbits,
+                                            const uint64_t *__restrict__ rrev, int kv, int G, int part, int n_cols, int chunk,
+                                            int lane, unsigned (&m)[kMaxGroup], unsigned &shared) {
+  const int w = chunk * kChunkWords + lane / kPiecesPerWord;
+  const int shift = (lane % kPiecesPerWord) * kPieceBits;
+  unsigned any = 0;
+  shared = 0;
+#pragma unroll
+  for (int x = 0; x < kMaxGroup; ++x) {
+    m[x] = 0;
+    if (x < G && w < gp.pw) {
+      const int h = kv * G + x;
+      uint64_t word;
+      if (part == 0) {
+        word = mask_word(gp, nullptr, nullptr, rrev + (int64_t)h * gp.pw, gp.S - 1, w);  // gp.S == P, gp.L == 0
+      } else {
+        word = cbits[(int64_t)h * gp.pw + w];
+        const int left = n_cols - w * 64;  // columns of this word that exist
+        word &= left >= 64 ? ~0ull : (left <= 0 ? 0ull : ~0ull >> (64 - left));
+      }
+      m[x] = (unsigned)(word >> shift) & ((1u << kPieceBits) - 1);
+    }
+    shared |= any & m[x];
+    any |= m[x];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_plan_count(Geom gp, const uint64_t *__restrict__ cbits,
+                                                    const uint64_t *__restrict__ rrev, int G, int n_cols, int nchunks,
+                                                    int *__restrict__ cnt) {
+  const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), kv = blockIdx.y, part = blockIdx.z;
+  if (chunk >= nchunks) return;  // whole waves
+  unsigned m[kMaxGroup], shared;
+  plan_pieces(gp, cbits, rrev, kv, G, part, n_cols, chunk, lane, m, shared);
+  int *out = cnt + (int64_t)(kv * 2 + part) * (G + 1) * nchunks + chunk;
+  const int c0 = wave_total(__popc(shared));
+  if (lane == 0) out[0] = c0;
+#pragma unroll
+  for (int x = 0; x < kMaxGroup; ++x) {
+    if (x < G) {
+      const int c = wave_total(__popc(m[x] & ~shared));
+      if (lane == 0) out[(int64_t)(1 + x) * nchunks] = c;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_plan_fill(Geom gp, const uint64_t *__restrict__ cbits,
+                                                   const uint64_t *__restrict__ rrev, int G, int n_cols, int nchunks,
+                                                   int n_groups, const int *__restrict__ first, int *__restrict__ kept_ptr,
+                                                   int *__restrict__ kept_idx, uint8_t *__restrict__ kept_member,
+                                                   int64_t capacity) {
+  const int lane = threadIdx.x & 63, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), kv = blockIdx.y, part = blockIdx.z;
+  if (chunk >= nchunks) return;  // whole waves
+  const int *mine_first = first + (int64_t)(kv * 2 + part) * (G + 1) * nchunks + chunk;
+  if (chunk == 0 && lane == 0 && part == 0) {
+    const int64_t clamp = kept_idx ? capacity : INT64_MAX;
+    kept_ptr[kv] = (int)min((int64_t)mine_first[0], clamp);
+    if (kv == n_groups - 1) kept_ptr[n_groups] = (int)min((int64_t)first[(int64_t)n_groups * 2 * (G + 1) * nchunks], clamp);
+  }
+  if (!kept_idx) return;
+  unsigned m[kMaxGroup], shared;
+  plan_pieces(gp, cbits, rrev, kv, G, part, n_cols, chunk, lane, m, shared);
+  const int key0 = (chunk * kChunkWords + lane / kPiecesPerWord) * 64 + (lane % kPiecesPerWord) * kPieceBits;
+  const int base = part == 0 ? key0 - gp.S : key0;  // diagonal part: key j of the virtual row P - 1 is -1 - (P - 1 - j) = j - P
+#pragma unroll
+  for (int r = 0; r <= kMaxGroup; ++r) {
+    if (r <= G) {
+      unsigned left = r == 0 ? shared : m[r - 1] & ~shared;
+      const int v = __popc(left);
+      int incl = v;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+      }
+      int64_t at = (int64_t)mine_first[(int64_t)r * nchunks] + incl - v;
+      while (left) {
+        const int bit = __ffs(left) - 1;
+        left &= left - 1;
+        unsigned who = r == 0 ? 0u : 1u << (r - 1);
+        if (r == 0) {
+#pragma unroll
+          for (int y = 0; y < kMaxGroup; ++y) who |= ((m[y] >> bit) & 1u) << y;
+        }
+        if (at < capacity) {
+          kept_idx[at] = base + bit;
+          if (kept_member) kept_member[at] = (uint8_t)who;
+        }
+        ++at;
+      }
+    }
+  }
+}
+
+// table[kv][r] = which maps of group kv have diagonal r matched (bit x: map kv * G + x)
+__global__ void k_plan_table(const uint8_t *__restrict__ diag_flag, int P, int G, uint8_t *__restrict__ table) {
+  const int kv = blockIdx.y;
+  for (int r = blockIdx.x * blockDim.x + threadIdx.x; r < P; r += gridDim.x * blockDim.x) {
+    unsigned who = 0;
+    for (int x = 0; x < G; ++x) who |= (diag_flag[(int64_t)(kv * G + x) * P + r] ? 1u : 0u) << x;
+    table[(int64_t)kv * P + r] = (uint8_t)who;
+  }
+}
+
 int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *diag_in,
              const uint8_t *vert_in, const dam_mask_out *o) {
   if (!p || !o) return DAM_ERR_INVALID_ARG;
   if (p->mode != DAM_FROM_ATTN_MAP && p->mode != DAM_FROM_PATTERNS) return DAM_ERR_INVALID_ARG;
   if (p->n_maps < 1 || p->seq < 1) return DAM_ERR_INVALID_ARG;
-  if (p->flags & ~(DAM_MASK_SKIP_FULL_TILE_BITS | DAM_MASK_GATHER_COLUMNS | DAM_MASK_GROUP_LISTS)) return DAM_ERR_INVALID_ARG;
+  if (p->flags & ~(DAM_MASK_SKIP_FULL_TILE_BITS | DAM_MASK_GATHER_COLUMNS | DAM_MASK_GROUP_LISTS | DAM_MASK_PATTERN_PLAN))
+    return DAM_ERR_INVALID_ARG;
+  const bool plan = (p->flags & DAM_MASK_PATTERN_PLAN) != 0;
+  if (plan && (!(p->flags & DAM_MASK_GROUP_LISTS) || !o->kept_ptr || !o->plan_table)) return DAM_ERR_INVALID_ARG;
   if ((p->flags & DAM_MASK_GROUP_LISTS) && o->kept_ptr) {
     if (p->group < 1 || p->group > kMaxGroup || p->n_maps % p->group) return DAM_ERR_INVALID_ARG;
-    if (p->row_end != p->row_begin + 1) return DAM_ERR_UNSUPPORTED;
+    if (!plan && p->row_end != p->row_begin + 1) return DAM_ERR_UNSUPPORTED;
     if (o->kept_idx && !o->kept_member) return DAM_ERR_INVALID_ARG;
   }
   if ((p->flags & DAM_MASK_GATHER_COLUMNS) && (!o->gather_idx || !o->gather_cnt)) return DAM_ERR_INVALID_ARG;
@@ -1485,7 +1599,7 @@ int validate(const dam_mask_params *p, const float *attn_sum, const uint8_t *dia
   if (o->dense_bits && p->seq > 65535) return DAM_ERR_UNSUPPORTED;
   if (o->kept_ptr || o->kept_idx || o->kept_total) {
     if (!o->kept_ptr || !o->kept_total || o->kept_capacity < 0) return DAM_ERR_INVALID_ARG;
-    if (p->row_begin < 0 || p->row_begin > p->row_end || p->row_end > p->seq) return DAM_ERR_INVALID_ARG;
+    if (!plan && (p->row_begin < 0 || p->row_begin > p->row_end || p->row_end > p->seq)) return DAM_ERR_INVALID_ARG;
     if ((int64_t)p->n_maps * (p->row_end - p->row_begin) > (int64_t)1 << 30) return DAM_ERR_UNSUPPORTED;
   }
   return DAM_OK;
@@ -1562,6 +1676,11 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   if (nrows == 1 && p->row_begin >= 0) {  // a single row goes through the group-list kernels: run sizes per chunk, and their scan
     const int group = list_group(p);
     n_first = (size_t)(g.H / group) * (size_t)group_chunks(p->row_begin) * (size_t)(group + 1) + 1;
+    n_cnt = std::max(n_cnt, n_first);
+  }
+  if (p->flags & DAM_MASK_PATTERN_PLAN) {  // two parts (diagonals, columns) over the P pattern positions
+    const int group = list_group(p);
+    n_first = std::max(n_first, (size_t)(g.H / group) * 2 * (size_t)group_chunks(g.P - 1) * (size_t)(group + 1) + 1);
     n_cnt = std::max(n_cnt, n_first);
   }
   w.row_cnt = c.take<int>(n_cnt);
@@ -1658,7 +1777,19 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
     const int sw = (g.S + 63) / 64;
     k_dense_bits<<<dim3((sw + 255) / 256, g.S, g.H), 256, 0, stream>>>(g, true_bits, w.cbits, w.rrev, sw, o->dense_bits);
   }
-  if (want_lists) {
+  if (want_lists && (p->flags & DAM_MASK_PATTERN_PLAN)) {
+    Geom gp = g;  // the P x P pattern-only mask whose last row lists the diagonals
+    gp.L = 0;
+    gp.S = g.P;
+    const int G = list_group(p), n_groups = g.H / G, nchunks = group_chunks(g.P - 1), n_cols = std::min(g.P, g.S);
+    const dim3 grid((nchunks + 3) / 4, n_groups, 2);
+    k_plan_count<<<grid, 256, 0, stream>>>(gp, w.cbits, w.rrev, G, n_cols, nchunks, w.row_cnt);
+    k_exclusive_scan<<<1, 1024, 0, stream>>>(w.row_cnt, (int64_t)n_groups * 2 * (G + 1) * nchunks, 0, w.group_first, o->kept_total,
+                                             INT64_MAX);
+    k_plan_fill<<<grid, 256, 0, stream>>>(gp, w.cbits, w.rrev, G, n_cols, nchunks, n_groups, w.group_first, o->kept_ptr,
+                                          o->kept_capacity > 0 ? o->kept_idx : nullptr, o->kept_member, o->kept_capacity);
+    k_plan_table<<<dim3((g.P + 255) / 256, n_groups), 256, 0, stream>>>(dflag, g.P, G, o->plan_table);
+  } else if (want_lists) {
     const int nrows = p->row_end - p->row_begin;
     if (nrows == 1) {
       // one row (a decode step): the chunked kernels below, whose longest dependent chain is eight steps; lists per

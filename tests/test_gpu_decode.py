@@ -406,3 +406,107 @@ def test_lists_of_a_row_a_million_keys_long():
     want = oracle.group_lists(lists, G)
     assert np.array_equal(mg.kept_ptr.cpu().numpy().astype(np.int64), want[0])
     assert np.array_equal(mg.kept_idx.cpu().numpy(), want[1]) and np.array_equal(mg.kept_member.cpu().numpy(), want[2])
+
+
+# ---------------------------------------------------------------------------------------------
+# Position-independent plans of pattern masks (DAM_MASK_PATTERN_PLAN) and the decode that reads them.
+def plan_inputs(seed, Hq, G, P, sinks=3, window=40, density=0.02):
+    rng = np.random.default_rng(seed)
+    d = (rng.random((Hq, P)) < density).astype(np.uint8)
+    v = (rng.random((Hq, P)) < density).astype(np.uint8)
+    for h in range(Hq):
+        d[h, :int(rng.integers(1, window))] = 1
+        v[h, :sinks] = 1
+    if Hq > 2:
+        d[2], v[2] = 0, 0                      # a head that keeps nothing
+    return d, v
+
+
+@pytest.mark.parametrize("Hq,G,P,S", [(8, 4, 3000, 3000), (4, 1, 700, 700), (16, 8, 1500, 1500), (4, 2, 640, 500)])
+def test_pattern_plan_matches_the_oracle_bit_for_bit(Hq, G, P, S):
+    d, v = plan_inputs(81, Hq, G, P)
+    want = oracle.pattern_plan(d, v, G, S=S)
+    if S < P:       # flags longer than the problem: the library takes [H][S] flags in pattern mode
+        d, v = d[:, :S].copy(), v[:, :S].copy()
+        want = oracle.pattern_plan(d, v, G, S=S)
+    m = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=S, diag_in=torch.from_numpy(d).cuda(),
+                     vert_in=torch.from_numpy(v).cuda(), blocks=False, group=G, plan=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.kept_ptr.cpu().numpy().astype(np.int64), want[0])
+    assert np.array_equal(m.kept_idx.cpu().numpy(), want[1])
+    assert np.array_equal(m.kept_member.cpu().numpy(), want[2])
+    assert np.array_equal(m.plan_table.cpu().numpy(), want[3])
+
+
+def test_pattern_plan_from_an_attention_map():
+    """The plan of masks derived by the paper's rule (flags over the capture length L, problem longer than L)."""
+    w = wl.scaled(wl.WORKLOADS["c2"], hq=8, hkv=2, seq=2048, pcl=512)
+    Q, K, V = wl.qkv_structured(w)
+    A = wl.capture_map(Q[:, :w.pcl], K[:, :w.pcl], w.pcl, w.hq // w.hkv)
+    art = oracle.derive(A, None, w.lam, w.eps, w.tau, w.mu)
+    want = oracle.pattern_plan(art.diag_flag, art.vert_flag, 4, S=w.seq)
+    m = B.build_mask(mode=B.DAM_FROM_ATTN_MAP, H=w.hq, L=w.pcl, S=w.seq, lam=w.lam, eps=w.eps, tau=w.tau, mu=w.mu,
+                     attn_sum=torch.from_numpy(A).cuda(), blocks=False, group=4, plan=True)
+    torch.cuda.synchronize()
+    assert int(want[0][-1]) > 0
+    assert np.array_equal(m.kept_ptr.cpu().numpy().astype(np.int64), want[0])
+    assert np.array_equal(m.kept_idx.cpu().numpy(), want[1]) and np.array_equal(m.kept_member.cpu().numpy(), want[2])
+    assert np.array_equal(m.plan_table.cpu().numpy(), want[3])
+
+
+@pytest.mark.parametrize("Hq,Hkv,T,positions", [(8, 2, 3000, (2999, 2998, 1500, 40, 3, 0)), (4, 4, 900, (899, 450)),
+                                                (16, 2, 2100, (2099, 777))])
+def test_decode_from_a_pattern_plan_matches_the_oracle_rows(Hq, Hkv, T, positions):
+    """dam_sparse_attn_decode_patterns at several positions of one plan (late, early, the very first rows: diagonals
+    and columns that do not exist yet; keys that are column and diagonal at once) against the oracle's attention
+    over each head's own row of the mask, and against the list form on the lists of that row."""
+    G = Hq // Hkv
+    Bn, dh = 3, 128
+    d, v = plan_inputs(82, Hq, G, T)
+    art = oracle.from_patterns(d, v)
+    plan = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=T, diag_in=torch.from_numpy(d).cuda(),
+                        vert_in=torch.from_numpy(v).cuda(), blocks=False, group=G, plan=True)
+    torch.cuda.synchronize()
+    longest = int(np.diff(plan.kept_ptr.cpu().numpy()).max())
+    g = torch.Generator().manual_seed(10)
+    kc = torch.randn((Bn, Hkv, T, dh), generator=g).to(torch.bfloat16)
+    vc = torch.randn((Bn, Hkv, T, dh), generator=g).to(torch.bfloat16)
+    q = torch.randn((Bn, Hq, dh), generator=g).to(torch.bfloat16)
+    Kf = kc.float().numpy().reshape(Bn * Hkv, T, dh)
+    Vf = vc.float().numpy().reshape(Bn * Hkv, T, dh)
+    kv_of = np.array([b * Hkv + h // G for b in range(Bn) for h in range(Hq)], np.int32)
+    kc_d, vc_d, q_d = kc.cuda(), vc.cuda(), q.cuda()
+    for pos in positions:
+        # rows beyond the position must not matter: poison them
+        kc_p, vc_p = kc_d.clone(), vc_d.clone()
+        kc_p[:, :, pos + 1:] = float("nan")
+        vc_p[:, :, pos + 1:] = float("nan")
+        lists = [oracle.kept_list(art, h, pos) for h in range(Hq)]
+        lens = np.array([len(x) for x in lists])
+        ptr_all = np.concatenate([[0], np.cumsum(np.tile(lens, Bn))]).astype(np.int64)
+        idx_all = np.tile(np.concatenate(lists), Bn).astype(np.int32) if lens.sum() else np.zeros(0, np.int32)
+        O, LSE = oracle.attend_lists(q.float().numpy().reshape(Bn * Hq, dh), Kf, Vf, kv_of, ptr_all, idx_all)
+        out, lse = B.dam_sparse_attn_decode_patterns(q_d, kc_p, vc_p, plan, pos, longest, want_lse=True)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().reshape(Bn * Hq, dh)
+        assert not np.isnan(got).any(), pos
+        assert np.abs(got - O).max() <= TOL["bf16"], pos
+        fin = np.isfinite(LSE)
+        got_lse = lse.cpu().numpy().reshape(-1)
+        assert np.array_equal(np.isneginf(got_lse), ~fin) and (got[~fin] == 0).all()
+        assert np.abs(got_lse[fin] - LSE[fin]).max() <= TOL["bf16"]
+
+
+def test_decode_patterns_argument_errors():
+    q = torch.zeros((1, 4, 128), dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros((1, 2, 64, 128), dtype=torch.bfloat16, device="cuda")
+    d = np.ones((4, 64), np.uint8)
+    plan = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=4, L=0, S=64, diag_in=torch.from_numpy(d).cuda(),
+                        vert_in=torch.from_numpy(d).cuda(), blocks=False, group=2, plan=True)
+    for pos in (-1, 64):
+        with pytest.raises(B.DamError) as e:
+            B.dam_sparse_attn_decode_patterns(q, kc, kc, plan, pos, 128)
+        assert e.value.status == B.DAM_ERR_INVALID_ARG
+    with pytest.raises(B.DamError) as e:
+        B.dam_sparse_attn_decode_patterns(q.float(), kc.float(), kc.float(), plan, 5, 128)
+    assert e.value.status == B.DAM_ERR_UNSUPPORTED

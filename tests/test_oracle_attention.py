@@ -207,7 +207,7 @@ def test_pattern_plan_worked_example():
     ptr, val, mem, table = oracle.pattern_plan(d, v, 2)
     # diagonals: shared {0}; head 0 alone {1, 5}; head 1 alone {2}. columns: shared {0}; head 0 alone {7}; head 1 alone {3}
     assert list(ptr) == [0, 7]
-    assert list(val) == [-1, -2, -6, -3, 0, 7, 3]
+    assert list(val) == [-1, -6, -2, -3, 0, 7, 3]          # (head 0's own diagonals 5, 1: descending offsets)
     assert list(mem) == [3, 1, 1, 2, 3, 1, 2]
     assert list(table[0]) == [3, 1, 2, 0, 0, 1, 0, 0, 0, 0, 0, 0]
     plan = (ptr, val, mem, table)
