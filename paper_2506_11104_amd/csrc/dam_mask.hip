@@ -37,14 +37,14 @@ struct Geom {
 // Sec. 4.2.2 in the fixed fp32 sequence (each op rounded to nearest, nothing contracted: this file
 // is compiled with contraction off and with correctly rounded fp32 divide and square root; the
 // __fsqrt_rn / __fdiv_rn intrinsics are NOT used because they map to the approximate forms).
-__device__ __forceinline__ float clamp_mean(float a, float c, float eps) {
+__host__ __device__ __forceinline__ float clamp_mean(float a, float c, float eps) {
   const float denom = c + eps;
   const float abar = a / denom;
   return fmaxf(abar, eps);
 }
 
 template <int LAMBDA2>  // 2 * lambda: 1 -> lambda 0.5, 2 -> lambda 1
-__device__ __forceinline__ float box_cox(float x) {
+__host__ __device__ __forceinline__ float box_cox(float x) {
   if (LAMBDA2 == 1) {
     const float root = sqrtf(x);
     const float num = root - 1.0f;
@@ -114,42 +114,52 @@ constexpr int kTmRows = 64;  // rows per block (4 passes of 4 rows per wave)
 // sequence at each probe; k_true_mask then needs one comparison per element and stays bit-exact.
 // Ordered key: increasing with the value over [-inf, +inf]; a NaN is treated as -inf, which is what
 // the sequence does with it (fmaxf(NaN, eps) = eps, the smallest clamped value).
-__device__ __forceinline__ unsigned key_of(float x) {
-  const unsigned b = __float_as_uint(x);
+__host__ __device__ __forceinline__ unsigned key_of(float x) {
+  const unsigned b = __builtin_bit_cast(unsigned, x);
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
-__device__ __forceinline__ float value_of(unsigned k) {
-  return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+__host__ __device__ __forceinline__ float value_of(unsigned k) {
+  return __builtin_bit_cast(float, (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 constexpr unsigned kKeyNegInf = 0x007FFFFFu, kKeyPosInf = 0xFF800000u;
 constexpr unsigned kKeepAll = 0u, kKeepNone = 0xFFFFFFFFu;
 
 template <int LAMBDA2, bool FROM_A>
-__device__ __forceinline__ bool keep_at(float v, float eps, float tau, float bmin) {
+__host__ __device__ __forceinline__ bool keep_at(float v, float eps, float tau, float bmin) {
   const float x = FROM_A ? clamp_mean(v, 1.0f, eps) : fmaxf(v, eps);
   const float bstar = box_cox<LAMBDA2>(x) - bmin;
   return bstar >= tau;
 }
 
+// (host and device: the sequence is correctly rounded IEEE arithmetic on both, so when the minimum is known
+// without looking at the data -- an override, or the closed form of a single causal capture -- the bisection runs
+// on the host and the first kernel of the chain takes the key by value)
 template <int LAMBDA2, bool FROM_A>
-__global__ void k_threshold(float eps, float tau, const float *__restrict__ bmin_p, unsigned *__restrict__ theta_key) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  const float bmin = *bmin_p;
+__host__ __device__ unsigned threshold_key(float eps, float tau, float bmin) {
   unsigned lo = kKeyNegInf, hi = kKeyPosInf;
-  if (!keep_at<LAMBDA2, FROM_A>(value_of(hi), eps, tau, bmin)) {
-    *theta_key = kKeepNone;
-    return;
-  }
-  if (keep_at<LAMBDA2, FROM_A>(value_of(lo), eps, tau, bmin)) {
-    *theta_key = kKeepAll;
-    return;
-  }
+  if (!keep_at<LAMBDA2, FROM_A>(value_of(hi), eps, tau, bmin)) return kKeepNone;
+  if (keep_at<LAMBDA2, FROM_A>(value_of(lo), eps, tau, bmin)) return kKeepAll;
   while (hi - lo > 1u) {  // keep(lo) false, keep(hi) true
     const unsigned mid = lo + (hi - lo) / 2u;
     if (keep_at<LAMBDA2, FROM_A>(value_of(mid), eps, tau, bmin)) hi = mid;
     else lo = mid;
   }
-  *theta_key = hi;
+  return hi;
+}
+
+template <int LAMBDA2, bool FROM_A>
+__global__ void k_threshold(float eps, float tau, const float *__restrict__ bmin_p, unsigned *__restrict__ theta_key) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  *theta_key = threshold_key<LAMBDA2, FROM_A>(eps, tau, *bmin_p);
+}
+
+// minimum and key found on the host: into the workspace (and the caller's bmin) for the kernels that read them there
+__global__ void k_set_threshold(float bmin, unsigned key, float *__restrict__ ws_bmin, unsigned *__restrict__ ws_key,
+                                float *__restrict__ out_bmin) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  *ws_bmin = bmin;
+  *ws_key = key;
+  if (out_bmin) *out_bmin = bmin;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -312,14 +322,29 @@ __global__ void k_transform_threshold(int kind, float lambda, float eps, float t
   *theta_key = hi;
 }
 
+// The threshold key comes from the workspace (theta_key) or, when the host found it, by value (theta_key == nullptr:
+// theta_val, and bmin_val goes to the caller's bmin from here, this being the first kernel of the chain).
+struct Threshold {
+  const unsigned *theta_key;
+  unsigned theta_val;
+  float bmin_val;
+  float *bmin_out;
+};
+
+__device__ __forceinline__ unsigned take_threshold(const Threshold &t) {
+  if (t.theta_key) return *t.theta_key;
+  if (t.bmin_out && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *t.bmin_out = t.bmin_val;
+  return t.theta_val;
+}
+
 template <bool FROM_A, bool RAW = false>
 __global__ __launch_bounds__(256) void k_true_mask(const float *__restrict__ A, const float *__restrict__ C, int L,
-                                                   int tbw, float eps, const unsigned *__restrict__ theta_key,
+                                                   int tbw, float eps, Threshold thr,
                                                    uint64_t *__restrict__ true_bits) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = blockIdx.z;
   const int w0 = blockIdx.x * 4;
-  const unsigned theta = *theta_key;
+  const unsigned theta = take_threshold(thr);
   const float *Ah = A + (int64_t)h * L * L;
   const float *Ch = FROM_A ? nullptr : C + (int64_t)h * L * L;
   constexpr int kIter = kTmRows / 16;  // passes of 4 rows per wave
@@ -431,9 +456,8 @@ __device__ __forceinline__ void true_mask_pairs(const float *__restrict__ A, int
 }
 
 __global__ __launch_bounds__(256) void k_true_mask_rows(const float *__restrict__ A, int L, int tbw, int n_pairs,
-                                                        const unsigned *__restrict__ theta_key,
-                                                        uint64_t *__restrict__ true_bits) {
-  const unsigned theta = *theta_key;
+                                                        Threshold thr, uint64_t *__restrict__ true_bits) {
+  const unsigned theta = take_threshold(thr);
   if (theta >= 0x80800000u) true_mask_pairs<true>(A, L, tbw, n_pairs, theta, true_bits);  // key of FLT_MIN
   else true_mask_pairs<false>(A, L, tbw, n_pairs, theta, true_bits);
 }
@@ -454,13 +478,17 @@ __device__ __forceinline__ void csa(uint64_t &carry, uint64_t &sum, uint64_t a, 
   sum = u ^ c;
 }
 
-template <bool DIAG>
+// (one launch for both pattern kinds: the upper half of the grid's x range counts diagonals)
 __global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restrict__ true_bits, int L, int tbw,
-                                                        int n_chunks, uint64_t *__restrict__ slices) {
+                                                        int n_chunks, uint64_t *__restrict__ vslices,
+                                                        uint64_t *__restrict__ dslices) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = blockIdx.z;
   const int chunk = blockIdx.y * 4 + wave;
-  const int wl = blockIdx.x * 64 + lane;  // word of columns (or of diagonal offsets) owned by this lane
+  const int xw = gridDim.x / 2;
+  const bool DIAG = (int)blockIdx.x >= xw;  // block-uniform
+  uint64_t *slices = DIAG ? dslices : vslices;
+  const int wl = ((int)blockIdx.x - (DIAG ? xw : 0)) * 64 + lane;  // word of columns (or of diagonal offsets) owned by this lane
   if (chunk >= n_chunks || wl >= tbw) return;
   const int i0 = chunk * kChunkRows;
   const uint64_t *tb = true_bits + (int64_t)h * L * tbw;
@@ -613,28 +641,29 @@ __device__ __forceinline__ unsigned flags16(const uint8_t *__restrict__ row, int
   return bits;
 }
 
-__global__ __launch_bounds__(256) void k_pattern_bitsets(const uint8_t *__restrict__ diag_flag,
-                                                         const uint8_t *__restrict__ vert_flag, int P, int pw,
-                                                         uint64_t *__restrict__ cbits,
-                                                         uint64_t *__restrict__ rrev) {
+// (every thread of the workgroup calls this; 256 words per pass)
+__device__ __forceinline__ void pattern_bitsets_of_head(const uint8_t *__restrict__ diag_flag,
+                                                        const uint8_t *__restrict__ vert_flag, int P, int pw, int h,
+                                                        uint64_t *__restrict__ cbits, uint64_t *__restrict__ rrev) {
   const int part = threadIdx.x & 3;
-  const int w = blockIdx.x * 64 + (threadIdx.x >> 2);
-  const int h = blockIdx.y;
-  const bool live = w < pw;
   const uint8_t *drow = diag_flag + (int64_t)h * P, *vrow = vert_flag + (int64_t)h * P;
   const bool d_al = (reinterpret_cast<uintptr_t>(drow) & 15) == 0, v_al = (reinterpret_cast<uintptr_t>(vrow) & 15) == 0;
-  uint64_t cw = 0, rw = 0;
-  if (live) {
-    cw = (uint64_t)flags16(vrow, w * 64 + part * 16, P, v_al) << (16 * part);
-    rw = (uint64_t)flags16(drow, (pw - 1 - w) * 64 + part * 16, P, d_al) << (16 * part);  // ascending offsets
-  }
-  cw |= __shfl_xor(cw, 1);
-  cw |= __shfl_xor(cw, 2);
-  rw |= __shfl_xor(rw, 1);
-  rw |= __shfl_xor(rw, 2);
-  if (live && part == 0) {
-    cbits[(int64_t)h * pw + w] = cw;
-    rrev[(int64_t)h * pw + w] = __brevll(rw);  // bit q of the word <- offset (pw*64 - 1) - (64 w + q)
+  for (int w0 = 0; w0 < pw; w0 += blockDim.x / 4) {
+    const int w = w0 + (threadIdx.x >> 2);
+    const bool live = w < pw;
+    uint64_t cw = 0, rw = 0;
+    if (live) {
+      cw = (uint64_t)flags16(vrow, w * 64 + part * 16, P, v_al) << (16 * part);
+      rw = (uint64_t)flags16(drow, (pw - 1 - w) * 64 + part * 16, P, d_al) << (16 * part);  // ascending offsets
+    }
+    cw |= __shfl_xor(cw, 1);
+    cw |= __shfl_xor(cw, 2);
+    rw |= __shfl_xor(rw, 1);
+    rw |= __shfl_xor(rw, 2);
+    if (live && part == 0) {
+      cbits[(int64_t)h * pw + w] = cw;
+      rrev[(int64_t)h * pw + w] = __brevll(rw);  // bit q of the word <- offset (pw*64 - 1) - (64 w + q)
+    }
   }
 }
 
@@ -747,35 +776,38 @@ __device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_
 // property of kt alone and "some offset matched" / "all offsets matched" of d alone. The d classes
 // are stored reversed (d at position 64 dw - 1 - d), like the diagonal set, so that the 64 key tiles
 // of an occupancy word are 64 consecutive bits.
-__global__ void k_tile_classes(Geom g, const uint64_t *__restrict__ cbits, const uint64_t *__restrict__ rrev,
-                               uint64_t *__restrict__ col_any, uint64_t *__restrict__ col_all,
-                               uint64_t *__restrict__ off_any, uint64_t *__restrict__ off_all) {
-  const int lane = threadIdx.x, w = blockIdx.x, h = blockIdx.y;
+__device__ __forceinline__ void tile_classes_of_head(const Geom &g, const uint64_t *__restrict__ cbits,
+                                                     const uint64_t *__restrict__ rrev, int h, uint64_t *__restrict__ col_any,
+                                                     uint64_t *__restrict__ col_all, uint64_t *__restrict__ off_any,
+                                                     uint64_t *__restrict__ off_all) {
+  const int lane = threadIdx.x & 63;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
   const int T = g.tile_n;
   const int64_t Q = (int64_t)g.pw * 64 - 1;
-  {
-    const int kt = w * 64 + lane;
-    const int64_t j0 = (int64_t)kt * T, j1 = j0 + T - 1;
-    const bool any = kt < g.nKt && range_any(cb, g.pw, j0, j1);
-    const bool all = kt < g.nKt && j1 <= Q && range_all(cb, j0, j1);
-    const uint64_t wa = __ballot(any), wf = __ballot(all);
-    if (lane == 0) {
-      col_any[(int64_t)h * g.occw + w] = wa;
-      col_all[(int64_t)h * g.occw + w] = wf;
+  for (int w = threadIdx.x >> 6; w < g.occw; w += blockDim.x >> 6) {  // a wave per occupancy word
+    {
+      const int kt = w * 64 + lane;
+      const int64_t j0 = (int64_t)kt * T, j1 = j0 + T - 1;
+      const bool any = kt < g.nKt && range_any(cb, g.pw, j0, j1);
+      const bool all = kt < g.nKt && j1 <= Q && range_all(cb, j0, j1);
+      const uint64_t wa = __ballot(any), wf = __ballot(all);
+      if (lane == 0) {
+        col_any[(int64_t)h * g.occw + w] = wa;
+        col_all[(int64_t)h * g.occw + w] = wf;
+      }
     }
-  }
-  {
-    const int64_t d = (int64_t)g.occw * 64 - 1 - ((int64_t)w * 64 + lane);
-    const int64_t a = d * T - (T - 1), b = d * T + (T - 1);  // offsets of the tile, a >= 1 when d >= 1
-    const bool live = d >= 1 && d < g.nQt;
-    const bool any = live && range_any(rr, g.pw, Q - b, Q - a);
-    const bool all = live && b <= Q && range_all(rr, Q - b, Q - a);
-    const uint64_t wa = __ballot(any), wf = __ballot(all);
-    if (lane == 0) {
-      off_any[(int64_t)h * g.occw + w] = wa;
-      off_all[(int64_t)h * g.occw + w] = wf;
+    {
+      const int64_t d = (int64_t)g.occw * 64 - 1 - ((int64_t)w * 64 + lane);
+      const int64_t a = d * T - (T - 1), b = d * T + (T - 1);  // offsets of the tile, a >= 1 when d >= 1
+      const bool live = d >= 1 && d < g.nQt;
+      const bool any = live && range_any(rr, g.pw, Q - b, Q - a);
+      const bool all = live && b <= Q && range_all(rr, Q - b, Q - a);
+      const uint64_t wa = __ballot(any), wf = __ballot(all);
+      if (lane == 0) {
+        off_any[(int64_t)h * g.occw + w] = wa;
+        off_all[(int64_t)h * g.occw + w] = wf;
+      }
     }
   }
 }
@@ -812,10 +844,10 @@ __device__ __forceinline__ void stage_sets(uint64_t *lds_sets, bool staged, int 
 
 // The matched columns below S of one head, ascending, padded with -1 up to the stride. One workgroup per
 // head, a word of the column bitset per thread and pass.
-__global__ __launch_bounds__(1024) void k_gather_columns(Geom g, const uint64_t *__restrict__ cbits, int stride,
-                                                         int *__restrict__ gidx, int *__restrict__ gcnt) {
+__device__ __forceinline__ void gather_columns_of_head(const Geom &g, const uint64_t *__restrict__ cbits, int stride, int h,
+                                                       int *__restrict__ gidx, int *__restrict__ gcnt) {
   __shared__ int s_wave[16];
-  const int h = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   int *out = gidx + (int64_t)h * stride;
   const int n_cols = min(g.P, g.S);
@@ -848,6 +880,23 @@ __global__ __launch_bounds__(1024) void k_gather_columns(Geom g, const uint64_t 
   }
   if (threadIdx.x == 0) gcnt[h] = base;
   for (int x = base + threadIdx.x; x < stride; x += blockDim.x) out[x] = -1;
+}
+
+// Everything the block index needs from the pattern flags of one head, in one launch (one workgroup of 1024
+// per head: the three steps are short chains of dependent work, and as separate kernels each paid a launch):
+// the two bitsets, the tile classes, the gathered column list.
+__global__ __launch_bounds__(1024) void k_pattern_prep(Geom g, const uint8_t *__restrict__ diag_flag,
+                                                       const uint8_t *__restrict__ vert_flag, uint64_t *__restrict__ cbits,
+                                                       uint64_t *__restrict__ rrev, bool classes,
+                                                       uint64_t *__restrict__ col_any, uint64_t *__restrict__ col_all,
+                                                       uint64_t *__restrict__ off_any, uint64_t *__restrict__ off_all,
+                                                       int gstride, int *__restrict__ gidx, int *__restrict__ gcnt) {
+  const int h = blockIdx.x;
+  pattern_bitsets_of_head(diag_flag, vert_flag, g.P, g.pw, h, cbits, rrev);
+  if (!classes) return;  // uniform over the grid
+  __syncthreads();       // the sets are read back from memory by other threads of this workgroup
+  tile_classes_of_head(g, cbits, rrev, h, col_any, col_all, off_any, off_all);
+  if (gidx) gather_columns_of_head(g, cbits, gstride, h, gidx, gcnt);
 }
 
 // Transpose of the 64 x 64 bit matrix whose row l is the word x of lane l: lane r returns the word whose
@@ -889,26 +938,13 @@ __device__ __forceinline__ void slot_rows(const Geom &g, const uint64_t *__restr
 // strictly below the diagonal and outside the true-mask block are decided by their lane alone (from
 // the class bitsets, or by pattern_tile_flags); only the tiles on the diagonal or inside the
 // true-mask block are then evaluated word by word by the whole wave. No LDS, no barrier.
-__global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__restrict__ true_bits,
-                                                   const uint64_t *__restrict__ cbits,
-                                                   const uint64_t *__restrict__ rrev,
-                                                   const uint64_t *__restrict__ col_any,
-                                                   const uint64_t *__restrict__ col_all,
-                                                   const uint64_t *__restrict__ off_any,
-                                                   const uint64_t *__restrict__ off_all,
-                                                   uint64_t *__restrict__ occ,
-                                                   uint64_t *__restrict__ full, int *__restrict__ cnt, bool staged,
-                                                   const int *__restrict__ gidx, const int *__restrict__ gcnt,
-                                                   int gstride, uint64_t *__restrict__ vocc,
-                                                   uint64_t *__restrict__ vfull) {
-  extern __shared__ uint64_t lds_sets[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int h = blockIdx.y, qt = blockIdx.x * 4 + wave;
-  const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
-  const uint64_t *cb = cbits + (int64_t)h * g.pw;
-  const uint64_t *rr = rrev + (int64_t)h * g.pw;
-  stage_sets(lds_sets, staged, g.pw, cb, rr);
-  if (qt >= g.nQt) return;
+__device__ __forceinline__ void tile_scan_row(const Geom &g, const uint64_t *__restrict__ tb, const uint64_t *__restrict__ cb,
+                                              const uint64_t *__restrict__ rr, const uint64_t *__restrict__ col_any,
+                                              const uint64_t *__restrict__ col_all, const uint64_t *__restrict__ off_any,
+                                              const uint64_t *__restrict__ off_all, uint64_t *__restrict__ occ,
+                                              uint64_t *__restrict__ full, int *__restrict__ cnt, const int *__restrict__ gidx,
+                                              const int *__restrict__ gcnt, int gstride, uint64_t *__restrict__ vocc,
+                                              uint64_t *__restrict__ vfull, int h, int qt, int lane) {
   const int i0 = qt * g.tile_m;
   const int i_last = min(g.S - 1, i0 + g.tile_m - 1);
   const int kmax = i_last / g.tile_n;
@@ -1010,14 +1046,15 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
 // scan, one exchange of the wave totals) is paid once per 8192 counts.
 constexpr int kScanItems = 8;
 
-__global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__ cnt, int64_t n,
-                                                         int group, int *__restrict__ ptr,
-                                                         int64_t *__restrict__ total, int64_t clamp) {
+// The scan itself, run by every thread of one workgroup of THREADS threads (a multiple of 64, at most 1024).
+template <int THREADS>
+__device__ __forceinline__ void block_exclusive_scan(const int *__restrict__ cnt, int64_t n, int group, int *__restrict__ ptr,
+                                                     int64_t *__restrict__ total, int64_t clamp) {
   __shared__ int64_t wave_sum[2][16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int64_t carry = 0;  // the same value in every thread
   int pass = 0;
-  for (int64_t base = 0; base < n; base += 1024 * kScanItems, ++pass) {
+  for (int64_t base = 0; base < n; base += THREADS * kScanItems, ++pass) {
     const int64_t e0 = base + (int64_t)threadIdx.x * kScanItems;
     int v[kScanItems];
 #pragma unroll
@@ -1033,7 +1070,7 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__
     if (lane == 63) wave_sum[pass & 1][wave] = incl;
     __syncthreads();  // one barrier per pass: the totals of consecutive passes live in alternating buffers
     int64_t before = carry, all = 0;
-    for (int w = 0; w < 16; ++w) {
+    for (int w = 0; w < THREADS / 64; ++w) {
       const int64_t ws = wave_sum[pass & 1][w];
       if (w < wave) before += ws;
       all += ws;
@@ -1073,6 +1110,37 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__
     }
     if (total) *total = carry;
   }
+}
+
+__global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__ cnt, int64_t n,
+                                                         int group, int *__restrict__ ptr,
+                                                         int64_t *__restrict__ total, int64_t clamp) {
+  block_exclusive_scan<1024>(cnt, n, group, ptr, total, clamp);
+}
+
+// Pass 1 as a kernel: a wave per query tile. (The CSR offsets stay a launch of their own: folding the scan into
+// the last workgroup to finish needs a device-wide release fence in every workgroup, which on this chip writes
+// back the L2 of its XCD each time: 20 -> 190 us at S = 32768.)
+__global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__restrict__ true_bits,
+                                                   const uint64_t *__restrict__ cbits,
+                                                   const uint64_t *__restrict__ rrev,
+                                                   const uint64_t *__restrict__ col_any,
+                                                   const uint64_t *__restrict__ col_all,
+                                                   const uint64_t *__restrict__ off_any,
+                                                   const uint64_t *__restrict__ off_all,
+                                                   uint64_t *__restrict__ occ,
+                                                   uint64_t *__restrict__ full, int *__restrict__ cnt, bool staged,
+                                                   const int *__restrict__ gidx, const int *__restrict__ gcnt,
+                                                   int gstride, uint64_t *__restrict__ vocc,
+                                                   uint64_t *__restrict__ vfull) {
+  extern __shared__ uint64_t lds_sets[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.y, qt = blockIdx.x * 4 + wave;
+  const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
+  const uint64_t *cb = cbits + (int64_t)h * g.pw;
+  const uint64_t *rr = rrev + (int64_t)h * g.pw;
+  stage_sets(lds_sets, staged, g.pw, cb, rr);
+  if (qt < g.nQt) tile_scan_row(g, tb, cb, rr, col_any, col_all, off_any, off_all, occ, full, cnt, gidx, gcnt, gstride, vocc, vfull, h, qt, lane);
 }
 
 // Pass 2: write column, kind and the tile's element bits for every listed tile (below capacity).
@@ -1689,9 +1757,13 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   return w;
 }
 
-// a1 and the threshold of a2. attn_sum / attn_cnt are only read in the general minimum.
-void stage_threshold(const dam_mask_params *p, const Geom &g, const Workspace &w, const float *attn_sum,
-                     const float *attn_cnt, hipStream_t stream) {
+// a1 and the threshold of a2. attn_sum / attn_cnt are only read in the general minimum. Returns how the
+// true-mask kernel gets the key: by value when the host could find it (then that kernel also writes out_bmin),
+// else from the workspace (in_workspace forces that form: the capture kernels read the key there).
+Threshold stage_threshold(const dam_mask_params *p, const Geom &g, const Workspace &w, const float *attn_sum,
+                          const float *attn_cnt, hipStream_t stream, float *out_bmin, bool in_workspace, bool *bmin_written) {
+  const Threshold from_ws{w.theta_key, 0u, 0.0f, nullptr};
+  *bmin_written = false;
   if (p->transform != DAM_T_BOXCOX) {
     // App. B alternatives: one reduction pass for the statistics, then minimum and threshold together
     const int64_t n = (int64_t)g.H * g.L * g.L;
@@ -1700,23 +1772,30 @@ void stage_threshold(const dam_mask_params *p, const Geom &g, const Workspace &w
     k_stats<<<blocks, 256, 0, stream>>>(attn_sum, attn_cnt, n, g.L, p->eps, w.stats);
     k_transform_threshold<<<1, 64, 0, stream>>>(p->transform, p->lambda, p->eps, p->tau, p->bmin_override, w.stats,
                                                 attn_cnt == nullptr, (float)n, (double)n, w.bmin, w.theta_key);
-    return;
+    return from_ws;
   }
   const bool half = p->lambda == 0.5f;
-  // a1: the global minimum of the Box-Cox map
-  if (!isnan(p->bmin_override)) {
-    k_set_f32<<<1, 64, 0, stream>>>(w.bmin, p->bmin_override);
-  } else if (!attn_cnt && g.L >= 2) {
-    if (half) k_bmin_closed<1><<<1, 64, 0, stream>>>(p->eps, w.bmin);
-    else k_bmin_closed<2><<<1, 64, 0, stream>>>(p->eps, w.bmin);
-  } else {
-    const int64_t n = (int64_t)g.H * g.L * g.L;
-    k_fill_u32<<<1, 64, 0, stream>>>(w.xmin_bits, 1, 0x7F800000u);
-    const int blocks = (int)std::min<int64_t>((n + 1023) / 1024, 256 * 16);
-    k_min_x<<<blocks, 256, 0, stream>>>(attn_sum, attn_cnt, n, g.L, p->eps, w.xmin_bits);
-    if (half) k_bmin_from_x<1><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
-    else k_bmin_from_x<2><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
+  // a1: the global minimum of the Box-Cox map. Known without the data when the caller overrides it, and for a single
+  // causal capture with L >= 2 (some pair was never computed: its X is the clamp eps, and no X is smaller)
+  if (!isnan(p->bmin_override) || (!attn_cnt && g.L >= 2)) {
+    const float x_min = clamp_mean(0.0f, 0.0f, p->eps);
+    const float bmin = !isnan(p->bmin_override) ? p->bmin_override : (half ? box_cox<1>(x_min) : box_cox<2>(x_min));
+    unsigned key;
+    if (half) key = attn_cnt ? threshold_key<1, false>(p->eps, p->tau, bmin) : threshold_key<1, true>(p->eps, p->tau, bmin);
+    else key = attn_cnt ? threshold_key<2, false>(p->eps, p->tau, bmin) : threshold_key<2, true>(p->eps, p->tau, bmin);
+    *bmin_written = true;
+    if (in_workspace) {
+      k_set_threshold<<<1, 64, 0, stream>>>(bmin, key, w.bmin, w.theta_key, out_bmin);
+      return from_ws;
+    }
+    return Threshold{nullptr, key, bmin, out_bmin};
   }
+  const int64_t n = (int64_t)g.H * g.L * g.L;
+  k_fill_u32<<<1, 64, 0, stream>>>(w.xmin_bits, 1, 0x7F800000u);
+  const int blocks = (int)std::min<int64_t>((n + 1023) / 1024, 256 * 16);
+  k_min_x<<<blocks, 256, 0, stream>>>(attn_sum, attn_cnt, n, g.L, p->eps, w.xmin_bits);
+  if (half) k_bmin_from_x<1><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
+  else k_bmin_from_x<2><<<1, 64, 0, stream>>>(w.xmin_bits, w.bmin);
   // a2: the threshold, found once
   if (half) {
     if (attn_cnt) k_threshold<1, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
@@ -1725,24 +1804,24 @@ void stage_threshold(const dam_mask_params *p, const Geom &g, const Workspace &w
     if (attn_cnt) k_threshold<2, false><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
     else k_threshold<2, true><<<1, 64, 0, stream>>>(p->eps, p->tau, w.bmin, w.theta_key);
   }
+  return from_ws;
 }
 
 // a3: match scores of the true mask in o->true_bits; returns where the flags were written.
 void stage_patterns(const dam_mask_params *p, const Geom &g, const Workspace &w, const dam_mask_out *o,
-                    hipStream_t stream, const uint8_t **dflag, const uint8_t **vflag) {
+                    hipStream_t stream, const uint8_t **dflag, const uint8_t **vflag, bool bmin_written) {
   uint8_t *df = o->diag_flag ? o->diag_flag : w.diag_flag;
   uint8_t *vf = o->vert_flag ? o->vert_flag : w.vert_flag;
   const int n_chunks = (g.L + kChunkRows - 1) / kChunkRows;
-  const dim3 sgrid((g.tbw + 63) / 64, (n_chunks + 3) / 4, g.H);
-  k_pattern_slices<false><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices);
-  k_pattern_slices<true><<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.dslices);
+  const dim3 sgrid(2 * ((g.tbw + 63) / 64), (n_chunks + 3) / 4, g.H);
+  k_pattern_slices<<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices, w.dslices);
   int nb = 1;  // bits of the largest possible count, L
   while ((g.L >> nb) != 0) ++nb;
   k_pattern_finish<<<dim3((g.tbw + 63) / 64, g.H, 2), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, nb, p->mu,
                                                                        o->vert_cnt, o->diag_cnt, vf, df);
   *dflag = df;
   *vflag = vf;
-  if (o->bmin) k_copy_f32<<<1, 64, 0, stream>>>(o->bmin, w.bmin);
+  if (o->bmin && !bmin_written) k_copy_f32<<<1, 64, 0, stream>>>(o->bmin, w.bmin);
 }
 
 // a4 + a5 and the kept lists: everything downstream of the stored artefact.
@@ -1750,21 +1829,20 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
                      const uint64_t *true_bits, const uint8_t *dflag, const uint8_t *vflag, hipStream_t stream) {
   const bool want_blocks = o->blk_row_ptr != nullptr;
   const bool want_lists = o->kept_ptr != nullptr;
+  const bool gather = want_blocks && (p->flags & DAM_MASK_GATHER_COLUMNS) != 0;
+  const int gstride = dam_gather_stride(p);
+  const int *gidx = gather ? o->gather_idx : nullptr, *gcnt = gather ? o->gather_cnt : nullptr;
   if (want_blocks || want_lists || o->dense_bits) {
-    k_pattern_bitsets<<<dim3((g.pw + 63) / 64, g.H), 256, 0, stream>>>(dflag, vflag, g.P, g.pw, w.cbits, w.rrev);
+    k_pattern_prep<<<g.H, 1024, 0, stream>>>(g, dflag, vflag, w.cbits, w.rrev, want_blocks, w.col_any, w.col_all, w.off_any,
+                                            w.off_all, gstride, gather ? o->gather_idx : nullptr, gather ? o->gather_cnt : nullptr);
   }
   // a4 + a5: tile occupancy, CSR offsets, tile bits
   if (want_blocks) {
-    k_tile_classes<<<dim3(g.occw, g.H), 64, 0, stream>>>(g, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any, w.off_all);
     const size_t lds_sets = staged_bytes(g);
-    const bool gather = (p->flags & DAM_MASK_GATHER_COLUMNS) != 0;
-    const int gstride = dam_gather_stride(p);
-    const int *gidx = gather ? o->gather_idx : nullptr, *gcnt = gather ? o->gather_cnt : nullptr;
-    if (gather) k_gather_columns<<<g.H, 1024, 0, stream>>>(g, w.cbits, gstride, o->gather_idx, o->gather_cnt);
+    const bool fill = o->blk_col || o->blk_kind || o->tile_bits;
     k_tile_scan<<<dim3((g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
                                                                      w.off_all, w.occ, w.full, w.tile_cnt, lds_sets > 0, gidx,
                                                                      gcnt, gstride, w.vocc, w.vfull);
-    const bool fill = o->blk_col || o->blk_kind || o->tile_bits;
     k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total,
                                              fill ? o->blk_capacity : INT64_MAX);
     if (fill)
@@ -1845,20 +1923,21 @@ extern "C" int dam_mask_build(const dam_mask_params *p, const float *attn_sum, c
   const uint64_t *true_bits = g.L > 0 ? o->true_bits : nullptr;
 
   if (p->mode == DAM_FROM_ATTN_MAP) {
-    stage_threshold(p, g, w, attn_sum, attn_cnt, stream);
+    bool bmin_written;
+    const Threshold thr = stage_threshold(p, g, w, attn_sum, attn_cnt, stream, o->bmin, false, &bmin_written);
     // a2: true mask, one comparison per element
     dim3 grid((g.tbw + 3) / 4, (g.L + kTmRows - 1) / kTmRows, g.H);
     if (attn_cnt && p->transform == DAM_T_RAW_SUM)
-      k_true_mask<false, true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
+      k_true_mask<false, true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, thr, o->true_bits);
     else if (attn_cnt)
-      k_true_mask<false><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
+      k_true_mask<false><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, thr, o->true_bits);
     else if (g.L % 4 == 0 && (reinterpret_cast<uintptr_t>(attn_sum) & 15) == 0) {
       const int n_pairs = (((g.L + 1) / 2) + 3) / 4;
       const int per_map = std::max(1, std::min(n_pairs, kGridTarget / g.H));
-      k_true_mask_rows<<<dim3(per_map, g.H), 256, 0, stream>>>(attn_sum, g.L, g.tbw, n_pairs, w.theta_key, o->true_bits);
+      k_true_mask_rows<<<dim3(per_map, g.H), 256, 0, stream>>>(attn_sum, g.L, g.tbw, n_pairs, thr, o->true_bits);
     } else
-      k_true_mask<true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, w.theta_key, o->true_bits);
-    stage_patterns(p, g, w, o, stream, &dflag, &vflag);
+      k_true_mask<true><<<grid, 256, 0, stream>>>(attn_sum, attn_cnt, g.L, g.tbw, p->eps, thr, o->true_bits);
+    stage_patterns(p, g, w, o, stream, &dflag, &vflag, bmin_written);
   }
   stage_extension(p, g, w, o, true_bits, dflag, vflag, stream);
   return launch_status();
@@ -1890,9 +1969,10 @@ extern "C" int dam_mask_build_from_qk(const dam_mask_params *p, const dam_captur
   const Workspace w = carve(p, ws);
   float *lse2 = reinterpret_cast<float *>(static_cast<char *>(ws) + w.bytes);
   const uint8_t *dflag = nullptr, *vflag = nullptr;
-  stage_threshold(p, g, w, nullptr, nullptr, stream);
+  bool bmin_written;
+  stage_threshold(p, g, w, nullptr, nullptr, stream, o->bmin, true, &bmin_written);
   launch_capture_true_bits(cp, q, k, lse2, w.theta_key, o->true_bits, stream);
-  stage_patterns(p, g, w, o, stream, &dflag, &vflag);
+  stage_patterns(p, g, w, o, stream, &dflag, &vflag, bmin_written);
   stage_extension(p, g, w, o, o->true_bits, dflag, vflag, stream);
   return launch_status();
 }
