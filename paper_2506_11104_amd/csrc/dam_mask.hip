@@ -1143,7 +1143,11 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
   if (qt < g.nQt) tile_scan_row(g, tb, cb, rr, col_any, col_all, off_any, off_all, occ, full, cnt, gidx, gcnt, gstride, vocc, vfull, h, qt, lane);
 }
 
-// Pass 2: write column, kind and the tile's element bits for every listed tile (below capacity).
+// Pass 2: write column, kind and the tile's element bits for every listed tile (below capacity). A wave per
+// query tile (the four of a workgroup belong to one head and share its staged sets): the wave walks its own row
+// of the index and writes every listed tile itself, a lane per tile row. With few query tiles in all (share = 4) the
+// four waves of a workgroup share one query tile instead, each walking the whole row and taking every fourth
+// tile: more waves, but the walk is then three quarters of the instructions.
 __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__restrict__ true_bits,
                                                    const uint64_t *__restrict__ cbits,
                                                    const uint64_t *__restrict__ rrev,
@@ -1156,11 +1160,13 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
                                                    bool skip_full_bits, bool staged,
                                                    const int *__restrict__ gidx, const int *__restrict__ gcnt,
                                                    int gstride, const uint64_t *__restrict__ vocc,
-                                                   const uint64_t *__restrict__ vfull) {
+                                                   const uint64_t *__restrict__ vfull, int share) {
   extern __shared__ uint64_t lds_sets[];
-  __shared__ int s_kind;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int qt = blockIdx.x, h = blockIdx.y;
+  const int h = blockIdx.y;
+  const int my_qt = share == 4 ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave, my_turn = share == 4 ? wave : 0;
+  const bool live = my_qt < g.nQt;
+  const int qt = live ? my_qt : g.nQt - 1;  // (a spare wave reads a valid row and writes nothing)
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
@@ -1171,6 +1177,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int64_t first = row_ptr[(int64_t)h * (g.nQt + 1) + qt];
   uint64_t ow_next = oc[0], fw_next = fl[0];
   stage_sets(lds_sets, staged, g.pw, cb, rr);
+  if (!live) return;
   const int i_last = min(g.S - 1, qt * g.tile_m + g.tile_m - 1);
   const int kmax = i_last / g.tile_n;
   const int words = g.tile_m * g.wpr;
@@ -1178,7 +1185,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   // gathered columns: the ordinary tiles of a query tile of the pattern region hold the diagonal part only
   const bool split = gidx != nullptr && qt * g.tile_m >= g.L;
   if (split) cb = nullptr;
-  // walk the listed tiles of this query tile in ascending order; wave w takes every fourth one
+  // walk the listed tiles of this query tile in ascending order
   int rank = 0;
   for (int ow_i = 0; ow_i <= (kmax >> 6); ++ow_i) {
     uint64_t ow = ow_next;
@@ -1191,7 +1198,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       const int kt = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
       ow &= ow - 1;
       const int64_t t = first + rank;
-      const bool mine = (rank & 3) == wave;
+      const bool mine = rank % share == my_turn;
       ++rank;
       if (!mine || t >= capacity) continue;
       // element words, and which key quarters of the tile hold a kept entry
@@ -1291,8 +1298,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int n_gt = (gcnt[h] + g.tile_n - 1) / g.tile_n;
   const int *gi = gidx + (int64_t)h * gstride;
   const int i0 = qt * g.tile_m;
-  // every gathered tile is shared by the four waves: unit u = (slot group wg, row word k) goes to wave
-  // u % 4 (128 x 128 tiles: one unit each), the quarter flags meet in s_kind
+  // a gathered tile: its units u = (slot group wg, row word k), one after the other (128 x 128 tiles: four)
   const int units = g.wpr * (g.tile_m / 64);
   for (int ow_i = 0; ow_i * 64 < n_gt; ++ow_i) {
     uint64_t ow = voc[ow_i];
@@ -1301,13 +1307,12 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       const int v = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
       ow &= ow - 1;
       const int64_t t = first + rank;
+      const bool mine = rank % share == my_turn;
       ++rank;
-      if (t >= capacity) continue;  // the same in every wave
+      if (!mine || t >= capacity) continue;
       const bool is_full = (vfw >> (v & 63)) & 1;
-      if (threadIdx.x == 0) s_kind = 0;
-      __syncthreads();
       int kind = 0;
-      for (int u = wave; u < units; u += 4) {
+      for (int u = 0; u < units; ++u) {
         const int wg = u % g.wpr, k = u / g.wpr;
         const int slot = wg * 64 + lane;  // slot of this lane inside the tile
         uint64_t keep[4];
@@ -1328,11 +1333,9 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
           tile_bits[t * words + (int64_t)(64 * k + lane) * g.wpr + wg] = transpose64(rows_k, lane);
         }
       }
-      if (lane == 0 && kind) atomicOr(&s_kind, kind);
-      __syncthreads();
-      if (threadIdx.x == 0) {
+      if (lane == 0) {
         if (blk_col) blk_col[t] = g.nKt + v;
-        if (blk_kind) blk_kind[t] = (uint8_t)((is_full ? 1 : 0) | s_kind);
+        if (blk_kind) blk_kind[t] = (uint8_t)((is_full ? 1 : 0) | kind);
       }
     }
   }
@@ -1845,11 +1848,12 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
                                                                      gcnt, gstride, w.vocc, w.vfull);
     k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total,
                                              fill ? o->blk_capacity : INT64_MAX);
-    if (fill)
-      k_tile_fill<<<dim3(g.nQt, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr,
-                                                               o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
-                                                               (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0,
-                                                               gidx, gcnt, gstride, w.vocc, w.vfull);
+    if (fill) {
+      const int share = (int64_t)g.H * g.nQt >= 2048 ? 1 : 4;  // enough query tiles to give every wave its own
+      k_tile_fill<<<dim3(share == 4 ? g.nQt : (g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(
+          g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr, o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
+          (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0, gidx, gcnt, gstride, w.vocc, w.vfull, share);
+    }
   }
   if (o->dense_bits) {
     const int sw = (g.S + 63) / 64;
