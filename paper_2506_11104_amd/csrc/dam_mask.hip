@@ -53,17 +53,6 @@ __host__ __device__ __forceinline__ float box_cox(float x) {
   return x - 1.0f;
 }
 
-// Single causal capture with L >= 2: some pair was never computed, its X is the clamp eps, and no
-// X is smaller; Box-Cox is non-decreasing, so the global minimum is the Box-Cox of eps.
-template <int LAMBDA2>
-__global__ void k_bmin_closed(float eps, float *bmin) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *bmin = box_cox<LAMBDA2>(clamp_mean(0.0f, 0.0f, eps));
-}
-
-__global__ void k_set_f32(float *p, float v) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
-}
-
 __global__ void k_copy_f32(float *dst, const float *src) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *dst = *src;
 }
