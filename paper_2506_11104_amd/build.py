@@ -19,6 +19,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.j
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fhip-fp32-correctly-rounded-divide-sqrt", "-Wall", "-Wno-unused-function",
          "-Wno-unknown-warning-option", "-Wno-inline-asm"]
 
+# The capture kernels read every accumulator right after its chain of products: with the results in
+# ordinary vector registers no copies out of the accumulation registers are needed.
+EXTRA = {"dam_capture.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
@@ -33,7 +37,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
     def compile_one(src):
         obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-        cmd = ["hipcc", "-c", src, "-o", obj] + FLAGS
+        cmd = ["hipcc", "-c", src, "-o", obj] + FLAGS + EXTRA.get(os.path.basename(src), [])
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
