@@ -467,8 +467,10 @@ __device__ __forceinline__ void csa(uint64_t &carry, uint64_t &sum, uint64_t a, 
   sum = u ^ c;
 }
 
-// (one launch for both pattern kinds: the upper half of the grid's x range counts diagonals)
-__global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restrict__ true_bits, int L, int tbw,
+// Form for rows of more than 128 words (capture lengths above 8192): a wave per 64 rows and 64 words,
+// every word fetched from global memory by the lane that owns it (one launch for both pattern kinds: the
+// upper half of the grid's x range counts diagonals).
+__global__ __launch_bounds__(256) void k_pattern_slices_wide(const uint64_t *__restrict__ true_bits, int L, int tbw,
                                                         int n_chunks, uint64_t *__restrict__ vslices,
                                                         uint64_t *__restrict__ dslices) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -530,12 +532,114 @@ __global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restri
   for (int k = 0; k < kSlices; ++k) out[(int64_t)k * tbw] = s[k];
 }
 
+// Form for rows of up to 128 words: one workgroup per (head, chunk of 64 rows) counts both pattern
+// kinds from one copy of the chunk in LDS, so that the true mask is read once (its lower triangle
+// only: a word past the chunk's diagonal holds nothing). W = the row length in words rounded up to
+// a power of two (16 .. 128); thread t owns word t % W of the rows t / W, t / W + 256 / W, ...:
+// for the columns that is the row's word itself, for the diagonals the window of the row that ends
+// at column i - 64 w, reversed (two neighbouring words of the LDS copy, a funnel shift and a bit
+// reversal). The 256 / W partial counters of a word are added through LDS (bit-sliced, 7 + 7 bits).
+__global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restrict__ true_bits, int L, int tbw,
+                                                        int n_chunks, int W, uint64_t *__restrict__ vslices,
+                                                        uint64_t *__restrict__ dslices) {
+  extern __shared__ uint64_t sm[];  // [64][W] row words, afterwards [2][256 / W][kSlices][W] partial counters
+  const int chunk = blockIdx.x, h = blockIdx.y, i0 = chunk * kChunkRows;
+  const int rows = min(kChunkRows, L - i0);
+  const int wmax = min(tbw, chunk + 1);  // words that can hold a kept entry of these rows
+  const int wl = threadIdx.x & (W - 1), sub = threadIdx.x / W, nsub = 256 / W;
+  const uint64_t *tb = true_bits + ((int64_t)h * L + i0) * tbw;
+  for (int r = sub; r < kChunkRows; r += nsub)
+    sm[r * W + wl] = (r < rows && wl < wmax) ? __builtin_nontemporal_load(tb + (int64_t)r * tbw + wl) : 0;
+  __syncthreads();
+  uint64_t sc[kSlices], sd[kSlices];
+#pragma unroll
+  for (int k = 0; k < kSlices; ++k) sc[k] = sd[k] = 0;
+  const int wj = chunk - wl;  // word of column i - 64 wl, the same for every row of the chunk
+  const int per_thread = kChunkRows / nsub;
+  for (int g = 0; g < per_thread; g += 8) {
+    uint64_t c[8], d[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = sub + nsub * (g + u);  // rows past the chunk's end are zero in LDS
+      uint64_t xc = 0, xd = 0;
+      if (g + u < per_thread) {
+        xc = sm[r * W + wl];
+        if (wj >= 0) {
+          const int sh = r + 1;  // window = bits jhi - 63 .. jhi of the row, jhi = 64 wj + r
+          const uint64_t hi = sm[r * W + wj];
+          const uint64_t lo = wj > 0 ? sm[r * W + wj - 1] : 0;
+          const uint64_t win = sh == 64 ? hi : ((hi << (64 - sh)) | (lo >> sh));
+          xd = __brevll(win);  // offset r = 64 wl + t at bit t
+        }
+      }
+      c[u] = xc;
+      d[u] = xd;
+    }
+    uint64_t t0, t1, f0, f1, e;
+    csa(t0, sc[0], sc[0], c[0], c[1]);
+    csa(t1, sc[0], sc[0], c[2], c[3]);
+    csa(f0, sc[1], sc[1], t0, t1);
+    csa(t0, sc[0], sc[0], c[4], c[5]);
+    csa(t1, sc[0], sc[0], c[6], c[7]);
+    csa(f1, sc[1], sc[1], t0, t1);
+    csa(e, sc[2], sc[2], f0, f1);
+#pragma unroll
+    for (int k = 3; k < kSlices; ++k) {
+      const uint64_t cy = sc[k] & e;
+      sc[k] ^= e;
+      e = cy;
+    }
+    csa(t0, sd[0], sd[0], d[0], d[1]);
+    csa(t1, sd[0], sd[0], d[2], d[3]);
+    csa(f0, sd[1], sd[1], t0, t1);
+    csa(t0, sd[0], sd[0], d[4], d[5]);
+    csa(t1, sd[0], sd[0], d[6], d[7]);
+    csa(f1, sd[1], sd[1], t0, t1);
+    csa(e, sd[2], sd[2], f0, f1);
+#pragma unroll
+    for (int k = 3; k < kSlices; ++k) {
+      const uint64_t cy = sd[k] & e;
+      sd[k] ^= e;
+      e = cy;
+    }
+  }
+  __syncthreads();  // the row words are no longer needed: their place takes the partial counters
+#pragma unroll
+  for (int k = 0; k < kSlices; ++k) {
+    sm[((0 * nsub + sub) * kSlices + k) * W + wl] = sc[k];
+    sm[((1 * nsub + sub) * kSlices + k) * W + wl] = sd[k];
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < 2 * W) {
+    const int kind = threadIdx.x / W;  // 0 columns, 1 diagonals
+    uint64_t acc[kSlices];
+#pragma unroll
+    for (int k = 0; k < kSlices; ++k) acc[k] = 0;
+    for (int x = 0; x < nsub; ++x) {
+      uint64_t carry = 0;
+#pragma unroll
+      for (int k = 0; k < kSlices; ++k) {
+        const uint64_t in = sm[((kind * nsub + x) * kSlices + k) * W + wl];
+        const uint64_t u = acc[k] ^ in;
+        const uint64_t cy = (acc[k] & in) | (u & carry);
+        acc[k] = u ^ carry;
+        carry = cy;
+      }
+    }
+    if (wl < tbw) {
+      uint64_t *out = (kind ? dslices : vslices) + (((int64_t)h * n_chunks + chunk) * kSlices) * tbw + wl;
+#pragma unroll
+      for (int k = 0; k < kSlices; ++k) out[(int64_t)k * tbw] = acc[k];
+    }
+  }
+}
+
 // gamma = count / size >= mu for pattern p of head h (Sec. 4.2.4), counts summed over the row chunks.
-// The chunk counts stay bit-sliced while they are added: lane = word of 64 patterns (coalesced loads
-// of the slices), each wave ripple-adds the 7-slice counts of its share of the chunks into a wider
-// bit-sliced sum (a full adder is five logic operations on 64 patterns at once), the four sums are
-// added once more, and only then every thread extracts the integer counts of its patterns.
-// blockIdx.z: 0 vertical, 1 diagonal patterns; blockIdx.x: group of 64 words.
+// The chunk counts stay bit-sliced while they are added: a thread owns one word of 64 patterns and a
+// sixteenth of the chunks, ripple-adds their 7-slice counts into a wider bit-sliced sum (a full adder is
+// five logic operations on 64 patterns at once), the sixteen sums of a word are added pairwise, and only
+// then every thread extracts the integer counts of its patterns.
+// blockIdx.z: 0 vertical, 1 diagonal patterns; blockIdx.x: group of 16 words.
 constexpr int kAccSlices = 17;  // counts below 2^17: pcl is limited accordingly
 
 template <int NIN>
@@ -553,54 +657,59 @@ __device__ __forceinline__ void sliced_add(uint64_t (&acc)[kAccSlices], const ui
   }
 }
 
+constexpr int kFinWords = 16;  // words (of 64 patterns) per workgroup of k_pattern_finish
+
 __global__ __launch_bounds__(256) void k_pattern_finish(const uint64_t *__restrict__ vslices,
                                                         const uint64_t *__restrict__ dslices, int L, int tbw,
                                                         int n_chunks, int nb, float mu, int *__restrict__ vert_cnt,
                                                         int *__restrict__ diag_cnt, uint8_t *__restrict__ vert_flag,
                                                         uint8_t *__restrict__ diag_flag) {
-  __shared__ uint64_t part[3][kAccSlices][64];
-  __shared__ uint64_t total[kAccSlices][64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int h = blockIdx.y, word0 = blockIdx.x * 64;
+  // thread t: word t % 16 of the group, chunks t / 16, t / 16 + 16, ...; the 16 partial sums of a word are
+  // then added pairwise through LDS
+  __shared__ uint64_t part[16][kAccSlices][kFinWords];
+  const int wi = threadIdx.x & (kFinWords - 1), sub = threadIdx.x / kFinWords;
+  const int h = blockIdx.y, word0 = blockIdx.x * kFinWords;
   const bool diag = blockIdx.z == 1;
   const uint64_t *slices = diag ? dslices : vslices;
   int *cnt_out = diag ? diag_cnt : vert_cnt;
   uint8_t *flag_out = diag ? diag_flag : vert_flag;
-  const int wl = word0 + lane;
+  const int wl = word0 + wi;
   uint64_t acc[kAccSlices];
 #pragma unroll
   for (int k = 0; k < kAccSlices; ++k) acc[k] = 0;
   // rows above pattern p hold nothing of it: start at the chunk of the group's first pattern
-  for (int chunk = word0 * 64 / kChunkRows + wave; chunk < n_chunks; chunk += 4) {
+  for (int chunk = word0 * 64 / kChunkRows + sub; chunk < n_chunks; chunk += 16) {
     uint64_t in[kSlices];
     const int64_t at = (((int64_t)h * n_chunks + chunk) * kSlices) * tbw + wl;
 #pragma unroll
     for (int k = 0; k < kSlices; ++k) in[k] = wl < tbw ? slices[at + (int64_t)k * tbw] : 0;
     sliced_add(acc, in, nb);
   }
-  if (wave > 0) {
+  for (int half = 8; half >= 1; half >>= 1) {
+    if (sub >= half && sub < 2 * half) {
 #pragma unroll
-    for (int k = 0; k < kAccSlices; ++k) part[wave - 1][k][lane] = acc[k];
-  }
-  __syncthreads();
-  if (wave == 0) {
-    for (int w = 0; w < 3; ++w) {
+      for (int k = 0; k < kAccSlices; ++k) part[sub][k][wi] = acc[k];
+    }
+    __syncthreads();
+    if (sub < half) {
       uint64_t in[kAccSlices];
 #pragma unroll
-      for (int k = 0; k < kAccSlices; ++k) in[k] = part[w][k][lane];
+      for (int k = 0; k < kAccSlices; ++k) in[k] = part[sub + half][k][wi];
       sliced_add(acc, in, nb);
     }
+  }
+  if (sub == 0) {
 #pragma unroll
-    for (int k = 0; k < kAccSlices; ++k) total[k][lane] = acc[k];
+    for (int k = 0; k < kAccSlices; ++k) part[0][k][wi] = acc[k];
   }
   __syncthreads();
-  const int p_end = min(L, (word0 + 64) * 64);
+  const int p_end = min(L, (word0 + kFinWords) * 64);
   for (int p = word0 * 64 + threadIdx.x; p < p_end; p += 256) {
     const int wd = (p >> 6) - word0, t = p & 63;
     int cnt = 0;
 #pragma unroll
     for (int k = 0; k < kAccSlices; ++k)
-      if (k < nb) cnt |= (int)((total[k][wd] >> t) & 1) << k;
+      if (k < nb) cnt |= (int)((part[0][k][wd] >> t) & 1) << k;
     const int64_t e = (int64_t)h * L + p;
     if (cnt_out) cnt_out[e] = cnt;
     const float size = (float)(L - p);
@@ -1805,11 +1914,18 @@ void stage_patterns(const dam_mask_params *p, const Geom &g, const Workspace &w,
   uint8_t *df = o->diag_flag ? o->diag_flag : w.diag_flag;
   uint8_t *vf = o->vert_flag ? o->vert_flag : w.vert_flag;
   const int n_chunks = (g.L + kChunkRows - 1) / kChunkRows;
-  const dim3 sgrid(2 * ((g.tbw + 63) / 64), (n_chunks + 3) / 4, g.H);
-  k_pattern_slices<<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices, w.dslices);
+  if (g.tbw <= 128) {
+    int W = 16;
+    while (W < g.tbw) W *= 2;
+    const size_t lds = std::max<size_t>((size_t)kChunkRows * W, (size_t)2 * 256 * kSlices) * sizeof(uint64_t);
+    k_pattern_slices<<<dim3(n_chunks, g.H), 256, lds, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, W, w.vslices, w.dslices);
+  } else {
+    const dim3 sgrid(2 * ((g.tbw + 63) / 64), (n_chunks + 3) / 4, g.H);
+    k_pattern_slices_wide<<<sgrid, 256, 0, stream>>>(o->true_bits, g.L, g.tbw, n_chunks, w.vslices, w.dslices);
+  }
   int nb = 1;  // bits of the largest possible count, L
   while ((g.L >> nb) != 0) ++nb;
-  k_pattern_finish<<<dim3((g.tbw + 63) / 64, g.H, 2), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, nb, p->mu,
+  k_pattern_finish<<<dim3((g.tbw + kFinWords - 1) / kFinWords, g.H, 2), 256, 0, stream>>>(w.vslices, w.dslices, g.L, g.tbw, n_chunks, nb, p->mu,
                                                                        o->vert_cnt, o->diag_cnt, vf, df);
   *dflag = df;
   *vflag = vf;

@@ -124,6 +124,14 @@ def test_threshold_boundary_values_round_like_the_oracle():
     run_from_map(A, None, 300, 64, 64, 1.0, 1e-8, float(theta) - 1e-8, 0.8)
 
 
+@pytest.mark.parametrize("L", [1100, 4160, 8256])   # rows of 18, 65 and 129 words: every form of the pattern counters
+def test_pattern_counts_at_every_row_length(L):
+    rng = np.random.default_rng(20250611 + L)
+    A = np.tril(rng.random((1, L, L), dtype=np.float32) ** 4).astype(np.float32)
+    # kept iff sqrt(a) >= tau / 2 (+ 1e-4): a third of the entries, so that gamma scatters around mu
+    run_from_map(A, None, L, 128, 128, 0.5, 1e-8, 0.9, 0.33, dense=False)
+
+
 @pytest.mark.parametrize("L", [256, 202])       # the row-streaming kernel (L % 4 == 0) and the general one
 @pytest.mark.parametrize("tau", [0.3, 0.0, -0.5, 1e30])
 def test_special_values_in_the_map_follow_the_fixed_sequence(L, tau):
