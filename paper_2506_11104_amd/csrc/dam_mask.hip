@@ -534,22 +534,36 @@ __global__ __launch_bounds__(256) void k_pattern_slices_wide(const uint64_t *__r
 
 // Form for rows of up to 128 words: one workgroup per (head, chunk of 64 rows) counts both pattern
 // kinds from one copy of the chunk in LDS, so that the true mask is read once (its lower triangle
-// only: a word past the chunk's diagonal holds nothing). W = the row length in words rounded up to
-// a power of two (16 .. 128); thread t owns word t % W of the rows t / W, t / W + 256 / W, ...:
+// only: a word past the chunk's diagonal holds nothing). W = the number of words up to that diagonal
+// rounded up to a power of two (16 .. 128); thread t owns word t % W of the rows t / W, t / W + 256 / W, ...:
 // for the columns that is the row's word itself, for the diagonals the window of the row that ends
 // at column i - 64 w, reversed (two neighbouring words of the LDS copy, a funnel shift and a bit
 // reversal). The 256 / W partial counters of a word are added through LDS (bit-sliced, 7 + 7 bits).
 __global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restrict__ true_bits, int L, int tbw,
-                                                        int n_chunks, int W, uint64_t *__restrict__ vslices,
+                                                        int n_chunks, int Wmax, uint64_t *__restrict__ vslices,
                                                         uint64_t *__restrict__ dslices) {
   extern __shared__ uint64_t sm[];  // [64][W] row words, afterwards [2][256 / W][kSlices][W] partial counters
   const int chunk = blockIdx.x, h = blockIdx.y, i0 = chunk * kChunkRows;
   const int rows = min(kChunkRows, L - i0);
   const int wmax = min(tbw, chunk + 1);  // words that can hold a kept entry of these rows
+  int W = 16;                            // ... rounded up to a power of two: the threads share those words only
+  while (W < wmax) W *= 2;
+  W = min(W, Wmax);
   const int wl = threadIdx.x & (W - 1), sub = threadIdx.x / W, nsub = 256 / W;
   const uint64_t *tb = true_bits + ((int64_t)h * L + i0) * tbw;
-  for (int r = sub; r < kChunkRows; r += nsub)
-    sm[r * W + wl] = (r < rows && wl < wmax) ? __builtin_nontemporal_load(tb + (int64_t)r * tbw + wl) : 0;
+  for (int r0 = sub; r0 < kChunkRows; r0 += 8 * nsub) {  // eight loads in flight per thread
+    uint64_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = r0 + u * nsub;
+      v[u] = (r < rows && wl < wmax) ? __builtin_nontemporal_load(tb + (int64_t)r * tbw + wl) : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = r0 + u * nsub;
+      if (r < kChunkRows) sm[r * W + wl] = v[u];
+    }
+  }
   __syncthreads();
   uint64_t sc[kSlices], sd[kSlices];
 #pragma unroll
@@ -631,6 +645,12 @@ __global__ __launch_bounds__(256) void k_pattern_slices(const uint64_t *__restri
 #pragma unroll
       for (int k = 0; k < kSlices; ++k) out[(int64_t)k * tbw] = acc[k];
     }
+  }
+  // words past the chunk's diagonal: nothing counted
+  const int rest = tbw - W;
+  for (int x = threadIdx.x; x < 2 * kSlices * rest; x += 256) {
+    const int kind = x / (kSlices * rest), k = (x / rest) % kSlices, w = W + x % rest;
+    ((kind ? dslices : vslices) + (((int64_t)h * n_chunks + chunk) * kSlices) * tbw)[(int64_t)k * tbw + w] = 0;
   }
 }
 
