@@ -351,7 +351,12 @@ __device__ __forceinline__ void pipe_iter(const unsigned char *__restrict__ lds,
 // one piece per segment (bk(x)), behind the operand reads (the copies are volatile statements that LDS reads do
 // not move across), and only the flag test, the wait for the copies, the barrier and the first operand reads
 // remain between two iterations.
-template <int PH, class Bk>
+// PART says which of the three streams the iteration holds: kAll in the steady state; the first iteration of a
+// pass (block -1, kChainOnly) has no weights to compute and nothing to add to O, the second one (block 0,
+// kNoPV) nothing to add to O yet (P_{-1} is zero). (The last iteration, whose block is the trailing dummy, stays
+// whole: a second way out of the loop's iterations makes the compiler copy the 64 accumulators of O every time.)
+enum { kAll = 0, kChainOnly = 1, kNoPV = 2 };
+template <int PH, int PART, class Bk>
 __device__ __forceinline__ void pipe_iter_seg(const unsigned char *__restrict__ lds, const bf16x8 (&qf)[8],
                                               f32x16 (&oacc)[4], const f32x16 &sA, f32x16 &sB,
                                               const unsigned (&pPrev)[8], unsigned (&pCur)[8], float &l_run,
@@ -367,25 +372,30 @@ __device__ __forceinline__ void pipe_iter_seg(const unsigned char *__restrict__ 
   typedef __attribute__((ext_vector_type(8))) short s16x8;
   bf16x8 kf[8];
   s16x8 vf[2][4];
+  constexpr bool kChain = true, kWeights = PART != kChainOnly, kPV = PART == kAll;
   auto fetch = [&](int x) {
-    kf[x] = lds_read_b128(lds, KS + kaddr[x]);
-    const int a2 = x >> 2, db = x & 3;
-    const s16x4 r0 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16) * 256);
-    const s16x4 r1 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16 + 8) * 256);
-    vf[a2][db] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+    if (kChain) kf[x] = lds_read_b128(lds, KS + kaddr[x]);
+    if (kPV) {
+      const int a2 = x >> 2, db = x & 3;
+      const s16x4 r0 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16) * 256);
+      const s16x4 r1 = lds_read_tr(lds, VS + vaddr[db] + (a2 * 16 + 8) * 256);
+      vf[a2][db] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
   };
   // ---- the operands of the first four segments, and this row's mask word of the block
   const bool full_tile = (flags_next & 1) != 0;
   unsigned bits_next = 0xFFFFFFFFu;
-  if (!full_tile) bits_next = *reinterpret_cast<const unsigned *>(lds + kBitsRing + PH * 1024 + bits_addr);
+  if (kChain && !full_tile) bits_next = *reinterpret_cast<const unsigned *>(lds + kBitsRing + PH * 1024 + bits_addr);
 #pragma unroll
   for (int x = 0; x < 4; ++x) fetch(x);
   __builtin_amdgcn_sched_barrier(0);
-  if (full_tile) {
-    seen_full = 1;
-  } else {
-    if (flags_next & 2) bits_next = 0u;  // dummy block: nothing kept
-    seen |= bits_next;
+  if (kChain) {
+    if (full_tile) {
+      seen_full = 1;
+    } else {
+      if (flags_next & 2) bits_next = 0u;  // dummy block: nothing kept
+      seen |= bits_next;
+    }
   }
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -393,32 +403,36 @@ __device__ __forceinline__ void pipe_iter_seg(const unsigned char *__restrict__ 
   for (int x = 0; x < 8; ++x) {
     const int a2 = x >> 2, db = x & 3;
     // P_{b-1} V_{b-1}, step x (first: it needs no mask)
-    const u32x4 praw = {pPrev[4 * a2], pPrev[4 * a2 + 1], pPrev[4 * a2 + 2], pPrev[4 * a2 + 3]};
-    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[a2][db]),
-                                                       __builtin_bit_cast(bf16x8, praw), oacc[db], 0, 0, 0);
+    if (kPV) {
+      const u32x4 praw = {pPrev[4 * a2], pPrev[4 * a2 + 1], pPrev[4 * a2 + 2], pPrev[4 * a2 + 3]};
+      oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[a2][db]),
+                                                         __builtin_bit_cast(bf16x8, praw), oacc[db], 0, 0, 0);
+    }
     // S_{b+1} chain, step x. Accumulator e is key 8 (e / 4) + 4 hf + e % 4 of the block and starts at 0 (kept)
     // or -inf (masked); a block whose 32 x 32 entries of this wave are all kept starts from a literal zero
-    if (x == 0) {
-      if (__builtin_amdgcn_ballot_w64(bits_next != 0xFFFFFFFFu) == 0) {
-        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], zero, 0, 0, 0);
+    if (kChain) {
+      if (x == 0) {
+        if (__builtin_amdgcn_ballot_w64(bits_next != 0xFFFFFFFFu) == 0) {
+          sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], zero, 0, 0, 0);
+        } else {
+          const int inv = (int)~(bits_next >> (4 * hf));
+          mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
+          sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], sB, 0, 0, 0);
+        }
       } else {
-        const int inv = (int)~(bits_next >> (4 * hf));
-        mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
-        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], sB, 0, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], sB, 0, 0, 0);
       }
-    } else {
-      sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], sB, 0, 0, 0);
     }
     if (x < 4) fetch(x + 4);
     // the weights of two entries of block b and their part of the row sum
-    {
+    if (kWeights) {
       const float p0 = __builtin_amdgcn_exp2f(sA[2 * x] * c2);
       const float p1 = __builtin_amdgcn_exp2f(sA[2 * x + 1] * c2);
       pCur[x] = pack_bf16(p0, p1);
       l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pCur[x]), ones, l_run, false);
       asm volatile("" ::"v"(pCur[x]));
     }
-    bk(std::integral_constant<int, 0>{} , x);
+    if (kChain) bk(std::integral_constant<int, 0>{} , x);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -669,10 +683,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int e = 0; e < 8; ++e) pbuf[1][e] = 0u;
         d[3].flags = 0;  // stands for block -1: the leading dummy must not end the loop
         // iteration b with (b + 1) % 4 == PH; returns true when the stream is finished
-        auto step = [&](auto ph) {
-          constexpr int PH = decltype(ph)::value;
+        auto step = [&](auto ph, auto partc) {
+          constexpr int PH = decltype(ph)::value, PART = decltype(partc)::value;
           const int flag_cur = d[(PH + 3) & 3].flags;  // block b, whose descriptor is replaced now
           if constexpr (FAST) {
+
             // the bookkeeping of this iteration, dealt out over the segments of the product stream: the copies
             // only behind the last operand reads (segments 0 .. 3 issue those of segments 4 .. 7)
             auto bk = [&](auto, int x) {
@@ -682,8 +697,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
               if (x == 6) copy_v(d[(PH + 1) & 3], std::integral_constant<int, (PH + 1) & 3>{});  // block b+2
               if (x == 7) pre_raw = list_read(++cursor);               // block b+5 (a read past the list returns its dummy)
             };
-            pipe_iter_seg<PH>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], l_run, seen,
-                              seen_full, d[PH].flags, bits_addr, c2, kbase, vbase, hf, bk);
+            pipe_iter_seg<PH, PART>(lds, qf, oacc, sbuf[PH & 1], sbuf[(PH + 1) & 1], pbuf[(PH + 1) & 1], pbuf[PH & 1], l_run,
+                                    seen, seen_full, d[PH].flags, bits_addr, c2, kbase, vbase, hf, bk);
             if (flag_cur & 2) return true;      // block b was the trailing dummy: P_{b-1} V_{b-1} is in
           } else {
             d[(PH + 3) & 3] = decode(pre_raw);           // block b+4
@@ -702,11 +717,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           asm volatile("s_waitcnt vmcnt(10)\n\ts_barrier" ::: "memory");
           return false;
         };
-        while (true) {
-          if (step(I0{})) break;
-          if (step(I1{})) break;
-          if (step(I2{})) break;
-          if (step(I3{})) break;
+        using PAll = std::integral_constant<int, kAll>;
+        // block -1 (nothing to weigh, nothing to add) and block 0 (nothing to add yet) in front of the loop,
+        // which therefore starts at phase 2
+        if (!step(I0{}, std::integral_constant<int, FAST ? kChainOnly : kAll>{}) &&
+            !step(I1{}, std::integral_constant<int, FAST ? kNoPV : kAll>{})) {
+          while (true) {
+            if (step(I2{}, PAll{})) break;
+            if (step(I3{}, PAll{})) break;
+            if (step(I0{}, PAll{})) break;
+            if (step(I1{}, PAll{})) break;
+          }
         }
       }
     }
