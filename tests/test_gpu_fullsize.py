@@ -216,9 +216,10 @@ def test_c4_full_size():
 
 
 def test_c5_full_size_lists_and_decode():
-    """Four consecutive positions of the 64k decode workload: the kept lists built on the GPU equal
-    the oracle's rows of the mask, and the decode outputs of every (sequence, head) match."""
-    w = wl.scaled(wl.WORKLOADS["c5"], steps=4)
+    """Every position of the 64k decode workload (256 consecutive ones): the kept lists built on the GPU equal
+    the oracle's rows of the mask, and the decode outputs of every (sequence, head) match, from the lists
+    per head, from the merged lists and from the position-independent plan."""
+    w = wl.WORKLOADS["c5"]   # all of its 256 steps
     cap = w.seq + w.steps
     dflag, vflag = wl.patterns_c5(w)
     art = oracle.from_patterns(dflag, vflag)
@@ -230,6 +231,16 @@ def test_c5_full_size_lists_and_decode():
     G = w.hq // w.hkv
     kv_of = np.array([b * w.hkv + h // G for b in range(w.batch) for h in range(w.hq)], np.int32)
     d_in, v_in = torch.from_numpy(dflag).cuda(), torch.from_numpy(vflag).cuda()
+    # the position-independent plan, built once (the form the bench times as a whole decode step)
+    plan = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False, group=G,
+                        plan=True)
+    torch.cuda.synchronize()
+    want_plan = oracle.pattern_plan(dflag, vflag, G, S=cap)
+    assert np.array_equal(plan.kept_ptr.cpu().numpy().astype(np.int64), want_plan[0])
+    assert np.array_equal(plan.kept_idx.cpu().numpy(), want_plan[1]) and np.array_equal(plan.kept_member.cpu().numpy(), want_plan[2])
+    assert np.array_equal(plan.plan_table.cpu().numpy(), want_plan[3])
+    plan_longest = int(np.diff(want_plan[0]).max())
+    worst = 0.0
     for step in range(w.steps):
         p = w.seq - 1 + step
         mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=w.hq, L=0, S=cap, diag_in=d_in, vert_in=v_in, blocks=False,
@@ -267,4 +278,11 @@ def test_c5_full_size_lists_and_decode():
         err_g = np.abs(out_g.float().cpu().numpy().reshape(w.batch * w.hq, w.head_dim) - O).max()
         assert err_g <= TOL_BF16, f"position {p}, grouped: max abs err {err_g}"
         assert np.abs(lse_g.cpu().numpy().reshape(-1) - LSE).max() <= TOL_BF16
-        say(f"c5: position {p}: {int(lens.sum())} kept keys per sequence, max abs err {err:.2e} (grouped {err_g:.2e})")
+        out_p, lse_p = B.dam_sparse_attn_decode_patterns(qs[step].cuda(), kc_d, vc_d, plan, p, plan_longest, want_lse=True)
+        torch.cuda.synchronize()
+        err_p = np.abs(out_p.float().cpu().numpy().reshape(w.batch * w.hq, w.head_dim) - O).max()
+        assert err_p <= TOL_BF16, f"position {p}, from the plan: max abs err {err_p}"
+        assert np.abs(lse_p.cpu().numpy().reshape(-1) - LSE).max() <= TOL_BF16
+        worst = max(worst, err, err_g, err_p)
+        if step % 32 == 31:
+            say(f"c5: up to position {p}: {int(lens.sum())} kept keys per sequence, max abs err so far {worst:.2e}")
