@@ -278,7 +278,8 @@ size_t dam_capture_workspace(const dam_capture_params *params);
  * attn_sum  device f32 [hq][pcl][pcl], read and written (the caller zeroes it before the first
  *           capture). attn_cnt the same for the counts, or NULL.
  * ws        device workspace of at least dam_capture_workspace(params) bytes.
- * pcl up to 8192. Errors as for the other entry points. */
+ * pcl up to 8192 and a position stride of k below 2^24 elements (DAM_ERR_UNSUPPORTED beyond). Errors as for
+ * the other entry points. */
 int dam_capture_accumulate(const dam_capture_params *params, const void *q, const void *k,
                            float *attn_sum, float *attn_cnt, void *ws, size_t ws_bytes, void *stream);
 

@@ -186,6 +186,7 @@ def test_capture_argument_errors():
     assert call(capture_params(dtype=3)) == B.DAM_ERR_UNSUPPORTED
     assert call(capture_params(len=64, pcl=16384)) == B.DAM_ERR_UNSUPPORTED
     assert call(capture_params(q_stride=(ctypes.c_int64 * 2)(64 * 128, 132))) == B.DAM_ERR_INVALID_ARG
+    assert call(capture_params(k_stride=(ctypes.c_int64 * 2)(64 << 24, 1 << 24))) == B.DAM_ERR_UNSUPPORTED  # 32-bit row offsets
     assert call(capture_params(), ws_bytes=8) == B.DAM_ERR_WORKSPACE
     assert L.dam_capture_workspace(ctypes.byref(capture_params())) >= 2 * 64 * 4
 
