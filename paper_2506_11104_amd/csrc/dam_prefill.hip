@@ -399,6 +399,9 @@ __device__ __forceinline__ void pipe_iter_seg(const unsigned char *__restrict__ 
   }
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // no entry of this wave's 32 x 32 square is kept (wave-uniform): every logit is -inf without any product. (The
+  // weights of such a square and its products with V stay: branches around them cost more than they save.)
+  const bool skip_s = __builtin_amdgcn_ballot_w64(bits_next != 0u) == 0;
 #pragma unroll
   for (int x = 0; x < 8; ++x) {
     const int a2 = x >> 2, db = x & 3;
@@ -414,12 +417,15 @@ __device__ __forceinline__ void pipe_iter_seg(const unsigned char *__restrict__ 
       if (x == 0) {
         if (__builtin_amdgcn_ballot_w64(bits_next != 0xFFFFFFFFu) == 0) {
           sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], zero, 0, 0, 0);
+        } else if (skip_s) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sB[e] = -INFINITY;
         } else {
           const int inv = (int)~(bits_next >> (4 * hf));
           mask_init(sB, inv, std::make_integer_sequence<int, 16>{});
           sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], sB, 0, 0, 0);
         }
-      } else {
+      } else if (!skip_s) {
         sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], sB, 0, 0, 0);
       }
     }
