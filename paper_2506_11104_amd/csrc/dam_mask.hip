@@ -24,6 +24,7 @@ using namespace dam;
 // Workgroups of a launch whose items are short: enough to fill the chip twice (256 CUs x 8 workgroups of
 // 256 threads); each takes several items in turn.
 constexpr int kGridTarget = 4096;
+constexpr int kHeadSub = 16;  // partial sums per head of the listed-tile counts
 
 struct Geom {
   int H, L, S, P;            // P: length of the pattern flag arrays (L from a map, S when given)
@@ -1008,8 +1009,10 @@ __global__ __launch_bounds__(1024) void k_pattern_prep(Geom g, const uint8_t *__
                                                        uint64_t *__restrict__ rrev, bool classes,
                                                        uint64_t *__restrict__ col_any, uint64_t *__restrict__ col_all,
                                                        uint64_t *__restrict__ off_any, uint64_t *__restrict__ off_all,
-                                                       int gstride, int *__restrict__ gidx, int *__restrict__ gcnt) {
+                                                       int gstride, int *__restrict__ gidx, int *__restrict__ gcnt,
+                                                       int *__restrict__ head_cnt) {
   const int h = blockIdx.x;
+  if (threadIdx.x < kHeadSub) head_cnt[h * kHeadSub + threadIdx.x] = 0;  // the head's number of listed tiles: summed by k_tile_scan
   pattern_bitsets_of_head(diag_flag, vert_flag, g.P, g.pw, h, cbits, rrev);
   if (!classes) return;  // uniform over the grid
   __syncthreads();       // the sets are read back from memory by other threads of this workgroup
@@ -1056,7 +1059,7 @@ __device__ __forceinline__ void slot_rows(const Geom &g, const uint64_t *__restr
 // strictly below the diagonal and outside the true-mask block are decided by their lane alone (from
 // the class bitsets, or by pattern_tile_flags); only the tiles on the diagonal or inside the
 // true-mask block are then evaluated word by word by the whole wave. No LDS, no barrier.
-__device__ __forceinline__ void tile_scan_row(const Geom &g, const uint64_t *__restrict__ tb, const uint64_t *__restrict__ cb,
+__device__ __forceinline__ int tile_scan_row(const Geom &g, const uint64_t *__restrict__ tb, const uint64_t *__restrict__ cb,
                                               const uint64_t *__restrict__ rr, const uint64_t *__restrict__ col_any,
                                               const uint64_t *__restrict__ col_all, const uint64_t *__restrict__ off_any,
                                               const uint64_t *__restrict__ off_all, uint64_t *__restrict__ occ,
@@ -1153,6 +1156,7 @@ __device__ __forceinline__ void tile_scan_row(const Geom &g, const uint64_t *__r
     }
   }
   if (lane == 0) cnt[(int64_t)h * g.nQt + qt] = total;
+  return total;
 }
 
 // Exclusive scan of n counts by one block. group > 0: the result is laid out as [n / group]
@@ -1236,9 +1240,11 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int *__restrict__
   block_exclusive_scan<1024>(cnt, n, group, ptr, total, clamp);
 }
 
-// Pass 1 as a kernel: a wave per query tile. (The CSR offsets stay a launch of their own: folding the scan into
-// the last workgroup to finish needs a device-wide release fence in every workgroup, which on this chip writes
-// back the L2 of its XCD each time: 20 -> 190 us at S = 32768.)
+// Pass 1 as a kernel: a wave per query tile; the workgroup adds its four counts to the head's total. The CSR offsets
+// need no launch of their own: every wave of the fill kernel adds up the totals of the heads before its own and the
+// counts of the query tiles before its own. (Folding a scan into the last workgroup to finish was measured and
+// dropped: it needs a device-wide release fence in every workgroup, which on this chip writes back the L2 of its
+// XCD each time: 20 -> 190 us at S = 32768.)
 __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__restrict__ true_bits,
                                                    const uint64_t *__restrict__ cbits,
                                                    const uint64_t *__restrict__ rrev,
@@ -1250,15 +1256,23 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
                                                    uint64_t *__restrict__ full, int *__restrict__ cnt, bool staged,
                                                    const int *__restrict__ gidx, const int *__restrict__ gcnt,
                                                    int gstride, uint64_t *__restrict__ vocc,
-                                                   uint64_t *__restrict__ vfull) {
+                                                   uint64_t *__restrict__ vfull, int *__restrict__ head_cnt) {
   extern __shared__ uint64_t lds_sets[];
+  __shared__ int wave_cnt[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = blockIdx.y, qt = blockIdx.x * 4 + wave;
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
   stage_sets(lds_sets, staged, g.pw, cb, rr);
-  if (qt < g.nQt) tile_scan_row(g, tb, cb, rr, col_any, col_all, off_any, off_all, occ, full, cnt, gidx, gcnt, gstride, vocc, vfull, h, qt, lane);
+  int mine = 0;
+  if (qt < g.nQt) mine = tile_scan_row(g, tb, cb, rr, col_any, col_all, off_any, off_all, occ, full, cnt, gidx, gcnt, gstride, vocc, vfull, h, qt, lane);
+  // the head's total, for the offsets that the fill kernel derives itself (plain atomics, read by the next kernel
+  // only; spread over kHeadSub words per head, because atomics on one address are served one after the other)
+  if (lane == 0) wave_cnt[wave] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    atomicAdd(head_cnt + h * kHeadSub + (blockIdx.x & (kHeadSub - 1)), wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3]);
 }
 
 // Pass 2: write column, kind and the tile's element bits for every listed tile (below capacity). A wave per
@@ -1271,7 +1285,8 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
                                                    const uint64_t *__restrict__ rrev,
                                                    const uint64_t *__restrict__ occ,
                                                    const uint64_t *__restrict__ full,
-                                                   const int *__restrict__ row_ptr,
+                                                   const int *__restrict__ tile_cnt, const int *__restrict__ head_cnt,
+                                                   int *__restrict__ row_ptr, int64_t *__restrict__ blk_total,
                                                    int *__restrict__ blk_col,
                                                    uint8_t *__restrict__ blk_kind,
                                                    uint64_t *__restrict__ tile_bits, int64_t capacity,
@@ -1292,10 +1307,26 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const uint64_t *fl = full + ((int64_t)h * g.nQt + qt) * g.occw;
   // the walk below is a chain of dependent steps: its index words are fetched one word of 64 tiles ahead,
   // the first ones before the sets are staged, so that no step of the chain waits for memory alone
-  const int64_t first = row_ptr[(int64_t)h * (g.nQt + 1) + qt];
+  // where this query tile's entries start: the listed tiles of the heads before h and of the query tiles before
+  // qt (no scan kernel between the two passes: the counts are few enough for every wave to add up its own prefix)
+  int64_t part = 0;
+  for (int x = lane; x < h * kHeadSub; x += 64) part += head_cnt[x];
+  const int *cnt_h = tile_cnt + (int64_t)h * g.nQt;
+  for (int x = lane; x < qt; x += 64) part += cnt_h[x];
+  const int my_cnt = cnt_h[qt];
   uint64_t ow_next = oc[0], fw_next = fl[0];
   stage_sets(lds_sets, staged, g.pw, cb, rr);
   if (!live) return;
+  for (int off = 32; off; off >>= 1) part += __shfl_xor(part, off);
+  const int64_t first = part;
+  if (lane == 0 && my_turn == 0) {  // the CSR offsets, cut to the capacity like everything they point into
+    int *rp = row_ptr + (int64_t)h * (g.nQt + 1);
+    rp[qt] = (int)min(first, capacity);
+    if (qt == g.nQt - 1) {
+      rp[g.nQt] = (int)min(first + my_cnt, capacity);
+      if (h == (int)gridDim.y - 1 && blk_total) *blk_total = first + my_cnt;
+    }
+  }
   const int i_last = min(g.S - 1, qt * g.tile_m + g.tile_m - 1);
   const int kmax = i_last / g.tile_n;
   const int words = g.tile_m * g.wpr;
@@ -1801,7 +1832,7 @@ struct Workspace {
   uint64_t *vslices, *dslices;
   uint8_t *diag_flag, *vert_flag;
   uint64_t *cbits, *rrev, *occ, *full, *col_any, *col_all, *off_any, *off_all, *vocc, *vfull;
-  int *tile_cnt, *row_cnt, *group_first;
+  int *tile_cnt, *head_cnt, *row_cnt, *group_first;
   size_t bytes;
 };
 
@@ -1859,6 +1890,7 @@ Workspace carve(const dam_mask_params *p, void *ws) {
   w.vocc = c.take<uint64_t>(gather ? (size_t)g.H * g.nQt * g.occw : 1);
   w.vfull = c.take<uint64_t>(gather ? (size_t)g.H * g.nQt * g.occw : 1);
   w.tile_cnt = c.take<int>((size_t)g.H * g.nQt);
+  w.head_cnt = c.take<int>((size_t)g.H * kHeadSub);
   const int nrows = p->row_end > p->row_begin ? p->row_end - p->row_begin : 0;
   size_t n_cnt = (size_t)g.H * (size_t)(nrows > 0 ? nrows : 1);
   size_t n_first = 1;
@@ -1962,7 +1994,8 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
   const int *gidx = gather ? o->gather_idx : nullptr, *gcnt = gather ? o->gather_cnt : nullptr;
   if (want_blocks || want_lists || o->dense_bits) {
     k_pattern_prep<<<g.H, 1024, 0, stream>>>(g, dflag, vflag, w.cbits, w.rrev, want_blocks, w.col_any, w.col_all, w.off_any,
-                                            w.off_all, gstride, gather ? o->gather_idx : nullptr, gather ? o->gather_cnt : nullptr);
+                                            w.off_all, gstride, gather ? o->gather_idx : nullptr, gather ? o->gather_cnt : nullptr,
+                                            w.head_cnt);
   }
   // a4 + a5: tile occupancy, CSR offsets, tile bits
   if (want_blocks) {
@@ -1970,14 +2003,16 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
     const bool fill = o->blk_col || o->blk_kind || o->tile_bits;
     k_tile_scan<<<dim3((g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(g, true_bits, w.cbits, w.rrev, w.col_any, w.col_all, w.off_any,
                                                                      w.off_all, w.occ, w.full, w.tile_cnt, lds_sets > 0, gidx,
-                                                                     gcnt, gstride, w.vocc, w.vfull);
-    k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total,
-                                             fill ? o->blk_capacity : INT64_MAX);
+                                                                     gcnt, gstride, w.vocc, w.vfull, w.head_cnt);
     if (fill) {
+      // (the CSR offsets come out of the fill kernel: no scan launch between the two passes)
       const int share = (int64_t)g.H * g.nQt >= 2048 ? 1 : 4;  // enough query tiles to give every wave its own
       k_tile_fill<<<dim3(share == 4 ? g.nQt : (g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(
-          g, true_bits, w.cbits, w.rrev, w.occ, w.full, o->blk_row_ptr, o->blk_col, o->blk_kind, o->tile_bits, o->blk_capacity,
+          g, true_bits, w.cbits, w.rrev, w.occ, w.full, w.tile_cnt, w.head_cnt, o->blk_row_ptr, o->blk_total, o->blk_col,
+          o->blk_kind, o->tile_bits, o->blk_capacity,
           (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0, gidx, gcnt, gstride, w.vocc, w.vfull, share);
+    } else {  // the sizing call: offsets and total only
+      k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total, INT64_MAX);
     }
   }
   if (o->dense_bits) {
