@@ -1343,23 +1343,33 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       ow_next = oc[ow_i + 1];
       fw_next = fl[ow_i + 1];
     }
+    const uint64_t listed = ow;
+    if (skip_full_bits) {
+      // full tiles get a column and a kind only: all of the word's at once, lane j takes tile 64 ow_i + j
+      const uint64_t below = (1ull << lane) - 1;
+      const int r = rank + __popcll(listed & below);
+      if (((listed & fw) >> lane) & 1) {
+        const int64_t t = first + r;
+        if (r % share == my_turn && t < capacity) {
+          if (blk_col) blk_col[t] = ow_i * 64 + lane;
+          if (blk_kind) blk_kind[t] = (uint8_t)31;
+        }
+      }
+      ow &= ~fw;
+    }
+    const int rank0 = rank;
+    rank += __popcll(listed);
     while (ow) {
-      const int kt = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
+      const int bit = __ffsll((unsigned long long)ow) - 1;
+      const int kt = ow_i * 64 + bit;
       ow &= ow - 1;
-      const int64_t t = first + rank;
-      const bool mine = rank % share == my_turn;
-      ++rank;
+      const int rk = rank0 + __popcll(listed & ((1ull << bit) - 1));
+      const int64_t t = first + rk;
+      const bool mine = rk % share == my_turn;
       if (!mine || t >= capacity) continue;
       // element words, and which key quarters of the tile hold a kept entry
       const bool is_full = (fw >> (kt & 63)) & 1;
       int quarters = 0;
-      if (is_full && skip_full_bits) {  // wave-uniform: column and kind only
-        if (lane == 0) {
-          if (blk_col) blk_col[t] = kt;
-          if (blk_kind) blk_kind[t] = (uint8_t)31;
-        }
-        continue;
-      }
       if (words == 256 && g.wpr == 2 && qt * 128 >= g.L && qt * 128 + 128 <= g.S) {
         // 128 x 128 tile with every row in the pattern region: a lane takes rows lane and lane + 64 whole
         // (128 keys = two words). The offsets i - j of a row's 128 keys are 128 consecutive positions of
