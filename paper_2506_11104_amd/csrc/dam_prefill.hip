@@ -466,6 +466,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, hf = lane >> 5;
   const float c2 = a.scale * 1.4426950408889634f;
+  if (!FAST && ctl[kRedoCount] == 0) return;  // nothing to redo (the usual case): leave before any set-up
   if (FAST && tid == 0) s_bad = 0;
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds;
 
