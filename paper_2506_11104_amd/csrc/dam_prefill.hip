@@ -90,6 +90,8 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
                                                      const int *__restrict__ gather_idx,
                                                      float *__restrict__ out, float *__restrict__ lse) {
   constexpr int N = 4, LPR = D / N, GROUPS = 256 / LPR;
+  // a workgroup takes GROUPS rows of a query tile at a time; blockIdx.y spreads a tile's passes over workgroups
+  // (a row's keys are folded in one after the other: the more rows in flight, the better)
   const WorkItem w = decode_work(a, blockIdx.x);
   if (!w.valid) return;
   const int group = threadIdx.x / LPR, sub = threadIdx.x % LPR;
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
   const int t1 = row_ptr[(int64_t)w.hq * (a.nQt + 1) + w.qt + 1];
   const float *kb = k + w.b * a.k_sb + w.hkv * a.k_sh + sub * N;
   const float *vb = v + w.b * a.v_sb + w.hkv * a.v_sh + sub * N;
-  for (int rl = group; rl < a.tile_m; rl += GROUPS) {
+  for (int rl = blockIdx.y * GROUPS + group; rl < a.tile_m; rl += GROUPS * gridDim.y) {
     const int i = w.qt * a.tile_m + rl;
     if (i >= a.S) break;
     const float4 qv = *reinterpret_cast<const float4 *>(q + w.b * a.q_sb + w.hq * a.q_sh + i * a.q_ss + sub * N);
@@ -113,23 +115,36 @@ __global__ __launch_bounds__(256) void k_prefill_f32(AttnArgs a, const float *__
       for (int wd = 0; wd < a.wpr; ++wd) {
         uint64_t bits = full ? ~0ull : tile_bits[((int64_t)t * a.tile_m + rl) * a.wpr + wd];
         while (bits) {
-          const int slot = wd * 64 + __ffsll((unsigned long long)bits) - 1;
-          const int j = min(max(gcols ? gcols[slot] : j0 + slot, 0), a.S - 1);
-          bits &= bits - 1;
-          const float4 kv = *reinterpret_cast<const float4 *>(kb + j * a.k_ss);
-          const float4 vv = *reinterpret_cast<const float4 *>(vb + j * a.v_ss);
-          float d = qv.x * kv.x + qv.y * kv.y + qv.z * kv.z + qv.w * kv.w;
+          // the rows of up to four kept keys are fetched together (their addresses depend on the bits, so nothing
+          // else hides the latency), then folded into the running softmax one after the other, in key order
+          constexpr int U = 4;
+          float4 kv[U], vv[U];
+          bool have[U];
 #pragma unroll
-          for (int off = LPR / 2; off; off >>= 1) d += __shfl_xor(d, off);
-          const float s = d * a.scale;
-          const float mn = fmaxf(m, s);
-          const float corr = expf(m - mn), p = expf(s - mn);
-          l = l * corr + p;
-          o.x = o.x * corr + p * vv.x;
-          o.y = o.y * corr + p * vv.y;
-          o.z = o.z * corr + p * vv.z;
-          o.w = o.w * corr + p * vv.w;
-          m = mn;
+          for (int u = 0; u < U; ++u) {
+            have[u] = bits != 0;
+            const int slot = wd * 64 + (have[u] ? __ffsll((unsigned long long)bits) - 1 : 0);
+            const int j = min(max(gcols ? gcols[slot] : j0 + slot, 0), a.S - 1);
+            bits &= bits - 1;  // (0 stays 0)
+            kv[u] = *reinterpret_cast<const float4 *>(kb + j * a.k_ss);
+            vv[u] = *reinterpret_cast<const float4 *>(vb + j * a.v_ss);
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            if (!have[u]) break;  // uniform over the lanes of a row
+            float d = qv.x * kv[u].x + qv.y * kv[u].y + qv.z * kv[u].z + qv.w * kv[u].w;
+#pragma unroll
+            for (int off = LPR / 2; off; off >>= 1) d += __shfl_xor(d, off);
+            const float s = d * a.scale;
+            const float mn = fmaxf(m, s);
+            const float corr = expf(m - mn), p = expf(s - mn);
+            l = l * corr + p;
+            o.x = o.x * corr + p * vv[u].x;
+            o.y = o.y * corr + p * vv[u].y;
+            o.z = o.z * corr + p * vv[u].z;
+            o.w = o.w * corr + p * vv[u].w;
+            m = mn;
+          }
         }
       }
     }
@@ -897,11 +912,14 @@ extern "C" int dam_sparse_attn_prefill(const dam_attn_params *p, const void *q, 
   }
   const int blocks = work_blocks(a);
   if (p->dtype == DAM_F32) {
+    // (passes of a query tile as separate workgroups while the launch stays small)
+    const int rows_per_pass = 256 / (p->head_dim / 4), passes = (p->tile_m + rows_per_pass - 1) / rows_per_pass;
+    const int spread = blocks * passes <= 16384 ? passes : 1;
     if (p->head_dim == 64)
-      k_prefill_f32<64><<<blocks, 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
+      k_prefill_f32<64><<<dim3(blocks, spread), 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
                                                mk->blk_col, mk->blk_kind, mk->tile_bits, mk->gather_idx, (float *)out, lse);
     else
-      k_prefill_f32<128><<<blocks, 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
+      k_prefill_f32<128><<<dim3(blocks, spread), 256, 0, st>>>(a, (const float *)q, (const float *)k, (const float *)v, mk->blk_row_ptr,
                                                 mk->blk_col, mk->blk_kind, mk->tile_bits, mk->gather_idx, (float *)out, lse);
     return launch_status();
   }
