@@ -605,6 +605,7 @@ def bench_mask_from_map(args, torch, B, wl, name):
         p2 = B.MaskParams(B.DAM_FROM_ATTN_MAP, H, L, S, 128, 128, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"))
         ws2 = B.mask_workspace(p2, "cuda")
         o2 = B.MaskOut()
+        tb_map = tb
         o2.true_bits, o2.diag_flag, o2.vert_flag = tb.data_ptr(), fl[0].data_ptr(), fl[1].data_ptr()
         tot = torch.zeros(1, dtype=torch.int64, device="cuda")
         o2.blk_row_ptr, o2.blk_col, o2.blk_kind = sized.blk_row_ptr.data_ptr(), sized.blk_col.data_ptr(), sized.blk_kind.data_ptr()
@@ -628,6 +629,18 @@ def bench_mask_from_map(args, torch, B, wl, name):
                 torch.cuda.synchronize()
             wsf = B.prefill_workspace(B.attn_params(qf, kf, vf, outf, 128, 128, gather_rows=mk.gather_rows), "cuda")
             ms_p = timed(lambda: B.dam_sparse_attn_prefill(qf, kf, vf, mk, out=outf, ws=wsf), 5)
+            ms_b = None
+            if label == "gathered":   # the build of the layout this prefill reads (full tiles without bits, columns gathered)
+                fl_g = B.DAM_MASK_SKIP_FULL_TILE_BITS | B.DAM_MASK_GATHER_COLUMNS
+                p3 = B.MaskParams(B.DAM_FROM_ATTN_MAP, H, L, S, 128, 128, 0, 0, w.lam, w.eps, w.tau, w.mu, float("nan"), fl_g)
+                ws3 = B.mask_workspace(p3, "cuda")
+                o3 = B.MaskOut()
+                o3.true_bits, o3.diag_flag, o3.vert_flag = tb_map.data_ptr(), fl[0].data_ptr(), fl[1].data_ptr()
+                o3.blk_row_ptr, o3.blk_col, o3.blk_kind = mk.blk_row_ptr.data_ptr(), mk.blk_col.data_ptr(), mk.blk_kind.data_ptr()
+                o3.tile_bits, o3.blk_capacity, o3.blk_total = mk.tile_bits.data_ptr(), mk.n_tiles, tot.data_ptr()
+                o3.gather_idx, o3.gather_cnt = mk.gather_idx.data_ptr(), mk.gather_cnt.data_ptr()
+                ms_b = timed(lambda: B.dam_mask_build(p3, A, None, None, None, o3, ws3), 10)
+                del ws3
             kd = mk.blk_kind.cpu().numpy()
             part = (mk.blk_kind & 1) == 0
             nnz = int((kd & 1).sum()) * 128 * 128
@@ -637,6 +650,10 @@ def bench_mask_from_map(args, torch, B, wl, name):
             pre[label] = {"listed_tiles": mk.n_tiles, "key_blocks_of_32": int(np.unpackbits((kd >> 1)[:, None].astype(np.uint8), axis=1).sum()),
                           "prefill_ms": ms_p, "nnz": nnz, "tflops_kept_entries": 4.0 * w.head_dim * nnz / (ms_p * 1e-3) / 1e12,
                           "frac_of_bf16_peak": 4.0 * w.head_dim * nnz / (ms_p * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+            if ms_b is not None:
+                pre[label]["mask_build_ms"] = ms_b
+                pre[label]["step_ms"] = ms_b + ms_p
+                pre[label]["tflops_kept_entries_step"] = 4.0 * w.head_dim * nnz / ((ms_b + ms_p) * 1e-3) / 1e12
             del wsf
         res["prefill_128k"] = pre
     return res
