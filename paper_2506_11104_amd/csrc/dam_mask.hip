@@ -1130,9 +1130,40 @@ __device__ __forceinline__ int tile_scan_row(const Geom &g, const uint64_t *__re
     const int n_gt = split ? (gcnt[h] + g.tile_n - 1) / g.tile_n : 0;
     const int *gi = gidx + (int64_t)h * gstride;
     const int row_words = g.tile_m / 64;
+    // No matched diagonal lies beyond r_bound: the largest tile distance with a matched offset (the first set bit
+    // of the reversed class words) covers offsets up to T d + T - 1. (Square tiles only: the classes are theirs.)
+    int64_t r_bound = INT64_MAX;
+    if (n_gt >= 4 && g.tile_m == g.tile_n) {  // (with a handful of gathered tiles the look-up costs more than it saves)
+      int64_t first = -1;
+      for (int w0 = 0; w0 < g.occw && first < 0; w0 += 64) {
+        const uint64_t word = w0 + lane < g.occw ? da[w0 + lane] : 0;
+        const uint64_t nz = __ballot(word != 0);
+        if (nz) {
+          const int wl = __ffsll((unsigned long long)nz) - 1;
+          const uint64_t hit = __shfl(word, wl);
+          first = (int64_t)(w0 + wl) * 64 + __ffsll((unsigned long long)hit) - 1;
+        }
+      }
+      const int64_t dmax = first < 0 ? 0 : (int64_t)g.occw * 64 - 1 - first;
+      r_bound = dmax * g.tile_n + g.tile_n - 1;
+    }
+    const int n_cols = split ? gcnt[h] : 0;
     for (int w = 0; w < g.occw; ++w) {
-      uint64_t ow = 0, fw = 0;
+      // A complete gathered tile whose columns all lie further above this query tile than any matched diagonal
+      // reaches is full without looking: every row is causal for every slot and no offset i - c is a matched
+      // one. One lane per tile; the other tiles are evaluated slot by slot.
+      bool certain = false;
+      if (w * 64 < n_gt && r_bound != INT64_MAX) {  // wave-uniform
+        const int v = w * 64 + lane;
+        if (v < n_gt && (v + 1) * g.tile_n <= n_cols && i0 + g.tile_m <= g.S) {
+          const int cmax = gi[v * g.tile_n + g.tile_n - 1];  // the columns of a tile ascend
+          certain = cmax >= 0 && (int64_t)i0 - cmax > r_bound;
+        }
+      }
+      const uint64_t sure = __ballot(certain);
+      uint64_t ow = sure, fw = sure;
       for (int v = w * 64; v < min(n_gt, w * 64 + 64); ++v) {
+        if ((sure >> (v & 63)) & 1) continue;  // wave-uniform
         bool any = false, all = true;
         for (int wg = 0; wg < g.wpr; ++wg) {
           const int c = gi[v * g.tile_n + wg * 64 + lane];
@@ -1470,6 +1501,13 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       ++rank;
       if (!mine || t >= capacity) continue;
       const bool is_full = (vfw >> (v & 63)) & 1;
+      if (is_full && skip_full_bits) {  // wave-uniform: column and kind only (every quarter of a full tile is occupied)
+        if (lane == 0) {
+          if (blk_col) blk_col[t] = g.nKt + v;
+          if (blk_kind) blk_kind[t] = (uint8_t)31;
+        }
+        continue;
+      }
       int kind = 0;
       for (int u = 0; u < units; ++u) {
         const int wg = u % g.wpr, k = u / g.wpr;
