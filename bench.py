@@ -697,8 +697,10 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "k_prefill_bf16_pipe", "achieved": res["tflops_kept_prefill"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": res["tflops_kept_prefill"] / PEAK_BF16_TFLOPS,
                      "traffic": None,
-                     # the matrix work the kernel issues: 4 * head_dim * 128 * 32 per occupied 32-key block of a listed
-                     # tile (empty key quarters of a tile are skipped): the figure "on kept tiles"
+                     # the matrix work of the occupied 32-key blocks of the listed tiles, 4 * head_dim * 128 * 32 each
+                     # (empty key quarters of a tile are not visited): the figure "on kept tiles". The kernel issues a
+                     # few per cent fewer matrix instructions than that: a wave whose 32 x 32 square of a block holds
+                     # no kept entry does not run that square's Q K^T products
                      "achieved_issued_blocks": res["tflops_blocks_prefill"],
                      "frac_issued_blocks": res["tflops_blocks_prefill"] / PEAK_BF16_TFLOPS,
                      "plain_layout": res["plain_layout"]},
