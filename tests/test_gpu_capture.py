@@ -139,3 +139,22 @@ def test_fused_build_ragged_capture_length():
     w = wl.scaled(wl.WORKLOADS["c2"], hq=4, hkv=2, seq=500, pcl=200)
     Q, K, _ = wl.qkv_structured(w)
     fused_against_oracle(Q, K, w, w.seq, 128, 128, 0.05, 0.8, "bf16")
+
+
+@pytest.mark.parametrize("n", [2, 33, 64, 65, 128, 130, 192])   # one, two and three stages of 64 keys, whole and ragged
+def test_short_captures_on_the_matrix_core_path(n):
+    """Capture lengths around the kernels' stage (64 keys), block (32) and tile (128 rows) sizes: the summed form
+    against the oracle, and the fused build of a map of that very length."""
+    Hq, Hkv, d = 4, 2, 128
+    Q, K = seq_pair(300 + n, Hq, Hkv, n, d, "bf16", std=1.2)
+    L = max(n, 4)
+    A, C = oracle.capture(Q, K, L)
+    a_dev = torch.zeros((Hq, L, L), dtype=torch.float32, device="cuda")
+    c_dev = torch.zeros((Hq, L, L), dtype=torch.float32, device="cuda")
+    B.dam_capture_accumulate(dev(Q, "bf16"), dev(K, "bf16"), a_dev, c_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(c_dev.cpu().numpy(), C)
+    err = np.abs(a_dev.cpu().numpy() - A)
+    assert (err <= ATOL + RTOL * A).all(), err.max()
+    w = wl.scaled(wl.WORKLOADS["c2"], hq=Hq, hkv=Hkv, seq=n, pcl=n)
+    fused_against_oracle(Q, K, w, n, 128, 128, 0.05, 0.8, "bf16")
