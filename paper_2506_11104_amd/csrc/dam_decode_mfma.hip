@@ -132,8 +132,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         // (PLAN: a pattern whose key does not exist yet is masked below; its row is taken from the keys that do, since
         // rows beyond the position may hold anything, and a NaN there would survive a zero weight)
         const int key = min(max(v, 0), PLAN ? min(a.pos, a.cap - 1) : a.cap - 1);
-        koff[it] = (unsigned)key * a.row_bytes + ((pos ^ (r & 15)) << 4);
-        voff[it] = (unsigned)key * a.row_bytes + ((pos ^ (sub << 2)) << 4);
+        // (row index and row stride are below 2^24: the 24-bit multiply runs at full rate, the 32-bit one does not)
+        const unsigned row_at = __umul24((unsigned)key, a.row_bytes);
+        koff[it] = row_at + ((pos ^ (r & 15)) << 4);
+        voff[it] = row_at + ((pos ^ (sub << 2)) << 4);
       }
       lds_copy16_once<0 * 1024>(k_at, kg, koff[0]);
       lds_copy16_once<1 * 1024>(k_at, kg, koff[1]);
@@ -212,8 +214,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       unsigned mine = 0;  // bit k: key k of the block is kept by this lane's head
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
-        const unsigned kept_x = (unsigned)__ballot((mem >> x) & 1);
-        if (n == x) mine = kept_x;
+        if (x < G) {  // wave-uniform
+          const unsigned kept_x = (unsigned)__ballot((mem >> x) & 1);
+          if (n == x) mine = kept_x;
+        }
       }
       if (n >= G) mine = 0;
 
@@ -308,7 +312,9 @@ namespace dam {
 bool decode_group_mfma_fits(const dam_decode_params *p) {
   if (p->dtype != DAM_BF16 || p->head_dim != 128) return false;
   if (p->hq / p->hkv > 8) return false;
-  // row addresses are a base per (sequence, KV head) plus a 32-bit byte offset
+  // row addresses are a base per (sequence, KV head) plus a 32-bit byte offset, the product of a row index and a
+  // row stride of at most 24 bits each
+  if (p->kv_capacity >= (1 << 24) || p->kv_stride[2] * 2 >= (1 << 24)) return false;
   return (uint64_t)p->kv_capacity * (uint64_t)p->kv_stride[2] * 2u < (1ull << 32);
 }
 
