@@ -13,6 +13,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "dam_internal.h"
 
@@ -933,24 +934,27 @@ __device__ __forceinline__ void tile_classes_of_head(const Geom &g, const uint64
 
 // The column bitset and the reversed diagonal bitset of one head, copied into LDS by the whole
 // workgroup when they fit (lds_words = 2 pw, else 0): every mask word then costs LDS reads instead
-// of dependent global loads. Returns the pointers to use; contains a barrier.
+// of dependent global loads. Contains a barrier. The callers then run their body on the
+// LDS array itself, in a call of its own: only then does the compiler know the address space of the sets and read
+// them with LDS instructions (a pointer that may be either is read through the flat path, with waits on both counters).
 constexpr size_t kMaxStagedBytes = 48 * 1024;
+constexpr int kGuardFront = 4, kGuardBack = 2;
 
 inline size_t staged_bytes(const Geom &g) {
-  const size_t b = (size_t)g.pw * 2 * sizeof(uint64_t);
+  const size_t b = ((size_t)g.pw * 2 + kGuardFront + kGuardBack) * sizeof(uint64_t);
   return b <= kMaxStagedBytes ? b : 0;
 }
 
-__device__ __forceinline__ void stage_sets(uint64_t *lds_sets, bool staged, int pw, const uint64_t *&cb,
-                                           const uint64_t *&rr) {
-  if (!staged) return;  // uniform over the grid
+// Layout: the column set (pw words), kGuardFront zero words, the reversed diagonal set (pw words), kGuardBack zero
+// words: words -kGuardFront .. -1 and pw, pw + 1 of the staged diagonal set read as empty without a test.
+__device__ __forceinline__ void stage_sets(uint64_t *lds_sets, int pw, const uint64_t *cb, const uint64_t *rr) {
   for (int x = threadIdx.x; x < pw; x += blockDim.x) {
     lds_sets[x] = cb[x];
-    lds_sets[pw + x] = rr[x];
+    lds_sets[pw + kGuardFront + x] = rr[x];
   }
+  if (threadIdx.x < kGuardFront + kGuardBack)
+    lds_sets[threadIdx.x < kGuardFront ? pw + threadIdx.x : 2 * pw + threadIdx.x] = 0;
   __syncthreads();
-  cb = lds_sets;
-  rr = lds_sets + pw;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1295,9 +1299,16 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
   const uint64_t *tb = true_bits ? true_bits + (int64_t)h * g.L * g.tbw : nullptr;
   const uint64_t *cb = cbits + (int64_t)h * g.pw;
   const uint64_t *rr = rrev + (int64_t)h * g.pw;
-  stage_sets(lds_sets, staged, g.pw, cb, rr);
   int mine = 0;
-  if (qt < g.nQt) mine = tile_scan_row(g, tb, cb, rr, col_any, col_all, off_any, off_all, occ, full, cnt, gidx, gcnt, gstride, vocc, vfull, h, qt, lane);
+  if (staged) {  // uniform over the grid
+    stage_sets(lds_sets, g.pw, cb, rr);
+    if (qt < g.nQt)
+      mine = tile_scan_row(g, tb, lds_sets, lds_sets + g.pw + kGuardFront, col_any, col_all, off_any, off_all, occ, full, cnt, gidx, gcnt,
+                           gstride, vocc, vfull, h, qt, lane);
+  } else if (qt < g.nQt) {
+    mine = tile_scan_row(g, tb, cb, rr, col_any, col_all, off_any, off_all, occ, full, cnt, gidx, gcnt, gstride, vocc, vfull, h,
+                         qt, lane);
+  }
   // the head's total, for the offsets that the fill kernel derives itself (plain atomics, read by the next kernel
   // only; spread over kHeadSub words per head, because atomics on one address are served one after the other)
   if (lane == 0) wave_cnt[wave] = mine;
@@ -1346,7 +1357,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   for (int x = lane; x < qt; x += 64) part += cnt_h[x];
   const int my_cnt = cnt_h[qt];
   uint64_t ow_next = oc[0], fw_next = fl[0];
-  stage_sets(lds_sets, staged, g.pw, cb, rr);
+  if (staged) stage_sets(lds_sets, g.pw, cb, rr);  // uniform over the grid
   if (!live) return;
   for (int off = 32; off; off >>= 1) part += __shfl_xor(part, off);
   const int64_t first = part;
@@ -1364,6 +1375,9 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int qw = g.tile_n / 4;  // quarter width in keys, a multiple of 16
   // gathered columns: the ordinary tiles of a query tile of the pattern region hold the diagonal part only
   const bool split = gidx != nullptr && qt * g.tile_m >= g.L;
+  // the walk, once for sets in LDS and once for sets in global memory (see stage_sets)
+  auto walk = [&](const uint64_t *cb, const uint64_t *rr, auto in_lds) __attribute__((always_inline)) {
+  constexpr bool IN_LDS = decltype(in_lds)::value;
   if (split) cb = nullptr;
   // walk the listed tiles of this query tile in ascending order
   int rank = 0;
@@ -1400,45 +1414,66 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       if (!mine || t >= capacity) continue;
       // element words, and which key quarters of the tile hold a kept entry
       const bool is_full = (fw >> (kt & 63)) & 1;
-      int quarters = 0;
+      int quarters = 0, kind_q = 0;  // occupied key quarters: per lane (summed up by ballots below), or for the wave
+      const bool quarters_used = !(words == 256 && g.wpr == 2 && qt * 128 >= g.L && qt * 128 + 128 <= g.S);
       if (words == 256 && g.wpr == 2 && qt * 128 >= g.L && qt * 128 + 128 <= g.S) {
         // 128 x 128 tile with every row in the pattern region: a lane takes rows lane and lane + 64 whole
-        // (128 keys = two words). The offsets i - j of a row's 128 keys are 128 consecutive positions of
-        // the reversed diagonal set, starting at Q - (i - 128 kt): two funnel shifts over three words.
+        // (128 keys = two words). The offsets i - j of a row's 128 keys are 128 consecutive positions of the
+        // reversed diagonal set, starting at Q - (i - 128 kt); row lane + 64 starts 64 positions below row lane,
+        // so both rows come out of four consecutive words of the set: 256 bits, of which row lane + 64 takes
+        // bits [sh, sh + 128) and row lane bits [64 + sh, 64 + sh + 128), as 32-bit funnel shifts.
         const int Q = g.pw * 64 - 1;
         const uint64_t c0 = cb ? set_word(cb, 2 * kt, g.pw) : 0, c1 = cb ? set_word(cb, 2 * kt + 1, g.pw) : 0;
-        uint64_t m[2][2];
+        const int u_lane = (qt - kt) * 128 + lane;  // offset of the tile's first key in row lane, >= 0
+        const int s0 = Q - u_lane;                  // (negative where the row's offsets lie beyond the pattern length)
+        const int w0 = max(s0 >> 6, -3);            // from word -3 down all four words are outside the set
+        // (staged sets carry four zero words in front and two behind: words -4 .. -1, pw and pw + 1 read as nothing)
+        // (written out value by value: arrays indexed in unrolled loops end up in scratch memory here, because the
+        // choice between neighbours below is turned into an index first)
+        auto word = [&](int w) { return IN_LDS ? rr[w] : set_word(rr, w, g.pw); };
+        const uint64_t wd0 = word(w0 - 1), wd1 = word(w0), wd2 = word(w0 + 1), wd3 = word(w0 + 2);
+        const uint32_t e0 = (uint32_t)wd0, e1 = (uint32_t)(wd0 >> 32), e2 = (uint32_t)wd1, e3 = (uint32_t)(wd1 >> 32);
+        const uint32_t e4 = (uint32_t)wd2, e5 = (uint32_t)(wd2 >> 32), e6 = (uint32_t)wd3, e7 = (uint32_t)(wd3 >> 32);
+        const bool odd = (s0 & 32) != 0;
+        const int r = s0 & 31;
+        const uint32_t f0 = odd ? e1 : e0, f1 = odd ? e2 : e1, f2 = odd ? e3 : e2, f3 = odd ? e4 : e3;
+        const uint32_t f4 = odd ? e5 : e4, f5 = odd ? e6 : e5, f6 = odd ? e7 : e6;
+        uint32_t row[2][4];  // [u][dword]: row lane + 64 u
+        row[1][0] = __builtin_amdgcn_alignbit(f1, f0, r);
+        row[1][1] = __builtin_amdgcn_alignbit(f2, f1, r);
+        row[1][2] = __builtin_amdgcn_alignbit(f3, f2, r);
+        row[1][3] = __builtin_amdgcn_alignbit(f4, f3, r);
+        row[0][0] = row[1][2];
+        row[0][1] = row[1][3];
+        row[0][2] = __builtin_amdgcn_alignbit(f5, f4, r);
+        row[0][3] = __builtin_amdgcn_alignbit(f6, f5, r);
+        const uint32_t cd[4] = {(uint32_t)c0, (uint32_t)(c0 >> 32), (uint32_t)c1, (uint32_t)(c1 >> 32)};
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int u0 = (qt - kt) * 128 + lane + 64 * u;  // offset of the tile's first key in this row, >= 0
-          const int s0 = Q - u0;
-          const int w0 = s0 >> 6, sh = s0 & 63;             // floor division also for negative positions
-          const uint64_t a = set_word(rr, w0, g.pw), b = set_word(rr, w0 + 1, g.pw), c = set_word(rr, w0 + 2, g.pw);
-          uint64_t d0 = a, d1 = b;
-          if (sh) {
-            d0 = (a >> sh) | (b << (64 - sh));
-            d1 = (b >> sh) | (c << (64 - sh));
-          }
-          m[u][0] = is_full ? ~0ull : (d0 | c0);
-          m[u][1] = is_full ? ~0ull : (d1 | c1);
-          if (kt == qt) {  // the diagonal tile (wave-uniform): keys up to u0 only
-            m[u][0] &= u0 >= 63 ? ~0ull : ((2ull << u0) - 1);
-            m[u][1] &= u0 >= 127 ? ~0ull : (u0 < 64 ? 0ull : ((2ull << (u0 - 64)) - 1));
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int k = 0; k < 4; ++k) row[u][k] = is_full ? ~0u : (row[u][k] | cd[k]);
+        if (kt == qt) {  // the diagonal tile (wave-uniform): keys up to the row's own only
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const int u0 = u_lane + 64 * u;  // = the row's index inside the tile
+            const uint64_t lo = u0 >= 63 ? ~0ull : ((2ull << u0) - 1);
+            const uint64_t hi = u0 >= 127 ? ~0ull : (u0 < 64 ? 0ull : ((2ull << (u0 - 64)) - 1));
+            row[u][0] &= (uint32_t)lo; row[u][1] &= (uint32_t)(lo >> 32);
+            row[u][2] &= (uint32_t)hi; row[u][3] &= (uint32_t)(hi >> 32);
           }
         }
+        if (tile_bits) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          if (tile_bits) {
+          for (int u = 0; u < 2; ++u) {
             uint4 st;
-            st.x = (uint32_t)m[u][0]; st.y = (uint32_t)(m[u][0] >> 32);
-            st.z = (uint32_t)m[u][1]; st.w = (uint32_t)(m[u][1] >> 32);
+            st.x = row[u][0]; st.y = row[u][1]; st.z = row[u][2]; st.w = row[u][3];
             *reinterpret_cast<uint4 *>(tile_bits + t * 256 + 2 * (lane + 64 * u)) = st;
           }
-          if ((uint32_t)m[u][0]) quarters |= 1;
-          if (m[u][0] >> 32) quarters |= 2;
-          if ((uint32_t)m[u][1]) quarters |= 4;
-          if (m[u][1] >> 32) quarters |= 8;
         }
+        // a key quarter is 32 keys: one of the four 32-bit words of a row
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (__ballot((row[0][k] | row[1][k]) != 0)) kind_q |= 2 << k;
       } else if (words == 256 && g.wpr == 2) {
         // 128 x 128 tiles: four words per lane, evaluated together so that their loads overlap
         uint64_t m[4];
@@ -1472,9 +1507,10 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
           }
         }
       }
-      int kind = is_full ? 1 : 0;
-      for (int q = 0; q < 4; ++q)
-        if (__ballot(quarters & (1 << q))) kind |= 2 << q;
+      int kind = (is_full ? 1 : 0) | kind_q;
+      if (quarters_used)
+        for (int q = 0; q < 4; ++q)
+          if (__ballot(quarters & (1 << q))) kind |= 2 << q;
       if (lane == 0) {
         if (blk_col) blk_col[t] = kt;
         if (blk_kind) blk_kind[t] = (uint8_t)kind;
@@ -1488,8 +1524,6 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int n_gt = (gcnt[h] + g.tile_n - 1) / g.tile_n;
   const int *gi = gidx + (int64_t)h * gstride;
   const int i0 = qt * g.tile_m;
-  // a gathered tile: its units u = (slot group wg, row word k), one after the other (128 x 128 tiles: four)
-  const int units = g.wpr * (g.tile_m / 64);
   for (int ow_i = 0; ow_i * 64 < n_gt; ++ow_i) {
     uint64_t ow = voc[ow_i];
     const uint64_t vfw = vfl[ow_i];
@@ -1509,11 +1543,10 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
         continue;
       }
       int kind = 0;
-      for (int u = 0; u < units; ++u) {
-        const int wg = u % g.wpr, k = u / g.wpr;
-        const int slot = wg * 64 + lane;  // slot of this lane inside the tile
+      for (int wg = 0; wg < g.wpr; ++wg) {  // the tile's slots, 64 at a time: lane = slot
+        const int c = gi[v * g.tile_n + wg * 64 + lane];
         uint64_t keep[4];
-        slot_rows(g, rr, i0, gi[v * g.tile_n + slot], keep);
+        slot_rows(g, rr, i0, c, keep);
         const bool any = (keep[0] | keep[1] | keep[2] | keep[3]) != 0;
         const uint64_t lanes_any = __ballot(any);
         for (int q = 0; q < 4; ++q) {  // quarter q: slots [q qw, (q + 1) qw)
@@ -1524,10 +1557,18 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
             if (lanes_any & span) kind |= 2 << q;
           }
         }
-        if (tile_bits && !(is_full && skip_full_bits)) {
-          // transpose: lane r gets the word (row 64 k + r, group wg), whose bit l is slot l of the group
-          const uint64_t rows_k = k == 0 ? keep[0] : k == 1 ? keep[1] : k == 2 ? keep[2] : keep[3];
-          tile_bits[t * words + (int64_t)(64 * k + lane) * g.wpr + wg] = transpose64(rows_k, lane);
+        if (tile_bits) {
+          const uint64_t filled = __ballot(c >= 0);
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            if (k < g.tile_m / 64) {
+              // rows 64 k .. 64 k + 63 of the group: lane r gets the word (row 64 k + r, group wg), whose bit l is
+              // slot l. Where every filled slot keeps all 64 rows (no row above a column, no matched offset met:
+              // the usual case away from the diagonal) every row's word is the set of filled slots; otherwise the
+              // 64 x 64 bits are transposed.
+              const bool plain = __ballot(keep[k] != (c >= 0 ? ~0ull : 0ull)) == 0;  // wave-uniform
+              tile_bits[t * words + (int64_t)(64 * k + lane) * g.wpr + wg] = plain ? filled : transpose64(keep[k], lane);
+            }
         }
       }
       if (lane == 0) {
@@ -1536,6 +1577,11 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
       }
     }
   }
+  };
+  if (staged)
+    walk(lds_sets, lds_sets + g.pw + kGuardFront, std::true_type{});
+  else
+    walk(cb, rr, std::false_type{});
 }
 
 __global__ void k_dense_bits(Geom g, const uint64_t *__restrict__ true_bits,
