@@ -1084,7 +1084,7 @@ __device__ __forceinline__ int tile_scan_row(const Geom &g, const uint64_t *__re
   const uint64_t *da = off_any + (int64_t)h * g.occw, *df = off_all + (int64_t)h * g.occw;
   const int words = g.tile_m * g.wpr;
   int total = 0;
-  for (int w = 0; w < g.occw; ++w) {
+  for (int w = 0; w <= (kmax >> 6); ++w) {  // (the words past the diagonal tile's are neither written nor read)
     const int kt = w * 64 + lane;
     int f = 0;
     if (kt <= kmax) {
@@ -1152,22 +1152,26 @@ __device__ __forceinline__ int tile_scan_row(const Geom &g, const uint64_t *__re
       r_bound = dmax * g.tile_n + g.tile_n - 1;
     }
     const int n_cols = split ? gcnt[h] : 0;
-    for (int w = 0; w < g.occw; ++w) {
+    for (int w = 0; w * 64 < n_gt; ++w) {  // (only the words that hold a gathered tile are written, and read)
       // A complete gathered tile whose columns all lie further above this query tile than any matched diagonal
       // reaches is full without looking: every row is causal for every slot and no offset i - c is a matched
-      // one. One lane per tile; the other tiles are evaluated slot by slot.
-      bool certain = false;
-      if (w * 64 < n_gt && r_bound != INT64_MAX) {  // wave-uniform
+      // one. A tile whose first column lies below the query tile's last row holds nothing (its columns ascend).
+      // One lane per tile; the other tiles are evaluated slot by slot.
+      bool certain = false, nothing = false;
+      {
         const int v = w * 64 + lane;
-        if (v < n_gt && (v + 1) * g.tile_n <= n_cols && i0 + g.tile_m <= g.S) {
-          const int cmax = gi[v * g.tile_n + g.tile_n - 1];  // the columns of a tile ascend
-          certain = cmax >= 0 && (int64_t)i0 - cmax > r_bound;
+        if (v < n_gt) {
+          nothing = gi[v * g.tile_n] > i_last;
+          if (r_bound != INT64_MAX && (v + 1) * g.tile_n <= n_cols && i0 + g.tile_m <= g.S) {
+            const int cmax = gi[v * g.tile_n + g.tile_n - 1];  // the columns of a tile ascend
+            certain = cmax >= 0 && (int64_t)i0 - cmax > r_bound;
+          }
         }
       }
-      const uint64_t sure = __ballot(certain);
+      const uint64_t sure = __ballot(certain), skip = sure | __ballot(nothing);
       uint64_t ow = sure, fw = sure;
       for (int v = w * 64; v < min(n_gt, w * 64 + 64); ++v) {
-        if ((sure >> (v & 63)) & 1) continue;  // wave-uniform
+        if ((skip >> (v & 63)) & 1) continue;  // wave-uniform
         bool any = false, all = true;
         for (int wg = 0; wg < g.wpr; ++wg) {
           const int c = gi[v * g.tile_n + wg * 64 + lane];
@@ -1524,27 +1528,51 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   const int n_gt = (gcnt[h] + g.tile_n - 1) / g.tile_n;
   const int *gi = gidx + (int64_t)h * gstride;
   const int i0 = qt * g.tile_m;
+  // (a tile's columns are fetched while the tile before it is written: a load issued behind stores waits for them)
+  int v_pre = -1, c_pre[4] = {-1, -1, -1, -1};  // (tiles are at most 256 wide: four groups of 64 slots)
   for (int ow_i = 0; ow_i * 64 < n_gt; ++ow_i) {
     uint64_t ow = voc[ow_i];
     const uint64_t vfw = vfl[ow_i];
-    while (ow) {
-      const int v = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
-      ow &= ow - 1;
-      const int64_t t = first + rank;
-      const bool mine = rank % share == my_turn;
-      ++rank;
-      if (!mine || t >= capacity) continue;
-      const bool is_full = (vfw >> (v & 63)) & 1;
-      if (is_full && skip_full_bits) {  // wave-uniform: column and kind only (every quarter of a full tile is occupied)
-        if (lane == 0) {
-          if (blk_col) blk_col[t] = g.nKt + v;
+    if (skip_full_bits) {
+      // full tiles get a column and a kind only: all of the word's at once, lane j takes gathered tile 64 ow_i + j
+      const uint64_t listed = ow;
+      const int r = rank + __popcll(listed & ((1ull << lane) - 1));
+      if (((listed & vfw) >> lane) & 1) {
+        const int64_t t = first + r;
+        if (r % share == my_turn && t < capacity) {
+          if (blk_col) blk_col[t] = g.nKt + ow_i * 64 + lane;
           if (blk_kind) blk_kind[t] = (uint8_t)31;
         }
-        continue;
+      }
+    }
+    const uint64_t listed_v = ow;
+    const int rank0_v = rank;
+    rank += __popcll(listed_v);
+    if (skip_full_bits) ow &= ~vfw;
+    while (ow) {
+      const int bit = __ffsll((unsigned long long)ow) - 1;
+      const int v = ow_i * 64 + bit;
+      ow &= ow - 1;
+      const int rk = rank0_v + __popcll(listed_v & ((1ull << bit) - 1));
+      const int64_t t = first + rk;
+      const bool mine = rk % share == my_turn;
+      if (!mine || t >= capacity) continue;
+      const bool is_full = (vfw >> (v & 63)) & 1;
+      int c_all[4];
+#pragma unroll
+      for (int wg = 0; wg < 4; ++wg)
+        if (wg < g.wpr) c_all[wg] = v == v_pre ? c_pre[wg] : gi[v * g.tile_n + wg * 64 + lane];
+      if (ow) {  // the next listed tile of this word (if it turns out not to be this wave's, the fetch is wasted)
+        v_pre = ow_i * 64 + __ffsll((unsigned long long)ow) - 1;
+#pragma unroll
+        for (int wg = 0; wg < 4; ++wg)
+          if (wg < g.wpr) c_pre[wg] = gi[v_pre * g.tile_n + wg * 64 + lane];
       }
       int kind = 0;
-      for (int wg = 0; wg < g.wpr; ++wg) {  // the tile's slots, 64 at a time: lane = slot
-        const int c = gi[v * g.tile_n + wg * 64 + lane];
+#pragma unroll
+      for (int wg = 0; wg < 4; ++wg) {  // the tile's slots, 64 at a time: lane = slot
+        if (wg >= g.wpr) break;
+        const int c = c_all[wg];
         uint64_t keep[4];
         slot_rows(g, rr, i0, c, keep);
         const bool any = (keep[0] | keep[1] | keep[2] | keep[3]) != 0;
