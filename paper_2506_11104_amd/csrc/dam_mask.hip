@@ -764,7 +764,8 @@ __device__ __forceinline__ unsigned flags16(const uint8_t *__restrict__ row, int
 // (every thread of the workgroup calls this; 256 words per pass)
 __device__ __forceinline__ void pattern_bitsets_of_head(const uint8_t *__restrict__ diag_flag,
                                                         const uint8_t *__restrict__ vert_flag, int P, int pw, int h,
-                                                        uint64_t *__restrict__ cbits, uint64_t *__restrict__ rrev) {
+                                                        uint64_t *__restrict__ cbits, uint64_t *__restrict__ rrev,
+                                                        uint64_t *lds_copy) {  // both sets again, [2 pw], or nullptr
   const int part = threadIdx.x & 3;
   const uint8_t *drow = diag_flag + (int64_t)h * P, *vrow = vert_flag + (int64_t)h * P;
   const bool d_al = (reinterpret_cast<uintptr_t>(drow) & 15) == 0, v_al = (reinterpret_cast<uintptr_t>(vrow) & 15) == 0;
@@ -781,8 +782,13 @@ __device__ __forceinline__ void pattern_bitsets_of_head(const uint8_t *__restric
     rw |= __shfl_xor(rw, 1);
     rw |= __shfl_xor(rw, 2);
     if (live && part == 0) {
+      const uint64_t rev = __brevll(rw);  // bit q of the word <- offset (pw*64 - 1) - (64 w + q)
       cbits[(int64_t)h * pw + w] = cw;
-      rrev[(int64_t)h * pw + w] = __brevll(rw);  // bit q of the word <- offset (pw*64 - 1) - (64 w + q)
+      rrev[(int64_t)h * pw + w] = rev;
+      if (lds_copy) {
+        lds_copy[w] = cw;
+        lds_copy[pw + w] = rev;
+      }
     }
   }
 }
@@ -896,13 +902,11 @@ __device__ int pattern_tile_flags(const uint64_t *__restrict__ cb, const uint64_
 // property of kt alone and "some offset matched" / "all offsets matched" of d alone. The d classes
 // are stored reversed (d at position 64 dw - 1 - d), like the diagonal set, so that the 64 key tiles
 // of an occupancy word are 64 consecutive bits.
-__device__ __forceinline__ void tile_classes_of_head(const Geom &g, const uint64_t *__restrict__ cbits,
-                                                     const uint64_t *__restrict__ rrev, int h, uint64_t *__restrict__ col_any,
+__device__ __forceinline__ void tile_classes_of_head(const Geom &g, const uint64_t *__restrict__ cb,  // the head's sets
+                                                     const uint64_t *__restrict__ rr, int h, uint64_t *__restrict__ col_any,
                                                      uint64_t *__restrict__ col_all, uint64_t *__restrict__ off_any,
                                                      uint64_t *__restrict__ off_all) {
   const int lane = threadIdx.x & 63;
-  const uint64_t *cb = cbits + (int64_t)h * g.pw;
-  const uint64_t *rr = rrev + (int64_t)h * g.pw;
   const int T = g.tile_n;
   const int64_t Q = (int64_t)g.pw * 64 - 1;
   for (int w = threadIdx.x >> 6; w < g.occw; w += blockDim.x >> 6) {  // a wave per occupancy word
@@ -967,11 +971,10 @@ __device__ __forceinline__ void stage_sets(uint64_t *lds_sets, int pw, const uin
 
 // The matched columns below S of one head, ascending, padded with -1 up to the stride. One workgroup per
 // head, a word of the column bitset per thread and pass.
-__device__ __forceinline__ void gather_columns_of_head(const Geom &g, const uint64_t *__restrict__ cbits, int stride, int h,
-                                                       int *__restrict__ gidx, int *__restrict__ gcnt) {
+__device__ __forceinline__ void gather_columns_of_head(const Geom &g, const uint64_t *__restrict__ cb,  // the head's column set
+                                                       int stride, int h, int *__restrict__ gidx, int *__restrict__ gcnt) {
   __shared__ int s_wave[16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint64_t *cb = cbits + (int64_t)h * g.pw;
   int *out = gidx + (int64_t)h * stride;
   const int n_cols = min(g.P, g.S);
   int base = 0;  // the same value in every thread
@@ -1002,7 +1005,16 @@ __device__ __forceinline__ void gather_columns_of_head(const Geom &g, const uint
     __syncthreads();  // s_wave is rewritten in the next pass
   }
   if (threadIdx.x == 0) gcnt[h] = base;
-  for (int x = base + threadIdx.x; x < stride; x += blockDim.x) out[x] = -1;
+  // the empty slots: 16 bytes per store where the row allows it (rows are `stride` ints apart, a multiple of 64)
+  const int first4 = (base + 3) & ~3;
+  if ((reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+    if (base + (int)threadIdx.x < min(first4, stride)) out[base + threadIdx.x] = -1;
+    for (int x = first4 + 4 * (int)threadIdx.x; x + 4 <= stride; x += 4 * blockDim.x)
+      *reinterpret_cast<int4 *>(out + x) = make_int4(-1, -1, -1, -1);
+    if ((int)threadIdx.x < (stride & 3)) out[(stride & ~3) + threadIdx.x] = -1;
+  } else {
+    for (int x = base + threadIdx.x; x < stride; x += blockDim.x) out[x] = -1;
+  }
 }
 
 // Everything the block index needs from the pattern flags of one head, in one launch (one workgroup of 1024
@@ -1014,14 +1026,22 @@ __global__ __launch_bounds__(1024) void k_pattern_prep(Geom g, const uint8_t *__
                                                        uint64_t *__restrict__ col_any, uint64_t *__restrict__ col_all,
                                                        uint64_t *__restrict__ off_any, uint64_t *__restrict__ off_all,
                                                        int gstride, int *__restrict__ gidx, int *__restrict__ gcnt,
-                                                       int *__restrict__ head_cnt) {
+                                                       int *__restrict__ head_cnt, bool in_lds) {
+  extern __shared__ uint64_t prep_sets[];  // in_lds: the head's two sets, [2 pw]
   const int h = blockIdx.x;
   if (threadIdx.x < kHeadSub) head_cnt[h * kHeadSub + threadIdx.x] = 0;  // the head's number of listed tiles: summed by k_tile_scan
-  pattern_bitsets_of_head(diag_flag, vert_flag, g.P, g.pw, h, cbits, rrev);
+  pattern_bitsets_of_head(diag_flag, vert_flag, g.P, g.pw, h, cbits, rrev, in_lds && classes ? prep_sets : nullptr);
   if (!classes) return;  // uniform over the grid
-  __syncthreads();       // the sets are read back from memory by other threads of this workgroup
-  tile_classes_of_head(g, cbits, rrev, h, col_any, col_all, off_any, off_all);
-  if (gidx) gather_columns_of_head(g, cbits, gstride, h, gidx, gcnt);
+  __syncthreads();       // the sets are read back by other threads of this workgroup
+  // (from the LDS copy when they fit: the steps below are chains of dependent reads. One call per address space,
+  // so that the compiler knows which kind of read to use.)
+  if (in_lds) {
+    tile_classes_of_head(g, prep_sets, prep_sets + g.pw, h, col_any, col_all, off_any, off_all);
+    if (gidx) gather_columns_of_head(g, prep_sets, gstride, h, gidx, gcnt);
+  } else {
+    tile_classes_of_head(g, cbits + (int64_t)h * g.pw, rrev + (int64_t)h * g.pw, h, col_any, col_all, off_any, off_all);
+    if (gidx) gather_columns_of_head(g, cbits + (int64_t)h * g.pw, gstride, h, gidx, gcnt);
+  }
 }
 
 // Transpose of the 64 x 64 bit matrix whose row l is the word x of lane l: lane r returns the word whose
@@ -2115,9 +2135,10 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
   const int gstride = dam_gather_stride(p);
   const int *gidx = gather ? o->gather_idx : nullptr, *gcnt = gather ? o->gather_cnt : nullptr;
   if (want_blocks || want_lists || o->dense_bits) {
-    k_pattern_prep<<<g.H, 1024, 0, stream>>>(g, dflag, vflag, w.cbits, w.rrev, want_blocks, w.col_any, w.col_all, w.off_any,
-                                            w.off_all, gstride, gather ? o->gather_idx : nullptr, gather ? o->gather_cnt : nullptr,
-                                            w.head_cnt);
+    const size_t prep_lds = want_blocks && (size_t)g.pw * 16 <= kMaxStagedBytes ? (size_t)g.pw * 16 : 0;
+    k_pattern_prep<<<g.H, 1024, prep_lds, stream>>>(g, dflag, vflag, w.cbits, w.rrev, want_blocks, w.col_any, w.col_all, w.off_any,
+                                                   w.off_all, gstride, gather ? o->gather_idx : nullptr,
+                                                   gather ? o->gather_cnt : nullptr, w.head_cnt, prep_lds > 0);
   }
   // a4 + a5: tile occupancy, CSR offsets, tile bits
   if (want_blocks) {
