@@ -537,10 +537,12 @@ int decode_grouped_run(const dam_decode_params *p, const void *q, const void *kc
   float *part_o = c.take<float>((size_t)a.B * a.Hq * a.splits * p->head_dim);
   float *part_ml = c.take<float>((size_t)a.B * a.Hq * a.splits * 2);
   if (mfma) {
-    // matrix-core partial pass, then the merge pass (also for one split: it normalises and stores)
-    launch_decode_group_mfma(p, a.splits, a.scale, q, kcache, vcache, kept_ptr, kept_idx, kept_member, part_o, part_ml, st,
-                             plan_table, n_flags, pos);
-    k_decode_merge<__hip_bfloat16, 128><<<a.B * a.Hq, 128, 0, st>>>(a, part_o, part_ml, static_cast<__hip_bfloat16 *>(out), lse);
+    // matrix-core pass; with more than four splits its partial results go through the merge pass
+    const int rc = launch_decode_group_mfma(p, a.splits, a.scale, q, kcache, vcache, kept_ptr, kept_idx, kept_member, part_o,
+                                            part_ml, out, lse, st, plan_table, n_flags, pos);
+    if (rc != DAM_OK) return rc;
+    if (!decode_group_mfma_merges(a.splits))
+      k_decode_merge<__hip_bfloat16, 128><<<a.B * a.Hq, 128, 0, st>>>(a, part_o, part_ml, static_cast<__hip_bfloat16 *>(out), lse);
   } else if (plan_table) {
     return DAM_ERR_UNSUPPORTED;  // plans are decoded by the matrix-core kernel only
   } else if (p->dtype == DAM_BF16) {

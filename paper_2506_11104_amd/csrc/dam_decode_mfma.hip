@@ -12,13 +12,15 @@
 // products of the prefill kernel with the query heads in the place of query rows, so the arithmetic
 // of a 32-key block shrinks to 16 matrix instructions and a 16-value softmax per lane.
 //
-// One wave per workgroup, no barriers: a wave owns every splits-th block of 32 list entries and two
+// No barrier inside the loop: a wave owns every splits-th block of 32 list entries and two
 // LDS slots of K and V rows (8 KiB each), filled by load-to-LDS copies whose row addresses come from
 // the list. The entries themselves (key indices and member bits) are staged in LDS by the same kind
 // of copy three blocks ahead, so that every vector-memory operation of the loop is one of these
 // copies and the waits can be counted by hand. While block i is computed the copies of block i + 1
 // are in flight; those of block i + 2 are issued as soon as block i has left its slot. Four waves
-// per CU (LDS), each with 16 to 32 KiB in flight.
+// per CU (LDS), each with 16 to 32 KiB in flight. The splits of a list are the waves of one workgroup
+// when there are at most four (the workgroup merges them and stores the output), else workgroups of
+// one wave each whose partial results go through the merge kernel.
 #include <math.h>
 
 #include "dam_internal.h"
@@ -36,8 +38,9 @@ constexpr int kLds = kFix + 4 * 256;
 
 struct MfmaArgs {
   int B, Hq, Hkv, cap, splits, shared_lists;
+  int fused;  // the splits of a list are the waves of one workgroup, which merges them itself and stores the result
   float scale;
-  int64_t q_sb, q_sh, kv_sb, kv_sh;
+  int64_t q_sb, q_sh, kv_sb, kv_sh, o_sb, o_sh;
   unsigned row_bytes;  // byte stride of a cache row
   int pos, n_flags;    // PLAN: position of the query row, length P of the pattern flags
 };
@@ -57,18 +60,23 @@ __device__ __forceinline__ void lds_copy4_at(unsigned lds_at, uint64_t addr) {
 // key does not exist yet (v > pos; a diagonal beyond pos likewise). The table byte of every column entry of a
 // block is fetched into LDS by one more copy per block, issued as soon as the block's entries have landed, two
 // blocks before its use, so that the loop still holds nothing but hand-counted copies.
+//
+// Up to four splits: they are the waves of one workgroup (each with LDS slots of its own; still no barrier inside the
+// loop), and at the end wave 0 merges the partial results through LDS, normalises and stores the output: no merge
+// launch. More splits: one wave per workgroup, partial results to the workspace for the merge kernel.
 template <bool PLAN>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_decode_group_mfma(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_decode_group_mfma(
     MfmaArgs a, const __hip_bfloat16 *__restrict__ q, const __hip_bfloat16 *__restrict__ kc,
     const __hip_bfloat16 *__restrict__ vc, const int *__restrict__ kept_ptr, const int *__restrict__ kept_idx,
     const uint8_t *__restrict__ kept_member, const uint8_t *__restrict__ plan_table, float *__restrict__ part_o,
-    float *__restrict__ part_ml) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-  const int lane = threadIdx.x;
+    float *__restrict__ part_ml, __hip_bfloat16 *__restrict__ out, float *__restrict__ lse) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_all[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  unsigned char *lds = lds_all + wave * kLds;  // this wave's slots
   const int n = lane & 31, hf = lane >> 5;     // column of the products (query head of the group), half-wave
   const int sub = lane >> 4, pos = lane & 15;  // copies: row within the instruction's four, 16-byte position
   const int G = a.Hq / a.Hkv;
-  const int split = blockIdx.x % a.splits, pair = blockIdx.x / a.splits;
+  const int split = a.fused ? wave : (int)blockIdx.x % a.splits, pair = a.fused ? (int)blockIdx.x : (int)blockIdx.x / a.splits;
   const int b = pair / a.Hkv, hkv = pair % a.Hkv;
   const int list = a.shared_lists ? hkv : pair;
   const int lo = __builtin_amdgcn_readfirstlane(kept_ptr[list]), end = __builtin_amdgcn_readfirstlane(kept_ptr[list + 1]);
@@ -289,6 +297,59 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
   // partial results in the form the merge pass takes: reference in log2 units, sum, un-normalised O
   const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float m2 = m_run == -INFINITY ? -INFINITY : m_run * c2;
+  if (a.fused) {
+    // waves 1 .. splits - 1 hand their results to wave 0 through their own (now idle) slots: value e of lane l at
+    // word 64 e + l (64 values of O, then the reference and the sum)
+    float *mine_x = reinterpret_cast<float *>(lds);
+    if (wave > 0) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mine_x[(16 * db + e) * 64 + lane] = oacc[db][e];
+      mine_x[64 * 64 + lane] = m2;
+      mine_x[65 * 64 + lane] = l_tot;
+    }
+    __syncthreads();
+    if (wave > 0) return;
+    // the merge of the splits as the merge kernel does it: weights 2^(reference - largest reference)
+    float M = m2;
+    for (int sp = 1; sp < a.splits; ++sp) M = fmaxf(M, reinterpret_cast<const float *>(lds_all + sp * kLds)[64 * 64 + lane]);
+    float L = 0.0f;
+    if (M > -INFINITY) {
+      const float w0 = exp2f(m2 - M);
+      L = w0 * l_tot;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[db][e] *= w0;
+      for (int sp = 1; sp < a.splits; ++sp) {
+        const float *theirs = reinterpret_cast<const float *>(lds_all + sp * kLds);
+        const float ws = exp2f(theirs[64 * 64 + lane] - M);
+        L += ws * theirs[65 * 64 + lane];
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[db][e] += ws * theirs[(16 * db + e) * 64 + lane];
+      }
+    }
+    if (n < G) {
+      const float inv = L > 0.0f ? 1.0f / L : 0.0f;
+      const int hq = hkv * G + n;
+      __hip_bfloat16 *op = out + b * a.o_sb + hq * a.o_sh;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 pr;
+          pr.x = pack_bf16(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
+          pr.y = pack_bf16(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
+          *reinterpret_cast<uint2 *>(op + 32 * db + 8 * g + 4 * hf) = pr;
+        }
+      if (lse && hf == 0) lse[(int64_t)b * a.Hq + hq] = L > 0.0f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+    }
+    return;
+  }
   if (n < G) {
     const int64_t slot_out = ((int64_t)b * a.Hq + hkv * G + n) * a.splits + split;
     float *po = part_o + slot_out * 128;
@@ -299,7 +360,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         *reinterpret_cast<float4 *>(po + 32 * db + 8 * g + 4 * hf) =
             make_float4(oacc[db][4 * g], oacc[db][4 * g + 1], oacc[db][4 * g + 2], oacc[db][4 * g + 3]);
     if (hf == 0) {
-      part_ml[slot_out * 2] = m_run == -INFINITY ? -INFINITY : m_run * c2;
+      part_ml[slot_out * 2] = m2;
       part_ml[slot_out * 2 + 1] = l_tot;
     }
   }
@@ -318,27 +379,41 @@ bool decode_group_mfma_fits(const dam_decode_params *p) {
   return (uint64_t)p->kv_capacity * (uint64_t)p->kv_stride[2] * 2u < (1ull << 32);
 }
 
-void launch_decode_group_mfma(const dam_decode_params *p, int splits, float scale, const void *q, const void *kc,
-                              const void *vc, const int32_t *kept_ptr, const int32_t *kept_idx,
-                              const uint8_t *kept_member, float *part_o, float *part_ml, hipStream_t st,
-                              const uint8_t *plan_table, int n_flags, int pos) {
+bool decode_group_mfma_merges(int splits) { return splits <= 4; }
+
+int launch_decode_group_mfma(const dam_decode_params *p, int splits, float scale, const void *q, const void *kc,
+                             const void *vc, const int32_t *kept_ptr, const int32_t *kept_idx,
+                             const uint8_t *kept_member, float *part_o, float *part_ml, void *out, float *lse,
+                             hipStream_t st, const uint8_t *plan_table, int n_flags, int pos) {
   MfmaArgs a;
   a.B = p->batch; a.Hq = p->hq; a.Hkv = p->hkv; a.cap = p->kv_capacity; a.splits = splits;
   a.shared_lists = p->shared_lists != 0;
   a.scale = scale;
   a.q_sb = p->q_stride[0]; a.q_sh = p->q_stride[1];
   a.kv_sb = p->kv_stride[0]; a.kv_sh = p->kv_stride[1];
+  a.o_sb = p->o_stride[0]; a.o_sh = p->o_stride[1];
   a.row_bytes = (unsigned)(p->kv_stride[2] * 2);
   a.pos = pos;
   a.n_flags = n_flags;
+  a.fused = decode_group_mfma_merges(splits) ? 1 : 0;
+  const int waves = a.fused ? splits : 1;
+  const int blocks = a.fused ? p->batch * p->hkv : p->batch * p->hkv * splits;
+  const size_t lds_bytes = (size_t)kLds * waves;
+  const void *kernel = plan_table ? reinterpret_cast<const void *>(k_decode_group_mfma<true>)
+                                  : reinterpret_cast<const void *>(k_decode_group_mfma<false>);
+  // (more than the default limit of dynamic LDS with two or more waves; idempotent, set on every call)
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kLds) != hipSuccess) return DAM_ERR_DEVICE;
   if (plan_table)
-    k_decode_group_mfma<true><<<p->batch * p->hkv * splits, 64, kLds, st>>>(
+    k_decode_group_mfma<true><<<blocks, 64 * waves, lds_bytes, st>>>(
         a, static_cast<const __hip_bfloat16 *>(q), static_cast<const __hip_bfloat16 *>(kc),
-        static_cast<const __hip_bfloat16 *>(vc), kept_ptr, kept_idx, kept_member, plan_table, part_o, part_ml);
+        static_cast<const __hip_bfloat16 *>(vc), kept_ptr, kept_idx, kept_member, plan_table, part_o, part_ml,
+        static_cast<__hip_bfloat16 *>(out), lse);
   else
-    k_decode_group_mfma<false><<<p->batch * p->hkv * splits, 64, kLds, st>>>(
+    k_decode_group_mfma<false><<<blocks, 64 * waves, lds_bytes, st>>>(
         a, static_cast<const __hip_bfloat16 *>(q), static_cast<const __hip_bfloat16 *>(kc),
-        static_cast<const __hip_bfloat16 *>(vc), kept_ptr, kept_idx, kept_member, nullptr, part_o, part_ml);
+        static_cast<const __hip_bfloat16 *>(vc), kept_ptr, kept_idx, kept_member, nullptr, part_o, part_ml,
+        static_cast<__hip_bfloat16 *>(out), lse);
+  return DAM_OK;
 }
 
 }  // namespace dam

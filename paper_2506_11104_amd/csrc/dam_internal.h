@@ -42,9 +42,11 @@ void launch_capture_true_bits(const dam_capture_params *p, const void *q, const 
 // head, split) in the layout the merge pass of dam_decode.hip reads. plan_table != nullptr: the lists are a
 // position-independent plan (DAM_MASK_PATTERN_PLAN) decoded at position pos; n_flags is the table's row length.
 bool decode_group_mfma_fits(const dam_decode_params *p);
-void launch_decode_group_mfma(const dam_decode_params *p, int splits, float scale, const void *q, const void *kc,
-                              const void *vc, const int32_t *kept_ptr, const int32_t *kept_idx,
-                              const uint8_t *kept_member, float *part_o, float *part_ml, hipStream_t st,
-                              const uint8_t *plan_table = nullptr, int n_flags = 0, int pos = 0);
+// true: the kernel merges the splits itself and stores the output (no merge pass, part_o / part_ml unused)
+bool decode_group_mfma_merges(int splits);
+int launch_decode_group_mfma(const dam_decode_params *p, int splits, float scale, const void *q, const void *kc,
+                             const void *vc, const int32_t *kept_ptr, const int32_t *kept_idx,
+                             const uint8_t *kept_member, float *part_o, float *part_ml, void *out, float *lse,
+                             hipStream_t st, const uint8_t *plan_table = nullptr, int n_flags = 0, int pos = 0);
 
 }  // namespace dam

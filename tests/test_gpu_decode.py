@@ -200,6 +200,19 @@ def test_grouped_decode_more_pairs_than_waves_fit():
     run_grouped(rng, "bf16", Bn, Hq, Hkv, 128, T, lists, shared=True)
 
 
+@pytest.mark.parametrize("Bn,Hkv", [(64, 8), (57, 6), (32, 8)])
+def test_grouped_decode_two_to_four_splits_merged_inside_the_workgroup(Bn, Hkv):
+    """512, 342 and 256 (sequence, KV head) pairs with lists of several blocks: two, three and four splits per list,
+    which the matrix-core kernel runs as the waves of one workgroup and merges itself (no merge pass)."""
+    rng = np.random.default_rng(56 + Hkv + Bn)
+    G, T = 2, 600
+    Hq = Hkv * G
+    lens = rng.integers(0, 520, Hq)
+    lens[0], lens[1], lens[2 * G] = 600, 0, 1
+    lens[G:2 * G] = 0                # a whole group that keeps nothing
+    run_grouped(rng, "bf16", Bn, Hq, Hkv, 128, T, overlapping_lists(rng, Hq, T, lens), shared=True)
+
+
 def test_grouped_decode_member_bytes_at_any_alignment():
     """The member bytes of a block are fetched as aligned words: the result may not depend on where the array
     starts."""
