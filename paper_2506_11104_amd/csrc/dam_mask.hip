@@ -1346,6 +1346,7 @@ __global__ __launch_bounds__(256) void k_tile_scan(Geom g, const uint64_t *__res
 // of the index and writes every listed tile itself, a lane per tile row. With few query tiles in all (share = 4) the
 // four waves of a workgroup share one query tile instead, each walking the whole row and taking every fourth
 // tile: more waves, but the walk is then three quarters of the instructions.
+template <bool STAGED>  // the head's pattern sets are staged in LDS (they fit), or read from global memory
 __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__restrict__ true_bits,
                                                    const uint64_t *__restrict__ cbits,
                                                    const uint64_t *__restrict__ rrev,
@@ -1356,7 +1357,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
                                                    int *__restrict__ blk_col,
                                                    uint8_t *__restrict__ blk_kind,
                                                    uint64_t *__restrict__ tile_bits, int64_t capacity,
-                                                   bool skip_full_bits, bool staged,
+                                                   bool skip_full_bits,
                                                    const int *__restrict__ gidx, const int *__restrict__ gcnt,
                                                    int gstride, const uint64_t *__restrict__ vocc,
                                                    const uint64_t *__restrict__ vfull, int share) {
@@ -1381,7 +1382,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
   for (int x = lane; x < qt; x += 64) part += cnt_h[x];
   const int my_cnt = cnt_h[qt];
   uint64_t ow_next = oc[0], fw_next = fl[0];
-  if (staged) stage_sets(lds_sets, g.pw, cb, rr);  // uniform over the grid
+  if (STAGED) stage_sets(lds_sets, g.pw, cb, rr);
   if (!live) return;
   for (int off = 32; off; off >>= 1) part += __shfl_xor(part, off);
   const int64_t first = part;
@@ -1626,7 +1627,7 @@ __global__ __launch_bounds__(256) void k_tile_fill(Geom g, const uint64_t *__res
     }
   }
   };
-  if (staged)
+  if constexpr (STAGED)
     walk(lds_sets, lds_sets + g.pw + kGuardFront, std::true_type{});
   else
     walk(cb, rr, std::false_type{});
@@ -2150,10 +2151,16 @@ void stage_extension(const dam_mask_params *p, const Geom &g, const Workspace &w
     if (fill) {
       // (the CSR offsets come out of the fill kernel: no scan launch between the two passes)
       const int share = (int64_t)g.H * g.nQt >= 2048 ? 1 : 4;  // enough query tiles to give every wave its own
-      k_tile_fill<<<dim3(share == 4 ? g.nQt : (g.nQt + 3) / 4, g.H), 256, lds_sets, stream>>>(
-          g, true_bits, w.cbits, w.rrev, w.occ, w.full, w.tile_cnt, w.head_cnt, o->blk_row_ptr, o->blk_total, o->blk_col,
-          o->blk_kind, o->tile_bits, o->blk_capacity,
-          (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0, lds_sets > 0, gidx, gcnt, gstride, w.vocc, w.vfull, share);
+      const dim3 fill_grid(share == 4 ? g.nQt : (g.nQt + 3) / 4, g.H);
+      const bool skip_full = (p->flags & DAM_MASK_SKIP_FULL_TILE_BITS) != 0;
+      if (lds_sets > 0)
+        k_tile_fill<true><<<fill_grid, 256, lds_sets, stream>>>(
+            g, true_bits, w.cbits, w.rrev, w.occ, w.full, w.tile_cnt, w.head_cnt, o->blk_row_ptr, o->blk_total, o->blk_col,
+            o->blk_kind, o->tile_bits, o->blk_capacity, skip_full, gidx, gcnt, gstride, w.vocc, w.vfull, share);
+      else
+        k_tile_fill<false><<<fill_grid, 256, 0, stream>>>(
+            g, true_bits, w.cbits, w.rrev, w.occ, w.full, w.tile_cnt, w.head_cnt, o->blk_row_ptr, o->blk_total, o->blk_col,
+            o->blk_kind, o->tile_bits, o->blk_capacity, skip_full, gidx, gcnt, gstride, w.vocc, w.vfull, share);
     } else {  // the sizing call: offsets and total only
       k_exclusive_scan<<<1, 1024, 0, stream>>>(w.tile_cnt, (int64_t)g.H * g.nQt, g.nQt, o->blk_row_ptr, o->blk_total, INT64_MAX);
     }
