@@ -354,6 +354,27 @@ def test_gathered_column_tiles_match_oracle(S, tm, tn, L):
     assert (col >= (S + tn - 1) // tn).any()
 
 
+def test_pattern_sets_too_long_for_lds_are_read_from_global_memory():
+    """S = 197 376: the two pattern bitsets of a head (2 x 3084 words) no longer fit the 48 KiB that the tile scan and
+    the tile fill stage in LDS, so both run their global-memory form; block index and bits against the oracle in the
+    plain and in the gathered layout (one head, a window, three far diagonals, sinks and far columns)."""
+    S = 197376
+    d = np.zeros((1, S), np.uint8)
+    v = np.zeros((1, S), np.uint8)
+    d[0, :70] = 1
+    d[0, [5000, 70000, 150001]] = 1
+    v[0, [0, 1, 2, 3, 900, 64000, 64001, 190000]] = 1
+    art = oracle.from_patterns(d, v, None)
+    d_in, v_in = torch.from_numpy(d).cuda(), torch.from_numpy(v).cuda()
+    mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=1, L=0, S=S, tile_m=128, tile_n=128, diag_in=d_in, vert_in=v_in)
+    torch.cuda.synchronize()
+    check_against_oracle(art, S, 128, 128, mask, dense=False)
+    for flags in (B.DAM_MASK_GATHER_COLUMNS, B.DAM_MASK_GATHER_COLUMNS | B.DAM_MASK_SKIP_FULL_TILE_BITS):
+        mask = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=1, L=0, S=S, tile_m=128, tile_n=128, diag_in=d_in, vert_in=v_in, flags=flags)
+        torch.cuda.synchronize()
+        check_gathered(art, S, 128, 128, mask, skip_full=bool(flags & B.DAM_MASK_SKIP_FULL_TILE_BITS))
+
+
 def test_gathered_column_tiles_from_a_map():
     # the columns come out of the match step of the same call (c2's recipe, scaled)
     w = wl.scaled(wl.WORKLOADS["c2"], hq=8, hkv=2, seq=2048, pcl=512)
