@@ -467,14 +467,17 @@ def test_pattern_plan_from_an_attention_map():
     assert np.array_equal(m.plan_table.cpu().numpy(), want[3])
 
 
-@pytest.mark.parametrize("Hq,Hkv,T,positions", [(8, 2, 3000, (2999, 2998, 1500, 40, 3, 0)), (4, 4, 900, (899, 450)),
-                                                (16, 2, 2100, (2099, 777))])
-def test_decode_from_a_pattern_plan_matches_the_oracle_rows(Hq, Hkv, T, positions):
+@pytest.mark.parametrize("Hq,Hkv,T,positions,Bn", [(8, 2, 3000, (2999, 2998, 1500, 40, 3, 0), 3), (4, 4, 900, (899, 450), 3),
+                                                   (16, 2, 2100, (2099, 777), 3),
+                                                   # 512 and 264 (sequence, KV head) pairs: two and four splits per
+                                                   # plan, merged inside the workgroup
+                                                   (8, 4, 700, (699, 300, 5), 128), (4, 2, 900, (899, 64), 132)])
+def test_decode_from_a_pattern_plan_matches_the_oracle_rows(Hq, Hkv, T, positions, Bn):
     """dam_sparse_attn_decode_patterns at several positions of one plan (late, early, the very first rows: diagonals
     and columns that do not exist yet; keys that are column and diagonal at once) against the oracle's attention
     over each head's own row of the mask, and against the list form on the lists of that row."""
     G = Hq // Hkv
-    Bn, dh = 3, 128
+    dh = 128
     d, v = plan_inputs(82, Hq, G, T)
     art = oracle.from_patterns(d, v)
     plan = B.build_mask(mode=B.DAM_FROM_PATTERNS, H=Hq, L=0, S=T, diag_in=torch.from_numpy(d).cuda(),
